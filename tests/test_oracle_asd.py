@@ -1,0 +1,227 @@
+"""Pins for the oracle's ASD (Alg. 1 + Alg. 2) against what the paper fixes:
+exactness in law (correctness theorem), the structure of a round (Lemma of the
+correctness proof, worst-case round lemma), special cases that reduce to the
+sequential chain, and the round-complexity theorem."""
+import numpy as np
+from scipy import special, stats
+
+import asd_workloads as W
+from oracle import asd, denoisers, schedule
+from oracle_helpers import chain_randoms, gmm_model, oracle_setup
+
+
+def _run(cfg, seed, chain, L=None, T=None, model=None):
+    if T is None:
+        T, _, model = oracle_setup(cfg)
+    xi, u = chain_randoms(seed, chain, cfg["K"], cfg["d"])
+    y, R, rounds = asd.asd_sample(xi[0], L or cfg["L"], T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+    return y, R, rounds, xi, u
+
+
+def test_L1_is_the_sequential_chain_value_for_value():
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    for chain in range(3):
+        y, R, rounds, xi, _ = _run(cfg, 0, chain, L=1, T=T, model=model)
+        ys = asd.sequential_chain(xi[0], T["c_x"], T["c_0"], T["sigma"], model, xi)
+        assert R == cfg["K"]
+        np.testing.assert_array_equal(y, ys)
+
+
+def test_constant_denoiser_accepts_everything():
+    """Point-mass data: D is constant, proposal == target, v == 0.  Every slot
+    is accepted except the sigma = 0 last step, which is resampled to its
+    (identical) mean; the trajectory equals the sequential chain."""
+    K, d = 37, 3
+    T = schedule.ddpm_tables(K)
+    p = dict(means=np.array([[0.5, -1.0, 2.0]]), log_w=np.zeros(1), var=0.0)
+    model = gmm_model(T, p)
+    xi, u = chain_randoms(5, 0, K, d)
+    ys = asd.sequential_chain(xi[0], T["c_x"], T["c_0"], T["sigma"], model, xi)
+    for L in (2, 5, 8, 37, 64):
+        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+        np.testing.assert_allclose(y, ys, rtol=0, atol=1e-13)
+        assert R == -(-K // L)
+        for r in rounds[:-1]:
+            assert r["acc"].all()
+
+
+def test_round_structure_invariants():
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    K, L = cfg["K"], cfg["L"]
+    for chain in range(12):
+        y, R, rounds, xi, u = _run(cfg, 1, chain, T=T, model=model)
+        assert -(-K // L) <= R <= -(-K // 2)
+        a = 0
+        for r in rounds:
+            assert r["a"] == a and r["b"] == min(K, a + L)
+            w = r["b"] - r["a"]
+            assert r["acc"][0]                                   # slot a+1 never rejected
+            assert abs(r["dot"][0]) == 0.0 and r["vv"][0] == 0.0
+            assert min(2, w) <= r["a_next"] - a <= w
+            n_acc = r["j"] - a
+            assert r["acc"][:n_acc].all() and (n_acc == w or not r["acc"][n_acc])
+            # accepted values are the drafted samples, bit for bit
+            np.testing.assert_array_equal(y[a + 1: r["j"] + 1], r["yhat"][:n_acc])
+            if r["r"] >= 0:
+                assert r["a_next"] == r["j"] + 1 == r["r"]
+                assert not np.array_equal(y[r["r"]], r["yhat"][n_acc])
+            else:
+                assert r["a_next"] == r["b"]
+            a = r["a_next"]
+        assert a == K
+        # the final sigma = 0 step equals the deterministic target mean
+        g = model([K - 1], y[K - 1][None])[0]
+        np.testing.assert_allclose(y[K], T["c_x"][K - 1] * y[K - 1] + T["c_0"][K - 1] * g, atol=1e-13)
+
+
+def test_worst_case_round_lemma():
+    """R <= 1 + K/theta + #(rounds that advanced by at most theta - 1 steps and
+    did not end at K)  -- a weaker, checkable form of the round-complexity lemma."""
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    for chain in range(6):
+        _, R, rounds, _, _ = _run(cfg, 2, chain, T=T, model=model)
+        bad = sum(1 for r in rounds if r["a_next"] - r["a"] < cfg["L"])
+        assert R <= 1 + cfg["K"] / cfg["L"] + bad
+
+
+def test_exact_in_law_gaussian_data_closed_form():
+    """Single Gaussian data law: the chain is linear-Gaussian, so Law(y_i) is
+    N(mean_i, var_i) by a scalar recursion.  ASD samples must follow it."""
+    K, d, L, n = 24, 1, 6, 3000
+    T = schedule.ddpm_tables(K)
+    mu, s2 = 1.5, 0.25
+    p = dict(means=np.array([[mu]]), log_w=np.zeros(1), var=s2)
+    model = gmm_model(T, p)
+    mean, var = np.zeros(K + 1), np.ones(K + 1)
+    for i in range(K):
+        ab = T["abar"][T["tau"][i]]
+        k = np.sqrt(ab) * s2 / (ab * s2 + 1 - ab)          # D(x) = mu + k (x - sqrt(ab) mu)
+        slope = T["c_x"][i] + T["c_0"][i] * k
+        mean[i + 1] = slope * mean[i] + T["c_0"][i] * (mu - k * np.sqrt(ab) * mu)
+        var[i + 1] = slope ** 2 * var[i] + T["sigma"][i] ** 2
+    Y = np.empty((n, K + 1))
+    rej = 0
+    for c in range(n):
+        xi, u = chain_randoms(9, c, K, d)
+        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+        Y[c] = y[:, 0]
+        rej += sum(1 for r in rounds if r["r"] >= 0 and r["r"] < K)
+    assert rej > n / 4                                      # the rejection branch is exercised
+    for i in (1, 5, 11, 17, 23, 24):
+        z = (Y[:, i] - mean[i]) / np.sqrt(var[i])
+        assert stats.kstest(z, "norm").pvalue > 1e-3, i
+    # joint law: lag-one covariance  Cov(y_i, y_{i+1}) = slope_i var_i
+    i = 12
+    ab = T["abar"][T["tau"][i]]
+    slope = T["c_x"][i] + T["c_0"][i] * np.sqrt(ab) * s2 / (ab * s2 + 1 - ab)
+    c_emp = np.cov(Y[:, i], Y[:, i + 1])[0, 1]
+    assert abs(c_emp - slope * var[i]) < 5 * var[i] / np.sqrt(n)
+
+
+def test_exact_in_law_mixture_vs_sequential():
+    """Workload-1 shape (4-component mixture, d=2, K=100, L=8): ASD samples and
+    independent sequential samples agree in moments and by two-sample KS."""
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    n = 500
+    A = np.empty((n, 3, 2))
+    S = np.empty((n, 3, 2))
+    pick = [40, 80, 100]
+    for c in range(n):
+        y, _, _, _, _ = _run(cfg, 21, c, T=T, model=model)
+        A[c] = y[pick]
+        xi, _ = chain_randoms(22, c, cfg["K"], cfg["d"])
+        S[c] = asd.sequential_chain(xi[0], T["c_x"], T["c_0"], T["sigma"], model, xi)[pick]
+    for t in range(3):
+        for k in range(2):
+            assert stats.ks_2samp(A[:, t, k], S[:, t, k]).pvalue > 1e-3
+            sd = np.sqrt(A[:, t, k].var() / n + S[:, t, k].var() / n)
+            assert abs(A[:, t, k].mean() - S[:, t, k].mean()) < 4.5 * sd
+        ca, cs = np.cov(A[:, t].T), np.cov(S[:, t].T)
+        assert np.max(np.abs(ca - cs)) < 0.25 * max(1.0, np.max(np.abs(cs)))
+
+
+def test_sl_coordinates_give_the_same_run():
+    """Run ASD on the SL Euler chain (Eq. sl-defn / Eq. euler-sde, A=1, Bc=eta,
+    sigma=sqrt(eta), g=m(t,.)) and on the DDPM tables with the same xi, u:
+    same accept bits, trajectories equal under y^SL = gamma x  (Thm. 1)."""
+    K, d, L = 60, 2, 8
+    p = W.gmm_params(d, 4)
+    T = schedule.ddpm_tables(K)
+    S = schedule.sl_tables(K)
+    Km = K - 1
+    model_x = gmm_model(T, p)
+
+    def model_sl(idx, rows):
+        return denoisers.gmm_sl_mean(rows, S["t"][np.asarray(idx)], p["means"], p["log_w"], p["var"])
+
+    for chain in range(4):
+        xi, u = chain_randoms(4, chain, K, d)
+        yx, Rx, rx = asd.asd_sample(xi[0], L, T["c_x"][:Km], T["c_0"][:Km], T["sigma"][:Km], model_x, xi, u)
+        ysl, Rs, rs = asd.asd_sample(S["gamma"][0] * xi[0], L, np.ones(Km), S["eta"], np.sqrt(S["eta"]),
+                                     model_sl, xi, u)
+        assert Rx == Rs
+        for a_, b_ in zip(rx, rs):
+            assert a_["j"] == b_["j"] and np.array_equal(a_["acc"], b_["acc"])
+        np.testing.assert_allclose(ysl, S["gamma"][:, None] * yx, rtol=1e-7)
+
+
+def test_rejection_rate_matches_total_variation_on_own_path():
+    """Law of total expectation on tested slots: E[reject bit] =
+    E[ erf(|v| / (2 sqrt2 sigma)) ] with v from the oracle's own path."""
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    obs = exp = var = 0.0
+    hist = np.zeros(cfg["L"] + 1)
+    hists = []
+    for c in range(240):
+        _, _, rounds, _, _ = _run(cfg, 31, c, T=T, model=model)
+        for r in rounds:
+            hist[r["j"] - r["a"]] += 1
+            for k in range(1, r["b"] - r["a"]):
+                s = T["sigma"][r["a"] + k]
+                if s == 0.0:
+                    continue
+                tv = special.erf(np.sqrt(r["vv"][k]) / (2 * np.sqrt(2) * s))
+                obs += not r["acc"][k]
+                exp += tv
+                var += tv * (1 - tv)
+        if c % 80 == 79:
+            hists.append(hist / hist.sum())
+            hist = np.zeros(cfg["L"] + 1)
+    assert var > 50 and abs(obs - exp) < 4.5 * np.sqrt(var)
+    # accepted-prefix histogram is stable across seed blocks
+    for h in hists[1:]:
+        assert np.max(np.abs(h - hists[0])) < 0.08
+
+
+def test_round_complexity_scaling():
+    """SL chain, fixed step eta, theta = ceil((K/(beta eta d))^(1/3)): mean rounds
+    grow no faster than K^(2/3) (round-complexity theorem; an upper bound with
+    an unnamed constant, so a sanity check, not an equality)."""
+    d, eta, beta = 2, 0.05, 4.25
+    p = W.gmm_params(d, 4)
+    Ks = [125, 500, 2000, 8000]
+    means = []
+    for K in Ks:
+        L = int(np.ceil((K / (beta * eta * d)) ** (1 / 3)))
+        t = np.arange(K) * eta
+
+        def model(idx, rows, t=t):
+            return denoisers.gmm_sl_mean(rows, t[np.asarray(idx)], p["means"], p["log_w"], p["var"])
+
+        Rs = []
+        for chain in range(4):
+            xi, u = chain_randoms(7, chain, K, d)
+            _, R, _ = asd.asd_sample(np.zeros(d), L, np.ones(K), np.full(K, eta), np.full(K, np.sqrt(eta)),
+                                     model, xi, u, keep_rounds=False)
+            Rs.append(R)
+        means.append(np.mean(Rs))
+    slope = np.polyfit(np.log(Ks), np.log(means), 1)[0]
+    assert slope < 0.72
+    ratio = np.array(means) / (np.array(Ks) ** (2 / 3) * (beta * d * eta) ** (1 / 3))
+    assert ratio.max() < 2.0 and ratio.max() / ratio.min() < 1.3
+    assert means[-1] < Ks[-1] / 10

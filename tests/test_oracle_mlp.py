@@ -1,0 +1,63 @@
+"""Pins for the MLP denoiser of the oracle.  Its definition is not in the
+paper ("parity unpinned"): only special cases and a hand-computed example."""
+import numpy as np
+import torch
+
+import asd_workloads as W
+from oracle import denoisers
+
+
+def test_bf16_rounding_matches_library_conversion():
+    rng = np.random.default_rng(0)
+    a = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, 5000),
+                        [1.00390625, 1.01171875, 0.0, -0.0, 3.0e38]])   # two exact ties
+    ref = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(denoisers.round_to_bf16(a), ref)
+    bits = W.f32_to_bf16_bits(a.astype(np.float32))
+    np.testing.assert_array_equal(denoisers.bf16_bits_to_f64(bits), ref)
+
+
+def _params(w_in, w_blk, w_out, temb):
+    f = W.f32_to_bf16_bits
+    return dict(w_in=f(w_in), w_blk=f(w_blk), w_out=f(w_out), temb=f(temb),
+                b_in=np.zeros(w_in.shape[0], np.float32), b_blk=np.zeros(w_blk.shape[:2], np.float32),
+                b_out=np.zeros(w_out.shape[0], np.float32))
+
+
+def test_hand_computed_two_wide_example():
+    # d=1, E=1, width=2, one block; all values exactly representable in bf16.
+    w_in = np.array([[1.0, 0.5], [-2.0, 1.0]], np.float32)        # rows: out, cols: [x, temb]
+    w_blk = np.array([[[1.0, 0.0], [0.5, 0.5]]], np.float32)
+    w_out = np.array([[2.0, -1.0]], np.float32)
+    temb = np.array([[0.0], [4.0], [-2.0]], np.float32)            # tau = 0,1,2
+    mlp = denoisers.MLPOracle(_params(w_in, w_blk, w_out, temb))
+    x, tau = 0.5, 2
+    h = np.array([1.0 * x + 0.5 * -2.0, -2.0 * x + 1.0 * -2.0])   # [-0.5, -3.0]
+    zlin = np.array([h[0], 0.5 * h[0] + 0.5 * h[1]])              # [-0.5, -1.75]
+    h1 = h + zlin / (1 + np.exp(-zlin))
+    h1r = denoisers.round_to_bf16(h1)
+    want = 2.0 * h1r[0] - 1.0 * h1r[1]
+    got = mlp([[x]], [tau])[0, 0]
+    assert abs(got - want) < 1e-15
+    p = _params(w_in, w_blk, w_out, temb)
+    p["b_in"] = np.array([0.25, -1.0], np.float32)
+    p["b_out"] = np.array([3.0], np.float32)
+    p["w_blk"] = np.zeros_like(p["w_blk"])
+    # zero block weights: SiLU(0) = 0, the block is the identity
+    got = denoisers.MLPOracle(p)([[x]], [1])[0, 0]
+    h = np.array([1.0 * x + 0.5 * 4.0 + 0.25, -2.0 * x + 4.0 - 1.0])
+    assert abs(got - (2 * h[0] - h[1] + 3.0)) < 1e-15
+
+
+def test_rows_are_independent_and_rounding_points_matter():
+    p = W.mlp_params(d=12, E=8, width=32, n_blocks=2, K=10, model_seed=3)
+    mlp = denoisers.MLPOracle(p)
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((6, 12))
+    tau = np.array([1, 5, 10, 3, 3, 7])
+    full = mlp(x, tau)
+    for n in range(6):
+        np.testing.assert_allclose(mlp(x[n:n + 1], tau[n:n + 1])[0], full[n], rtol=1e-13)
+    # inputs that differ by less than half a bf16 ulp are the same to the network
+    np.testing.assert_array_equal(mlp(np.full((1, 12), 1.0), [2]), mlp(np.full((1, 12), 1.0 + 2.0 ** -10), [2]))
+    assert np.max(np.abs(full)) < 50 and np.std(full) > 0.05
