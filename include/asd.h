@@ -1,0 +1,202 @@
+/*
+ * asd.h -- C boundary of the MI355X (gfx950) implementation of one round of
+ * Autospeculative Decoding (ASD) for DDPM sampling over a batch of chains.
+ *
+ * The library samples the Euler chain
+ *     y_{i+1} = c_x[i] y_i + c_0[i] D(y_i, tau[i]) + sigma[i] xi_{i+1}
+ * (Eq. euler-sde written in the x0-prediction form of the Remark after
+ * Alg. 3; D is the denoiser E[x_0 | y_i], the paper's "model call") with
+ * Alg. 1: draft a window of L steps from one model call, evaluate the model at
+ * all drafted points in one batched pass, run the Gaussian Rejection Sampler
+ * (Alg. 3) on every slot, advance to the first rejection (Alg. 2) and
+ * resample that step by reflection.
+ *
+ * Conventions
+ *  - "HOST" pointers are read during the call and may be freed afterwards.
+ *    "DEV" pointers are device (HBM) memory owned by the caller; the library
+ *    never frees them.  Denoiser weight pointers given to asd_init must stay
+ *    valid until asd_destroy; every other pointer is only used by the call it
+ *    is passed to (asynchronously, on `stream`).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Stage calls are asynchronous; only asd_sample synchronises (it polls a
+ *    per-round live-chain count).
+ *  - All state is fp32; trajectories are row-major traj[chain][step][dim] with
+ *    step = 0..K (K+1 rows per chain).  Random numbers come from a
+ *    counter-based Philox4x32-10 keyed by `seed` with counter
+ *    (block = dim/4, step, chain, stream-id): Alg. 1 draws u_{1:K}, xi_{1:K}
+ *    once and indexes them by step, never by round.
+ *  - No call throws or aborts: every entry returns an asd_status.  Argument
+ *    errors are detected on the host before any launch.  A ctx is bound to the
+ *    device that was current at asd_init and is not thread-safe.
+ */
+#ifndef ASD_H
+#define ASD_H
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define ASD_API __attribute__((visibility("default")))
+#else
+#define ASD_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct asd_ctx asd_ctx; /* opaque, owned by the library */
+
+typedef enum {
+  ASD_OK = 0,
+  ASD_EINVAL = -1,       /* NULL pointer, size or value out of range          */
+  ASD_ENOMEM = -2,       /* host or device allocation failed                  */
+  ASD_EDEVICE = -3,      /* a HIP call failed (no device, launch error, ...)  */
+  ASD_ESTATE = -4,       /* stage calls out of order (draft->verify->accept)  */
+  ASD_EUNSUPPORTED = -5  /* valid request this build does not implement       */
+} asd_status;
+
+/* Alg. 1 inputs "steps K, step sizes, variances", in x0-prediction form.
+ * All arrays HOST, length K; copied by asd_init.
+ *   c_x, c_0 : coefficients of y_i and of D(y_i, tau[i]) in the mean of step i
+ *   sigma    : standard deviation of the noise of step i (>= 0; 0 allowed:
+ *              such a slot is treated as the sigma -> 0 limit of Alg. 3)
+ *   tau      : time index fed to the denoiser at step i, in [0, n_tau) */
+typedef struct {
+  int32_t K;
+  const float* c_x;
+  const float* c_0;
+  const float* sigma;
+  const int32_t* tau;
+} asd_schedule;
+
+typedef enum { ASD_DEN_GMM = 1, ASD_DEN_MLP = 2 } asd_den_kind;
+
+/* The model g of Alg. 1, as a denoiser D(x, tau) = E[x_0 | x_tau = x].
+ *
+ * GMM: data law sum_k w_k N(mu_k, var I) observed as
+ *   x_tau = sqrt(abar[tau]) x_0 + sqrt(1 - abar[tau]) eps; D is the exact
+ *   posterior mean (the mean function m(t, y) of Eq. sl-defn for this law).
+ *   means DEV fp32 [C, d] row-major; log_w DEV fp32 [C] (unnormalised logs
+ *   allowed); abar HOST fp32 [n_tau], values in (0, 1].
+ * MLP: in = [bf16(x) ; temb[tau]] (d + temb_dim), h = W_in in + b_in,
+ *   n_blocks times h += SiLU(W_l bf16(h) + b_l), out = W_out bf16(h) + b_out.
+ *   Weights DEV bf16 row-major [out, in]: w_in [width, d+temb_dim],
+ *   w_blk [n_blocks, width, width], w_out [d, width]; biases DEV fp32 or NULL
+ *   (= 0): b_in [width], b_blk [n_blocks, width], b_out [d];
+ *   temb DEV bf16 [n_tau, temb_dim].  Products accumulate in fp32.
+ *   linears_per_block must be 1.  d, temb_dim and width must be multiples of 8. */
+typedef struct {
+  int32_t kind; /* asd_den_kind */
+  int32_t d;
+  int32_t n_tau;
+  /* GMM */
+  int32_t C;
+  const float* means;
+  const float* log_w;
+  float var;
+  const float* abar;
+  /* MLP */
+  int32_t width, n_blocks, linears_per_block, temb_dim;
+  const void* w_in;
+  const void* w_blk;
+  const void* w_out;
+  const float* b_in;
+  const float* b_blk;
+  const float* b_out;
+  const void* temb;
+} asd_denoiser;
+
+/* Problem statement of Alg. 1 for a batch: schedule, model, speculation
+ * length L (the paper's theta; 1 <= L <= 64), number of chains, seed. */
+typedef struct {
+  asd_schedule sched;
+  asd_denoiser den;
+  int32_t L;
+  int32_t chains;
+  uint64_t seed;
+} asd_config;
+
+/* Validates the configuration (ASD_EINVAL / ASD_EUNSUPPORTED before touching
+ * the device), copies the tables to the device and allocates all scratch
+ * (sized for chains*L rows).  *out is NULL on failure. */
+ASD_API asd_status asd_init(const asd_config* cfg, asd_ctx** out);
+ASD_API asd_status asd_destroy(asd_ctx* ctx); /* NULL is allowed */
+
+/* Re-key the random streams; the next asd_sample / stage calls use it. */
+ASD_API asd_status asd_set_seed(asd_ctx* ctx, uint64_t seed);
+
+/* ---- one round (body of the while-loop of Alg. 1), three stages ----------
+ * a DEV int32 [chains]: current index a_c of each chain (0 <= a_c <= K; a
+ * chain with a_c == K is finished and is left untouched).
+ * Call order draft -> verify -> accept is enforced (ASD_ESTATE otherwise).
+ *
+ * asd_draft: model call 1 and the proposal samples.  Reads traj[c][a_c],
+ *   evaluates x0a_c = D(y_a, tau[a_c]) (kept in ctx scratch) and writes the
+ *   proposal samples yhat_{a+1..b}, b = min(K, a+L), into traj[c][a_c+1..b]:
+ *   yhat_{i+1} = c_x[i] yhat_i + c_0[i] x0a + sigma[i] xi_{i+1}. */
+ASD_API asd_status asd_draft(asd_ctx* ctx, float* traj, const int32_t* a, void* stream);
+
+/* asd_verify: model call 2, the batched target-mean evaluation.
+ *   x0hat DEV fp32 [chains, L, d]; slot 0 receives a copy of x0a (proposal
+ *   mean == target mean for step a+1, so it is not recomputed); slot s in
+ *   1..b-a-1 receives D(yhat_{a+s}, tau[a+s]).  Slots >= b-a are unspecified. */
+ASD_API asd_status asd_verify(asd_ctx* ctx, const float* traj, const int32_t* a, float* x0hat, void* stream);
+
+/* asd_accept: Alg. 3 on every slot, first-rejection scan (Alg. 2), resample,
+ *   advance.  Slot a+1 is accepted; for s >= 1, v = c_0 (x0a - x0hat[s]),
+ *   accept iff log u <= -(<v,xi>/sigma + |v|^2 / (2 sigma^2)); sigma == 0
+ *   rejects.  With j the end of the accepted prefix: if j < b the row
+ *   traj[c][j+1] is overwritten by the reflected sample and a_c = j+1, else
+ *   a_c = j.  accepted (DEV int32 [chains], may be NULL) receives j - a_c(old)
+ *   (-1 for finished chains).
+ *   stats (DEV fp32 [chains, L, 4], may be NULL) receives per slot
+ *   (<d,xi>, |d|^2, log u, rho) with d = x0a - x0hat[s]  (slot 0: zeros). */
+ASD_API asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
+                      int32_t* accepted, float* stats, void* stream);
+
+/* ---- whole sample (Alg. 1) ------------------------------------------------
+ * y0 DEV fp32 [chains, d] or NULL (then y_0 ~ N(0, I) from the Philox stream
+ * at step 0).  Fills traj DEV fp32 [chains, K+1, d] and rounds DEV int32
+ * [chains] (iterations of the while-loop each chain took; may be NULL).
+ * Rounds are lock-step launches over all unfinished chains. */
+ASD_API asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream);
+
+/* Sequential chain with the same random inputs (one model call per step, K
+ * launches): the baseline ASD is compared against in the paper's speedups. */
+ASD_API asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream);
+
+/* Number of lock-step rounds launched by the last asd_sample (host value). */
+ASD_API int32_t asd_last_round_count(const asd_ctx* ctx);
+
+/* ---- pieces exposed for testing and profiling ----------------------------
+ * asd_denoise: out[n] = D(x[n], tau[n]) for n rows (n <= chains*L).
+ *   x, out DEV fp32 [n, d]; tau DEV int32 [n]. */
+ASD_API asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t n, float* out, void* stream);
+
+/* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
+ * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
+ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,
+                            int32_t nblk, uint32_t* out, void* stream);
+/* xi DEV fp32 [d] = the normals of (chain, step); u DEV fp32 [1] = the uniform. */
+ASD_API asd_status asd_debug_randoms(uint64_t seed, uint32_t chain, uint32_t step, int32_t d,
+                             float* xi, float* u, void* stream);
+
+/* ---- host-only helpers -----------------------------------------------------
+ * DDPM linear-beta schedule (beta_tau from beta_min to beta_max over tau=1..K)
+ * in the x0-prediction form, computed in double and rounded to fp32:
+ * the coefficients obtained by mapping a DDPM iterate to Stochastic
+ * Localization, taking one Euler step there and mapping back (Sec. 3), which
+ * is ancestral sampling with the posterior variance.  Step i handles
+ * tau[i] = K - i.  Arrays HOST: c_x, c_0, sigma, tau [K]; abar [K+1]
+ * (abar[0] = 1).  Any output pointer may be NULL. */
+ASD_API asd_status asd_schedule_ddpm_linear(int32_t K, double beta_min, double beta_max,
+                                    float* c_x, float* c_0, float* sigma, int32_t* tau, float* abar);
+
+ASD_API const char* asd_status_string(asd_status s);
+/* Message of the last failure on this thread ("" if none). */
+ASD_API const char* asd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASD_H */

@@ -1,0 +1,207 @@
+"""Thin ctypes binding of libasd.so: same names as include/asd.h, argument
+marshalling only.  Every step of the sampling path runs in the HIP library;
+PyTorch is used for device memory and streams."""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libasd.so")
+
+ASD_OK, ASD_EINVAL, ASD_ENOMEM, ASD_EDEVICE, ASD_ESTATE, ASD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+ASD_DEN_GMM, ASD_DEN_MLP = 1, 2
+
+
+class AsdError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (status_string(status), message))
+        self.status = status
+
+
+class asd_schedule(C.Structure):
+    _fields_ = [("K", C.c_int32), ("c_x", C.c_void_p), ("c_0", C.c_void_p), ("sigma", C.c_void_p),
+                ("tau", C.c_void_p)]
+
+
+class asd_denoiser(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("d", C.c_int32), ("n_tau", C.c_int32),
+                ("C", C.c_int32), ("means", C.c_void_p), ("log_w", C.c_void_p), ("var", C.c_float),
+                ("abar", C.c_void_p),
+                ("width", C.c_int32), ("n_blocks", C.c_int32), ("linears_per_block", C.c_int32),
+                ("temb_dim", C.c_int32),
+                ("w_in", C.c_void_p), ("w_blk", C.c_void_p), ("w_out", C.c_void_p),
+                ("b_in", C.c_void_p), ("b_blk", C.c_void_p), ("b_out", C.c_void_p), ("temb", C.c_void_p)]
+
+
+class asd_config(C.Structure):
+    _fields_ = [("sched", asd_schedule), ("den", asd_denoiser), ("L", C.c_int32), ("chains", C.c_int32),
+                ("seed", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libasd.so is not built: run `python -m paper_2505_03983_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, u32, u64 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64
+        sig = {
+            "asd_init": (i32, [C.POINTER(asd_config), C.POINTER(vp)]),
+            "asd_destroy": (i32, [vp]),
+            "asd_set_seed": (i32, [vp, u64]),
+            "asd_draft": (i32, [vp, vp, vp, vp]),
+            "asd_verify": (i32, [vp, vp, vp, vp, vp]),
+            "asd_accept": (i32, [vp, vp, vp, vp, vp, vp, vp]),
+            "asd_sample": (i32, [vp, vp, vp, vp, vp]),
+            "asd_sample_sequential": (i32, [vp, vp, vp, vp]),
+            "asd_last_round_count": (i32, [vp]),
+            "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
+            "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
+            "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
+            "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
+            "asd_status_string": (C.c_char_p, [i32]),
+            "asd_last_error": (C.c_char_p, []),
+        }
+        for name, (res, args) in sig.items():
+            f = getattr(L, name)
+            f.restype, f.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def status_string(s):
+    return lib().asd_status_string(int(s)).decode()
+
+
+def last_error():
+    return lib().asd_last_error().decode()
+
+
+def _check(s):
+    if s != ASD_OK:
+        raise AsdError(s, last_error())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return t.data_ptr()
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"]
+        return t.ctypes.data
+    return int(t)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def asd_schedule_ddpm_linear(K, beta_min=1e-4, beta_max=0.02):
+    """Host tables of the library: dict(c_x, c_0, sigma [K] f32; tau [K] i32; abar [K+1] f32)."""
+    n = max(int(K), 0)
+    out = dict(c_x=np.zeros(n, np.float32), c_0=np.zeros(n, np.float32), sigma=np.zeros(n, np.float32),
+               tau=np.zeros(n, np.int32), abar=np.zeros(n + 1, np.float32))
+    _check(lib().asd_schedule_ddpm_linear(int(K), float(beta_min), float(beta_max), _ptr(out["c_x"]),
+                                          _ptr(out["c_0"]), _ptr(out["sigma"]), _ptr(out["tau"]),
+                                          _ptr(out["abar"])))
+    return out
+
+
+def make_config(sched, den, L, chains, seed):
+    """sched: dict of host numpy tables; den: dict with 'kind' and parameters
+    (device torch tensors for DEV fields, numpy for HOST fields).  Returns
+    (asd_config, keepalive list)."""
+    keep = []
+
+    def host(a, dt):
+        a = np.ascontiguousarray(a, dtype=dt)
+        keep.append(a)
+        return a.ctypes.data
+
+    cfg = asd_config()
+    cfg.sched.K = int(sched["K"]) if "K" in sched else len(sched["c_x"])
+    cfg.sched.c_x = host(sched["c_x"], np.float32)
+    cfg.sched.c_0 = host(sched["c_0"], np.float32)
+    cfg.sched.sigma = host(sched["sigma"], np.float32)
+    cfg.sched.tau = host(sched["tau"], np.int32)
+    cfg.den.kind = ASD_DEN_GMM if den["kind"] == "gmm" else ASD_DEN_MLP if den["kind"] == "mlp" else int(den["kind"])
+    cfg.den.d = int(den["d"])
+    cfg.den.n_tau = int(den["n_tau"])
+    if den["kind"] == "gmm":
+        cfg.den.C = int(den["C"])
+        cfg.den.means = _ptr(den["means"])
+        cfg.den.log_w = _ptr(den["log_w"])
+        cfg.den.var = float(den["var"])
+        cfg.den.abar = host(den["abar"], np.float32) if den.get("abar") is not None else None
+    elif den["kind"] == "mlp":
+        cfg.den.width = int(den["width"])
+        cfg.den.n_blocks = int(den["n_blocks"])
+        cfg.den.linears_per_block = int(den.get("linears_per_block", 1))
+        cfg.den.temb_dim = int(den["temb_dim"])
+        for k in ("w_in", "w_blk", "w_out", "b_in", "b_blk", "b_out", "temb"):
+            setattr(cfg.den, k, _ptr(den.get(k)))
+    keep.append(den)
+    cfg.L = int(L)
+    cfg.chains = int(chains)
+    cfg.seed = int(seed)
+    return cfg, keep
+
+
+class Ctx:
+    """Owns an asd_ctx*; methods are the C entry points."""
+
+    def __init__(self, sched, den, L, chains, seed=0):
+        self.cfg, self._keep = make_config(sched, den, L, chains, seed)
+        h = C.c_void_p()
+        _check(lib().asd_init(C.byref(self.cfg), C.byref(h)))
+        self.h = h
+        self.K, self.L, self.chains, self.d = self.cfg.sched.K, int(L), int(chains), self.cfg.den.d
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().asd_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def set_seed(self, seed):
+        _check(lib().asd_set_seed(self.h, int(seed)))
+
+    def draft(self, traj, a, stream=None):
+        _check(lib().asd_draft(self.h, _ptr(traj), _ptr(a), _stream(stream)))
+
+    def verify(self, traj, a, x0hat, stream=None):
+        _check(lib().asd_verify(self.h, _ptr(traj), _ptr(a), _ptr(x0hat), _stream(stream)))
+
+    def accept(self, traj, a, x0hat, accepted=None, stats=None, stream=None):
+        _check(lib().asd_accept(self.h, _ptr(traj), _ptr(a), _ptr(x0hat), _ptr(accepted), _ptr(stats),
+                                _stream(stream)))
+
+    def sample(self, traj, rounds=None, y0=None, stream=None):
+        _check(lib().asd_sample(self.h, _ptr(y0), _ptr(traj), _ptr(rounds), _stream(stream)))
+        return lib().asd_last_round_count(self.h)
+
+    def sample_sequential(self, traj, y0=None, stream=None):
+        _check(lib().asd_sample_sequential(self.h, _ptr(y0), _ptr(traj), _stream(stream)))
+
+    def denoise(self, x, tau, out, stream=None):
+        _check(lib().asd_denoise(self.h, _ptr(x), _ptr(tau), int(x.shape[0]), _ptr(out), _stream(stream)))
+
+
+def asd_debug_philox(seed, chain, step, stream_id, nblk, out, stream=None):
+    _check(lib().asd_debug_philox(int(seed), int(chain), int(step), int(stream_id), int(nblk), _ptr(out),
+                                  _stream(stream)))
+
+
+def asd_debug_randoms(seed, chain, step, d, xi, u, stream=None):
+    _check(lib().asd_debug_randoms(int(seed), int(chain), int(step), int(d), _ptr(xi), _ptr(u), _stream(stream)))

@@ -1,0 +1,369 @@
+// C entry points of the ASD library: validation, context life cycle, the three
+// stages of a round and the whole-sample driver (the while-loop of Alg. 1 run
+// in lock step over a batch of independent chains).
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace asd {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static asd_status fail(asd_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// ---- validation (host only; no HIP call) -------------------------------------
+static asd_status validate(const asd_config* cfg) {
+  if (!cfg) return fail(ASD_EINVAL, "cfg is NULL");
+  const asd_schedule& s = cfg->sched;
+  const asd_denoiser& m = cfg->den;
+  if (s.K < 1) return fail(ASD_EINVAL, "K must be >= 1 (got %d)", s.K);
+  if (cfg->L < 1) return fail(ASD_EINVAL, "L must be >= 1 (got %d)", cfg->L);
+  if (cfg->chains < 1) return fail(ASD_EINVAL, "chains must be >= 1 (got %d)", cfg->chains);
+  if (!s.c_x || !s.c_0 || !s.sigma || !s.tau) return fail(ASD_EINVAL, "schedule table is NULL");
+  if (m.d < 1) return fail(ASD_EINVAL, "d must be >= 1 (got %d)", m.d);
+  if (m.n_tau < 1) return fail(ASD_EINVAL, "n_tau must be >= 1 (got %d)", m.n_tau);
+  for (int i = 0; i < s.K; ++i) {
+    if (!isfinite(s.c_x[i]) || !isfinite(s.c_0[i]) || !isfinite(s.sigma[i]))
+      return fail(ASD_EINVAL, "schedule entry %d is not finite", i);
+    if (s.sigma[i] < 0.f) return fail(ASD_EINVAL, "sigma[%d] is negative", i);
+    if (s.tau[i] < 0 || s.tau[i] >= m.n_tau) return fail(ASD_EINVAL, "tau[%d]=%d outside [0,%d)", i, s.tau[i], m.n_tau);
+  }
+  if ((double)cfg->chains * cfg->L > 1.0e9 || (double)cfg->chains * ((double)s.K + 1.0) * m.d > 4.0e12)
+    return fail(ASD_EINVAL, "problem too large");
+  if (m.kind == ASD_DEN_GMM) {
+    if (m.C < 1) return fail(ASD_EINVAL, "C must be >= 1 (got %d)", m.C);
+    if (!m.means || !m.log_w || !m.abar) return fail(ASD_EINVAL, "GMM parameter pointer is NULL");
+    if (!(m.var >= 0.f) || !isfinite(m.var)) return fail(ASD_EINVAL, "var must be finite and >= 0");
+    for (int t = 0; t < m.n_tau; ++t) {
+      const float ab = m.abar[t];
+      if (!(ab > 0.f) || !(ab <= 1.f)) return fail(ASD_EINVAL, "abar[%d] outside (0,1]", t);
+      if ((double)ab * m.var + 1.0 - ab <= 0.0) return fail(ASD_EINVAL, "abar[%d]=1 with var=0 is degenerate", t);
+    }
+  } else if (m.kind == ASD_DEN_MLP) {
+    if (m.width < 1 || m.n_blocks < 0 || m.temb_dim < 0) return fail(ASD_EINVAL, "bad MLP shape");
+    if (!m.w_in || !m.w_out || (m.n_blocks > 0 && !m.w_blk) || (m.temb_dim > 0 && !m.temb))
+      return fail(ASD_EINVAL, "MLP parameter pointer is NULL");
+    if (m.linears_per_block != 1) return fail(ASD_EUNSUPPORTED, "linears_per_block must be 1");
+    if (m.d % 8 || m.temb_dim % 8 || m.width % 8)
+      return fail(ASD_EUNSUPPORTED, "MLP needs d, temb_dim and width to be multiples of 8");
+  } else {
+    return fail(ASD_EINVAL, "unknown denoiser kind %d", m.kind);
+  }
+  if (cfg->chains > 65535) return fail(ASD_EUNSUPPORTED, "chains > 65535 (got %d)", cfg->chains);
+  if (cfg->L > 64) return fail(ASD_EUNSUPPORTED, "L > 64 needs a multi-word first-rejection scan (got %d)", cfg->L);
+  return ASD_OK;
+}
+
+static asd_status check_ctx(asd_ctx* ctx) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ASD_HIP(hipSetDevice(ctx->device));
+  return ASD_OK;
+}
+
+static asd_status check_rows_ptr(const asd_ctx* ctx, const void* p, const char* name) {
+  if (!p) return fail(ASD_EINVAL, "%s is NULL", name);
+  if ((ctx->d & 3) == 0 && !aligned16(p)) return fail(ASD_EINVAL, "%s must be 16-byte aligned", name);
+  return ASD_OK;
+}
+
+template <class T>
+static asd_status upload(T** dst, const T* src, size_t n) {
+  ASD_HIP(hipMalloc(dst, sizeof(T) * n));
+  ASD_HIP(hipMemcpy(*dst, src, sizeof(T) * n, hipMemcpyHostToDevice));
+  return ASD_OK;
+}
+
+static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
+  ASD_HIP(hipGetDevice(&ctx->device));
+  ctx->K = cfg->sched.K;
+  ctx->L = cfg->L;
+  ctx->B = cfg->chains;
+  ctx->d = cfg->den.d;
+  ctx->n_tau = cfg->den.n_tau;
+  ctx->n_rows_max = (int64_t)cfg->chains * cfg->L;
+  ctx->key = make_key(cfg->seed);
+  ctx->kind = cfg->den.kind;
+  const size_t K = (size_t)ctx->K, rows = (size_t)ctx->n_rows_max;
+  ASD_TRY(upload(&ctx->c_x, cfg->sched.c_x, K));
+  ASD_TRY(upload(&ctx->c_0, cfg->sched.c_0, K));
+  ASD_TRY(upload(&ctx->sigma, cfg->sched.sigma, K));
+  ASD_TRY(upload(&ctx->tau, cfg->sched.tau, K));
+  ASD_HIP(hipMalloc(&ctx->in_off, sizeof(int64_t) * rows));
+  ASD_HIP(hipMalloc(&ctx->out_off, sizeof(int64_t) * rows));
+  ASD_HIP(hipMalloc(&ctx->row_tau, sizeof(int32_t) * rows));
+  ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
+  ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
+  ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * kLiveRing));
+  ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * kLiveRing));
+  ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * kLiveRing, hipHostMallocDefault));
+  ctx->live_ev = new (std::nothrow) hipEvent_t[kLiveRing]();
+  if (!ctx->live_ev) return ASD_ENOMEM;
+  for (int i = 0; i < kLiveRing; ++i) ASD_HIP(hipEventCreateWithFlags(&ctx->live_ev[i], hipEventDisableTiming));
+  if (ctx->kind == ASD_DEN_GMM) return gmm_create(ctx, cfg->den);
+  return mlp_create(ctx, cfg->den);
+}
+
+static void teardown(asd_ctx* ctx) {
+  if (!ctx) return;
+  gmm_destroy(ctx);
+  mlp_destroy(ctx);
+  (void)hipFree(ctx->c_x);
+  (void)hipFree(ctx->c_0);
+  (void)hipFree(ctx->sigma);
+  (void)hipFree(ctx->tau);
+  (void)hipFree(ctx->in_off);
+  (void)hipFree(ctx->out_off);
+  (void)hipFree(ctx->row_tau);
+  (void)hipFree(ctx->x0a);
+  (void)hipFree(ctx->x0hat);
+  (void)hipFree(ctx->a);
+  (void)hipFree(ctx->live);
+  if (ctx->live_host) (void)hipHostFree(ctx->live_host);
+  if (ctx->live_ev) {
+    for (int i = 0; i < kLiveRing; ++i)
+      if (ctx->live_ev[i]) (void)hipEventDestroy(ctx->live_ev[i]);
+    delete[] ctx->live_ev;
+  }
+  delete ctx;
+}
+
+static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
+  return RowPlan{ctx->B, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau};
+}
+
+static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
+  return RowPlan{ctx->B * (ctx->L - 1), traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau};
+}
+
+__global__ void plan_dense_kernel(int n, int d, int n_tau, const int32_t* __restrict__ tau,
+                                  int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
+                                  int32_t* __restrict__ row_tau) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  in_off[i] = (int64_t)i * d;
+  out_off[i] = (int64_t)i * d;
+  row_tau[i] = min(max(tau[i], 0), n_tau - 1);
+}
+
+}  // namespace asd
+
+using namespace asd;
+
+extern "C" {
+
+asd_status asd_init(const asd_config* cfg, asd_ctx** out) {
+  if (!out) return fail(ASD_EINVAL, "out is NULL");
+  *out = nullptr;
+  ASD_TRY(validate(cfg));
+  asd_ctx* ctx = new (std::nothrow) asd_ctx();
+  if (!ctx) return fail(ASD_ENOMEM, "host allocation failed");
+  asd_status s = build(ctx, cfg);
+  if (s != ASD_OK) {
+    teardown(ctx);
+    return s;
+  }
+  *out = ctx;
+  return ASD_OK;
+}
+
+asd_status asd_destroy(asd_ctx* ctx) {
+  if (!ctx) return ASD_OK;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  teardown(ctx);
+  return ASD_OK;
+}
+
+asd_status asd_set_seed(asd_ctx* ctx, uint64_t seed) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ctx->key = make_key(seed);
+  return ASD_OK;
+}
+
+asd_status asd_draft(asd_ctx* ctx, float* traj, const int32_t* a, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  if (!a) return fail(ASD_EINVAL, "a is NULL");
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_draft called out of order (expected stage %d)", ctx->stage);
+  hipStream_t st = (hipStream_t)stream;
+  ASD_TRY(launch_plan_draft(ctx, a, st));
+  ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
+  ASD_TRY(launch_draft(ctx, traj, a, st));
+  ctx->stage = 1;
+  return ASD_OK;
+}
+
+asd_status asd_verify(asd_ctx* ctx, const float* traj, const int32_t* a, float* x0hat, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  ASD_TRY(check_rows_ptr(ctx, x0hat, "x0hat"));
+  if (!a) return fail(ASD_EINVAL, "a is NULL");
+  if (ctx->stage != 1) return fail(ASD_ESTATE, "asd_verify called out of order (expected stage %d)", ctx->stage);
+  hipStream_t st = (hipStream_t)stream;
+  ASD_TRY(launch_copy_slot0(ctx, x0hat, st));
+  if (ctx->L > 1) {
+    ASD_TRY(launch_plan_verify(ctx, a, st));
+    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
+  }
+  ctx->stage = 2;
+  return ASD_OK;
+}
+
+asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted, float* stats,
+                      void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  ASD_TRY(check_rows_ptr(ctx, x0hat, "x0hat"));
+  if (!a) return fail(ASD_EINVAL, "a is NULL");
+  if (ctx->stage != 2) return fail(ASD_ESTATE, "asd_accept called out of order (expected stage %d)", ctx->stage);
+  ASD_TRY(launch_accept(ctx, traj, a, x0hat, accepted, stats, nullptr, nullptr, (hipStream_t)stream));
+  ctx->stage = 0;
+  return ASD_OK;
+}
+
+asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample called between stage calls");
+  hipStream_t st = (hipStream_t)stream;
+  if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
+  ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, rounds, st));
+  // The live-chain count of a round is read back `lag` rounds later so that the
+  // host keeps queueing launches for cheap rounds; a finished batch then runs
+  // `lag` empty rounds (every kernel exits early on finished chains).  Rounds
+  // with heavy model calls are checked at once instead.
+  const double verify_work = (double)ctx->n_rows_max * ctx->model_macs_per_row;
+  const int lag = verify_work > 2.0e9 ? 0 : 2;
+  int r = 0;
+  int done_at = -1;
+  const int r_cap = ctx->K + lag + 1;  // Alg. 1 ends within K iterations (correctness theorem)
+  for (; r < r_cap; ++r) {
+    const int slot = r % kLiveRing;
+    ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live + slot));
+    ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
+    ASD_TRY(launch_draft(ctx, traj, ctx->a, st));
+    if (ctx->L > 1) {
+      ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
+      ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+    }
+    ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live + slot, st));
+    ASD_HIP(hipMemcpyAsync(ctx->live_host + slot, ctx->live + slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    ASD_HIP(hipEventRecord(ctx->live_ev[slot], st));
+    if (r >= lag) {
+      const int q = (r - lag) % kLiveRing;
+      ASD_HIP(hipEventSynchronize(ctx->live_ev[q]));
+      if (ctx->live_host[q] == 0) {
+        done_at = r - lag;
+        break;
+      }
+    }
+  }
+  ASD_HIP(hipStreamSynchronize(st));
+  if (done_at < 0) return fail(ASD_EDEVICE, "asd_sample: chains did not finish within %d rounds", r_cap);
+  ctx->last_rounds = done_at + 1;
+  return ASD_OK;
+}
+
+asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample_sequential called between stage calls");
+  hipStream_t st = (hipStream_t)stream;
+  ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, nullptr, st));
+  for (int i = 0; i < ctx->K; ++i) {
+    ASD_TRY(launch_plan_seq(ctx, i, st));
+    ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
+    ASD_TRY(launch_seq_step(ctx, traj, i, st));
+  }
+  ASD_HIP(hipStreamSynchronize(st));
+  return ASD_OK;
+}
+
+int32_t asd_last_round_count(const asd_ctx* ctx) { return ctx ? ctx->last_rounds : -1; }
+
+asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t n, float* out, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, x, "x"));
+  ASD_TRY(check_rows_ptr(ctx, out, "out"));
+  if (!tau) return fail(ASD_EINVAL, "tau is NULL");
+  if (n < 0 || n > ctx->n_rows_max) return fail(ASD_EINVAL, "n=%d outside [0, chains*L=%lld]", n, (long long)ctx->n_rows_max);
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_denoise called between stage calls");
+  if (n == 0) return ASD_OK;
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(plan_dense_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, n, ctx->d, ctx->n_tau,
+                     tau, ctx->in_off, ctx->out_off, ctx->row_tau);
+  ASD_HIP(hipGetLastError());
+  return model_eval(ctx, RowPlan{n, x, out, ctx->in_off, ctx->out_off, ctx->row_tau}, st);
+}
+
+asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,
+                            uint32_t* out, void* stream) {
+  if (!out || nblk < 1) return fail(ASD_EINVAL, "asd_debug_philox: bad arguments");
+  return launch_debug_philox(make_key(seed), chain, step, stream_id, nblk, out, (hipStream_t)stream);
+}
+
+asd_status asd_debug_randoms(uint64_t seed, uint32_t chain, uint32_t step, int32_t d, float* xi, float* u,
+                             void* stream) {
+  if (d < 0 || (!xi && !u) || (xi && d < 1)) return fail(ASD_EINVAL, "asd_debug_randoms: bad arguments");
+  return launch_debug_randoms(make_key(seed), chain, step, d, xi, u, (hipStream_t)stream);
+}
+
+asd_status asd_schedule_ddpm_linear(int32_t K, double beta_min, double beta_max, float* c_x, float* c_0,
+                                    float* sigma, int32_t* tau, float* abar) {
+  if (K < 1) return fail(ASD_EINVAL, "K must be >= 1");
+  if (!(beta_min > 0.0) || !(beta_max < 1.0) || !(beta_min <= beta_max))
+    return fail(ASD_EINVAL, "need 0 < beta_min <= beta_max < 1");
+  // abar_t = prod_{s<=t} (1 - beta_s), walked from t = 1 up; step i = K - t.
+  double ab_prev = 1.0;
+  if (abar) abar[0] = 1.0f;
+  for (int t = 1; t <= K; ++t) {
+    const double beta = (K > 1) ? beta_min + (double)(t - 1) * (beta_max - beta_min) / (double)(K - 1) : beta_min;
+    const double ab = ab_prev * (1.0 - beta);
+    const int i = K - t;
+    const double shrink = (1.0 - ab_prev) / (1.0 - ab);
+    if (c_x) c_x[i] = (float)(sqrt(1.0 - beta) * shrink);
+    if (c_0) c_0[i] = (float)(sqrt(ab_prev) * beta / (1.0 - ab));
+    if (sigma) sigma[i] = (float)sqrt(beta * shrink);
+    if (tau) tau[i] = t;
+    if (abar) abar[t] = (float)ab;
+    ab_prev = ab;
+  }
+  return ASD_OK;
+}
+
+const char* asd_status_string(asd_status s) {
+  switch (s) {
+    case ASD_OK: return "ASD_OK";
+    case ASD_EINVAL: return "ASD_EINVAL";
+    case ASD_ENOMEM: return "ASD_ENOMEM";
+    case ASD_EDEVICE: return "ASD_EDEVICE";
+    case ASD_ESTATE: return "ASD_ESTATE";
+    case ASD_EUNSUPPORTED: return "ASD_EUNSUPPORTED";
+  }
+  return "ASD_UNKNOWN";
+}
+
+const char* asd_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Shared declarations of the ASD library internals (host side + launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+
+#include "../../include/asd.h"
+#include "rng.h"
+
+namespace asd {
+
+// ---- error plumbing ---------------------------------------------------------
+void set_error(const char* fmt, ...);
+
+#define ASD_HIP(call)                                                              \
+  do {                                                                             \
+    hipError_t e__ = (call);                                                       \
+    if (e__ != hipSuccess) {                                                       \
+      ::asd::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+      return ASD_EDEVICE;                                                          \
+    }                                                                              \
+  } while (0)
+
+#define ASD_TRY(call)                 \
+  do {                                \
+    asd_status s__ = (call);          \
+    if (s__ != ASD_OK) return s__;    \
+  } while (0)
+
+// ---- a row of a batched model call -----------------------------------------
+// The denoiser is always evaluated on a *list of rows*: row n is read at
+// in_base + in_off[n] (d floats), its time index is tau[n], and its result is
+// written at out_base + out_off[n].  Draft call: one row per chain (y_a);
+// verify call: the drafted samples of slots 1..L-1 of every chain, read in
+// place from the trajectory and written into x0hat.
+struct RowPlan {
+  int n;                  // number of rows
+  const float* in_base;   // DEV
+  float* out_base;        // DEV
+  const int64_t* in_off;  // DEV [n], in floats
+  const int64_t* out_off; // DEV [n]
+  const int32_t* tau;     // DEV [n]
+};
+
+struct GmmState;
+struct MlpState;
+
+}  // namespace asd
+
+// The context behind the opaque handle.
+struct asd_ctx {
+  int device = 0;
+  int32_t K = 0, L = 0, B = 0, d = 0, n_tau = 0;
+  int64_t n_rows_max = 0;  // B * L
+  asd::Key key{0, 0};
+  int kind = 0;
+  // schedule on the device
+  float* c_x = nullptr;
+  float* c_0 = nullptr;
+  float* sigma = nullptr;
+  int32_t* tau = nullptr;
+  // row plan scratch
+  int64_t* in_off = nullptr;
+  int64_t* out_off = nullptr;
+  int32_t* row_tau = nullptr;
+  // x0a: model value at y_a of every chain [B, d]
+  float* x0a = nullptr;
+  // owned by asd_sample
+  float* x0hat = nullptr;  // [B, L, d]
+  int32_t* a = nullptr;    // [B]
+  int32_t* live = nullptr;       // DEV ring of live-chain counters
+  int32_t* live_host = nullptr;  // pinned mirror
+  hipEvent_t* live_ev = nullptr;
+  int32_t last_rounds = 0;
+  int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
+  double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
+  asd::GmmState* gmm = nullptr;
+  asd::MlpState* mlp = nullptr;
+};
+
+namespace asd {
+
+constexpr int kLiveRing = 8;
+
+// denoisers (gmm.hip / mlp.hip)
+asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den);
+void gmm_destroy(asd_ctx* ctx);
+asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
+
+asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den);
+void mlp_destroy(asd_ctx* ctx);
+asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
+
+inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
+  if (rows.n <= 0) return ASD_OK;
+  return ctx->kind == ASD_DEN_GMM ? gmm_eval(ctx, rows, st) : mlp_eval(ctx, rows, st);
+}
+
+// round kernels (round.hip)
+asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds, hipStream_t st);
+asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me = nullptr);
+asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st);
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st);
+asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st);
+asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
+                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st);
+asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st);
+asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st);
+asd_status launch_debug_philox(Key key, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,
+                               uint32_t* out, hipStream_t st);
+asd_status launch_debug_randoms(Key key, uint32_t chain, uint32_t step, int32_t d, float* xi, float* u,
+                                hipStream_t st);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace asd

@@ -1,0 +1,153 @@
+// fp32 "NT" GEMM on the gfx950 matrix cores:  acc[m][n] = sum_k A[m][k] * B[n][k]
+// with both operands K-contiguous, handed to an epilogue functor.
+//
+// Tiling: a workgroup of 4 wavefronts owns a 128 x 128 tile; each wavefront a
+// 64 x 64 quadrant as 2 x 2 blocks of v_mfma_f32_32x32x2_f32 (64 accumulator
+// VGPRs).  K is consumed in slabs of 16, staged through LDS with register
+// prefetch of the next slab (double-buffered LDS, one barrier per slab).
+//
+// Operand layout of the 32x32x2 instruction: lane l supplies A[row l%32][k l/32]
+// and B[col l%32][k l/32]; it receives 16 results, register r holding
+// C[8*(r/4) + 4*(l/32) + r%4][l%32].  The order in which k values are fed is
+// free as long as A and B agree, so each lane reads four consecutive k of its
+// row with one 128-bit LDS load and the four values go to four MFMAs: in MFMA
+// t of a group, half-wave h feeds k = 8*group + 4*h + t.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asd {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// Rows of the A operand: dense (base + m*ld) or gathered (base + off[m]).
+struct RowSrc {
+  const float* base;
+  const int64_t* off;
+  int64_t ld;
+  __device__ __forceinline__ const float* row(int m) const {
+    return off ? base + off[m] : base + (int64_t)m * ld;
+  }
+};
+
+namespace gemm32 {
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LDSS = BK + 4;  // row stride in floats (80 B): keeps 128-bit reads 16 B aligned
+constexpr int THREADS = 256;
+}  // namespace gemm32
+
+// Requirements (checked by the host launcher): K % 4 == 0, rows 16 B aligned.
+// M, N arbitrary (edge tiles clamp their loads and mask their stores).
+template <class Epi>
+__global__ __launch_bounds__(gemm32::THREADS, 2) void gemm_f32_nt_kernel(int M, int N, int K, RowSrc A,
+                                                                         const float* __restrict__ Bm,
+                                                                         int64_t ldb, Epi epi) {
+  using namespace gemm32;
+  __shared__ __attribute__((aligned(16))) float As[2][BM * LDSS];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDSS];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  // loader: thread handles rows (tid/4) and (tid/4 + 64), k-quad tid%4
+  const int lrow = tid >> 2, lkq = tid & 3;
+  const float* ap[2];
+  const float* bp[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int ra = min(m0 + lrow + 64 * i, M - 1);
+    const int rb = min(n0 + lrow + 64 * i, N - 1);
+    ap[i] = A.row(ra) + lkq * 4;
+    bp[i] = Bm + (int64_t)rb * ldb + lkq * 4;
+  }
+  const int nk = (K + BK - 1) / BK;
+
+  float4 ra[2], rb[2];
+  auto gload = [&](int kt) {
+    const int k = kt * BK + lkq * 4;
+    const bool ok = k < K;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      ra[i] = ok ? *reinterpret_cast<const float4*>(ap[i] + kt * BK) : make_float4(0.f, 0.f, 0.f, 0.f);
+      rb[i] = ok ? *reinterpret_cast<const float4*>(bp[i] + kt * BK) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      *reinterpret_cast<float4*>(&As[buf][(lrow + 64 * i) * LDSS + lkq * 4]) = ra[i];
+      *reinterpret_cast<float4*>(&Bs[buf][(lrow + 64 * i) * LDSS + lkq * 4]) = rb[i];
+    }
+  };
+
+  v16f acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) gload(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < BK / 8; ++ks) {
+      float4 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = *reinterpret_cast<const float4*>(&As[cur][(wm * 64 + i * 32 + l32) * LDSS + ks * 8 + half * 4]);
+        bf[i] = *reinterpret_cast<const float4*>(&Bs[cur][(wn * 64 + i * 32 + l32) * LDSS + ks * 8 + half * 4]);
+      }
+      const float a0[4] = {af[0].x, af[0].y, af[0].z, af[0].w};
+      const float a1[4] = {af[1].x, af[1].y, af[1].z, af[1].w};
+      const float b0[4] = {bf[0].x, bf[0].y, bf[0].z, bf[0].w};
+      const float b1[4] = {bf[1].x, bf[1].y, bf[1].z, bf[1].w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+      }
+    }
+    if (kt + 1 < nk) sstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: register r of block (i, j) is C[row][col] with
+  //   row = m0 + wm*64 + i*32 + 8*(r/4) + 4*half + r%4,  col = n0 + wn*64 + j*32 + l32
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int n = n0 + wn * 64 + j * 32 + l32;
+          if (n < N) epi(m, n, acc[i][j][r]);
+        }
+      }
+    }
+  }
+}
+
+template <class Epi>
+inline hipError_t launch_gemm_f32_nt(int M, int N, int K, RowSrc A, const float* Bm, int64_t ldb, Epi epi,
+                                     hipStream_t st) {
+  using namespace gemm32;
+  dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
+  hipLaunchKernelGGL((gemm_f32_nt_kernel<Epi>), grid, dim3(THREADS), 0, st, M, N, K, A, Bm, ldb, epi);
+  return hipGetLastError();
+}
+
+}  // namespace asd

@@ -1,0 +1,268 @@
+// Gaussian-mixture posterior-mean denoiser  D(x, tau) = E[x_0 | x_tau = x]
+// for data  sum_k w_k N(mu_k, s2 I)  (the mean function m(t, y) of Eq. sl-defn
+// for that law): the "model call" of Alg. 1 in the analytic workloads.
+//
+// With ab = abar[tau], V = ab*s2 + 1 - ab:
+//   logit_k = (sqrt(ab)/V) <x, mu_k> - (ab/(2V)) |mu_k|^2 + log w_k     (|x|^2 cancels)
+//   r       = softmax(logit)
+//   D       = (sqrt(ab) s2 / V) x + (1 - ab s2 / V) sum_k r_k mu_k
+// i.e. single-head attention with keys = values = the component means.
+//
+// Two paths:
+//  * row-wise kernel (one wavefront per row) for small or oddly shaped
+//    problems, where a launch is latency-bound anyway;
+//  * matrix-core path for large aligned problems: logits = X M^T (fp32 MFMA
+//    GEMM with the affine map fused in the epilogue) materialised in HBM
+//    [rows, C] -- at 288 GB of HBM the 1 GB of logits of the largest workload
+//    costs ~4% of the GEMM time to write and re-read, and keeps both GEMMs at
+//    full tile efficiency with head dimension d = 1024 -- then a row softmax,
+//    then P M (second MFMA GEMM against the pre-transposed means) with the
+//    final affine combination fused in the epilogue.
+#include "common.h"
+#include "gemm_f32.h"
+
+namespace asd {
+
+struct GmmState {
+  int C = 0;
+  float var = 0.f;
+  const float* means = nullptr;  // caller's [C, d]
+  const float* log_w = nullptr;  // caller's [C]
+  float* means_t = nullptr;      // [d, C]
+  float* musq = nullptr;         // [C]
+  float4* coef_tau = nullptr;    // [n_tau]: (kappa, gamma, cx, cm)
+  float* logits = nullptr;       // [rows_max, C] (matrix-core path only)
+  bool use_mfma = false;
+  size_t rowwise_lds = 0;
+};
+
+// (kappa, gamma, cx, cm) of a row
+__device__ __forceinline__ float4 row_coef(const float4* coef_tau, const int32_t* tau, int n) {
+  return coef_tau[tau[n]];
+}
+
+// ---------------------------------------------------------------------------
+// preparation kernels
+// ---------------------------------------------------------------------------
+__global__ void gmm_prep_kernel(int C, int d, const float* __restrict__ means, float* __restrict__ means_t,
+                                float* __restrict__ musq) {
+  const int k = blockIdx.x;
+  float s = 0.f;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    const float m = means[(int64_t)k * d + j];
+    means_t[(int64_t)j * C + k] = m;
+    s = fmaf(m, m, s);
+  }
+  __shared__ float red[256];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) musq[k] = red[0];
+}
+
+// ---------------------------------------------------------------------------
+// row-wise path: 4 wavefronts per workgroup, one row per wavefront per pass
+// LDS per wavefront: x[d] then p[C]
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gmm_rowwise_kernel(int nrows, int d, int C, const float* __restrict__ in_base,
+                                                          const int64_t* __restrict__ in_off,
+                                                          float* __restrict__ out_base,
+                                                          const int64_t* __restrict__ out_off,
+                                                          const int32_t* __restrict__ tau,
+                                                          const float4* __restrict__ coef_tau,
+                                                          const float* __restrict__ means,
+                                                          const float* __restrict__ musq,
+                                                          const float* __restrict__ log_w) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  float* xs = lds + (size_t)wave * (d + C);
+  float* ps = xs + d;
+  for (int base = blockIdx.x * 4; base < nrows; base += gridDim.x * 4) {
+    const int n = base + wave;
+    const bool active = n < nrows;
+    float4 cf = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* x = nullptr;
+    if (active) {
+      cf = row_coef(coef_tau, tau, n);
+      x = in_base + in_off[n];
+      for (int j = lane; j < d; j += 64) xs[j] = x[j];
+    }
+    __syncthreads();
+    float mx = -INFINITY;
+    if (active) {
+      for (int k = lane; k < C; k += 64) {
+        const float* mu = means + (int64_t)k * d;
+        float dot = 0.f;
+        for (int j = 0; j < d; ++j) dot = fmaf(xs[j], mu[j], dot);
+        const float lg = fmaf(cf.x, dot, fmaf(-cf.y, musq[k], log_w[k]));
+        ps[k] = lg;
+        mx = fmaxf(mx, lg);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float sum = 0.f;
+    if (active) {
+      for (int k = lane; k < C; k += 64) {
+        const float p = expf(ps[k] - mx);
+        ps[k] = p;
+        sum += p;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    __syncthreads();
+    if (active) {
+      const float inv = 1.0f / sum;
+      float* out = out_base + out_off[n];
+      for (int j = lane; j < d; j += 64) {
+        float acc = 0.f;
+        for (int k = 0; k < C; ++k) acc = fmaf(ps[k], means[(int64_t)k * d + j], acc);
+        out[j] = fmaf(cf.z, xs[j], cf.w * (acc * inv));
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// matrix-core path
+// ---------------------------------------------------------------------------
+struct LogitEpi {
+  float* logits;
+  int64_t ld;
+  const float4* coef_tau;
+  const int32_t* tau;
+  const float* musq;
+  const float* log_w;
+  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
+    const float4 cf = coef_tau[tau[m]];
+    logits[(int64_t)m * ld + n] = fmaf(cf.x, acc, fmaf(-cf.y, musq[n], log_w[n]));
+  }
+};
+
+// in-place row softmax of [rows, C]; one workgroup per row
+__global__ __launch_bounds__(256) void softmax_rows_kernel(int C, float* __restrict__ logits) {
+  __shared__ float red[4];
+  float* row = logits + (int64_t)blockIdx.x * C;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float mx = -INFINITY;
+  for (int k = tid; k < C; k += 256) mx = fmaxf(mx, row[k]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int k = tid; k < C; k += 256) {
+    const float p = expf(row[k] - mx);
+    row[k] = p;
+    sum += p;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  const float inv = 1.0f / (red[0] + red[1] + red[2] + red[3]);
+  for (int k = tid; k < C; k += 256) row[k] *= inv;
+}
+
+struct CombineEpi {
+  const float* in_base;
+  const int64_t* in_off;
+  float* out_base;
+  const int64_t* out_off;
+  const float4* coef_tau;
+  const int32_t* tau;
+  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
+    const float4 cf = coef_tau[tau[m]];
+    out_base[out_off[m] + n] = fmaf(cf.z, in_base[in_off[m] + n], cf.w * acc);
+  }
+};
+
+// ---------------------------------------------------------------------------
+// host
+// ---------------------------------------------------------------------------
+asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
+  GmmState* g = new (std::nothrow) GmmState();
+  if (!g) return ASD_ENOMEM;
+  ctx->gmm = g;
+  g->C = den.C;
+  g->var = den.var;
+  g->means = den.means;
+  g->log_w = den.log_w;
+  const int d = ctx->d, C = den.C;
+  ctx->model_macs_per_row = 2.0 * C * d;
+  ASD_HIP(hipMalloc(&g->means_t, sizeof(float) * (size_t)d * C));
+  ASD_HIP(hipMalloc(&g->musq, sizeof(float) * (size_t)C));
+  ASD_HIP(hipMalloc(&g->coef_tau, sizeof(float4) * (size_t)ctx->n_tau));
+  // per-time-index coefficients, in double on the host
+  float4* h = new (std::nothrow) float4[ctx->n_tau];
+  if (!h) return ASD_ENOMEM;
+  for (int t = 0; t < ctx->n_tau; ++t) {
+    const double ab = den.abar[t];
+    const double V = ab * (double)den.var + 1.0 - ab;
+    h[t].x = (float)(sqrt(ab) / V);
+    h[t].y = (float)(ab / (2.0 * V));
+    h[t].z = (float)(sqrt(ab) * (double)den.var / V);
+    h[t].w = (float)(1.0 - ab * (double)den.var / V);
+  }
+  hipError_t e = hipMemcpy(g->coef_tau, h, sizeof(float4) * (size_t)ctx->n_tau, hipMemcpyHostToDevice);
+  delete[] h;
+  ASD_HIP(e);
+  hipLaunchKernelGGL(gmm_prep_kernel, dim3(C), dim3(256), 0, 0, C, d, g->means, g->means_t, g->musq);
+  ASD_HIP(hipGetLastError());
+  ASD_HIP(hipDeviceSynchronize());
+
+  g->rowwise_lds = sizeof(float) * 4 * (size_t)(d + C);
+  const bool aligned = (d % 4 == 0) && (C % 4 == 0);
+  const bool big = (double)ctx->n_rows_max * C * d >= (double)(1 << 26);
+  const bool rowwise_ok = g->rowwise_lds <= 64 * 1024;
+  g->use_mfma = aligned && (big || !rowwise_ok);
+  if (!g->use_mfma && !rowwise_ok) {
+    set_error("GMM denoiser: C=%d, d=%d needs d %% 4 == 0 and C %% 4 == 0 at this size", C, d);
+    return ASD_EUNSUPPORTED;
+  }
+  if (g->use_mfma) ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
+  return ASD_OK;
+}
+
+void gmm_destroy(asd_ctx* ctx) {
+  GmmState* g = ctx->gmm;
+  if (!g) return;
+  (void)hipFree(g->means_t);
+  (void)hipFree(g->musq);
+  (void)hipFree(g->coef_tau);
+  (void)hipFree(g->logits);
+  delete g;
+  ctx->gmm = nullptr;
+}
+
+asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
+  GmmState* g = ctx->gmm;
+  const int d = ctx->d, C = g->C, n = rows.n;
+  if (!g->use_mfma) {
+    const int blocks = (int)std::min<int64_t>(ceil_div(n, 4), 4096);
+    hipLaunchKernelGGL(gmm_rowwise_kernel, dim3(blocks), dim3(256), g->rowwise_lds, st, n, d, C, rows.in_base,
+                       rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, g->means, g->musq,
+                       g->log_w);
+    ASD_HIP(hipGetLastError());
+    return ASD_OK;
+  }
+  RowSrc X{rows.in_base, rows.in_off, 0};
+  LogitEpi e1{g->logits, C, g->coef_tau, rows.tau, g->musq, g->log_w};
+  ASD_HIP(launch_gemm_f32_nt(n, C, d, X, g->means, d, e1, st));
+  hipLaunchKernelGGL(softmax_rows_kernel, dim3(n), dim3(256), 0, st, C, g->logits);
+  ASD_HIP(hipGetLastError());
+  RowSrc P{g->logits, nullptr, C};
+  CombineEpi e2{rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau};
+  ASD_HIP(launch_gemm_f32_nt(n, d, C, P, g->means_t, C, e2, st));
+  return ASD_OK;
+}
+
+}  // namespace asd

@@ -1,0 +1,67 @@
+// Device-side counter-based random numbers for ASD.
+//
+// Alg. 1 draws (u_1..u_K) and (xi_1..xi_K) once per chain and indexes them by
+// step.  Here nothing is stored: the value of (chain, step, coordinate) is a
+// pure function of the seed, recomputed wherever it is needed (the draft
+// kernel adds sigma*xi, the accept kernel needs the same xi for <v, xi> and for
+// the reflection), so the noise costs ALU work and no HBM traffic.
+//
+// Generator: Philox4x32-10 (Salmon et al., SC'11).  Counter =
+// (block = coordinate/4, step, chain, stream id), key = 64-bit seed.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asd {
+
+constexpr uint32_t kStreamXi = 0u;  // normals xi_i (step 0: the initial state y_0)
+constexpr uint32_t kStreamU = 1u;   // uniforms u_i of the accept test
+
+struct Key {
+  uint32_t k0, k1;
+};
+
+__host__ __device__ inline Key make_key(uint64_t seed) {
+  return Key{(uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32)};
+}
+
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, Key key) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t k0 = key.k0, k1 = key.k1;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)M0 * c.x;
+    const uint64_t p1 = (uint64_t)M1 * c.z;
+    const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+    const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+    c = make_uint4(hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0);
+    k0 += W0;
+    k1 += W1;
+  }
+  return c;
+}
+
+// ((w >> 9) + 1/2) * 2^-23: 23 random bits, centred, exact in fp32, in (0,1).
+__device__ __forceinline__ float word_to_uniform(uint32_t w) {
+  return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;
+}
+
+// Four standard normals for coordinates 4*blk .. 4*blk+3 of (chain, step):
+// Box-Muller on (w0, w1) -> (r cos, r sin) and on (w2, w3) likewise.
+__device__ __forceinline__ float4 normal4(Key key, uint32_t chain, uint32_t step, uint32_t blk) {
+  const uint4 w = philox4x32_10(make_uint4(blk, step, chain, kStreamXi), key);
+  const float r0 = sqrtf(-2.0f * logf(word_to_uniform(w.x)));
+  const float r1 = sqrtf(-2.0f * logf(word_to_uniform(w.z)));
+  float s0, c0, s1, c1;
+  sincospif(2.0f * word_to_uniform(w.y), &s0, &c0);
+  sincospif(2.0f * word_to_uniform(w.w), &s1, &c1);
+  return make_float4(r0 * c0, r0 * s0, r1 * c1, r1 * s1);
+}
+
+__device__ __forceinline__ float uniform1(Key key, uint32_t chain, uint32_t step) {
+  const uint4 w = philox4x32_10(make_uint4(0u, step, chain, kStreamU), key);
+  return word_to_uniform(w.x);
+}
+
+}  // namespace asd

@@ -1,0 +1,391 @@
+// Round kernels of ASD: state initialisation, row planning for the two model
+// calls, the fused draft kernel (Alg. 1, proposal means and samples) and the
+// fused accept / first-rejection scan / reflection-resample kernel
+// (Alg. 3 on every slot, Alg. 2, and the advance rule of Alg. 1).
+#include "common.h"
+
+namespace asd {
+
+// ----------------------------------------------------------------------------
+// helpers: a row of d floats is handled in blocks of four coordinates, one
+// Philox call per block.  d need not be a multiple of four.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ float4 load4(const float* p, int blk, int d, bool vec) {
+  if (vec) return reinterpret_cast<const float4*>(p)[blk];
+  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int j = blk * 4;
+  if (j + 0 < d) r.x = p[j + 0];
+  if (j + 1 < d) r.y = p[j + 1];
+  if (j + 2 < d) r.z = p[j + 2];
+  if (j + 3 < d) r.w = p[j + 3];
+  return r;
+}
+
+__device__ __forceinline__ void store4(float* p, int blk, int d, bool vec, float4 v) {
+  if (vec) {
+    reinterpret_cast<float4*>(p)[blk] = v;
+    return;
+  }
+  const int j = blk * 4;
+  if (j + 0 < d) p[j + 0] = v.x;
+  if (j + 1 < d) p[j + 1] = v.y;
+  if (j + 2 < d) p[j + 2] = v.z;
+  if (j + 3 < d) p[j + 3] = v.w;
+}
+
+// ----------------------------------------------------------------------------
+// y_0, a = 0, rounds = 0
+// ----------------------------------------------------------------------------
+__global__ void init_state_kernel(int B, int K, int d, Key key, const float* __restrict__ y0,
+                                  float* __restrict__ traj, int32_t* __restrict__ a,
+                                  int32_t* __restrict__ rounds) {
+  const int c = blockIdx.x;
+  const int nblk = (d + 3) >> 2;
+  const bool vec = (d & 3) == 0;
+  float* row = traj + (int64_t)c * (K + 1) * d;
+  for (int blk = threadIdx.x; blk < nblk; blk += blockDim.x) {
+    float4 v = y0 ? load4(y0 + (int64_t)c * d, blk, d, vec) : normal4(key, (uint32_t)c, 0u, (uint32_t)blk);
+    store4(row, blk, d, vec, v);
+  }
+  if (threadIdx.x == 0) {
+    a[c] = 0;
+    if (rounds) rounds[c] = 0;
+  }
+}
+
+asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key, y0,
+                     traj, a, rounds);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// ----------------------------------------------------------------------------
+// Row plans.  Draft call: row c = y_a of chain c.  Verify call: row
+// c*(L-1)+(s-1) = proposal sample of slot s (s = 1..L-1) of chain c.  Rows of
+// finished chains or beyond the window are clamped to a valid trajectory row;
+// their results are never read.
+// ----------------------------------------------------------------------------
+__global__ void plan_draft_kernel(int B, int K, int d, const int32_t* __restrict__ a,
+                                  const int32_t* __restrict__ tau, int64_t* __restrict__ in_off,
+                                  int64_t* __restrict__ out_off, int32_t* __restrict__ row_tau,
+                                  int32_t* __restrict__ zero_me) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c == 0 && zero_me) *zero_me = 0;  // live-chain counter of the round that starts here
+  if (c >= B) return;
+  const int ac = min(max(a[c], 0), K);
+  in_off[c] = ((int64_t)c * (K + 1) + ac) * d;
+  out_off[c] = (int64_t)c * d;
+  row_tau[c] = tau[min(ac, K - 1)];
+}
+
+__global__ void plan_verify_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
+                                   const int32_t* __restrict__ tau, int64_t* __restrict__ in_off,
+                                   int64_t* __restrict__ out_off, int32_t* __restrict__ row_tau) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= B * (L - 1)) return;
+  const int c = n / (L - 1);
+  const int s = n - c * (L - 1) + 1;
+  const int ac = min(max(a[c], 0), K);
+  const int i = min(ac + s, K);
+  in_off[n] = ((int64_t)c * (K + 1) + i) * d;
+  out_off[n] = ((int64_t)c * L + s) * d;
+  row_tau[n] = tau[min(i, K - 1)];
+}
+
+asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me) {
+  hipLaunchKernelGGL(plan_draft_kernel, dim3((unsigned)ceil_div(ctx->B, 256)), dim3(256), 0, st, ctx->B, ctx->K,
+                     ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau, zero_me);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
+  const int64_t n = (int64_t)ctx->B * (ctx->L - 1);
+  if (n <= 0) return ASD_OK;
+  hipLaunchKernelGGL(plan_verify_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, ctx->B, ctx->K,
+                     ctx->L, ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// ----------------------------------------------------------------------------
+// Draft (Alg. 1, proposal loop): for k = 0..w-1, i = a+k,
+//   yhat_{i+1} = c_x[i] yhat_i + c_0[i] x0a + sigma[i] xi_{i+1},
+// written straight into traj[c][i+1].  A first-order linear recurrence along
+// the window, independent per coordinate: one thread owns four coordinates and
+// walks the window; rows are written coalesced.  HBM-bound: reads 2 rows,
+// writes w rows per chain.
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, Key key,
+                                                    const int32_t* __restrict__ a,
+                                                    const float* __restrict__ c_x,
+                                                    const float* __restrict__ c_0,
+                                                    const float* __restrict__ sigma,
+                                                    const float* __restrict__ x0a, float* __restrict__ traj) {
+  const int c = blockIdx.y;
+  const int blk = blockIdx.x * blockDim.x + threadIdx.x;
+  const int nblk = (d + 3) >> 2;
+  const int ac = a[c];
+  if (blk >= nblk || ac >= K || ac < 0) return;
+  const bool vec = (d & 3) == 0;
+  const int w = min(Lwin, K - ac);
+  float* row = traj + ((int64_t)c * (K + 1) + ac) * d;
+  float4 y = load4(row, blk, d, vec);
+  const float4 g = load4(x0a + (int64_t)c * d, blk, d, vec);
+  for (int k = 0; k < w; ++k) {
+    const int i = ac + k;
+    const float cx = c_x[i], c0 = c_0[i], sg = sigma[i];
+    const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(i + 1), (uint32_t)blk);
+    y.x = fmaf(sg, xi.x, fmaf(cx, y.x, c0 * g.x));
+    y.y = fmaf(sg, xi.y, fmaf(cx, y.y, c0 * g.y));
+    y.z = fmaf(sg, xi.z, fmaf(cx, y.z, c0 * g.z));
+    y.w = fmaf(sg, xi.w, fmaf(cx, y.w, c0 * g.w));
+    row += d;
+    store4(row, blk, d, vec, y);
+  }
+}
+
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st) {
+  const int nblk = (ctx->d + 3) / 4;
+  const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
+  dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
+  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a, ctx->c_x,
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// Sequential baseline: every chain takes step `step` (window of one).
+__global__ void fill_i32_kernel(int n, int32_t v, int32_t* p) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)ceil_div(ctx->B, 256)), dim3(256), 0, st, ctx->B, step,
+                     ctx->a);
+  ASD_HIP(hipGetLastError());
+  return launch_plan_draft(ctx, ctx->a, st);
+}
+
+asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st) {
+  (void)step;
+  const int nblk = (ctx->d + 3) / 4;
+  const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
+  dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
+  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key, ctx->a, ctx->c_x,
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// x0hat[c][0][:] = x0a[c][:]
+__global__ void copy_slot0_kernel(int B, int L, int d, const float* __restrict__ x0a, float* __restrict__ x0hat) {
+  const int c = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < d) x0hat[(int64_t)c * L * d + j] = x0a[(int64_t)c * d + j];
+}
+
+asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st) {
+  dim3 grid((unsigned)ceil_div(ctx->d, 256), (unsigned)ctx->B);
+  hipLaunchKernelGGL(copy_slot0_kernel, grid, dim3(256), 0, st, ctx->B, ctx->L, ctx->d, ctx->x0a, x0hat);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// ----------------------------------------------------------------------------
+// Accept + scan + resample + advance.  One workgroup (4 wavefronts) per chain.
+//
+// Phase 1 (Alg. 3, accept test): wavefront q takes slots k = 1+q, 5+q, ...;
+//   with D = x0a - x0hat[k] (so v = c_0 D) it reduces <D, xi> and |D|^2 over
+//   the row, regenerating xi_{a+k+1} from the counter, and lane 0 evaluates
+//       rho = -( c_0 <D,xi> / sigma + c_0^2 |D|^2 / (2 sigma^2) ),
+//       bit = [ log u_{a+k+1} <= rho ].
+//   Slot 0 (step a+1) has v == 0 by construction and is accepted; a slot with
+//   sigma == 0 is rejected (sigma -> 0 limit of the test).
+// Phase 2 (Alg. 2): one wavefront ballots the <= 64 bits into a mask and
+//   counts its trailing ones: n_acc = length of the accepted prefix.
+// Phase 3 (Alg. 3 reject branch + advance rule of Alg. 1): if n_acc < w the
+//   row of step r = a + n_acc + 1 becomes
+//       m + sigma (xi - 2 v <v,xi>/|v|^2) = yhat_r - D (c_0 + 2 sigma <D,xi>/|D|^2)
+//   (using yhat = m + v + sigma xi), and a <- r; else a <- a + w.
+// HBM-bound: reads (w+1) rows of x0hat and one trajectory row, writes one row.
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key key, int32_t* __restrict__ a,
+                                                     const float* __restrict__ c_0,
+                                                     const float* __restrict__ sigma,
+                                                     const float* __restrict__ x0a,
+                                                     const float* __restrict__ x0hat, float* __restrict__ traj,
+                                                     int32_t* __restrict__ accepted, float* __restrict__ stats,
+                                                     int32_t* __restrict__ rounds, int32_t* __restrict__ live) {
+  __shared__ float s_dot[64];
+  __shared__ float s_vv[64];
+  __shared__ int s_bit[64];
+  __shared__ int s_nacc;
+
+  const int c = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int ac = a[c];
+  if (ac >= K || ac < 0) {
+    if (tid == 0 && accepted) accepted[c] = -1;
+    return;
+  }
+  const int w = min(L, K - ac);
+  const int nblk = (d + 3) >> 2;
+  const bool vec = (d & 3) == 0;
+  const float* g_a = x0a + (int64_t)c * d;
+  const float* g_w = x0hat + (int64_t)c * L * d;
+
+  if (tid < 64) {
+    s_dot[tid] = 0.f;
+    s_vv[tid] = 0.f;
+    s_bit[tid] = (tid == 0) ? 1 : 0;
+  }
+  __syncthreads();
+
+  for (int k = 1 + wave; k < w; k += 4) {
+    const int i = ac + k;
+    const float* g_k = g_w + (int64_t)k * d;
+    float dot = 0.f, vv = 0.f;
+    for (int blk = lane; blk < nblk; blk += 64) {
+      const float4 ga = load4(g_a, blk, d, vec);
+      const float4 gk = load4(g_k, blk, d, vec);
+      const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(i + 1), (uint32_t)blk);
+      // coordinates past d load as zero in both rows, so they add nothing
+      const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
+      dot = fmaf(dx, xi.x, dot);
+      dot = fmaf(dy, xi.y, dot);
+      dot = fmaf(dz, xi.z, dot);
+      dot = fmaf(dw, xi.w, dot);
+      vv = fmaf(dx, dx, vv);
+      vv = fmaf(dy, dy, vv);
+      vv = fmaf(dz, dz, vv);
+      vv = fmaf(dw, dw, vv);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      dot += __shfl_xor(dot, off, 64);
+      vv += __shfl_xor(vv, off, 64);
+    }
+    if (lane == 0) {
+      const float sg = sigma[i], c0 = c_0[i];
+      float rho = -INFINITY, logu = 0.f;
+      int bit = 0;
+      if (sg > 0.f) {
+        const float vxi = c0 * dot;
+        const float v2 = c0 * c0 * vv;
+        rho = -(vxi / sg + v2 / (2.0f * sg * sg));
+        logu = logf(uniform1(key, (uint32_t)c, (uint32_t)(i + 1)));
+        bit = (logu <= rho) ? 1 : 0;
+      }
+      s_dot[k] = dot;
+      s_vv[k] = vv;
+      s_bit[k] = bit;
+      if (stats) {
+        float* sp = stats + ((int64_t)c * L + k) * 4;
+        sp[0] = dot;
+        sp[1] = vv;
+        sp[2] = logu;
+        sp[3] = rho;
+      }
+    }
+  }
+  __syncthreads();
+
+  if (wave == 0) {
+    const int bit = (lane < w) ? s_bit[lane] : 0;
+    const unsigned long long mask = __ballot(bit);
+    // trailing ones of the mask = accepted prefix (bit 0 is always set)
+    const unsigned long long inv = ~mask;
+    const int n_acc = inv ? (__ffsll((long long)inv) - 1) : 64;
+    if (lane == 0) s_nacc = min(n_acc, w);
+  }
+  __syncthreads();
+  const int n_acc = s_nacc;
+
+  int a_next;
+  if (n_acc < w) {
+    const int k = n_acc;  // slot index of the first rejection (>= 1)
+    const int i = ac + k;
+    const float sg = sigma[i], c0 = c_0[i];
+    const float dot = s_dot[k], vv = s_vv[k];
+    const float coef = (vv > 0.f) ? (c0 + 2.0f * sg * dot / vv) : 0.f;
+    const float* g_k = g_w + (int64_t)k * d;
+    float* row = traj + ((int64_t)c * (K + 1) + i + 1) * d;
+    for (int blk = tid; blk < nblk; blk += 256) {
+      const float4 ga = load4(g_a, blk, d, vec);
+      const float4 gk = load4(g_k, blk, d, vec);
+      float4 y = load4(row, blk, d, vec);
+      y.x = fmaf(-(ga.x - gk.x), coef, y.x);
+      y.y = fmaf(-(ga.y - gk.y), coef, y.y);
+      y.z = fmaf(-(ga.z - gk.z), coef, y.z);
+      y.w = fmaf(-(ga.w - gk.w), coef, y.w);
+      store4(row, blk, d, vec, y);
+    }
+    a_next = i + 1;
+  } else {
+    a_next = ac + w;
+  }
+  if (tid == 0) {
+    a[c] = a_next;
+    if (accepted) accepted[c] = n_acc;
+    if (rounds) rounds[c] += 1;
+    if (live && a_next < K) atomicAdd(live, 1);
+    if (stats) {
+      float* sp = stats + (int64_t)c * L * 4;
+      sp[0] = sp[1] = sp[2] = sp[3] = 0.f;
+    }
+  }
+}
+
+asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
+                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a,
+                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+// ----------------------------------------------------------------------------
+// debug: raw generator words / normals / uniform of one (chain, step)
+// ----------------------------------------------------------------------------
+__global__ void debug_philox_kernel(Key key, uint32_t chain, uint32_t step, uint32_t stream_id, int nblk,
+                                    uint32_t* out) {
+  const int blk = blockIdx.x * blockDim.x + threadIdx.x;
+  if (blk >= nblk) return;
+  const uint4 w = philox4x32_10(make_uint4((uint32_t)blk, step, chain, stream_id), key);
+  out[4 * blk + 0] = w.x;
+  out[4 * blk + 1] = w.y;
+  out[4 * blk + 2] = w.z;
+  out[4 * blk + 3] = w.w;
+}
+
+__global__ void debug_randoms_kernel(Key key, uint32_t chain, uint32_t step, int d, float* xi, float* u) {
+  const int blk = blockIdx.x * blockDim.x + threadIdx.x;
+  const int nblk = (d + 3) >> 2;
+  if (blk < nblk && xi) store4(xi, blk, d, false, normal4(key, chain, step, (uint32_t)blk));
+  if (blk == 0 && u) u[0] = uniform1(key, chain, step);
+}
+
+asd_status launch_debug_philox(Key key, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,
+                               uint32_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(debug_philox_kernel, dim3((unsigned)ceil_div(nblk, 256)), dim3(256), 0, st, key, chain,
+                     step, stream_id, nblk, out);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+asd_status launch_debug_randoms(Key key, uint32_t chain, uint32_t step, int32_t d, float* xi, float* u,
+                                hipStream_t st) {
+  const int nblk = (d + 3) / 4;
+  hipLaunchKernelGGL(debug_randoms_kernel, dim3((unsigned)ceil_div(nblk > 0 ? nblk : 1, 256)), dim3(256), 0, st,
+                     key, chain, step, d, xi, u);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
+}  // namespace asd

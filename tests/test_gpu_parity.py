@@ -1,0 +1,296 @@
+"""GPU parity: the HIP library (through its C boundary) against the CPU oracle,
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import asd_workloads as W
+from oracle import asd as oasd
+from oracle import philox
+from oracle_helpers import chain_randoms, oracle_setup
+
+pytestmark = pytest.mark.gpu
+
+try:
+    from paper_2505_03983_amd import binding, runtime
+    import gpu_helpers as H
+except Exception:  # pragma: no cover - import errors surface in the tests
+    raise
+
+DEV = "cuda:0"
+
+
+def _log(*a):
+    print(*a, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# random numbers
+# ---------------------------------------------------------------------------
+def test_philox_words_bit_identical():
+    for seed, chain, step, sid in [(0, 0, 0, 0), (12345, 7, 999, 1), ((1 << 40) + 17, 1023, 1000, 0)]:
+        nblk = 300
+        out = torch.zeros((nblk, 4), dtype=torch.int32, device=DEV)
+        binding.asd_debug_philox(seed, chain, step, sid, nblk, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint32)
+        ctr = np.zeros((nblk, 4), dtype=np.uint64)
+        ctr[:, 0] = np.arange(nblk)
+        ctr[:, 1], ctr[:, 2], ctr[:, 3] = step, chain, sid
+        want = philox.philox4x32_10(ctr, philox.seed_key(seed))
+        assert np.array_equal(got, want)
+
+
+def test_normals_and_uniforms_match_oracle():
+    d = 1023
+    worst = 0.0
+    for seed, chain, step in [(0, 0, 0), (3, 5, 17), (99, 1000, 1000)]:
+        xi = torch.zeros(d, dtype=torch.float32, device=DEV)
+        u = torch.zeros(1, dtype=torch.float32, device=DEV)
+        binding.asd_debug_randoms(seed, chain, step, d, xi, u)
+        torch.cuda.synchronize()
+        want = philox.normals(seed, chain, [step], d)[0]
+        worst = max(worst, float(np.max(np.abs(xi.cpu().numpy() - want))))
+        assert float(u.cpu()[0]) == philox.uniforms(seed, chain, [step])[0]      # exact in fp32
+    _log("max |xi_dev - xi_oracle| =", worst)
+    assert worst < 5e-6
+
+
+# ---------------------------------------------------------------------------
+# denoisers
+# ---------------------------------------------------------------------------
+def _denoise_case(cfg, n_rows, seed=0, chains=None, L=None):
+    T, p, model = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=seed, chains=chains, L=L)
+    rng = np.random.default_rng(seed)
+    tau = rng.integers(1, cfg["K"] + 1, n_rows).astype(np.int32)
+    ab = T["abar"][tau]
+    if cfg["kind"] == "gmm":     # clean samples of the data law: a component mean plus within-component noise
+        x0 = p["means"][rng.integers(0, cfg["C"], n_rows)] + np.sqrt(p["var"]) * rng.standard_normal((n_rows, cfg["d"]))
+    else:
+        x0 = 2.0 * rng.standard_normal((n_rows, cfg["d"]))
+    x = (np.sqrt(ab)[:, None] * x0 + np.sqrt(1 - ab)[:, None] * rng.standard_normal((n_rows, cfg["d"]))).astype(np.float32)
+    xd = torch.from_numpy(x).to(DEV)
+    out = torch.zeros_like(xd)
+    ctx.denoise(xd, torch.from_numpy(tau).to(DEV), out)
+    torch.cuda.synchronize()
+    want = model(K_minus(tau, cfg["K"]), x.astype(np.float64))
+    ctx.close()
+    return out.cpu().numpy(), want
+
+
+def K_minus(tau, K):
+    return K - np.asarray(tau)          # step index i with tau[i] = K - i
+
+
+@pytest.mark.parametrize("shape", [dict(d=2, C=4), dict(d=64, C=256), dict(d=7, C=5), dict(d=3, C=130)])
+def test_gmm_rowwise_denoiser(shape):
+    cfg = dict(kind="gmm", K=50, chains=4, L=8, var=0.25, **shape)
+    got, want = _denoise_case(cfg, 29)
+    e = H.rel_err(got, want)
+    _log("gmm rowwise", shape, "rel err", e)
+    assert e <= 1e-4
+
+
+@pytest.mark.parametrize("shape", [dict(d=128, C=384, rows=300), dict(d=36, C=132, rows=131), dict(d=1024, C=4096, rows=160)])
+def test_gmm_matrix_core_denoiser(shape):
+    rows = shape.pop("rows")
+    # enough rows*C*d to select the matrix-core path
+    chains = max(8, -(-rows // 16), int(np.ceil((1 << 26) / (shape["C"] * shape["d"] * 16))) + 1)
+    cfg = dict(kind="gmm", K=50, chains=chains, L=16, var=0.25, **shape)
+    got, want = _denoise_case(cfg, rows)
+    e = H.rel_err(got, want)
+    _log("gmm mfma", shape, "rows", rows, "rel err", e)
+    assert e <= 1e-4
+
+
+@pytest.mark.parametrize("shape", [dict(d=8, E=8, width=16, n_blocks=1, rows=5),
+                                   dict(d=112, E=128, width=1024, n_blocks=4, rows=200),
+                                   dict(d=40, E=24, width=136, n_blocks=2, rows=131)])
+def test_mlp_denoiser(shape):
+    rows = shape.pop("rows")
+    cfg = dict(kind="mlp", K=20, chains=16, L=16, **shape)
+    got, want = _denoise_case(cfg, rows)
+    e = H.rel_err(got, want)
+    _log("mlp", shape, "rel err", e)
+    assert e <= 2e-2
+    assert e <= 5e-3     # observed far below the 2e-2 bar; guards against layout slips hidden by the loose bar
+
+
+# ---------------------------------------------------------------------------
+# one round, teacher-forced from oracle states
+# ---------------------------------------------------------------------------
+def _teacher_forced(cfg, seed, chains_checked, rounds_per_chain=4, model_seed=1):
+    T, p, model = oracle_setup(cfg, model_seed)
+    tol = H.TOL[cfg["kind"]]
+    ctx = runtime.open_ctx(cfg, p, seed=seed)
+    B, K = cfg["chains"], cfg["K"]
+    recs = {}
+    for c in chains_checked:
+        y, R, rounds, xi, u = H.oracle_chain(cfg, T, model, seed, c, eps=tol)
+        recs[c] = (y, rounds)
+    n_checked = n_skipped = 0
+    for t in range(rounds_per_chain):
+        states = []
+        picked = {}
+        for c in range(B):
+            if c in recs:
+                y, rounds = recs[c]
+                # spread picks over the run: first, middle, late and the final round
+                idx = [0, len(rounds) // 2, max(len(rounds) - 2, 0), len(rounds) - 1][t % 4]
+                rec = rounds[idx]
+                picked[c] = rec
+                states.append((rec["a"], y[rec["a"]].astype(np.float32)))
+            else:
+                states.append((K, np.zeros(cfg["d"], np.float32)))       # finished chain: must stay untouched
+        out = H.teacher_forced_round(ctx, cfg, states)
+        for c, rec in picked.items():
+            ok = H.compare_round(out, c, rec, tol, K)
+            n_checked += ok
+            n_skipped += (not ok)
+        for c in range(B):
+            if c not in recs:
+                assert out["a_next"][c] == K and out["accepted"][c] == -1
+                assert not out["traj"][c].any()
+    ctx.close()
+    _log("teacher-forced", cfg["kind"], "d", cfg["d"], "rounds compared", n_checked, "skipped at near-ties", n_skipped)
+    assert n_checked >= 0.8 * (n_checked + n_skipped)
+
+
+def test_round_config1():
+    _teacher_forced(W.CONFIGS[1], seed=0, chains_checked=range(8))
+
+
+def test_round_config2():
+    _teacher_forced(W.CONFIGS[2], seed=0, chains_checked=[0, 1, 31, 63])
+
+
+def test_round_config3_bf16_mlp():
+    _teacher_forced(W.CONFIGS[3], seed=0, chains_checked=[0, 100, 255], rounds_per_chain=4)
+
+
+def test_round_ragged_shapes():
+    # d not a multiple of 4, K not a multiple of L, tiny K
+    for cfg in (dict(kind="gmm", d=7, C=5, K=23, chains=5, L=6, var=0.25),
+                dict(kind="gmm", d=3, C=9, K=2, chains=3, L=64, var=0.25),
+                dict(kind="gmm", d=5, C=3, K=1, chains=2, L=4, var=0.25)):
+        _teacher_forced(cfg, seed=5, chains_checked=range(cfg["chains"] - 1))
+
+
+# ---------------------------------------------------------------------------
+# whole samples, free-running
+# ---------------------------------------------------------------------------
+def _free_running(cfg, seed, chains_checked, y0=None):
+    T, p, model = oracle_setup(cfg)
+    tol = H.TOL[cfg["kind"]]
+    ctx = runtime.open_ctx(cfg, p, seed=seed)
+    traj = runtime.alloc_traj(ctx)
+    rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    n_launch = ctx.sample(traj, rounds)
+    tj, rd = traj.cpu().numpy(), rounds.cpu().numpy()
+    assert n_launch == rd.max()
+    full = 0
+    for c in chains_checked:
+        y, R, recs, xi, u = H.oracle_chain(cfg, T, model, seed, c, eps=tol)
+        # first step whose decision is flagged as a near-tie inside an examined prefix
+        stop = None
+        for rec in recs:
+            n_acc = rec["j"] - rec["a"]
+            fl = np.nonzero(rec["flagged"][: min(n_acc + 1, rec["b"] - rec["a"])])[0]
+            if fl.size:
+                stop = rec["a"]          # compare up to the state this round started from
+                break
+        upto = cfg["K"] if stop is None else stop
+        e = H.rel_err(tj[c, : upto + 1], y[: upto + 1])
+        assert e <= tol, ("trajectory", c, e, upto)
+        if stop is None:
+            assert rd[c] == R, ("rounds", c, rd[c], R)
+            full += 1
+    ctx.close()
+    _log("free-running", cfg["kind"], "d", cfg["d"], "chains fully compared", full, "of", len(list(chains_checked)),
+         "rounds mean/max", rd.mean(), rd.max())
+    return full
+
+
+def test_sample_config1_all_chains():
+    full = 0
+    for seed in range(4):
+        full += _free_running(W.CONFIGS[1], seed, range(8))
+    assert full >= 24
+
+
+def test_sample_config2_subset():
+    assert _free_running(W.CONFIGS[2], 0, [0, 17, 63]) >= 1
+
+
+def test_sample_is_deterministic_and_chain_local():
+    cfg = W.CONFIGS[2]
+    T, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=3)
+    t1, t2 = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+    r1 = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    r2 = torch.zeros_like(r1)
+    ctx.sample(t1, r1)
+    ctx.sample(t2, r2)
+    assert torch.equal(t1, t2) and torch.equal(r1, r2)
+    ctx.close()
+    # a batch of 5 chains reproduces the first 5 chains of the batch of 64 (counter keyed by chain id)
+    ctx5 = runtime.open_ctx(cfg, p, seed=3, chains=5)
+    t5 = runtime.alloc_traj(ctx5)
+    ctx5.sample(t5)
+    assert torch.equal(t5, t1[:5])
+    ctx5.close()
+
+
+def test_L1_equals_sequential_sampler_bitwise():
+    cfg = dict(W.CONFIGS[1], L=1)
+    T, p, model = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=2)
+    ta, ts = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+    rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    ctx.sample(ta, rounds)
+    ctx.sample_sequential(ts)
+    assert torch.equal(ta, ts)
+    assert (rounds.cpu().numpy() == cfg["K"]).all()
+    for c in (0, 7):
+        xi, _ = chain_randoms(2, c, cfg["K"], cfg["d"])
+        ys = oasd.sequential_chain(xi[0], T["c_x"], T["c_0"], T["sigma"], model, xi)
+        assert H.rel_err(ts[c].cpu().numpy(), ys) <= 1e-4
+    ctx.close()
+
+
+def test_given_y0_and_sigma_zero_last_step():
+    cfg = W.CONFIGS[1]
+    T, p, model = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=4)
+    y0 = torch.full((cfg["chains"], cfg["d"]), 0.5, dtype=torch.float32, device=DEV)
+    traj = runtime.alloc_traj(ctx)
+    ctx.sample(traj, y0=y0)
+    tj = traj.cpu().numpy()
+    assert (tj[:, 0] == 0.5).all()
+    # last step is deterministic: y_K = c_x y_{K-1} + c_0 D(y_{K-1})
+    K = cfg["K"]
+    g = model([K - 1] * cfg["chains"], tj[:, K - 1].astype(np.float64))
+    want = T["c_x"][K - 1] * tj[:, K - 1] + T["c_0"][K - 1] * g
+    assert H.rel_err(tj[:, K], want) <= 1e-4
+    ctx.close()
+
+
+def test_stage_order_is_enforced():
+    cfg = W.CONFIGS[1]
+    _, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p)
+    traj = runtime.alloc_traj(ctx)
+    a = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    x0 = torch.zeros((cfg["chains"], cfg["L"], cfg["d"]), dtype=torch.float32, device=DEV)
+    with pytest.raises(binding.AsdError) as ei:
+        ctx.verify(traj, a, x0)
+    assert ei.value.status == binding.ASD_ESTATE
+    traj.zero_()
+    ctx.draft(traj, a)
+    with pytest.raises(binding.AsdError):
+        ctx.draft(traj, a)
+    ctx.verify(traj, a, x0)
+    ctx.accept(traj, a, x0)
+    torch.cuda.synchronize()
+    ctx.close()
