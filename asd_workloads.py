@@ -53,9 +53,12 @@ def sinusoidal_table(n_rows, E):
     return f32_to_bf16_bits(tab.astype(np.float32))
 
 
-def mlp_params(d, E, width, n_blocks, K, model_seed=1):
+def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0):
     """Weights ~ N(0, 1/fan_in) rounded to bf16 (uint16 patterns), zero biases
-    (fp32), time-embedding table [K+1, E] (bf16 patterns), row-major [out, in]."""
+    (fp32), time-embedding table [K+1, E] (bf16 patterns), row-major [out, in].
+    out_clip: the predicted x_0 is clipped to [-1, 1] as DDPM samplers commonly
+    do (a random-weight network is not a contraction; without the clip the
+    chain leaves the fp32 range within a few hundred steps)."""
     rng = _rng(model_seed, 2)
 
     def w(out_f, in_f):
@@ -70,6 +73,7 @@ def mlp_params(d, E, width, n_blocks, K, model_seed=1):
         b_blk=np.zeros((n_blocks, width), dtype=np.float32),
         b_out=np.zeros(d, dtype=np.float32),
         temb=sinusoidal_table(K + 1, E),
+        out_clip=float(out_clip),
     )
 
 

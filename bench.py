@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the ASD hot path on one MI355X.
+
+One "step" of this benchmark is one complete `asd_sample` over the whole batch
+of chains of the workload: every round (draft model call, draft, batched
+verify model call, accept/scan/resample) until every chain has reached K.
+The metric is DDPM steps per second = chains * K / wall-clock of a sample,
+with all inputs resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see README for the fields).  Besides the
+throughput it carries
+  roofline      the dominant kernel of the workload against the MI355X peak,
+                timed live with HIP events on the launch stream,
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a
+                bounded sample of the same workload (a reported baseline).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK = {"f32": 157.3, "bf16": 2500.0}          # dense MFMA TFLOP/s, MI355X
+HBM_PEAK_GBS = 8000.0
+
+
+def workload_name(w, cfg):
+    if cfg["kind"] == "gmm":
+        return "cfg%d: GMM denoiser d=%d C=%d K=%d chains=%d L=%d fp32" % (
+            w, cfg["d"], cfg["C"], cfg["K"], cfg["chains"], cfg["L"])
+    return "cfg%d: MLP denoiser d=%d E=%d width=%d blocks=%d K=%d chains=%d L=%d bf16 weights, fp32 state" % (
+        w, cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], cfg["chains"], cfg["L"])
+
+
+def run_gpu(w, steps, warmup, seed, profile=True):
+    import torch
+    import asd_workloads as W
+    from paper_2505_03983_amd import binding, runtime
+
+    cfg = W.CONFIGS[w]
+    params = W.make_params(cfg, model_seed=1)
+    ctx = runtime.open_ctx(cfg, params, seed=seed)
+    traj = runtime.alloc_traj(ctx)
+    rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device="cuda:0")
+    for i in range(warmup):
+        ctx.set_seed(seed + 1000 + i)
+        ctx.sample(traj, rounds)
+    torch.cuda.synchronize()
+    if profile:
+        ctx.profile_enable(True)
+    launched = []
+    rmean, rmax = [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ctx.set_seed(seed + i)
+        launched.append(ctx.sample(traj, rounds))
+        if not profile:
+            continue
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    r = rounds.cpu().numpy()
+    rmean.append(float(r.mean()))
+    rmax.append(int(r.max()))
+    finite = bool(torch.isfinite(traj[:, -1]).all().item())
+    wall = t1 - t0
+    out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
+               ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
+               rounds_launched=launched, finite=finite)
+    if profile:
+        P = binding.PROF
+        table = {}
+        for name, kid in P.items():
+            for call in (0, 1):
+                n, ms = ctx.profile_read(kid, call)
+                if n:
+                    table["%s/%s" % (name, "verify" if call else "draft")] = dict(launches=n, total_ms=ms,
+                                                                                 avg_us=1e3 * ms / n)
+        out["kernels"] = table
+        out["rows"] = ctx.profile_rows()
+        ctx.profile_enable(False)
+    ctx.close()
+    del traj
+    torch.cuda.empty_cache()
+    return out
+
+
+def roofline(res):
+    """Roofline entry of the dominant kernel of a profiled run."""
+    cfg, k = res["cfg"], res["kernels"]
+    draft_rows, verify_rows = res["rows"]
+    if cfg["kind"] == "gmm":
+        cand = [n for n in ("GMM_LOGITS/verify", "GMM_COMBINE/verify", "GMM_ROWWISE/verify") if n in k]
+        name = max(cand, key=lambda n: k[n]["total_ms"])
+        launches = k[name]["launches"]
+        # 2*C*d flops per row for either GEMM (the row-wise kernel does both: 4*C*d)
+        per_row = (4.0 if name.startswith("GMM_ROWWISE") else 2.0) * cfg["C"] * cfg["d"]
+        dtype = "f32"
+        # the row-wise kernel runs on the vector ALUs; its bound is the fp32 vector peak (same figure)
+        bound = "mfma" if not name.startswith("GMM_ROWWISE") else "alu"
+    else:
+        name = "MLP_GEMM_BLK/verify"
+        launches = k[name]["launches"]
+        per_row = 2.0 * cfg["width"] * cfg["width"]
+        verify_rows = verify_rows * cfg["n_blocks"]      # one launch per block, each over all rows
+        dtype = "bf16"
+        bound = "mfma"
+    flops_per_launch = per_row * verify_rows / launches
+    avg_s = 1e-3 * k[name]["total_ms"] / launches
+    achieved = flops_per_launch / avg_s / 1e12
+    peak = PEAK[dtype]
+    return dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
+                traffic=None, avg_launch_us=1e6 * avg_s, launches=launches,
+                algorithmic_flops_per_launch=flops_per_launch,
+                share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
+
+
+def hbm_kernels(res):
+    """Achieved algorithmic HBM bandwidth of the draft and accept kernels."""
+    cfg, k = res["cfg"], res["kernels"]
+    draft_rows, verify_rows = res["rows"]
+    d = cfg["d"]
+    # draft: reads y_a and x0a (2 rows), writes w rows; accept: reads w rows of x0hat (w-1 new + x0a) and one
+    # trajectory row, writes one row.  w summed over chains and rounds = verify_rows + draft_rows.
+    w_total = verify_rows + draft_rows
+    out = {}
+    if "DRAFT/draft" in k:
+        b = 4.0 * d * (2 * draft_rows + w_total)
+        out["draft"] = dict(GBps=b / (1e-3 * k["DRAFT/draft"]["total_ms"]) / 1e9,
+                            avg_us=k["DRAFT/draft"]["avg_us"])
+    if "ACCEPT/draft" in k:
+        b = 4.0 * d * (w_total + 3 * draft_rows)
+        out["accept"] = dict(GBps=b / (1e-3 * k["ACCEPT/draft"]["total_ms"]) / 1e9,
+                             avg_us=k["ACCEPT/draft"]["avg_us"])
+    for v in out.values():
+        v["frac_of_hbm_peak"] = v["GBps"] / HBM_PEAK_GBS
+    return out
+
+
+def cpu_baseline(w, seed, budget_s=15.0):
+    """The oracle as it stands, timed on the host: ASD rounds of single chains
+    of the same workload until `budget_s` seconds have been spent."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import asd_workloads as W
+    from oracle import asd as oasd
+    from oracle_helpers import chain_randoms, oracle_setup
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:                                   # pragma: no cover
+        threadpool_limits = None
+    cfg = W.CONFIGS[w]
+    T, p, model = oracle_setup(cfg)
+    K, L = cfg["K"], cfg["L"]
+    ctxmgr = threadpool_limits(limits=1) if threadpool_limits else None
+    steps_done = rounds_done = 0
+    t0 = time.perf_counter()
+    chain = 0
+    try:
+        while time.perf_counter() - t0 < budget_s:
+            xi, u = chain_randoms(seed, chain, K, cfg["d"])
+            a, y = 0, xi[0]
+            while a < K and time.perf_counter() - t0 < budget_s:
+                rec = oasd.asd_round(y, a, L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+                y = rec["y_new"][-1]
+                steps_done += rec["a_next"] - a
+                a = rec["a_next"]
+                rounds_done += 1
+            chain += 1
+    finally:
+        if ctxmgr is not None:
+            ctxmgr.__exit__(None, None, None)
+    el = time.perf_counter() - t0
+    return dict(value=steps_done / el, unit="DDPM steps/s", cores=1, kind="oracle",
+                sample="%d ASD rounds (%d DDPM steps) of single chains (chain ids 0..%d) of the same workload, "
+                       "fp64 numpy, BLAS limited to 1 thread, %.1f s" % (rounds_done, steps_done, chain - 1, el))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=5, help="1..5 (asd_workloads.CONFIGS)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--others", type=int, default=1, help="also time the other four workloads (1 sample each)")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (chains shard trivially across GPUs, see DESIGN.md); "
+              "got --gpus %d" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library is the only path (no CPU fallback)", file=sys.stderr)
+        sys.exit(3)
+    import asd_workloads as W
+
+    res = run_gpu(args.workload, args.steps, args.warmup, args.seed)
+    if not res["finite"]:
+        print("bench.py: non-finite samples", file=sys.stderr)
+        sys.exit(4)
+    cfg = res["cfg"]
+    line = {
+        "metric": "DDPM steps/s (chains*K/wall) for ASD at 1 GPU",
+        "value": res["steps_per_s"],
+        "unit": "DDPM steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["ms_per_sample"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if cfg["kind"] == "gmm" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": workload_name(args.workload, cfg), "chains": cfg["chains"], "K": cfg["K"],
+                   "L": cfg["L"], "d": cfg["d"]},
+        "rounds_per_sample": {"mean": res["rounds_mean"], "max": res["rounds_max"],
+                              "launched": res["rounds_launched"]},
+        "roofline": roofline(res),
+        "hbm_kernels": hbm_kernels(res),
+        "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
+                        "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()},
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.workload, args.seed)
+    if args.others:
+        others = {}
+        for w in sorted(W.CONFIGS):
+            if w == args.workload:
+                continue
+            r = run_gpu(w, 1, 1, args.seed)
+            rf = roofline(r)
+            others["cfg%d" % w] = dict(workload=workload_name(w, r["cfg"]), steps_per_s=r["steps_per_s"],
+                                       ms_per_sample=r["ms_per_sample"], rounds_mean=r["rounds_mean"],
+                                       rounds_max=r["rounds_max"], roofline_kernel=rf["kernel"],
+                                       roofline_frac=rf["frac"], achieved=rf["achieved"], peak=rf["peak"],
+                                       hbm_kernels=hbm_kernels(r))
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -79,7 +79,9 @@ typedef enum { ASD_DEN_GMM = 1, ASD_DEN_MLP = 2 } asd_den_kind;
  *   means DEV fp32 [C, d] row-major; log_w DEV fp32 [C] (unnormalised logs
  *   allowed); abar HOST fp32 [n_tau], values in (0, 1].
  * MLP: in = [bf16(x) ; temb[tau]] (d + temb_dim), h = W_in in + b_in,
- *   n_blocks times h += SiLU(W_l bf16(h) + b_l), out = W_out bf16(h) + b_out.
+ *   n_blocks times h += SiLU(W_l bf16(h) + b_l), out = W_out bf16(h) + b_out,
+ *   D = clamp(out, -out_clip, out_clip) if out_clip > 0 (the usual clipping of
+ *   the predicted x_0 to the data range), D = out if out_clip == 0.
  *   Weights DEV bf16 row-major [out, in]: w_in [width, d+temb_dim],
  *   w_blk [n_blocks, width, width], w_out [d, width]; biases DEV fp32 or NULL
  *   (= 0): b_in [width], b_blk [n_blocks, width], b_out [d];
@@ -97,6 +99,7 @@ typedef struct {
   const float* abar;
   /* MLP */
   int32_t width, n_blocks, linears_per_block, temb_dim;
+  float out_clip;
   const void* w_in;
   const void* w_blk;
   const void* w_out;
@@ -180,6 +183,34 @@ ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step
 /* xi DEV fp32 [d] = the normals of (chain, step); u DEV fp32 [1] = the uniform. */
 ASD_API asd_status asd_debug_randoms(uint64_t seed, uint32_t chain, uint32_t step, int32_t d,
                              float* xi, float* u, void* stream);
+
+/* ---- per-kernel timing -------------------------------------------------------
+ * When enabled, every kernel launch of the sampling path is bracketed by HIP
+ * events on its own stream.  asd_profile_read synchronises the device and
+ * returns, for one kernel kind within one of the two model calls (call = 0:
+ * the draft call on one row per chain, call = 1: the batched verify call;
+ * kinds that belong to no model call use call = 0), the number of launches
+ * and their summed duration since the last asd_profile_enable(ctx, 1).
+ * asd_profile_rows returns the number of live rows (rows inside a window of an
+ * unfinished chain) the two model calls were asked to evaluate since then. */
+typedef enum {
+  ASD_PROF_MODEL = 0,        /* a whole model call (all its kernels)          */
+  ASD_PROF_PLAN = 1,         /* row planning                                  */
+  ASD_PROF_GMM_ROWWISE = 2,  /* GMM denoiser, one wavefront per row           */
+  ASD_PROF_GMM_LOGITS = 3,   /* GMM logits GEMM  X M^T  (fp32 MFMA)           */
+  ASD_PROF_GMM_SOFTMAX = 4,  /* GMM row softmax                               */
+  ASD_PROF_GMM_COMBINE = 5,  /* GMM  P M  GEMM + affine combination           */
+  ASD_PROF_MLP_PACK = 6,     /* MLP input packing (bf16 x ; time embedding)   */
+  ASD_PROF_MLP_GEMM_IN = 7,  /* MLP first layer                               */
+  ASD_PROF_MLP_GEMM_BLK = 8, /* MLP residual blocks (one launch per block)    */
+  ASD_PROF_MLP_GEMM_OUT = 9, /* MLP output layer                              */
+  ASD_PROF_DRAFT = 10,       /* fused draft kernel                            */
+  ASD_PROF_ACCEPT = 11,      /* fused accept / scan / resample kernel         */
+  ASD_PROF_KINDS = 16
+} asd_prof_kernel;
+ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
+ASD_API asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms);
+ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows);
 
 /* ---- host-only helpers -----------------------------------------------------
  * DDPM linear-beta schedule (beta_tau from beta_min to beta_max over tau=1..K)

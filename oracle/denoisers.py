@@ -88,12 +88,14 @@ def bf16_bits_to_f64(bits):
 
 
 def silu(z):
-    return z / (1.0 + np.exp(-z))
+    with np.errstate(over="ignore"):      # exp(-z) = inf for very negative z gives -0.0, the right limit
+        return z / (1.0 + np.exp(-z))
 
 
 class MLPOracle:
     """x0hat = W_out h_n + b_out, h_0 = W_in [x ; temb(tau)] + b_in,
-    h_{l+1} = h_l + SiLU(W_l h_l + b_l).
+    h_{l+1} = h_l + SiLU(W_l h_l + b_l); the result is clipped to
+    [-out_clip, out_clip] when out_clip > 0.
 
     Every matrix-product input is rounded to bf16 just before the product;
     weights are bf16; sums, bias, SiLU and the residual stream are fp64 here
@@ -108,6 +110,7 @@ class MLPOracle:
         self.b_blk = np.asarray(params["b_blk"], dtype=np.float64)
         self.b_out = np.asarray(params["b_out"], dtype=np.float64)
         self.temb = bf16_bits_to_f64(params["temb"])       # [K+1, E]
+        self.out_clip = float(params.get("out_clip", 0.0))  # 0: no clipping
 
     def __call__(self, x, tau):
         x = np.atleast_2d(np.asarray(x, dtype=np.float64))
@@ -116,4 +119,7 @@ class MLPOracle:
         h = inp @ self.w_in.T + self.b_in
         for l in range(self.w_blk.shape[0]):
             h = h + silu(round_to_bf16(h) @ self.w_blk[l].T + self.b_blk[l])
-        return round_to_bf16(h) @ self.w_out.T + self.b_out
+        out = round_to_bf16(h) @ self.w_out.T + self.b_out
+        if self.out_clip > 0.0:            # predicted x_0 clipped to the data range
+            out = np.clip(out, -self.out_clip, self.out_clip)
+        return out

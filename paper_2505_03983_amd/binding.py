@@ -12,6 +12,8 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 
 ASD_OK, ASD_EINVAL, ASD_ENOMEM, ASD_EDEVICE, ASD_ESTATE, ASD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ASD_DEN_GMM, ASD_DEN_MLP = 1, 2
+PROF = dict(MODEL=0, PLAN=1, GMM_ROWWISE=2, GMM_LOGITS=3, GMM_SOFTMAX=4, GMM_COMBINE=5, MLP_PACK=6, MLP_GEMM_IN=7,
+            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11)
 
 
 class AsdError(RuntimeError):
@@ -30,7 +32,7 @@ class asd_denoiser(C.Structure):
                 ("C", C.c_int32), ("means", C.c_void_p), ("log_w", C.c_void_p), ("var", C.c_float),
                 ("abar", C.c_void_p),
                 ("width", C.c_int32), ("n_blocks", C.c_int32), ("linears_per_block", C.c_int32),
-                ("temb_dim", C.c_int32),
+                ("temb_dim", C.c_int32), ("out_clip", C.c_float),
                 ("w_in", C.c_void_p), ("w_blk", C.c_void_p), ("w_out", C.c_void_p),
                 ("b_in", C.c_void_p), ("b_blk", C.c_void_p), ("b_out", C.c_void_p), ("temb", C.c_void_p)]
 
@@ -62,6 +64,9 @@ def lib():
             "asd_sample_sequential": (i32, [vp, vp, vp, vp]),
             "asd_last_round_count": (i32, [vp]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
+            "asd_profile_enable": (i32, [vp, i32]),
+            "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
+            "asd_profile_rows": (i32, [vp, vp, vp]),
             "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
             "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
@@ -148,6 +153,7 @@ def make_config(sched, den, L, chains, seed):
         cfg.den.n_blocks = int(den["n_blocks"])
         cfg.den.linears_per_block = int(den.get("linears_per_block", 1))
         cfg.den.temb_dim = int(den["temb_dim"])
+        cfg.den.out_clip = float(den.get("out_clip", 0.0))
         for k in ("w_in", "w_blk", "w_out", "b_in", "b_blk", "b_out", "temb"):
             setattr(cfg.den, k, _ptr(den.get(k)))
     keep.append(den)
@@ -193,6 +199,19 @@ class Ctx:
 
     def sample_sequential(self, traj, y0=None, stream=None):
         _check(lib().asd_sample_sequential(self.h, _ptr(y0), _ptr(traj), _stream(stream)))
+
+    def profile_enable(self, on=True):
+        _check(lib().asd_profile_enable(self.h, int(bool(on))))
+
+    def profile_read(self, kernel, call=0):
+        n, ms = C.c_int64(0), C.c_double(0.0)
+        _check(lib().asd_profile_read(self.h, int(kernel), int(call), C.addressof(n), C.addressof(ms)))
+        return n.value, ms.value
+
+    def profile_rows(self):
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(lib().asd_profile_rows(self.h, C.addressof(a), C.addressof(b)))
+        return a.value, b.value
 
     def denoise(self, x, tau, out, stream=None):
         _check(lib().asd_denoise(self.h, _ptr(x), _ptr(tau), int(x.shape[0]), _ptr(out), _stream(stream)))

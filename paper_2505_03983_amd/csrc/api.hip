@@ -62,6 +62,7 @@ static asd_status validate(const asd_config* cfg) {
     if (m.width < 1 || m.n_blocks < 0 || m.temb_dim < 0) return fail(ASD_EINVAL, "bad MLP shape");
     if (!m.w_in || !m.w_out || (m.n_blocks > 0 && !m.w_blk) || (m.temb_dim > 0 && !m.temb))
       return fail(ASD_EINVAL, "MLP parameter pointer is NULL");
+    if (!(m.out_clip >= 0.f)) return fail(ASD_EINVAL, "out_clip must be >= 0");
     if (m.linears_per_block != 1) return fail(ASD_EUNSUPPORTED, "linears_per_block must be 1");
     if (m.d % 8 || m.temb_dim % 8 || m.width % 8)
       return fail(ASD_EUNSUPPORTED, "MLP needs d, temb_dim and width to be multiples of 8");
@@ -112,6 +113,8 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->row_tau, sizeof(int32_t) * rows));
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
+  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 2));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * kLiveRing));
   ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * kLiveRing));
   ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * kLiveRing, hipHostMallocDefault));
@@ -137,6 +140,8 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->x0hat);
   (void)hipFree(ctx->a);
   (void)hipFree(ctx->live);
+  (void)hipFree(ctx->row_counts);
+  ctx->prof.destroy();
   if (ctx->live_host) (void)hipHostFree(ctx->live_host);
   if (ctx->live_ev) {
     for (int i = 0; i < kLiveRing; ++i)
@@ -147,11 +152,11 @@ static void teardown(asd_ctx* ctx) {
 }
 
 static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
-  return RowPlan{ctx->B, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau};
+  return RowPlan{ctx->B, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau, 0};
 }
 
 static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
-  return RowPlan{ctx->B * (ctx->L - 1), traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau};
+  return RowPlan{ctx->B * (ctx->L - 1), traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
 }
 
 __global__ void plan_dense_kernel(int n, int d, int n_tau, const int32_t* __restrict__ tau,
@@ -314,7 +319,43 @@ asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t
   hipLaunchKernelGGL(plan_dense_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, n, ctx->d, ctx->n_tau,
                      tau, ctx->in_off, ctx->out_off, ctx->row_tau);
   ASD_HIP(hipGetLastError());
-  return model_eval(ctx, RowPlan{n, x, out, ctx->in_off, ctx->out_off, ctx->row_tau}, st);
+  return model_eval(ctx, RowPlan{n, x, out, ctx->in_off, ctx->out_off, ctx->row_tau, 1}, st);
+}
+
+asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_HIP(hipDeviceSynchronize());
+  ctx->prof.reset();
+  ctx->prof.on = on != 0;
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
+  return ASD_OK;
+}
+
+asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms) {
+  ASD_TRY(check_ctx(ctx));
+  if (kernel < 0 || kernel >= ASD_PROF_KINDS || call < 0 || call > 1) return fail(ASD_EINVAL, "bad profile slot");
+  ASD_HIP(hipDeviceSynchronize());
+  int64_t n = 0;
+  double ms = 0.0;
+  for (const Profiler::Rec& r : ctx->prof.recs) {
+    if (r.slot != kernel + 16 * call) continue;
+    float t = 0.f;
+    ASD_HIP(hipEventElapsedTime(&t, r.e0, r.e1));
+    ms += t;
+    ++n;
+  }
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
+  return ASD_OK;
+}
+
+asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows) {
+  ASD_TRY(check_ctx(ctx));
+  int64_t h[2] = {0, 0};
+  ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
+  if (draft_rows) *draft_rows = h[0];
+  if (verify_rows) *verify_rows = h[1];
+  return ASD_OK;
 }
 
 asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <string>
+#include <vector>
 
 #include "../../include/asd.h"
 #include "rng.h"
@@ -41,10 +42,41 @@ struct RowPlan {
   const int64_t* in_off;  // DEV [n], in floats
   const int64_t* out_off; // DEV [n]
   const int32_t* tau;     // DEV [n]
+  int call;               // 0: draft model call (one row per chain), 1: verify (batched)
 };
 
 struct GmmState;
 struct MlpState;
+
+// Optional per-kernel timing with HIP events recorded on the launch stream.
+// Slot = kernel kind + 16 * call kind (see asd_prof_kernel in asd.h).
+struct Profiler {
+  struct Rec {
+    int slot;
+    hipEvent_t e0, e1;
+  };
+  bool on = false;
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  hipEvent_t take() {
+    if (used == pool.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+  void reset() {
+    recs.clear();
+    used = 0;
+  }
+  void destroy() {
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+    pool.clear();
+    reset();
+  }
+};
 
 }  // namespace asd
 
@@ -74,6 +106,8 @@ struct asd_ctx {
   hipEvent_t* live_ev = nullptr;
   int32_t last_rounds = 0;
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
+  asd::Profiler prof;
+  int64_t* row_counts = nullptr;  // DEV [2]: live rows summed over launches (draft call, verify call)
   double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
   asd::GmmState* gmm = nullptr;
   asd::MlpState* mlp = nullptr;
@@ -82,6 +116,27 @@ struct asd_ctx {
 namespace asd {
 
 constexpr int kLiveRing = 8;
+
+// Times everything launched on `st` during its lifetime under `slot`.
+struct ProfScope {
+  asd_ctx* ctx;
+  hipStream_t st;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int slot;
+  ProfScope(asd_ctx* c, int kernel, int call, hipStream_t s) : ctx(c), st(s), slot(kernel + 16 * call) {
+    if (!ctx->prof.on) return;
+    e0 = ctx->prof.take();
+    e1 = ctx->prof.take();
+    if (e0 && e1) (void)hipEventRecord(e0, st);
+  }
+  ~ProfScope() {
+    if (e0 && e1) {
+      (void)hipEventRecord(e1, st);
+      ctx->prof.recs.push_back({slot, e0, e1});
+    }
+  }
+};
+
 
 // denoisers (gmm.hip / mlp.hip)
 asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den);
@@ -94,6 +149,7 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
 
 inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   if (rows.n <= 0) return ASD_OK;
+  ProfScope ps(ctx, ASD_PROF_MODEL, rows.call, st);
   return ctx->kind == ASD_DEN_GMM ? gmm_eval(ctx, rows, st) : mlp_eval(ctx, rows, st);
 }
 

@@ -38,7 +38,8 @@ constexpr int THREADS = 256;
 
 // Requirements (checked by the host launcher): K % 4 == 0, rows 16 B aligned.
 // M, N arbitrary (edge tiles clamp their loads and mask their stores).
-template <class Epi>
+// CALL only gives the draft-call and verify-call launches distinct symbols in profiles.
+template <class Epi, int CALL>
 __global__ __launch_bounds__(gemm32::THREADS, 2) void gemm_f32_nt_kernel(int M, int N, int K, RowSrc A,
                                                                          const float* __restrict__ Bm,
                                                                          int64_t ldb, Epi epi) {
@@ -141,12 +142,12 @@ __global__ __launch_bounds__(gemm32::THREADS, 2) void gemm_f32_nt_kernel(int M, 
   }
 }
 
-template <class Epi>
+template <int CALL, class Epi>
 inline hipError_t launch_gemm_f32_nt(int M, int N, int K, RowSrc A, const float* Bm, int64_t ldb, Epi epi,
                                      hipStream_t st) {
   using namespace gemm32;
   dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-  hipLaunchKernelGGL((gemm_f32_nt_kernel<Epi>), grid, dim3(THREADS), 0, st, M, N, K, A, Bm, ldb, epi);
+  hipLaunchKernelGGL((gemm_f32_nt_kernel<Epi, CALL>), grid, dim3(THREADS), 0, st, M, N, K, A, Bm, ldb, epi);
   return hipGetLastError();
 }
 

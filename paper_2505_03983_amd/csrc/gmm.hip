@@ -247,6 +247,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   GmmState* g = ctx->gmm;
   const int d = ctx->d, C = g->C, n = rows.n;
   if (!g->use_mfma) {
+    ProfScope ps(ctx, ASD_PROF_GMM_ROWWISE, rows.call, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(n, 4), 4096);
     hipLaunchKernelGGL(gmm_rowwise_kernel, dim3(blocks), dim3(256), g->rowwise_lds, st, n, d, C, rows.in_base,
                        rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, g->means, g->musq,
@@ -256,12 +257,23 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   RowSrc X{rows.in_base, rows.in_off, 0};
   LogitEpi e1{g->logits, C, g->coef_tau, rows.tau, g->musq, g->log_w};
-  ASD_HIP(launch_gemm_f32_nt(n, C, d, X, g->means, d, e1, st));
-  hipLaunchKernelGGL(softmax_rows_kernel, dim3(n), dim3(256), 0, st, C, g->logits);
-  ASD_HIP(hipGetLastError());
+  {
+    ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
+    ASD_HIP(rows.call ? launch_gemm_f32_nt<1>(n, C, d, X, g->means, d, e1, st)
+                      : launch_gemm_f32_nt<0>(n, C, d, X, g->means, d, e1, st));
+  }
+  {
+    ProfScope ps(ctx, ASD_PROF_GMM_SOFTMAX, rows.call, st);
+    hipLaunchKernelGGL(softmax_rows_kernel, dim3(n), dim3(256), 0, st, C, g->logits);
+    ASD_HIP(hipGetLastError());
+  }
   RowSrc P{g->logits, nullptr, C};
   CombineEpi e2{rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau};
-  ASD_HIP(launch_gemm_f32_nt(n, d, C, P, g->means_t, C, e2, st));
+  {
+    ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
+    ASD_HIP(rows.call ? launch_gemm_f32_nt<1>(n, d, C, P, g->means_t, C, e2, st)
+                      : launch_gemm_f32_nt<0>(n, d, C, P, g->means_t, C, e2, st));
+  }
   return ASD_OK;
 }
 

@@ -3,7 +3,7 @@
 //   in  = [ bf16(x) ; temb[tau] ]                    (d + E)
 //   h   = W_in in + b_in
 //   h  += SiLU( W_l bf16(h) + b_l )                  l = 0..n_blocks-1
-//   out = W_out bf16(h) + b_out                      interpreted as E[x_0 | x]
+//   out = W_out bf16(h) + b_out,  D = clamp(out, -clip, clip)   interpreted as E[x_0 | x]
 // Every matrix product takes bf16 inputs and accumulates in fp32 on the matrix
 // cores; bias, SiLU and the residual stream are fp32 and are fused into the
 // GEMM epilogues, which also emit the bf16 copy of h the next product reads.
@@ -14,6 +14,7 @@ namespace asd {
 
 struct MlpState {
   int width = 0, n_blocks = 0, E = 0, in_dim = 0;
+  float out_clip = 0.f;
   const uint16_t* w_in = nullptr;
   const uint16_t* w_blk = nullptr;
   const uint16_t* w_out = nullptr;
@@ -80,8 +81,11 @@ struct OutEpi {  // out[out_off[m] + n] = acc + b
   float* out_base;
   const int64_t* out_off;
   const float* bias;
+  float clip;  // 0: none
   __device__ __forceinline__ void operator()(int m, int n, float acc) const {
-    out_base[out_off[m] + n] = acc + (bias ? bias[n] : 0.f);
+    float v = acc + (bias ? bias[n] : 0.f);
+    if (clip > 0.f) v = fminf(fmaxf(v, -clip), clip);
+    out_base[out_off[m] + n] = v;
   }
 };
 
@@ -92,6 +96,7 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den) {
   s->width = den.width;
   s->n_blocks = den.n_blocks;
   s->E = den.temb_dim;
+  s->out_clip = den.out_clip;
   s->in_dim = ctx->d + den.temb_dim;
   s->w_in = (const uint16_t*)den.w_in;
   s->w_blk = (const uint16_t*)den.w_blk;
@@ -125,6 +130,7 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   MlpState* s = ctx->mlp;
   const int n = rows.n, d = ctx->d, W = s->width;
   {
+    ProfScope ps(ctx, ASD_PROF_MLP_PACK, rows.call, st);
     const int groups = s->in_dim / 8;
     const int threads = groups >= 256 ? 256 : 64;
     dim3 grid((unsigned)n, (unsigned)ceil_div(groups, threads));
@@ -132,17 +138,27 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                        rows.tau, s->temb, s->in_bf);
     ASD_HIP(hipGetLastError());
   }
-  ASD_HIP(launch_gemm_bf16_nt(n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim,
-                              InEpi{s->h, s->hb[0], s->b_in, W}, st));
+  {
+    ProfScope ps(ctx, ASD_PROF_MLP_GEMM_IN, rows.call, st);
+    const InEpi e{s->h, s->hb[0], s->b_in, W};
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st)
+                      : launch_gemm_bf16_nt<0>(n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st));
+  }
   int cur = 0;
   for (int l = 0; l < s->n_blocks; ++l) {
-    ASD_HIP(launch_gemm_bf16_nt(n, W, W, s->hb[cur], W, s->w_blk + (size_t)l * W * W, W,
-                                BlockEpi{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W},
-                                st));
+    ProfScope ps(ctx, ASD_PROF_MLP_GEMM_BLK, rows.call, st);
+    const BlockEpi e{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W};
+    const uint16_t* wl = s->w_blk + (size_t)l * W * W;
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, W, W, s->hb[cur], W, wl, W, e, st)
+                      : launch_gemm_bf16_nt<0>(n, W, W, s->hb[cur], W, wl, W, e, st));
     cur ^= 1;
   }
-  ASD_HIP(launch_gemm_bf16_nt(n, d, W, s->hb[cur], W, s->w_out, W, OutEpi{rows.out_base, rows.out_off, s->b_out},
-                              st));
+  {
+    ProfScope ps(ctx, ASD_PROF_MLP_GEMM_OUT, rows.call, st);
+    const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip};
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, d, W, s->hb[cur], W, s->w_out, W, e, st)
+                      : launch_gemm_bf16_nt<0>(n, d, W, s->hb[cur], W, s->w_out, W, e, st));
+  }
   return ASD_OK;
 }
 

@@ -67,14 +67,18 @@ asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t
 // finished chains or beyond the window are clamped to a valid trajectory row;
 // their results are never read.
 // ----------------------------------------------------------------------------
-__global__ void plan_draft_kernel(int B, int K, int d, const int32_t* __restrict__ a,
+__global__ void plan_draft_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
                                   const int32_t* __restrict__ tau, int64_t* __restrict__ in_off,
                                   int64_t* __restrict__ out_off, int32_t* __restrict__ row_tau,
-                                  int32_t* __restrict__ zero_me) {
+                                  int32_t* __restrict__ zero_me, int64_t* __restrict__ row_counts) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c == 0 && zero_me) *zero_me = 0;  // live-chain counter of the round that starts here
   if (c >= B) return;
   const int ac = min(max(a[c], 0), K);
+  if (row_counts && ac < K) {  // live rows asked of the two model calls (profiling only)
+    atomicAdd((unsigned long long*)&row_counts[0], 1ull);
+    atomicAdd((unsigned long long*)&row_counts[1], (unsigned long long)(min(L, K - ac) - 1));
+  }
   in_off[c] = ((int64_t)c * (K + 1) + ac) * d;
   out_off[c] = (int64_t)c * d;
   row_tau[c] = tau[min(ac, K - 1)];
@@ -95,8 +99,10 @@ __global__ void plan_verify_kernel(int B, int K, int L, int d, const int32_t* __
 }
 
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me) {
+  ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_draft_kernel, dim3((unsigned)ceil_div(ctx->B, 256)), dim3(256), 0, st, ctx->B, ctx->K,
-                     ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau, zero_me);
+                     ctx->L, ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau, zero_me,
+                     ctx->prof.on ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -104,6 +110,7 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   const int64_t n = (int64_t)ctx->B * (ctx->L - 1);
   if (n <= 0) return ASD_OK;
+  ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
   hipLaunchKernelGGL(plan_verify_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, ctx->B, ctx->K,
                      ctx->L, ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau);
   ASD_HIP(hipGetLastError());
@@ -151,6 +158,7 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   const int nblk = (ctx->d + 3) / 4;
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
+  ProfScope ps(ctx, ASD_PROF_DRAFT, 0, st);
   hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a, ctx->c_x,
                      ctx->c_0, ctx->sigma, ctx->x0a, traj);
   ASD_HIP(hipGetLastError());
@@ -344,6 +352,7 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key ke
 
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
+  ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
   hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a,
                      ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live);
   ASD_HIP(hipGetLastError());

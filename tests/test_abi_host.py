@@ -1,0 +1,109 @@
+"""Host-only checks of the C boundary: the library loads, exports every symbol
+the header declares, validates arguments before touching a device, and its
+schedule builder agrees with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import schedule
+from paper_2505_03983_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "asd.h")).read()
+    return sorted(set(re.findall(r"ASD_API[^;(]*?\b(asd_\w+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 15 and "asd_init" in names and "asd_sample" in names
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    # and the binding binds them all
+    L = binding.lib()
+    for n in names:
+        assert getattr(L, n).argtypes is not None, n
+
+
+def test_status_strings():
+    assert binding.status_string(0) == "ASD_OK"
+    assert binding.status_string(-5) == "ASD_EUNSUPPORTED"
+
+
+def test_schedule_matches_oracle_tables():
+    for K in (1, 2, 100, 1000):
+        s = binding.asd_schedule_ddpm_linear(K)
+        T = schedule.ddpm_tables(K)
+        for k in ("c_x", "c_0", "sigma", "abar"):
+            np.testing.assert_allclose(s[k], T[k], rtol=2e-7, atol=1e-30)
+        assert np.array_equal(s["tau"], T["tau"])
+        assert s["sigma"][K - 1] == 0.0
+    with pytest.raises(binding.AsdError):
+        binding.asd_schedule_ddpm_linear(0)
+    with pytest.raises(binding.AsdError):
+        binding.asd_schedule_ddpm_linear(10, 0.5, 0.1)
+
+
+def _cfg(**over):
+    s = binding.asd_schedule_ddpm_linear(10)
+    den = dict(kind="gmm", d=4, C=3, var=0.25, means=16, log_w=16, abar=s["abar"], n_tau=11)
+    kw = dict(L=4, chains=2)
+    for k, v in over.items():
+        if k in kw:
+            kw[k] = v
+        elif k in s:
+            s[k] = v
+        else:
+            den[k] = v
+    return s, den, kw
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(L=0), binding.ASD_EINVAL),
+    (dict(L=65), binding.ASD_EUNSUPPORTED),
+    (dict(chains=0), binding.ASD_EINVAL),
+    (dict(d=0), binding.ASD_EINVAL),
+    (dict(C=0), binding.ASD_EINVAL),
+    (dict(means=None), binding.ASD_EINVAL),
+    (dict(var=-1.0), binding.ASD_EINVAL),
+    (dict(n_tau=5), binding.ASD_EINVAL),                         # tau values out of range
+    (dict(sigma=np.full(10, -1.0, np.float32)), binding.ASD_EINVAL),
+    (dict(c_x=np.full(10, np.nan, np.float32)), binding.ASD_EINVAL),
+    (dict(kind=7), binding.ASD_EINVAL),
+])
+def test_init_rejects_bad_configs_on_the_host(over, status):
+    s, den, kw = _cfg(**over)
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, kw["L"], kw["chains"])
+    assert ei.value.status == status
+
+
+def test_mlp_shape_rules():
+    s = binding.asd_schedule_ddpm_linear(10)
+    den = dict(kind="mlp", d=12, n_tau=11, width=16, n_blocks=1, temb_dim=8, w_in=16, w_blk=16, w_out=16, temb=16)
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EUNSUPPORTED           # d not a multiple of 8
+    den.update(d=16, linears_per_block=2)
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EUNSUPPORTED
+    den.update(linears_per_block=1, w_out=None)
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EINVAL
+
+
+def test_null_handles():
+    L = binding.lib()
+    assert L.asd_destroy(None) == binding.ASD_OK
+    assert L.asd_init(None, None) == binding.ASD_EINVAL
+    assert L.asd_sample(None, None, None, None, None) == binding.ASD_EINVAL
+    assert L.asd_last_round_count(None) == -1
+    assert "NULL" in binding.last_error()
