@@ -111,6 +111,8 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->in_off, sizeof(int64_t) * rows));
   ASD_HIP(hipMalloc(&ctx->out_off, sizeof(int64_t) * rows));
   ASD_HIP(hipMalloc(&ctx->row_tau, sizeof(int32_t) * rows));
+  ASD_HIP(hipMalloc(&ctx->n_rows_dev, sizeof(int32_t) * 2));
+  ASD_HIP(hipMemset(ctx->n_rows_dev, 0, sizeof(int32_t) * 2));
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 2));
@@ -136,6 +138,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->in_off);
   (void)hipFree(ctx->out_off);
   (void)hipFree(ctx->row_tau);
+  (void)hipFree(ctx->n_rows_dev);
   (void)hipFree(ctx->x0a);
   (void)hipFree(ctx->x0hat);
   (void)hipFree(ctx->a);
@@ -152,17 +155,18 @@ static void teardown(asd_ctx* ctx) {
 }
 
 static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
-  return RowPlan{ctx->B, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau, 0};
+  return RowPlan{ctx->B, ctx->n_rows_dev + 0, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau, 0};
 }
 
 static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
-  return RowPlan{ctx->B * (ctx->L - 1), traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
+  return RowPlan{ctx->B * (ctx->L - 1), ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
 }
 
 __global__ void plan_dense_kernel(int n, int d, int n_tau, const int32_t* __restrict__ tau,
                                   int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
-                                  int32_t* __restrict__ row_tau) {
+                                  int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) *n_rows = n;
   if (i >= n) return;
   in_off[i] = (int64_t)i * d;
   out_off[i] = (int64_t)i * d;
@@ -317,9 +321,9 @@ asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t
   if (n == 0) return ASD_OK;
   hipStream_t st = (hipStream_t)stream;
   hipLaunchKernelGGL(plan_dense_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, n, ctx->d, ctx->n_tau,
-                     tau, ctx->in_off, ctx->out_off, ctx->row_tau);
+                     tau, ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1);
   ASD_HIP(hipGetLastError());
-  return model_eval(ctx, RowPlan{n, x, out, ctx->in_off, ctx->out_off, ctx->row_tau, 1}, st);
+  return model_eval(ctx, RowPlan{n, ctx->n_rows_dev + 1, x, out, ctx->in_off, ctx->out_off, ctx->row_tau, 1}, st);
 }
 
 asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {

@@ -14,11 +14,11 @@ namespace asd {
 // ---- error plumbing ---------------------------------------------------------
 void set_error(const char* fmt, ...);
 
-#define ASD_HIP(call)                                                              \
+#define ASD_HIP(...)                                                               \
   do {                                                                             \
-    hipError_t e__ = (call);                                                       \
+    hipError_t e__ = (__VA_ARGS__);                                                       \
     if (e__ != hipSuccess) {                                                       \
-      ::asd::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+      ::asd::set_error("%s failed: %s (%s:%d)", #__VA_ARGS__, hipGetErrorString(e__), __FILE__, __LINE__); \
       return ASD_EDEVICE;                                                          \
     }                                                                              \
   } while (0)
@@ -36,7 +36,8 @@ void set_error(const char* fmt, ...);
 // verify call: the drafted samples of slots 1..L-1 of every chain, read in
 // place from the trajectory and written into x0hat.
 struct RowPlan {
-  int n;                  // number of rows
+  int n;                  // upper bound on the number of rows (grid sizing)
+  const int32_t* n_dev;   // DEV: actual number of rows (the plan is compacted on the device)
   const float* in_base;   // DEV
   float* out_base;        // DEV
   const int64_t* in_off;  // DEV [n], in floats
@@ -96,6 +97,7 @@ struct asd_ctx {
   int64_t* in_off = nullptr;
   int64_t* out_off = nullptr;
   int32_t* row_tau = nullptr;
+  int32_t* n_rows_dev = nullptr;  // DEV [2]: rows of the current draft-call / verify-call plan
   // x0a: model value at y_a of every chain [B, d]
   float* x0a = nullptr;
   // owned by asd_sample

@@ -32,7 +32,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 // Requirements (checked by the host): K % 8 == 0, rows 16 B aligned.
 // CALL only gives the draft-call and verify-call launches distinct symbols in profiles.
 template <class Epi, int CALL>
-__global__ __launch_bounds__(gemm16::THREADS, 2) void gemm_bf16_nt_kernel(int M, int N, int K,
+__global__ __launch_bounds__(gemm16::THREADS, 2) void gemm_bf16_nt_kernel(const int* __restrict__ M_dev, int M_max,
+                                                                          int N, int K,
                                                                           const uint16_t* __restrict__ A,
                                                                           int64_t lda,
                                                                           const uint16_t* __restrict__ W,
@@ -47,6 +48,9 @@ __global__ __launch_bounds__(gemm16::THREADS, 2) void gemm_bf16_nt_kernel(int M,
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, half = lane >> 5;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // the row count lives on the device (compacted row plan); the grid covers M_max
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  if (m0 >= M) return;
 
   const int lrow = tid >> 2, lkq = tid & 3;
   const uint16_t* ap[2];
@@ -126,11 +130,12 @@ __global__ __launch_bounds__(gemm16::THREADS, 2) void gemm_bf16_nt_kernel(int M,
 }
 
 template <int CALL, class Epi>
-inline hipError_t launch_gemm_bf16_nt(int M, int N, int K, const uint16_t* A, int64_t lda, const uint16_t* W,
+inline hipError_t launch_gemm_bf16_nt(const int* M_dev, int M, int N, int K, const uint16_t* A, int64_t lda, const uint16_t* W,
                                       int64_t ldw, Epi epi, hipStream_t st) {
   using namespace gemm16;
   dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-  hipLaunchKernelGGL((gemm_bf16_nt_kernel<Epi, CALL>), grid, dim3(THREADS), 0, st, M, N, K, A, lda, W, ldw, epi);
+  hipLaunchKernelGGL((gemm_bf16_nt_kernel<Epi, CALL>), grid, dim3(THREADS), 0, st, M_dev, M, N, K, A, lda,
+                     W, ldw, epi);
   return hipGetLastError();
 }
 

@@ -1,10 +1,13 @@
-// fp32 "NT" GEMM on the gfx950 matrix cores:  acc[m][n] = sum_k A[m][k] * B[n][k]
-// with both operands K-contiguous, handed to an epilogue functor.
+// fp32 "NT" GEMM on the gfx950 matrix cores:  acc[m][n] = sum_k f(A[m][k]) * B[n][k]
+// with both operands K-contiguous.  What happens to the A operand on its way
+// into LDS (f) and to the accumulators at the end is supplied by an `Op`.
 //
-// Tiling: a workgroup of 4 wavefronts owns a 128 x 128 tile; each wavefront a
-// 64 x 64 quadrant as 2 x 2 blocks of v_mfma_f32_32x32x2_f32 (64 accumulator
-// VGPRs).  K is consumed in slabs of 16, staged through LDS with register
-// prefetch of the next slab (double-buffered LDS, one barrier per slab).
+// Tiling (Cfg): a workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile; each
+// wavefront a (BM/2) x (BN/2) quadrant as MI x NJ blocks of
+// v_mfma_f32_32x32x2_f32.  K is consumed in slabs of BK, staged through LDS
+// with register prefetch of the next slab (double-buffered LDS, one barrier
+// per slab); inside a slab the LDS fragments of the next group of 8 k values
+// are fetched while the MFMAs of the current group issue.
 //
 // Operand layout of the 32x32x2 instruction: lane l supplies A[row l%32][k l/32]
 // and B[col l%32][k l/32]; it receives 16 results, register r holding
@@ -12,6 +15,13 @@
 // free as long as A and B agree, so each lane reads four consecutive k of its
 // row with one 128-bit LDS load and the four values go to four MFMAs: in MFMA
 // t of a group, half-wave h feeds k = 8*group + 4*h + t.
+//
+// LDS rows are BK + 4 floats apart: 16 B aligned for the 128-bit reads, and
+// eight consecutive rows then start in eight different groups of four banks.
+//
+// The number of rows M is read from device memory (the row plan of a model
+// call is compacted on the device, so the host does not know it): the grid is
+// sized for M_max and workgroups past M exit at once.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,66 +40,93 @@ struct RowSrc {
   }
 };
 
-namespace gemm32 {
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LDSS = BK + 4;  // row stride in floats (80 B): keeps 128-bit reads 16 B aligned
-constexpr int THREADS = 256;
-}  // namespace gemm32
+template <int BM_, int BN_, int BK_>
+struct GemmCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  static constexpr int THREADS = 256;
+  static constexpr int LDSS = BK + 4;          // LDS row stride in floats
+  static constexpr int KQ = BK / 4;            // loader threads per row (one float4 each)
+  static constexpr int RPP = THREADS / KQ;     // rows covered by one loader pass
+  static constexpr int RA = BM / RPP;          // loader passes over the A tile
+  static constexpr int RB = BN / RPP;          // loader passes over the B tile
+  static constexpr int MI = BM / 64, NJ = BN / 64;  // 32x32 blocks per wavefront
+  static constexpr int KS = BK / 8;            // groups of 8 k per slab
+  static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (BM + BN) * LDSS + BM);
+  static_assert(BM % 64 == 0 && BN % 64 == 0 && BK % 8 == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
+};
 
+// Position of a lane's accumulators inside the workgroup tile.
+template <class Cfg>
+struct Frag {
+  int wm, wn, l32, half;
+  __device__ __forceinline__ int row(int i, int r) const {
+    return wm * (Cfg::BM / 2) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+  }
+  __device__ __forceinline__ int col(int j) const { return wn * (Cfg::BN / 2) + j * 32 + l32; }
+};
+
+// Op interface (all __device__, templated on Cfg where the tile shape matters):
+//   void   init<Cfg>(int m0, int M, int lrow, int lkq)   once, before the K loop; loader rows lrow + p*RPP
+//   float4 load_a(float4 v, int p)                        transform of loader pass p's 4 values (not called on padding)
+//   void   finish<Cfg>(int lrow, int lkq, float* s_row)   after the K loop, before a barrier; s_row = BM floats of LDS
+//   void   epilogue<Cfg>(acc, frag, m0, n0, M, N, s_row)  writes the results
+// KTAIL: K is not a multiple of BK (the last slab is zero-padded).
 // Requirements (checked by the host launcher): K % 4 == 0, rows 16 B aligned.
-// M, N arbitrary (edge tiles clamp their loads and mask their stores).
 // CALL only gives the draft-call and verify-call launches distinct symbols in profiles.
-template <class Epi, int CALL>
-__global__ __launch_bounds__(gemm32::THREADS, 2) void gemm_f32_nt_kernel(int M, int N, int K, RowSrc A,
-                                                                         const float* __restrict__ Bm,
-                                                                         int64_t ldb, Epi epi) {
-  using namespace gemm32;
-  __shared__ __attribute__((aligned(16))) float As[2][BM * LDSS];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDSS];
+template <class Cfg, class Op, bool KTAIL, int CALL>
+__global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict__ M_dev, int M_max, int N, int K,
+                                                          RowSrc A, const float* __restrict__ Bm, int64_t ldb,
+                                                          Op op) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LDSS = Cfg::LDSS;
+  constexpr int KQ = Cfg::KQ, RPP = Cfg::RPP, RA = Cfg::RA, RB = Cfg::RB, MI = Cfg::MI, NJ = Cfg::NJ, KS = Cfg::KS;
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  float* As = lds;                       // [2][BM * LDSS]
+  float* Bs = lds + 2 * BM * LDSS;       // [2][BN * LDSS]
+  float* s_row = Bs + 2 * BN * LDSS;     // [BM]
+
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  if (m0 >= M) return;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const Frag<Cfg> fr{wave >> 1, wave & 1, lane & 31, lane >> 5};
 
-  // loader: thread handles rows (tid/4) and (tid/4 + 64), k-quad tid%4
-  const int lrow = tid >> 2, lkq = tid & 3;
-  const float* ap[2];
-  const float* bp[2];
+  const int lrow = tid / KQ, lkq = tid % KQ;
+  const float* ap[RA];
+  const float* bp[RB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int ra = min(m0 + lrow + 64 * i, M - 1);
-    const int rb = min(n0 + lrow + 64 * i, N - 1);
-    ap[i] = A.row(ra) + lkq * 4;
-    bp[i] = Bm + (int64_t)rb * ldb + lkq * 4;
-  }
+  for (int p = 0; p < RA; ++p) ap[p] = A.row(min(m0 + lrow + RPP * p, M - 1)) + lkq * 4;
+#pragma unroll
+  for (int p = 0; p < RB; ++p) bp[p] = Bm + (int64_t)min(n0 + lrow + RPP * p, N - 1) * ldb + lkq * 4;
+  op.template init<Cfg>(m0, M, lrow, lkq);
   const int nk = (K + BK - 1) / BK;
 
-  float4 ra[2], rb[2];
+  float4 ra[RA], rb[RB];
   auto gload = [&](int kt) {
-    const int k = kt * BK + lkq * 4;
-    const bool ok = k < K;
+    const bool ok = !KTAIL || (kt * BK + lkq * 4 < K);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      ra[i] = ok ? *reinterpret_cast<const float4*>(ap[i] + kt * BK) : make_float4(0.f, 0.f, 0.f, 0.f);
-      rb[i] = ok ? *reinterpret_cast<const float4*>(bp[i] + kt * BK) : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int p = 0; p < RA; ++p)
+      ra[p] = ok ? op.load_a(*reinterpret_cast<const float4*>(ap[p] + kt * BK), p) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int p = 0; p < RB; ++p)
+      rb[p] = ok ? *reinterpret_cast<const float4*>(bp[p] + kt * BK) : make_float4(0.f, 0.f, 0.f, 0.f);
   };
   auto sstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      *reinterpret_cast<float4*>(&As[buf][(lrow + 64 * i) * LDSS + lkq * 4]) = ra[i];
-      *reinterpret_cast<float4*>(&Bs[buf][(lrow + 64 * i) * LDSS + lkq * 4]) = rb[i];
-    }
+    for (int p = 0; p < RA; ++p)
+      *reinterpret_cast<float4*>(&As[buf * BM * LDSS + (lrow + RPP * p) * LDSS + lkq * 4]) = ra[p];
+#pragma unroll
+    for (int p = 0; p < RB; ++p)
+      *reinterpret_cast<float4*>(&Bs[buf * BN * LDSS + (lrow + RPP * p) * LDSS + lkq * 4]) = rb[p];
   };
 
-  v16f acc[2][2];
+  v16f acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -97,57 +134,75 @@ __global__ __launch_bounds__(gemm32::THREADS, 2) void gemm_f32_nt_kernel(int M, 
   sstore(0);
   __syncthreads();
 
+  const int a_lane = (fr.wm * (BM / 2) + fr.l32) * LDSS + fr.half * 4;
+  const int b_lane = (fr.wn * (BN / 2) + fr.l32) * LDSS + fr.half * 4;
+
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) gload(kt + 1);
+    const float* Ac = As + cur * BM * LDSS + a_lane;
+    const float* Bc = Bs + cur * BN * LDSS + b_lane;
+    float4 af[2][MI], bf[2][NJ];
 #pragma unroll
-    for (int ks = 0; ks < BK / 8; ++ks) {
-      float4 af[2], bf[2];
+    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const float4*>(&As[cur][(wm * 64 + i * 32 + l32) * LDSS + ks * 8 + half * 4]);
-        bf[i] = *reinterpret_cast<const float4*>(&Bs[cur][(wn * 64 + i * 32 + l32) * LDSS + ks * 8 + half * 4]);
+    for (int j = 0; j < NJ; ++j) bf[0][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[c ^ 1][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS + (ks + 1) * 8);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) bf[c ^ 1][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS + (ks + 1) * 8);
       }
-      const float a0[4] = {af[0].x, af[0].y, af[0].z, af[0].w};
-      const float a1[4] = {af[1].x, af[1].y, af[1].z, af[1].w};
-      const float b0[4] = {bf[0].x, bf[0].y, bf[0].z, bf[0].w};
-      const float b1[4] = {bf[1].x, bf[1].y, bf[1].z, bf[1].w};
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const float av = t == 0 ? af[c][i].x : t == 1 ? af[c][i].y : t == 2 ? af[c][i].z : af[c][i].w;
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            const float bv = t == 0 ? bf[c][j].x : t == 1 ? bf[c][j].y : t == 2 ? bf[c][j].z : bf[c][j].w;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+          }
+        }
       }
     }
     if (kt + 1 < nk) sstore(cur ^ 1);
     __syncthreads();
   }
 
-  // epilogue: register r of block (i, j) is C[row][col] with
-  //   row = m0 + wm*64 + i*32 + 8*(r/4) + 4*half + r%4,  col = n0 + wn*64 + j*32 + l32
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m < M) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int n = n0 + wn * 64 + j * 32 + l32;
-          if (n < N) epi(m, n, acc[i][j][r]);
-        }
-      }
-    }
-  }
+  op.template finish<Cfg>(lrow, lkq, s_row);
+  __syncthreads();
+  op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
-template <int CALL, class Epi>
-inline hipError_t launch_gemm_f32_nt(int M, int N, int K, RowSrc A, const float* Bm, int64_t ldb, Epi epi,
-                                     hipStream_t st) {
-  using namespace gemm32;
-  dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-  hipLaunchKernelGGL((gemm_f32_nt_kernel<Epi, CALL>), grid, dim3(THREADS), 0, st, M, N, K, A, Bm, ldb, epi);
+template <class Cfg, int CALL, class Op>
+inline hipError_t launch_gemm_f32_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const float* Bm,
+                                     int64_t ldb, Op op, hipStream_t st) {
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM));
+  if (K % Cfg::BK == 0) {
+    auto kern = gemm_f32_nt_kernel<Cfg, Op, false, CALL>;
+    static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per kernel
+    if (!attr_set && Cfg::LDS_BYTES > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)Cfg::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op);
+  } else {
+    auto kern = gemm_f32_nt_kernel<Cfg, Op, true, CALL>;
+    static bool attr_set = false;
+    if (!attr_set && Cfg::LDS_BYTES > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)Cfg::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op);
+  }
   return hipGetLastError();
 }
 

@@ -23,6 +23,18 @@
 
 namespace asd {
 
+#ifndef ASD_G32_BM
+#define ASD_G32_BM 128
+#endif
+#ifndef ASD_G32_BN
+#define ASD_G32_BN 128
+#endif
+#ifndef ASD_G32_BK
+#define ASD_G32_BK 16
+#endif
+typedef GemmCfg<ASD_G32_BM, ASD_G32_BN, ASD_G32_BK> GmmTile;  // verify call: tens of thousands of rows
+typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one row per chain, fill the chip
+
 struct GmmState {
   int C = 0;
   float var = 0.f;
@@ -32,6 +44,8 @@ struct GmmState {
   float* musq = nullptr;         // [C]
   float4* coef_tau = nullptr;    // [n_tau]: (kappa, gamma, cx, cm)
   float* logits = nullptr;       // [rows_max, C] (matrix-core path only)
+  float* pmax = nullptr;         // [rows_max, np] partial row maxima of the logits
+  int np = 0;
   bool use_mfma = false;
   size_t rowwise_lds = 0;
 };
@@ -67,7 +81,7 @@ __global__ void gmm_prep_kernel(int C, int d, const float* __restrict__ means, f
 // row-wise path: 4 wavefronts per workgroup, one row per wavefront per pass
 // LDS per wavefront: x[d] then p[C]
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gmm_rowwise_kernel(int nrows, int d, int C, const float* __restrict__ in_base,
+__global__ __launch_bounds__(256) void gmm_rowwise_kernel(const int* __restrict__ n_dev, int nrows_max, int d, int C, const float* __restrict__ in_base,
                                                           const int64_t* __restrict__ in_off,
                                                           float* __restrict__ out_base,
                                                           const int64_t* __restrict__ out_off,
@@ -81,6 +95,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_kernel(int nrows, int d, int 
   const int wave = threadIdx.x >> 6;
   float* xs = lds + (size_t)wave * (d + C);
   float* ps = xs + d;
+  const int nrows = min(*n_dev, nrows_max);
   for (int base = blockIdx.x * 4; base < nrows; base += gridDim.x * 4) {
     const int n = base + wave;
     const bool active = n < nrows;
@@ -132,56 +147,132 @@ __global__ __launch_bounds__(256) void gmm_rowwise_kernel(int nrows, int d, int 
 // ---------------------------------------------------------------------------
 // matrix-core path
 // ---------------------------------------------------------------------------
-struct LogitEpi {
+// GEMM 1: logits.  The epilogue applies the affine map, stores the logits and
+// the maximum of each row over the 64 columns the wavefront owns
+// (pmax[row][2*column_tile + wn]); the softmax normalisation is finished
+// inside GEMM 2, so the logits are written once and read once.
+struct LogitOp {
   float* logits;
   int64_t ld;
+  float* pmax;
+  int np;  // partial maxima per row = 2 * number of column tiles
   const float4* coef_tau;
   const int32_t* tau;
   const float* musq;
   const float* log_w;
-  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
-    const float4 cf = coef_tau[tau[m]];
-    logits[(int64_t)m * ld + n] = fmaf(cf.x, acc, fmaf(-cf.y, musq[n], log_w[n]));
+  template <class Cfg>
+  __device__ __forceinline__ void init(int, int, int, int) {}
+  __device__ __forceinline__ float4 load_a(float4 v, int) const { return v; }
+  template <class Cfg>
+  __device__ __forceinline__ void finish(int, int, float*) {}
+  template <class Cfg>
+  __device__ __forceinline__ void epilogue(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0, int n0,
+                                           int M, int N, const float*) const {
+    constexpr int MI = Cfg::MI, NJ = Cfg::NJ;
+    constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
+    float bias[NJ], q[NJ];
+    bool nok[NJ];
+    int n[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int nn = n0 + fr.col(j);
+      nok[j] = nn < N;
+      n[j] = nok[j] ? nn : N - 1;
+      bias[j] = log_w[n[j]];
+      q[j] = musq[n[j]];
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + fr.row(i, r);
+        const bool mok = m < M;
+        const float4 cf = coef_tau[tau[mok ? m : M - 1]];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const float v = kLog2e * fmaf(cf.x, acc[i][j][r], fmaf(-cf.y, q[j], bias[j]));
+          if (nok[j]) {
+            mx = fmaxf(mx, v);
+            if (mok) logits[(int64_t)m * ld + n[j]] = v;
+          }
+        }
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // stays inside the half-wave
+        if (mok && fr.l32 == 0) pmax[(int64_t)m * np + 2 * blockIdx.x + fr.wn] = mx;
+      }
+    }
   }
 };
 
-// in-place row softmax of [rows, C]; one workgroup per row
-__global__ __launch_bounds__(256) void softmax_rows_kernel(int C, float* __restrict__ logits) {
-  __shared__ float red[4];
-  float* row = logits + (int64_t)blockIdx.x * C;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  float mx = -INFINITY;
-  for (int k = tid; k < C; k += 256) mx = fmaxf(mx, row[k]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-  if (lane == 0) red[wave] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  __syncthreads();
-  float sum = 0.f;
-  for (int k = tid; k < C; k += 256) {
-    const float p = expf(row[k] - mx);
-    row[k] = p;
-    sum += p;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-  if (lane == 0) red[wave] = sum;
-  __syncthreads();
-  const float inv = 1.0f / (red[0] + red[1] + red[2] + red[3]);
-  for (int k = tid; k < C; k += 256) row[k] *= inv;
-}
-
-struct CombineEpi {
+// GEMM 2: out = c_x' x + c_m' (softmax(logits) M).  The A operand is turned
+// into exp(logit - rowmax) on its way into LDS; the row sums are accumulated on
+// the side and divided out in the epilogue.
+struct CombineOp {
+  const float* pmax;
+  int np;
   const float* in_base;
   const int64_t* in_off;
   float* out_base;
   const int64_t* out_off;
   const float4* coef_tau;
   const int32_t* tau;
-  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
-    const float4 cf = coef_tau[tau[m]];
-    out_base[out_off[m] + n] = fmaf(cf.z, in_base[in_off[m] + n], cf.w * acc);
+  static constexpr int kMaxPasses = 8;
+  float rmax[kMaxPasses];
+  float rsum[kMaxPasses];
+  template <class Cfg>
+  __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq) {
+    static_assert(Cfg::RA <= kMaxPasses, "loader passes");
+#pragma unroll
+    for (int p = 0; p < Cfg::RA; ++p) {
+      const int m = min(m0 + lrow + Cfg::RPP * p, M - 1);
+      float mx = -INFINITY;
+      for (int q = lkq; q < np; q += Cfg::KQ) mx = fmaxf(mx, pmax[(int64_t)m * np + q]);
+#pragma unroll
+      for (int o = 1; o < Cfg::KQ; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // the KQ lanes of a row are adjacent
+      rmax[p] = mx;
+      rsum[p] = 0.f;
+    }
+  }
+  // logits are in base-2 units: p = 2^(l - rowmax) <= 1
+  __device__ __forceinline__ float4 load_a(float4 v, int p) {
+    const float mx = rmax[p];
+    float4 e = make_float4(__builtin_amdgcn_exp2f(v.x - mx), __builtin_amdgcn_exp2f(v.y - mx),
+                           __builtin_amdgcn_exp2f(v.z - mx), __builtin_amdgcn_exp2f(v.w - mx));
+    rsum[p] += (e.x + e.y) + (e.z + e.w);
+    return e;
+  }
+  template <class Cfg>
+  __device__ __forceinline__ void finish(int lrow, int lkq, float* s_row) {
+#pragma unroll
+    for (int p = 0; p < Cfg::RA; ++p) {
+      float s = rsum[p];
+#pragma unroll
+      for (int o = 1; o < Cfg::KQ; o <<= 1) s += __shfl_xor(s, o, 64);
+      if (lkq == 0) s_row[lrow + Cfg::RPP * p] = s;
+    }
+  }
+  template <class Cfg>
+  __device__ __forceinline__ void epilogue(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0, int n0,
+                                           int M, int N, const float* s_row) const {
+#pragma unroll
+    for (int i = 0; i < Cfg::MI; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int ml = fr.row(i, r);
+        const int m = m0 + ml;
+        if (m >= M) continue;
+        const float4 cf = coef_tau[tau[m]];
+        const float scale = cf.w / s_row[ml];
+        const float* x = in_base + in_off[m];
+        float* o = out_base + out_off[m];
+#pragma unroll
+        for (int j = 0; j < Cfg::NJ; ++j) {
+          const int n = n0 + fr.col(j);
+          if (n < N) o[n] = fmaf(cf.z, x[n], scale * acc[i][j][r]);
+        }
+      }
+    }
   }
 };
 
@@ -228,7 +319,11 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     set_error("GMM denoiser: C=%d, d=%d needs d %% 4 == 0 and C %% 4 == 0 at this size", C, d);
     return ASD_EUNSUPPORTED;
   }
-  if (g->use_mfma) ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
+  if (g->use_mfma) {
+    g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finer of the two tilings
+    ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
+    ASD_HIP(hipMalloc(&g->pmax, sizeof(float) * (size_t)ctx->n_rows_max * g->np));
+  }
   return ASD_OK;
 }
 
@@ -239,6 +334,7 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->musq);
   (void)hipFree(g->coef_tau);
   (void)hipFree(g->logits);
+  (void)hipFree(g->pmax);
   delete g;
   ctx->gmm = nullptr;
 }
@@ -249,30 +345,27 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   if (!g->use_mfma) {
     ProfScope ps(ctx, ASD_PROF_GMM_ROWWISE, rows.call, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(n, 4), 4096);
-    hipLaunchKernelGGL(gmm_rowwise_kernel, dim3(blocks), dim3(256), g->rowwise_lds, st, n, d, C, rows.in_base,
+    hipLaunchKernelGGL(gmm_rowwise_kernel, dim3(blocks), dim3(256), g->rowwise_lds, st, rows.n_dev, n, d, C, rows.in_base,
                        rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, g->means, g->musq,
                        g->log_w);
     ASD_HIP(hipGetLastError());
     return ASD_OK;
   }
+  // partial row maxima per row: two per column tile of the tiling in use
+  const int np = 2 * (int)ceil_div(C, rows.call ? GmmTile::BN : GmmTileSkinny::BN);
   RowSrc X{rows.in_base, rows.in_off, 0};
-  LogitEpi e1{g->logits, C, g->coef_tau, rows.tau, g->musq, g->log_w};
+  LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    ASD_HIP(rows.call ? launch_gemm_f32_nt<1>(n, C, d, X, g->means, d, e1, st)
-                      : launch_gemm_f32_nt<0>(n, C, d, X, g->means, d, e1, st));
-  }
-  {
-    ProfScope ps(ctx, ASD_PROF_GMM_SOFTMAX, rows.call, st);
-    hipLaunchKernelGGL(softmax_rows_kernel, dim3(n), dim3(256), 0, st, C, g->logits);
-    ASD_HIP(hipGetLastError());
+    ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
+                      : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
   RowSrc P{g->logits, nullptr, C};
-  CombineEpi e2{rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau};
+  CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    ASD_HIP(rows.call ? launch_gemm_f32_nt<1>(n, d, C, P, g->means_t, C, e2, st)
-                      : launch_gemm_f32_nt<0>(n, d, C, P, g->means_t, C, e2, st));
+    ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
+                      : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st));
   }
   return ASD_OK;
 }

@@ -28,13 +28,13 @@ struct MlpState {
 };
 
 // in_bf[n] = [ bf16(x_n) ; temb[tau_n] ], eight elements per thread
-__global__ void mlp_pack_kernel(int n_rows, int d, int E, const float* __restrict__ in_base,
+__global__ void mlp_pack_kernel(const int* __restrict__ n_dev, int n_rows, int d, int E, const float* __restrict__ in_base,
                                 const int64_t* __restrict__ in_off, const int32_t* __restrict__ tau,
                                 const uint16_t* __restrict__ temb, uint16_t* __restrict__ in_bf) {
   const int n = blockIdx.x;
   const int q = blockIdx.y * blockDim.x + threadIdx.x;  // group of 8 elements
   const int in_dim = d + E;
-  if (q * 8 >= in_dim) return;
+  if (q * 8 >= in_dim || n >= min(*n_dev, n_rows)) return;
   uint4 o;
   if (q * 8 < d) {
     const float* x = in_base + in_off[n] + q * 8;
@@ -134,30 +134,30 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     const int groups = s->in_dim / 8;
     const int threads = groups >= 256 ? 256 : 64;
     dim3 grid((unsigned)n, (unsigned)ceil_div(groups, threads));
-    hipLaunchKernelGGL(mlp_pack_kernel, grid, dim3(threads), 0, st, n, d, s->E, rows.in_base, rows.in_off,
+    hipLaunchKernelGGL(mlp_pack_kernel, grid, dim3(threads), 0, st, rows.n_dev, n, d, s->E, rows.in_base, rows.in_off,
                        rows.tau, s->temb, s->in_bf);
     ASD_HIP(hipGetLastError());
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_IN, rows.call, st);
     const InEpi e{s->h, s->hb[0], s->b_in, W};
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st)
-                      : launch_gemm_bf16_nt<0>(n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st));
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st)
+                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st));
   }
   int cur = 0;
   for (int l = 0; l < s->n_blocks; ++l) {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_BLK, rows.call, st);
     const BlockEpi e{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W};
     const uint16_t* wl = s->w_blk + (size_t)l * W * W;
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, W, W, s->hb[cur], W, wl, W, e, st)
-                      : launch_gemm_bf16_nt<0>(n, W, W, s->hb[cur], W, wl, W, e, st));
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, W, W, s->hb[cur], W, wl, W, e, st)
+                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, W, W, s->hb[cur], W, wl, W, e, st));
     cur ^= 1;
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_OUT, rows.call, st);
     const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip};
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(n, d, W, s->hb[cur], W, s->w_out, W, e, st)
-                      : launch_gemm_bf16_nt<0>(n, d, W, s->hb[cur], W, s->w_out, W, e, st));
+    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, d, W, s->hb[cur], W, s->w_out, W, e, st)
+                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, d, W, s->hb[cur], W, s->w_out, W, e, st));
   }
   return ASD_OK;
 }

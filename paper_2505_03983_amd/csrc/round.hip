@@ -62,57 +62,97 @@ asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t
 }
 
 // ----------------------------------------------------------------------------
-// Row plans.  Draft call: row c = y_a of chain c.  Verify call: row
-// c*(L-1)+(s-1) = proposal sample of slot s (s = 1..L-1) of chain c.  Rows of
-// finished chains or beyond the window are clamped to a valid trajectory row;
-// their results are never read.
+// Row plans.  A model call evaluates a list of rows; the list is built on the
+// device and is *compacted*: only rows inside the window of an unfinished
+// chain are listed (finished chains and the tail of a window cut by K cost
+// nothing), and their number is left in device memory for the model kernels.
+// Draft call: row = y_a of live chain c.  Verify call: rows = proposal samples
+// of slots s = 1..w-1 of live chain c (slot 0 reuses the draft call's value).
+// One workgroup scans the chains in chunks of 1024.
 // ----------------------------------------------------------------------------
-__global__ void plan_draft_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
-                                  const int32_t* __restrict__ tau, int64_t* __restrict__ in_off,
-                                  int64_t* __restrict__ out_off, int32_t* __restrict__ row_tau,
-                                  int32_t* __restrict__ zero_me, int64_t* __restrict__ row_counts) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c == 0 && zero_me) *zero_me = 0;  // live-chain counter of the round that starts here
-  if (c >= B) return;
-  const int ac = min(max(a[c], 0), K);
-  if (row_counts && ac < K) {  // live rows asked of the two model calls (profiling only)
-    atomicAdd((unsigned long long*)&row_counts[0], 1ull);
-    atomicAdd((unsigned long long*)&row_counts[1], (unsigned long long)(min(L, K - ac) - 1));
+__device__ __forceinline__ int block_exclusive_scan(int v, int* s_wave, int* s_total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
   }
-  in_off[c] = ((int64_t)c * (K + 1) + ac) * d;
-  out_off[c] = (int64_t)c * d;
-  row_tau[c] = tau[min(ac, K - 1)];
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
+  if (wave == 0) {
+    const int wv = (lane < 16) ? s_wave[lane] : 0;
+    int winc = wv;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int t = __shfl_up(winc, o, 64);
+      if (lane >= o) winc += t;
+    }
+    if (lane < 16) s_wave[lane] = winc - wv;
+    if (lane == 15) *s_total = winc;
+  }
+  __syncthreads();
+  return inc - v + s_wave[wave];
 }
 
-__global__ void plan_verify_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
-                                   const int32_t* __restrict__ tau, int64_t* __restrict__ in_off,
-                                   int64_t* __restrict__ out_off, int32_t* __restrict__ row_tau) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= B * (L - 1)) return;
-  const int c = n / (L - 1);
-  const int s = n - c * (L - 1) + 1;
-  const int ac = min(max(a[c], 0), K);
-  const int i = min(ac + s, K);
-  in_off[n] = ((int64_t)c * (K + 1) + i) * d;
-  out_off[n] = ((int64_t)c * L + s) * d;
-  row_tau[n] = tau[min(i, K - 1)];
+// MODE 0: draft call, MODE 1: verify call
+template <int MODE>
+__global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
+                                                         const int32_t* __restrict__ tau,
+                                                         int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
+                                                         int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows,
+                                                         int32_t* __restrict__ zero_me,
+                                                         int64_t* __restrict__ row_counts) {
+  __shared__ int s_wave[16];
+  __shared__ int s_total;
+  if (threadIdx.x == 0 && zero_me) *zero_me = 0;  // live-chain counter of the round that starts here
+  int base = 0;
+  for (int c0 = 0; c0 < B; c0 += 1024) {
+    const int c = c0 + threadIdx.x;
+    int ac = K, cnt = 0;
+    if (c < B) {
+      ac = min(max(a[c], 0), K);
+      if (ac < K) cnt = (MODE == 0) ? 1 : min(L, K - ac) - 1;
+    }
+    const int off = base + block_exclusive_scan(cnt, s_wave, &s_total);
+    if (MODE == 0) {
+      if (cnt) {
+        in_off[off] = ((int64_t)c * (K + 1) + ac) * d;
+        out_off[off] = (int64_t)c * d;
+        row_tau[off] = tau[ac];
+      }
+    } else {
+      for (int s = 1; s <= cnt; ++s) {
+        const int i = ac + s;
+        in_off[off + s - 1] = ((int64_t)c * (K + 1) + i) * d;
+        out_off[off + s - 1] = ((int64_t)c * L + s) * d;
+        row_tau[off + s - 1] = tau[i];
+      }
+    }
+    base += s_total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *n_rows = base;
+    if (row_counts) atomicAdd((unsigned long long*)&row_counts[MODE], (unsigned long long)base);
+  }
 }
 
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me) {
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
-  hipLaunchKernelGGL(plan_draft_kernel, dim3((unsigned)ceil_div(ctx->B, 256)), dim3(256), 0, st, ctx->B, ctx->K,
-                     ctx->L, ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau, zero_me,
+  hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
+                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, zero_me,
                      ctx->prof.on ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
 
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
-  const int64_t n = (int64_t)ctx->B * (ctx->L - 1);
-  if (n <= 0) return ASD_OK;
+  if (ctx->L <= 1) return ASD_OK;
   ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
-  hipLaunchKernelGGL(plan_verify_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, ctx->B, ctx->K,
-                     ctx->L, ctx->d, a, ctx->tau, ctx->in_off, ctx->out_off, ctx->row_tau);
+  hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
+                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
+                     ctx->prof.on ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
