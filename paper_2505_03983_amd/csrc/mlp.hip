@@ -9,11 +9,44 @@
 // GEMM epilogues, which also emit the bf16 copy of h the next product reads.
 #include "common.h"
 #include "gemm_bf16.h"
+#include "gemm_bf16_pipe.h"
 
 namespace asd {
 
+typedef GemmCfg16<64, 64, 64> MlpTileSkinny;                      // draft call: few rows, stream the weights
+
+// Verify call, K % 64 == 0: the direct-to-LDS pipeline.  A CU moves about 30 bytes per clock from
+// L2 into LDS whatever the kernel does, so the tile is as large as the problem allows: 128 x 256
+// (MFMA-bound fraction of the loop ~60%) when that still gives every CU a tile, else 128 x 128.
+typedef PipeCfg16<128, 256, 3, 2, 4> MlpPipeWide;
+typedef PipeCfg16<128, 128, 4, 2, 4> MlpPipeSquare;
+
+// Both operands have row pitch ld = padded(K) (see pitch_of).
+template <class Epi>
+static hipError_t mlp_gemm(int call, const int* n_dev, int n, int N, int K, int64_t ld, const uint16_t* A,
+                           const uint16_t* Wt, Epi e, hipStream_t st) {
+  if (call == 1) {
+    // K is rounded up to the slab size: columns K .. ld-1 of both operands are zero (pitch_of leaves
+    // room for it), so the extra products vanish.
+    const int Kp = (int)(ceil_div(K, 64) * 64);
+    const int64_t wide_tiles = ceil_div(n, 128) * ceil_div(N, 256);
+    return wide_tiles >= 192 ? launch_gemm_bf16_nt_pipe<MlpPipeWide, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st)
+                             : launch_gemm_bf16_nt_pipe<MlpPipeSquare, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st);
+  }
+  return launch_gemm_bf16_nt<MlpTileSkinny, 0>(n_dev, n, N, K, A, ld, Wt, ld, e, st);
+}
+
+// Row pitch (elements) of every bf16 matrix the GEMMs read: K plus 64 elements (128 bytes).
+// With the natural pitch (a power of two times 2 bytes for the widths used here) the rows a
+// workgroup streams in parallel all start on the same few HBM channels; the odd pitch spreads them.
+static inline int64_t pitch_of(int K) { return (int64_t)K + 64; }
+
 struct MlpState {
   int width = 0, n_blocks = 0, E = 0, in_dim = 0;
+  int64_t ld_in = 0, ld_h = 0;   // padded pitches of [*, in_dim] and [*, width] bf16 matrices
+  uint16_t* wp_in = nullptr;     // padded copies of the caller's weights
+  uint16_t* wp_blk = nullptr;
+  uint16_t* wp_out = nullptr;
   float out_clip = 0.f;
   const uint16_t* w_in = nullptr;
   const uint16_t* w_blk = nullptr;
@@ -22,7 +55,7 @@ struct MlpState {
   const float* b_blk = nullptr;
   const float* b_out = nullptr;
   const uint16_t* temb = nullptr;
-  uint16_t* in_bf = nullptr;  // [rows_max, in_dim]
+  uint16_t* in_bf = nullptr;  // [rows_max, ld_in]
   float* h = nullptr;         // [rows_max, width]
   uint16_t* hb[2] = {nullptr, nullptr};
 };
@@ -30,7 +63,7 @@ struct MlpState {
 // in_bf[n] = [ bf16(x_n) ; temb[tau_n] ], eight elements per thread
 __global__ void mlp_pack_kernel(const int* __restrict__ n_dev, int n_rows, int d, int E, const float* __restrict__ in_base,
                                 const int64_t* __restrict__ in_off, const int32_t* __restrict__ tau,
-                                const uint16_t* __restrict__ temb, uint16_t* __restrict__ in_bf) {
+                                const uint16_t* __restrict__ temb, uint16_t* __restrict__ in_bf, int64_t ld_in) {
   const int n = blockIdx.x;
   const int q = blockIdx.y * blockDim.x + threadIdx.x;  // group of 8 elements
   const int in_dim = d + E;
@@ -47,20 +80,42 @@ __global__ void mlp_pack_kernel(const int* __restrict__ n_dev, int n_rows, int d
   } else {
     o = *reinterpret_cast<const uint4*>(temb + (int64_t)tau[n] * E + (q * 8 - d));
   }
-  *reinterpret_cast<uint4*>(in_bf + (int64_t)n * in_dim + q * 8) = o;
+  *reinterpret_cast<uint4*>(in_bf + (int64_t)n * ld_in + q * 8) = o;
 }
 
-__device__ __forceinline__ float silu(float z) { return z / (1.0f + expf(-z)); }
+// SiLU with the hardware exp2 and reciprocal: relative error ~1e-6, far inside what the bf16
+// re-rounding of the activations leaves of the value.
+__device__ __forceinline__ float silu(float z) {
+  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
+
+__device__ __forceinline__ uint2 pack4_bf16(float4 v) {
+  return make_uint2((uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16),
+                    (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16));
+}
+__device__ __forceinline__ float4 load_bias4(const float* bias, int n) {
+  return bias ? *reinterpret_cast<const float4*>(bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+}
 
 struct InEpi {  // h = acc + b; hb = bf16(h)
   float* h;
   uint16_t* hb;
   const float* bias;
-  int64_t ld;
-  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
+  int64_t ld, ldb;  // pitch of h (fp32) and of hb (bf16)
+  static constexpr bool kLoads = false;
+  __device__ __forceinline__ float load(int, int) const { return 0.f; }
+  __device__ __forceinline__ void store(int m, int n, float acc, float) const {
     const float v = acc + (bias ? bias[n] : 0.f);
     h[(int64_t)m * ld + n] = v;
-    hb[(int64_t)m * ld + n] = f32_to_bf16_rne(v);
+    hb[(int64_t)m * ldb + n] = f32_to_bf16_rne(v);
+  }
+  // four consecutive columns n..n+3 (n % 4 == 0) of row m
+  __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
+    const float4 b = load_bias4(bias, n);
+    const float4 v = make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+    *reinterpret_cast<float4*>(h + (int64_t)m * ld + n) = v;
+    *reinterpret_cast<uint2*>(hb + (int64_t)m * ldb + n) = pack4_bf16(v);
   }
 };
 
@@ -68,12 +123,24 @@ struct BlockEpi {  // h += SiLU(acc + b); hb_next = bf16(h)
   float* h;
   uint16_t* hb_next;
   const float* bias;
-  int64_t ld;
-  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
-    const int64_t o = (int64_t)m * ld + n;
-    const float v = h[o] + silu(acc + (bias ? bias[n] : 0.f));
-    h[o] = v;
-    hb_next[o] = f32_to_bf16_rne(v);
+  int64_t ld, ldb;
+  static constexpr bool kLoads = true;
+  __device__ __forceinline__ float load(int m, int n) const { return h[(int64_t)m * ld + n]; }
+  __device__ __forceinline__ void store(int m, int n, float acc, float prev) const {
+    const float v = prev + silu(acc + (bias ? bias[n] : 0.f));
+    h[(int64_t)m * ld + n] = v;
+    hb_next[(int64_t)m * ldb + n] = f32_to_bf16_rne(v);
+  }
+  __device__ __forceinline__ float4 load4(int m, int n) const {
+    return *reinterpret_cast<const float4*>(h + (int64_t)m * ld + n);
+  }
+  __device__ __forceinline__ void store4(int m, int n, float4 a, float4 p) const {
+    const float4 b = load_bias4(bias, n);
+    float* hp = h + (int64_t)m * ld + n;
+    const float4 v = make_float4(p.x + silu(a.x + b.x), p.y + silu(a.y + b.y), p.z + silu(a.z + b.z),
+                                 p.w + silu(a.w + b.w));
+    *reinterpret_cast<float4*>(hp) = v;
+    *reinterpret_cast<uint2*>(hb_next + (int64_t)m * ldb + n) = pack4_bf16(v);
   }
 };
 
@@ -82,10 +149,24 @@ struct OutEpi {  // out[out_off[m] + n] = acc + b
   const int64_t* out_off;
   const float* bias;
   float clip;  // 0: none
-  __device__ __forceinline__ void operator()(int m, int n, float acc) const {
+  static constexpr bool kLoads = false;
+  __device__ __forceinline__ float load(int, int) const { return 0.f; }
+  __device__ __forceinline__ void store(int m, int n, float acc, float) const {
     float v = acc + (bias ? bias[n] : 0.f);
     if (clip > 0.f) v = fminf(fmaxf(v, -clip), clip);
     out_base[out_off[m] + n] = v;
+  }
+  __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
+    const float4 b = load_bias4(bias, n);
+    float4 v = make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+    if (clip > 0.f) {
+      v.x = fminf(fmaxf(v.x, -clip), clip);
+      v.y = fminf(fmaxf(v.y, -clip), clip);
+      v.z = fminf(fmaxf(v.z, -clip), clip);
+      v.w = fminf(fmaxf(v.w, -clip), clip);
+    }
+    *reinterpret_cast<float4*>(out_base + out_off[m] + n) = v;
   }
 };
 
@@ -108,10 +189,30 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den) {
   const size_t rows = (size_t)ctx->n_rows_max;
   ctx->model_macs_per_row = (double)s->in_dim * s->width + (double)s->n_blocks * s->width * s->width +
                             (double)s->width * ctx->d;
-  ASD_HIP(hipMalloc(&s->in_bf, sizeof(uint16_t) * rows * s->in_dim));
+  s->ld_in = pitch_of(s->in_dim);
+  s->ld_h = pitch_of(s->width);
+  const size_t Wd = (size_t)s->width, nb = (size_t)s->n_blocks, dd = (size_t)ctx->d;
+  ASD_HIP(hipMalloc(&s->in_bf, sizeof(uint16_t) * rows * s->ld_in));
   ASD_HIP(hipMalloc(&s->h, sizeof(float) * rows * s->width));
-  ASD_HIP(hipMalloc(&s->hb[0], sizeof(uint16_t) * rows * s->width));
-  ASD_HIP(hipMalloc(&s->hb[1], sizeof(uint16_t) * rows * s->width));
+  ASD_HIP(hipMalloc(&s->hb[0], sizeof(uint16_t) * rows * s->ld_h));
+  ASD_HIP(hipMalloc(&s->hb[1], sizeof(uint16_t) * rows * s->ld_h));
+  ASD_HIP(hipMemset(s->in_bf, 0, sizeof(uint16_t) * rows * s->ld_in));
+  ASD_HIP(hipMemset(s->hb[0], 0, sizeof(uint16_t) * rows * s->ld_h));
+  ASD_HIP(hipMemset(s->hb[1], 0, sizeof(uint16_t) * rows * s->ld_h));
+  // padded copies of the weights (one-time; the caller's arrays are not read again)
+  ASD_HIP(hipMalloc(&s->wp_in, sizeof(uint16_t) * Wd * s->ld_in));
+  ASD_HIP(hipMalloc(&s->wp_out, sizeof(uint16_t) * dd * s->ld_h));
+  ASD_HIP(hipMemset(s->wp_in, 0, sizeof(uint16_t) * Wd * s->ld_in));
+  ASD_HIP(hipMemset(s->wp_out, 0, sizeof(uint16_t) * dd * s->ld_h));
+  ASD_HIP(hipMemcpy2D(s->wp_in, 2 * s->ld_in, s->w_in, 2 * (size_t)s->in_dim, 2 * (size_t)s->in_dim, Wd,
+                      hipMemcpyDeviceToDevice));
+  ASD_HIP(hipMemcpy2D(s->wp_out, 2 * s->ld_h, s->w_out, 2 * Wd, 2 * Wd, dd, hipMemcpyDeviceToDevice));
+  if (nb) {
+    ASD_HIP(hipMalloc(&s->wp_blk, sizeof(uint16_t) * nb * Wd * s->ld_h));
+    ASD_HIP(hipMemset(s->wp_blk, 0, sizeof(uint16_t) * nb * Wd * s->ld_h));
+    ASD_HIP(hipMemcpy2D(s->wp_blk, 2 * s->ld_h, s->w_blk, 2 * Wd, 2 * Wd, nb * Wd, hipMemcpyDeviceToDevice));
+  }
+  ASD_HIP(hipDeviceSynchronize());
   return ASD_OK;
 }
 
@@ -122,6 +223,9 @@ void mlp_destroy(asd_ctx* ctx) {
   (void)hipFree(s->h);
   (void)hipFree(s->hb[0]);
   (void)hipFree(s->hb[1]);
+  (void)hipFree(s->wp_in);
+  (void)hipFree(s->wp_blk);
+  (void)hipFree(s->wp_out);
   delete s;
   ctx->mlp = nullptr;
 }
@@ -135,29 +239,25 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     const int threads = groups >= 256 ? 256 : 64;
     dim3 grid((unsigned)n, (unsigned)ceil_div(groups, threads));
     hipLaunchKernelGGL(mlp_pack_kernel, grid, dim3(threads), 0, st, rows.n_dev, n, d, s->E, rows.in_base, rows.in_off,
-                       rows.tau, s->temb, s->in_bf);
+                       rows.tau, s->temb, s->in_bf, s->ld_in);
     ASD_HIP(hipGetLastError());
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_IN, rows.call, st);
-    const InEpi e{s->h, s->hb[0], s->b_in, W};
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st)
-                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, W, s->in_dim, s->in_bf, s->in_dim, s->w_in, s->in_dim, e, st));
+    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, W, s->in_dim, s->ld_in, s->in_bf, s->wp_in,
+                     InEpi{s->h, s->hb[0], s->b_in, W, s->ld_h}, st));
   }
   int cur = 0;
   for (int l = 0; l < s->n_blocks; ++l) {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_BLK, rows.call, st);
-    const BlockEpi e{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W};
-    const uint16_t* wl = s->w_blk + (size_t)l * W * W;
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, W, W, s->hb[cur], W, wl, W, e, st)
-                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, W, W, s->hb[cur], W, wl, W, e, st));
+    const BlockEpi e{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W, s->ld_h};
+    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, W, W, s->ld_h, s->hb[cur], s->wp_blk + (size_t)l * W * s->ld_h, e, st));
     cur ^= 1;
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_OUT, rows.call, st);
     const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip};
-    ASD_HIP(rows.call ? launch_gemm_bf16_nt<1>(rows.n_dev, n, d, W, s->hb[cur], W, s->w_out, W, e, st)
-                      : launch_gemm_bf16_nt<0>(rows.n_dev, n, d, W, s->hb[cur], W, s->w_out, W, e, st));
+    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, d, W, s->ld_h, s->hb[cur], s->wp_out, e, st));
   }
   return ASD_OK;
 }
