@@ -48,9 +48,9 @@ struct PipeCfg16 {
   static constexpr int LPS = A_LOADS + W_LOADS;
   static constexpr int STAGE_BYTES = (BM + BN) * 128;
   static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
-  static_assert(WM % 32 == 0 && WN % 32 == 0 && STAGES >= 2 && STAGES <= 4, "tile shape");
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && STAGES >= 3 && STAGES <= 8, "tile shape");
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "wave-loads must divide evenly among the wavefronts");
-  static_assert(LPS <= 63, "vmcnt range");
+  static_assert(LPS * (STAGES - 1) <= 63, "vmcnt range");
   // loads of the next slab issued inside MFMA group g (0..3), and those of group 3 issued after the hand-over
   static constexpr int loads_in_group(int g) { return LPS / 4 + (g < LPS % 4 ? 1 : 0); }
   static constexpr int loads_before_group(int g) { return g == 0 ? 0 : loads_before_group(g - 1) + loads_in_group(g - 1); }
@@ -60,6 +60,20 @@ struct PipeCfg16 {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Wait until at most `slabs` * LPS + EXTRA of this wavefront's loads are outstanding (slabs in 0..6).
+template <int LPS, int EXTRA>
+__device__ __forceinline__ void wait_vmcnt_slabs(int slabs) {
+  switch (slabs) {
+    case 0: wait_vmcnt<EXTRA>(); break;
+    case 1: wait_vmcnt<(1 * LPS + EXTRA <= 63 ? 1 * LPS + EXTRA : 63)>(); break;
+    case 2: wait_vmcnt<(2 * LPS + EXTRA <= 63 ? 2 * LPS + EXTRA : 63)>(); break;
+    case 3: wait_vmcnt<(3 * LPS + EXTRA <= 63 ? 3 * LPS + EXTRA : 63)>(); break;
+    case 4: wait_vmcnt<(4 * LPS + EXTRA <= 63 ? 4 * LPS + EXTRA : 63)>(); break;
+    case 5: wait_vmcnt<(5 * LPS + EXTRA <= 63 ? 5 * LPS + EXTRA : 63)>(); break;
+    default: wait_vmcnt<(6 * LPS + EXTRA <= 63 ? 6 * LPS + EXTRA : 63)>(); break;
+  }
 }
 
 // `pairs` times {one MFMA, then `per` instructions of class `mask`}
@@ -179,7 +193,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
             __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][q / NJ], wf[buf][q % NJ], acc[q / NJ][q % NJ], 0, 0, 0);
   };
 
-  if (nk > 1 && STAGES > 2) wait_vmcnt<LPS>(); else wait_vmcnt<0>();   // slab 0 landed (slab 1 may be in flight)
+  wait_vmcnt_slabs<LPS, 0>(min(STAGES - 2, nk - 1));   // slab 0 landed; the other prologue slabs may be in flight
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -206,8 +220,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
     sched_pairs<0x010, (LB < H1 ? LB : H1), 1>();
     sched_mfma<H1 - (LB < H1 ? LB : H1)>();
     if (kt + 1 < nk) {
-      // this wavefront's loads of slab kt+1 must have landed; of the younger slab, LPS-LA loads are out
-      if (more && STAGES > 2) wait_vmcnt<LPS - LA>(); else wait_vmcnt<0>();
+      // This wavefront's loads of slab kt+1 must have landed.  Younger loads that may stay in flight:
+      // whole slabs kt+2 .. and, if slab kt+STAGES-1 exists, the LPS-LA loads of it issued so far.
+      if (more) wait_vmcnt_slabs<LPS, LPS - LA>(STAGES - 3);
+      else wait_vmcnt_slabs<LPS, 0>(nk - 2 - kt);
       // A bare barrier: __syncthreads() would add a fence that waits for *all* outstanding loads.
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();

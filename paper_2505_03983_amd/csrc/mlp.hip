@@ -20,20 +20,23 @@ typedef GemmCfg16<64, 64, 64> MlpTileSkinny;                      // draft call:
 // (MFMA-bound fraction of the loop ~60%) when that still gives every CU a tile, else 128 x 128.
 typedef PipeCfg16<128, 256, 3, 2, 4> MlpPipeWide;
 typedef PipeCfg16<128, 128, 4, 2, 4> MlpPipeSquare;
+// Draft call (one row per chain): the weights are streamed once for a handful of rows, so the grid is
+// cut fine along N (32 columns per workgroup, two wavefronts) to put every CU on the weight stream.
+typedef PipeCfg16<64, 32, 8, 2, 1> MlpPipeSkinny;  // 7 slabs (84 KB) in flight per workgroup: latency-bound otherwise
 
 // Both operands have row pitch ld = padded(K) (see pitch_of).
 template <class Epi>
 static hipError_t mlp_gemm(int call, const int* n_dev, int n, int N, int K, int64_t ld, const uint16_t* A,
                            const uint16_t* Wt, Epi e, hipStream_t st) {
-  if (call == 1) {
-    // K is rounded up to the slab size: columns K .. ld-1 of both operands are zero (pitch_of leaves
-    // room for it), so the extra products vanish.
-    const int Kp = (int)(ceil_div(K, 64) * 64);
+  // K is rounded up to the slab size: columns K .. ld-1 of both operands are zero (pitch_of leaves
+  // room for it), so the extra products vanish.
+  const int Kp = (int)(ceil_div(K, 64) * 64);
+  if (call == 0) return launch_gemm_bf16_nt_pipe<MlpPipeSkinny, 0>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st);
+  {
     const int64_t wide_tiles = ceil_div(n, 128) * ceil_div(N, 256);
     return wide_tiles >= 192 ? launch_gemm_bf16_nt_pipe<MlpPipeWide, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st)
                              : launch_gemm_bf16_nt_pipe<MlpPipeSquare, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st);
   }
-  return launch_gemm_bf16_nt<MlpTileSkinny, 0>(n_dev, n, N, K, A, ld, Wt, ld, e, st);
 }
 
 // Row pitch (elements) of every bf16 matrix the GEMMs read: K plus 64 elements (128 bytes).
