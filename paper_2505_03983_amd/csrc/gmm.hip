@@ -48,6 +48,7 @@ struct GmmState {
   int np = 0;
   bool use_mfma = false;
   size_t rowwise_lds = 0;
+  size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
 };
 
 // (kappa, gamma, cx, cm) of a row
@@ -141,6 +142,99 @@ __global__ __launch_bounds__(256) void gmm_rowwise_kernel(const int* __restrict_
       }
     }
     __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// row-wise path with the mixture in LDS (d % 4 == 0 and C*(d+4) floats fit): the workgroup copies
+// the means (rows padded by 4 floats, so that 16 lanes reading the same 16-byte column of 16
+// different rows hit 16 different bank groups), |mu|^2 and log w into LDS, then each wavefront
+// serves rows from it.  No cross-lane traffic inside the loops:
+//   pass 1: lane = component: <x, mu_k> over d from LDS (x is a broadcast read),
+//   pass 2: softmax over the C logits (two wavefront reductions),
+//   pass 3: lane = coordinate: sum_k p_k mu_k[j] (p is a broadcast read).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restrict__ n_dev, int nrows_max, int d,
+                                                              int C, int rows_per_wave,
+                                                              const float* __restrict__ in_base,
+                                                              const int64_t* __restrict__ in_off,
+                                                              float* __restrict__ out_base,
+                                                              const int64_t* __restrict__ out_off,
+                                                              const int32_t* __restrict__ tau,
+                                                              const float4* __restrict__ coef_tau,
+                                                              const float* __restrict__ means,
+                                                              const float* __restrict__ musq,
+                                                              const float* __restrict__ log_w) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int d4 = d >> 2, dp = d + 4, C4 = (C + 3) & ~3;
+  const int nrows = min(*n_dev, nrows_max);
+  if (blockIdx.x * 4 * rows_per_wave >= nrows) return;
+  float* m_l = lds;                          // [C][dp]
+  float* q_l = m_l + (size_t)C * dp;         // [C]
+  float* lw_l = q_l + C4;                    // [C]
+  float* ps = lw_l + C4 + (size_t)wave * C4; // [4][C4] logits, then softmax weights
+  float* xs = lw_l + C4 + 4 * (size_t)C4 + (size_t)wave * d;  // [4][d]
+  {
+    const float4* Mg = reinterpret_cast<const float4*>(means);
+    for (int t = threadIdx.x; t < C * d4; t += 256) {
+      const int k = t / d4, c = t - k * d4;
+      *reinterpret_cast<float4*>(&m_l[k * dp + 4 * c]) = Mg[t];
+    }
+    for (int t = threadIdx.x; t < C; t += 256) {
+      q_l[t] = musq[t];
+      lw_l[t] = log_w[t];
+    }
+  }
+  __syncthreads();
+  for (int it = 0; it < rows_per_wave; ++it) {
+    const int n = (blockIdx.x * rows_per_wave + it) * 4 + wave;
+    if (n >= nrows) break;  // uniform per wavefront; no workgroup barrier below
+    const float4 cf = coef_tau[tau[n]];
+    const float* x = in_base + in_off[n];
+    for (int j = lane; j < d; j += 64) xs[j] = x[j];
+    // (LDS operations of one wavefront complete in order: xs is visible to all its lanes below)
+    float mx = -INFINITY;
+    for (int k = lane; k < C; k += 64) {
+      const float* mk = m_l + k * dp;
+      float dot = 0.f;
+#pragma unroll 4
+      for (int c = 0; c < d4; ++c) {
+        const float4 xv = *reinterpret_cast<const float4*>(&xs[4 * c]);
+        const float4 mv = *reinterpret_cast<const float4*>(&mk[4 * c]);
+        dot = fmaf(xv.x, mv.x, fmaf(xv.y, mv.y, fmaf(xv.z, mv.z, fmaf(xv.w, mv.w, dot))));
+      }
+      const float lg = fmaf(cf.x, dot, fmaf(-cf.y, q_l[k], lw_l[k]));
+      ps[k] = lg;
+      mx = fmaxf(mx, lg);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float sum = 0.f;
+    for (int k = lane; k < C4; k += 64) {
+      const float p = (k < C) ? expf(ps[k] - mx) : 0.f;
+      ps[k] = p;
+      sum += p;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    const float sc = cf.w / sum;
+    float* out = out_base + out_off[n];
+    for (int j = lane; j < d; j += 64) {
+      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+      const float* mj = m_l + j;
+#pragma unroll 2
+      for (int k = 0; k < C4; k += 4) {
+        const float4 p = *reinterpret_cast<const float4*>(&ps[k]);
+        // rows past C do not exist: their weights are 0 and the reads are clamped to the last row
+        a0 = fmaf(p.x, mj[min(k + 0, C - 1) * dp], a0);
+        a1 = fmaf(p.y, mj[min(k + 1, C - 1) * dp], a1);
+        a2 = fmaf(p.z, mj[min(k + 2, C - 1) * dp], a2);
+        a3 = fmaf(p.w, mj[min(k + 3, C - 1) * dp], a3);
+      }
+      out[j] = fmaf(cf.z, xs[j], sc * ((a0 + a1) + (a2 + a3)));
+    }
   }
 }
 
@@ -319,6 +413,15 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     set_error("GMM denoiser: C=%d, d=%d needs d %% 4 == 0 and C %% 4 == 0 at this size", C, d);
     return ASD_EUNSUPPORTED;
   }
+  if (!g->use_mfma && d % 4 == 0) {
+    const size_t C4 = ((size_t)C + 3) & ~(size_t)3;
+    const size_t bytes = sizeof(float) * ((size_t)C * (d + 4) + 2 * C4 + 4 * C4 + 4 * (size_t)d);
+    if (bytes <= 150 * 1024) {
+      g->lds_rowwise_bytes = bytes;
+      ASD_HIP(hipFuncSetAttribute((const void*)gmm_rowwise_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024));
+    }
+  }
   if (g->use_mfma) {
     g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finer of the two tilings
     ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
@@ -342,6 +445,16 @@ void gmm_destroy(asd_ctx* ctx) {
 asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   GmmState* g = ctx->gmm;
   const int d = ctx->d, C = g->C, n = rows.n;
+  if (!g->use_mfma && g->lds_rowwise_bytes) {
+    ProfScope ps(ctx, ASD_PROF_GMM_ROWWISE, rows.call, st);
+    // one row per wavefront while that still gives fewer workgroups than CUs, else four
+    const int rpw = n > 4 * 256 ? 4 : 1;
+    hipLaunchKernelGGL(gmm_rowwise_lds_kernel, dim3((unsigned)ceil_div(n, 4 * rpw)), dim3(256),
+                       g->lds_rowwise_bytes, st, rows.n_dev, n, d, C, rpw, rows.in_base, rows.in_off, rows.out_base,
+                       rows.out_off, rows.tau, g->coef_tau, g->means, g->musq, g->log_w);
+    ASD_HIP(hipGetLastError());
+    return ASD_OK;
+  }
   if (!g->use_mfma) {
     ProfScope ps(ctx, ASD_PROF_GMM_ROWWISE, rows.call, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(n, 4), 4096);

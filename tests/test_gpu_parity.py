@@ -86,7 +86,9 @@ def K_minus(tau, K):
     return K - np.asarray(tau)          # step index i with tau[i] = K - i
 
 
-@pytest.mark.parametrize("shape", [dict(d=2, C=4), dict(d=64, C=256), dict(d=7, C=5), dict(d=3, C=130)])
+@pytest.mark.parametrize("shape", [dict(d=2, C=4), dict(d=64, C=256), dict(d=7, C=5), dict(d=3, C=130),
+                                   dict(d=4, C=3), dict(d=8, C=5), dict(d=100, C=67), dict(d=256, C=33),
+                                   dict(d=260, C=9)])
 def test_gmm_rowwise_denoiser(shape):
     cfg = dict(kind="gmm", K=50, chains=4, L=8, var=0.25, **shape)
     got, want = _denoise_case(cfg, 29)
