@@ -164,6 +164,11 @@ ASD_API asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float
  * Rounds are lock-step launches over all unfinished chains. */
 ASD_API asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream);
 
+/* asd_sample launches the rounds of launch-bound workloads as one captured HIP graph per round
+ * (kernels only; the graph is rebuilt when traj, rounds or the stream change).  on = 0 switches to
+ * plain kernel launches; the results are identical.  Default: on. */
+ASD_API asd_status asd_use_graphs(asd_ctx* ctx, int32_t on);
+
 /* Sequential chain with the same random inputs (one model call per step, K
  * launches): the baseline ASD is compared against in the paper's speedups. */
 ASD_API asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream);

@@ -117,8 +117,10 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 2));
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
-  ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * kLiveRing));
-  ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * kLiveRing));
+  ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
+  ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
+  ASD_HIP(hipMalloc(&ctx->key_dev, sizeof(Key)));
+  ASD_HIP(hipMemcpy(ctx->key_dev, &ctx->key, sizeof(Key), hipMemcpyHostToDevice));
   ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * kLiveRing, hipHostMallocDefault));
   ctx->live_ev = new (std::nothrow) hipEvent_t[kLiveRing]();
   if (!ctx->live_ev) return ASD_ENOMEM;
@@ -143,6 +145,9 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->x0hat);
   (void)hipFree(ctx->a);
   (void)hipFree(ctx->live);
+  (void)hipFree(ctx->key_dev);
+  if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
+  if (ctx->own_stream) (void)hipStreamDestroy(ctx->own_stream);
   (void)hipFree(ctx->row_counts);
   ctx->prof.destroy();
   if (ctx->live_host) (void)hipHostFree(ctx->live_host);
@@ -203,8 +208,10 @@ asd_status asd_destroy(asd_ctx* ctx) {
 }
 
 asd_status asd_set_seed(asd_ctx* ctx, uint64_t seed) {
-  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ASD_TRY(check_ctx(ctx));
   ctx->key = make_key(seed);
+  ASD_HIP(hipDeviceSynchronize());  // nothing in flight may still read the old key
+  ASD_HIP(hipMemcpy(ctx->key_dev, &ctx->key, sizeof(Key), hipMemcpyHostToDevice));
   return ASD_OK;
 }
 
@@ -249,6 +256,49 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
   return ASD_OK;
 }
 
+// All launches of one round of Alg. 1 on `st`, plus the copy of the live-chain ring to the host.
+static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
+  ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
+  ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
+  ASD_TRY(launch_draft(ctx, traj, ctx->a, st));
+  if (ctx->L > 1) {
+    ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
+    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+  }
+  ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live, st));
+  // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
+  // long after the host has read it.
+  ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * kLiveRing, hipMemcpyDeviceToHost, st));
+  return ASD_OK;
+}
+
+// Capture one round into a graph (launch-bound workloads: one graph launch instead of ~8 kernel launches).
+// Every launch argument of a round is the same in every round: the round index and the live ring are
+// advanced on the device, the seed is read from device memory.
+static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
+  if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st) return ASD_OK;
+  hipGraph_t graph = nullptr;
+  ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+  asd_status s = enqueue_round(ctx, traj, rounds, st);
+  hipError_t e = hipStreamEndCapture(st, &graph);
+  if (s != ASD_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return s;
+  }
+  ASD_HIP(e);
+  if (ctx->gexec) {
+    (void)hipGraphExecDestroy(ctx->gexec);
+    ctx->gexec = nullptr;
+  }
+  e = hipGraphInstantiate(&ctx->gexec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  ASD_HIP(e);
+  ctx->g_traj = traj;
+  ctx->g_rounds = rounds;
+  ctx->g_stream = st;
+  return ASD_OK;
+}
+
 asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream) {
   ASD_TRY(check_ctx(ctx));
   ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
@@ -256,27 +306,31 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample called between stage calls");
   hipStream_t st = (hipStream_t)stream;
   if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
+  // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
+  // round it has just queued; a finished batch then runs `lag` empty rounds, which cost next to nothing
+  // (every kernel exits at once on finished chains and the model calls see zero rows).
+  const int lag = 2;
+  const bool use_graph = ctx->graphs_enabled && !ctx->prof.on;
+  hipStream_t caller = st;
+  if (use_graph && st == nullptr) {
+    // the legacy default stream cannot be captured: run on a stream of our own, ordered after the caller's work
+    if (!ctx->own_stream) ASD_HIP(hipStreamCreateWithFlags(&ctx->own_stream, hipStreamNonBlocking));
+    ASD_HIP(hipEventRecord(ctx->live_ev[0], caller));
+    ASD_HIP(hipStreamWaitEvent(ctx->own_stream, ctx->live_ev[0], 0));
+    st = ctx->own_stream;
+  }
   ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, rounds, st));
-  // The live-chain count of a round is read back `lag` rounds later so that the
-  // host keeps queueing launches for cheap rounds; a finished batch then runs
-  // `lag` empty rounds (every kernel exits early on finished chains).  Rounds
-  // with heavy model calls are checked at once instead.
-  const double verify_work = (double)ctx->n_rows_max * ctx->model_macs_per_row;
-  const int lag = verify_work > 2.0e9 ? 0 : 2;
   int r = 0;
   int done_at = -1;
   const int r_cap = ctx->K + lag + 1;  // Alg. 1 ends within K iterations (correctness theorem)
   for (; r < r_cap; ++r) {
     const int slot = r % kLiveRing;
-    ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live + slot));
-    ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
-    ASD_TRY(launch_draft(ctx, traj, ctx->a, st));
-    if (ctx->L > 1) {
-      ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
-      ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+    if (use_graph && r > 0) {
+      if (r == 1) ASD_TRY(ensure_round_graph(ctx, traj, rounds, st));  // round 0 ran eagerly (first-use set-up)
+      ASD_HIP(hipGraphLaunch(ctx->gexec, st));
+    } else {
+      ASD_TRY(enqueue_round(ctx, traj, rounds, st));
     }
-    ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live + slot, st));
-    ASD_HIP(hipMemcpyAsync(ctx->live_host + slot, ctx->live + slot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     ASD_HIP(hipEventRecord(ctx->live_ev[slot], st));
     if (r >= lag) {
       const int q = (r - lag) % kLiveRing;
@@ -306,6 +360,12 @@ asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, voi
     ASD_TRY(launch_seq_step(ctx, traj, i, st));
   }
   ASD_HIP(hipStreamSynchronize(st));
+  return ASD_OK;
+}
+
+asd_status asd_use_graphs(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ctx->graphs_enabled = on != 0;
   return ASD_OK;
 }
 

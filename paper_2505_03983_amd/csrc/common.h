@@ -87,6 +87,7 @@ struct asd_ctx {
   int32_t K = 0, L = 0, B = 0, d = 0, n_tau = 0;
   int64_t n_rows_max = 0;  // B * L
   asd::Key key{0, 0};
+  asd::Key* key_dev = nullptr;    // DEV copy of the key: kernels read it, so launches do not depend on the seed
   int kind = 0;
   // schedule on the device
   float* c_x = nullptr;
@@ -103,10 +104,17 @@ struct asd_ctx {
   // owned by asd_sample
   float* x0hat = nullptr;  // [B, L, d]
   int32_t* a = nullptr;    // [B]
-  int32_t* live = nullptr;       // DEV ring of live-chain counters
+  int32_t* live = nullptr;       // DEV [1 + kLiveRing]: round index, then the ring of live-chain counters
   int32_t* live_host = nullptr;  // pinned mirror
   hipEvent_t* live_ev = nullptr;
   int32_t last_rounds = 0;
+  // one round of the cheap-round path as an instantiated HIP graph, valid for (g_traj, g_rounds, g_stream)
+  hipGraphExec_t gexec = nullptr;
+  const void* g_traj = nullptr;
+  const void* g_rounds = nullptr;
+  hipStream_t g_stream = nullptr;
+  hipStream_t own_stream = nullptr;  // used instead of the legacy default stream, which cannot be captured
+  bool graphs_enabled = true;
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
   int64_t* row_counts = nullptr;  // DEV [2]: live rows summed over launches (draft call, verify call)

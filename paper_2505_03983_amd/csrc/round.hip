@@ -36,10 +36,12 @@ __device__ __forceinline__ void store4(float* p, int blk, int d, bool vec, float
 // ----------------------------------------------------------------------------
 // y_0, a = 0, rounds = 0
 // ----------------------------------------------------------------------------
-__global__ void init_state_kernel(int B, int K, int d, Key key, const float* __restrict__ y0,
+__global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ key_p, const float* __restrict__ y0,
                                   float* __restrict__ traj, int32_t* __restrict__ a,
-                                  int32_t* __restrict__ rounds) {
+                                  int32_t* __restrict__ rounds, int32_t* __restrict__ round_idx) {
   const int c = blockIdx.x;
+  const Key key = *key_p;
+  if (c == 0 && threadIdx.x == 0 && round_idx) *round_idx = 0;
   const int nblk = (d + 3) >> 2;
   const bool vec = (d & 3) == 0;
   float* row = traj + (int64_t)c * (K + 1) * d;
@@ -55,8 +57,8 @@ __global__ void init_state_kernel(int B, int K, int d, Key key, const float* __r
 
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds,
                              hipStream_t st) {
-  hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key, y0,
-                     traj, a, rounds);
+  hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key_dev, y0,
+                     traj, a, rounds, ctx->live);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -101,11 +103,17 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          const int32_t* __restrict__ tau,
                                                          int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
                                                          int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows,
-                                                         int32_t* __restrict__ zero_me,
+                                                         int32_t* __restrict__ ring,
                                                          int64_t* __restrict__ row_counts) {
   __shared__ int s_wave[16];
   __shared__ int s_total;
-  if (threadIdx.x == 0 && zero_me) *zero_me = 0;  // live-chain counter of the round that starts here
+  // A round starts here: advance the round index and clear this round's slot of the live-chain ring
+  // (ring[0] = index of the next round, ring[1 + r % kLiveRing] = chains still unfinished after round r).
+  if (threadIdx.x == 0 && ring) {
+    const int r = ring[0];
+    ring[0] = r + 1;
+    ring[1 + (r % kLiveRing)] = 0;
+  }
   int base = 0;
   for (int c0 = 0; c0 < B; c0 += 1024) {
     const int c = c0 + threadIdx.x;
@@ -138,10 +146,10 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
   }
 }
 
-asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me) {
+asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* ring) {
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
-                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, zero_me,
+                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, ring,
                      ctx->prof.on ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -165,7 +173,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
 // walks the window; rows are written coalesced.  HBM-bound: reads 2 rows,
 // writes w rows per chain.
 // ----------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, Key key,
+__global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, const Key* __restrict__ key_p,
                                                     const int32_t* __restrict__ a,
                                                     const float* __restrict__ c_x,
                                                     const float* __restrict__ c_0,
@@ -176,6 +184,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, Key 
   const int nblk = (d + 3) >> 2;
   const int ac = a[c];
   if (blk >= nblk || ac >= K || ac < 0) return;
+  const Key key = *key_p;
   const bool vec = (d & 3) == 0;
   const int w = min(Lwin, K - ac);
   float* row = traj + ((int64_t)c * (K + 1) + ac) * d;
@@ -199,7 +208,7 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   ProfScope ps(ctx, ASD_PROF_DRAFT, 0, st);
-  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a, ctx->c_x,
+  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
                      ctx->c_0, ctx->sigma, ctx->x0a, traj);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -223,7 +232,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int nblk = (ctx->d + 3) / 4;
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
-  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key, ctx->a, ctx->c_x,
+  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
                      ctx->c_0, ctx->sigma, ctx->x0a, traj);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -261,7 +270,8 @@ asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st) {
 //   (using yhat = m + v + sigma xi), and a <- r; else a <- a + w.
 // HBM-bound: reads (w+1) rows of x0hat and one trajectory row, writes one row.
 // ----------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key key, int32_t* __restrict__ a,
+__global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const Key* __restrict__ key_p,
+                                                     int32_t* __restrict__ a,
                                                      const float* __restrict__ c_0,
                                                      const float* __restrict__ sigma,
                                                      const float* __restrict__ x0a,
@@ -282,6 +292,7 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key ke
     if (tid == 0 && accepted) accepted[c] = -1;
     return;
   }
+  const Key key = *key_p;
   const int w = min(L, K - ac);
   const int nblk = (d + 3) >> 2;
   const bool vec = (d & 3) == 0;
@@ -382,7 +393,8 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key ke
     a[c] = a_next;
     if (accepted) accepted[c] = n_acc;
     if (rounds) rounds[c] += 1;
-    if (live && a_next < K) atomicAdd(live, 1);
+    // the plan kernel of this round already advanced the round index
+    if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
     if (stats) {
       float* sp = stats + (int64_t)c * L * 4;
       sp[0] = sp[1] = sp[2] = sp[3] = 0.f;
@@ -393,7 +405,7 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, Key ke
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
   ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
-  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->K, ctx->L, ctx->d, ctx->key, a,
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
                      ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live);
   ASD_HIP(hipGetLastError());
   return ASD_OK;

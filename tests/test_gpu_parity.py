@@ -252,6 +252,34 @@ def test_sample_is_deterministic_and_chain_local():
     ctx5.close()
 
 
+def test_graph_rounds_equal_plain_launches():
+    """The captured per-round graph is replayed many times, with eager work (other samples, other
+    contexts, synchronisations) in between; every replayed sample must equal the plainly launched one."""
+    for w in (1, 2, 3):
+        cfg = W.CONFIGS[w]
+        _, p, _ = oracle_setup(cfg)
+        ctx = runtime.open_ctx(cfg, p, seed=0)
+        tg, te = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+        rg = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+        re_ = torch.zeros_like(rg)
+        side = torch.cuda.Stream()
+        for i, seed in enumerate((11, 12, 11, 13)):
+            ctx.set_seed(seed)
+            ctx.use_graphs(True)
+            if i % 2:
+                with torch.cuda.stream(side):          # a capturable stream
+                    ng = ctx.sample(tg, rg)
+                side.synchronize()
+            else:
+                ng = ctx.sample(tg, rg)                # torch's default stream (the library uses its own)
+            ctx.use_graphs(False)
+            ne = ctx.sample(te, re_)
+            torch.cuda.synchronize()
+            assert ng == ne
+            assert torch.equal(tg, te) and torch.equal(rg, re_), (w, seed)
+        ctx.close()
+
+
 def test_L1_equals_sequential_sampler_bitwise():
     cfg = dict(W.CONFIGS[1], L=1)
     T, p, model = oracle_setup(cfg)
