@@ -270,6 +270,20 @@ asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st) {
 //   (using yhat = m + v + sigma xi), and a <- r; else a <- a + w.
 // HBM-bound: reads (w+1) rows of x0hat and one trajectory row, writes one row.
 // ----------------------------------------------------------------------------
+// Sum over the 64 lanes of a wavefront, returned in every lane.  Four DPP steps reduce each row of
+// 16 lanes (swap inside pairs, swap pairs, mirror the half row, mirror the row); the four row totals
+// are then read out as scalars.  (A butterfly of ds_bpermute-based shuffles costs an LDS round trip
+// per step.)
+__device__ __forceinline__ float wave_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, true));  // row_mirror
+  const int b = __float_as_int(v);
+  return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+         (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
+
 __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const Key* __restrict__ key_p,
                                                      int32_t* __restrict__ a,
                                                      const float* __restrict__ c_0,
@@ -278,6 +292,7 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
                                                      const float* __restrict__ x0hat, float* __restrict__ traj,
                                                      int32_t* __restrict__ accepted, float* __restrict__ stats,
                                                      int32_t* __restrict__ rounds, int32_t* __restrict__ live) {
+  __shared__ float s_part[64][4][2];  // per slot, per wavefront: partial <D,xi>, |D|^2
   __shared__ float s_dot[64];
   __shared__ float s_vv[64];
   __shared__ int s_bit[64];
@@ -299,41 +314,69 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
   const float* g_a = x0a + (int64_t)c * d;
   const float* g_w = x0hat + (int64_t)c * L * d;
 
-  if (tid < 64) {
-    s_dot[tid] = 0.f;
-    s_vv[tid] = 0.f;
-    s_bit[tid] = (tid == 0) ? 1 : 0;
+  // Phase 1: every thread owns the coordinate blocks tid, tid+256, ... and walks the slots; the loads
+  // of successive slots are independent, so many rows are in flight per wavefront.
+  auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {
+    // coordinates past d load as zero in both rows, so they add nothing
+    const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
+    dot = fmaf(dx, xi.x, dot);
+    dot = fmaf(dy, xi.y, dot);
+    dot = fmaf(dz, xi.z, dot);
+    dot = fmaf(dw, xi.w, dot);
+    vv = fmaf(dx, dx, vv);
+    vv = fmaf(dy, dy, vv);
+    vv = fmaf(dz, dz, vv);
+    vv = fmaf(dw, dw, vv);
+  };
+  if (nblk <= 256) {  // one block per thread: x0a stays in registers
+    const bool on = tid < nblk;
+    const float4 ga = on ? load4(g_a, tid, d, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int k = 1; k < w; ++k) {
+      float dot = 0.f, vv = 0.f;
+      if (on) {
+        const float4 gk = load4(g_w + (int64_t)k * d, tid, d, vec);
+        const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)tid);
+        slot_terms(ga, gk, xi, dot, vv);
+      }
+      dot = wave_sum(dot);
+      vv = wave_sum(vv);
+      if (lane == 0) {
+        s_part[k][wave][0] = dot;
+        s_part[k][wave][1] = vv;
+      }
+    }
+  } else {
+    for (int k = 1; k < w; ++k) {
+      const float* g_k = g_w + (int64_t)k * d;
+      float dot = 0.f, vv = 0.f;
+#pragma unroll 2
+      for (int blk = tid; blk < nblk; blk += 256) {
+        const float4 ga = load4(g_a, blk, d, vec);
+        const float4 gk = load4(g_k, blk, d, vec);
+        const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)blk);
+        slot_terms(ga, gk, xi, dot, vv);
+      }
+      dot = wave_sum(dot);
+      vv = wave_sum(vv);
+      if (lane == 0) {
+        s_part[k][wave][0] = dot;
+        s_part[k][wave][1] = vv;
+      }
+    }
   }
   __syncthreads();
 
-  for (int k = 1 + wave; k < w; k += 4) {
-    const int i = ac + k;
-    const float* g_k = g_w + (int64_t)k * d;
-    float dot = 0.f, vv = 0.f;
-    for (int blk = lane; blk < nblk; blk += 64) {
-      const float4 ga = load4(g_a, blk, d, vec);
-      const float4 gk = load4(g_k, blk, d, vec);
-      const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(i + 1), (uint32_t)blk);
-      // coordinates past d load as zero in both rows, so they add nothing
-      const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
-      dot = fmaf(dx, xi.x, dot);
-      dot = fmaf(dy, xi.y, dot);
-      dot = fmaf(dz, xi.z, dot);
-      dot = fmaf(dw, xi.w, dot);
-      vv = fmaf(dx, dx, vv);
-      vv = fmaf(dy, dy, vv);
-      vv = fmaf(dz, dz, vv);
-      vv = fmaf(dw, dw, vv);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      dot += __shfl_xor(dot, off, 64);
-      vv += __shfl_xor(vv, off, 64);
-    }
-    if (lane == 0) {
+  // Alg. 3 accept test, one thread per slot
+  if (tid < 64) {
+    const int k = tid;
+    float dot = 0.f, vv = 0.f, rho = -INFINITY, logu = 0.f;
+    int bit = (k == 0) ? 1 : 0;
+    if (k >= 1 && k < w) {
+      const int i = ac + k;
+      dot = (s_part[k][0][0] + s_part[k][1][0]) + (s_part[k][2][0] + s_part[k][3][0]);
+      vv = (s_part[k][0][1] + s_part[k][1][1]) + (s_part[k][2][1] + s_part[k][3][1]);
       const float sg = sigma[i], c0 = c_0[i];
-      float rho = -INFINITY, logu = 0.f;
-      int bit = 0;
       if (sg > 0.f) {
         const float vxi = c0 * dot;
         const float v2 = c0 * c0 * vv;
@@ -341,24 +384,19 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
         logu = logf(uniform1(key, (uint32_t)c, (uint32_t)(i + 1)));
         bit = (logu <= rho) ? 1 : 0;
       }
-      s_dot[k] = dot;
-      s_vv[k] = vv;
-      s_bit[k] = bit;
-      if (stats) {
-        float* sp = stats + ((int64_t)c * L + k) * 4;
-        sp[0] = dot;
-        sp[1] = vv;
-        sp[2] = logu;
-        sp[3] = rho;
-      }
     }
-  }
-  __syncthreads();
-
-  if (wave == 0) {
-    const int bit = (lane < w) ? s_bit[lane] : 0;
-    const unsigned long long mask = __ballot(bit);
-    // trailing ones of the mask = accepted prefix (bit 0 is always set)
+    s_dot[k] = dot;
+    s_vv[k] = vv;
+    s_bit[k] = bit;
+    if (stats && k < w) {
+      float* sp = stats + ((int64_t)c * L + k) * 4;
+      sp[0] = dot;
+      sp[1] = vv;
+      sp[2] = (k == 0) ? 0.f : logu;
+      sp[3] = (k == 0) ? 0.f : rho;
+    }
+    // Alg. 2: accepted prefix = trailing ones of the ballot (bit 0 is always set)
+    const unsigned long long mask = __ballot(k < w ? bit : 0);
     const unsigned long long inv = ~mask;
     const int n_acc = inv ? (__ffsll((long long)inv) - 1) : 64;
     if (lane == 0) s_nacc = min(n_acc, w);
@@ -395,10 +433,6 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
     if (rounds) rounds[c] += 1;
     // the plan kernel of this round already advanced the round index
     if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
-    if (stats) {
-      float* sp = stats + (int64_t)c * L * 4;
-      sp[0] = sp[1] = sp[2] = sp[3] = 0.f;
-    }
   }
 }
 

@@ -44,7 +44,8 @@ def test_philox_words_bit_identical():
 def test_normals_and_uniforms_match_oracle():
     d = 1023
     worst = 0.0
-    for seed, chain, step in [(0, 0, 0), (3, 5, 17), (99, 1000, 1000)]:
+    cases = [(0, 0, 0), (3, 5, 17), (99, 1000, 1000)] + [(7, c, s) for c in range(6) for s in range(1, 40, 3)]
+    for seed, chain, step in cases:
         xi = torch.zeros(d, dtype=torch.float32, device=DEV)
         u = torch.zeros(1, dtype=torch.float32, device=DEV)
         binding.asd_debug_randoms(seed, chain, step, d, xi, u)
