@@ -189,6 +189,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--others", type=int, default=1, help="also time the other four workloads (1 sample each)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (chains shard trivially across GPUs, see DESIGN.md); "
@@ -200,6 +203,13 @@ def main():
         sys.exit(3)
     import asd_workloads as W
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     res = run_gpu(args.workload, args.steps, args.warmup, args.seed)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)

@@ -19,6 +19,12 @@
 // LDS rows are BK + 4 floats apart: 16 B aligned for the 128-bit reads, and
 // eight consecutive rows then start in eight different groups of four banks.
 //
+// Tile order: blockIdx.x = column tile (fastest), blockIdx.y = row tile.  Workgroups go to the 8 XCDs
+// round-robin by linear id, so an XCD keeps a fixed set of column tiles (its share of B stays in its
+// L2) and streams the row tiles of A.  An XCD-aware order over 8 x 8 super-tiles was measured: it cut
+// the L2 fills of the second GEMM by 40% but raised those of the first and was ~3% slower overall --
+// these kernels are bound by the matrix pipe, not by L2 fills -- so the plain order stays.
+//
 // The number of rows M is read from device memory (the row plan of a model
 // call is compacted on the device, so the host does not know it): the grid is
 // sized for M_max and workgroups past M exit at once.
@@ -59,6 +65,7 @@ struct GemmCfg {
 template <class Cfg>
 struct Frag {
   int wm, wn, l32, half;
+  int tile_n;  // column-tile index of the workgroup
   __device__ __forceinline__ int row(int i, int r) const {
     return wm * (Cfg::BM / 2) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
   }
@@ -85,13 +92,14 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
   float* s_row = Bs + 2 * BN * LDSS;     // [BM]
 
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tile_n = blockIdx.x;
+  const int m0 = blockIdx.y * BM, n0 = tile_n * BN;
   if (m0 >= M) return;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const Frag<Cfg> fr{wave >> 1, wave & 1, lane & 31, lane >> 5};
+  const Frag<Cfg> fr{wave >> 1, wave & 1, lane & 31, lane >> 5, tile_n};
 
   const int lrow = tid / KQ, lkq = tid % KQ;
   const float* ap[RA];

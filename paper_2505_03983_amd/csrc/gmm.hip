@@ -293,7 +293,7 @@ struct LogitOp {
         }
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // stays inside the half-wave
-        if (mok && fr.l32 == 0) pmax[(int64_t)m * np + 2 * blockIdx.x + fr.wn] = mx;
+        if (mok && fr.l32 == 0) pmax[(int64_t)m * np + 2 * fr.tile_n + fr.wn] = mx;
       }
     }
   }
