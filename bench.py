@@ -28,6 +28,14 @@ import numpy as np  # noqa: E402
 PEAK = {"f32": 157.3, "bf16": 2500.0}          # dense MFMA TFLOP/s, MI355X
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per launch (mean over the launches of one sample of workload 5) of the two verify GEMMs:
+# rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 1 GiB copy in the same run);
+# see profiles/cfg5_gmm_verify_gemm_hbm_traffic.txt for the commands and the raw readings.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    (5, "GMM_LOGITS/verify"): 1024.0 * (2.0 * 1147350.1 + 758070.6),
+    (5, "GMM_COMBINE/verify"): 1024.0 * (2.0 * 3274713.3 + 175748.3),
+}
+
 
 def workload_name(w, cfg):
     if cfg["kind"] == "gmm":
@@ -90,7 +98,7 @@ def run_gpu(w, steps, warmup, seed, profile=True):
     return out
 
 
-def roofline(res):
+def roofline(res, w=None):
     """Roofline entry of the dominant kernel of a profiled run."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
@@ -115,7 +123,7 @@ def roofline(res):
     achieved = flops_per_launch / avg_s / 1e12
     peak = PEAK[dtype]
     return dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
-                traffic=None, avg_launch_us=1e6 * avg_s, launches=launches,
+                traffic=TRAFFIC_BYTES_PER_LAUNCH.get((w, name)), avg_launch_us=1e6 * avg_s, launches=launches,
                 algorithmic_flops_per_launch=flops_per_launch,
                 share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
 
@@ -232,7 +240,7 @@ def main():
                    "L": cfg["L"], "d": cfg["d"]},
         "rounds_per_sample": {"mean": res["rounds_mean"], "max": res["rounds_max"],
                               "launched": res["rounds_launched"]},
-        "roofline": roofline(res),
+        "roofline": roofline(res, args.workload),
         "hbm_kernels": hbm_kernels(res),
         "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
                         "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()},

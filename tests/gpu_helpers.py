@@ -22,6 +22,19 @@ def rel_err(got, want):
     return float(np.max(np.abs(got - want)) / max(1.0, np.max(np.abs(want))))
 
 
+def unclipped_scale(cfg, T, p, rec):
+    """max |network output before the clip| over the rows of a round (1.0 for the exact GMM denoiser)."""
+    if cfg["kind"] != "mlp" or not p.get("out_clip"):
+        return 1.0
+    from oracle_helpers import mlp_model
+    raw = mlp_model(T, dict(p, out_clip=0.0))
+    a, b = rec["a"], rec["b"]
+    rows = np.concatenate([rec["yhat"][: b - a - 1]]) if b - a > 1 else rec["yhat"][:0]
+    if rows.shape[0] == 0:
+        return 1.0
+    return float(np.abs(raw(list(range(a + 1, b)), rows)).max())
+
+
 def oracle_chain(cfg, T, model, seed, chain, eps, L=None, K=None):
     K = K or cfg["K"]
     xi, u = chain_randoms(seed, chain, K, cfg["d"])
@@ -56,16 +69,18 @@ def teacher_forced_round(ctx, cfg, states, L=None):
                 x0hat=x0hat.cpu().numpy(), stats=stats.cpu().numpy())
 
 
-def compare_round(out, c, rec, tol, K):
+def compare_round(out, c, rec, tol, K, x0_scale=1.0):
     """Compare device results of chain c with the oracle's record of the same round.
     Returns (ok_bits, first_flagged) and asserts on everything else."""
     a, b = rec["a"], rec["b"]
     w = b - a
     # proposal samples
-    e = rel_err(out["drafted"][c, a + 1: b + 1], rec["yhat"])
+    e = rel_err(out["drafted"][c][a + 1: b + 1], rec["yhat"])
     assert e <= tol, ("yhat", c, a, e)
     # model values at slots 0..w-1
-    e = rel_err(out["x0hat"][c, :w], rec["g"])
+    # For the clipped bf16 network the rounding noise lives on the scale of the *unclipped* output
+    # (x0_scale = max |unclipped oracle output| over these rows, >= 1), which the clip then hides.
+    e = rel_err(out["x0hat"][c][:w], rec["g"]) / max(1.0, x0_scale)
     assert e <= tol, ("x0hat", c, a, e)
     # decisions: exact off flagged near-ties, walking the prefix as Alg. 2 does
     n_acc_dev = int(out["accepted"][c])
@@ -77,6 +92,6 @@ def compare_round(out, c, rec, tol, K):
         return False
     assert out["a_next"][c] == rec["a_next"]
     # values written by the round
-    e = rel_err(out["traj"][c, a + 1: rec["a_next"] + 1], rec["y_new"])
+    e = rel_err(out["traj"][c][a + 1: rec["a_next"] + 1], rec["y_new"])
     assert e <= tol, ("y_new", c, a, e)
     return True

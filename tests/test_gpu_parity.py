@@ -156,7 +156,7 @@ def _teacher_forced(cfg, seed, chains_checked, rounds_per_chain=4, model_seed=1)
                 states.append((K, np.zeros(cfg["d"], np.float32)))       # finished chain: must stay untouched
         out = H.teacher_forced_round(ctx, cfg, states)
         for c, rec in picked.items():
-            ok = H.compare_round(out, c, rec, tol, K)
+            ok = H.compare_round(out, c, rec, tol, K, H.unclipped_scale(cfg, T, p, rec))
             n_checked += ok
             n_skipped += (not ok)
         for c in range(B):
@@ -333,3 +333,73 @@ def test_stage_order_is_enforced():
     ctx.accept(traj, a, x0)
     torch.cuda.synchronize()
     ctx.close()
+
+
+# ---------------------------------------------------------------------------
+# full-size workloads in the launch configuration bench.py times: one round from synthetic
+# mid-run states, sampled chains checked against the oracle, all chains against invariants
+# ---------------------------------------------------------------------------
+def _full_size_round(w, sampled, seed=0):
+    cfg = W.CONFIGS[w]
+    T, p, model = oracle_setup(cfg)
+    tol = H.TOL[cfg["kind"]]
+    B, K, L, d = cfg["chains"], cfg["K"], cfg["L"], cfg["d"]
+    ctx = runtime.open_ctx(cfg, p, seed=seed)
+    rng = np.random.default_rng(seed + 100 * w)
+    # states: start, middle, a window cut by K, a finished chain
+    choices = np.array([0, K // 3, (2 * K) // 3, K - L // 2, K - 1, K])
+    a_host = choices[rng.integers(0, len(choices), B)].astype(np.int32)
+    a_host[list(sampled)] = [0, K // 3, K - L // 2, (2 * K) // 3][: len(sampled)]
+    ya = np.zeros((B, d), np.float32)
+    for c in range(B):
+        if a_host[c] >= K:
+            continue
+        ab = T["abar"][T["tau"][a_host[c]]]
+        if cfg["kind"] == "gmm":
+            x0 = p["means"][rng.integers(0, cfg["C"])] + np.sqrt(p["var"]) * rng.standard_normal(d)
+        else:
+            x0 = rng.uniform(-1, 1, d)
+        ya[c] = np.sqrt(ab) * x0 + np.sqrt(1 - ab) * rng.standard_normal(d)
+    traj = torch.zeros((B, K + 1, d), dtype=torch.float32, device=DEV)
+    idx = torch.arange(B, device=DEV)
+    a_dev = torch.from_numpy(a_host).to(DEV)
+    traj[idx, a_dev.long().clamp(max=K)] = torch.from_numpy(ya).to(DEV)
+    x0hat = torch.zeros((B, L, d), dtype=torch.float32, device=DEV)
+    accepted = torch.zeros(B, dtype=torch.int32, device=DEV)
+    a_run = a_dev.clone()
+    ctx.draft(traj, a_run)
+    ctx.verify(traj, a_run, x0hat)
+    drafted = {c: traj[c].cpu().numpy().copy() for c in sampled}
+    ctx.accept(traj, a_run, x0hat, accepted)
+    torch.cuda.synchronize()
+    a_next, acc = a_run.cpu().numpy(), accepted.cpu().numpy()
+    # invariants on every chain (structure of a round, correctness lemma)
+    for c in range(B):
+        if a_host[c] >= K:
+            assert a_next[c] == K and acc[c] == -1
+            continue
+        wdw = min(L, K - a_host[c])
+        assert 1 <= acc[c] <= wdw
+        assert a_next[c] == a_host[c] + (acc[c] + 1 if acc[c] < wdw else wdw)
+    assert torch.isfinite(x0hat[torch.from_numpy(a_host < K).to(DEV), 0]).all()
+    compared = 0
+    for c in sampled:
+        xi, u = chain_randoms(seed, c, K, d)
+        _log("oracle round", w, "chain", c, "a", int(a_host[c]))
+        rec = oasd.asd_round(ya[c].astype(np.float64), int(a_host[c]), L, T["c_x"], T["c_0"], T["sigma"], model, xi, u,
+                             eps=tol)
+        out = dict(drafted={c: drafted[c]}, x0hat={c: x0hat[c].cpu().numpy()}, accepted={c: acc[c]},
+                   a_next={c: a_next[c]}, traj={c: traj[c].cpu().numpy()})
+        compared += bool(H.compare_round(out, c, rec, tol, K, H.unclipped_scale(cfg, T, p, rec)))
+    ctx.close()
+    _log("full-size round cfg", w, "chains compared in full", compared, "of", len(sampled),
+         "mean accepted", float(acc[acc >= 0].mean()))
+    assert compared >= len(sampled) - 1
+
+
+def test_round_config4_full_size_sampled():
+    _full_size_round(4, sampled=[0, 31, 63])
+
+
+def test_round_config5_full_size_sampled():
+    _full_size_round(5, sampled=[0, 517, 1023])
