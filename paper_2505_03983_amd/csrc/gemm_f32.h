@@ -155,6 +155,9 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
     for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) bf[0][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS);
+    // While it has fragments to feed, a wavefront outranks its SIMD neighbours that are between slabs
+    // (loading, storing to LDS, at the barrier): the matrix pipe is the resource to keep busy.
+    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int c = ks & 1;
@@ -177,6 +180,7 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
         }
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     if (kt + 1 < nk) sstore(cur ^ 1);
     __syncthreads();
   }

@@ -107,6 +107,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          int64_t* __restrict__ row_counts) {
   __shared__ int s_wave[16];
   __shared__ int s_total;
+  __shared__ int s_off[1024], s_cnt[1024], s_ac[1024];
   // A round starts here: advance the round index and clear this round's slot of the live-chain ring
   // (ring[0] = index of the next round, ring[1 + r % kLiveRing] = chains still unfinished after round r).
   if (threadIdx.x == 0 && ring) {
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     ring[0] = r + 1;
     ring[1 + (r % kLiveRing)] = 0;
   }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int base = 0;
   for (int c0 = 0; c0 < B; c0 += 1024) {
     const int c = c0 + threadIdx.x;
@@ -130,11 +132,19 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
         row_tau[off] = tau[ac];
       }
     } else {
-      for (int s = 1; s <= cnt; ++s) {
-        const int i = ac + s;
-        in_off[off + s - 1] = ((int64_t)c * (K + 1) + i) * d;
-        out_off[off + s - 1] = ((int64_t)c * L + s) * d;
-        row_tau[off + s - 1] = tau[i];
+      // the rows of a chain are written by a whole wavefront (consecutive entries, coalesced)
+      s_off[threadIdx.x] = off;
+      s_cnt[threadIdx.x] = cnt;
+      s_ac[threadIdx.x] = ac;
+      __syncthreads();
+      for (int t = wave; t < 1024 && c0 + t < B; t += 16) {
+        const int n_t = s_cnt[t], o_t = s_off[t], a_t = s_ac[t], c_t = c0 + t;
+        for (int s = 1 + lane; s <= n_t; s += 64) {
+          const int i = a_t + s;
+          in_off[o_t + s - 1] = ((int64_t)c_t * (K + 1) + i) * d;
+          out_off[o_t + s - 1] = ((int64_t)c_t * L + s) * d;
+          row_tau[o_t + s - 1] = tau[i];
+        }
       }
     }
     base += s_total;
