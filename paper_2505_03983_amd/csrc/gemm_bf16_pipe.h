@@ -23,6 +23,13 @@
 //
 // Requirements (checked by the host): K % 64 == 0, lda and ldw multiples of 8,
 // 16-byte aligned bases.  M comes from device memory (compacted row plan).
+//
+// Split K (gridDim.z > 1): for a handful of rows the kernel is a stream of the weight matrix, and HBM
+// only delivers its bandwidth with ~16 MB in flight -- more workgroups than the output has tiles.  The
+// z-th workgroup of a tile contracts the z-th share of K and leaves its fp32 partial tile in scratch;
+// splitk_finish_kernel then adds the partials in z order and runs the epilogue.  (Finishing inside the
+// GEMM, by whichever workgroup of a tile arrives last, was measured: the device-scope fences it needs
+// write back and invalidate an XCD's whole L2 and cost more than the second launch.)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -95,7 +102,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
                                                                          int N, int K,
                                                                          const uint16_t* __restrict__ A, int64_t lda,
                                                                          const uint16_t* __restrict__ W, int64_t ldw,
-                                                                         Epi epi) {
+                                                                         Epi epi, float* __restrict__ part) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, STAGES = Cfg::STAGES, MI = Cfg::MI, NJ = Cfg::NJ, NW = Cfg::NW;
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
   constexpr int A_LOADS = Cfg::A_LOADS, W_LOADS = Cfg::W_LOADS, LPS = Cfg::LPS, STAGE_BYTES = Cfg::STAGE_BYTES;
@@ -111,6 +118,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
   const int l32 = lane & 31, half = lane >> 5;
 
+  const int splits = gridDim.z;
+  const int nk = K / 64 / splits;                       // slabs of this workgroup's share of K
+  const int64_t k0 = (int64_t)blockIdx.z * nk * 64;
+
   // loader: wave-load q covers rows 8q..8q+7; lane L fills chunk slot L of that 1 KB block
   const int lr = lane >> 3;
   const uint16_t* ap[A_LOADS];
@@ -119,16 +130,14 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   for (int p = 0; p < A_LOADS; ++p) {
     const int row = (wave + NW * p) * 8 + lr;                // row inside the tile
     const int chunk = (lane & 7) ^ ((row >> 1) & 7);         // global chunk that belongs in slot (lane & 7)
-    ap[p] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8;
+    ap[p] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8 + k0;
   }
 #pragma unroll
   for (int p = 0; p < W_LOADS; ++p) {
     const int row = (wave + NW * p) * 8 + lr;
     const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-    wp[p] = W + (int64_t)min(n0 + row, N - 1) * ldw + chunk * 8;
+    wp[p] = W + (int64_t)min(n0 + row, N - 1) * ldw + chunk * 8 + k0;
   }
-  const int nk = K / 64;
-
   // wave-loads first .. first+count-1 (A loads, then W loads) of slab kt into `stage`
   auto issue = [&](int kt, int stage, int first, int count) {
     uint8_t* sb = ldsb + stage * STAGE_BYTES;
@@ -257,6 +266,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   constexpr int ITERS = WM / RPI, BATCH = ITERS < 8 ? ITERS : 8;
   static_assert(ITERS % BATCH == 0, "epilogue batching");
   const int n = n0 + wn * WN + lcol;
+  if (splits > 1) {
+    for (int it = 0; it < ITERS; ++it) {
+      const int row = it * RPI + lrow;
+      const int m = m0 + wm * WM + row;
+      if (m < M && n < N)
+        *reinterpret_cast<float4*>(part + ((int64_t)blockIdx.z * M_max + m) * N + n) =
+            *reinterpret_cast<const float4*>(&stage[row * WN + lcol]);
+    }
+    return;
+  }
   for (int it0 = 0; it0 < ITERS; it0 += BATCH) {
     float4 v[BATCH], prev[BATCH];
 #pragma unroll
@@ -274,10 +293,30 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   }
 }
 
+// One thread per four columns of a row: partials added in z order, then the epilogue.
+template <class Epi>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const int* __restrict__ M_dev, int M_max, int N, int splits,
+                                                            const float* __restrict__ part, Epi epi) {
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  const int m = blockIdx.y;
+  const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (m >= M || n >= N) return;
+  const float4 prev = Epi::kLoads ? epi.load4(m, n) : make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 v = *reinterpret_cast<const float4*>(part + (int64_t)m * N + n);
+  for (int z = 1; z < splits; ++z) {
+    const float4 q = *reinterpret_cast<const float4*>(part + ((int64_t)z * M_max + m) * N + n);
+    v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+  }
+  epi.store4(m, n, v, prev);
+}
+
+// splits > 1 needs (K / 64) % splits == 0 and `part` of splits * M * N floats.
 template <class Cfg, int CALL, class Epi>
 inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K, const uint16_t* A, int64_t lda,
-                                           const uint16_t* W, int64_t ldw, Epi epi, hipStream_t st) {
-  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M + Cfg::BM - 1) / Cfg::BM));
+                                           const uint16_t* W, int64_t ldw, Epi epi, hipStream_t st, int splits = 1,
+                                           float* part = nullptr) {
+  if (splits < 1 || (K / 64) % splits != 0 || (splits > 1 && !part)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)splits);
   auto kern = gemm_bf16_nt_pipe_kernel<Cfg, Epi, CALL>;
   static bool attr_set = false;  // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {
@@ -286,7 +325,10 @@ inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, W, ldw, epi);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, W, ldw, epi, part);
+  if (splits > 1)
+    hipLaunchKernelGGL(splitk_finish_kernel<Epi>, dim3((unsigned)((N / 4 + 255) / 256), (unsigned)M), dim3(256), 0, st,
+                       M_dev, M, N, splits, part, epi);
   return hipGetLastError();
 }
 

@@ -20,18 +20,31 @@ typedef GemmCfg16<64, 64, 64> MlpTileSkinny;                      // draft call:
 // (MFMA-bound fraction of the loop ~60%) when that still gives every CU a tile, else 128 x 128.
 typedef PipeCfg16<128, 256, 3, 2, 4> MlpPipeWide;
 typedef PipeCfg16<128, 128, 4, 2, 4> MlpPipeSquare;
-// Draft call (one row per chain): the weights are streamed once for a handful of rows, so the grid is
-// cut fine along N (32 columns per workgroup, two wavefronts) to put every CU on the weight stream.
-typedef PipeCfg16<64, 32, 8, 2, 1> MlpPipeSkinny;  // 7 slabs (84 KB) in flight per workgroup: latency-bound otherwise
+// Draft call (one row per chain): the weights are streamed once for a handful of rows.  64 x 64 tiles
+// with 7 slabs (56 KB of weights) in flight each, and K split so that there are at least as many
+// workgroups as CUs: ~14 MB of the weight stream in flight, which is what HBM latency asks for.
+typedef PipeCfg16<64, 64, 8, 2, 2> MlpPipeSkinny;
+constexpr int kMaxSplits = 8;
+
+struct SplitScratch {
+  float* part = nullptr;   // [kMaxSplits][rows][max N] fp32 partial tiles
+  int rows = 0;            // rows the scratch was sized for (one per chain)
+};
 
 // Both operands have row pitch ld = padded(K) (see pitch_of).
 template <class Epi>
 static hipError_t mlp_gemm(int call, const int* n_dev, int n, int N, int K, int64_t ld, const uint16_t* A,
-                           const uint16_t* Wt, Epi e, hipStream_t st) {
+                           const uint16_t* Wt, Epi e, hipStream_t st, const SplitScratch& sc) {
   // K is rounded up to the slab size: columns K .. ld-1 of both operands are zero (pitch_of leaves
   // room for it), so the extra products vanish.
   const int Kp = (int)(ceil_div(K, 64) * 64);
-  if (call == 0) return launch_gemm_bf16_nt_pipe<MlpPipeSkinny, 0>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st);
+  if (call == 0) {
+    const int64_t tiles = ceil_div(n, MlpPipeSkinny::BM) * ceil_div(N, MlpPipeSkinny::BN);
+    int splits = 1;
+    if (n <= sc.rows)
+      while (splits < kMaxSplits && tiles * splits < 256 && (Kp / 64) % (2 * splits) == 0) splits *= 2;
+    return launch_gemm_bf16_nt_pipe<MlpPipeSkinny, 0>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st, splits, sc.part);
+  }
   {
     const int64_t wide_tiles = ceil_div(n, 128) * ceil_div(N, 256);
     return wide_tiles >= 192 ? launch_gemm_bf16_nt_pipe<MlpPipeWide, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st)
@@ -61,6 +74,7 @@ struct MlpState {
   uint16_t* in_bf = nullptr;  // [rows_max, ld_in]
   float* h = nullptr;         // [rows_max, width]
   uint16_t* hb[2] = {nullptr, nullptr};
+  SplitScratch split;
 };
 
 // in_bf[n] = [ bf16(x_n) ; temb[tau_n] ], eight elements per thread
@@ -215,6 +229,11 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den) {
     ASD_HIP(hipMemset(s->wp_blk, 0, sizeof(uint16_t) * nb * Wd * s->ld_h));
     ASD_HIP(hipMemcpy2D(s->wp_blk, 2 * s->ld_h, s->w_blk, 2 * Wd, 2 * Wd, nb * Wd, hipMemcpyDeviceToDevice));
   }
+  {
+    const size_t max_n = std::max(Wd, dd);
+    s->split.rows = ctx->B;
+    ASD_HIP(hipMalloc(&s->split.part, sizeof(float) * kMaxSplits * (size_t)ctx->B * max_n));
+  }
   ASD_HIP(hipDeviceSynchronize());
   return ASD_OK;
 }
@@ -229,6 +248,7 @@ void mlp_destroy(asd_ctx* ctx) {
   (void)hipFree(s->wp_in);
   (void)hipFree(s->wp_blk);
   (void)hipFree(s->wp_out);
+  (void)hipFree(s->split.part);
   delete s;
   ctx->mlp = nullptr;
 }
@@ -248,19 +268,20 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_IN, rows.call, st);
     ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, W, s->in_dim, s->ld_in, s->in_bf, s->wp_in,
-                     InEpi{s->h, s->hb[0], s->b_in, W, s->ld_h}, st));
+                     InEpi{s->h, s->hb[0], s->b_in, W, s->ld_h}, st, s->split));
   }
   int cur = 0;
   for (int l = 0; l < s->n_blocks; ++l) {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_BLK, rows.call, st);
     const BlockEpi e{s->h, s->hb[cur ^ 1], s->b_blk ? s->b_blk + (size_t)l * W : nullptr, W, s->ld_h};
-    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, W, W, s->ld_h, s->hb[cur], s->wp_blk + (size_t)l * W * s->ld_h, e, st));
+    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, W, W, s->ld_h, s->hb[cur], s->wp_blk + (size_t)l * W * s->ld_h, e, st,
+                     s->split));
     cur ^= 1;
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_OUT, rows.call, st);
     const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip};
-    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, d, W, s->ld_h, s->hb[cur], s->wp_out, e, st));
+    ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, d, W, s->ld_h, s->hb[cur], s->wp_out, e, st, s->split));
   }
   return ASD_OK;
 }
