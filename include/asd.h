@@ -152,8 +152,11 @@ ASD_API asd_status asd_verify(asd_ctx* ctx, const float* traj, const int32_t* a,
  *   traj[c][j+1] is overwritten by the reflected sample and a_c = j+1, else
  *   a_c = j.  accepted (DEV int32 [chains], may be NULL) receives j - a_c(old)
  *   (-1 for finished chains).
- *   stats (DEV fp32 [chains, L, 4], may be NULL) receives per slot
- *   (<d,xi>, |d|^2, log u, rho) with d = x0a - x0hat[s]  (slot 0: zeros). */
+ *   stats (DEV fp32 [chains, L, 4], may be NULL) receives per examined slot
+ *   (<d,xi>, |d|^2, log u, rho) with d = x0a - x0hat[s]  (slot 0: zeros).
+ *   The window is examined in order, eight slots at a time, up to the group
+ *   that holds the first rejection; entries of later slots are left as they
+ *   were. */
 ASD_API asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
                       int32_t* accepted, float* stats, void* stream);
 
@@ -168,6 +171,13 @@ ASD_API asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_
  * (kernels only; the graph is rebuilt when traj, rounds or the stream change).  on = 0 switches to
  * plain kernel launches; the results are identical.  Default: on. */
 ASD_API asd_status asd_use_graphs(asd_ctx* ctx, int32_t on);
+
+/* For a Gaussian-mixture denoiser small enough to sit in one CU's LDS (with the window of a chain),
+ * asd_sample runs Alg. 1 for each chain inside one workgroup: one launch per sample instead of
+ * several per round (chains do not interact, so no step of the method changes; rounds[c] keeps its
+ * meaning and asd_last_round_count returns the largest of them).  on = 0 forces the lock-step
+ * round kernels; the two paths agree to rounding.  Default: on.  Other shapes ignore the switch. */
+ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
 
 /* Sequential chain with the same random inputs (one model call per step, K
  * launches): the baseline ASD is compared against in the paper's speedups. */

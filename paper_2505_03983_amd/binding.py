@@ -64,6 +64,7 @@ def lib():
             "asd_sample_sequential": (i32, [vp, vp, vp, vp]),
             "asd_last_round_count": (i32, [vp]),
             "asd_use_graphs": (i32, [vp, i32]),
+            "asd_use_resident": (i32, [vp, i32]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
             "asd_profile_enable": (i32, [vp, i32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
@@ -183,6 +184,9 @@ class Ctx:
 
     def use_graphs(self, on=True):
         _check(lib().asd_use_graphs(self.h, int(bool(on))))
+
+    def use_resident(self, on=True):
+        _check(lib().asd_use_resident(self.h, int(bool(on))))
 
     def set_seed(self, seed):
         _check(lib().asd_set_seed(self.h, int(seed)))

@@ -305,6 +305,10 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
   if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample called between stage calls");
   hipStream_t st = (hipStream_t)stream;
+  // Small mixtures: the whole sample is one launch, a workgroup per chain (profiling wants the
+  // stand-alone kernels, whose times it reports).
+  if (ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx))
+    return gmm_chain_sample(ctx, y0, traj, rounds, st);
   if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
   // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
   // round it has just queued; a finished batch then runs `lag` empty rounds, which cost next to nothing
@@ -366,6 +370,12 @@ asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, voi
 asd_status asd_use_graphs(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   ctx->graphs_enabled = on != 0;
+  return ASD_OK;
+}
+
+asd_status asd_use_resident(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ctx->resident_enabled = on != 0;
   return ASD_OK;
 }
 

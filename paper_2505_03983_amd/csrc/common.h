@@ -115,6 +115,7 @@ struct asd_ctx {
   hipStream_t g_stream = nullptr;
   hipStream_t own_stream = nullptr;  // used instead of the legacy default stream, which cannot be captured
   bool graphs_enabled = true;
+  bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
   int64_t* row_counts = nullptr;  // DEV [2]: live rows summed over launches (draft call, verify call)
@@ -152,6 +153,9 @@ struct ProfScope {
 asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den);
 void gmm_destroy(asd_ctx* ctx);
 asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
+// chain-resident sampler (gmm_chain.hip): all of Alg. 1 for a chain in one workgroup, one launch per sample
+bool gmm_chain_supported(const asd_ctx* ctx);
+asd_status gmm_chain_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, hipStream_t st);
 
 asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den);
 void mlp_destroy(asd_ctx* ctx);

@@ -20,6 +20,7 @@
 //    final affine combination fused in the epilogue.
 #include "common.h"
 #include "gemm_f32.h"
+#include "gmm_state.h"
 
 namespace asd {
 
@@ -34,22 +35,6 @@ namespace asd {
 #endif
 typedef GemmCfg<ASD_G32_BM, ASD_G32_BN, ASD_G32_BK> GmmTile;  // verify call: tens of thousands of rows
 typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one row per chain, fill the chip
-
-struct GmmState {
-  int C = 0;
-  float var = 0.f;
-  const float* means = nullptr;  // caller's [C, d]
-  const float* log_w = nullptr;  // caller's [C]
-  float* means_t = nullptr;      // [d, C]
-  float* musq = nullptr;         // [C]
-  float4* coef_tau = nullptr;    // [n_tau]: (kappa, gamma, cx, cm)
-  float* logits = nullptr;       // [rows_max, C] (matrix-core path only)
-  float* pmax = nullptr;         // [rows_max, np] partial row maxima of the logits
-  int np = 0;
-  bool use_mfma = false;
-  size_t rowwise_lds = 0;
-  size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
-};
 
 // (kappa, gamma, cx, cm) of a row
 __device__ __forceinline__ float4 row_coef(const float4* coef_tau, const int32_t* tau, int n) {

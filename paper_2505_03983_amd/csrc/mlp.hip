@@ -41,7 +41,8 @@ static hipError_t mlp_gemm(int call, const int* n_dev, int n, int N, int K, int6
   if (call == 0) {
     const int64_t tiles = ceil_div(n, MlpPipeSkinny::BM) * ceil_div(N, MlpPipeSkinny::BN);
     int splits = 1;
-    if (n <= sc.rows)
+    // only a weight matrix that takes several microseconds to stream repays the second launch
+    if (n <= sc.rows && (int64_t)N * Kp * 2 >= (8 << 20))
       while (splits < kMaxSplits && tiles * splits < 256 && (Kp / 64) % (2 * splits) == 0) splits *= 2;
     return launch_gemm_bf16_nt_pipe<MlpPipeSkinny, 0>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st, splits, sc.part);
   }

@@ -3,35 +3,9 @@
 // fused accept / first-rejection scan / reflection-resample kernel
 // (Alg. 3 on every slot, Alg. 2, and the advance rule of Alg. 1).
 #include "common.h"
+#include "device_util.h"
 
 namespace asd {
-
-// ----------------------------------------------------------------------------
-// helpers: a row of d floats is handled in blocks of four coordinates, one
-// Philox call per block.  d need not be a multiple of four.
-// ----------------------------------------------------------------------------
-__device__ __forceinline__ float4 load4(const float* p, int blk, int d, bool vec) {
-  if (vec) return reinterpret_cast<const float4*>(p)[blk];
-  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-  const int j = blk * 4;
-  if (j + 0 < d) r.x = p[j + 0];
-  if (j + 1 < d) r.y = p[j + 1];
-  if (j + 2 < d) r.z = p[j + 2];
-  if (j + 3 < d) r.w = p[j + 3];
-  return r;
-}
-
-__device__ __forceinline__ void store4(float* p, int blk, int d, bool vec, float4 v) {
-  if (vec) {
-    reinterpret_cast<float4*>(p)[blk] = v;
-    return;
-  }
-  const int j = blk * 4;
-  if (j + 0 < d) p[j + 0] = v.x;
-  if (j + 1 < d) p[j + 1] = v.y;
-  if (j + 2 < d) p[j + 2] = v.z;
-  if (j + 3 < d) p[j + 3] = v.w;
-}
 
 // ----------------------------------------------------------------------------
 // y_0, a = 0, rounds = 0
@@ -263,55 +237,47 @@ asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st) {
 }
 
 // ----------------------------------------------------------------------------
-// Accept + scan + resample + advance.  One workgroup (4 wavefronts) per chain.
+// Accept + scan + resample + advance.  One workgroup per chain; its size follows d
+// (one thread per four coordinates, 1 to 16 wavefronts).
 //
-// Phase 1 (Alg. 3, accept test): wavefront q takes slots k = 1+q, 5+q, ...;
-//   with D = x0a - x0hat[k] (so v = c_0 D) it reduces <D, xi> and |D|^2 over
-//   the row, regenerating xi_{a+k+1} from the counter, and lane 0 evaluates
+// The window is examined kAcceptChunk slots at a time, in order, and the walk stops at the
+// chunk that holds the first rejection: Alg. 2 only needs the accepted prefix, and the slots
+// behind the first rejection (most of the window, typically) are never read.
+// Per chunk:
+//   Alg. 3, accept test: with D = x0a - x0hat[k] (so v = c_0 D) every thread adds its
+//   coordinates' share of <D, xi> and |D|^2 for each slot k of the chunk, regenerating
+//   xi_{a+k+1} from the counter; the wavefront totals go to LDS and one thread per slot evaluates
 //       rho = -( c_0 <D,xi> / sigma + c_0^2 |D|^2 / (2 sigma^2) ),
 //       bit = [ log u_{a+k+1} <= rho ].
 //   Slot 0 (step a+1) has v == 0 by construction and is accepted; a slot with
 //   sigma == 0 is rejected (sigma -> 0 limit of the test).
-// Phase 2 (Alg. 2): one wavefront ballots the <= 64 bits into a mask and
-//   counts its trailing ones: n_acc = length of the accepted prefix.
-// Phase 3 (Alg. 3 reject branch + advance rule of Alg. 1): if n_acc < w the
+//   Alg. 2: the wavefront ballots the chunk's bits and counts the trailing ones.
+// Then (Alg. 3 reject branch + advance rule of Alg. 1): if n_acc < w the
 //   row of step r = a + n_acc + 1 becomes
 //       m + sigma (xi - 2 v <v,xi>/|v|^2) = yhat_r - D (c_0 + 2 sigma <D,xi>/|D|^2)
 //   (using yhat = m + v + sigma xi), and a <- r; else a <- a + w.
-// HBM-bound: reads (w+1) rows of x0hat and one trajectory row, writes one row.
+// HBM-bound: reads x0a, the examined rows of x0hat and one trajectory row, writes one row.
 // ----------------------------------------------------------------------------
-// Sum over the 64 lanes of a wavefront, returned in every lane.  Four DPP steps reduce each row of
-// 16 lanes (swap inside pairs, swap pairs, mirror the half row, mirror the row); the four row totals
-// are then read out as scalars.  (A butterfly of ds_bpermute-based shuffles costs an LDS round trip
-// per step.)
-__device__ __forceinline__ float wave_sum(float v) {
-  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
-  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
-  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));  // row_half_mirror
-  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, true));  // row_mirror
-  const int b = __float_as_int(v);
-  return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
-         (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
-}
+constexpr int kAcceptChunk = 8;
 
-__global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const Key* __restrict__ key_p,
-                                                     int32_t* __restrict__ a,
-                                                     const float* __restrict__ c_0,
-                                                     const float* __restrict__ sigma,
-                                                     const float* __restrict__ x0a,
-                                                     const float* __restrict__ x0hat, float* __restrict__ traj,
-                                                     int32_t* __restrict__ accepted, float* __restrict__ stats,
-                                                     int32_t* __restrict__ rounds, int32_t* __restrict__ live) {
-  __shared__ float s_part[64][4][2];  // per slot, per wavefront: partial <D,xi>, |D|^2
-  __shared__ float s_dot[64];
-  __shared__ float s_vv[64];
-  __shared__ int s_bit[64];
-  __shared__ int s_nacc;
+__global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const Key* __restrict__ key_p,
+                                                      int32_t* __restrict__ a,
+                                                      const float* __restrict__ c_0,
+                                                      const float* __restrict__ sigma,
+                                                      const float* __restrict__ x0a,
+                                                      const float* __restrict__ x0hat, float* __restrict__ traj,
+                                                      int32_t* __restrict__ accepted, float* __restrict__ stats,
+                                                      int32_t* __restrict__ rounds, int32_t* __restrict__ live) {
+  __shared__ float s_part[kAcceptChunk][16][2];  // per slot of the chunk, per wavefront: partial <D,xi>, |D|^2
+  __shared__ float s_rej[2];                     // <D,xi>, |D|^2 of the first rejected slot
+  __shared__ int s_first;                        // index inside the chunk of the first rejection, 64 if none
 
   const int c = blockIdx.x;
   const int tid = threadIdx.x;
+  const int nthreads = blockDim.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int nwaves = nthreads >> 6;
   const int ac = a[c];
   if (ac >= K || ac < 0) {
     if (tid == 0 && accepted) accepted[c] = -1;
@@ -324,8 +290,6 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
   const float* g_a = x0a + (int64_t)c * d;
   const float* g_w = x0hat + (int64_t)c * L * d;
 
-  // Phase 1: every thread owns the coordinate blocks tid, tid+256, ... and walks the slots; the loads
-  // of successive slots are independent, so many rows are in flight per wavefront.
   auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {
     // coordinates past d load as zero in both rows, so they add nothing
     const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
@@ -338,92 +302,107 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
     vv = fmaf(dz, dz, vv);
     vv = fmaf(dw, dw, vv);
   };
-  if (nblk <= 256) {  // one block per thread: x0a stays in registers
-    const bool on = tid < nblk;
-    const float4 ga = on ? load4(g_a, tid, d, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int k = 1; k < w; ++k) {
-      float dot = 0.f, vv = 0.f;
-      if (on) {
-        const float4 gk = load4(g_w + (int64_t)k * d, tid, d, vec);
-        const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)tid);
-        slot_terms(ga, gk, xi, dot, vv);
-      }
-      dot = wave_sum(dot);
-      vv = wave_sum(vv);
-      if (lane == 0) {
-        s_part[k][wave][0] = dot;
-        s_part[k][wave][1] = vv;
-      }
-    }
-  } else {
-    for (int k = 1; k < w; ++k) {
-      const float* g_k = g_w + (int64_t)k * d;
-      float dot = 0.f, vv = 0.f;
-#pragma unroll 2
-      for (int blk = tid; blk < nblk; blk += 256) {
-        const float4 ga = load4(g_a, blk, d, vec);
-        const float4 gk = load4(g_k, blk, d, vec);
-        const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)blk);
-        slot_terms(ga, gk, xi, dot, vv);
-      }
-      dot = wave_sum(dot);
-      vv = wave_sum(vv);
-      if (lane == 0) {
-        s_part[k][wave][0] = dot;
-        s_part[k][wave][1] = vv;
-      }
-    }
-  }
-  __syncthreads();
+  const bool single = nblk <= nthreads;  // one coordinate block per thread: x0a stays in registers
+  const float4 ga1 = (single && tid < nblk) ? load4(g_a, tid, d, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
 
-  // Alg. 3 accept test, one thread per slot
-  if (tid < 64) {
-    const int k = tid;
-    float dot = 0.f, vv = 0.f, rho = -INFINITY, logu = 0.f;
-    int bit = (k == 0) ? 1 : 0;
-    if (k >= 1 && k < w) {
-      const int i = ac + k;
-      dot = (s_part[k][0][0] + s_part[k][1][0]) + (s_part[k][2][0] + s_part[k][3][0]);
-      vv = (s_part[k][0][1] + s_part[k][1][1]) + (s_part[k][2][1] + s_part[k][3][1]);
-      const float sg = sigma[i], c0 = c_0[i];
-      if (sg > 0.f) {
-        const float vxi = c0 * dot;
-        const float v2 = c0 * c0 * vv;
-        rho = -(vxi / sg + v2 / (2.0f * sg * sg));
-        logu = logf(uniform1(key, (uint32_t)c, (uint32_t)(i + 1)));
-        bit = (logu <= rho) ? 1 : 0;
+  int n_acc = w;
+  for (int base = 0; base < w; base += kAcceptChunk) {
+    // every thread walks the chunk's slots over its own coordinate blocks; the loads of the slots are
+    // independent, so a whole chunk of rows is in flight per wavefront
+    float dot[kAcceptChunk], vv[kAcceptChunk];
+#pragma unroll
+    for (int kk = 0; kk < kAcceptChunk; ++kk) dot[kk] = vv[kk] = 0.f;
+    if (single) {
+      if (tid < nblk) {
+#pragma unroll
+        for (int kk = 0; kk < kAcceptChunk; ++kk) {
+          const int k = base + kk;
+          if (k >= 1 && k < w) {
+            const float4 gk = load4(g_w + (int64_t)k * d, tid, d, vec);
+            const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)tid);
+            slot_terms(ga1, gk, xi, dot[kk], vv[kk]);
+          }
+        }
+      }
+    } else {
+      for (int blk = tid; blk < nblk; blk += nthreads) {
+        const float4 ga = load4(g_a, blk, d, vec);
+#pragma unroll
+        for (int kk = 0; kk < kAcceptChunk; ++kk) {
+          const int k = base + kk;
+          if (k >= 1 && k < w) {
+            const float4 gk = load4(g_w + (int64_t)k * d, blk, d, vec);
+            const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)blk);
+            slot_terms(ga, gk, xi, dot[kk], vv[kk]);
+          }
+        }
       }
     }
-    s_dot[k] = dot;
-    s_vv[k] = vv;
-    s_bit[k] = bit;
-    if (stats && k < w) {
-      float* sp = stats + ((int64_t)c * L + k) * 4;
-      sp[0] = dot;
-      sp[1] = vv;
-      sp[2] = (k == 0) ? 0.f : logu;
-      sp[3] = (k == 0) ? 0.f : rho;
+#pragma unroll
+    for (int kk = 0; kk < kAcceptChunk; ++kk) {
+      const float ds = wave_sum(dot[kk]), vs = wave_sum(vv[kk]);
+      if (lane == 0) {
+        s_part[kk][wave][0] = ds;
+        s_part[kk][wave][1] = vs;
+      }
     }
-    // Alg. 2: accepted prefix = trailing ones of the ballot (bit 0 is always set)
-    const unsigned long long mask = __ballot(k < w ? bit : 0);
-    const unsigned long long inv = ~mask;
-    const int n_acc = inv ? (__ffsll((long long)inv) - 1) : 64;
-    if (lane == 0) s_nacc = min(n_acc, w);
+    __syncthreads();
+
+    // Alg. 3 accept test, one thread per slot of the chunk
+    if (tid < 64) {
+      const int k = base + lane;
+      const bool valid = lane < kAcceptChunk && k < w;
+      float sd = 0.f, sv = 0.f, rho = -INFINITY, logu = 0.f;
+      int bit = 1;  // slot 0, and the lanes that stand for no slot
+      if (valid && k >= 1) {
+        for (int q = 0; q < nwaves; ++q) {
+          sd += s_part[lane][q][0];
+          sv += s_part[lane][q][1];
+        }
+        const int i = ac + k;
+        const float sg = sigma[i], c0 = c_0[i];
+        bit = 0;
+        if (sg > 0.f) {
+          const float vxi = c0 * sd;
+          const float v2 = c0 * c0 * sv;
+          rho = -(vxi / sg + v2 / (2.0f * sg * sg));
+          logu = logf(uniform1(key, (uint32_t)c, (uint32_t)(i + 1)));
+          bit = (logu <= rho) ? 1 : 0;
+        }
+      }
+      if (stats && valid) {
+        float* sp = stats + ((int64_t)c * L + k) * 4;
+        sp[0] = sd;
+        sp[1] = sv;
+        sp[2] = (k == 0) ? 0.f : logu;
+        sp[3] = (k == 0) ? 0.f : rho;
+      }
+      // Alg. 2: accepted prefix = trailing ones of the ballot
+      const unsigned long long inv = ~__ballot(bit);
+      const int first = inv ? (__ffsll((long long)inv) - 1) : 64;
+      if (lane == first) {
+        s_rej[0] = sd;
+        s_rej[1] = sv;
+      }
+      if (lane == 0) s_first = first;
+    }
+    __syncthreads();
+    if (s_first < 64) {
+      n_acc = base + s_first;
+      break;
+    }
   }
-  __syncthreads();
-  const int n_acc = s_nacc;
 
   int a_next;
   if (n_acc < w) {
     const int k = n_acc;  // slot index of the first rejection (>= 1)
     const int i = ac + k;
     const float sg = sigma[i], c0 = c_0[i];
-    const float dot = s_dot[k], vv = s_vv[k];
-    const float coef = (vv > 0.f) ? (c0 + 2.0f * sg * dot / vv) : 0.f;
+    const float dotr = s_rej[0], vvr = s_rej[1];
+    const float coef = (vvr > 0.f) ? (c0 + 2.0f * sg * dotr / vvr) : 0.f;
     const float* g_k = g_w + (int64_t)k * d;
     float* row = traj + ((int64_t)c * (K + 1) + i + 1) * d;
-    for (int blk = tid; blk < nblk; blk += 256) {
+    for (int blk = tid; blk < nblk; blk += nthreads) {
       const float4 ga = load4(g_a, blk, d, vec);
       const float4 gk = load4(g_k, blk, d, vec);
       float4 y = load4(row, blk, d, vec);
@@ -449,7 +428,9 @@ __global__ __launch_bounds__(256) void accept_kernel(int K, int L, int d, const 
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
   ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
-  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
+  const int nblk = (ctx->d + 3) / 4;
+  const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
                      ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live);
   ASD_HIP(hipGetLastError());
   return ASD_OK;

@@ -191,10 +191,13 @@ def test_round_ragged_shapes():
 # ---------------------------------------------------------------------------
 # whole samples, free-running
 # ---------------------------------------------------------------------------
-def _free_running(cfg, seed, chains_checked, y0=None):
+def _free_running(cfg, seed, chains_checked, y0=None, resident=True):
+    """resident: let asd_sample use the chain-resident kernel where the shape allows (the default);
+    False forces the lock-step round kernels."""
     T, p, model = oracle_setup(cfg)
     tol = H.TOL[cfg["kind"]]
     ctx = runtime.open_ctx(cfg, p, seed=seed)
+    ctx.use_resident(resident)
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
     n_launch = ctx.sample(traj, rounds)
@@ -223,15 +226,57 @@ def _free_running(cfg, seed, chains_checked, y0=None):
     return full
 
 
-def test_sample_config1_all_chains():
+@pytest.mark.parametrize("resident", [False, True])
+def test_sample_config1_all_chains(resident):
     full = 0
     for seed in range(4):
-        full += _free_running(W.CONFIGS[1], seed, range(8))
+        full += _free_running(W.CONFIGS[1], seed, range(8), resident=resident)
     assert full >= 24
 
 
-def test_sample_config2_subset():
-    assert _free_running(W.CONFIGS[2], 0, [0, 17, 63]) >= 1
+@pytest.mark.parametrize("resident", [False, True])
+def test_sample_config2_subset(resident):
+    assert _free_running(W.CONFIGS[2], 0, [0, 17, 63], resident=resident) >= 1
+
+
+@pytest.mark.parametrize("resident", [False, True])
+def test_sample_ragged_shapes(resident):
+    """Whole samples on shapes with d not a multiple of 4, C not a multiple of 4 or 64, windows cut
+    by K, L = 64 and a single chain."""
+    for cfg in (dict(kind="gmm", d=7, C=5, K=37, chains=5, L=6, var=0.25),
+                dict(kind="gmm", d=3, C=130, K=70, chains=3, L=64, var=0.25),
+                dict(kind="gmm", d=20, C=66, K=25, chains=1, L=9, var=0.25),
+                dict(kind="gmm", d=5, C=3, K=1, chains=2, L=4, var=0.25)):
+        full = _free_running(cfg, 6, range(cfg["chains"]), resident=resident)
+        assert full >= 1
+
+
+def test_resident_sampler_agrees_with_round_kernels():
+    """One launch per sample against the lock-step rounds: same counters and formulas, so chains
+    agree to rounding unless a near-tie decision falls differently (rare; those chains differ in
+    their round counts and are only counted)."""
+    for w, seed in ((1, 21), (2, 22)):
+        cfg = W.CONFIGS[w]
+        _, p, _ = oracle_setup(cfg)
+        ctx = runtime.open_ctx(cfg, p, seed=seed)
+        tr, tk = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+        rr = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+        rk = torch.zeros_like(rr)
+        ctx.use_resident(True)
+        n_r = ctx.sample(tr, rr)
+        ctx.use_resident(False)
+        ctx.sample(tk, rk)
+        assert n_r == int(rr.max())
+        same = (rr == rk).cpu().numpy()
+        assert same.mean() >= 0.9, (w, same.mean())
+        a, b = tr.cpu().numpy()[same], tk.cpu().numpy()[same]
+        assert H.rel_err(a, b) <= 1e-4, (w, H.rel_err(a, b))
+        # a second resident sample of the same seed is bit-identical
+        t2 = runtime.alloc_traj(ctx)
+        ctx.use_resident(True)
+        ctx.sample(t2)
+        assert torch.equal(t2, tr)
+        ctx.close()
 
 
 def test_sample_is_deterministic_and_chain_local():
@@ -260,6 +305,7 @@ def test_graph_rounds_equal_plain_launches():
         cfg = W.CONFIGS[w]
         _, p, _ = oracle_setup(cfg)
         ctx = runtime.open_ctx(cfg, p, seed=0)
+        ctx.use_resident(False)                        # the rounds are what is under test here
         tg, te = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
         rg = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
         re_ = torch.zeros_like(rg)
@@ -287,9 +333,15 @@ def test_L1_equals_sequential_sampler_bitwise():
     ctx = runtime.open_ctx(cfg, p, seed=2)
     ta, ts = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    ctx.use_resident(False)
     ctx.sample(ta, rounds)
     ctx.sample_sequential(ts)
     assert torch.equal(ta, ts)
+    assert (rounds.cpu().numpy() == cfg["K"]).all()
+    # the chain-resident kernel walks the same chain (its reductions round differently)
+    ctx.use_resident(True)
+    ctx.sample(ta, rounds)
+    assert H.rel_err(ta.cpu().numpy(), ts.cpu().numpy()) <= 1e-4
     assert (rounds.cpu().numpy() == cfg["K"]).all()
     for c in (0, 7):
         xi, _ = chain_randoms(2, c, cfg["K"], cfg["d"])
