@@ -110,7 +110,9 @@ typedef struct {
 } asd_denoiser;
 
 /* Problem statement of Alg. 1 for a batch: schedule, model, speculation
- * length L (the paper's theta; 1 <= L <= 64), number of chains, seed. */
+ * length L (the paper's theta; L >= 1; windows are cut at K, so L >= K is the
+ * paper's ASD-infinity: every round speculates to the end of the chain),
+ * number of chains, seed.  Scratch memory grows with chains * L. */
 typedef struct {
   asd_schedule sched;
   asd_denoiser den;

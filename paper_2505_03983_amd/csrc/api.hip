@@ -70,7 +70,6 @@ static asd_status validate(const asd_config* cfg) {
     return fail(ASD_EINVAL, "unknown denoiser kind %d", m.kind);
   }
   if (cfg->chains > 65535) return fail(ASD_EUNSUPPORTED, "chains > 65535 (got %d)", cfg->chains);
-  if (cfg->L > 64) return fail(ASD_EUNSUPPORTED, "L > 64 needs a multi-word first-rejection scan (got %d)", cfg->L);
   return ASD_OK;
 }
 

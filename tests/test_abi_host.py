@@ -66,7 +66,6 @@ def _cfg(**over):
 
 @pytest.mark.parametrize("over,status", [
     (dict(L=0), binding.ASD_EINVAL),
-    (dict(L=65), binding.ASD_EUNSUPPORTED),
     (dict(chains=0), binding.ASD_EINVAL),
     (dict(d=0), binding.ASD_EINVAL),
     (dict(C=0), binding.ASD_EINVAL),

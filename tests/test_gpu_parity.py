@@ -251,6 +251,19 @@ def test_sample_ragged_shapes(resident):
         assert full >= 1
 
 
+def test_windows_longer_than_64_and_asd_infinity():
+    """L > 64 (the first-rejection scan walks the window in groups) and L >= K (the paper's
+    ASD-infinity: every round speculates to the end of the chain), as single rounds and whole samples."""
+    big = dict(kind="gmm", d=8, C=6, K=150, chains=4, L=100, var=0.25)
+    _teacher_forced(big, seed=8, chains_checked=range(3))
+    assert _free_running(big, 8, range(4)) >= 1
+    inf = dict(W.CONFIGS[1], L=W.CONFIGS[1]["K"])
+    _teacher_forced(inf, seed=9, chains_checked=range(4))
+    assert _free_running(inf, 9, range(8)) >= 4
+    wide = dict(kind="gmm", d=132, C=40, K=90, chains=3, L=130, var=0.25)      # matrix-core or row-wise GMM path
+    assert _free_running(wide, 10, range(3)) >= 1
+
+
 def test_resident_sampler_agrees_with_round_kernels():
     """One launch per sample against the lock-step rounds: same counters and formulas, so chains
     agree to rounding unless a near-tie decision falls differently (rare; those chains differ in
