@@ -61,6 +61,8 @@ def run_gpu(w, steps, warmup, seed, profile=True):
     torch.cuda.synchronize()
     if profile:
         ctx.profile_enable(True)
+    path = "chain-resident kernel, one launch per sample" if ctx.resident_active() else \
+        "lock-step round kernels" + ("" if profile else ", one captured graph per round")
     launched = []
     rmean, rmax = [], []
     torch.cuda.synchronize()
@@ -79,7 +81,7 @@ def run_gpu(w, steps, warmup, seed, profile=True):
     wall = t1 - t0
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
-               rounds_launched=launched, finite=finite)
+               rounds_launched=launched, finite=finite, path=path)
     if profile:
         P = binding.PROF
         table = {}
@@ -129,7 +131,10 @@ def roofline(res, w=None):
 
 
 def hbm_kernels(res):
-    """Achieved algorithmic HBM bandwidth of the draft and accept kernels."""
+    """Achieved algorithmic HBM bandwidth of the draft and accept kernels (event-timed: a few
+    microseconds of launch overhead are inside each figure; profiles/ has the rocprofv3 durations).
+    The accept kernel's bytes are those of the whole window, (w + 3) rows per chain; it stops reading
+    at the group of eight slots that holds the first rejection, so it touches fewer."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
     d = cfg["d"]
@@ -197,6 +202,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--others", type=int, default=1, help="also time the other four workloads (1 sample each)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--plain", action="store_true",
+                    help="time the sample without the library's per-kernel events (the production path: captured "
+                         "graphs or the chain-resident kernel); the line then has no roofline object -- meant for "
+                         "runs under rocprofv3, which times the kernels itself")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -218,7 +227,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    res = run_gpu(args.workload, args.steps, args.warmup, args.seed)
+    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -240,11 +249,13 @@ def main():
                    "L": cfg["L"], "d": cfg["d"]},
         "rounds_per_sample": {"mean": res["rounds_mean"], "max": res["rounds_max"],
                               "launched": res["rounds_launched"]},
-        "roofline": roofline(res, args.workload),
-        "hbm_kernels": hbm_kernels(res),
-        "kernels": {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
-                        "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()},
+        "path": res["path"],
     }
+    if not args.plain:
+        line["roofline"] = roofline(res, args.workload)
+        line["hbm_kernels"] = hbm_kernels(res)
+        line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
+                               "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, args.seed)
     if args.others:
@@ -256,7 +267,9 @@ def main():
             r = run_gpu(w, 1, 0, args.seed, profile=True)        # per-kernel figures
             rf = roofline(r)
             others["cfg%d" % w] = dict(workload=workload_name(w, r["cfg"]), steps_per_s=r0["steps_per_s"],
-                                       ms_per_sample=r0["ms_per_sample"], rounds_mean=r0["rounds_mean"],
+                                       ms_per_sample=r0["ms_per_sample"], path=r0["path"],
+                                       kernel_figures_from=r["path"] + " (profiled pass)",
+                                       rounds_mean=r0["rounds_mean"],
                                        rounds_max=r0["rounds_max"], roofline_kernel=rf["kernel"],
                                        roofline_frac=rf["frac"], achieved=rf["achieved"], peak=rf["peak"],
                                        unit=rf["unit"], avg_launch_us=rf["avg_launch_us"],

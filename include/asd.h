@@ -180,6 +180,8 @@ ASD_API asd_status asd_use_graphs(asd_ctx* ctx, int32_t on);
  * meaning and asd_last_round_count returns the largest of them).  on = 0 forces the lock-step
  * round kernels; the two paths agree to rounding.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
+/* 1 if the next asd_sample on this context will take that path (shape fits, switch on, profiling off). */
+ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 
 /* Sequential chain with the same random inputs (one model call per step, K
  * launches): the baseline ASD is compared against in the paper's speedups. */

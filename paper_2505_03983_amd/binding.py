@@ -65,6 +65,7 @@ def lib():
             "asd_last_round_count": (i32, [vp]),
             "asd_use_graphs": (i32, [vp, i32]),
             "asd_use_resident": (i32, [vp, i32]),
+            "asd_resident_active": (i32, [vp]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
             "asd_profile_enable": (i32, [vp, i32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
@@ -187,6 +188,9 @@ class Ctx:
 
     def use_resident(self, on=True):
         _check(lib().asd_use_resident(self.h, int(bool(on))))
+
+    def resident_active(self):
+        return bool(lib().asd_resident_active(self.h))
 
     def set_seed(self, seed):
         _check(lib().asd_set_seed(self.h, int(seed)))

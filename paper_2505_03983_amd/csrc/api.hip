@@ -378,6 +378,10 @@ asd_status asd_use_resident(asd_ctx* ctx, int32_t on) {
   return ASD_OK;
 }
 
+int32_t asd_resident_active(const asd_ctx* ctx) {
+  return (ctx && ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx)) ? 1 : 0;
+}
+
 int32_t asd_last_round_count(const asd_ctx* ctx) { return ctx ? ctx->last_rounds : -1; }
 
 asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t n, float* out, void* stream) {

@@ -209,6 +209,8 @@ __device__ __forceinline__ float4 lds4(const float* row, int blk) {
   return *reinterpret_cast<const float4*>(row + 4 * blk);
 }
 
+}  // namespace
+
 template <int RW>
 __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
     int K, int L, int d, int C, const Key* __restrict__ key_p, const float* __restrict__ c_x,
@@ -408,6 +410,8 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
     atomicMax(max_rounds, R);
   }
 }
+
+namespace {
 
 __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
 
