@@ -118,6 +118,8 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
+  ASD_HIP(hipMalloc(&ctx->chain_max, sizeof(unsigned long long)));
+  ASD_HIP(hipMemset(ctx->chain_max, 0, sizeof(unsigned long long)));
   ASD_HIP(hipMalloc(&ctx->key_dev, sizeof(Key)));
   ASD_HIP(hipMemcpy(ctx->key_dev, &ctx->key, sizeof(Key), hipMemcpyHostToDevice));
   ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * kLiveRing, hipHostMallocDefault));
@@ -144,6 +146,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->x0hat);
   (void)hipFree(ctx->a);
   (void)hipFree(ctx->live);
+  (void)hipFree(ctx->chain_max);
   (void)hipFree(ctx->key_dev);
   if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->own_stream);

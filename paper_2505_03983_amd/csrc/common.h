@@ -115,6 +115,8 @@ struct asd_ctx {
   hipStream_t g_stream = nullptr;
   hipStream_t own_stream = nullptr;  // used instead of the legacy default stream, which cannot be captured
   bool graphs_enabled = true;
+  unsigned long long* chain_max = nullptr;  // DEV: (launch id << 32 | largest round count) of the chain-resident sampler
+  uint32_t chain_launches = 0;
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
