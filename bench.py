@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 1 GiB copy in the same run);
 # see profiles/cfg5_gmm_verify_gemm_hbm_traffic.txt for the commands and the raw readings.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    (5, "GMM_LOGITS/verify"): 1024.0 * (2.0 * 1147350.1 + 758070.6),
-    (5, "GMM_COMBINE/verify"): 1024.0 * (2.0 * 3274713.3 + 175748.3),
+    (5, "GMM_LOGITS/verify"): 1024.0 * (2.0 * 1137560.1 + 758386.0),
+    (5, "GMM_COMBINE/verify"): 1024.0 * (2.0 * 3308168.4 + 175748.3),
 }
 
 
