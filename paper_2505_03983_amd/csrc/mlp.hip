@@ -13,8 +13,6 @@
 
 namespace asd {
 
-typedef GemmCfg16<64, 64, 64> MlpTileSkinny;                      // draft call: few rows, stream the weights
-
 // Verify call, K % 64 == 0: the direct-to-LDS pipeline.  A CU moves about 30 bytes per clock from
 // L2 into LDS whatever the kernel does, so the tile is as large as the problem allows: 128 x 256
 // (MFMA-bound fraction of the loop ~60%) when that still gives every CU a tile, else 128 x 128.
@@ -121,12 +119,6 @@ struct InEpi {  // h = acc + b; hb = bf16(h)
   const float* bias;
   int64_t ld, ldb;  // pitch of h (fp32) and of hb (bf16)
   static constexpr bool kLoads = false;
-  __device__ __forceinline__ float load(int, int) const { return 0.f; }
-  __device__ __forceinline__ void store(int m, int n, float acc, float) const {
-    const float v = acc + (bias ? bias[n] : 0.f);
-    h[(int64_t)m * ld + n] = v;
-    hb[(int64_t)m * ldb + n] = f32_to_bf16_rne(v);
-  }
   // four consecutive columns n..n+3 (n % 4 == 0) of row m
   __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
@@ -143,12 +135,6 @@ struct BlockEpi {  // h += SiLU(acc + b); hb_next = bf16(h)
   const float* bias;
   int64_t ld, ldb;
   static constexpr bool kLoads = true;
-  __device__ __forceinline__ float load(int m, int n) const { return h[(int64_t)m * ld + n]; }
-  __device__ __forceinline__ void store(int m, int n, float acc, float prev) const {
-    const float v = prev + silu(acc + (bias ? bias[n] : 0.f));
-    h[(int64_t)m * ld + n] = v;
-    hb_next[(int64_t)m * ldb + n] = f32_to_bf16_rne(v);
-  }
   __device__ __forceinline__ float4 load4(int m, int n) const {
     return *reinterpret_cast<const float4*>(h + (int64_t)m * ld + n);
   }
@@ -168,12 +154,6 @@ struct OutEpi {  // out[out_off[m] + n] = acc + b
   const float* bias;
   float clip;  // 0: none
   static constexpr bool kLoads = false;
-  __device__ __forceinline__ float load(int, int) const { return 0.f; }
-  __device__ __forceinline__ void store(int m, int n, float acc, float) const {
-    float v = acc + (bias ? bias[n] : 0.f);
-    if (clip > 0.f) v = fminf(fmaxf(v, -clip), clip);
-    out_base[out_off[m] + n] = v;
-  }
   __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
     const float4 b = load_bias4(bias, n);
