@@ -174,6 +174,16 @@ ASD_API asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_
  * plain kernel launches; the results are identical.  Default: on. */
 ASD_API asd_status asd_use_graphs(asd_ctx* ctx, int32_t on);
 
+/* Window control for asd_sample (an extension; Alg. 1 takes the speculation length as a fixed input).
+ * on = 1: each chain chooses the window of its next round from its own past, never longer than L: three
+ * quarters of a running mean of its accepted run length (integers: state <- state - state/4 + obs, obs =
+ * accepted slots, or twice the window when all of it was accepted; window = clamp(3 state / 16, min(4, L),
+ * L); state starts at 4 L).  A window that depends on the chain's past only leaves the law of every
+ * step intact (the correctness proof conditions on the past), so samples stay exact; the model calls a
+ * round spends on slots behind the first rejection shrink.  Default: off (every window is L).  The stage
+ * calls always use L. */
+ASD_API asd_status asd_use_adaptive_window(asd_ctx* ctx, int32_t on);
+
 /* For a Gaussian-mixture denoiser small enough to sit in one CU's LDS (with the window of a chain),
  * asd_sample runs Alg. 1 for each chain inside one workgroup: one launch per sample instead of
  * several per round (chains do not interact, so no step of the method changes; rounds[c] keeps its

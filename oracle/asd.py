@@ -120,18 +120,45 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
                 y_new=y_new)
 
 
-def asd_sample(y0, L, A, Bc, sigma, model, xi, u, eps=1e-4, keep_rounds=True):
+def window_init(L):
+    """State of the window controller before the first round (see window_next)."""
+    return 4 * L
+
+
+def window_of(state, L):
+    """Window length the controller asks for: three quarters of the running mean of the accepted run
+    length (state / 4), within [min(4, L), L]."""
+    return max(min(4, L), min(L, (3 * state) >> 4))
+
+
+def window_next(state, w_used, n_acc):
+    """Window controller (an extension: Alg. 1 takes the speculation length as a fixed input).
+
+    The length of the next window may depend on the past of the chain only, which keeps every step's law
+    intact (the correctness proof conditions on the past; the proposal of a round is any function of it).
+    The controller tracks a running mean of the accepted run length n_acc in integers:
+    state <- state - floor(state / 4) + obs,  obs = n_acc, or 2 * w_used when the whole window was
+    accepted (the run was cut short by the window, so the observation is censored)."""
+    obs = 2 * w_used if n_acc == w_used else n_acc
+    return state - (state >> 2) + obs
+
+
+def asd_sample(y0, L, A, Bc, sigma, model, xi, u, eps=1e-4, keep_rounds=True, adaptive=False):
     """Alg. 1.  Returns (y [K+1, d], R, rounds) with rounds the list of
-    per-iteration records of `asd_round` (empty if keep_rounds is False)."""
+    per-iteration records of `asd_round` (empty if keep_rounds is False).
+    adaptive: the window of each round comes from the controller above (never longer than L)."""
     K = len(A)
     y = np.empty((K + 1, len(y0)))
     y[0] = y0
     a = 0
     R = 0
     rounds = []
+    state = window_init(L)
     while a < K:
-        rec = asd_round(y[a], a, L, A, Bc, sigma, model, xi, u, eps)
+        win = window_of(state, L) if adaptive else L
+        rec = asd_round(y[a], a, win, A, Bc, sigma, model, xi, u, eps)
         y[a + 1: rec["a_next"] + 1] = rec["y_new"]
+        state = window_next(state, rec["b"] - a, rec["j"] - a)
         a = rec["a_next"]
         R += 1
         if keep_rounds:

@@ -65,6 +65,7 @@ def lib():
             "asd_last_round_count": (i32, [vp]),
             "asd_use_graphs": (i32, [vp, i32]),
             "asd_use_resident": (i32, [vp, i32]),
+            "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
             "asd_profile_enable": (i32, [vp, i32]),
@@ -185,6 +186,9 @@ class Ctx:
 
     def use_graphs(self, on=True):
         _check(lib().asd_use_graphs(self.h, int(bool(on))))
+
+    def use_adaptive_window(self, on=True):
+        _check(lib().asd_use_adaptive_window(self.h, int(bool(on))))
 
     def use_resident(self, on=True):
         _check(lib().asd_use_resident(self.h, int(bool(on))))

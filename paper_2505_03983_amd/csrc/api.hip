@@ -118,6 +118,7 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
+  ASD_HIP(hipMalloc(&ctx->win, sizeof(int32_t) * 2 * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->chain_max, sizeof(unsigned long long)));
   ASD_HIP(hipMemset(ctx->chain_max, 0, sizeof(unsigned long long)));
   ASD_HIP(hipMalloc(&ctx->key_dev, sizeof(Key)));
@@ -147,6 +148,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->a);
   (void)hipFree(ctx->live);
   (void)hipFree(ctx->chain_max);
+  (void)hipFree(ctx->win);
   (void)hipFree(ctx->key_dev);
   if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->own_stream);
@@ -278,7 +280,9 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipS
 // Every launch argument of a round is the same in every round: the round index and the live ring are
 // advanced on the device, the seed is read from device memory.
 static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
-  if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st) return ASD_OK;
+  if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st &&
+      ctx->g_win == ctx->cur_win)
+    return ASD_OK;
   hipGraph_t graph = nullptr;
   ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
   asd_status s = enqueue_round(ctx, traj, rounds, st);
@@ -298,6 +302,7 @@ static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds,
   ctx->g_traj = traj;
   ctx->g_rounds = rounds;
   ctx->g_stream = st;
+  ctx->g_win = ctx->cur_win;
   return ASD_OK;
 }
 
@@ -312,6 +317,11 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   if (ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx))
     return gmm_chain_sample(ctx, y0, traj, rounds, st);
   if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
+  struct WinScope {  // the round kernels see the per-chain windows only while this sample runs
+    asd_ctx* c;
+    explicit WinScope(asd_ctx* x) : c(x) { c->cur_win = c->adaptive ? c->win : nullptr; }
+    ~WinScope() { c->cur_win = nullptr; }
+  } win_scope(ctx);
   // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
   // round it has just queued; a finished batch then runs `lag` empty rounds, which cost next to nothing
   // (every kernel exits at once on finished chains and the model calls see zero rows).
@@ -372,6 +382,12 @@ asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, voi
 asd_status asd_use_graphs(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   ctx->graphs_enabled = on != 0;
+  return ASD_OK;
+}
+
+asd_status asd_use_adaptive_window(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ctx->adaptive = on != 0;
   return ASD_OK;
 }
 

@@ -117,6 +117,10 @@ struct asd_ctx {
   bool graphs_enabled = true;
   unsigned long long* chain_max = nullptr;  // DEV: (launch id << 32 | largest round count) of the chain-resident sampler
   uint32_t chain_launches = 0;
+  int32_t* win = nullptr;      // DEV [2 B]: window of each chain, then the controller's state (asd_sample, adaptive)
+  int32_t* cur_win = nullptr;  // what the round kernels are given: win while an adaptive sample runs, else NULL (= L)
+  bool adaptive = false;
+  const void* g_win = nullptr; // cur_win the round graph was captured with
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
@@ -157,7 +161,7 @@ void gmm_destroy(asd_ctx* ctx);
 asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
 // chain-resident sampler (gmm_chain.hip): all of Alg. 1 for a chain in one workgroup, one launch per sample
 bool gmm_chain_supported(const asd_ctx* ctx);
-asd_status gmm_chain_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, hipStream_t st);
+asd_status gmm_chain_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, hipStream_t st);  // honours ctx->adaptive
 
 asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den);
 void mlp_destroy(asd_ctx* ctx);

@@ -57,4 +57,16 @@ __device__ __forceinline__ float wave_max(float v) {
                fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
 }
 
+// ----------------------------------------------------------------------------
+// Window controller (an extension: Alg. 1 takes the speculation length as a fixed input).  The next
+// window may depend on the chain's past only, which leaves every step's law intact.  It follows a
+// running mean of the accepted run length in integers: state <- state - state/4 + obs, obs = n_acc, or
+// 2 w when the whole window of w was accepted (the run was cut by the window); the window asked for is
+// 3/4 of that mean (state / 4), within [min(4, L), L].  win[c] = window, win[B + c] = state.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ int window_of(int state, int L) { return max(min(4, L), min(L, (3 * state) >> 4)); }
+__device__ __forceinline__ int window_next(int state, int w_used, int n_acc) {
+  return state - (state >> 2) + (n_acc == w_used ? 2 * w_used : n_acc);
+}
+
 }  // namespace asd

@@ -102,15 +102,19 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
                                                                          int N, int K,
                                                                          const uint16_t* __restrict__ A, int64_t lda,
                                                                          const uint16_t* __restrict__ W, int64_t ldw,
-                                                                         Epi epi, float* __restrict__ part) {
+                                                                         Epi epi, float* __restrict__ part, int m_lo,
+                                                                         int m_hi) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, STAGES = Cfg::STAGES, MI = Cfg::MI, NJ = Cfg::NJ, NW = Cfg::NW;
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
   constexpr int A_LOADS = Cfg::A_LOADS, W_LOADS = Cfg::W_LOADS, LPS = Cfg::LPS, STAGE_BYTES = Cfg::STAGE_BYTES;
   extern __shared__ __attribute__((aligned(16))) uint8_t ldsb[];
 
-  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  const int M_all = M_dev ? *M_dev : M_max;   // the gate below looks at the true row count
+  const int M = min(M_all, M_max);
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  if (m0 >= M) return;
+  // (m_lo, m_hi]: the row counts this launch serves -- the caller may queue several tile shapes for one
+  // product and let the row count, known on the device only, pick the one that runs
+  if (m0 >= M || M_all <= m_lo || M_all > m_hi) return;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -296,11 +300,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
 // One thread per four columns of a row: partials added in z order, then the epilogue.
 template <class Epi>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const int* __restrict__ M_dev, int M_max, int N, int splits,
-                                                            const float* __restrict__ part, Epi epi) {
-  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+                                                            const float* __restrict__ part, Epi epi, int m_lo,
+                                                            int m_hi) {
+  const int M_all = M_dev ? *M_dev : M_max;
+  const int M = min(M_all, M_max);
   const int m = blockIdx.y;
   const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
-  if (m >= M || n >= N) return;
+  if (m >= M || n >= N || M_all <= m_lo || M_all > m_hi) return;
   const float4 prev = Epi::kLoads ? epi.load4(m, n) : make_float4(0.f, 0.f, 0.f, 0.f);
   float4 v = *reinterpret_cast<const float4*>(part + (int64_t)m * N + n);
   for (int z = 1; z < splits; ++z) {
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const int* __restric
 template <class Cfg, int CALL, class Epi>
 inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K, const uint16_t* A, int64_t lda,
                                            const uint16_t* W, int64_t ldw, Epi epi, hipStream_t st, int splits = 1,
-                                           float* part = nullptr) {
+                                           float* part = nullptr, int m_lo = -1, int m_hi = 0x7fffffff) {
   if (splits < 1 || (K / 64) % splits != 0 || (splits > 1 && !part)) return hipErrorInvalidValue;
   dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)splits);
   auto kern = gemm_bf16_nt_pipe_kernel<Cfg, Epi, CALL>;
@@ -325,10 +331,11 @@ inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, W, ldw, epi, part);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, W, ldw, epi, part,
+                     m_lo, m_hi);
   if (splits > 1)
     hipLaunchKernelGGL(splitk_finish_kernel<Epi>, dim3((unsigned)((N / 4 + 255) / 256), (unsigned)M), dim3(256), 0, st,
-                       M_dev, M, N, splits, part, epi);
+                       M_dev, M, N, splits, part, epi, m_lo, m_hi);
   return hipGetLastError();
 }
 

@@ -270,7 +270,8 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
     const float* __restrict__ c_0, const float* __restrict__ sigma, const int32_t* __restrict__ tau,
     const float4* __restrict__ coef_tau, const float* __restrict__ means, const float* __restrict__ musq,
     const float* __restrict__ log_w, const float* __restrict__ y0, float* __restrict__ traj,
-    int32_t* __restrict__ rounds, unsigned long long* __restrict__ max_rounds, uint32_t launch_id) {
+    int32_t* __restrict__ rounds, unsigned long long* __restrict__ max_rounds, uint32_t launch_id,
+    int adaptive) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   __shared__ float s_logu[64], s_dot[64], s_vv[64], s_sc[64];
   __shared__ int s_bit[64];
@@ -322,9 +323,10 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
   lds_barrier();
 
   int a = 0, R = 0;
+  int wstate = 4 * L;  // window controller (device_util.h); without it every window is L
   ASD_T_DECL
   while (a < K) {
-    const int w = min(L, K - a);
+    const int w = min(adaptive ? window_of(wstate, L) : L, K - a);
     // A. the window's noise, then x0a
     for (int t = tid; t < w * nblk; t += nthreads) {
       const int k = t / nblk, blk = t - k * nblk;
@@ -444,6 +446,7 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
     // every thread moves the blocks it wrote (or, on full acceptance, rows nobody writes any more)
     for (int blk = tid; blk < nblk; blk += nthreads)
       *reinterpret_cast<float4*>(yh + 4 * blk) = lds4(yh + (size_t)src * dp, blk);
+    wstate = window_next(wstate, w, n_acc);
     a = a_next;
     ++R;
     lds_barrier();
@@ -492,7 +495,7 @@ asd_status gmm_chain_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t*
   }
   hipLaunchKernelGGL(gmm_chain_sample_kernel, dim3(ctx->B), dim3(64 * nw), lds_bytes, st, ctx->K, ctx->L, ctx->d,
                      g->C, ctx->key_dev, ctx->c_x, ctx->c_0, ctx->sigma, ctx->tau, g->coef_tau, g->means, g->musq,
-                     g->log_w, y0, traj, rounds, ctx->chain_max, ++ctx->chain_launches);
+                     g->log_w, y0, traj, rounds, ctx->chain_max, ++ctx->chain_launches, ctx->adaptive ? 1 : 0);
   ASD_HIP(hipGetLastError());
   ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->chain_max, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
   ASD_HIP(hipStreamSynchronize(st));

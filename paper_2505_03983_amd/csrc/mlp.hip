@@ -27,7 +27,11 @@ constexpr int kMaxSplits = 8;
 struct SplitScratch {
   float* part = nullptr;   // [kMaxSplits][rows][max N] fp32 partial tiles
   int rows = 0;            // rows the scratch was sized for (one per chain)
+  bool small_verify = false;  // verify calls may be far below their row bound (windows from the controller)
 };
+// Verify calls of at most this many rows go to the 64 x 64 tiles of the draft call: a few row tiles
+// against a whole weight matrix is a weight stream again, not a 128 x 256-tile problem.
+constexpr int kSmallVerifyRows = 256;
 
 // Both operands have row pitch ld = padded(K) (see pitch_of).
 template <class Epi>
@@ -46,8 +50,17 @@ static hipError_t mlp_gemm(int call, const int* n_dev, int n, int N, int K, int6
   }
   {
     const int64_t wide_tiles = ceil_div(n, 128) * ceil_div(N, 256);
-    return wide_tiles >= 192 ? launch_gemm_bf16_nt_pipe<MlpPipeWide, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st)
-                             : launch_gemm_bf16_nt_pipe<MlpPipeSquare, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st);
+    int m_lo = -1;
+    if (sc.small_verify && n > kSmallVerifyRows && (int64_t)N * Kp * 2 >= (8 << 20)) {
+      // both shapes are queued; the row count in device memory decides which one does the work
+      hipError_t e0 = launch_gemm_bf16_nt_pipe<MlpPipeSkinny, 1>(n_dev, kSmallVerifyRows, N, Kp, A, ld, Wt, ld, e, st, 1,
+                                                                 nullptr, -1, kSmallVerifyRows);
+      if (e0 != hipSuccess) return e0;
+      m_lo = kSmallVerifyRows;
+    }
+    return wide_tiles >= 192 ? launch_gemm_bf16_nt_pipe<MlpPipeWide, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st, 1, nullptr, m_lo)
+                             : launch_gemm_bf16_nt_pipe<MlpPipeSquare, 1>(n_dev, n, N, Kp, A, ld, Wt, ld, e, st, 1, nullptr,
+                                                                          m_lo);
   }
 }
 
@@ -237,6 +250,7 @@ void mlp_destroy(asd_ctx* ctx) {
 asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   MlpState* s = ctx->mlp;
   const int n = rows.n, d = ctx->d, W = s->width;
+  s->split.small_verify = ctx->cur_win != nullptr;
   {
     ProfScope ps(ctx, ASD_PROF_MLP_PACK, rows.call, st);
     const int groups = s->in_dim / 8;

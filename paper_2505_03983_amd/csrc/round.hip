@@ -12,7 +12,8 @@ namespace asd {
 // ----------------------------------------------------------------------------
 __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ key_p, const float* __restrict__ y0,
                                   float* __restrict__ traj, int32_t* __restrict__ a,
-                                  int32_t* __restrict__ rounds, int32_t* __restrict__ round_idx) {
+                                  int32_t* __restrict__ rounds, int32_t* __restrict__ round_idx, int L,
+                                  int32_t* __restrict__ win) {
   const int c = blockIdx.x;
   const Key key = *key_p;
   if (c == 0 && threadIdx.x == 0 && round_idx) *round_idx = 0;
@@ -26,13 +27,17 @@ __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ k
   if (threadIdx.x == 0) {
     a[c] = 0;
     if (rounds) rounds[c] = 0;
+    if (win) {
+      win[B + c] = 4 * L;
+      win[c] = window_of(4 * L, L);
+    }
   }
 }
 
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds,
                              hipStream_t st) {
   hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key_dev, y0,
-                     traj, a, rounds, ctx->live);
+                     traj, a, rounds, ctx->live, ctx->L, ctx->cur_win);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -78,7 +83,8 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
                                                          int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows,
                                                          int32_t* __restrict__ ring,
-                                                         int64_t* __restrict__ row_counts) {
+                                                         int64_t* __restrict__ row_counts,
+                                                         const int32_t* __restrict__ win) {
   __shared__ int s_wave[16];
   __shared__ int s_total;
   __shared__ int s_off[1024], s_cnt[1024], s_ac[1024];
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     int ac = K, cnt = 0;
     if (c < B) {
       ac = min(max(a[c], 0), K);
-      if (ac < K) cnt = (MODE == 0) ? 1 : min(L, K - ac) - 1;
+      if (ac < K) cnt = (MODE == 0) ? 1 : min(win ? win[c] : L, K - ac) - 1;
     }
     const int off = base + block_exclusive_scan(cnt, s_wave, &s_total);
     if (MODE == 0) {
@@ -134,7 +140,7 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, ring,
-                     ctx->prof.on ? ctx->row_counts : nullptr);
+                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -144,7 +150,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
-                     ctx->prof.on ? ctx->row_counts : nullptr);
+                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -162,7 +168,8 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
                                                     const float* __restrict__ c_x,
                                                     const float* __restrict__ c_0,
                                                     const float* __restrict__ sigma,
-                                                    const float* __restrict__ x0a, float* __restrict__ traj) {
+                                                    const float* __restrict__ x0a, float* __restrict__ traj,
+                                                    const int32_t* __restrict__ win) {
   const int c = blockIdx.y;
   const int blk = blockIdx.x * blockDim.x + threadIdx.x;
   const int nblk = (d + 3) >> 2;
@@ -170,7 +177,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
   if (blk >= nblk || ac >= K || ac < 0) return;
   const Key key = *key_p;
   const bool vec = (d & 3) == 0;
-  const int w = min(Lwin, K - ac);
+  const int w = min(win ? win[c] : Lwin, K - ac);
   float* row = traj + ((int64_t)c * (K + 1) + ac) * d;
   float4 y = load4(row, blk, d, vec);
   const float4 g = load4(x0a + (int64_t)c * d, blk, d, vec);
@@ -193,7 +200,7 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   ProfScope ps(ctx, ASD_PROF_DRAFT, 0, st);
   hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj);
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -217,7 +224,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj);
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -267,7 +274,8 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
                                                       const float* __restrict__ x0a,
                                                       const float* __restrict__ x0hat, float* __restrict__ traj,
                                                       int32_t* __restrict__ accepted, float* __restrict__ stats,
-                                                      int32_t* __restrict__ rounds, int32_t* __restrict__ live) {
+                                                      int32_t* __restrict__ rounds, int32_t* __restrict__ live,
+                                                      int32_t* __restrict__ win) {
   __shared__ float s_part[kAcceptChunk][16][2];  // per slot of the chunk, per wavefront: partial <D,xi>, |D|^2
   __shared__ float s_rej[2];                     // <D,xi>, |D|^2 of the first rejected slot
   __shared__ int s_first;                        // index inside the chunk of the first rejection, 64 if none
@@ -284,7 +292,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
     return;
   }
   const Key key = *key_p;
-  const int w = min(L, K - ac);
+  const int w = min(win ? win[c] : L, K - ac);
   const int nblk = (d + 3) >> 2;
   const bool vec = (d & 3) == 0;
   const float* g_a = x0a + (int64_t)c * d;
@@ -420,6 +428,12 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
     a[c] = a_next;
     if (accepted) accepted[c] = n_acc;
     if (rounds) rounds[c] += 1;
+    if (win) {
+      const int B = gridDim.x;
+      const int st = window_next(win[B + c], w, n_acc);
+      win[B + c] = st;
+      win[c] = window_of(st, L);
+    }
     // the plan kernel of this round already advanced the round index
     if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
   }
@@ -431,7 +445,7 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
   hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live);
+                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }

@@ -35,11 +35,11 @@ def unclipped_scale(cfg, T, p, rec):
     return float(np.abs(raw(list(range(a + 1, b)), rows)).max())
 
 
-def oracle_chain(cfg, T, model, seed, chain, eps, L=None, K=None):
+def oracle_chain(cfg, T, model, seed, chain, eps, L=None, K=None, adaptive=False):
     K = K or cfg["K"]
     xi, u = chain_randoms(seed, chain, K, cfg["d"])
     y, R, rounds = oasd.asd_sample(xi[0], L or cfg["L"], T["c_x"][:K], T["c_0"][:K], T["sigma"][:K], model, xi, u,
-                                   eps=eps)
+                                   eps=eps, adaptive=adaptive)
     return y, R, rounds, xi, u
 
 

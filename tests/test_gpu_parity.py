@@ -191,13 +191,14 @@ def test_round_ragged_shapes():
 # ---------------------------------------------------------------------------
 # whole samples, free-running
 # ---------------------------------------------------------------------------
-def _free_running(cfg, seed, chains_checked, y0=None, resident=True):
+def _free_running(cfg, seed, chains_checked, y0=None, resident=True, adaptive=False):
     """resident: let asd_sample use the chain-resident kernel where the shape allows (the default);
-    False forces the lock-step round kernels."""
+    False forces the lock-step round kernels.  adaptive: windows from the controller, on both sides."""
     T, p, model = oracle_setup(cfg)
     tol = H.TOL[cfg["kind"]]
     ctx = runtime.open_ctx(cfg, p, seed=seed)
     ctx.use_resident(resident)
+    ctx.use_adaptive_window(adaptive)
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
     n_launch = ctx.sample(traj, rounds)
@@ -205,7 +206,7 @@ def _free_running(cfg, seed, chains_checked, y0=None, resident=True):
     assert n_launch == rd.max()
     full = 0
     for c in chains_checked:
-        y, R, recs, xi, u = H.oracle_chain(cfg, T, model, seed, c, eps=tol)
+        y, R, recs, xi, u = H.oracle_chain(cfg, T, model, seed, c, eps=tol, adaptive=adaptive)
         # first step whose decision is flagged as a near-tie inside an examined prefix
         stop = None
         for rec in recs:
@@ -262,6 +263,58 @@ def test_windows_longer_than_64_and_asd_infinity():
     assert _free_running(inf, 9, range(8)) >= 4
     wide = dict(kind="gmm", d=132, C=40, K=90, chains=3, L=130, var=0.25)      # matrix-core or row-wise GMM path
     assert _free_running(wide, 10, range(3)) >= 1
+
+
+@pytest.mark.parametrize("resident", [False, True])
+def test_adaptive_windows_match_the_oracle(resident):
+    """Windows chosen by the controller from each chain's past: same integer rule on both sides, so
+    rounds, windows and trajectories must agree with the oracle as for fixed windows."""
+    full = 0
+    for seed in range(2):
+        full += _free_running(W.CONFIGS[1], 30 + seed, range(8), resident=resident, adaptive=True)
+    assert full >= 12
+    assert _free_running(W.CONFIGS[2], 32, [0, 5, 63], resident=resident, adaptive=True) >= 1
+    ragged = dict(kind="gmm", d=7, C=5, K=61, chains=5, L=40, var=0.25)
+    assert _free_running(ragged, 33, range(5), resident=resident, adaptive=True) >= 1
+    if not resident:
+        small_mlp = dict(kind="mlp", d=16, E=8, width=64, n_blocks=2, K=30, chains=6, L=12)
+        _free_running(small_mlp, 34, range(6), resident=False, adaptive=True)
+        # weight matrices large enough (8 MB) that verify calls far below their row bound are routed,
+        # on the device, to the small-row tile shape: windows of 4 give 120 rows, windows of 9 give 320
+        wide_mlp = dict(kind="mlp", d=64, E=64, width=2048, n_blocks=1, K=14, chains=40, L=12)
+        _free_running(wide_mlp, 35, [0, 7, 39], resident=False, adaptive=True)
+        _free_running(wide_mlp, 35, [1, 38], resident=False, adaptive=False)
+
+
+def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
+    """On a workload whose windows are mostly rejected early the controller must cut the verify rows;
+    switching it off again restores the fixed-window sample bit for bit (the round graph is rebuilt)."""
+    cfg = W.CONFIGS[2]
+    _, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=5)
+    ctx.use_resident(False)
+    t0, t1, t2 = (runtime.alloc_traj(ctx) for _ in range(3))
+    r0 = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    r1, r2 = torch.zeros_like(r0), torch.zeros_like(r0)
+    ctx.sample(t0, r0)
+    ctx.use_adaptive_window(True)
+    ctx.sample(t1, r1)
+    ctx.use_adaptive_window(False)
+    ctx.sample(t2, r2)
+    assert torch.equal(t0, t2) and torch.equal(r0, r2)
+    assert torch.isfinite(t1).all()
+    ctx.profile_enable(True)
+    ctx.sample(t2, r2)
+    fixed_rows = ctx.profile_rows()[1]
+    ctx.profile_enable(False)
+    ctx.use_adaptive_window(True)
+    ctx.profile_enable(True)
+    ctx.sample(t1, r1)
+    adaptive_rows = ctx.profile_rows()[1]
+    ctx.profile_enable(False)
+    _log("verify rows per sample: fixed", fixed_rows, "adaptive", adaptive_rows, "rounds max", int(r2.max()), int(r1.max()))
+    assert adaptive_rows < fixed_rows
+    ctx.close()
 
 
 def test_resident_sampler_agrees_with_round_kernels():

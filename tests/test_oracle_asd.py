@@ -3,6 +3,7 @@ exactness in law (correctness theorem), the structure of a round (Lemma of the
 correctness proof, worst-case round lemma), special cases that reduce to the
 sequential chain, and the round-complexity theorem."""
 import numpy as np
+import pytest
 from scipy import special, stats
 
 import asd_workloads as W
@@ -87,9 +88,30 @@ def test_worst_case_round_lemma():
         assert R <= 1 + cfg["K"] / cfg["L"] + bad
 
 
-def test_exact_in_law_gaussian_data_closed_form():
+def test_window_controller_is_bounded_and_follows_the_run_length():
+    """The integer controller: window within [min(4, L), L]; a string of fully accepted windows drives
+    it to L, a string of early rejections to the floor; censored observations count double."""
+    for L in (1, 3, 8, 64, 200):
+        st = asd.window_init(L)
+        assert asd.window_of(st, L) == max(min(4, L), (3 * L) // 4)
+        for _ in range(40):                                  # everything accepted
+            w = asd.window_of(st, L)
+            assert min(4, L) <= w <= L
+            st = asd.window_next(st, w, w)
+        assert asd.window_of(st, L) == L
+        for _ in range(40):                                  # rejected right after the forced slot
+            w = asd.window_of(st, L)
+            st = asd.window_next(st, w, 1)
+        assert asd.window_of(st, L) == min(4, L)
+    assert asd.window_next(40, 10, 10) == 40 - 10 + 20       # censored: 2 w
+    assert asd.window_next(40, 10, 7) == 40 - 10 + 7
+
+
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_exact_in_law_gaussian_data_closed_form(adaptive):
     """Single Gaussian data law: the chain is linear-Gaussian, so Law(y_i) is
-    N(mean_i, var_i) by a scalar recursion.  ASD samples must follow it."""
+    N(mean_i, var_i) by a scalar recursion.  ASD samples must follow it -- with fixed windows and
+    with windows chosen from the chain's past by the controller."""
     K, d, L, n = 24, 1, 6, 3000
     T = schedule.ddpm_tables(K)
     mu, s2 = 1.5, 0.25
@@ -106,7 +128,7 @@ def test_exact_in_law_gaussian_data_closed_form():
     rej = 0
     for c in range(n):
         xi, u = chain_randoms(9, c, K, d)
-        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u, adaptive=adaptive)
         Y[c] = y[:, 0]
         rej += sum(1 for r in rounds if r["r"] >= 0 and r["r"] < K)
     assert rej > n / 4                                      # the rejection branch is exercised
