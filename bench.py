@@ -45,7 +45,7 @@ def workload_name(w, cfg):
         w, cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], cfg["chains"], cfg["L"])
 
 
-def run_gpu(w, steps, warmup, seed, profile=True):
+def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False):
     import torch
     import asd_workloads as W
     from paper_2505_03983_amd import binding, runtime
@@ -53,6 +53,7 @@ def run_gpu(w, steps, warmup, seed, profile=True):
     cfg = W.CONFIGS[w]
     params = W.make_params(cfg, model_seed=1)
     ctx = runtime.open_ctx(cfg, params, seed=seed)
+    ctx.use_adaptive_window(adaptive)
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device="cuda:0")
     for i in range(warmup):
@@ -258,6 +259,11 @@ def main():
                                "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, args.seed)
+    # The same workload with the window controller on (windows <= L chosen per chain from its past:
+    # an extension of Alg. 1, exact in law; the headline `value` above keeps the configured fixed L).
+    ra = run_gpu(args.workload, max(1, min(args.steps, 2)), 1, args.seed, profile=False, adaptive=True)
+    line["window_control"] = dict(steps_per_s=ra["steps_per_s"], ms_per_sample=ra["ms_per_sample"],
+                                  rounds_mean=ra["rounds_mean"], rounds_max=ra["rounds_max"], path=ra["path"])
     if args.others:
         others = {}
         for w in sorted(W.CONFIGS):
@@ -265,6 +271,7 @@ def main():
                 continue
             r0 = run_gpu(w, 2, 1, args.seed, profile=False)      # throughput without the event overhead
             r = run_gpu(w, 1, 0, args.seed, profile=True)        # per-kernel figures
+            ra = run_gpu(w, 2, 1, args.seed, profile=False, adaptive=True)
             rf = roofline(r)
             others["cfg%d" % w] = dict(workload=workload_name(w, r["cfg"]), steps_per_s=r0["steps_per_s"],
                                        ms_per_sample=r0["ms_per_sample"], path=r0["path"],
@@ -273,7 +280,11 @@ def main():
                                        rounds_max=r0["rounds_max"], roofline_kernel=rf["kernel"],
                                        roofline_frac=rf["frac"], achieved=rf["achieved"], peak=rf["peak"],
                                        unit=rf["unit"], avg_launch_us=rf["avg_launch_us"],
-                                       hbm_kernels=hbm_kernels(r))
+                                       hbm_kernels=hbm_kernels(r),
+                                       window_control=dict(steps_per_s=ra["steps_per_s"],
+                                                           ms_per_sample=ra["ms_per_sample"],
+                                                           rounds_mean=ra["rounds_mean"],
+                                                           rounds_max=ra["rounds_max"]))
         line["other_workloads"] = others
     print(json.dumps(line))
 
