@@ -145,45 +145,58 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
   const int a_lane = (fr.wm * (BM / 2) + fr.l32) * LDSS + fr.half * 4;
   const int b_lane = (fr.wn * (BN / 2) + fr.l32) * LDSS + fr.half * 4;
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
-    const float* Ac = As + cur * BM * LDSS + a_lane;
-    const float* Bc = Bs + cur * BN * LDSS + b_lane;
-    float4 af[2][MI], bf[2][NJ];
+  static_assert(KS % 2 == 0, "the first fragments of a slab go to fragment buffer 0");
+  float4 af[2][MI], bf[2][NJ];
+  auto read_frags = [&](const float* Ac, const float* Bc, int ks, int buf) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS);
+    for (int i = 0; i < MI; ++i) af[buf][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS + ks * 8);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) bf[0][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS);
-    // While it has fragments to feed, a wavefront outranks its SIMD neighbours that are between slabs
-    // (loading, storing to LDS, at the barrier): the matrix pipe is the resource to keep busy.
-    __builtin_amdgcn_s_setprio(2);
+    for (int j = 0; j < NJ; ++j) bf[buf][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS + ks * 8);
+  };
+  auto mma = [&](int c, int t) {  // the MI x NJ MFMAs that consume element t of the fragments in buffer c
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int c = ks & 1;
-      if (ks + 1 < KS) {
+    for (int i = 0; i < MI; ++i) {
+      const float av = t == 0 ? af[c][i].x : t == 1 ? af[c][i].y : t == 2 ? af[c][i].z : af[c][i].w;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) af[c ^ 1][i] = *reinterpret_cast<const float4*>(Ac + i * 32 * LDSS + (ks + 1) * 8);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) bf[c ^ 1][j] = *reinterpret_cast<const float4*>(Bc + j * 32 * LDSS + (ks + 1) * 8);
-      }
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-          const float av = t == 0 ? af[c][i].x : t == 1 ? af[c][i].y : t == 2 ? af[c][i].z : af[c][i].w;
-#pragma unroll
-          for (int j = 0; j < NJ; ++j) {
-            const float bv = t == 0 ? bf[c][j].x : t == 1 ? bf[c][j].y : t == 2 ? bf[c][j].z : bf[c][j].w;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-          }
-        }
+      for (int j = 0; j < NJ; ++j) {
+        const float bv = t == 0 ? bf[c][j].x : t == 1 ? bf[c][j].y : t == 2 ? bf[c][j].z : bf[c][j].w;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
       }
     }
+  };
+  read_frags(As + a_lane, Bs + b_lane, 0, 0);
+
+  // Per slab: the global loads of the next slab are issued first; its LDS buffer is free for the whole
+  // slab (everybody left it at the previous barrier), so the store into it, the barrier and the first
+  // fragment reads of the next slab all sit in the middle of the last group of MFMAs -- whose
+  // fragments are in registers by then -- and their latency is covered by this wavefront's own MFMAs.
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < nk;
+    if (more) gload(kt + 1);
+    const float* Ac = As + cur * BM * LDSS + a_lane;
+    const float* Bc = Bs + cur * BN * LDSS + b_lane;
+    // While it has fragments to feed, a wavefront outranks its SIMD neighbours that are between slabs:
+    // the matrix pipe is the resource to keep busy.
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags(Ac, Bc, ks + 1, (ks + 1) & 1);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) mma(ks & 1, t);
+    }
+    mma((KS - 1) & 1, 0);
+    mma((KS - 1) & 1, 1);
+    if (more) {
+      sstore(cur ^ 1);
+      __syncthreads();
+      read_frags(As + (cur ^ 1) * BM * LDSS + a_lane, Bs + (cur ^ 1) * BN * LDSS + b_lane, 0, 0);
+    }
+    mma((KS - 1) & 1, 2);
+    mma((KS - 1) & 1, 3);
     __builtin_amdgcn_s_setprio(0);
-    if (kt + 1 < nk) sstore(cur ^ 1);
-    __syncthreads();
   }
+  __syncthreads();   // every wavefront is done with the operand buffers (the Op may reuse LDS)
 
   op.template finish<Cfg>(lrow, lkq, s_row);
   __syncthreads();
