@@ -261,9 +261,11 @@ def main():
         line["cpu_baseline"] = cpu_baseline(args.workload, args.seed)
     # The same workload with the window controller on (windows <= L chosen per chain from its past:
     # an extension of Alg. 1, exact in law; the headline `value` above keeps the configured fixed L).
-    ra = run_gpu(args.workload, max(1, min(args.steps, 2)), 1, args.seed, profile=False, adaptive=True)
-    line["window_control"] = dict(steps_per_s=ra["steps_per_s"], ms_per_sample=ra["ms_per_sample"],
-                                  rounds_mean=ra["rounds_mean"], rounds_max=ra["rounds_max"], path=ra["path"])
+    # (Skipped with --others 0, so that a profiler run of this script sees the fixed-L launches only.)
+    if args.others:
+        ra = run_gpu(args.workload, max(1, min(args.steps, 2)), 1, args.seed, profile=False, adaptive=True)
+        line["window_control"] = dict(steps_per_s=ra["steps_per_s"], ms_per_sample=ra["ms_per_sample"],
+                                      rounds_mean=ra["rounds_mean"], rounds_max=ra["rounds_max"], path=ra["path"])
     if args.others:
         others = {}
         for w in sorted(W.CONFIGS):
