@@ -276,8 +276,13 @@ struct LogitOp {
             if (mok) logits[(int64_t)m * ld + n[j]] = v;
           }
         }
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // stays inside the half-wave
+        // maximum over the 32 lanes of the half-wave: four DPP steps inside each row of 16 lanes, then one
+        // cross-lane exchange between the two rows (a full butterfly of shuffles costs five LDS round trips)
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         if (mok && fr.l32 == 0) pmax[(int64_t)m * np + 2 * fr.tile_n + fr.wn] = mx;
       }
     }
