@@ -317,6 +317,19 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.close()
 
 
+def test_sample_random_small_shapes():
+    """A seeded sweep over small mixture shapes (d, C, K, L, chains drawn at random, windows fixed or
+    controlled, either sampling path): whole samples against the oracle."""
+    rng = np.random.default_rng(2024)
+    total = 0
+    for case in range(10):
+        cfg = dict(kind="gmm", var=0.25, d=int(rng.integers(1, 40)), C=int(rng.integers(1, 90)),
+                   K=int(rng.integers(1, 60)), L=int(rng.integers(1, 70)), chains=int(rng.integers(1, 6)))
+        resident, adaptive = bool(case & 1), bool(case & 2)
+        total += _free_running(cfg, 40 + case, range(cfg["chains"]), resident=resident, adaptive=adaptive)
+    assert total >= 10
+
+
 def test_resident_sampler_agrees_with_round_kernels():
     """One launch per sample against the lock-step rounds: same counters and formulas, so chains
     agree to rounding unless a near-tie decision falls differently (rare; those chains differ in
