@@ -78,6 +78,12 @@ typedef enum { ASD_DEN_GMM = 1, ASD_DEN_MLP = 2 } asd_den_kind;
  *   posterior mean (the mean function m(t, y) of Eq. sl-defn for this law).
  *   means DEV fp32 [C, d] row-major; log_w DEV fp32 [C] (unnormalised logs
  *   allowed); abar HOST fp32 [n_tau], values in (0, 1].
+ *   Alternatively (abar NULL) the chain may run in the paper's own stochastic-
+ *   localization coordinates: sl_time HOST fp32 [n_tau], values t >= 0, and D
+ *   is the mean function itself, m(t, y) = E[x* | t x* + sqrt(t) xi = y] of
+ *   Eq. sl-defn; the schedule is then the Euler chain of Eq. euler-sde
+ *   (c_x = 1, c_0 = eta_i, sigma = sqrt(eta_i)).  Exactly one of abar and
+ *   sl_time is given.
  * MLP: in = [bf16(x) ; temb[tau]] (d + temb_dim), h = W_in in + b_in,
  *   n_blocks times h += SiLU(W_l bf16(h) + b_l), out = W_out bf16(h) + b_out,
  *   D = clamp(out, -out_clip, out_clip) if out_clip > 0 (the usual clipping of
@@ -97,6 +103,7 @@ typedef struct {
   const float* log_w;
   float var;
   const float* abar;
+  const float* sl_time;
   /* MLP */
   int32_t width, n_blocks, linears_per_block, temb_dim;
   float out_clip;

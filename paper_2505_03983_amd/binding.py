@@ -30,7 +30,7 @@ class asd_schedule(C.Structure):
 class asd_denoiser(C.Structure):
     _fields_ = [("kind", C.c_int32), ("d", C.c_int32), ("n_tau", C.c_int32),
                 ("C", C.c_int32), ("means", C.c_void_p), ("log_w", C.c_void_p), ("var", C.c_float),
-                ("abar", C.c_void_p),
+                ("abar", C.c_void_p), ("sl_time", C.c_void_p),
                 ("width", C.c_int32), ("n_blocks", C.c_int32), ("linears_per_block", C.c_int32),
                 ("temb_dim", C.c_int32), ("out_clip", C.c_float),
                 ("w_in", C.c_void_p), ("w_blk", C.c_void_p), ("w_out", C.c_void_p),
@@ -152,6 +152,7 @@ def make_config(sched, den, L, chains, seed):
         cfg.den.log_w = _ptr(den["log_w"])
         cfg.den.var = float(den["var"])
         cfg.den.abar = host(den["abar"], np.float32) if den.get("abar") is not None else None
+        cfg.den.sl_time = host(den["sl_time"], np.float32) if den.get("sl_time") is not None else None
     elif den["kind"] == "mlp":
         cfg.den.width = int(den["width"])
         cfg.den.n_blocks = int(den["n_blocks"])

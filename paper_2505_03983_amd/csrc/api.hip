@@ -51,12 +51,19 @@ static asd_status validate(const asd_config* cfg) {
     return fail(ASD_EINVAL, "problem too large");
   if (m.kind == ASD_DEN_GMM) {
     if (m.C < 1) return fail(ASD_EINVAL, "C must be >= 1 (got %d)", m.C);
-    if (!m.means || !m.log_w || !m.abar) return fail(ASD_EINVAL, "GMM parameter pointer is NULL");
+    if (!m.means || !m.log_w) return fail(ASD_EINVAL, "GMM parameter pointer is NULL");
+    if ((m.abar != nullptr) == (m.sl_time != nullptr))
+      return fail(ASD_EINVAL, "a GMM denoiser takes exactly one of abar and sl_time");
     if (!(m.var >= 0.f) || !isfinite(m.var)) return fail(ASD_EINVAL, "var must be finite and >= 0");
     for (int t = 0; t < m.n_tau; ++t) {
-      const float ab = m.abar[t];
-      if (!(ab > 0.f) || !(ab <= 1.f)) return fail(ASD_EINVAL, "abar[%d] outside (0,1]", t);
-      if ((double)ab * m.var + 1.0 - ab <= 0.0) return fail(ASD_EINVAL, "abar[%d]=1 with var=0 is degenerate", t);
+      if (m.abar) {
+        const float ab = m.abar[t];
+        if (!(ab > 0.f) || !(ab <= 1.f)) return fail(ASD_EINVAL, "abar[%d] outside (0,1]", t);
+        if ((double)ab * m.var + 1.0 - ab <= 0.0) return fail(ASD_EINVAL, "abar[%d]=1 with var=0 is degenerate", t);
+      } else {
+        const float tt = m.sl_time[t];
+        if (!(tt >= 0.f) || !isfinite(tt)) return fail(ASD_EINVAL, "sl_time[%d] must be finite and >= 0", t);
+      }
     }
   } else if (m.kind == ASD_DEN_MLP) {
     if (m.width < 1 || m.n_blocks < 0 || m.temb_dim < 0) return fail(ASD_EINVAL, "bad MLP shape");

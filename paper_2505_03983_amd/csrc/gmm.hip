@@ -2,6 +2,7 @@
 // for data  sum_k w_k N(mu_k, s2 I)  (the mean function m(t, y) of Eq. sl-defn
 // for that law): the "model call" of Alg. 1 in the analytic workloads.
 //
+// (DDPM coordinates; the same four coefficients per time index express the SL mean function, see gmm_create)
 // With ab = abar[tau], V = ab*s2 + 1 - ab:
 //   logit_k = (sqrt(ab)/V) <x, mu_k> - (ab/(2V)) |mu_k|^2 + log w_k     (|x|^2 cancels)
 //   r       = softmax(logit)
@@ -380,12 +381,24 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
   float4* h = new (std::nothrow) float4[ctx->n_tau];
   if (!h) return ASD_ENOMEM;
   for (int t = 0; t < ctx->n_tau; ++t) {
-    const double ab = den.abar[t];
-    const double V = ab * (double)den.var + 1.0 - ab;
-    h[t].x = (float)(sqrt(ab) / V);
-    h[t].y = (float)(ab / (2.0 * V));
-    h[t].z = (float)(sqrt(ab) * (double)den.var / V);
-    h[t].w = (float)(1.0 - ab * (double)den.var / V);
+    const double s2 = (double)den.var;
+    if (den.abar) {
+      const double ab = den.abar[t];
+      const double V = ab * s2 + 1.0 - ab;
+      h[t].x = (float)(sqrt(ab) / V);
+      h[t].y = (float)(ab / (2.0 * V));
+      h[t].z = (float)(sqrt(ab) * s2 / V);
+      h[t].w = (float)(1.0 - ab * s2 / V);
+    } else {
+      // Stochastic-localization coordinates (Eq. sl-defn): y ~ N(t mu_k, (t^2 s2 + t) I) under component
+      // k, E[x* | y, k] = mu_k + s2 (y - t mu_k) / (t s2 + 1).  The |y|^2 term drops out of the softmax.
+      const double tt = den.sl_time[t];
+      const double W1 = tt * s2 + 1.0;
+      h[t].x = (float)(1.0 / W1);
+      h[t].y = (float)(tt / (2.0 * W1));
+      h[t].z = (float)(s2 / W1);
+      h[t].w = (float)(1.0 / W1);
+    }
   }
   hipError_t e = hipMemcpy(g->coef_tau, h, sizeof(float4) * (size_t)ctx->n_tau, hipMemcpyHostToDevice);
   delete[] h;

@@ -57,10 +57,10 @@ def _cfg(**over):
     for k, v in over.items():
         if k in kw:
             kw[k] = v
-        elif k in s:
-            s[k] = v
-        else:
+        elif k in den or k not in s:
             den[k] = v
+        else:
+            s[k] = v
     return s, den, kw
 
 
@@ -70,6 +70,9 @@ def _cfg(**over):
     (dict(d=0), binding.ASD_EINVAL),
     (dict(C=0), binding.ASD_EINVAL),
     (dict(means=None), binding.ASD_EINVAL),
+    (dict(abar=None), binding.ASD_EINVAL),                        # neither abar nor sl_time
+    (dict(sl_time=np.ones(11, np.float32)), binding.ASD_EINVAL),  # both
+    (dict(abar=None, sl_time=np.full(11, -1.0, np.float32)), binding.ASD_EINVAL),
     (dict(var=-1.0), binding.ASD_EINVAL),
     (dict(n_tau=5), binding.ASD_EINVAL),                         # tau values out of range
     (dict(sigma=np.full(10, -1.0, np.float32)), binding.ASD_EINVAL),

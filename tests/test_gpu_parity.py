@@ -317,6 +317,59 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.close()
 
 
+@pytest.mark.parametrize("resident", [False, True])
+def test_sample_in_sl_coordinates(resident):
+    """The paper's own coordinates: the Euler chain of Eq. euler-sde on the stochastic-localization
+    process (c_x = 1, c_0 = eta_i, sigma = sqrt(eta_i)) with the mean function m(t, y) of Eq. sl-defn as
+    the model, given to the library as tables plus the SL time of every index.  Whole samples against
+    the oracle run in the same coordinates; y_0 = gamma_0 xi_0 is passed in."""
+    from oracle import denoisers, schedule
+    K, d, C, L, chains, seed = 60, 6, 5, 8, 6, 12
+    p = W.gmm_params(d, C)
+    S = schedule.sl_tables(K)
+    Km = K - 1
+    eta = S["eta"].astype(np.float32)
+    sched = dict(c_x=np.ones(Km, np.float32), c_0=eta, sigma=np.sqrt(S["eta"]).astype(np.float32),
+                 tau=np.arange(Km, dtype=np.int32))
+    den = runtime.device_params(dict(kind="gmm", d=d, C=C), p)
+    den["n_tau"] = K
+    den["sl_time"] = S["t"].astype(np.float32)
+    ctx = binding.Ctx(sched, den, L, chains, seed)
+    ctx.use_resident(resident)
+    A64, B64, S64 = sched["c_x"].astype(np.float64), sched["c_0"].astype(np.float64), sched["sigma"].astype(np.float64)
+    t64 = den["sl_time"].astype(np.float64)
+
+    def model_sl(idx, rows):
+        return denoisers.gmm_sl_mean(rows, t64[np.asarray(idx)], p["means"], p["log_w"], p["var"])
+
+    y0 = np.empty((chains, d), np.float32)
+    runs = []
+    for c in range(chains):
+        xi, u = chain_randoms(seed, c, Km, d)
+        y0[c] = (S["gamma"][0] * xi[0]).astype(np.float32)
+        runs.append(oasd.asd_sample(y0[c].astype(np.float64), L, A64, B64, S64, model_sl, xi, u, eps=1e-4))
+    traj = runtime.alloc_traj(ctx)
+    rounds = torch.zeros(chains, dtype=torch.int32, device=DEV)
+    ctx.sample(traj, rounds, y0=torch.from_numpy(y0).to(DEV))
+    tj, rd = traj.cpu().numpy(), rounds.cpu().numpy()
+    full = 0
+    for c, (y, R, recs) in enumerate(runs):
+        stop = None
+        for rec in recs:
+            n_acc = rec["j"] - rec["a"]
+            if rec["flagged"][: min(n_acc + 1, rec["b"] - rec["a"])].any():
+                stop = rec["a"]
+                break
+        upto = Km if stop is None else stop
+        # SL states grow like t (up to ~1e4 here): the bar is relative to the largest state compared
+        assert H.rel_err(tj[c, : upto + 1], y[: upto + 1]) <= 1e-4, (c, upto)
+        if stop is None:
+            assert rd[c] == R
+            full += 1
+    assert full >= 3
+    ctx.close()
+
+
 def test_sample_random_small_shapes():
     """A seeded sweep over small mixture shapes (d, C, K, L, chains drawn at random, windows fixed or
     controlled, either sampling path): whole samples against the oracle."""
