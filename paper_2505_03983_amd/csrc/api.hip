@@ -269,13 +269,11 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
 
 // All launches of one round of Alg. 1 on `st`, plus the copy of the live-chain ring to the host.
 static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
-  ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
+  // No planning kernels here: the rows of the draft call were listed by the previous round's accept
+  // kernel (by init_state before round 0), those of the verify call are listed by the draft kernel.
   ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
-  ASD_TRY(launch_draft(ctx, traj, ctx->a, st));
-  if (ctx->L > 1) {
-    ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
-    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
-  }
+  ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live));
+  if (ctx->L > 1) ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
   ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live, st));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
@@ -326,8 +324,14 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
   struct WinScope {  // the round kernels see the per-chain windows only while this sample runs
     asd_ctx* c;
-    explicit WinScope(asd_ctx* x) : c(x) { c->cur_win = c->adaptive ? c->win : nullptr; }
-    ~WinScope() { c->cur_win = nullptr; }
+    explicit WinScope(asd_ctx* x) : c(x) {
+      c->cur_win = c->adaptive ? c->win : nullptr;
+      c->fold_plans = true;
+    }
+    ~WinScope() {
+      c->cur_win = nullptr;
+      c->fold_plans = false;
+    }
   } win_scope(ctx);
   // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
   // round it has just queued; a finished batch then runs `lag` empty rounds, which cost next to nothing

@@ -29,6 +29,22 @@ void set_error(const char* fmt, ...);
     if (s__ != ASD_OK) return s__;    \
   } while (0)
 
+// ---- row plans written by the round kernels themselves (asd_sample) ------------------------------
+// The stage entries plan their model calls with a scan over the chains (plan_rows_kernel, ordered rows).
+// Inside asd_sample the kernels that already visit every chain append the rows of the *next* model
+// call with one atomic add per chain: the accept kernel lists y_{a_next} of every unfinished chain for
+// the next round's draft call, the draft kernel lists the drafted slots for this round's verify call.
+// The order of the rows then varies from run to run; a row's result does not depend on its position.
+struct PlanOut {
+  int64_t* in_off = nullptr;    // NULL: the kernel writes no plan
+  int64_t* out_off = nullptr;
+  int32_t* row_tau = nullptr;
+  int32_t* n_rows = nullptr;    // [2]: rows of the draft call, rows of the verify call
+  const int32_t* tau = nullptr; // step -> time index
+  int64_t* row_counts = nullptr;  // [2] running totals for the profiler, or NULL
+  int32_t* ring = nullptr;      // round index + live-chain ring, advanced once per round
+};
+
 // ---- a row of a batched model call -----------------------------------------
 // The denoiser is always evaluated on a *list of rows*: row n is read at
 // in_base + in_off[n] (d floats), its time index is tau[n], and its result is
@@ -121,6 +137,7 @@ struct asd_ctx {
   int32_t* cur_win = nullptr;  // what the round kernels are given: win while an adaptive sample runs, else NULL (= L)
   bool adaptive = false;
   const void* g_win = nullptr; // cur_win the round graph was captured with
+  bool fold_plans = false;     // set while asd_sample's rounds run: see PlanOut
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
@@ -177,7 +194,7 @@ inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) 
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds, hipStream_t st);
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me = nullptr);
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st);
-asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st);
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring = nullptr);
 asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st);
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st);

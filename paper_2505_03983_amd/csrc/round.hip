@@ -13,10 +13,20 @@ namespace asd {
 __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ key_p, const float* __restrict__ y0,
                                   float* __restrict__ traj, int32_t* __restrict__ a,
                                   int32_t* __restrict__ rounds, int32_t* __restrict__ round_idx, int L,
-                                  int32_t* __restrict__ win) {
+                                  int32_t* __restrict__ win, PlanOut plan) {
   const int c = blockIdx.x;
   const Key key = *key_p;
   if (c == 0 && threadIdx.x == 0 && round_idx) *round_idx = 0;
+  if (plan.in_off && threadIdx.x == 0) {  // the draft call of round 0: y_0 of every chain
+    plan.in_off[c] = (int64_t)c * (K + 1) * d;
+    plan.out_off[c] = (int64_t)c * d;
+    plan.row_tau[c] = plan.tau[0];
+    if (c == 0) {
+      plan.n_rows[0] = B;
+      plan.n_rows[1] = 0;
+      if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[0], (unsigned long long)B);
+    }
+  }
   const int nblk = (d + 3) >> 2;
   const bool vec = (d & 3) == 0;
   float* row = traj + (int64_t)c * (K + 1) * d;
@@ -34,10 +44,23 @@ __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ k
   }
 }
 
+static PlanOut plan_out(asd_ctx* ctx, int32_t* ring) {
+  PlanOut p;
+  if (!ctx->fold_plans) return p;
+  p.in_off = ctx->in_off;
+  p.out_off = ctx->out_off;
+  p.row_tau = ctx->row_tau;
+  p.n_rows = ctx->n_rows_dev;
+  p.tau = ctx->tau;
+  p.row_counts = ctx->prof.on ? ctx->row_counts : nullptr;
+  p.ring = ring;
+  return p;
+}
+
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds,
                              hipStream_t st) {
   hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key_dev, y0,
-                     traj, a, rounds, ctx->live, ctx->L, ctx->cur_win);
+                     traj, a, rounds, ctx->live, ctx->L, ctx->cur_win, plan_out(ctx, nullptr));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -169,15 +192,44 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
                                                     const float* __restrict__ c_0,
                                                     const float* __restrict__ sigma,
                                                     const float* __restrict__ x0a, float* __restrict__ traj,
-                                                    const int32_t* __restrict__ win) {
+                                                    const int32_t* __restrict__ win, PlanOut plan) {
   const int c = blockIdx.y;
   const int blk = blockIdx.x * blockDim.x + threadIdx.x;
   const int nblk = (d + 3) >> 2;
   const int ac = a[c];
-  if (blk >= nblk || ac >= K || ac < 0) return;
+  const bool live = ac < K && ac >= 0;
+  const int w = live ? min(win ? win[c] : Lwin, K - ac) : 0;
+  if (plan.in_off && blockIdx.x == 0) {
+    // Bookkeeping of the round, once: the draft call has consumed its row count; the round index
+    // advances and this round's slot of the live-chain ring starts at zero (the accept kernel adds to it).
+    if (c == 0 && threadIdx.x == 0) {
+      plan.n_rows[0] = 0;
+      if (plan.ring) {
+        const int r = plan.ring[0];
+        plan.ring[0] = r + 1;
+        plan.ring[1 + (r % kLiveRing)] = 0;
+      }
+    }
+    // This chain's rows of the verify call: the drafted samples of slots 1..w-1, read in place from the
+    // trajectory, results to x0hat[c][slot].  One atomic add reserves the range; the first wavefront fills it.
+    if (threadIdx.x < 64 && w > 1) {
+      int base = 0;
+      if (threadIdx.x == 0) {
+        base = atomicAdd(&plan.n_rows[1], w - 1);
+        if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[1], (unsigned long long)(w - 1));
+      }
+      base = __shfl(base, 0, 64);
+      for (int s = 1 + (int)threadIdx.x; s < w; s += 64) {
+        const int i = ac + s;
+        plan.in_off[base + s - 1] = ((int64_t)c * (K + 1) + i) * d;
+        plan.out_off[base + s - 1] = ((int64_t)c * Lwin + s) * d;
+        plan.row_tau[base + s - 1] = plan.tau[i];
+      }
+    }
+  }
+  if (blk >= nblk || !live) return;
   const Key key = *key_p;
   const bool vec = (d & 3) == 0;
-  const int w = min(win ? win[c] : Lwin, K - ac);
   float* row = traj + ((int64_t)c * (K + 1) + ac) * d;
   float4 y = load4(row, blk, d, vec);
   const float4 g = load4(x0a + (int64_t)c * d, blk, d, vec);
@@ -194,13 +246,13 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
   }
 }
 
-asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st) {
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring) {
   const int nblk = (ctx->d + 3) / 4;
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   ProfScope ps(ctx, ASD_PROF_DRAFT, 0, st);
   hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win);
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan_out(ctx, ring));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -224,7 +276,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr);
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut());
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -275,7 +327,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
                                                       const float* __restrict__ x0hat, float* __restrict__ traj,
                                                       int32_t* __restrict__ accepted, float* __restrict__ stats,
                                                       int32_t* __restrict__ rounds, int32_t* __restrict__ live,
-                                                      int32_t* __restrict__ win) {
+                                                      int32_t* __restrict__ win, PlanOut plan) {
   __shared__ float s_part[kAcceptChunk][16][2];  // per slot of the chunk, per wavefront: partial <D,xi>, |D|^2
   __shared__ float s_rej[2];                     // <D,xi>, |D|^2 of the first rejected slot
   __shared__ int s_first;                        // index inside the chunk of the first rejection, 64 if none
@@ -287,6 +339,8 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   const int wave = tid >> 6;
   const int nwaves = nthreads >> 6;
   const int ac = a[c];
+  // the verify call has consumed its row count: the draft kernel of the next round starts from zero
+  if (plan.in_off && c == 0 && tid == 0) plan.n_rows[1] = 0;
   if (ac >= K || ac < 0) {
     if (tid == 0 && accepted) accepted[c] = -1;
     return;
@@ -434,8 +488,15 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
       win[B + c] = st;
       win[c] = window_of(st, L);
     }
-    // the plan kernel of this round already advanced the round index
+    // the round index was advanced at the start of this round
     if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
+    if (plan.in_off && a_next < K) {  // this chain's row of the next round's draft call
+      const int idx = atomicAdd(&plan.n_rows[0], 1);
+      plan.in_off[idx] = ((int64_t)c * (K + 1) + a_next) * d;
+      plan.out_off[idx] = (int64_t)c * d;
+      plan.row_tau[idx] = plan.tau[a_next];
+      if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[0], 1ull);
+    }
   }
 }
 
@@ -445,7 +506,8 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
   hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win);
+                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win,
+                     plan_out(ctx, nullptr));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
