@@ -271,9 +271,14 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
 static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
   // No planning kernels here: the rows of the draft call were listed by the previous round's accept
   // kernel (by init_state before round 0), those of the verify call are listed by the draft kernel.
+  // (or, for large batches, by the planning kernels: see fold_plans)
+  if (!ctx->fold_plans) ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
   ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
   ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live));
-  if (ctx->L > 1) ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+  if (ctx->L > 1) {
+    if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
+    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+  }
   ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live, st));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
@@ -326,7 +331,11 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
     asd_ctx* c;
     explicit WinScope(asd_ctx* x) : c(x) {
       c->cur_win = c->adaptive ? c->win : nullptr;
-      c->fold_plans = true;
+      // Appending the row plans from the draft / accept kernels saves two launches per round but costs
+      // those kernels an atomic per chain and the index writes: a gain for launch-bound rounds (cfg 3:
+      // -5% per sample), a wash for large batches, whose draft / accept kernels run near their own
+      // limits (cfg 5: +13 and +18 us on them against 27 us of planning kernels).
+      c->fold_plans = c->n_rows_max <= 16384;
     }
     ~WinScope() {
       c->cur_win = nullptr;

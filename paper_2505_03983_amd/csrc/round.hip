@@ -186,6 +186,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
 // walks the window; rows are written coalesced.  HBM-bound: reads 2 rows,
 // writes w rows per chain.
 // ----------------------------------------------------------------------------
+template <bool FOLD>  // FOLD: also list this chain's rows of the verify call and keep the round's books (see PlanOut)
 __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, const Key* __restrict__ key_p,
                                                     const int32_t* __restrict__ a,
                                                     const float* __restrict__ c_x,
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
   const int ac = a[c];
   const bool live = ac < K && ac >= 0;
   const int w = live ? min(win ? win[c] : Lwin, K - ac) : 0;
-  if (plan.in_off && blockIdx.x == 0) {
+  if (FOLD && blockIdx.x == 0) {
     // Bookkeeping of the round, once: the draft call has consumed its row count; the round index
     // advances and this round's slot of the live-chain ring starts at zero (the accept kernel adds to it).
     if (c == 0 && threadIdx.x == 0) {
@@ -251,8 +252,13 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   ProfScope ps(ctx, ASD_PROF_DRAFT, 0, st);
-  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan_out(ctx, ring));
+  const PlanOut plan = plan_out(ctx, ring);
+  if (plan.in_off)
+    hipLaunchKernelGGL(draft_kernel<true>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan);
+  else
+    hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -275,7 +281,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int nblk = (ctx->d + 3) / 4;
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
-  hipLaunchKernelGGL(draft_kernel, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
+  hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
                      ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut());
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -319,6 +325,7 @@ asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st) {
 // ----------------------------------------------------------------------------
 constexpr int kAcceptChunk = 8;
 
+template <bool FOLD>  // FOLD: also list this chain's row of the next round's draft call (see PlanOut)
 __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const Key* __restrict__ key_p,
                                                       int32_t* __restrict__ a,
                                                       const float* __restrict__ c_0,
@@ -340,7 +347,9 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   const int nwaves = nthreads >> 6;
   const int ac = a[c];
   // the verify call has consumed its row count: the draft kernel of the next round starts from zero
-  if (plan.in_off && c == 0 && tid == 0) plan.n_rows[1] = 0;
+  if constexpr (FOLD) {
+    if (c == 0 && tid == 0) plan.n_rows[1] = 0;
+  }
   if (ac >= K || ac < 0) {
     if (tid == 0 && accepted) accepted[c] = -1;
     return;
@@ -490,7 +499,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
     }
     // the round index was advanced at the start of this round
     if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
-    if (plan.in_off && a_next < K) {  // this chain's row of the next round's draft call
+    if constexpr (FOLD) if (a_next < K) {  // this chain's row of the next round's draft call
       const int idx = atomicAdd(&plan.n_rows[0], 1);
       plan.in_off[idx] = ((int64_t)c * (K + 1) + a_next) * d;
       plan.out_off[idx] = (int64_t)c * d;
@@ -505,9 +514,13 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
-  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                     ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win,
-                     plan_out(ctx, nullptr));
+  const PlanOut plan = plan_out(ctx, nullptr);
+  if (plan.in_off)
+    hipLaunchKernelGGL(accept_kernel<true>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
+                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan);
+  else
+    hipLaunchKernelGGL(accept_kernel<false>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
+                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
