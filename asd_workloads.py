@@ -53,7 +53,7 @@ def sinusoidal_table(n_rows, E):
     return f32_to_bf16_bits(tab.astype(np.float32))
 
 
-def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0):
+def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0, predict_eps=False):
     """Weights ~ N(0, 1/fan_in) rounded to bf16 (uint16 patterns), zero biases
     (fp32), time-embedding table [K+1, E] (bf16 patterns), row-major [out, in].
     out_clip: the predicted x_0 is clipped to [-1, 1] as DDPM samplers commonly
@@ -74,10 +74,12 @@ def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0):
         b_out=np.zeros(d, dtype=np.float32),
         temb=sinusoidal_table(K + 1, E),
         out_clip=float(out_clip),
+        predict_eps=bool(predict_eps),
     )
 
 
 def make_params(cfg, model_seed=1):
     if cfg["kind"] == "gmm":
         return gmm_params(cfg["d"], cfg["C"], cfg["var"], model_seed)
-    return mlp_params(cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], model_seed)
+    return mlp_params(cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], model_seed,
+                      predict_eps=cfg.get("predict_eps", False))

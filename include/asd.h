@@ -88,6 +88,10 @@ typedef enum { ASD_DEN_GMM = 1, ASD_DEN_MLP = 2 } asd_den_kind;
  *   n_blocks times h += SiLU(W_l bf16(h) + b_l), out = W_out bf16(h) + b_out,
  *   D = clamp(out, -out_clip, out_clip) if out_clip > 0 (the usual clipping of
  *   the predicted x_0 to the data range), D = out if out_clip == 0.
+ *   predict_eps = 1: the network predicts the noise of x_tau = sqrt(abar) x_0 +
+ *   sqrt(1 - abar) eps instead (the parametrisation of the paper's image
+ *   models); then out is replaced by (x - sqrt(1 - abar[tau]) out) / sqrt(abar[tau])
+ *   before the clip, and abar (HOST fp32 [n_tau], values in (0, 1]) is required.
  *   Weights DEV bf16 row-major [out, in]: w_in [width, d+temb_dim],
  *   w_blk [n_blocks, width, width], w_out [d, width]; biases DEV fp32 or NULL
  *   (= 0): b_in [width], b_blk [n_blocks, width], b_out [d];
@@ -107,6 +111,7 @@ typedef struct {
   /* MLP */
   int32_t width, n_blocks, linears_per_block, temb_dim;
   float out_clip;
+  int32_t predict_eps;
   const void* w_in;
   const void* w_blk;
   const void* w_out;

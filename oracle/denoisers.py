@@ -100,9 +100,14 @@ class MLPOracle:
     Every matrix-product input is rounded to bf16 just before the product;
     weights are bf16; sums, bias, SiLU and the residual stream are fp64 here
     (fp32 on the device).  temb is a table [K+1, E] of bf16 values, row tau.
+
+    predict_eps: the network output is the noise estimate of
+    x_tau = sqrt(abar) x_0 + sqrt(1 - abar) eps (the parametrisation of the
+    paper's image models); x0hat = (x - sqrt(1 - abar[tau]) out) / sqrt(abar[tau]),
+    then the clip.  abar is then a table indexed by tau.
     """
 
-    def __init__(self, params):
+    def __init__(self, params, abar=None):
         self.w_in = bf16_bits_to_f64(params["w_in"])       # [W, d+E]
         self.w_blk = bf16_bits_to_f64(params["w_blk"])     # [n_blocks, W, W]
         self.w_out = bf16_bits_to_f64(params["w_out"])     # [d, W]
@@ -111,6 +116,10 @@ class MLPOracle:
         self.b_out = np.asarray(params["b_out"], dtype=np.float64)
         self.temb = bf16_bits_to_f64(params["temb"])       # [K+1, E]
         self.out_clip = float(params.get("out_clip", 0.0))  # 0: no clipping
+        self.predict_eps = bool(params.get("predict_eps", False))
+        self.abar = None if abar is None else np.asarray(abar, dtype=np.float64)
+        if self.predict_eps and self.abar is None:
+            raise ValueError("a noise-predicting network needs abar")
 
     def __call__(self, x, tau):
         x = np.atleast_2d(np.asarray(x, dtype=np.float64))
@@ -120,6 +129,9 @@ class MLPOracle:
         for l in range(self.w_blk.shape[0]):
             h = h + silu(round_to_bf16(h) @ self.w_blk[l].T + self.b_blk[l])
         out = round_to_bf16(h) @ self.w_out.T + self.b_out
+        if self.predict_eps:
+            ab = self.abar[tau][:, None]
+            out = (x - np.sqrt(1.0 - ab) * out) / np.sqrt(ab)
         if self.out_clip > 0.0:            # predicted x_0 clipped to the data range
             out = np.clip(out, -self.out_clip, self.out_clip)
         return out

@@ -70,6 +70,11 @@ static asd_status validate(const asd_config* cfg) {
     if (!m.w_in || !m.w_out || (m.n_blocks > 0 && !m.w_blk) || (m.temb_dim > 0 && !m.temb))
       return fail(ASD_EINVAL, "MLP parameter pointer is NULL");
     if (!(m.out_clip >= 0.f)) return fail(ASD_EINVAL, "out_clip must be >= 0");
+    if (m.predict_eps) {
+      if (!m.abar) return fail(ASD_EINVAL, "predict_eps needs abar");
+      for (int t = 0; t < m.n_tau; ++t)
+        if (!(m.abar[t] > 0.f) || !(m.abar[t] <= 1.f)) return fail(ASD_EINVAL, "abar[%d] outside (0,1]", t);
+    }
     if (m.linears_per_block != 1) return fail(ASD_EUNSUPPORTED, "linears_per_block must be 1");
     if (m.d % 8 || m.temb_dim % 8 || m.width % 8)
       return fail(ASD_EUNSUPPORTED, "MLP needs d, temb_dim and width to be multiples of 8");

@@ -76,6 +76,7 @@ struct MlpState {
   uint16_t* wp_blk = nullptr;
   uint16_t* wp_out = nullptr;
   float out_clip = 0.f;
+  float2* eps_coef = nullptr;    // [n_tau] (1/sqrt(abar), sqrt(1-abar)/sqrt(abar)) when the network predicts the noise
   const uint16_t* w_in = nullptr;
   const uint16_t* w_blk = nullptr;
   const uint16_t* w_out = nullptr;
@@ -161,16 +162,29 @@ struct BlockEpi {  // h += SiLU(acc + b); hb_next = bf16(h)
   }
 };
 
-struct OutEpi {  // out[out_off[m] + n] = acc + b
+struct OutEpi {  // out[out_off[m] + n] = acc + b, as x_0 (or converted from a noise estimate), clipped
   float* out_base;
   const int64_t* out_off;
   const float* bias;
   float clip;  // 0: none
+  // noise-predicting networks: x_0 = x / sqrt(abar) - out * sqrt(1 - abar) / sqrt(abar), x = the row evaluated
+  const float2* eps_coef;  // NULL: the network predicts x_0
+  const int32_t* tau;
+  const float* in_base;
+  const int64_t* in_off;
   static constexpr bool kLoads = false;
   __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
     const float4 b = load_bias4(bias, n);
     float4 v = make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+    if (eps_coef) {
+      const float2 ec = eps_coef[tau[m]];
+      const float4 x = *reinterpret_cast<const float4*>(in_base + in_off[m] + n);
+      v.x = fmaf(x.x, ec.x, -v.x * ec.y);
+      v.y = fmaf(x.y, ec.x, -v.y * ec.y);
+      v.z = fmaf(x.z, ec.x, -v.z * ec.y);
+      v.w = fmaf(x.w, ec.x, -v.w * ec.y);
+    }
     if (clip > 0.f) {
       v.x = fminf(fmaxf(v.x, -clip), clip);
       v.y = fminf(fmaxf(v.y, -clip), clip);
@@ -189,6 +203,15 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den) {
   s->n_blocks = den.n_blocks;
   s->E = den.temb_dim;
   s->out_clip = den.out_clip;
+  if (den.predict_eps) {
+    std::vector<float2> ec((size_t)ctx->n_tau);
+    for (int t = 0; t < ctx->n_tau; ++t) {
+      const double ab = den.abar[t];
+      ec[t] = make_float2((float)(1.0 / sqrt(ab)), (float)(sqrt(1.0 - ab) / sqrt(ab)));
+    }
+    ASD_HIP(hipMalloc(&s->eps_coef, sizeof(float2) * ec.size()));
+    ASD_HIP(hipMemcpy(s->eps_coef, ec.data(), sizeof(float2) * ec.size(), hipMemcpyHostToDevice));
+  }
   s->in_dim = ctx->d + den.temb_dim;
   s->w_in = (const uint16_t*)den.w_in;
   s->w_blk = (const uint16_t*)den.w_blk;
@@ -242,6 +265,7 @@ void mlp_destroy(asd_ctx* ctx) {
   (void)hipFree(s->wp_in);
   (void)hipFree(s->wp_blk);
   (void)hipFree(s->wp_out);
+  (void)hipFree(s->eps_coef);
   (void)hipFree(s->split.part);
   delete s;
   ctx->mlp = nullptr;
@@ -275,7 +299,7 @@ asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   {
     ProfScope ps(ctx, ASD_PROF_MLP_GEMM_OUT, rows.call, st);
-    const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip};
+    const OutEpi e{rows.out_base, rows.out_off, s->b_out, s->out_clip, s->eps_coef, rows.tau, rows.in_base, rows.in_off};
     ASD_HIP(mlp_gemm(rows.call, rows.n_dev, n, d, W, s->ld_h, s->hb[cur], s->wp_out, e, st, s->split));
   }
   return ASD_OK;

@@ -21,7 +21,7 @@ def device_params(cfg, params, device="cuda:0"):
         return dict(kind="gmm", d=cfg["d"], C=cfg["C"], var=params["var"], means=up(params["means"]),
                     log_w=up(params["log_w"]))
     out = dict(kind="mlp", d=cfg["d"], width=cfg["width"], n_blocks=cfg["n_blocks"], temb_dim=cfg["E"],
-               out_clip=float(params.get("out_clip", 0.0)))
+               out_clip=float(params.get("out_clip", 0.0)), predict_eps=bool(params.get("predict_eps", False)))
     for k in ("w_in", "w_blk", "w_out", "b_in", "b_blk", "b_out", "temb"):
         out[k] = up(params[k])
     return out
@@ -33,7 +33,7 @@ def open_ctx(cfg, params, seed=0, device="cuda:0", beta_min=1e-4, beta_max=0.02,
     sched = binding.asd_schedule_ddpm_linear(cfg["K"], beta_min, beta_max)
     den = device_params(cfg, params, device)
     den["n_tau"] = cfg["K"] + 1
-    if cfg["kind"] == "gmm":
+    if cfg["kind"] == "gmm" or den.get("predict_eps"):
         den["abar"] = sched["abar"]
     ctx = binding.Ctx(sched, den, L or cfg["L"], chains or cfg["chains"], seed)
     ctx.sched = sched

@@ -23,7 +23,7 @@ def gmm_model(T, p):
 
 
 def mlp_model(T, p):
-    net = denoisers.MLPOracle(p)
+    net = denoisers.MLPOracle(p, abar=T["abar"] if p.get("predict_eps") else None)
 
     def model(idx, rows):
         return net(rows, T["tau"][np.asarray(idx)])

@@ -168,6 +168,20 @@ def _teacher_forced(cfg, seed, chains_checked, rounds_per_chain=4, model_seed=1)
     assert n_checked >= 0.8 * (n_checked + n_skipped)
 
 
+def test_noise_predicting_mlp():
+    """predict_eps: the network output is turned into x_0 in the last epilogue.  The conversion
+    multiplies the output by sqrt(1 - abar)/sqrt(abar) (up to ~10 at K = 20), so unclipped values are
+    compared relative to their own scale, clipped ones to the usual bar; then single rounds and whole
+    samples against the oracle."""
+    cfg = dict(kind="mlp", d=40, E=24, width=136, n_blocks=2, K=20, chains=12, L=6, predict_eps=True)
+    got, want = _denoise_case(cfg, 67)
+    assert H.rel_err(got, want) <= 2e-2
+    got, want = _denoise_case(cfg, 67, out_clip=0.0)
+    assert H.rel_err(got, want) <= 5e-3
+    _teacher_forced(cfg, seed=11, chains_checked=range(4))
+    _free_running(cfg, 11, range(6), resident=False)
+
+
 def test_round_config1():
     _teacher_forced(W.CONFIGS[1], seed=0, chains_checked=range(8))
 

@@ -1,6 +1,7 @@
 """Pins for the MLP denoiser of the oracle.  Its definition is not in the
 paper ("parity unpinned"): only special cases and a hand-computed example."""
 import numpy as np
+import pytest
 import torch
 
 import asd_workloads as W
@@ -61,3 +62,29 @@ def test_rows_are_independent_and_rounding_points_matter():
     # inputs that differ by less than half a bf16 ulp are the same to the network
     np.testing.assert_array_equal(mlp(np.full((1, 12), 1.0), [2]), mlp(np.full((1, 12), 1.0 + 2.0 ** -10), [2]))
     assert np.max(np.abs(full)) < 50 and np.std(full) > 0.05
+
+
+def test_noise_prediction_is_the_affine_map_of_the_output():
+    """predict_eps: x0hat = (x - sqrt(1 - abar) out) / sqrt(abar).  Pins: zero weights give
+    out = b_out exactly, so x0hat = (x - sqrt(1 - abar) b) / sqrt(abar); and for any weights the
+    result is that affine map of the x0-parametrised network's output (same rows, same time)."""
+    import asd_workloads as W
+    from oracle import denoisers, schedule
+    K, d, E, width = 12, 8, 8, 16
+    T = schedule.ddpm_tables(K)
+    p = W.mlp_params(d, E, width, 2, K, model_seed=3, out_clip=0.0, predict_eps=True)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((5, d))
+    tau = np.array([1, 4, 7, 12, 12])
+    ab = T["abar"][tau][:, None]
+    zero = dict(p, w_in=np.zeros_like(p["w_in"]), w_blk=np.zeros_like(p["w_blk"]), w_out=np.zeros_like(p["w_out"]),
+                b_out=np.linspace(-1, 1, d).astype(np.float32))
+    got = denoisers.MLPOracle(zero, abar=T["abar"])(x, tau)
+    np.testing.assert_allclose(got, (x - np.sqrt(1 - ab) * zero["b_out"][None, :]) / np.sqrt(ab), rtol=1e-12)
+    raw = denoisers.MLPOracle(dict(p, predict_eps=False))(x, tau)
+    eps = denoisers.MLPOracle(p, abar=T["abar"])(x, tau)
+    np.testing.assert_allclose(eps, (x - np.sqrt(1 - ab) * raw) / np.sqrt(ab), rtol=1e-12)
+    clipped = denoisers.MLPOracle(dict(p, out_clip=1.0), abar=T["abar"])(x, tau)
+    np.testing.assert_array_equal(clipped, np.clip(eps, -1.0, 1.0))
+    with pytest.raises(ValueError):
+        denoisers.MLPOracle(p)
