@@ -100,6 +100,14 @@ def test_mlp_shape_rules():
     with pytest.raises(binding.AsdError) as ei:
         binding.Ctx(s, den, 4, 2)
     assert ei.value.status == binding.ASD_EINVAL
+    den.update(w_out=16, predict_eps=True)                       # a noise-predicting network needs abar
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EINVAL
+    den.update(abar=np.full(11, 1.5, np.float32))
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EINVAL
 
 
 def test_null_handles():
@@ -109,3 +117,6 @@ def test_null_handles():
     assert L.asd_sample(None, None, None, None, None) == binding.ASD_EINVAL
     assert L.asd_last_round_count(None) == -1
     assert "NULL" in binding.last_error()
+    for name in ("asd_use_graphs", "asd_use_resident", "asd_use_adaptive_window"):
+        assert getattr(L, name)(None, 1) == binding.ASD_EINVAL, name
+    assert L.asd_resident_active(None) == 0
