@@ -384,6 +384,14 @@ def test_sample_in_sl_coordinates(resident):
     ctx.close()
 
 
+@pytest.mark.parametrize("resident", [False, True])
+def test_many_chains_small_problem(resident):
+    """A batch far wider than the machine (20000 chains: several workgroups per CU for the chain-resident
+    kernel, twenty scan chunks for the row planner), windows cut by K; sampled chains against the oracle."""
+    cfg = dict(kind="gmm", d=4, C=3, K=9, chains=20000, L=4, var=0.25)
+    assert _free_running(cfg, 50, [0, 1, 1023, 1024, 9999, 19999], resident=resident) >= 3
+
+
 def test_sample_random_small_shapes():
     """A seeded sweep over small mixture shapes (d, C, K, L, chains drawn at random, windows fixed or
     controlled, either sampling path): whole samples against the oracle."""
