@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 1 GiB copy in the same run);
 # see profiles/cfg5_gmm_verify_gemm_hbm_traffic.txt for the commands and the raw readings.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    (5, "GMM_LOGITS/verify"): 1024.0 * (2.0 * 1137560.1 + 758386.0),
-    (5, "GMM_COMBINE/verify"): 1024.0 * (2.0 * 3308168.4 + 175748.3),
+    (5, "GMM_LOGITS/verify", "f32"): 1024.0 * (2.0 * 1137560.1 + 758386.0),
+    (5, "GMM_COMBINE/verify", "f32"): 1024.0 * (2.0 * 3308168.4 + 175748.3),
 }
 
 
@@ -45,7 +45,7 @@ def workload_name(w, cfg):
         w, cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], cfg["chains"], cfg["L"])
 
 
-def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False):
+def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True):
     import torch
     import asd_workloads as W
     from paper_2505_03983_amd import binding, runtime
@@ -54,6 +54,8 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False):
     params = W.make_params(cfg, model_seed=1)
     ctx = runtime.open_ctx(cfg, params, seed=seed)
     ctx.use_adaptive_window(adaptive)
+    ctx.use_split_gemm(split)
+    split_active = ctx.split_gemm_active()
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device="cuda:0")
     for i in range(warmup):
@@ -82,7 +84,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False):
     wall = t1 - t0
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
-               rounds_launched=launched, finite=finite, path=path)
+               rounds_launched=launched, finite=finite, path=path, split=split_active)
     if profile:
         P = binding.PROF
         table = {}
@@ -114,6 +116,11 @@ def roofline(res, w=None):
         dtype = "f32"
         # the row-wise kernel runs on the vector ALUs; its bound is the fp32 vector peak (same figure)
         bound = "mfma" if not name.startswith("GMM_ROWWISE") else "alu"
+        if bound == "mfma" and res.get("split"):
+            # bf16 MFMA on three-way split operands: six bf16 products stand for one fp32 product, and
+            # those are the flops the kernel performs and its roofline is drawn against
+            dtype = "bf16"
+            per_row *= 6.0
     else:
         name = "MLP_GEMM_BLK/verify"
         launches = k[name]["launches"]
@@ -125,10 +132,14 @@ def roofline(res, w=None):
     avg_s = 1e-3 * k[name]["total_ms"] / launches
     achieved = flops_per_launch / avg_s / 1e12
     peak = PEAK[dtype]
-    return dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
-                traffic=TRAFFIC_BYTES_PER_LAUNCH.get((w, name)), avg_launch_us=1e6 * avg_s, launches=launches,
-                algorithmic_flops_per_launch=flops_per_launch,
-                share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
+    out = dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
+               traffic=TRAFFIC_BYTES_PER_LAUNCH.get((w, name, dtype)), avg_launch_us=1e6 * avg_s, launches=launches,
+               algorithmic_flops_per_launch=flops_per_launch, mfma_dtype=dtype,
+               share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
+    if cfg["kind"] == "gmm" and dtype == "bf16":
+        out["bf16_products_per_fp32_product"] = 6
+        out["fp32_equivalent_tflops"] = achieved / 6.0
+    return out
 
 
 def hbm_kernels(res):
@@ -207,6 +218,9 @@ def main():
                     help="time the sample without the library's per-kernel events (the production path: captured "
                          "graphs or the chain-resident kernel); the line then has no roofline object -- meant for "
                          "runs under rocprofv3, which times the kernels itself")
+    ap.add_argument("--fp32-mfma", action="store_true",
+                    help="Gaussian-mixture verify GEMMs on the fp32 matrix pipe instead of the bf16 pipe with "
+                         "three-way split operands")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -228,7 +242,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain)
+    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -244,7 +258,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if cfg["kind"] == "gmm" else "bf16",
+        "dtype": ("f32 (verify GEMM products as 6 bf16 MFMA terms, fp32 accumulation)" if res["split"] else "f32")
+        if cfg["kind"] == "gmm" else "bf16",
         "data": "synthetic",
         "config": {"workload": workload_name(args.workload, cfg), "chains": cfg["chains"], "K": cfg["K"],
                    "L": cfg["L"], "d": cfg["d"]},
@@ -257,11 +272,28 @@ def main():
         line["hbm_kernels"] = hbm_kernels(res)
         line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
                                "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
+    if not args.plain:
+        # what the matrix pipes of this chip sustain on random operands with no memory traffic at all (the chip is
+        # power-limited on dense MFMA work: the data-sheet peaks above hold for constant operands only)
+        from paper_2505_03983_amd import binding
+        sus = {"bf16": binding.asd_mfma_ceiling(True, True, 300), "f32": binding.asd_mfma_ceiling(False, True, 300)}
+        rf = line["roofline"]
+        if rf["bound"] == "mfma":
+            rf["sustained_random_operands"] = sus[rf["mfma_dtype"]]
+            rf["frac_of_sustained"] = rf["achieved"] / sus[rf["mfma_dtype"]]
+        line["mfma_sustained_random_operands_tflops"] = sus
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, args.seed)
     # The same workload with the window controller on (windows <= L chosen per chain from its past:
     # an extension of Alg. 1, exact in law; the headline `value` above keeps the configured fixed L).
     # (Skipped with --others 0, so that a profiler run of this script sees the fixed-L launches only.)
+    if args.others and res["split"]:
+        # the same sample with the verify GEMMs on the fp32 matrix pipe (asd_use_split_gemm off)
+        rp = run_gpu(args.workload, 1, 1, args.seed, profile=True, split=False)
+        rfp = roofline(rp, args.workload)
+        line["fp32_mfma_path"] = dict(steps_per_s=rp["steps_per_s"], ms_per_sample=rp["ms_per_sample"],
+                                      roofline_kernel=rfp["kernel"], achieved=rfp["achieved"], peak=rfp["peak"],
+                                      frac=rfp["frac"], avg_launch_us=rfp["avg_launch_us"], traffic=rfp["traffic"])
     if args.others:
         ra = run_gpu(args.workload, max(1, min(args.steps, 2)), 1, args.seed, profile=False, adaptive=True)
         line["window_control"] = dict(steps_per_s=ra["steps_per_s"], ms_per_sample=ra["ms_per_sample"],

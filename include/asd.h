@@ -205,6 +205,16 @@ ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
 /* 1 if the next asd_sample on this context will take that path (shape fits, switch on, profiling off). */
 ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 
+/* Verify-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
+ * operand split into three bf16 terms (six bf16 products per fp32 product, fp32 accumulation; what
+ * is left out is below 2^-24 of |a||b| per product, the order of fp32 rounding).  Nothing in the
+ * method changes: it is another way to evaluate the same fp32 contraction, about 1.5x faster on this
+ * chip than its fp32 matrix pipe.  Taken when d % 16 == 0 and C % 16 == 0 on the matrix-core path;
+ * on = 0 selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
+ASD_API asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on);
+/* 1 if the verify call of this context runs the split kernels. */
+ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
+
 /* Sequential chain with the same random inputs (one model call per step, K
  * launches): the baseline ASD is compared against in the paper's speedups. */
 ASD_API asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream);
@@ -252,6 +262,14 @@ typedef enum {
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
 ASD_API asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms);
 ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows);
+
+/* What the matrix pipe of the current device sustains: a register-only loop of 32x32 MFMAs (bf16 != 0:
+ * v_mfma_f32_32x32x16_bf16, else v_mfma_f32_32x32x2_f32) with no memory traffic, run for about
+ * ms_target milliseconds (1..5000) on the default stream; *tflops HOST receives the rate of the second
+ * half of the run.  random_data != 0: zero-mean random operands, as in real use; 0: constant operands.
+ * The chip is power-limited on dense MFMA work, so the two differ widely and the first -- not the
+ * data-sheet peak -- is the ceiling a GEMM on real data can approach.  Allocates and frees a few MB; synchronous. */
+ASD_API asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops);
 
 /* ---- host-only helpers -----------------------------------------------------
  * DDPM linear-beta schedule (beta_tau from beta_min to beta_max over tau=1..K)

@@ -67,10 +67,13 @@ def lib():
             "asd_use_resident": (i32, [vp, i32]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
+            "asd_use_split_gemm": (i32, [vp, i32]),
+            "asd_split_gemm_active": (i32, [vp]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
             "asd_profile_enable": (i32, [vp, i32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
             "asd_profile_rows": (i32, [vp, vp, vp]),
+            "asd_mfma_ceiling": (i32, [i32, i32, i32, vp]),
             "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
             "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
@@ -199,6 +202,12 @@ class Ctx:
     def resident_active(self):
         return bool(lib().asd_resident_active(self.h))
 
+    def use_split_gemm(self, on=True):
+        _check(lib().asd_use_split_gemm(self.h, int(bool(on))))
+
+    def split_gemm_active(self):
+        return bool(lib().asd_split_gemm_active(self.h))
+
     def set_seed(self, seed):
         _check(lib().asd_set_seed(self.h, int(seed)))
 
@@ -234,6 +243,13 @@ class Ctx:
 
     def denoise(self, x, tau, out, stream=None):
         _check(lib().asd_denoise(self.h, _ptr(x), _ptr(tau), int(x.shape[0]), _ptr(out), _stream(stream)))
+
+
+def asd_mfma_ceiling(bf16, random_data=True, ms_target=200):
+    """TFLOP/s a register-only MFMA loop sustains on the current device."""
+    t = C.c_double(0.0)
+    _check(lib().asd_mfma_ceiling(int(bool(bf16)), int(bool(random_data)), int(ms_target), C.addressof(t)))
+    return t.value
 
 
 def asd_debug_philox(seed, chain, step, stream_id, nblk, out, stream=None):

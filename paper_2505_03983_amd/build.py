@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasd.so")
-SOURCES = ["api.hip", "round.hip", "gmm.hip", "gmm_chain.hip", "mlp.hip"]
+SOURCES = ["api.hip", "round.hip", "gmm.hip", "gmm_chain.hip", "mlp.hip", "ceiling.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -8,6 +8,7 @@
 #include <new>
 
 #include "common.h"
+#include "gmm_state.h"
 
 namespace asd {
 
@@ -421,6 +422,20 @@ asd_status asd_use_resident(asd_ctx* ctx, int32_t on) {
   ctx->resident_enabled = on != 0;
   return ASD_OK;
 }
+
+asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  if (ctx->gmm && ctx->gmm->split_ok && ctx->gmm->use_split != (on != 0)) {
+    ctx->gmm->use_split = on != 0;
+    if (ctx->gexec) {   // the captured round holds the other kernels
+      (void)hipGraphExecDestroy(ctx->gexec);
+      ctx->gexec = nullptr;
+    }
+  }
+  return ASD_OK;
+}
+
+int32_t asd_split_gemm_active(const asd_ctx* ctx) { return (ctx && ctx->gmm && ctx->gmm->use_split) ? 1 : 0; }
 
 int32_t asd_resident_active(const asd_ctx* ctx) {
   return (ctx && ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx)) ? 1 : 0;

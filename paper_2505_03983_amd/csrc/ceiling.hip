@@ -1,0 +1,152 @@
+// What the matrix pipe of the chip at hand sustains: a register-only MFMA loop (no memory traffic at
+// all), timed over a stated duration, with operands that are either random (zero-mean, like real
+// data) or constant.  The two differ by almost 2x on this chip: the dense rate with random operands
+// is set by the power limit, not by the issue rate, so it -- not the data-sheet peak -- is the
+// ceiling a real GEMM can approach.  Exposed for profiling (asd_mfma_ceiling); not part of the path.
+#include "common.h"
+#include "gemm_bf16.h"
+
+#include <new>
+
+namespace asd {
+
+typedef uint32_t cu32x4 __attribute__((ext_vector_type(4)));
+typedef float cv16f __attribute__((ext_vector_type(16)));
+
+// 24 MFMAs per iteration on four accumulators, six A and six B fragments in rotation
+__global__ __launch_bounds__(256, 2) void ceiling_bf16_kernel(float* __restrict__ out, const cu32x4* __restrict__ in,
+                                                              int iters) {
+  cv16f acc[4];
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  v8bf a[6], b[6];
+  for (int i = 0; i < 6; ++i) {
+    a[i] = __builtin_bit_cast(v8bf, in[(threadIdx.x + 256 * i) & 4095]);
+    b[i] = __builtin_bit_cast(v8bf, in[(threadIdx.x + 256 * i + 2048) & 4095]);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 6; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 1) % 6], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 2) % 6], acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 3) % 6], b[u], acc[2], 0, 0, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 4) % 6], b[u], acc[3], 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256, 2) void ceiling_f32_kernel(float* __restrict__ out, const cu32x4* __restrict__ in,
+                                                             int iters) {
+  cv16f acc[4];
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  float a[6], b[6];
+  for (int i = 0; i < 6; ++i) {
+    // a bf16 pair read as one fp32: random sign, exponent near 1, random 23-bit significand
+    a[i] = __uint_as_float(in[(threadIdx.x + 256 * i) & 4095].x);
+    b[i] = __uint_as_float(in[(threadIdx.x + 256 * i + 2048) & 4095].y);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 6; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[(u + 1) % 6], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[(u + 2) % 6], acc[1], 0, 0, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[(u + 3) % 6], b[u], acc[2], 0, 0, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[(u + 4) % 6], b[u], acc[3], 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+  for (int i = 0; i < 4; ++i)
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace asd
+
+using namespace asd;
+
+asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops) {
+  if (!tflops || ms_target < 1 || ms_target > 5000) {
+    set_error("asd_mfma_ceiling: tflops is NULL or ms_target outside [1, 5000]");
+    return ASD_EINVAL;
+  }
+  constexpr int kWgs = 512, kWords = 4096 * 4, kBatch = 8;
+  float* out = nullptr;
+  cu32x4* in = nullptr;
+  uint32_t* h = new (std::nothrow) uint32_t[kWords];
+  if (!h) return ASD_ENOMEM;
+  uint64_t s = 0x9E3779B97F4A7C15ull;   // splitmix64
+  auto next = [&]() {
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return (uint32_t)((z ^ (z >> 31)) >> 16);
+  };
+  for (int i = 0; i < kWords; ++i) {
+    uint32_t w = 0;
+    for (int hlf = 0; hlf < 2; ++hlf) {
+      const uint32_t r = next();
+      const uint32_t sign = r & 1u, e = 125u + ((r >> 1) & 3u), m = (r >> 3) & 127u;   // |value| in [0.25, 4)
+      w |= (random_data ? ((sign << 15) | (e << 7) | m) : 0x3f80u) << (16 * hlf);
+    }
+    h[i] = w;
+  }
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  asd_status st = ASD_OK;
+  auto cleanup = [&]() {
+    delete[] h;
+    (void)hipFree(out);
+    (void)hipFree(in);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+#define CEIL_HIP(x)                                                            \
+  do {                                                                         \
+    hipError_t e__ = (x);                                                      \
+    if (e__ != hipSuccess) {                                                   \
+      set_error("%s failed: %s", #x, hipGetErrorString(e__));                  \
+      cleanup();                                                               \
+      return ASD_EDEVICE;                                                      \
+    }                                                                          \
+  } while (0)
+  CEIL_HIP(hipMalloc(&out, sizeof(float) * kWgs * 256));
+  CEIL_HIP(hipMalloc(&in, sizeof(uint32_t) * kWords));
+  CEIL_HIP(hipMemcpy(in, h, sizeof(uint32_t) * kWords, hipMemcpyHostToDevice));
+  CEIL_HIP(hipEventCreate(&e0));
+  CEIL_HIP(hipEventCreate(&e1));
+  // launches of ~5 ms each (at the data-sheet rate); the rate of the second half of the run is reported
+  const int iters = bf16 ? 4000 : 250;
+  const double flop_per_launch = (double)kWgs * 4 * iters * 24 * (32.0 * 32 * (bf16 ? 16 : 2) * 2);
+  double total_ms = 0.0, last = 0.0;
+  int launches_timed = 0;
+  for (int phase = 0; phase < 2; ++phase) {
+    double phase_ms = 0.0;
+    int n = 0;
+    while (phase_ms < 0.5 * ms_target) {
+      CEIL_HIP(hipEventRecord(e0, 0));
+      for (int l = 0; l < kBatch; ++l) {   // back to back: host round trips between launches let the chip recover
+        if (bf16) hipLaunchKernelGGL(ceiling_bf16_kernel, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
+        else hipLaunchKernelGGL(ceiling_f32_kernel, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
+      }
+      CEIL_HIP(hipGetLastError());
+      CEIL_HIP(hipEventRecord(e1, 0));
+      CEIL_HIP(hipEventSynchronize(e1));
+      float ms = 0.f;
+      CEIL_HIP(hipEventElapsedTime(&ms, e0, e1));
+      phase_ms += ms;
+      n += kBatch;
+    }
+    total_ms += phase_ms;
+    last = phase_ms;
+    launches_timed = n;
+  }
+#undef CEIL_HIP
+  (void)total_ms;
+  *tflops = flop_per_launch * launches_timed / (last * 1e-3) / 1e12;
+  cleanup();
+  return st;
+}

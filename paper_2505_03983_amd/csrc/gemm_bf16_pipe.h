@@ -38,9 +38,6 @@
 
 namespace asd {
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* glb_ptr_t;
-
 // BM x BN workgroup tile, STAGES LDS stages, WGM x WGN wavefronts (each owns a (BM/WGM) x (BN/WGN) sub-tile).
 // Eight wavefronts (two per SIMD) let one wavefront's MFMAs run while its SIMD neighbour waits on the
 // address unit: a direct-to-LDS load of 1 KB occupies the CU's single address path for ~16 cycles and
@@ -64,11 +61,6 @@ struct PipeCfg16 {
   static constexpr int LA = loads_in_group(3) > 0 ? 1 : 0;
 };
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // Wait until at most `slabs` * LPS + EXTRA of this wavefront's loads are outstanding (slabs in 0..6).
 template <int LPS, int EXTRA>
 __device__ __forceinline__ void wait_vmcnt_slabs(int slabs) {
@@ -81,20 +73,6 @@ __device__ __forceinline__ void wait_vmcnt_slabs(int slabs) {
     case 5: wait_vmcnt<(5 * LPS + EXTRA <= 63 ? 5 * LPS + EXTRA : 63)>(); break;
     default: wait_vmcnt<(6 * LPS + EXTRA <= 63 ? 6 * LPS + EXTRA : 63)>(); break;
   }
-}
-
-// `pairs` times {one MFMA, then `per` instructions of class `mask`}
-template <int MASK, int PAIRS, int PER>
-__device__ __forceinline__ void sched_pairs() {
-  if constexpr (PAIRS > 0) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(MASK, PER, 0);
-    sched_pairs<MASK, PAIRS - 1, PER>();
-  }
-}
-template <int COUNT>
-__device__ __forceinline__ void sched_mfma() {
-  if constexpr (COUNT > 0) __builtin_amdgcn_sched_group_barrier(0x008, COUNT, 0);
 }
 
 template <class Cfg, class Epi, int CALL>

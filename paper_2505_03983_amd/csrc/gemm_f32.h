@@ -55,28 +55,33 @@ struct GemmCfg {
   static constexpr int RPP = THREADS / KQ;     // rows covered by one loader pass
   static constexpr int RA = BM / RPP;          // loader passes over the A tile
   static constexpr int RB = BN / RPP;          // loader passes over the B tile
+  static constexpr int WGN = 2, WM = BM / 2, WN = BN / 2;   // 2 x 2 wavefronts and their sub-tile
   static constexpr int MI = BM / 64, NJ = BN / 64;  // 32x32 blocks per wavefront
   static constexpr int KS = BK / 8;            // groups of 8 k per slab
-  static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (BM + BN) * LDSS + BM);
+  static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (BM + BN) * LDSS + 8 * BM);
   static_assert(BM % 64 == 0 && BN % 64 == 0 && BK % 8 == 0 && BM % RPP == 0 && BN % RPP == 0, "tile shape");
 };
 
-// Position of a lane's accumulators inside the workgroup tile.
+// Position of a lane's accumulators inside the workgroup tile (wavefront (wm, wn) owns a WM x WN sub-tile).
 template <class Cfg>
 struct Frag {
   int wm, wn, l32, half;
   int tile_n;  // column-tile index of the workgroup
   __device__ __forceinline__ int row(int i, int r) const {
-    return wm * (Cfg::BM / 2) + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+    return wm * Cfg::WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
   }
-  __device__ __forceinline__ int col(int j) const { return wn * (Cfg::BN / 2) + j * 32 + l32; }
+  __device__ __forceinline__ int col(int j) const { return wn * Cfg::WN + j * 32 + l32; }
 };
 
 // Op interface (all __device__, templated on Cfg where the tile shape matters):
-//   void   init<Cfg>(int m0, int M, int lrow, int lkq)   once, before the K loop; loader rows lrow + p*RPP
+//   void   init<Cfg>(int m0, int M, int lrow, int lkq, float* s_row)  once, before the K loop (a barrier follows
+//                                                          before the epilogue); loader rows lrow + p*RPP
 //   float4 load_a(float4 v, int p)                        transform of loader pass p's 4 values (not called on padding)
-//   void   finish<Cfg>(int lrow, int lkq, float* s_row)   after the K loop, before a barrier; s_row = BM floats of LDS
+//   void   finish<Cfg>(int lrow, int lkq, float* s_row)   after the K loop, before a barrier
 //   void   epilogue<Cfg>(acc, frag, m0, n0, M, N, s_row)  writes the results
+// s_row: 8 floats of LDS per tile row, the Op's own (per-row coefficients and addresses are parked there by
+// the loader threads, so that the epilogue -- whose loads the compiler may not move above its stores -- has
+// no chain of dependent global loads per row).
 // KTAIL: K is not a multiple of BK (the last slab is zero-padded).
 // Requirements (checked by the host launcher): K % 4 == 0, rows 16 B aligned.
 // CALL only gives the draft-call and verify-call launches distinct symbols in profiles.
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
   extern __shared__ __attribute__((aligned(16))) float lds[];
   float* As = lds;                       // [2][BM * LDSS]
   float* Bs = lds + 2 * BM * LDSS;       // [2][BN * LDSS]
-  float* s_row = Bs + 2 * BN * LDSS;     // [BM]
+  float* s_row = Bs + 2 * BN * LDSS;     // [8 * BM]
 
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
   const int tile_n = blockIdx.x;
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
   for (int p = 0; p < RA; ++p) ap[p] = A.row(min(m0 + lrow + RPP * p, M - 1)) + lkq * 4;
 #pragma unroll
   for (int p = 0; p < RB; ++p) bp[p] = Bm + (int64_t)min(n0 + lrow + RPP * p, N - 1) * ldb + lkq * 4;
-  op.template init<Cfg>(m0, M, lrow, lkq);
+  op.template init<Cfg>(m0, M, lrow, lkq, s_row);
   const int nk = (K + BK - 1) / BK;
 
   float4 ra[RA], rb[RB];

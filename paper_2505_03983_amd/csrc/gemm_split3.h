@@ -1,0 +1,296 @@
+// fp32 "NT" GEMM on the gfx950 *bf16* matrix cores:  acc[m][n] = sum_k f(A[m][k]) * B[n][k]
+// with every fp32 operand split into three bf16 terms.
+//
+// An fp32 number has a 24-bit significand; cut into three runs of 8 bits it is the exact sum
+// x = x1 + x2 + x3 of three bf16 numbers (bf16 has fp32's exponent range, so nothing overflows; the
+// cut is by truncation: x1 = the top 16 bits of x, x2 = the top 16 bits of x - x1, x3 = the rest).
+// A product of two bf16 numbers is exact in fp32, and the matrix cores accumulate in fp32, so
+//   a*b ~= a1*b1 + (a1*b2 + a2*b1) + (a2*b2 + a1*b3 + a3*b1)
+// leaves out only terms below 2^-24 |a||b| (a2*b3, a3*b2, a3*b3): the same order as the rounding of
+// an fp32 multiply-add.  Six bf16 MFMAs replace one fp32 MFMA of the same shape, and the bf16 matrix
+// pipe of this chip is 16x as fast as its fp32 one on paper.  In practice dense bf16 MFMA work on random
+// data is power-limited at about half the data-sheet rate (asd_mfma_ceiling measures it: ~1.3 PFLOP/s),
+// so the gain over the fp32 pipe is ~1.5x, at fp32 accuracy.  (Splitting into bf16 terms for
+// higher-precision products is an old, published device -- e.g. Henry, Tang, Heinecke 2019; the
+// arrangement here is this file's.)
+//
+// Dataflow per K slab of 16 (one MFMA group):
+//  * B is constant across calls: it is split once (split3_pack_b_kernel) into an *image* of what a
+//    workgroup's LDS stage holds -- per column tile and slab: three planes of BN rows x 32 bytes,
+//    chunk-swizzled -- so a thread copies three 16-byte pieces (one per plane) at fixed offsets:
+//    no address arithmetic, no conversion.
+//  * A arrives as fp32 (rows gathered through RowSrc, transformed by the Op's load_a): each thread
+//    owns 8 consecutive k of one row, splits them (~5 VALU operations per element) and stores three
+//    16-byte chunks, one per plane.
+//  * Both operands are loaded two slabs ahead into registers and stored into LDS one slab ahead, under the
+//    first half of the MFMAs of a slab; half-way the wavefront meets the others at the barrier and
+//    reads the fragments of the next slab under the second half.  (Direct-to-LDS loads would spare the
+//    registers of B, but the compiler then waits for *every* load in flight before each use of a
+//    loaded register -- it counts the two kinds of load as returning out of order -- which drains the
+//    prefetch once per slab.)
+//  * Two LDS stages of 3 (BM + BN) 32 bytes; with 128 x 128 tiles and four wavefronts two workgroups
+//    share a CU, and the epilogue, the prologue and the barrier waits of one are covered by the
+//    MFMAs of the other.  Chunk c (0/1) of row r sits in slot c ^ ((r >> 3) & 1) of its 32-byte row:
+//    16 consecutive rows reading the same chunk then cover all 64 banks once.
+//  * MFMA v_mfma_f32_32x32x16_bf16: lane l feeds k = 8 (l / 32) .. + 7 of row l % 32, for A and B
+//    alike, so the pairing of elements is exact; per slab a wavefront reads 3 (MI + NJ) fragments
+//    and issues 6 MI NJ MFMAs -- twice the MFMAs per fragment of a plain bf16 GEMM.
+//
+// Requirements (checked by the host): K % 16 == 0, rows of A 16-byte aligned.  Rows of the image past
+// N are zero.  M is read from device memory; workgroups past it exit at once.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "gemm_bf16.h"
+#include "gemm_f32.h"
+
+namespace asd {
+
+template <int BM_, int BN_, int WGM_ = 2, int WGN_ = 2>
+struct Split3Cfg {
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, BK = 16, STAGES = 2;
+  static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
+  static constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NJ = WN / 32;
+  static constexpr int KQ = 2;                   // loader threads per row of A (8 k each)
+  static constexpr int RPP = THREADS / KQ;       // rows covered by one loader pass
+  static constexpr int RA = BM / RPP;            // loader passes over the A tile
+  static constexpr int A_PLANE = BM * 32, B_PLANE = BN * 32;      // bytes of one plane of a slab
+  static constexpr int A_STAGE = 3 * A_PLANE, B_STAGE = 3 * B_PLANE;
+  static constexpr int B_LOADS = B_STAGE / (16 * THREADS);        // 16-byte pieces of a slab's B image per thread
+  static constexpr size_t LDS_BYTES = (size_t)STAGES * (A_STAGE + B_STAGE) + sizeof(float) * 8 * BM;
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % RPP == 0 && B_STAGE % (16 * THREADS) == 0, "tile shape");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+// Bytes of the B image for an [N, K] operand.
+template <class Cfg>
+inline size_t split3_image_bytes(int N, int K) {
+  return (size_t)((N + Cfg::BN - 1) / Cfg::BN) * (size_t)(K / 16) * Cfg::B_STAGE;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// x[0..7] -> three planes of 8 bf16 each (element 0 in the low half of word 0)
+__device__ __forceinline__ void split3_pack(const float (&x)[8], u32x4& p1, u32x4& p2, u32x4& p3) {
+  uint32_t w1[4], w2[4], w3[4];
+  constexpr uint32_t kHiHalves = 0x07060302u;   // v_perm_b32: {S0[31:16], S1[31:16]}
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float xa = x[2 * j], xb = x[2 * j + 1];
+    const uint32_t ua = __float_as_uint(xa), ub = __float_as_uint(xb);
+    w1[j] = __builtin_amdgcn_perm(ub, ua, kHiHalves);
+    const float ra = xa - __uint_as_float(ua & 0xffff0000u), rb = xb - __uint_as_float(ub & 0xffff0000u);
+    const uint32_t va = __float_as_uint(ra), vb = __float_as_uint(rb);
+    w2[j] = __builtin_amdgcn_perm(vb, va, kHiHalves);
+    const float ta = ra - __uint_as_float(va & 0xffff0000u), tb = rb - __uint_as_float(vb & 0xffff0000u);
+    w3[j] = __builtin_amdgcn_perm(__float_as_uint(tb), __float_as_uint(ta), kHiHalves);
+  }
+  p1 = u32x4{w1[0], w1[1], w1[2], w1[3]};
+  p2 = u32x4{w2[0], w2[1], w2[2], w2[3]};
+  p3 = u32x4{w3[0], w3[1], w3[2], w3[3]};
+}
+
+// B [N, K] fp32 (row stride ldb) -> image.  One thread per (row of the padded tile grid, chunk of 8 k).
+template <class Cfg>
+__global__ __launch_bounds__(256) void split3_pack_b_kernel(const float* __restrict__ B, int64_t ldb, int N, int K,
+                                                            uint8_t* __restrict__ img) {
+  const int kc = K / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t n_pad = (int64_t)((N + Cfg::BN - 1) / Cfg::BN) * Cfg::BN;
+  if (idx >= n_pad * kc) return;
+  const int n = (int)(idx / kc), c8 = (int)(idx % kc);
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = n < N ? B[(int64_t)n * ldb + c8 * 8 + e] : 0.f;
+  u32x4 p[3];
+  split3_pack(x, p[0], p[1], p[2]);
+  const int tn = n / Cfg::BN, r = n % Cfg::BN, ks = c8 >> 1, c = c8 & 1;
+  uint8_t* dst = img + ((int64_t)tn * (K / 16) + ks) * Cfg::B_STAGE + r * 32 + ((c ^ ((r >> 3) & 1)) * 16);
+#pragma unroll
+  for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<u32x4*>(dst + pl * Cfg::B_PLANE) = p[pl];
+}
+
+template <class Cfg>
+inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K, uint8_t* img, hipStream_t st) {
+  const int64_t n_pad = (int64_t)((N + Cfg::BN - 1) / Cfg::BN) * Cfg::BN;
+  const int64_t threads = n_pad * (K / 8);
+  hipLaunchKernelGGL(split3_pack_b_kernel<Cfg>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, B, ldb, N, K,
+                     img);
+  return hipGetLastError();
+}
+
+// The Op interface is that of gemm_f32.h (init / load_a / finish / epilogue); load_a is applied when
+// the values are split, not when they are loaded.
+template <class Cfg, class Op, int CALL>
+__global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
+                                                                         int N, int K, RowSrc A,
+                                                                         const uint8_t* __restrict__ Bimg, Op op) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ;
+  constexpr int RA = Cfg::RA, RPP = Cfg::RPP, A_PLANE = Cfg::A_PLANE, B_PLANE = Cfg::B_PLANE;
+  constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS;
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
+  uint8_t* lds_a = lds_all;                                   // [2 stages][3 planes][BM rows][32 bytes]
+  uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][3 planes][BN rows][32 bytes]
+  float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
+
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  const int tile_n = blockIdx.x;
+  const int m0 = blockIdx.y * BM, n0 = tile_n * BN;
+  if (m0 >= M) return;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const Frag<Cfg> fr{wave / Cfg::WGN, wave % Cfg::WGN, lane & 31, lane >> 5, tile_n};
+  const int nk = K / 16;
+
+  // ---- loaders.  A: thread = (row lrow + RPP p, chunk lkq of 8 k).  B: thread t copies bytes 16 t + 16 THREADS q
+  // of a slab's image.  Slab j waits in register slot j & 1 and goes to LDS stage j & 1.
+  const int lrow = tid >> 1, lkq = tid & 1;
+  const float* ap[RA];
+  int a_dst[RA];
+#pragma unroll
+  for (int p = 0; p < RA; ++p) {
+    const int r = lrow + RPP * p;
+    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8;
+    a_dst[p] = r * 32 + ((lkq ^ ((r >> 3) & 1)) * 16);
+  }
+  op.template init<Cfg>(m0, M, lrow, lkq, s_row);
+  const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk * B_STAGE + tid * 16;
+  float4 ra[2][RA][2];
+  u32x4 rb[2][B_LOADS];
+  auto gload = [&](int kt, auto slot) {
+#pragma unroll
+    for (int p = 0; p < RA; ++p) {
+      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * 16);
+      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * 16 + 4);
+    }
+#pragma unroll
+    for (int q = 0; q < B_LOADS; ++q)
+      rb[slot][q] = *reinterpret_cast<const u32x4*>(bsrc + (int64_t)kt * B_STAGE + q * 16 * Cfg::THREADS);
+  };
+  auto sstore = [&](auto slot) {   // register slot `slot` -> LDS stage `slot`
+    uint8_t* sa = lds_a + slot * A_STAGE;
+    uint8_t* sb = lds_b + slot * B_STAGE + tid * 16;
+#pragma unroll
+    for (int q = 0; q < B_LOADS; ++q) *reinterpret_cast<u32x4*>(sb + q * 16 * Cfg::THREADS) = rb[slot][q];
+#pragma unroll
+    for (int p = 0; p < RA; ++p) {
+      const float4 v0 = op.load_a(ra[slot][p][0], p), v1 = op.load_a(ra[slot][p][1], p);
+      const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      u32x4 p1, p2, p3;
+      split3_pack(x, p1, p2, p3);
+      *reinterpret_cast<u32x4*>(sa + a_dst[p]) = p1;
+      *reinterpret_cast<u32x4*>(sa + A_PLANE + a_dst[p]) = p2;
+      *reinterpret_cast<u32x4*>(sa + 2 * A_PLANE + a_dst[p]) = p3;
+    }
+  };
+
+  v16f acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // ---- fragments (tile and sub-tile offsets are multiples of 32 rows, so the swizzle key depends on l32 only)
+  const int f_off = fr.l32 * 32 + ((fr.half ^ ((fr.l32 >> 3) & 1)) * 16);
+  const uint8_t* fa = lds_a + fr.wm * Cfg::WM * 32 + f_off;
+  const uint8_t* fb = lds_b + fr.wn * Cfg::WN * 32 + f_off;
+  v8bf af[2][3][MI], bf[2][3][NJ];
+  auto read_frags = [&](auto stage) {   // LDS stage `stage` -> fragment buffer `stage`
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+        af[stage][pl][i] = *reinterpret_cast<const v8bf*>(fa + stage * A_STAGE + pl * A_PLANE + i * 32 * 32);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        bf[stage][pl][j] = *reinterpret_cast<const v8bf*>(fb + stage * B_STAGE + pl * B_PLANE + j * 32 * 32);
+    }
+  };
+  constexpr int G = MI * NJ, NM = 6 * G;     // MFMAs per plane pair and per slab
+  auto mma = [&](auto buf, int first, int count) {   // MFMAs first .. first+count-1 of a slab
+    constexpr int pa[6] = {0, 0, 1, 1, 0, 2};
+    constexpr int pb[6] = {0, 1, 0, 1, 2, 0};
+#pragma unroll
+    for (int q = 0; q < NM; ++q)
+      if (q >= first && q < first + count) {
+        const int pr = q / G, i = (q % G) / NJ, j = q % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][pa[pr]][i], bf[buf][pb[pr]][j], acc[i][j], 0, 0, 0);
+      }
+  };
+  // this wavefront's LDS stores have completed; then meet the others (no fence: global loads stay in flight)
+  auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  typedef std::integral_constant<int, 0> I0;
+  typedef std::integral_constant<int, 1> I1;
+  // ---- prologue: slab 0 into stage 0, slab 1 on its way into registers
+  gload(0, I0());
+  if (nk > 1) gload(1, I1());
+  sstore(I0());
+  lds_barrier();
+  read_frags(I0());
+
+  // One slab, par = kt & 1.  steady: slabs kt+1 and kt+2 exist -- no branches, so that the interleaving
+  // below holds (a scheduling group does not cross a branch).
+  auto slab = [&](int kt, auto par, auto npar, auto steady) {
+    const bool l2 = steady || kt + 2 < nk, s1 = steady || kt + 1 < nk;
+    __builtin_amdgcn_s_setprio(2);
+    if (l2) gload(kt + 2, par);     // slot par held slab kt, which went to LDS during slab kt-1
+    mma(par, 0, NM / 2);
+    if (s1) sstore(npar);           // stage npar: its last readers (slab kt-1) passed the barrier of slab kt-1
+    if (steady) {
+      // first half: a load behind each of the first MFMAs, then the copy and the split spread over the rest
+      constexpr int NL = B_LOADS + 2 * RA, NV = NM / 2 - NL;
+      sched_pairs<0x020, NL, 1>();
+      sched_pairs<0x002, NV, (44 * RA + NV - 1) / NV>();
+    }
+    if (s1) {
+      lds_barrier();
+      read_frags(npar);
+    }
+    mma(par, NM / 2, NM - NM / 2);
+    if (steady) sched_pairs<0x100, NM - NM / 2, (3 * (MI + NJ) + NM - NM / 2 - 1) / (NM - NM / 2)>();
+    __builtin_amdgcn_s_setprio(0);
+  };
+  typedef std::integral_constant<bool, true> Steady;
+  typedef std::integral_constant<bool, false> Tail;
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    slab(kt, I0(), I1(), Steady());
+    slab(kt + 1, I1(), I0(), Steady());
+  }
+  for (; kt < nk; kt += 2) {
+    slab(kt, I0(), I1(), Tail());
+    if (kt + 1 < nk) slab(kt + 1, I1(), I0(), Tail());
+  }
+  __syncthreads();   // every wavefront is done with the operand stages
+
+  op.template finish<Cfg>(lrow, lkq, s_row);
+  __syncthreads();
+  op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
+}
+
+template <class Cfg, int CALL, class Op>
+inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
+                                        Op op, hipStream_t st) {
+  if (K % 16 != 0 || K <= 0) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM));
+  auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL>;
+  static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)Cfg::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bimg, op);
+  return hipGetLastError();
+}
+
+}  // namespace asd

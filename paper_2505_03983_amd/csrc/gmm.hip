@@ -21,6 +21,7 @@
 //    final affine combination fused in the epilogue.
 #include "common.h"
 #include "gemm_f32.h"
+#include "gemm_split3.h"
 #include "gmm_state.h"
 
 namespace asd {
@@ -29,6 +30,8 @@ namespace asd {
 // combine GEMM): 128x128x16 74 / 76%, 128x128x32 71 / 71%, 256x128x16 60 / 56%, 256x128x32 61 / 42%.
 typedef GemmCfg<128, 128, 16> GmmTile;
 typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one row per chain, fill the chip
+// verify call on the bf16 matrix pipe with three-way split operands (fp32 accuracy)
+typedef Split3Cfg<128, 128, 2, 2> GmmTileSplit;
 
 // (kappa, gamma, cx, cm) of a row
 __device__ __forceinline__ float4 row_coef(const float4* coef_tau, const int32_t* tau, int n) {
@@ -221,28 +224,38 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
 // matrix-core path
 // ---------------------------------------------------------------------------
 // GEMM 1: logits.  The epilogue applies the affine map, stores the logits and
-// the maximum of each row over the 64 columns the wavefront owns
-// (pmax[row][2*column_tile + wn]); the softmax normalisation is finished
+// the maximum of each row over the columns the wavefront owns
+// (pmax[row][WGN*column_tile + wn]); the softmax normalisation is finished
 // inside GEMM 2, so the logits are written once and read once.
 struct LogitOp {
   float* logits;
   int64_t ld;
   float* pmax;
-  int np;  // partial maxima per row = 2 * number of column tiles
+  int np;  // partial maxima per row = (wavefronts across a tile) * (number of column tiles)
   const float4* coef_tau;
   const int32_t* tau;
   const float* musq;
   const float* log_w;
+  static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
+  // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
-  __device__ __forceinline__ void init(int, int, int, int) {}
+  __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq, float* s_row) {
+    if (lkq != 0) return;
+#pragma unroll
+    for (int p = 0; p < Cfg::RA; ++p) {
+      const int r = lrow + Cfg::RPP * p;
+      const float4 cf = coef_tau[tau[min(m0 + r, M - 1)]];
+      s_row[8 * r + 1] = kLog2e * cf.x;
+      s_row[8 * r + 2] = kLog2e * cf.y;
+    }
+  }
   __device__ __forceinline__ float4 load_a(float4 v, int) const { return v; }
   template <class Cfg>
   __device__ __forceinline__ void finish(int, int, float*) {}
   template <class Cfg>
   __device__ __forceinline__ void epilogue(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0, int n0,
-                                           int M, int N, const float*) const {
+                                           int M, int N, const float* s_row) const {
     constexpr int MI = Cfg::MI, NJ = Cfg::NJ;
-    constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
     float bias[NJ], q[NJ];
     bool nok[NJ];
     int n[NJ];
@@ -251,20 +264,21 @@ struct LogitOp {
       const int nn = n0 + fr.col(j);
       nok[j] = nn < N;
       n[j] = nok[j] ? nn : N - 1;
-      bias[j] = log_w[n[j]];
+      bias[j] = kLog2e * log_w[n[j]];
       q[j] = musq[n[j]];
     }
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + fr.row(i, r);
+        const int ml = fr.row(i, r);
+        const int m = m0 + ml;
         const bool mok = m < M;
-        const float4 cf = coef_tau[tau[mok ? m : M - 1]];
+        const float c1 = s_row[8 * ml + 1], c2 = s_row[8 * ml + 2];
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-          const float v = kLog2e * fmaf(cf.x, acc[i][j][r], fmaf(-cf.y, q[j], bias[j]));
+          const float v = fmaf(c1, acc[i][j][r], fmaf(-c2, q[j], bias[j]));
           if (nok[j]) {
             mx = fmaxf(mx, v);
             if (mok) logits[(int64_t)m * ld + n[j]] = v;
@@ -277,7 +291,7 @@ struct LogitOp {
         mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xf, 0xf, true)));
         mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xf, 0xf, true)));
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        if (mok && fr.l32 == 0) pmax[(int64_t)m * np + 2 * fr.tile_n + fr.wn] = mx;
+        if (mok && fr.l32 == 0) pmax[(int64_t)m * np + Cfg::WGN * fr.tile_n + fr.wn] = mx;
       }
     }
   }
@@ -298,18 +312,27 @@ struct CombineOp {
   static constexpr int kMaxPasses = 8;
   float rmax[kMaxPasses];
   float rsum[kMaxPasses];
+  // s_row[8 r ..]: row sum, c_x', c_m', -, in_off (8 bytes), out_off (8 bytes) of tile row r
   template <class Cfg>
-  __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq) {
+  __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq, float* s_row) {
     static_assert(Cfg::RA <= kMaxPasses, "loader passes");
 #pragma unroll
     for (int p = 0; p < Cfg::RA; ++p) {
-      const int m = min(m0 + lrow + Cfg::RPP * p, M - 1);
+      const int r = lrow + Cfg::RPP * p;
+      const int m = min(m0 + r, M - 1);
       float mx = -INFINITY;
       for (int q = lkq; q < np; q += Cfg::KQ) mx = fmaxf(mx, pmax[(int64_t)m * np + q]);
 #pragma unroll
       for (int o = 1; o < Cfg::KQ; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // the KQ lanes of a row are adjacent
       rmax[p] = mx;
       rsum[p] = 0.f;
+      if (lkq == 0) {
+        const float4 cf = coef_tau[tau[m]];
+        s_row[8 * r + 1] = cf.z;
+        s_row[8 * r + 2] = cf.w;
+        *reinterpret_cast<int64_t*>(&s_row[8 * r + 4]) = in_off[m];
+        *reinterpret_cast<int64_t*>(&s_row[8 * r + 6]) = out_off[m];
+      }
     }
   }
   // logits are in base-2 units: p = 2^(l - rowmax) <= 1
@@ -327,27 +350,40 @@ struct CombineOp {
       float s = rsum[p];
 #pragma unroll
       for (int o = 1; o < Cfg::KQ; o <<= 1) s += __shfl_xor(s, o, 64);
-      if (lkq == 0) s_row[lrow + Cfg::RPP * p] = s;
+      if (lkq == 0) s_row[8 * (lrow + Cfg::RPP * p)] = s;
     }
   }
   template <class Cfg>
   __device__ __forceinline__ void epilogue(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0, int n0,
                                            int M, int N, const float* s_row) const {
+    constexpr int NJ = Cfg::NJ, RB = 8;   // rows per batch: all of a batch's reads of x are issued before its stores
 #pragma unroll
     for (int i = 0; i < Cfg::MI; ++i) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int ml = fr.row(i, r);
-        const int m = m0 + ml;
-        if (m >= M) continue;
-        const float4 cf = coef_tau[tau[m]];
-        const float scale = cf.w / s_row[ml];
-        const float* x = in_base + in_off[m];
-        float* o = out_base + out_off[m];
+      for (int r0 = 0; r0 < 16; r0 += RB) {
+        float xv[RB][NJ];
 #pragma unroll
-        for (int j = 0; j < Cfg::NJ; ++j) {
-          const int n = n0 + fr.col(j);
-          if (n < N) o[n] = fmaf(cf.z, x[n], scale * acc[i][j][r]);
+        for (int rr = 0; rr < RB; ++rr) {
+          const int ml = fr.row(i, r0 + rr);
+          const float* x = in_base + *reinterpret_cast<const int64_t*>(&s_row[8 * ml + 4]);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            const int n = n0 + fr.col(j);
+            xv[rr][j] = (m0 + ml < M && n < N) ? x[n] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr) {
+          const int ml = fr.row(i, r0 + rr);
+          if (m0 + ml >= M) continue;
+          const float cz = s_row[8 * ml + 1];
+          const float scale = s_row[8 * ml + 2] / s_row[8 * ml];
+          float* o = out_base + *reinterpret_cast<const int64_t*>(&s_row[8 * ml + 6]);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            const int n = n0 + fr.col(j);
+            if (n < N) o[n] = fmaf(cz, xv[rr][j], scale * acc[i][j][r0 + rr]);
+          }
         }
       }
     }
@@ -418,8 +454,16 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
                                   160 * 1024));
     }
   }
+  if (g->use_mfma && d % 16 == 0 && C % 16 == 0) {
+    ASD_HIP(hipMalloc(&g->means_img, split3_image_bytes<GmmTileSplit>(C, d)));
+    ASD_HIP(hipMalloc(&g->means_t_img, split3_image_bytes<GmmTileSplit>(d, C)));
+    ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means, d, C, d, g->means_img, 0));
+    ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means_t, C, d, C, g->means_t_img, 0));
+    ASD_HIP(hipDeviceSynchronize());
+    g->split_ok = g->use_split = true;
+  }
   if (g->use_mfma) {
-    g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finer of the two tilings
+    g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finest of the tilings
     ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
     ASD_HIP(hipMalloc(&g->pmax, sizeof(float) * (size_t)ctx->n_rows_max * g->np));
   }
@@ -430,6 +474,8 @@ void gmm_destroy(asd_ctx* ctx) {
   GmmState* g = ctx->gmm;
   if (!g) return;
   (void)hipFree(g->means_t);
+  (void)hipFree(g->means_img);
+  (void)hipFree(g->means_t_img);
   (void)hipFree(g->musq);
   (void)hipFree(g->coef_tau);
   (void)hipFree(g->logits);
@@ -460,21 +506,25 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     ASD_HIP(hipGetLastError());
     return ASD_OK;
   }
-  // partial row maxima per row: two per column tile of the tiling in use
-  const int np = 2 * (int)ceil_div(C, rows.call ? GmmTile::BN : GmmTileSkinny::BN);
+  // partial row maxima per row: one per wavefront column of the tiling in use
+  const bool split = rows.call == 1 && g->use_split;
+  const int np = split ? GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN)
+                       : 2 * (int)ceil_div(C, rows.call ? GmmTile::BN : GmmTileSkinny::BN);
   RowSrc X{rows.in_base, rows.in_off, 0};
   LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
-                      : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
+    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
+            : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
+                        : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
   RowSrc P{g->logits, nullptr, C};
   CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
-                      : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st));
+    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
+            : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
+                        : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st));
   }
   return ASD_OK;
 }

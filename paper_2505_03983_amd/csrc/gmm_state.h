@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <stdint.h>
 
 namespace asd {
 
@@ -17,6 +18,11 @@ struct GmmState {
   float* pmax = nullptr;         // [rows_max, np] partial row maxima of the logits
   int np = 0;
   bool use_mfma = false;
+  // split-bf16 verify GEMMs (gemm_split3.h): the means, split and laid out as LDS images, for both GEMMs
+  uint8_t* means_img = nullptr;    // B of the logits GEMM  ([C, d])
+  uint8_t* means_t_img = nullptr;  // B of the combine GEMM ([d, C])
+  bool split_ok = false;           // the shape allows them
+  bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
   size_t rowwise_lds = 0;
   size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
 };

@@ -117,6 +117,13 @@ def test_null_handles():
     assert L.asd_sample(None, None, None, None, None) == binding.ASD_EINVAL
     assert L.asd_last_round_count(None) == -1
     assert "NULL" in binding.last_error()
-    for name in ("asd_use_graphs", "asd_use_resident", "asd_use_adaptive_window"):
+    for name in ("asd_use_graphs", "asd_use_resident", "asd_use_adaptive_window", "asd_use_split_gemm"):
         assert getattr(L, name)(None, 1) == binding.ASD_EINVAL, name
     assert L.asd_resident_active(None) == 0
+    assert L.asd_split_gemm_active(None) == 0
+    # argument checks of the ceiling probe come before any device call
+    assert L.asd_mfma_ceiling(1, 1, 100, None) == binding.ASD_EINVAL
+    import ctypes
+    t = ctypes.c_double(0.0)
+    assert L.asd_mfma_ceiling(1, 1, 0, ctypes.addressof(t)) == binding.ASD_EINVAL
+    assert L.asd_mfma_ceiling(0, 0, 5001, ctypes.addressof(t)) == binding.ASD_EINVAL

@@ -60,12 +60,15 @@ def test_normals_and_uniforms_match_oracle():
 # ---------------------------------------------------------------------------
 # denoisers
 # ---------------------------------------------------------------------------
-def _denoise_case(cfg, n_rows, seed=0, chains=None, L=None, out_clip=None):
+def _denoise_case(cfg, n_rows, seed=0, chains=None, L=None, out_clip=None, split=None):
     T, p, model = oracle_setup(cfg)
     if out_clip is not None:
         p["out_clip"] = out_clip
         model = mlp_model(T, p)
     ctx = runtime.open_ctx(cfg, p, seed=seed, chains=chains, L=L)
+    if split is not None:
+        ctx.use_split_gemm(split)
+        assert ctx.split_gemm_active() == bool(split and cfg["d"] % 16 == 0 and cfg["C"] % 16 == 0)
     rng = np.random.default_rng(seed)
     tau = rng.integers(1, cfg["K"] + 1, n_rows).astype(np.int32)
     ab = T["abar"][tau]
@@ -98,15 +101,21 @@ def test_gmm_rowwise_denoiser(shape):
     assert e <= 1e-4
 
 
-@pytest.mark.parametrize("shape", [dict(d=128, C=384, rows=300), dict(d=36, C=132, rows=131), dict(d=1024, C=4096, rows=160)])
-def test_gmm_matrix_core_denoiser(shape):
+@pytest.mark.parametrize("split", [True, False])
+@pytest.mark.parametrize("shape", [dict(d=128, C=384, rows=300), dict(d=36, C=132, rows=131), dict(d=1024, C=4096, rows=160),
+                                   dict(d=48, C=272, rows=700), dict(d=16, C=16, rows=129)])
+def test_gmm_matrix_core_denoiser(shape, split):
+    """Both forms of the verify GEMMs (fp32 MFMA; bf16 MFMA on three-way split operands, taken when d and C
+    are multiples of 16) against the fp64 oracle, to the same tolerance: ragged last row tile, C and d
+    that are not multiples of the tile, one slab of K."""
+    shape = dict(shape)
     rows = shape.pop("rows")
     # enough rows*C*d to select the matrix-core path
     chains = max(8, -(-rows // 16), int(np.ceil((1 << 26) / (shape["C"] * shape["d"] * 16))) + 1)
     cfg = dict(kind="gmm", K=50, chains=chains, L=16, var=0.25, **shape)
-    got, want = _denoise_case(cfg, rows)
+    got, want = _denoise_case(cfg, rows, split=split)
     e = H.rel_err(got, want)
-    _log("gmm mfma", shape, "rows", rows, "rel err", e)
+    _log("gmm mfma", shape, "split", split, "rows", rows, "rel err", e)
     assert e <= 1e-4
 
 
@@ -545,12 +554,15 @@ def test_stage_order_is_enforced():
 # full-size workloads in the launch configuration bench.py times: one round from synthetic
 # mid-run states, sampled chains checked against the oracle, all chains against invariants
 # ---------------------------------------------------------------------------
-def _full_size_round(w, sampled, seed=0):
+def _full_size_round(w, sampled, seed=0, split=None):
     cfg = W.CONFIGS[w]
     T, p, model = oracle_setup(cfg)
     tol = H.TOL[cfg["kind"]]
     B, K, L, d = cfg["chains"], cfg["K"], cfg["L"], cfg["d"]
     ctx = runtime.open_ctx(cfg, p, seed=seed)
+    if split is not None:
+        ctx.use_split_gemm(split)
+        assert ctx.split_gemm_active() == split
     rng = np.random.default_rng(seed + 100 * w)
     # states: start, middle, a window cut by K, a finished chain
     choices = np.array([0, K // 3, (2 * K) // 3, K - L // 2, K - 1, K])
@@ -607,5 +619,6 @@ def test_round_config4_full_size_sampled():
     _full_size_round(4, sampled=[0, 31, 63])
 
 
-def test_round_config5_full_size_sampled():
-    _full_size_round(5, sampled=[0, 517, 1023])
+@pytest.mark.parametrize("split", [True, False])
+def test_round_config5_full_size_sampled(split):
+    _full_size_round(5, sampled=[0, 517, 1023], split=split)
