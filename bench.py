@@ -32,7 +32,9 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 1 GiB copy in the same run);
 # see profiles/cfg5_gmm_verify_gemm_hbm_traffic.txt for the commands and the raw readings.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    (5, "GMM_LOGITS/verify", "f32"): 1024.0 * (2.0 * 1137560.1 + 758386.0),
+    (5, "GMM_LOGITS/verify", "bf16"): 1024.0 * (2.0 * 1229850.2 + 747404.7),     # split-operand kernels (default)
+    (5, "GMM_COMBINE/verify", "bf16"): 1024.0 * (2.0 * 1695031.3 + 175748.3),
+    (5, "GMM_LOGITS/verify", "f32"): 1024.0 * (2.0 * 1137560.1 + 758386.0),      # fp32 MFMA kernels (--fp32-mfma)
     (5, "GMM_COMBINE/verify", "f32"): 1024.0 * (2.0 * 3308168.4 + 175748.3),
 }
 
@@ -272,7 +274,8 @@ def main():
         line["hbm_kernels"] = hbm_kernels(res)
         line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
                                "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
-    if not args.plain:
+    if not args.plain and args.others:
+        # (skipped with --others 0, so that a profiler run of this script sees the sampling kernels only)
         # what the matrix pipes of this chip sustain on random operands with no memory traffic at all (the chip is
         # power-limited on dense MFMA work: the data-sheet peaks above hold for constant operands only)
         from paper_2505_03983_amd import binding

@@ -124,7 +124,13 @@ inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K
 
 // The Op interface is that of gemm_f32.h (init / load_a / finish / epilogue); load_a is applied when
 // the values are split, not when they are loaded.
-template <class Cfg, class Op, int CALL>
+//
+// Tile order.  Workgroups go to the 8 XCDs round-robin by linear id (x fastest).  ROWS_PER_XCD = false: blockIdx.x
+// = column tile, so an XCD keeps a fixed set of column tiles (its share of B stays in its L2) and every XCD
+// streams all of A.  ROWS_PER_XCD = true, for an A that is large and a B that is re-read anyway (the second
+// GEMM of the mixture denoiser: A = 1 GB of logits, 8 column tiles): all column tiles of a row tile run on one
+// XCD, back to back, so a tile of A crosses the fabric once instead of once per XCD.
+template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
 __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
                                                                          int N, int K, RowSrc A,
                                                                          const uint8_t* __restrict__ Bimg, Op op) {
@@ -137,8 +143,15 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
 
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
-  const int tile_n = blockIdx.x;
-  const int m0 = blockIdx.y * BM, n0 = tile_n * BN;
+  int tile_n = blockIdx.x, tile_m = blockIdx.y;
+  if (ROWS_PER_XCD) {
+    // linear id = 8 ntn G + r: XCD r % 8 takes row tile 8 G + r % 8, column tile r / 8 (grid.y is a multiple of 8)
+    const unsigned ntn = gridDim.x, lin = blockIdx.x + ntn * blockIdx.y;
+    const unsigned G = lin / (8 * ntn), r = lin % (8 * ntn);
+    tile_m = (int)(8 * G + r % 8);
+    tile_n = (int)(r / 8);
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   if (m0 >= M) return;
 
   const int tid = threadIdx.x;
@@ -276,12 +289,14 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
-template <class Cfg, int CALL, class Op>
+template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
                                         Op op, hipStream_t st) {
   if (K % 16 != 0 || K <= 0) return hipErrorInvalidValue;
-  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM));
-  auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL>;
+  unsigned mt = (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM);
+  if (ROWS_PER_XCD) mt = (mt + 7) / 8 * 8;
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), mt);
+  auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL, ROWS_PER_XCD>;
   static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,

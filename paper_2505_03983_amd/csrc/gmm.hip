@@ -514,7 +514,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
+    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
             : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
@@ -522,7 +522,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
+    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
             : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st));
   }
