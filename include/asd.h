@@ -282,6 +282,16 @@ ASD_API asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t m
 ASD_API asd_status asd_schedule_ddpm_linear(int32_t K, double beta_min, double beta_max,
                                     float* c_x, float* c_0, float* sigma, int32_t* tau, float* abar);
 
+/* The same coefficients for any variance-preserving schedule given by its abar[0..K] (HOST, double; abar[0] = 1,
+ * strictly decreasing, abar[K] > 0): beta_tau = 1 - abar[tau]/abar[tau-1].  Cosine, sigmoid, learned ... schedules
+ * enter through this.  Outputs as above (any may be NULL; abar_f32 [K+1] is the fp32 copy a GMM or
+ * noise-predicting denoiser takes). */
+ASD_API asd_status asd_schedule_from_abar(int32_t K, const double* abar, float* c_x, float* c_0, float* sigma,
+                                  int32_t* tau, float* abar_f32);
+/* abar[0..K] (HOST, double) of the cosine schedule, abar ~ cos^2(((tau/K + s)/(1 + s)) pi/2), with every beta
+ * clipped at beta_clip (Nichol & Dhariwal 2021 use s = 0.008, beta_clip = 0.999). */
+ASD_API asd_status asd_abar_cosine(int32_t K, double s, double beta_clip, double* abar);
+
 ASD_API const char* asd_status_string(asd_status s);
 /* Message of the last failure on this thread ("" if none). */
 ASD_API const char* asd_last_error(void);

@@ -29,6 +29,33 @@ def linear_beta_abar(K, beta_min=1e-4, beta_max=0.02):
     return np.concatenate([[0.0], beta]), abar
 
 
+def cosine_abar(K, s=0.008, beta_clip=0.999):
+    """abar[tau], tau = 0..K, of the cosine noise schedule (Nichol & Dhariwal 2021): abar proportional to
+    cos^2(((tau/K + s) / (1 + s)) pi / 2), each beta = 1 - abar[tau]/abar[tau-1] clipped at beta_clip (the
+    unclipped last beta is 1: abar[K] = 0 would make the first model call meaningless)."""
+    f = np.cos((np.arange(K + 1, dtype=np.float64) / K + s) / (1.0 + s) * np.pi / 2.0) ** 2
+    beta = np.minimum(1.0 - f[1:] / f[:-1], beta_clip)
+    return np.concatenate([[1.0], np.cumprod(1.0 - beta)])
+
+
+def tables_from_abar(abar):
+    """The same translate-to-SL / Euler step / map-back coefficients for any decreasing abar[0..K] with
+    abar[0] = 1 (beta[tau] = 1 - abar[tau]/abar[tau-1]).  Returns dict(c_x, c_0, sigma, tau [K]; abar)."""
+    abar = np.asarray(abar, dtype=np.float64)
+    K = len(abar) - 1
+    c_x, c_0, sigma = np.empty(K), np.empty(K), np.empty(K)
+    tau = np.empty(K, dtype=np.int64)
+    for i in range(K):
+        t = K - i
+        tau[i] = t
+        alpha = abar[t] / abar[t - 1]
+        shrink = (1.0 - abar[t - 1]) / (1.0 - abar[t])
+        c_x[i] = np.sqrt(alpha) * shrink
+        c_0[i] = np.sqrt(abar[t - 1]) * (1.0 - alpha) / (1.0 - abar[t])
+        sigma[i] = np.sqrt((1.0 - alpha) * shrink)
+    return dict(c_x=c_x, c_0=c_0, sigma=sigma, tau=tau, abar=abar)
+
+
 def ddpm_tables(K, beta_min=1e-4, beta_max=0.02):
     """Per-step coefficients of  y_{i+1} = c_x y_i + c_0 D(y_i, tau_i) + sigma xi.
 

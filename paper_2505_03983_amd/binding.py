@@ -77,6 +77,8 @@ def lib():
             "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
             "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
+            "asd_schedule_from_abar": (i32, [i32, vp, vp, vp, vp, vp, vp]),
+            "asd_abar_cosine": (i32, [i32, C.c_double, C.c_double, vp]),
             "asd_status_string": (C.c_char_p, [i32]),
             "asd_last_error": (C.c_char_p, []),
         }
@@ -127,6 +129,24 @@ def asd_schedule_ddpm_linear(K, beta_min=1e-4, beta_max=0.02):
                                           _ptr(out["c_0"]), _ptr(out["sigma"]), _ptr(out["tau"]),
                                           _ptr(out["abar"])))
     return out
+
+
+def asd_schedule_from_abar(abar):
+    """Host tables for a variance-preserving schedule given by abar[0..K] (float64)."""
+    abar = np.ascontiguousarray(abar, dtype=np.float64)
+    n = len(abar) - 1
+    out = dict(c_x=np.zeros(max(n, 0), np.float32), c_0=np.zeros(max(n, 0), np.float32),
+               sigma=np.zeros(max(n, 0), np.float32), tau=np.zeros(max(n, 0), np.int32),
+               abar=np.zeros(max(n, 0) + 1, np.float32))
+    _check(lib().asd_schedule_from_abar(n, _ptr(abar), _ptr(out["c_x"]), _ptr(out["c_0"]), _ptr(out["sigma"]),
+                                        _ptr(out["tau"]), _ptr(out["abar"])))
+    return out
+
+
+def asd_abar_cosine(K, s=0.008, beta_clip=0.999):
+    abar = np.zeros(max(int(K), 0) + 1, np.float64)
+    _check(lib().asd_abar_cosine(int(K), float(s), float(beta_clip), _ptr(abar)))
+    return abar
 
 
 def make_config(sched, den, L, chains, seed):

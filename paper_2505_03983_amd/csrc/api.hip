@@ -529,6 +529,46 @@ asd_status asd_schedule_ddpm_linear(int32_t K, double beta_min, double beta_max,
   return ASD_OK;
 }
 
+asd_status asd_schedule_from_abar(int32_t K, const double* abar, float* c_x, float* c_0, float* sigma, int32_t* tau,
+                                  float* abar_f32) {
+  if (K < 1 || !abar) return fail(ASD_EINVAL, "K must be >= 1 and abar non-NULL");
+  if (abar[0] != 1.0) return fail(ASD_EINVAL, "abar[0] must be 1");
+  for (int t = 1; t <= K; ++t)
+    if (!(abar[t] > 0.0) || !(abar[t] < abar[t - 1])) return fail(ASD_EINVAL, "abar must decrease strictly and stay positive (tau = %d)", t);
+  if (abar_f32) abar_f32[0] = 1.0f;
+  for (int t = 1; t <= K; ++t) {
+    const double alpha = abar[t] / abar[t - 1];
+    const double shrink = (1.0 - abar[t - 1]) / (1.0 - abar[t]);
+    const int i = K - t;
+    if (c_x) c_x[i] = (float)(sqrt(alpha) * shrink);
+    if (c_0) c_0[i] = (float)(sqrt(abar[t - 1]) * (1.0 - alpha) / (1.0 - abar[t]));
+    if (sigma) sigma[i] = (float)sqrt((1.0 - alpha) * shrink);
+    if (tau) tau[i] = t;
+    if (abar_f32) abar_f32[t] = (float)abar[t];
+  }
+  return ASD_OK;
+}
+
+asd_status asd_abar_cosine(int32_t K, double s, double beta_clip, double* abar) {
+  if (K < 1 || !abar) return fail(ASD_EINVAL, "K must be >= 1 and abar non-NULL");
+  if (!(s >= 0.0) || !(beta_clip > 0.0) || !(beta_clip < 1.0)) return fail(ASD_EINVAL, "need s >= 0 and 0 < beta_clip < 1");
+  const double half_pi = 1.5707963267948966;
+  auto f = [&](int t) {
+    const double c = cos(((double)t / (double)K + s) / (1.0 + s) * half_pi);
+    return c * c;
+  };
+  abar[0] = 1.0;
+  double prev = f(0);
+  for (int t = 1; t <= K; ++t) {
+    const double cur = f(t);
+    double beta = 1.0 - cur / prev;
+    if (beta > beta_clip) beta = beta_clip;
+    abar[t] = abar[t - 1] * (1.0 - beta);
+    prev = cur;
+  }
+  return ASD_OK;
+}
+
 const char* asd_status_string(asd_status s) {
   switch (s) {
     case ASD_OK: return "ASD_OK";

@@ -29,8 +29,11 @@ def device_params(cfg, params, device="cuda:0"):
 
 def open_ctx(cfg, params, seed=0, device="cuda:0", beta_min=1e-4, beta_max=0.02, L=None, chains=None):
     """Context for a workload dict (asd_workloads.CONFIGS entry) with the
-    library's own linear-beta schedule."""
-    sched = binding.asd_schedule_ddpm_linear(cfg["K"], beta_min, beta_max)
+    library's own linear-beta schedule (or, cfg["schedule"] == "cosine", its cosine one)."""
+    if cfg.get("schedule", "linear") == "cosine":
+        sched = binding.asd_schedule_from_abar(binding.asd_abar_cosine(cfg["K"]))
+    else:
+        sched = binding.asd_schedule_ddpm_linear(cfg["K"], beta_min, beta_max)
     den = device_params(cfg, params, device)
     den["n_tau"] = cfg["K"] + 1
     if cfg["kind"] == "gmm" or den.get("predict_eps"):

@@ -32,7 +32,10 @@ def mlp_model(T, p):
 
 def oracle_setup(cfg, model_seed=1):
     """(tables, params, model) of a workload dict from asd_workloads.CONFIGS."""
-    T = schedule.ddpm_tables(cfg["K"], W.BETA_MIN, W.BETA_MAX)
+    if cfg.get("schedule", "linear") == "cosine":
+        T = schedule.tables_from_abar(schedule.cosine_abar(cfg["K"]))
+    else:
+        T = schedule.ddpm_tables(cfg["K"], W.BETA_MIN, W.BETA_MAX)
     p = W.make_params(cfg, model_seed)
     model = gmm_model(T, p) if cfg["kind"] == "gmm" else mlp_model(T, p)
     return T, p, model

@@ -50,6 +50,24 @@ def test_schedule_matches_oracle_tables():
         binding.asd_schedule_ddpm_linear(10, 0.5, 0.1)
 
 
+def test_general_and_cosine_schedules_match_the_oracle():
+    for K in (1, 7, 100, 1000):
+        ab = binding.asd_abar_cosine(K)
+        np.testing.assert_allclose(ab, schedule.cosine_abar(K), rtol=1e-13)
+        s = binding.asd_schedule_from_abar(ab)
+        T = schedule.tables_from_abar(schedule.cosine_abar(K))
+        for k in ("c_x", "c_0", "sigma", "abar"):
+            np.testing.assert_allclose(s[k], T[k], rtol=3e-7, atol=1e-30)
+        assert np.array_equal(s["tau"], T["tau"])
+    for bad in ([0.9, 0.5], [1.0, 0.5, 0.5], [1.0, 0.5, 0.0], [1.0, 1.2]):
+        with pytest.raises(binding.AsdError):
+            binding.asd_schedule_from_abar(np.array(bad))
+    with pytest.raises(binding.AsdError):
+        binding.asd_abar_cosine(10, -1.0)
+    with pytest.raises(binding.AsdError):
+        binding.asd_abar_cosine(0)
+
+
 def _cfg(**over):
     s = binding.asd_schedule_ddpm_linear(10)
     den = dict(kind="gmm", d=4, C=3, var=0.25, means=16, log_w=16, abar=s["abar"], n_tau=11)

@@ -401,6 +401,14 @@ def test_many_chains_small_problem(resident):
     assert _free_running(cfg, 50, [0, 1, 1023, 1024, 9999, 19999], resident=resident) >= 3
 
 
+@pytest.mark.parametrize("resident", [False, True])
+def test_sample_with_a_cosine_schedule(resident):
+    """Another variance-preserving schedule through the same tables (asd_abar_cosine + asd_schedule_from_abar):
+    its last steps have betas up to 0.999, i.e. a very different noise profile from the linear one."""
+    cfg = dict(kind="gmm", d=12, C=9, K=80, chains=6, L=10, var=0.25, schedule="cosine")
+    assert _free_running(cfg, 3, range(6), resident=resident) >= 4
+
+
 def test_sample_random_small_shapes():
     """A seeded sweep over small mixture shapes (d, C, K, L, chains drawn at random, windows fixed or
     controlled, either sampling path): whole samples against the oracle."""

@@ -24,6 +24,39 @@ def test_tables_against_ancestral_sampling_identities():
         assert abs(var_next - (1 - abar[t - 1])) < 1e-12
 
 
+def test_tables_from_any_abar_keep_the_forward_marginals():
+    """Cosine schedule and a random decreasing abar: a point mass at m must keep mean sqrt(abar) m and variance
+    1 - abar at every level (what ancestral sampling with the posterior variance means), and the one-step
+    coefficients must be one SL Euler step mapped back, as for the linear schedule."""
+    rng = np.random.default_rng(5)
+    K = 60
+    ab_cos = schedule.cosine_abar(K)
+    assert ab_cos[0] == 1.0 and np.all(np.diff(ab_cos) < 0) and ab_cos[K] > 0
+    # the unclipped part of the schedule is the closed form
+    f = lambda t: np.cos((t / K + 0.008) / 1.008 * np.pi / 2) ** 2
+    np.testing.assert_allclose(ab_cos[1:K // 2], f(np.arange(1, K // 2)) / f(0), rtol=1e-12)
+    assert abs((1 - ab_cos[K] / ab_cos[K - 1]) - 0.999) < 1e-12           # the last beta is the clipped one
+    ab_rand = np.concatenate([[1.0], np.cumprod(1.0 - rng.uniform(1e-4, 0.3, K))])
+    for abar in (ab_cos, ab_rand):
+        T = schedule.tables_from_abar(abar)
+        m = -0.9
+        for i in range(K):
+            t = K - i
+            assert abs(T["c_x"][i] * np.sqrt(abar[t]) * m + T["c_0"][i] * m - np.sqrt(abar[t - 1]) * m) < 1e-12
+            assert abs(T["c_x"][i] ** 2 * (1 - abar[t]) + T["sigma"][i] ** 2 - (1 - abar[t - 1])) < 1e-12
+        ab = abar[K:0:-1]
+        g, tt = schedule.sl_scale(ab), schedule.sl_time(ab)
+        eta = np.diff(tt)
+        np.testing.assert_allclose(g[:-1] / g[1:], T["c_x"][: K - 1], rtol=1e-9)
+        np.testing.assert_allclose(eta / g[1:], T["c_0"][: K - 1], rtol=1e-9)
+        np.testing.assert_allclose(np.sqrt(eta) / g[1:], T["sigma"][: K - 1], rtol=1e-9)
+    # and the general routine reproduces the linear-beta tables
+    _, ab_lin = schedule.linear_beta_abar(K)
+    A, B = schedule.tables_from_abar(ab_lin), schedule.ddpm_tables(K)
+    for k in ("c_x", "c_0", "sigma"):
+        np.testing.assert_allclose(A[k], B[k], rtol=1e-12, atol=1e-15)
+
+
 def test_tables_equal_one_sl_euler_step_mapped_back():
     """Translate to SL, step, map back (Sec. 3, after Eq. euler-sde):
     x' = (y + eta m + sqrt(eta) xi) / gamma' with y = gamma x  must have the
