@@ -7,7 +7,7 @@ verify model call, accept/scan/resample) until every chain has reached K.
 The metric is DDPM steps per second = chains * K / wall-clock of a sample,
 with all inputs resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see README for the fields).  Besides the
+Prints ONE JSON line.  Besides the
 throughput it carries
   roofline      the dominant kernel of the workload against the MI355X peak,
                 timed live with HIP events on the launch stream,
@@ -228,7 +228,7 @@ def main():
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (chains shard trivially across GPUs, see DESIGN.md); "
+        print("bench.py: this build runs on one GPU only (chains are independent, so a batch shards across GPUs by chain); "
               "got --gpus %d" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch

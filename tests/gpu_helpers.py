@@ -10,7 +10,7 @@ from paper_2505_03983_amd import runtime
 DEV = "cuda:0"
 
 # Tolerances (the benchmark spec): fp32 denoisers 1e-4, bf16 denoisers 2e-2, relative to the
-# scale of the compared array (sup norm), see DESIGN.md "Tolerances".
+# scale of the compared array (sup norm).
 TOL = {"gmm": 1e-4, "mlp": 2e-2}
 
 
