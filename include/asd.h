@@ -207,7 +207,7 @@ ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 
 /* Verify-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
  * operand split into three bf16 terms (six bf16 products per fp32 product, fp32 accumulation; what
- * is left out is below 2^-24 of |a||b| per product, the order of fp32 rounding).  Nothing in the
+ * is left out is 2^-23 of |a||b| per product on average and never above 2^-21, a few units of fp32 rounding).  Nothing in the
  * method changes: it is another way to evaluate the same fp32 contraction, about 1.5x faster on this
  * chip than its fp32 matrix pipe.  Taken when d % 16 == 0 and C % 16 == 0 on the matrix-core path;
  * on = 0 selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */

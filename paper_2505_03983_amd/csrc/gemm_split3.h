@@ -6,8 +6,9 @@
 // cut is by truncation: x1 = the top 16 bits of x, x2 = the top 16 bits of x - x1, x3 = the rest).
 // A product of two bf16 numbers is exact in fp32, and the matrix cores accumulate in fp32, so
 //   a*b ~= a1*b1 + (a1*b2 + a2*b1) + (a2*b2 + a1*b3 + a3*b1)
-// leaves out only terms below 2^-24 |a||b| (a2*b3, a3*b2, a3*b3): the same order as the rounding of
-// an fp32 multiply-add.  Six bf16 MFMAs replace one fp32 MFMA of the same shape, and the bf16 matrix
+// leaves out a2*b3 + a3*b2 + a3*b3: with |x2| < 2^-7 |x1| and |x3| < 2^-15 |x1| that is below 2^-21 |a||b|
+// always and 2^-23 |a||b| on average -- a few units of the rounding of one fp32 multiply-add (2^-24), and
+// small against the rounding that accumulating K = 10^3 terms in fp32 brings with it either way.  Six bf16 MFMAs replace one fp32 MFMA of the same shape, and the bf16 matrix
 // pipe of this chip is 16x as fast as its fp32 one on paper.  In practice dense bf16 MFMA work on random
 // data is power-limited at about half the data-sheet rate (asd_mfma_ceiling measures it: ~1.3 PFLOP/s),
 // so the gain over the fp32 pipe is ~1.5x, at fp32 accuracy.  (Splitting into bf16 terms for
