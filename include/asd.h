@@ -288,6 +288,13 @@ ASD_API asd_status asd_schedule_ddpm_linear(int32_t K, double beta_min, double b
  * noise-predicting denoiser takes). */
 ASD_API asd_status asd_schedule_from_abar(int32_t K, const double* abar, float* c_x, float* c_0, float* sigma,
                                   int32_t* tau, float* abar_f32);
+/* The Euler chain of Eq. euler-sde on the stochastic-localization process itself, for a mixture denoiser given
+ * sl_time: times t[0..K] (HOST, double; positive, strictly increasing), step i goes from t[i] to t[i+1] with
+ * c_x = 1, c_0 = eta_i = t[i+1] - t[i], sigma = sqrt(eta_i), tau[i] = i (the index into sl_time).  A
+ * variance-exploding diffusion x = x_0 + s eps is this process at t = 1/s^2, y = x/s^2.  Outputs HOST [K]
+ * (t_f32 [K+1]); any may be NULL. */
+ASD_API asd_status asd_schedule_sl_euler(int32_t K, const double* t, float* c_x, float* c_0, float* sigma,
+                                 int32_t* tau, float* t_f32);
 /* abar[0..K] (HOST, double) of the cosine schedule, abar ~ cos^2(((tau/K + s)/(1 + s)) pi/2), with every beta
  * clipped at beta_clip (Nichol & Dhariwal 2021 use s = 0.008, beta_clip = 0.999). */
 ASD_API asd_status asd_abar_cosine(int32_t K, double s, double beta_clip, double* abar);

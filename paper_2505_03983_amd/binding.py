@@ -79,6 +79,7 @@ def lib():
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
             "asd_schedule_from_abar": (i32, [i32, vp, vp, vp, vp, vp, vp]),
             "asd_abar_cosine": (i32, [i32, C.c_double, C.c_double, vp]),
+            "asd_schedule_sl_euler": (i32, [i32, vp, vp, vp, vp, vp, vp]),
             "asd_status_string": (C.c_char_p, [i32]),
             "asd_last_error": (C.c_char_p, []),
         }
@@ -140,6 +141,17 @@ def asd_schedule_from_abar(abar):
                abar=np.zeros(max(n, 0) + 1, np.float32))
     _check(lib().asd_schedule_from_abar(n, _ptr(abar), _ptr(out["c_x"]), _ptr(out["c_0"]), _ptr(out["sigma"]),
                                         _ptr(out["tau"]), _ptr(out["abar"])))
+    return out
+
+
+def asd_schedule_sl_euler(t):
+    """Host tables of the Euler chain on the SL process over times t[0..K] (float64); 'sl_time' is the fp32 copy."""
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    n = max(len(t) - 1, 0)
+    out = dict(c_x=np.zeros(n, np.float32), c_0=np.zeros(n, np.float32), sigma=np.zeros(n, np.float32),
+               tau=np.zeros(n, np.int32), sl_time=np.zeros(n + 1, np.float32))
+    _check(lib().asd_schedule_sl_euler(n, _ptr(t), _ptr(out["c_x"]), _ptr(out["c_0"]), _ptr(out["sigma"]),
+                                       _ptr(out["tau"]), _ptr(out["sl_time"])))
     return out
 
 

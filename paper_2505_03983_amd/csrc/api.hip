@@ -549,6 +549,24 @@ asd_status asd_schedule_from_abar(int32_t K, const double* abar, float* c_x, flo
   return ASD_OK;
 }
 
+asd_status asd_schedule_sl_euler(int32_t K, const double* t, float* c_x, float* c_0, float* sigma, int32_t* tau,
+                                 float* t_f32) {
+  if (K < 1 || !t) return fail(ASD_EINVAL, "K must be >= 1 and t non-NULL");
+  if (!(t[0] > 0.0)) return fail(ASD_EINVAL, "t[0] must be positive");
+  for (int i = 0; i < K; ++i)
+    if (!(t[i + 1] > t[i])) return fail(ASD_EINVAL, "t must increase strictly (index %d)", i + 1);
+  for (int i = 0; i < K; ++i) {
+    const double eta = t[i + 1] - t[i];
+    if (c_x) c_x[i] = 1.0f;
+    if (c_0) c_0[i] = (float)eta;
+    if (sigma) sigma[i] = (float)sqrt(eta);
+    if (tau) tau[i] = i;
+  }
+  if (t_f32)
+    for (int i = 0; i <= K; ++i) t_f32[i] = (float)t[i];
+  return ASD_OK;
+}
+
 asd_status asd_abar_cosine(int32_t K, double s, double beta_clip, double* abar) {
   if (K < 1 || !abar) return fail(ASD_EINVAL, "K must be >= 1 and abar non-NULL");
   if (!(s >= 0.0) || !(beta_clip > 0.0) || !(beta_clip < 1.0)) return fail(ASD_EINVAL, "need s >= 0 and 0 < beta_clip < 1");

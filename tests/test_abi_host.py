@@ -62,6 +62,14 @@ def test_general_and_cosine_schedules_match_the_oracle():
     for bad in ([0.9, 0.5], [1.0, 0.5, 0.5], [1.0, 0.5, 0.0], [1.0, 1.2]):
         with pytest.raises(binding.AsdError):
             binding.asd_schedule_from_abar(np.array(bad))
+    t = np.array([0.01, 0.5, 0.7, 40.0])
+    s = binding.asd_schedule_sl_euler(t)
+    np.testing.assert_allclose(s["c_0"], np.diff(t), rtol=2e-7)
+    np.testing.assert_allclose(s["sigma"], np.sqrt(np.diff(t)), rtol=2e-7)
+    assert np.all(s["c_x"] == 1.0) and list(s["tau"]) == [0, 1, 2] and s["sl_time"].dtype == np.float32
+    for bad in ([0.0, 1.0], [1.0, 1.0], [2.0, 1.0], [-1.0, 1.0]):
+        with pytest.raises(binding.AsdError):
+            binding.asd_schedule_sl_euler(np.array(bad))
     with pytest.raises(binding.AsdError):
         binding.asd_abar_cosine(10, -1.0)
     with pytest.raises(binding.AsdError):

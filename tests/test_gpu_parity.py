@@ -340,25 +340,35 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.close()
 
 
+@pytest.mark.parametrize("grid", ["ddpm", "ve"])
 @pytest.mark.parametrize("resident", [False, True])
-def test_sample_in_sl_coordinates(resident):
+def test_sample_in_sl_coordinates(resident, grid):
     """The paper's own coordinates: the Euler chain of Eq. euler-sde on the stochastic-localization
     process (c_x = 1, c_0 = eta_i, sigma = sqrt(eta_i)) with the mean function m(t, y) of Eq. sl-defn as
-    the model, given to the library as tables plus the SL time of every index.  Whole samples against
-    the oracle run in the same coordinates; y_0 = gamma_0 xi_0 is passed in."""
+    the model, given to the library as tables (asd_schedule_sl_euler) plus the SL time of every index.
+    Whole samples against the oracle run in the same coordinates; y_0 ~ N(0, t_0 I) is passed in
+    (the law of the process at t_0 up to the t_0 x* term, which is negligible at a small t_0).
+    grid "ddpm": the times of the linear-beta DDPM chain, t = abar / (1 - abar); "ve": a
+    variance-exploding diffusion x = x_0 + s eps, s geometric from 30 down to 0.05, i.e. t = 1 / s^2."""
     from oracle import denoisers, schedule
     K, d, C, L, chains, seed = 60, 6, 5, 8, 6, 12
     p = W.gmm_params(d, C)
-    S = schedule.sl_tables(K)
+    if grid == "ddpm":
+        t_grid = schedule.sl_tables(K)["t"]                      # K times -> K - 1 steps
+    else:
+        t_grid = 1.0 / np.geomspace(30.0, 0.05, K) ** 2
     Km = K - 1
-    eta = S["eta"].astype(np.float32)
-    sched = dict(c_x=np.ones(Km, np.float32), c_0=eta, sigma=np.sqrt(S["eta"]).astype(np.float32),
-                 tau=np.arange(Km, dtype=np.int32))
+    sched = binding.asd_schedule_sl_euler(t_grid)
+    eta64 = np.diff(t_grid)
+    np.testing.assert_allclose(sched["c_0"], eta64, rtol=2e-7)
+    np.testing.assert_allclose(sched["sigma"], np.sqrt(eta64), rtol=2e-7)
+    assert np.all(sched["c_x"] == 1.0) and np.array_equal(sched["tau"], np.arange(Km))
     den = runtime.device_params(dict(kind="gmm", d=d, C=C), p)
     den["n_tau"] = K
-    den["sl_time"] = S["t"].astype(np.float32)
+    den["sl_time"] = sched["sl_time"]
     ctx = binding.Ctx(sched, den, L, chains, seed)
     ctx.use_resident(resident)
+    S = dict(gamma=[np.sqrt(t_grid[0])])
     A64, B64, S64 = sched["c_x"].astype(np.float64), sched["c_0"].astype(np.float64), sched["sigma"].astype(np.float64)
     t64 = den["sl_time"].astype(np.float64)
 
