@@ -260,8 +260,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": ("f32 (verify GEMM products as 6 bf16 MFMA terms, fp32 accumulation)" if res["split"] else "f32")
-        if cfg["kind"] == "gmm" else "bf16",
+        "dtype": "f32" if cfg["kind"] == "gmm" else "bf16",
         "data": "synthetic",
         "config": {"workload": workload_name(args.workload, cfg), "chains": cfg["chains"], "K": cfg["K"],
                    "L": cfg["L"], "d": cfg["d"]},
@@ -269,6 +268,9 @@ def main():
                               "launched": res["rounds_launched"]},
         "path": res["path"],
     }
+    if cfg["kind"] == "gmm":
+        line["verify_gemm_arithmetic"] = ("every fp32 product as six bf16 MFMA products of three-way split operands, "
+                                          "fp32 accumulation" if res["split"] else "fp32 MFMA")
     if not args.plain:
         line["roofline"] = roofline(res, args.workload)
         line["hbm_kernels"] = hbm_kernels(res)
