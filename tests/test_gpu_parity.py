@@ -633,6 +633,46 @@ def _full_size_round(w, sampled, seed=0, split=None):
     assert compared >= len(sampled) - 1
 
 
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_sample_config5_full_size_prefix(adaptive):
+    """The whole-sample driver at the headline size, in the launch configuration the benchmark times (lock-step
+    round kernels, bf16 split-operand verify GEMMs): two sampled chains of a full 1024-chain sample against
+    the oracle run freely from y_0, for as many rounds as the oracle does in a few seconds (a whole chain
+    takes the CPU half a minute) or up to the first near-tie decision."""
+    cfg = W.CONFIGS[5]
+    T, p, model = oracle_setup(cfg)
+    tol, K, L, n_rounds = H.TOL["gmm"], cfg["K"], cfg["L"], 5
+    ctx = runtime.open_ctx(cfg, p, seed=3)
+    ctx.use_adaptive_window(adaptive)
+    assert ctx.split_gemm_active() and not ctx.resident_active()
+    traj = runtime.alloc_traj(ctx)
+    rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    ctx.sample(traj, rounds)
+    assert bool(torch.isfinite(traj[:, -1]).all().item())
+    compared = 0
+    for c in (0, 777):
+        tj = traj[c].cpu().numpy()
+        xi, u = chain_randoms(3, c, K, cfg["d"])
+        y = np.zeros((K + 1, cfg["d"]))
+        y[0] = xi[0]
+        a, state = 0, oasd.window_init(L)
+        for _ in range(n_rounds):
+            win = oasd.window_of(state, L) if adaptive else L
+            rec = oasd.asd_round(y[a], a, win, T["c_x"], T["c_0"], T["sigma"], model, xi, u, tol)
+            n_acc = rec["j"] - a
+            if rec["flagged"][: min(n_acc + 1, rec["b"] - a)].any():
+                break
+            y[a + 1: rec["a_next"] + 1] = rec["y_new"]
+            state = oasd.window_next(state, rec["b"] - a, n_acc)
+            a = rec["a_next"]
+        e = H.rel_err(tj[: a + 1], y[: a + 1])
+        _log("cfg5 free-running prefix: chain", c, "adaptive", adaptive, "steps compared", a, "rel err", e)
+        assert e <= tol, (c, a, e)
+        compared += a
+    ctx.close()
+    assert compared >= 10
+
+
 def test_round_config4_full_size_sampled():
     _full_size_round(4, sampled=[0, 31, 63])
 
