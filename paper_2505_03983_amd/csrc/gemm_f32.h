@@ -83,12 +83,16 @@ struct Frag {
 // the loader threads, so that the epilogue -- whose loads the compiler may not move above its stores -- has
 // no chain of dependent global loads per row).
 // KTAIL: K is not a multiple of BK (the last slab is zero-padded).
+// Split K (gridDim.z > 1, Ops with kSplitK only): workgroup z of a tile contracts the z-th share of the slabs and hands
+// its accumulators to op.store_partial (fp32 partial tiles in scratch) instead of the epilogue; a finishing kernel of
+// the Op's owner adds the partials in z order.  For products with few output tiles and a long K (the second GEMM of
+// the mixture denoiser on one row per chain: 256 tiles, K = 4096).
 // Requirements (checked by the host launcher): K % 4 == 0, rows 16 B aligned.
 // CALL only gives the draft-call and verify-call launches distinct symbols in profiles.
 template <class Cfg, class Op, bool KTAIL, int CALL>
 __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict__ M_dev, int M_max, int N, int K,
                                                           RowSrc A, const float* __restrict__ Bm, int64_t ldb,
-                                                          Op op) {
+                                                          Op op, float* __restrict__ part) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LDSS = Cfg::LDSS;
   constexpr int KQ = Cfg::KQ, RPP = Cfg::RPP, RA = Cfg::RA, RB = Cfg::RB, MI = Cfg::MI, NJ = Cfg::NJ, KS = Cfg::KS;
   extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -114,7 +118,10 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
 #pragma unroll
   for (int p = 0; p < RB; ++p) bp[p] = Bm + (int64_t)min(n0 + lrow + RPP * p, N - 1) * ldb + lkq * 4;
   op.template init<Cfg>(m0, M, lrow, lkq, s_row);
-  const int nk = (K + BK - 1) / BK;
+  const int nk_all = (K + BK - 1) / BK;
+  const int splits = gridDim.z;
+  const int nk = nk_all / splits;                 // slabs of this workgroup (the host makes it divide)
+  const int kb = blockIdx.z * nk;                 // its first slab
 
   float4 ra[RA], rb[RB];
   auto gload = [&](int kt) {
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  gload(0);
+  gload(kb);
   sstore(0);
   __syncthreads();
 
@@ -178,7 +185,7 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < nk;
-    if (more) gload(kt + 1);
+    if (more) gload(kb + kt + 1);
     const float* Ac = As + cur * BM * LDSS + a_lane;
     const float* Bc = Bs + cur * BN * LDSS + b_lane;
     // While it has fragments to feed, a wavefront outranks its SIMD neighbours that are between slabs:
@@ -205,13 +212,24 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const int* __restrict_
 
   op.template finish<Cfg>(lrow, lkq, s_row);
   __syncthreads();
+  if constexpr (Op::kSplitK) {
+    if (splits > 1) {
+      op.template store_partial<Cfg>(acc, fr, m0, n0, M, M_max, N, s_row, part, (int)blockIdx.z, splits);
+      return;
+    }
+  }
   op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
+// Floats of scratch a split-K launch needs: the partial tiles, then the Op's per-row partials ([splits][M_max]).
+inline size_t gemm_f32_splitk_floats(int splits, int M_max, int N) { return (size_t)splits * M_max * ((size_t)N + 1); }
+
 template <class Cfg, int CALL, class Op>
 inline hipError_t launch_gemm_f32_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const float* Bm,
-                                     int64_t ldb, Op op, hipStream_t st) {
-  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM));
+                                     int64_t ldb, Op op, hipStream_t st, int splits = 1, float* part = nullptr) {
+  if (splits < 1 || (splits > 1 && (!Op::kSplitK || !part || K % Cfg::BK != 0 || (K / Cfg::BK) % splits != 0)))
+    return hipErrorInvalidValue;
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM), (unsigned)splits);
   if (K % Cfg::BK == 0) {
     auto kern = gemm_f32_nt_kernel<Cfg, Op, false, CALL>;
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per kernel
@@ -221,7 +239,7 @@ inline hipError_t launch_gemm_f32_nt(const int* M_dev, int M_max, int N, int K, 
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op);
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op, part);
   } else {
     auto kern = gemm_f32_nt_kernel<Cfg, Op, true, CALL>;
     static bool attr_set = false;
@@ -231,7 +249,7 @@ inline hipError_t launch_gemm_f32_nt(const int* M_dev, int M_max, int N, int K, 
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op);
+    hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bm, ldb, op, part);
   }
   return hipGetLastError();
 }

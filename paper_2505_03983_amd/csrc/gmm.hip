@@ -228,6 +228,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
 // (pmax[row][WGN*column_tile + wn]); the softmax normalisation is finished
 // inside GEMM 2, so the logits are written once and read once.
 struct LogitOp {
+  static constexpr bool kSplitK = false;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -301,6 +302,7 @@ struct LogitOp {
 // into exp(logit - rowmax) on its way into LDS; the row sums are accumulated on
 // the side and divided out in the epilogue.
 struct CombineOp {
+  static constexpr bool kSplitK = true;
   const float* pmax;
   int np;
   const float* in_base;
@@ -353,6 +355,27 @@ struct CombineOp {
       if (lkq == 0) s_row[8 * (lrow + Cfg::RPP * p)] = s;
     }
   }
+  // split K: the partial tile and (from the workgroups of column tile 0) the partial row sums, for combine_finish_kernel
+  template <class Cfg>
+  __device__ __forceinline__ void store_partial(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0,
+                                                int n0, int M, int M_max, int N, const float* s_row, float* part,
+                                                int z, int splits) const {
+    float* tile = part + (size_t)z * M_max * N;
+    float* psum = part + (size_t)splits * M_max * N + (size_t)z * M_max;
+#pragma unroll
+    for (int i = 0; i < Cfg::MI; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int ml = fr.row(i, r), m = m0 + ml;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < Cfg::NJ; ++j) {
+          const int n = n0 + fr.col(j);
+          if (n < N) tile[(size_t)m * N + n] = acc[i][j][r];
+        }
+        if (n0 == 0 && fr.wn == 0 && fr.l32 == 0) psum[m] = s_row[8 * ml];
+      }
+  }
   template <class Cfg>
   __device__ __forceinline__ void epilogue(const v16f (&acc)[Cfg::MI][Cfg::NJ], const Frag<Cfg>& fr, int m0, int n0,
                                            int M, int N, const float* s_row) const {
@@ -389,6 +412,33 @@ struct CombineOp {
     }
   }
 };
+
+// Finish of a split-K second GEMM: one workgroup per row adds the partial tiles and row sums in split order and
+// applies  out = c_x' x + c_m' acc / sum.
+__global__ __launch_bounds__(256) void combine_finish_kernel(const int* __restrict__ M_dev, int M_max, int N, int splits,
+                                                             const float* __restrict__ part,
+                                                             const float* __restrict__ in_base,
+                                                             const int64_t* __restrict__ in_off,
+                                                             float* __restrict__ out_base,
+                                                             const int64_t* __restrict__ out_off,
+                                                             const float4* __restrict__ coef_tau,
+                                                             const int32_t* __restrict__ tau) {
+  const int M = min(*M_dev, M_max);
+  const int m = blockIdx.x;
+  if (m >= M) return;
+  const float* psum = part + (size_t)splits * M_max * N;
+  float sum = 0.f;
+  for (int z = 0; z < splits; ++z) sum += psum[(size_t)z * M_max + m];
+  const float4 cf = coef_tau[tau[m]];
+  const float scale = cf.w / sum;
+  const float* x = in_base + in_off[m];
+  float* o = out_base + out_off[m];
+  for (int n = threadIdx.x; n < N; n += 256) {
+    float a = 0.f;
+    for (int z = 0; z < splits; ++z) a += part[((size_t)z * M_max + m) * N + n];
+    o[n] = fmaf(cf.z, x[n], scale * a);
+  }
+}
 
 // ---------------------------------------------------------------------------
 // host
@@ -464,6 +514,18 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
   }
   if (g->use_mfma) {
     g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finest of the tilings
+    // split K for the second GEMM of the draft call (one row per chain): few output tiles, long K
+    const int64_t tiles = ceil_div(ctx->B, GmmTileSkinny::BM) * ceil_div(d, GmmTileSkinny::BN);
+    if (C % GmmTileSkinny::BK == 0) {
+      const int slabs = C / GmmTileSkinny::BK;
+      for (int sp = 4; sp >= 2; sp /= 2)   // up to ~4 workgroups per CU, at least 16 slabs each (8 splits measured no better)
+        if (tiles * sp <= 1024 && slabs % sp == 0 && slabs / sp >= 16) {
+          g->draft_splits = sp;
+          break;
+        }
+    }
+    if (g->draft_splits > 1)
+      ASD_HIP(hipMalloc(&g->part, sizeof(float) * gemm_f32_splitk_floats(g->draft_splits, ctx->B, d)));
     ASD_HIP(hipMalloc(&g->logits, sizeof(float) * (size_t)ctx->n_rows_max * C));
     ASD_HIP(hipMalloc(&g->pmax, sizeof(float) * (size_t)ctx->n_rows_max * g->np));
   }
@@ -478,6 +540,7 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->means_t_img);
   (void)hipFree(g->musq);
   (void)hipFree(g->coef_tau);
+  (void)hipFree(g->part);
   (void)hipFree(g->logits);
   (void)hipFree(g->pmax);
   delete g;
@@ -522,9 +585,16 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
+    const int splits = (!rows.call && g->draft_splits > 1 && n <= ctx->B) ? g->draft_splits : 1;
     ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
             : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
-                        : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st));
+                        : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st, splits,
+                                                                g->part));
+    if (splits > 1) {
+      hipLaunchKernelGGL(combine_finish_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, ctx->B, d, splits,
+                         g->part, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau);
+      ASD_HIP(hipGetLastError());
+    }
   }
   return ASD_OK;
 }

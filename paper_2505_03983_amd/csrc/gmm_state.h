@@ -17,6 +17,8 @@ struct GmmState {
   float* logits = nullptr;       // [rows_max, C] (matrix-core path only)
   float* pmax = nullptr;         // [rows_max, np] partial row maxima of the logits
   int np = 0;
+  float* part = nullptr;         // split-K scratch of the draft call's second GEMM: [splits][chains][d] tiles, [splits][chains] sums
+  int draft_splits = 1;
   bool use_mfma = false;
   // split-bf16 verify GEMMs (gemm_split3.h): the means, split and laid out as LDS images, for both GEMMs
   uint8_t* means_img = nullptr;    // B of the logits GEMM  ([C, d])

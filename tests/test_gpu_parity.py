@@ -211,6 +211,16 @@ def test_round_ragged_shapes():
         _teacher_forced(cfg, seed=5, chains_checked=range(cfg["chains"] - 1))
 
 
+def test_round_midsize_matrix_core_shapes():
+    """Rounds whose two model calls both take the matrix-core path on shapes that are not tile multiples:
+    a draft call of 70 rows with its second GEMM split over K (C = 1024, fp32 MFMA: d is not a multiple of 16),
+    and a shape that takes the split-operand kernels for the verify call (d = 48, C = 1040: ragged last column
+    tile, one-row-tile draft call without a K split)."""
+    for cfg in (dict(kind="gmm", d=40, C=1024, K=30, chains=70, L=24, var=0.25),
+                dict(kind="gmm", d=48, C=1040, K=20, chains=90, L=16, var=0.25)):
+        _teacher_forced(cfg, seed=2, chains_checked=[0, 33, cfg["chains"] - 1], rounds_per_chain=2)
+
+
 # ---------------------------------------------------------------------------
 # whole samples, free-running
 # ---------------------------------------------------------------------------
