@@ -211,6 +211,53 @@ def test_round_ragged_shapes():
         _teacher_forced(cfg, seed=5, chains_checked=range(cfg["chains"] - 1))
 
 
+def test_matrix_core_denoiser_is_deterministic():
+    """Repeated calls give bit-identical results on every matrix-core path: split-operand and fp32 verify GEMMs
+    (asd_denoise), and the draft call with its K-split second GEMM (partials added in a fixed order)."""
+    cfg = dict(kind="gmm", d=48, C=1024, K=30, chains=70, L=24, var=0.25)
+    T, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=1)
+    rng = np.random.default_rng(4)
+    x = torch.from_numpy(rng.standard_normal((900, cfg["d"])).astype(np.float32)).to(DEV)
+    tau = torch.from_numpy(rng.integers(1, cfg["K"] + 1, 900).astype(np.int32)).to(DEV)
+    for split in (True, False):
+        ctx.use_split_gemm(split)
+        outs = []
+        for _ in range(3):
+            out = torch.zeros_like(x)
+            ctx.denoise(x, tau, out)
+            outs.append(out.clone())
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), split
+    # one round from the same states, twice: draft call (K split), draft, verify call, accept
+    B, K, L, d = cfg["chains"], cfg["K"], cfg["L"], cfg["d"]
+    results = []
+    for _ in range(2):
+        traj = torch.zeros((B, K + 1, d), dtype=torch.float32, device=DEV)
+        traj[:, 0] = torch.arange(B, device=DEV, dtype=torch.float32)[:, None] * 0.01 + 0.3
+        a = torch.zeros(B, dtype=torch.int32, device=DEV)
+        x0hat = torch.zeros((B, L, d), dtype=torch.float32, device=DEV)
+        ctx.draft(traj, a)
+        ctx.verify(traj, a, x0hat)
+        ctx.accept(traj, a, x0hat)
+        torch.cuda.synchronize()
+        results.append((traj.clone(), a.clone(), x0hat.clone()))
+    for u, v in zip(results[0], results[1]):
+        assert torch.equal(u, v)
+    ctx.close()
+
+
+def test_mfma_ceiling_probe():
+    """The probe of what the matrix pipes sustain: plausible, finite figures (no fixed expectation: the rate is set
+    by the chip's power management), constant operands no slower than random ones."""
+    r_bf16 = binding.asd_mfma_ceiling(True, True, 60)
+    c_bf16 = binding.asd_mfma_ceiling(True, False, 60)
+    r_f32 = binding.asd_mfma_ceiling(False, True, 60)
+    _log("mfma ceiling: bf16 random", r_bf16, "constant", c_bf16, "f32 random", r_f32)
+    assert 200.0 < r_bf16 <= 2600.0 and 200.0 < c_bf16 <= 2600.0 and c_bf16 >= 0.95 * r_bf16
+    assert 40.0 < r_f32 <= 165.0
+
+
 def test_round_midsize_matrix_core_shapes():
     """Rounds whose two model calls both take the matrix-core path on shapes that are not tile multiples:
     a draft call of 70 rows with its second GEMM split over K (C = 1024, fp32 MFMA: d is not a multiple of 16),
