@@ -47,7 +47,45 @@ def workload_name(w, cfg):
         w, cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], cfg["chains"], cfg["L"])
 
 
-def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True):
+class ClockSampler:
+    """Shader clock of GPU 0 as rocm-smi reports it, polled from a host thread while a region runs (a child
+    process per poll; nothing is launched on the GPU).  The chip lowers it under dense matrix work."""
+
+    def __init__(self, period_s=0.2):
+        import threading
+        self.period, self.samples, self._stop = period_s, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                out = subprocess.run(["/opt/rocm/bin/rocm-smi", "-d", "0", "--showclocks"], capture_output=True,
+                                     text=True, timeout=5).stdout
+                m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", out)
+                if m:
+                    self.samples.append(int(m.group(1)))
+            except Exception:
+                return
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join(timeout=10)
+
+    def summary(self):
+        if not self.samples:
+            return None
+        return dict(samples=len(self.samples), min=min(self.samples), max=max(self.samples),
+                    mean=sum(self.samples) / len(self.samples), last=self.samples[-1])
+
+
+def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, clocks=False):
     import torch
     import asd_workloads as W
     from paper_2505_03983_amd import binding, runtime
@@ -70,15 +108,18 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True):
         "lock-step round kernels" + ("" if profile else ", one captured graph per round")
     launched = []
     rmean, rmax = [], []
+    sampler = ClockSampler() if clocks else None
+    if sampler:
+        sampler.__enter__()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
         ctx.set_seed(seed + i)
         launched.append(ctx.sample(traj, rounds))
-        if not profile:
-            continue
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    if sampler:
+        sampler.__exit__()
     r = rounds.cpu().numpy()
     rmean.append(float(r.mean()))
     rmax.append(int(r.max()))
@@ -86,7 +127,8 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True):
     wall = t1 - t0
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
-               rounds_launched=launched, finite=finite, path=path, split=split_active)
+               rounds_launched=launched, finite=finite, path=path, split=split_active,
+               sclk_mhz=sampler.summary() if sampler else None)
     if profile:
         P = binding.PROF
         table = {}
@@ -244,7 +286,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma)
+    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma,
+                  clocks=True)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -267,12 +310,18 @@ def main():
         "rounds_per_sample": {"mean": res["rounds_mean"], "max": res["rounds_max"],
                               "launched": res["rounds_launched"]},
         "path": res["path"],
+        "sclk_mhz_during_timed_region": res["sclk_mhz"],     # rocm-smi, polled from the host (nominal 2400)
     }
     if cfg["kind"] == "gmm":
         line["verify_gemm_arithmetic"] = ("every fp32 product as six bf16 MFMA products of three-way split operands, "
                                           "fp32 accumulation" if res["split"] else "fp32 MFMA")
     if not args.plain:
         line["roofline"] = roofline(res, args.workload)
+        if res["sclk_mhz"] and line["roofline"]["bound"] == "mfma":
+            # the data-sheet peak is quoted at 2400 MHz; under dense matrix work the chip runs slower than that
+            rf0 = line["roofline"]
+            rf0["peak_at_measured_clock"] = rf0["peak"] * res["sclk_mhz"]["mean"] / 2400.0
+            rf0["frac_at_measured_clock"] = rf0["achieved"] / rf0["peak_at_measured_clock"]
         line["hbm_kernels"] = hbm_kernels(res)
         line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
                                "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
@@ -294,11 +343,12 @@ def main():
     # (Skipped with --others 0, so that a profiler run of this script sees the fixed-L launches only.)
     if args.others and res["split"]:
         # the same sample with the verify GEMMs on the fp32 matrix pipe (asd_use_split_gemm off)
-        rp = run_gpu(args.workload, 1, 1, args.seed, profile=True, split=False)
+        rp = run_gpu(args.workload, 1, 1, args.seed, profile=True, split=False, clocks=True)
         rfp = roofline(rp, args.workload)
         line["fp32_mfma_path"] = dict(steps_per_s=rp["steps_per_s"], ms_per_sample=rp["ms_per_sample"],
                                       roofline_kernel=rfp["kernel"], achieved=rfp["achieved"], peak=rfp["peak"],
-                                      frac=rfp["frac"], avg_launch_us=rfp["avg_launch_us"], traffic=rfp["traffic"])
+                                      frac=rfp["frac"], avg_launch_us=rfp["avg_launch_us"], traffic=rfp["traffic"],
+                                      sclk_mhz_during_timed_region=rp["sclk_mhz"])
     if args.others:
         ra = run_gpu(args.workload, max(1, min(args.steps, 2)), 1, args.seed, profile=False, adaptive=True)
         line["window_control"] = dict(steps_per_s=ra["steps_per_s"], ms_per_sample=ra["ms_per_sample"],
