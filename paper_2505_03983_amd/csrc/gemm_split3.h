@@ -50,26 +50,34 @@
 
 namespace asd {
 
-template <int BM_, int BN_, int WGM_ = 2, int WGN_ = 2>
+// BK: K slab, 16 (one MFMA group) or 32 (two).  The large tile with BK = 16 lets two workgroups share a CU; small
+// tiles for few rows take BK = 32, so that a slab carries enough MFMAs to cover the load -> LDS -> fragment
+// chain of the next one even with few wavefronts per SIMD.
+template <int BM_, int BN_, int WGM_ = 2, int WGN_ = 2, int BK_ = 16>
 struct Split3Cfg {
-  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, BK = 16, STAGES = 2;
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, BK = BK_, STAGES = 2;
+  static constexpr int NG = BK / 16;             // MFMA groups (k = 16) per slab
+  static constexpr int RB = 2 * BK;              // bytes of a row of a plane in LDS
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NJ = WN / 32;
-  static constexpr int KQ = 2;                   // loader threads per row of A (8 k each)
+  static constexpr int KQ = BK / 8;              // loader threads per row of A (8 k each)
   static constexpr int RPP = THREADS / KQ;       // rows covered by one loader pass
   static constexpr int RA = BM / RPP;            // loader passes over the A tile
-  static constexpr int A_PLANE = BM * 32, B_PLANE = BN * 32;      // bytes of one plane of a slab
+  static constexpr int A_PLANE = BM * RB, B_PLANE = BN * RB;      // bytes of one plane of a slab
   static constexpr int A_STAGE = 3 * A_PLANE, B_STAGE = 3 * B_PLANE;
   static constexpr int B_LOADS = B_STAGE / (16 * THREADS);        // 16-byte pieces of a slab's B image per thread
   static constexpr size_t LDS_BYTES = (size_t)STAGES * (A_STAGE + B_STAGE) + sizeof(float) * 8 * BM;
-  static_assert(WM % 32 == 0 && WN % 32 == 0 && BM % RPP == 0 && B_STAGE % (16 * THREADS) == 0, "tile shape");
+  static_assert(BK == 16 || BK == 32, "K slab");
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && RA >= 1 && BM % RPP == 0 && B_STAGE % (16 * THREADS) == 0, "tile shape");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  // 16-byte slot of chunk c of row r inside the row: 16 consecutive rows reading one chunk cover all 64 banks once
+  __host__ __device__ static constexpr int slot(int r, int c) { return BK == 16 ? (c ^ ((r >> 3) & 1)) : (c ^ ((r >> 2) & 3)); }
 };
 
 // Bytes of the B image for an [N, K] operand.
 template <class Cfg>
 inline size_t split3_image_bytes(int N, int K) {
-  return (size_t)((N + Cfg::BN - 1) / Cfg::BN) * (size_t)(K / 16) * Cfg::B_STAGE;
+  return (size_t)((N + Cfg::BN - 1) / Cfg::BN) * (size_t)(K / Cfg::BK) * Cfg::B_STAGE;
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -108,8 +116,8 @@ __global__ __launch_bounds__(256) void split3_pack_b_kernel(const float* __restr
   for (int e = 0; e < 8; ++e) x[e] = n < N ? B[(int64_t)n * ldb + c8 * 8 + e] : 0.f;
   u32x4 p[3];
   split3_pack(x, p[0], p[1], p[2]);
-  const int tn = n / Cfg::BN, r = n % Cfg::BN, ks = c8 >> 1, c = c8 & 1;
-  uint8_t* dst = img + ((int64_t)tn * (K / 16) + ks) * Cfg::B_STAGE + r * 32 + ((c ^ ((r >> 3) & 1)) * 16);
+  const int tn = n / Cfg::BN, r = n % Cfg::BN, ks = c8 / Cfg::KQ, c = c8 % Cfg::KQ;
+  uint8_t* dst = img + ((int64_t)tn * (K / Cfg::BK) + ks) * Cfg::B_STAGE + r * Cfg::RB + Cfg::slot(r, c) * 16;
 #pragma unroll
   for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<u32x4*>(dst + pl * Cfg::B_PLANE) = p[pl];
 }
@@ -134,13 +142,14 @@ inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K
 template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
 __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
                                                                          int N, int K, RowSrc A,
-                                                                         const uint8_t* __restrict__ Bimg, Op op) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ;
+                                                                         const uint8_t* __restrict__ Bimg, Op op,
+                                                                         float* __restrict__ part) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ, BK = Cfg::BK, NG = Cfg::NG, RB = Cfg::RB;
   constexpr int RA = Cfg::RA, RPP = Cfg::RPP, A_PLANE = Cfg::A_PLANE, B_PLANE = Cfg::B_PLANE;
   constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
-  uint8_t* lds_a = lds_all;                                   // [2 stages][3 planes][BM rows][32 bytes]
-  uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][3 planes][BN rows][32 bytes]
+  uint8_t* lds_a = lds_all;                                   // [2 stages][3 planes][BM rows][RB bytes]
+  uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][3 planes][BN rows][RB bytes]
   float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
 
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
@@ -159,28 +168,29 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const Frag<Cfg> fr{wave / Cfg::WGN, wave % Cfg::WGN, lane & 31, lane >> 5, tile_n};
-  const int nk = K / 16;
+  const int splits = gridDim.z;                  // K split: this workgroup contracts slabs kb .. kb + nk - 1
+  const int nk_all = K / BK, nk = nk_all / splits, kb = blockIdx.z * nk;
 
   // ---- loaders.  A: thread = (row lrow + RPP p, chunk lkq of 8 k).  B: thread t copies bytes 16 t + 16 THREADS q
   // of a slab's image.  Slab j waits in register slot j & 1 and goes to LDS stage j & 1.
-  const int lrow = tid >> 1, lkq = tid & 1;
+  const int lrow = tid / Cfg::KQ, lkq = tid % Cfg::KQ;
   const float* ap[RA];
   int a_dst[RA];
 #pragma unroll
   for (int p = 0; p < RA; ++p) {
     const int r = lrow + RPP * p;
-    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8;
-    a_dst[p] = r * 32 + ((lkq ^ ((r >> 3) & 1)) * 16);
+    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8 + (int64_t)kb * BK;
+    a_dst[p] = r * RB + Cfg::slot(r, lkq) * 16;
   }
   op.template init<Cfg>(m0, M, lrow, lkq, s_row);
-  const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk * B_STAGE + tid * 16;
+  const uint8_t* bsrc = Bimg + ((int64_t)tile_n * nk_all + kb) * B_STAGE + tid * 16;
   float4 ra[2][RA][2];
   u32x4 rb[2][B_LOADS];
   auto gload = [&](int kt, auto slot) {
 #pragma unroll
     for (int p = 0; p < RA; ++p) {
-      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * 16);
-      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * 16 + 4);
+      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * BK);
+      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * BK + 4);
     }
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q)
@@ -212,23 +222,25 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // ---- fragments (tile and sub-tile offsets are multiples of 32 rows, so the swizzle key depends on l32 only)
-  const int f_off = fr.l32 * 32 + ((fr.half ^ ((fr.l32 >> 3) & 1)) * 16);
-  const uint8_t* fa = lds_a + fr.wm * Cfg::WM * 32 + f_off;
-  const uint8_t* fb = lds_b + fr.wn * Cfg::WN * 32 + f_off;
+  int f_off[NG];   // group g: chunk 2 g + half of this lane's rows
+#pragma unroll
+  for (int g = 0; g < NG; ++g) f_off[g] = fr.l32 * RB + Cfg::slot(fr.l32, 2 * g + fr.half) * 16;
+  const uint8_t* fa = lds_a + fr.wm * Cfg::WM * RB;
+  const uint8_t* fb = lds_b + fr.wn * Cfg::WN * RB;
   v8bf af[2][3][MI], bf[2][3][NJ];
-  auto read_frags = [&](auto stage) {   // LDS stage `stage` -> fragment buffer `stage`
+  auto read_frags = [&](auto stage, auto g, auto buf) {   // group g of LDS stage `stage` -> fragment buffer `buf`
 #pragma unroll
     for (int pl = 0; pl < 3; ++pl) {
 #pragma unroll
       for (int i = 0; i < MI; ++i)
-        af[stage][pl][i] = *reinterpret_cast<const v8bf*>(fa + stage * A_STAGE + pl * A_PLANE + i * 32 * 32);
+        af[buf][pl][i] = *reinterpret_cast<const v8bf*>(fa + stage * A_STAGE + pl * A_PLANE + i * 32 * RB + f_off[g]);
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        bf[stage][pl][j] = *reinterpret_cast<const v8bf*>(fb + stage * B_STAGE + pl * B_PLANE + j * 32 * 32);
+        bf[buf][pl][j] = *reinterpret_cast<const v8bf*>(fb + stage * B_STAGE + pl * B_PLANE + j * 32 * RB + f_off[g]);
     }
   };
-  constexpr int G = MI * NJ, NM = 6 * G;     // MFMAs per plane pair and per slab
-  auto mma = [&](auto buf, int first, int count) {   // MFMAs first .. first+count-1 of a slab
+  constexpr int G = MI * NJ, NM = 6 * G;     // MFMAs per plane pair and per group
+  auto mma = [&](auto buf, int first, int count) {   // MFMAs first .. first+count-1 of a group
     constexpr int pa[6] = {0, 0, 1, 1, 0, 2};
     constexpr int pb[6] = {0, 1, 0, 1, 2, 0};
 #pragma unroll
@@ -248,17 +260,25 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   if (nk > 1) gload(1, I1());
   sstore(I0());
   lds_barrier();
-  read_frags(I0());
+  read_frags(I0(), I0(), I0());
 
-  // One slab, par = kt & 1.  steady: slabs kt+1 and kt+2 exist -- no branches, so that the interleaving
-  // below holds (a scheduling group does not cross a branch).
+  // One slab, par = kt & 1 (its LDS stage and register slot).  Fragment buffers: with one group per slab the
+  // buffer of a slab is its parity; with two, group g sits in buffer g (buffer 0 is free again once group 0 has
+  // issued, which is before the hand-over).  steady: slabs kt+1 and kt+2 exist -- no branches, so that the
+  // interleaving below holds (a scheduling group does not cross a branch).
   auto slab = [&](int kt, auto par, auto npar, auto steady) {
     const bool l2 = steady || kt + 2 < nk, s1 = steady || kt + 1 < nk;
+    typedef std::integral_constant<int, (NG == 1 ? decltype(par)::value : NG - 1)> LastBuf;   // buffer of the last group
+    typedef std::integral_constant<int, (NG == 1 ? decltype(npar)::value : 0)> NextBuf;       // of group 0 of the next slab
     __builtin_amdgcn_s_setprio(2);
     if (l2) gload(kt + 2, par);     // slot par held slab kt, which went to LDS during slab kt-1
-    mma(par, 0, NM / 2);
+    if constexpr (NG == 2) {
+      read_frags(par, I1(), I1());
+      mma(I0(), 0, NM);
+    }
+    mma(LastBuf(), 0, NM / 2);
     if (s1) sstore(npar);           // stage npar: its last readers (slab kt-1) passed the barrier of slab kt-1
-    if (steady) {
+    if (steady && NG == 1) {
       // first half: a load behind each of the first MFMAs, then the copy and the split spread over the rest
       constexpr int NL = B_LOADS + 2 * RA, NV = NM / 2 - NL;
       sched_pairs<0x020, NL, 1>();
@@ -266,10 +286,10 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
     }
     if (s1) {
       lds_barrier();
-      read_frags(npar);
+      read_frags(npar, I0(), NextBuf());
     }
-    mma(par, NM / 2, NM - NM / 2);
-    if (steady) sched_pairs<0x100, NM - NM / 2, (3 * (MI + NJ) + NM - NM / 2 - 1) / (NM - NM / 2)>();
+    mma(LastBuf(), NM / 2, NM - NM / 2);
+    if (steady && NG == 1) sched_pairs<0x100, NM - NM / 2, (3 * (MI + NJ) + NM - NM / 2 - 1) / (NM - NM / 2)>();
     __builtin_amdgcn_s_setprio(0);
   };
   typedef std::integral_constant<bool, true> Steady;
@@ -287,16 +307,24 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
 
   op.template finish<Cfg>(lrow, lkq, s_row);
   __syncthreads();
+  if constexpr (Op::kSplitK) {
+    if (splits > 1) {   // partial tile and row sums to scratch; the Op's owner finishes (as for gemm_f32.h)
+      op.template store_partial<Cfg>(acc, fr, m0, n0, M, M_max, N, s_row, part, (int)blockIdx.z, splits);
+      return;
+    }
+  }
   op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
+// splits > 1 (Ops with kSplitK, not with ROWS_PER_XCD): `part` = gemm_f32_splitk_floats(splits, M_max, N) floats.
 template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
-                                        Op op, hipStream_t st) {
-  if (K % 16 != 0 || K <= 0) return hipErrorInvalidValue;
+                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr) {
+  if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
+  if (splits > 1 && (!Op::kSplitK || ROWS_PER_XCD || !part || (K / Cfg::BK) % splits != 0)) return hipErrorInvalidValue;
   unsigned mt = (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM);
   if (ROWS_PER_XCD) mt = (mt + 7) / 8 * 8;
-  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), mt);
+  dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), mt, (unsigned)splits);
   auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL, ROWS_PER_XCD>;
   static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {
@@ -305,7 +333,7 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bimg, op);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bimg, op, part);
   return hipGetLastError();
 }
 

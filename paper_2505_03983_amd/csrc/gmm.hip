@@ -32,6 +32,8 @@ typedef GemmCfg<128, 128, 16> GmmTile;
 typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one row per chain, fill the chip
 // verify call on the bf16 matrix pipe with three-way split operands (fp32 accuracy)
 typedef Split3Cfg<128, 128, 2, 2> GmmTileSplit;
+// draft call on the same pipe: half-height tiles, four wavefronts of 32 x 64, K slabs of 32
+typedef Split3Cfg<64, 128, 2, 2, 32> GmmTileSplitSkinny;
 
 // (kappa, gamma, cx, cm) of a row
 __device__ __forceinline__ float4 row_coef(const float4* coef_tau, const int32_t* tau, int n) {
@@ -509,6 +511,13 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     ASD_HIP(hipMalloc(&g->means_t_img, split3_image_bytes<GmmTileSplit>(d, C)));
     ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means, d, C, d, g->means_img, 0));
     ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means_t, C, d, C, g->means_t_img, 0));
+    if (d % 32 == 0 && C % 32 == 0) {   // the draft call's tiling has its own images (K slabs of 32)
+      ASD_HIP(hipMalloc(&g->means_img_s, split3_image_bytes<GmmTileSplitSkinny>(C, d)));
+      ASD_HIP(hipMalloc(&g->means_t_img_s, split3_image_bytes<GmmTileSplitSkinny>(d, C)));
+      ASD_HIP(launch_split3_pack_b<GmmTileSplitSkinny>(g->means, d, C, d, g->means_img_s, 0));
+      ASD_HIP(launch_split3_pack_b<GmmTileSplitSkinny>(g->means_t, C, d, C, g->means_t_img_s, 0));
+      g->split_draft_ok = true;
+    }
     ASD_HIP(hipDeviceSynchronize());
     g->split_ok = g->use_split = true;
   }
@@ -538,6 +547,8 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->means_t);
   (void)hipFree(g->means_img);
   (void)hipFree(g->means_t_img);
+  (void)hipFree(g->means_img_s);
+  (void)hipFree(g->means_t_img_s);
   (void)hipFree(g->musq);
   (void)hipFree(g->coef_tau);
   (void)hipFree(g->part);
@@ -570,24 +581,36 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     return ASD_OK;
   }
   // partial row maxima per row: one per wavefront column of the tiling in use
-  const bool split = rows.call == 1 && g->use_split;
+  const bool split = g->use_split && (rows.call == 1 || g->split_draft_ok);
+  static_assert(GmmTileSplit::BN == GmmTileSplitSkinny::BN && GmmTileSplit::WGN == GmmTileSplitSkinny::WGN,
+                "the two split tilings lay the row maxima out alike");
   const int np = split ? GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN)
                        : 2 * (int)ceil_div(C, rows.call ? GmmTile::BN : GmmTileSkinny::BN);
+  // K split of the draft call's second GEMM (few output tiles, long K); both of its tilings use slabs of 32
+  static_assert(GmmTileSplitSkinny::BK == GmmTileSkinny::BK, "one split plan for both");
+  const int splits = (!rows.call && g->draft_splits > 1 && n <= ctx->B) ? g->draft_splits : 1;
   RowSrc X{rows.in_base, rows.in_off, 0};
   LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
-            : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
+    if (split)
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
+                        : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img_s,
+                                                                               op1, st));
+    else
+      ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
   RowSrc P{g->logits, nullptr, C};
   CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    const int splits = (!rows.call && g->draft_splits > 1 && n <= ctx->B) ? g->draft_splits : 1;
-    ASD_HIP(split       ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
-            : rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
+    if (split)
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
+                        : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img_s,
+                                                                               op2, st, splits, g->part));
+    else
+      ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st, splits,
                                                                 g->part));
     if (splits > 1) {

@@ -23,6 +23,9 @@ struct GmmState {
   // split-bf16 verify GEMMs (gemm_split3.h): the means, split and laid out as LDS images, for both GEMMs
   uint8_t* means_img = nullptr;    // B of the logits GEMM  ([C, d])
   uint8_t* means_t_img = nullptr;  // B of the combine GEMM ([d, C])
+  uint8_t* means_img_s = nullptr;  // the same two for the draft call's tiling (K slabs of 32)
+  uint8_t* means_t_img_s = nullptr;
+  bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
   size_t rowwise_lds = 0;
