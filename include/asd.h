@@ -205,12 +205,13 @@ ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
 /* 1 if the next asd_sample on this context will take that path (shape fits, switch on, profiling off). */
 ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 
-/* Verify-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
+/* Model-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
  * operand split into three bf16 terms (six bf16 products per fp32 product, fp32 accumulation; what
- * is left out is 2^-23 of |a||b| per product on average and never above 2^-21, a few units of fp32 rounding).  Nothing in the
- * method changes: it is another way to evaluate the same fp32 contraction, about 1.5x faster on this
- * chip than its fp32 matrix pipe.  Taken when d % 16 == 0 and C % 16 == 0 on the matrix-core path;
- * on = 0 selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
+ * is left out is 2^-23 of |a||b| per product on average and never above 2^-21, a few units of fp32
+ * rounding).  Nothing in the method changes: it is another way to evaluate the same fp32 contraction,
+ * about 1.5x faster on this chip than its fp32 matrix pipe.  The verify call takes it when d % 16 == 0
+ * and C % 16 == 0 on the matrix-core path, the draft call when both are multiples of 32; on = 0
+ * selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on);
 /* 1 if the verify call of this context runs the split kernels. */
 ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
