@@ -261,10 +261,14 @@ def test_mfma_ceiling_probe():
 def test_round_midsize_matrix_core_shapes():
     """Rounds whose two model calls both take the matrix-core path on shapes that are not tile multiples:
     a draft call of 70 rows with its second GEMM split over K (C = 1024, fp32 MFMA: d is not a multiple of 16),
-    and a shape that takes the split-operand kernels for the verify call (d = 48, C = 1040: ragged last column
-    tile, one-row-tile draft call without a K split)."""
+    a shape that takes the split-operand kernels for the verify call only (d = 48, C = 1040: ragged last column
+    tile, fp32 draft call without a K split), and two that take them for both calls."""
     for cfg in (dict(kind="gmm", d=40, C=1024, K=30, chains=70, L=24, var=0.25),
-                dict(kind="gmm", d=48, C=1040, K=20, chains=90, L=16, var=0.25)):
+                dict(kind="gmm", d=48, C=1040, K=20, chains=90, L=16, var=0.25),
+                # both calls on the split-operand kernels: an odd number of 32-wide K slabs and a ragged column tile
+                # (no K split), then a ragged row tile with the second GEMM's K split two ways
+                dict(kind="gmm", d=96, C=1056, K=20, chains=90, L=8, var=0.25),
+                dict(kind="gmm", d=64, C=1024, K=20, chains=70, L=16, var=0.25)):
         _teacher_forced(cfg, seed=2, chains_checked=[0, 33, cfg["chains"] - 1], rounds_per_chain=2)
 
 
