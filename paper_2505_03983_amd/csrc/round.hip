@@ -113,7 +113,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
   __shared__ int s_off[1024], s_cnt[1024], s_ac[1024];
   // A round starts here: advance the round index and clear this round's slot of the live-chain ring
   // (ring[0] = index of the next round, ring[1 + r % kLiveRing] = chains still unfinished after round r).
-  if (threadIdx.x == 0 && ring) {
+  if (threadIdx.x == 0 && blockIdx.x == 0 && ring) {
     const int r = ring[0];
     ring[0] = r + 1;
     ring[1 + (r % kLiveRing)] = 0;
@@ -140,7 +140,9 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
       s_cnt[threadIdx.x] = cnt;
       s_ac[threadIdx.x] = ac;
       __syncthreads();
-      for (int t = wave; t < 1024 && c0 + t < B; t += 16) {
+      // (every workgroup of the launch computes the whole scan -- it is a thousand integers -- and fills the rows of
+      // its share of the chains, so nothing has to pass between workgroups)
+      for (int t = wave + 16 * (int)blockIdx.x; t < 1024 && c0 + t < B; t += 16 * (int)gridDim.x) {
         const int n_t = s_cnt[t], o_t = s_off[t], a_t = s_ac[t], c_t = c0 + t;
         for (int s = 1 + lane; s <= n_t; s += 64) {
           const int i = a_t + s;
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     base += s_total;
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
     *n_rows = base;
     if (row_counts) atomicAdd((unsigned long long*)&row_counts[MODE], (unsigned long long)base);
   }
@@ -171,7 +173,9 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   if (ctx->L <= 1) return ASD_OK;
   ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
-  hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
+  // up to 64 workgroups share the filling of a large plan (a chain per wavefront at a time, see the kernel)
+  const unsigned wgs = (unsigned)std::min<int64_t>(64, std::max<int64_t>(1, ctx->n_rows_max / 1024));
+  hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
                      ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win);
   ASD_HIP(hipGetLastError());
