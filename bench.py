@@ -265,6 +265,9 @@ def main():
     ap.add_argument("--fp32-mfma", action="store_true",
                     help="Gaussian-mixture verify GEMMs on the fp32 matrix pipe instead of the bf16 pipe with "
                          "three-way split operands")
+    ap.add_argument("--window-control", action="store_true",
+                    help="time the sample with the per-chain window controller on (an extension of Alg. 1; the "
+                         "default run keeps the configured fixed L and reports this mode in `window_control`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -287,13 +290,13 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma,
-                  clocks=True)
+                  clocks=True, adaptive=args.window_control)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
     cfg = res["cfg"]
     line = {
-        "metric": "DDPM steps/s (chains*K/wall) for ASD at 1 GPU",
+        "metric": "DDPM steps/s (chains*K/wall) for ASD at 1 GPU" + (" [window control on]" if args.window_control else ""),
         "value": res["steps_per_s"],
         "unit": "DDPM steps/s",
         "n_gpus": 1,
