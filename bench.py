@@ -332,8 +332,9 @@ def main():
         # (skipped with --others 0, so that a profiler run of this script sees the sampling kernels only)
         # what the matrix pipes of this chip sustain on random operands with no memory traffic at all (the chip is
         # power-limited on dense MFMA work: the data-sheet peaks above hold for constant operands only)
-        from paper_2505_03983_amd import binding
-        sus = {"bf16": binding.asd_mfma_ceiling(True, True, 300), "f32": binding.asd_mfma_ceiling(False, True, 300)}
+        from paper_2505_03983_amd import probe
+        sus = {"bf16": probe.asd_probe_mfma_ceiling(True, True, 300),
+               "f32": probe.asd_probe_mfma_ceiling(False, True, 300)}
         rf = line["roofline"]
         if rf["bound"] == "mfma":
             rf["sustained_random_operands"] = sus[rf["mfma_dtype"]]

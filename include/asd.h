@@ -14,9 +14,11 @@
  * Conventions
  *  - "HOST" pointers are read during the call and may be freed afterwards.
  *    "DEV" pointers are device (HBM) memory owned by the caller; the library
- *    never frees them.  Denoiser weight pointers given to asd_init must stay
- *    valid until asd_destroy; every other pointer is only used by the call it
- *    is passed to (asynchronously, on `stream`).
+ *    never frees them.  The denoiser's DEV parameters given to asd_init (GMM:
+ *    means, log_w; MLP: biases and the time-embedding table; the MLP weight
+ *    matrices are copied) must stay valid until asd_destroy; every other
+ *    pointer is only used by the call it is passed to (asynchronously, on
+ *    `stream`).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Stage calls are asynchronous; only asd_sample synchronises (it polls a
  *    per-round live-chain count).
@@ -135,11 +137,13 @@ typedef struct {
 
 /* Validates the configuration (ASD_EINVAL / ASD_EUNSUPPORTED before touching
  * the device), copies the tables to the device and allocates all scratch
- * (sized for chains*L rows).  *out is NULL on failure. */
+ * (sized for chains*L rows; the stage and sampling calls allocate no device
+ * memory).  chains <= 65535 (ASD_EUNSUPPORTED above).  *out is NULL on failure. */
 ASD_API asd_status asd_init(const asd_config* cfg, asd_ctx** out);
 ASD_API asd_status asd_destroy(asd_ctx* ctx); /* NULL is allowed */
 
-/* Re-key the random streams; the next asd_sample / stage calls use it. */
+/* Re-key the random streams; the next asd_sample / stage calls use it.  Waits for
+ * the work this context has queued (it may still read the old key). */
 ASD_API asd_status asd_set_seed(asd_ctx* ctx, uint64_t seed);
 
 /* ---- one round (body of the while-loop of Alg. 1), three stages ----------
@@ -202,8 +206,6 @@ ASD_API asd_status asd_use_adaptive_window(asd_ctx* ctx, int32_t on);
  * meaning and asd_last_round_count returns the largest of them).  on = 0 forces the lock-step
  * round kernels; the two paths agree to rounding.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
-/* 1 if the next asd_sample on this context will take that path (shape fits, switch on, profiling off). */
-ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 
 /* Model-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
  * operand split into three bf16 terms (six bf16 products per fp32 product, fp32 accumulation; what
@@ -213,8 +215,6 @@ ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
  * and C % 16 == 0 on the matrix-core path, the draft call when both are multiples of 32; on = 0
  * selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on);
-/* 1 if the verify call of this context runs the split kernels. */
-ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 
 /* Sequential chain with the same random inputs (one model call per step, K
  * launches): the baseline ASD is compared against in the paper's speedups. */
@@ -223,54 +223,11 @@ ASD_API asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* t
 /* Number of lock-step rounds launched by the last asd_sample (host value). */
 ASD_API int32_t asd_last_round_count(const asd_ctx* ctx);
 
-/* ---- pieces exposed for testing and profiling ----------------------------
- * asd_denoise: out[n] = D(x[n], tau[n]) for n rows (n <= chains*L).
+/* ---- the model call on its own ---------------------------------------------
+ * asd_denoise: out[n] = D(x[n], tau[n]) for n rows (n <= chains*L), through the
+ *   kernels of the batched verify call.
  *   x, out DEV fp32 [n, d]; tau DEV int32 [n]. */
 ASD_API asd_status asd_denoise(asd_ctx* ctx, const float* x, const int32_t* tau, int32_t n, float* out, void* stream);
-
-/* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
- * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
-ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,
-                            int32_t nblk, uint32_t* out, void* stream);
-/* xi DEV fp32 [d] = the normals of (chain, step); u DEV fp32 [1] = the uniform. */
-ASD_API asd_status asd_debug_randoms(uint64_t seed, uint32_t chain, uint32_t step, int32_t d,
-                             float* xi, float* u, void* stream);
-
-/* ---- per-kernel timing -------------------------------------------------------
- * When enabled, every kernel launch of the sampling path is bracketed by HIP
- * events on its own stream.  asd_profile_read synchronises the device and
- * returns, for one kernel kind within one of the two model calls (call = 0:
- * the draft call on one row per chain, call = 1: the batched verify call;
- * kinds that belong to no model call use call = 0), the number of launches
- * and their summed duration since the last asd_profile_enable(ctx, 1).
- * asd_profile_rows returns the number of live rows (rows inside a window of an
- * unfinished chain) the two model calls were asked to evaluate since then. */
-typedef enum {
-  ASD_PROF_MODEL = 0,        /* a whole model call (all its kernels)          */
-  ASD_PROF_PLAN = 1,         /* row planning                                  */
-  ASD_PROF_GMM_ROWWISE = 2,  /* GMM denoiser, one wavefront per row           */
-  ASD_PROF_GMM_LOGITS = 3,   /* GMM logits GEMM  X M^T  (fp32 MFMA)           */
-  ASD_PROF_GMM_SOFTMAX = 4,  /* GMM row softmax                               */
-  ASD_PROF_GMM_COMBINE = 5,  /* GMM  P M  GEMM + affine combination           */
-  ASD_PROF_MLP_PACK = 6,     /* MLP input packing (bf16 x ; time embedding)   */
-  ASD_PROF_MLP_GEMM_IN = 7,  /* MLP first layer                               */
-  ASD_PROF_MLP_GEMM_BLK = 8, /* MLP residual blocks (one launch per block)    */
-  ASD_PROF_MLP_GEMM_OUT = 9, /* MLP output layer                              */
-  ASD_PROF_DRAFT = 10,       /* fused draft kernel                            */
-  ASD_PROF_ACCEPT = 11,      /* fused accept / scan / resample kernel         */
-  ASD_PROF_KINDS = 16
-} asd_prof_kernel;
-ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
-ASD_API asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms);
-ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows);
-
-/* What the matrix pipe of the current device sustains: a register-only loop of 32x32 MFMAs (bf16 != 0:
- * v_mfma_f32_32x32x16_bf16, else v_mfma_f32_32x32x2_f32) with no memory traffic, run for about
- * ms_target milliseconds (1..5000) on the default stream; *tflops HOST receives the rate of the second
- * half of the run.  random_data != 0: zero-mean random operands, as in real use; 0: constant operands.
- * The chip is power-limited on dense MFMA work, so the two differ widely and the first -- not the
- * data-sheet peak -- is the ceiling a GEMM on real data can approach.  Allocates and frees a few MB; synchronous. */
-ASD_API asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops);
 
 /* ---- host-only helpers -----------------------------------------------------
  * DDPM linear-beta schedule (beta_tau from beta_min to beta_max over tau=1..K)

@@ -25,7 +25,7 @@ Readings of the printed algorithms (each is argued in the design notes):
 """
 import numpy as np
 
-from .grs import grs
+from .grs import grs, reflect
 
 
 def sequential_chain(y0, A, Bc, sigma, model, xi):
@@ -54,7 +54,12 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
     compared against: yhat (proposal samples for steps a+1..b), g (model
     values at slots i=a..b-1), acc (bits of slots a+1..b), log_ratio, log_u,
     dot = <v,xi>, vv = |v|^2, flagged (near-tie), j, r (index of the
-    resampled step or -1), y_new (values of y_{a+1..a_next}), a_next.
+    resampled step or -1), y_new (values of y_{a+1..a_next}), a_next, and
+    z_rej: what every slot's step would become were the slot rejected (the
+    reject branch of Alg. 3; the target mean where sigma = 0; NaN for slot a+1,
+    which cannot be rejected).  A comparison that has to follow another
+    implementation through a flagged near-tie decision takes the other
+    branch's value from z_rej.
     """
     K = len(A)
     b = min(K, a + L)
@@ -86,6 +91,7 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
     dot = np.zeros(w)
     vv = np.zeros(w)
     flagged = np.zeros(w, dtype=bool)
+    z_rej = np.full((w, d), np.nan)
     for k in range(w):
         i = a + k
         v = m_hat[k + 1] - m[k + 1]
@@ -96,11 +102,12 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
             z[k] = yhat[k + 1]
         elif sigma[i] == 0.0:
             acc[k] = False
-            z[k] = m[k + 1]
+            z[k] = z_rej[k] = m[k + 1]
         else:
             z[k], acc[k], log_ratio[k] = grs(u[i + 1], xi[i + 1], m_hat[k + 1], m[k + 1], sigma[i])
             log_u[k] = np.log(u[i + 1])
             flagged[k] = near_tie(log_u[k], log_ratio[k], eps)
+            z_rej[k] = reflect(xi[i + 1], m_hat[k + 1], m[k + 1], sigma[i]) if vv[k] > 0.0 else z[k]
     # --- accepted prefix
     n_acc = 0
     while n_acc < w and acc[n_acc]:
@@ -117,7 +124,7 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
         r = -1
     return dict(a=a, b=b, j=j, r=r, a_next=a_next, yhat=yhat[1:], g=g, acc=acc,
                 log_ratio=log_ratio, log_u=log_u, dot=dot, vv=vv, flagged=flagged,
-                y_new=y_new)
+                y_new=y_new, z_rej=z_rej)
 
 
 def window_init(L):

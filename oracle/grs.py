@@ -12,6 +12,13 @@ def log_accept_ratio(xi, v, sigma):
     return 0.5 * (np.dot(xi, xi) - np.dot(shifted, shifted))
 
 
+def reflect(xi, m_hat, m, sigma):
+    """Reject branch of Alg. 3: m + sigma (xi - 2 v <v,xi>/|v|^2), v = m_hat - m: the noise is mirrored
+    across the hyperplane orthogonal to v and added to the target mean.  Requires v != 0."""
+    v = m_hat - m
+    return m + sigma * (xi - 2.0 * v * (np.dot(v, xi) / np.dot(v, v)))
+
+
 def grs(u, xi, m_hat, m, sigma):
     """One call of Alg. 3.  Returns (x, accepted, log_ratio).
 
@@ -24,5 +31,4 @@ def grs(u, xi, m_hat, m, sigma):
     lr = log_accept_ratio(xi, v, sigma)
     if np.log(u) <= min(0.0, lr):
         return m_hat + sigma * xi, True, lr
-    vv = np.dot(v, v)
-    return m + sigma * (xi - 2.0 * v * (np.dot(v, xi) / vv)), False, lr
+    return reflect(xi, m_hat, m, sigma), False, lr

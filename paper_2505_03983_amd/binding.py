@@ -1,4 +1,5 @@
-"""Thin ctypes binding of libasd.so: same names as include/asd.h, argument
+"""Thin ctypes binding of libasd.so: same names as include/asd.h (the sampling
+boundary) and include/asd_testing.h (test / profiling hooks), argument
 marshalling only.  Every step of the sampling path runs in the HIP library;
 PyTorch is used for device memory and streams."""
 import ctypes as C
@@ -73,7 +74,6 @@ def lib():
             "asd_profile_enable": (i32, [vp, i32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
             "asd_profile_rows": (i32, [vp, vp, vp]),
-            "asd_mfma_ceiling": (i32, [i32, i32, i32, vp]),
             "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
             "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
@@ -211,16 +211,23 @@ class Ctx:
     def __init__(self, sched, den, L, chains, seed=0):
         self.cfg, self._keep = make_config(sched, den, L, chains, seed)
         h = C.c_void_p()
+        self._destroy = lib().asd_destroy
         _check(lib().asd_init(C.byref(self.cfg), C.byref(h)))
         self.h = h
         self.K, self.L, self.chains, self.d = self.cfg.sched.K, int(L), int(chains), self.cfg.den.d
 
     def close(self):
-        if getattr(self, "h", None):
-            lib().asd_destroy(self.h)
-            self.h = None
+        h, self.h = getattr(self, "h", None), None
+        if h:
+            self._destroy(h)
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter exit module globals may already be gone: the destroy function was captured at
+        # construction, and whatever still fails then is of no consequence
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def use_graphs(self, on=True):
         _check(lib().asd_use_graphs(self.h, int(bool(on))))
@@ -275,13 +282,6 @@ class Ctx:
 
     def denoise(self, x, tau, out, stream=None):
         _check(lib().asd_denoise(self.h, _ptr(x), _ptr(tau), int(x.shape[0]), _ptr(out), _stream(stream)))
-
-
-def asd_mfma_ceiling(bf16, random_data=True, ms_target=200):
-    """TFLOP/s a register-only MFMA loop sustains on the current device."""
-    t = C.c_double(0.0)
-    _check(lib().asd_mfma_ceiling(int(bool(bf16)), int(bool(random_data)), int(ms_target), C.addressof(t)))
-    return t.value
 
 
 def asd_debug_philox(seed, chain, step, stream_id, nblk, out, stream=None):

@@ -1,4 +1,5 @@
-"""Builds libasd.so (HIP, gfx950) in-tree with hipcc.  Run: python -m paper_2505_03983_amd.build"""
+"""Builds libasd.so (the sampling library) and libasd_probe.so (a measurement probe for bench.py) in-tree
+with hipcc for gfx950.  Run: python -m paper_2505_03983_amd.build"""
 import os
 import subprocess
 import sys
@@ -6,7 +7,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasd.so")
-SOURCES = ["api.hip", "round.hip", "gmm.hip", "gmm_chain.hip", "mlp.hip", "ceiling.hip"]
+PROBE_LIB = os.path.join(HERE, "libasd_probe.so")
+SOURCES = ["api.hip", "round.hip", "gmm.hip", "gmm_chain.hip", "mlp.hip"]
+PROBE_SOURCES = ["probe/ceiling.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -15,10 +18,16 @@ FLAGS = [
 
 
 def build(verbose=True, defines=(), lib=LIB, tag=""):
+    _build_one(SOURCES, lib, verbose, defines, tag)
+    _build_one(PROBE_SOURCES, PROBE_LIB, verbose, (), tag)
+    return lib
+
+
+def _build_one(sources, lib, verbose, defines, tag):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
-    for src in SOURCES:
+    for src in sources:
         obj = os.path.join(CSRC, src.replace(".hip", tag + ".o"))
         cmd = [hipcc] + [f for f in FLAGS if f != "-shared"] + ["-D" + d for d in defines] + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -126,6 +126,7 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->n_rows_dev, sizeof(int32_t) * 2));
   ASD_HIP(hipMemset(ctx->n_rows_dev, 0, sizeof(int32_t) * 2));
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
+  ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * rows * (size_t)ctx->d));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 2));
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
@@ -184,6 +185,18 @@ static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
   return RowPlan{ctx->B * (ctx->L - 1), ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
 }
 
+__global__ void set_key_kernel(Key* dst, Key key) { *dst = key; }
+
+// The kernels read the key from device memory (so that a captured round does not depend on the seed); a new
+// key travels as a kernel argument and is stored in stream order ahead of the launches that read it.
+static asd_status flush_key(asd_ctx* ctx, hipStream_t st) {
+  if (!ctx->key_dirty) return ASD_OK;
+  hipLaunchKernelGGL(set_key_kernel, dim3(1), dim3(1), 0, st, ctx->key_dev, ctx->key);
+  ASD_HIP(hipGetLastError());
+  ctx->key_dirty = false;
+  return ASD_OK;
+}
+
 __global__ void plan_dense_kernel(int n, int d, int n_tau, const int32_t* __restrict__ tau,
                                   int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
                                   int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows) {
@@ -225,10 +238,9 @@ asd_status asd_destroy(asd_ctx* ctx) {
 }
 
 asd_status asd_set_seed(asd_ctx* ctx, uint64_t seed) {
-  ASD_TRY(check_ctx(ctx));
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   ctx->key = make_key(seed);
-  ASD_HIP(hipDeviceSynchronize());  // nothing in flight may still read the old key
-  ASD_HIP(hipMemcpy(ctx->key_dev, &ctx->key, sizeof(Key), hipMemcpyHostToDevice));
+  ctx->key_dirty = true;   // written to the device by the next call that launches kernels, in stream order
   return ASD_OK;
 }
 
@@ -238,6 +250,7 @@ asd_status asd_draft(asd_ctx* ctx, float* traj, const int32_t* a, void* stream) 
   if (!a) return fail(ASD_EINVAL, "a is NULL");
   if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_draft called out of order (expected stage %d)", ctx->stage);
   hipStream_t st = (hipStream_t)stream;
+  ASD_TRY(flush_key(ctx, st));
   ASD_TRY(launch_plan_draft(ctx, a, st));
   ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
   ASD_TRY(launch_draft(ctx, traj, a, st));
@@ -268,13 +281,14 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
   ASD_TRY(check_rows_ptr(ctx, x0hat, "x0hat"));
   if (!a) return fail(ASD_EINVAL, "a is NULL");
   if (ctx->stage != 2) return fail(ASD_ESTATE, "asd_accept called out of order (expected stage %d)", ctx->stage);
+  ASD_TRY(flush_key(ctx, (hipStream_t)stream));
   ASD_TRY(launch_accept(ctx, traj, a, x0hat, accepted, stats, nullptr, nullptr, (hipStream_t)stream));
   ctx->stage = 0;
   return ASD_OK;
 }
 
 // All launches of one round of Alg. 1 on `st`, plus the copy of the live-chain ring to the host.
-static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
+static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, float* x0hat, hipStream_t st) {
   // No planning kernels here: the rows of the draft call were listed by the previous round's accept
   // kernel (by init_state before round 0), those of the verify call are listed by the draft kernel.
   // (or, for large batches, by the planning kernels: see fold_plans)
@@ -283,9 +297,9 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, hipS
   ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live));
   if (ctx->L > 1) {
     if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
-    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, ctx->x0hat), st));
+    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
   }
-  ASD_TRY(launch_accept(ctx, traj, ctx->a, ctx->x0hat, nullptr, nullptr, rounds, ctx->live, st));
+  ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, nullptr, nullptr, rounds, ctx->live, st));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
   ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * kLiveRing, hipMemcpyDeviceToHost, st));
@@ -301,7 +315,7 @@ static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds,
     return ASD_OK;
   hipGraph_t graph = nullptr;
   ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-  asd_status s = enqueue_round(ctx, traj, rounds, st);
+  asd_status s = enqueue_round(ctx, traj, rounds, ctx->x0hat, st);
   hipError_t e = hipStreamEndCapture(st, &graph);
   if (s != ASD_OK) {
     if (graph) (void)hipGraphDestroy(graph);
@@ -322,17 +336,10 @@ static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds,
   return ASD_OK;
 }
 
-asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream) {
-  ASD_TRY(check_ctx(ctx));
-  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
-  if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
-  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample called between stage calls");
-  hipStream_t st = (hipStream_t)stream;
-  // Small mixtures: the whole sample is one launch, a workgroup per chain (profiling wants the
-  // stand-alone kernels, whose times it reports).
-  if (ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx))
-    return gmm_chain_sample(ctx, y0, traj, rounds, st);
-  if (!ctx->x0hat) ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->n_rows_max * ctx->d));
+// The while-loop of Alg. 1 in lock step over the chains, on the round kernels.  x0hat: where the verify call
+// leaves its outputs; allow_setup: the call may create streams and graphs and take the one-launch path.
+static asd_status sample_rounds(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, float* x0hat,
+                                bool allow_setup, hipStream_t st) {
   struct WinScope {  // the round kernels see the per-chain windows only while this sample runs
     asd_ctx* c;
     explicit WinScope(asd_ctx* x) : c(x) {
@@ -352,7 +359,7 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   // round it has just queued; a finished batch then runs `lag` empty rounds, which cost next to nothing
   // (every kernel exits at once on finished chains and the model calls see zero rows).
   const int lag = 2;
-  const bool use_graph = ctx->graphs_enabled && !ctx->prof.on;
+  const bool use_graph = allow_setup && ctx->graphs_enabled && !ctx->prof.on;
   hipStream_t caller = st;
   if (use_graph && st == nullptr) {
     // the legacy default stream cannot be captured: run on a stream of our own, ordered after the caller's work
@@ -361,6 +368,7 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
     ASD_HIP(hipStreamWaitEvent(ctx->own_stream, ctx->live_ev[0], 0));
     st = ctx->own_stream;
   }
+  ASD_TRY(flush_key(ctx, st));
   ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, rounds, st));
   int r = 0;
   int done_at = -1;
@@ -371,7 +379,7 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
       if (r == 1) ASD_TRY(ensure_round_graph(ctx, traj, rounds, st));  // round 0 ran eagerly (first-use set-up)
       ASD_HIP(hipGraphLaunch(ctx->gexec, st));
     } else {
-      ASD_TRY(enqueue_round(ctx, traj, rounds, st));
+      ASD_TRY(enqueue_round(ctx, traj, rounds, x0hat, st));
     }
     ASD_HIP(hipEventRecord(ctx->live_ev[slot], st));
     if (r >= lag) {
@@ -389,12 +397,28 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
   return ASD_OK;
 }
 
+asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample called between stage calls");
+  hipStream_t st = (hipStream_t)stream;
+  // Small mixtures: the whole sample is one launch, a workgroup per chain (profiling wants the
+  // stand-alone kernels, whose times it reports).
+  if (ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx)) {
+    ASD_TRY(flush_key(ctx, st));
+    return gmm_chain_sample(ctx, y0, traj, rounds, st);
+  }
+  return sample_rounds(ctx, y0, traj, rounds, ctx->x0hat, true, st);
+}
+
 asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream) {
   ASD_TRY(check_ctx(ctx));
   ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
   if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
   if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample_sequential called between stage calls");
   hipStream_t st = (hipStream_t)stream;
+  ASD_TRY(flush_key(ctx, st));
   ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, nullptr, st));
   for (int i = 0; i < ctx->K; ++i) {
     ASD_TRY(launch_plan_seq(ctx, i, st));

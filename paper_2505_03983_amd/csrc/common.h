@@ -6,7 +6,7 @@
 #include <string>
 #include <vector>
 
-#include "../../include/asd.h"
+#include "../../include/asd_testing.h"
 #include "rng.h"
 
 namespace asd {
@@ -104,6 +104,7 @@ struct asd_ctx {
   int64_t n_rows_max = 0;  // B * L
   asd::Key key{0, 0};
   asd::Key* key_dev = nullptr;    // DEV copy of the key: kernels read it, so launches do not depend on the seed
+  bool key_dirty = false;         // key differs from *key_dev: the next launching call stores it first
   int kind = 0;
   // schedule on the device
   float* c_x = nullptr;

@@ -29,18 +29,6 @@ namespace asd {
 
 namespace {
 
-// Stage timing for development (-DASD_CHAIN_TIMING): thread 0 of chain 0 prints the cycles it spent
-// up to each mark, summed over rounds.
-#ifdef ASD_CHAIN_TIMING
-#define ASD_T_DECL long long t_acc[6] = {0, 0, 0, 0, 0, 0}; long long t_prev = clock64();
-#define ASD_T(i) { const long long t_now = clock64(); t_acc[i] += t_now - t_prev; t_prev = t_now; }
-#define ASD_T_END if (tid == 0 && c == 0) printf("chain timing: rounds %d cycles noise %lld x0a %lld draft %lld verify %lld accept %lld tail %lld\n", R, t_acc[0], t_acc[1], t_acc[2], t_acc[3], t_acc[4], t_acc[5]);
-#else
-#define ASD_T_DECL
-#define ASD_T(i)
-#define ASD_T_END
-#endif
-
 typedef float v4f_c __attribute__((ext_vector_type(4)));
 
 // LDS layout, in floats.  Rows that feed the matrix cores (mixture, proposal samples, softmax
@@ -324,7 +312,6 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
 
   int a = 0, R = 0;
   int wstate = 4 * L;  // window controller (device_util.h); without it every window is L
-  ASD_T_DECL
   while (a < K) {
     const int w = min(adaptive ? window_of(wstate, L) : L, K - a);
     // A. the window's noise, then x0a
@@ -334,10 +321,8 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
           normal4(key, (uint32_t)c, (uint32_t)(a + k + 1), (uint32_t)blk);
     }
     for (int k = 1 + tid; k < w; k += nthreads) s_logu[k] = logf(uniform1(key, (uint32_t)c, (uint32_t)(a + k + 1)));
-    ASD_T(0)
     gmm_eval_row(0, a, l, C, d, m_l, q_l, lw_l, ps, part, yh, x0, sch, s_sc, tid, nthreads);
     lds_barrier();
-    ASD_T(1)
     // B. draft (proposal loop of Alg. 1)
     for (int blk = tid; blk < nblk; blk += nthreads) {
       float4 y = lds4(yh, blk);
@@ -369,11 +354,9 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
       }
     }
     lds_barrier();
-    ASD_T(2)
     // C. verify: target-mean model values at the drafted points (slot 0 reuses x0a)
     if (w > 1) gmm_eval_tiles(1, w - 1, a, l, C, d, m_l, q_l, lw_l, ps, part, yh, x0, sch, s_sc, wave, nw, lane);
     lds_barrier();
-    ASD_T(3)
     // D. Alg. 3 accept test, a wavefront per slot
     for (int k = 1 + wave; k < w; k += nw) {
       float dot = 0.f, vv = 0.f;
@@ -415,7 +398,6 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
       if (lane == 0) s_nacc = min(first, w);
     }
     lds_barrier();
-    ASD_T(4)
     const int n_acc = s_nacc;
     // reject branch of Alg. 3 (reflection) and the advance rule of Alg. 1
     int a_next, src;  // src: row of yh that is y_{a_next}
@@ -450,9 +432,7 @@ __global__ __launch_bounds__(1024) void gmm_chain_sample_kernel(
     a = a_next;
     ++R;
     lds_barrier();
-    ASD_T(5)
   }
-  ASD_T_END
   if (tid == 0) {
     if (rounds) rounds[c] = R;
     // (launch id, rounds) packed so that the maximum needs no reset between samples

@@ -2,13 +2,28 @@
 // all), timed over a stated duration, with operands that are either random (zero-mean, like real
 // data) or constant.  The two differ by almost 2x on this chip: the dense rate with random operands
 // is set by the power limit, not by the issue rate, so it -- not the data-sheet peak -- is the
-// ceiling a real GEMM can approach.  Exposed for profiling (asd_mfma_ceiling); not part of the path.
-#include "common.h"
-#include "gemm_bf16.h"
+// ceiling a real GEMM can approach.  A measurement probe for the benchmark harness, built into a
+// library of its own (libasd_probe.so); the sampling library neither contains nor calls it.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
 
 #include <new>
 
-namespace asd {
+#include "../../../include/asd_probe.h"
+
+namespace asd_probe {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));      // A / B operand of v_mfma_f32_32x32x16_bf16
+
+static thread_local char g_err[256] = "";
+static void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
 
 typedef uint32_t cu32x4 __attribute__((ext_vector_type(4)));
 typedef float cv16f __attribute__((ext_vector_type(16)));
@@ -65,20 +80,22 @@ __global__ __launch_bounds__(256, 2) void ceiling_f32_kernel(float* __restrict__
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-}  // namespace asd
+}  // namespace asd_probe
 
-using namespace asd;
+using namespace asd_probe;
 
-asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops) {
+extern "C" const char* asd_probe_last_error(void) { return g_err; }
+
+extern "C" int32_t asd_probe_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops) {
   if (!tflops || ms_target < 1 || ms_target > 5000) {
-    set_error("asd_mfma_ceiling: tflops is NULL or ms_target outside [1, 5000]");
-    return ASD_EINVAL;
+    set_error("asd_probe_mfma_ceiling: tflops is NULL or ms_target outside [1, 5000]");
+    return -1;
   }
   constexpr int kWgs = 512, kWords = 4096 * 4, kBatch = 8;
   float* out = nullptr;
   cu32x4* in = nullptr;
   uint32_t* h = new (std::nothrow) uint32_t[kWords];
-  if (!h) return ASD_ENOMEM;
+  if (!h) return -3;
   uint64_t s = 0x9E3779B97F4A7C15ull;   // splitmix64
   auto next = [&]() {
     uint64_t z = (s += 0x9E3779B97F4A7C15ull);
@@ -96,7 +113,6 @@ asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target
     h[i] = w;
   }
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  asd_status st = ASD_OK;
   auto cleanup = [&]() {
     delete[] h;
     (void)hipFree(out);
@@ -110,7 +126,7 @@ asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target
     if (e__ != hipSuccess) {                                                   \
       set_error("%s failed: %s", #x, hipGetErrorString(e__));                  \
       cleanup();                                                               \
-      return ASD_EDEVICE;                                                      \
+      return -3;                                                      \
     }                                                                          \
   } while (0)
   CEIL_HIP(hipMalloc(&out, sizeof(float) * kWgs * 256));
@@ -148,5 +164,5 @@ asd_status asd_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target
   (void)total_ms;
   *tflops = flop_per_launch * launches_timed / (last * 1e-3) / 1e12;
   cleanup();
-  return st;
+  return 0;
 }

@@ -9,26 +9,38 @@ import numpy as np
 import pytest
 
 from oracle import schedule
-from paper_2505_03983_amd import binding
+from paper_2505_03983_amd import binding, probe
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    src = open(os.path.join(ROOT, "include", "asd.h")).read()
-    return sorted(set(re.findall(r"ASD_API[^;(]*?\b(asd_\w+)\s*\(", src)))
+def _declared(header, macro="ASD_API"):
+    src = open(os.path.join(ROOT, "include", header)).read()
+    return sorted(set(re.findall(macro + r"[^;(]*?\b(asd_\w+)\s*\(", src)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared()
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["asd.h", "asd_probe.h", "asd_testing.h"]
+    names = _declared("asd.h")
     assert len(names) >= 15 and "asd_init" in names and "asd_sample" in names
+    for n in ("asd_draft", "asd_verify", "asd_accept", "asd_destroy"):
+        assert n in names
+    testing = _declared("asd_testing.h")
+    assert "asd_profile_read" in testing and "asd_debug_philox" in testing
     lib = ctypes.CDLL(binding.LIB_PATH)
-    for n in names:
+    for n in names + testing:
         assert hasattr(lib, n), n
     # and the binding binds them all
     L = binding.lib()
-    for n in names:
+    for n in names + testing:
         assert getattr(L, n).argtypes is not None, n
+    # the measurement probe is a library of its own; the sampling library does not carry it
+    pnames = _declared("asd_probe.h", "ASD_PROBE_API")
+    assert pnames == ["asd_probe_last_error", "asd_probe_mfma_ceiling"]
+    plib = ctypes.CDLL(probe.LIB_PATH)
+    for n in pnames:
+        assert hasattr(plib, n), n
+        assert not hasattr(lib, n), n
 
 
 def test_status_strings():
@@ -148,8 +160,9 @@ def test_null_handles():
     assert L.asd_resident_active(None) == 0
     assert L.asd_split_gemm_active(None) == 0
     # argument checks of the ceiling probe come before any device call
-    assert L.asd_mfma_ceiling(1, 1, 100, None) == binding.ASD_EINVAL
-    import ctypes
+    P = probe.lib()
+    assert P.asd_probe_mfma_ceiling(1, 1, 100, None) == -1
     t = ctypes.c_double(0.0)
-    assert L.asd_mfma_ceiling(1, 1, 0, ctypes.addressof(t)) == binding.ASD_EINVAL
-    assert L.asd_mfma_ceiling(0, 0, 5001, ctypes.addressof(t)) == binding.ASD_EINVAL
+    assert P.asd_probe_mfma_ceiling(1, 1, 0, ctypes.addressof(t)) == -1
+    assert P.asd_probe_mfma_ceiling(0, 0, 5001, ctypes.addressof(t)) == -1
+    assert b"ms_target" in P.asd_probe_last_error()

@@ -68,8 +68,21 @@ def test_round_structure_invariants():
             if r["r"] >= 0:
                 assert r["a_next"] == r["j"] + 1 == r["r"]
                 assert not np.array_equal(y[r["r"]], r["yhat"][n_acc])
+                # the resampled value is the reject branch of that slot ...
+                np.testing.assert_array_equal(y[r["r"]], r["z_rej"][n_acc])
+                i = a + n_acc
+                if T["sigma"][i] > 0:
+                    # ... i.e. the target mean plus sigma times a vector of the same length as xi whose
+                    # component along v = m_hat - m has changed sign (reflection of Alg. 3)
+                    m_t = T["c_x"][i] * y[i] + T["c_0"][i] * r["g"][n_acc]
+                    m_h = T["c_x"][i] * y[i] + T["c_0"][i] * r["g"][0]
+                    refl = (y[r["r"]] - m_t) / T["sigma"][i]
+                    assert abs(np.linalg.norm(refl) - np.linalg.norm(xi[i + 1])) < 1e-9
+                    assert abs(np.dot(refl, m_h - m_t) + np.dot(xi[i + 1], m_h - m_t)) < 1e-9
             else:
                 assert r["a_next"] == r["b"]
+            # the other branch of every later-tested slot is on record too (slot a+1 has none)
+            assert np.isnan(r["z_rej"][0]).all() and np.isfinite(r["z_rej"][1:]).all()
             a = r["a_next"]
         assert a == K
         # the final sigma = 0 step equals the deterministic target mean
