@@ -53,12 +53,14 @@ def sinusoidal_table(n_rows, E):
     return f32_to_bf16_bits(tab.astype(np.float32))
 
 
-def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0, predict_eps=False):
+def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0, predict_eps=False, act_terms=2):
     """Weights ~ N(0, 1/fan_in) rounded to bf16 (uint16 patterns), zero biases
     (fp32), time-embedding table [K+1, E] (bf16 patterns), row-major [out, in].
     out_clip: the predicted x_0 is clipped to [-1, 1] as DDPM samplers commonly
     do (a random-weight network is not a contraction; without the clip the
-    chain leaves the fp32 range within a few hundred steps)."""
+    chain leaves the fp32 range within a few hundred steps).
+    act_terms: bf16 terms an fp32 activation enters a matrix product with (a setting of the
+    denoiser, passed through to both sides)."""
     rng = _rng(model_seed, 2)
 
     def w(out_f, in_f):
@@ -75,6 +77,7 @@ def mlp_params(d, E, width, n_blocks, K, model_seed=1, out_clip=1.0, predict_eps
         temb=sinusoidal_table(K + 1, E),
         out_clip=float(out_clip),
         predict_eps=bool(predict_eps),
+        act_terms=int(act_terms),
     )
 
 
@@ -82,4 +85,4 @@ def make_params(cfg, model_seed=1):
     if cfg["kind"] == "gmm":
         return gmm_params(cfg["d"], cfg["C"], cfg["var"], model_seed)
     return mlp_params(cfg["d"], cfg["E"], cfg["width"], cfg["n_blocks"], cfg["K"], model_seed,
-                      predict_eps=cfg.get("predict_eps", False))
+                      predict_eps=cfg.get("predict_eps", False), act_terms=cfg.get("act_terms", 2))

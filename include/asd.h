@@ -98,6 +98,11 @@ typedef enum { ASD_DEN_GMM = 1, ASD_DEN_MLP = 2 } asd_den_kind;
  *   w_blk [n_blocks, width, width], w_out [d, width]; biases DEV fp32 or NULL
  *   (= 0): b_in [width], b_blk [n_blocks, width], b_out [d];
  *   temb DEV bf16 [n_tau, temb_dim].  Products accumulate in fp32.
+ *   act_terms (1 or 2): how an fp32 activation v (x, h) enters a product.  1: as bf16(v), the formulas
+ *   above.  2: as the sum of two bf16 numbers, bf16(v) + bf16(v - bf16(v)) (16 significant bits; round to
+ *   nearest even both times), twice the matrix-core work.  With one term, the rounding of the activations
+ *   is amplified by a random-weight residual network to ~2e-3 of its output scale whatever the
+ *   accumulation order; with two it is ~4e-6.
  *   linears_per_block must be 1.  d, temb_dim and width must be multiples of 8. */
 typedef struct {
   int32_t kind; /* asd_den_kind */
@@ -114,6 +119,7 @@ typedef struct {
   int32_t width, n_blocks, linears_per_block, temb_dim;
   float out_clip;
   int32_t predict_eps;
+  int32_t act_terms;
   const void* w_in;
   const void* w_blk;
   const void* w_out;

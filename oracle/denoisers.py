@@ -81,6 +81,19 @@ def round_to_bf16(a):
     return out.astype(np.float64).reshape(np.shape(a))
 
 
+def round_to_bf16_terms(a, terms):
+    """An fp32 activation as it enters a matrix product: terms = 1: the nearest bf16; terms = 2: the sum of
+    two bf16 numbers, the nearest bf16 of the value plus the nearest bf16 of what that left (the
+    remainder is exact in fp32), i.e. 16 significant bits.  Returned as fp64."""
+    hi = round_to_bf16(a)
+    if terms == 1:
+        return hi
+    if terms != 2:
+        raise ValueError("an activation is one bf16 number or the sum of two")
+    a32 = np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+    return hi + round_to_bf16(a32 - hi)
+
+
 def bf16_bits_to_f64(bits):
     """uint16 bf16 patterns -> exact fp64 values."""
     b = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
@@ -97,9 +110,11 @@ class MLPOracle:
     h_{l+1} = h_l + SiLU(W_l h_l + b_l); the result is clipped to
     [-out_clip, out_clip] when out_clip > 0.
 
-    Every matrix-product input is rounded to bf16 just before the product;
-    weights are bf16; sums, bias, SiLU and the residual stream are fp64 here
-    (fp32 on the device).  temb is a table [K+1, E] of bf16 values, row tau.
+    Every matrix-product input is rounded just before the product -- to one bf16
+    number, or (params["act_terms"] == 2) to the sum of two, see
+    round_to_bf16_terms; weights are bf16; sums, bias, SiLU and the residual
+    stream are fp64 here (fp32 on the device).  temb is a table [K+1, E] of bf16
+    values, row tau.
 
     predict_eps: the network output is the noise estimate of
     x_tau = sqrt(abar) x_0 + sqrt(1 - abar) eps (the parametrisation of the
@@ -117,6 +132,7 @@ class MLPOracle:
         self.temb = bf16_bits_to_f64(params["temb"])       # [K+1, E]
         self.out_clip = float(params.get("out_clip", 0.0))  # 0: no clipping
         self.predict_eps = bool(params.get("predict_eps", False))
+        self.act_terms = int(params.get("act_terms", 1))
         self.abar = None if abar is None else np.asarray(abar, dtype=np.float64)
         if self.predict_eps and self.abar is None:
             raise ValueError("a noise-predicting network needs abar")
@@ -124,11 +140,12 @@ class MLPOracle:
     def __call__(self, x, tau):
         x = np.atleast_2d(np.asarray(x, dtype=np.float64))
         tau = np.broadcast_to(np.asarray(tau, dtype=np.int64), (x.shape[0],))
-        inp = np.concatenate([round_to_bf16(x), self.temb[tau]], axis=1)
+        rnd = lambda v: round_to_bf16_terms(v, self.act_terms)      # noqa: E731
+        inp = np.concatenate([rnd(x), self.temb[tau]], axis=1)
         h = inp @ self.w_in.T + self.b_in
         for l in range(self.w_blk.shape[0]):
-            h = h + silu(round_to_bf16(h) @ self.w_blk[l].T + self.b_blk[l])
-        out = round_to_bf16(h) @ self.w_out.T + self.b_out
+            h = h + silu(rnd(h) @ self.w_blk[l].T + self.b_blk[l])
+        out = rnd(h) @ self.w_out.T + self.b_out
         if self.predict_eps:
             ab = self.abar[tau][:, None]
             out = (x - np.sqrt(1.0 - ab) * out) / np.sqrt(ab)

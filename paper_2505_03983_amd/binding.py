@@ -34,6 +34,7 @@ class asd_denoiser(C.Structure):
                 ("abar", C.c_void_p), ("sl_time", C.c_void_p),
                 ("width", C.c_int32), ("n_blocks", C.c_int32), ("linears_per_block", C.c_int32),
                 ("temb_dim", C.c_int32), ("out_clip", C.c_float), ("predict_eps", C.c_int32),
+                ("act_terms", C.c_int32),
                 ("w_in", C.c_void_p), ("w_blk", C.c_void_p), ("w_out", C.c_void_p),
                 ("b_in", C.c_void_p), ("b_blk", C.c_void_p), ("b_out", C.c_void_p), ("temb", C.c_void_p)]
 
@@ -195,6 +196,7 @@ def make_config(sched, den, L, chains, seed):
         cfg.den.temb_dim = int(den["temb_dim"])
         cfg.den.out_clip = float(den.get("out_clip", 0.0))
         cfg.den.predict_eps = int(bool(den.get("predict_eps", False)))
+        cfg.den.act_terms = int(den.get("act_terms", 1))
         cfg.den.abar = host(den["abar"], np.float32) if den.get("abar") is not None else None
         for k in ("w_in", "w_blk", "w_out", "b_in", "b_blk", "b_out", "temb"):
             setattr(cfg.den, k, _ptr(den.get(k)))

@@ -76,6 +76,7 @@ static asd_status validate(const asd_config* cfg) {
       for (int t = 0; t < m.n_tau; ++t)
         if (!(m.abar[t] > 0.f) || !(m.abar[t] <= 1.f)) return fail(ASD_EINVAL, "abar[%d] outside (0,1]", t);
     }
+    if (m.act_terms != 1 && m.act_terms != 2) return fail(ASD_EINVAL, "act_terms must be 1 or 2 (got %d)", m.act_terms);
     if (m.linears_per_block != 1) return fail(ASD_EUNSUPPORTED, "linears_per_block must be 1");
     if (m.d % 8 || m.temb_dim % 8 || m.width % 8)
       return fail(ASD_EUNSUPPORTED, "MLP needs d, temb_dim and width to be multiples of 8");

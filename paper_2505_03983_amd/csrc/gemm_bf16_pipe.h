@@ -24,6 +24,11 @@
 // Requirements (checked by the host): K % 64 == 0, lda and ldw multiples of 8,
 // 16-byte aligned bases.  M comes from device memory (compacted row plan).
 //
+// Two-plane A operand (PLANES = 2): A is given as the sum of two bf16 matrices of the same shape, a_plane
+// elements apart (activations kept to 16 significant bits as hi + lo, see mlp.hip).  A stage then holds
+// the slab of both planes above the W slab and every (A fragment, W fragment) pair is multiplied twice,
+// once per plane, into the same accumulator: the weights are loaded once for both.
+//
 // Split K (gridDim.z > 1): for a handful of rows the kernel is a stream of the weight matrix, and HBM
 // only delivers its bandwidth with ~16 MB in flight -- more workgroups than the output has tiles.  The
 // z-th workgroup of a tile contracts the z-th share of K and leaves its fp32 partial tile in scratch;
@@ -42,18 +47,21 @@ namespace asd {
 // Eight wavefronts (two per SIMD) let one wavefront's MFMAs run while its SIMD neighbour waits on the
 // address unit: a direct-to-LDS load of 1 KB occupies the CU's single address path for ~16 cycles and
 // the issuing wavefront stalls until it is accepted.
-template <int BM_, int BN_, int STAGES_, int WGM_ = 2, int WGN_ = 4>
+template <int BM_, int BN_, int STAGES_, int WGM_ = 2, int WGN_ = 4, int PLANES_ = 1>
 struct PipeCfg16 {
-  static constexpr int BM = BM_, BN = BN_, STAGES = STAGES_, BK = 64, WGM = WGM_, WGN = WGN_;
+  static constexpr int BM = BM_, BN = BN_, STAGES = STAGES_, BK = 64, WGM = WGM_, WGN = WGN_, PLANES = PLANES_;
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;          // wavefront sub-tile
   static constexpr int MI = WM / 32, NJ = WN / 32;
-  static constexpr int A_LOADS = BM / 8 / NW, W_LOADS = BN / 8 / NW;  // wave-loads (8 rows each) per wavefront per slab
+  static constexpr int AR = PLANES * BM;                      // A rows of a stage: the tile's rows of every plane
+  static constexpr int A_LOADS = AR / 8 / NW, W_LOADS = BN / 8 / NW;  // wave-loads (8 rows each) per wavefront per slab
   static constexpr int LPS = A_LOADS + W_LOADS;
-  static constexpr int STAGE_BYTES = (BM + BN) * 128;
+  static constexpr int STAGE_BYTES = (AR + BN) * 128;
   static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
+  static_assert(PLANES == 1 || PLANES == 2, "A operand planes");
   static_assert(WM % 32 == 0 && WN % 32 == 0 && STAGES >= 3 && STAGES <= 8, "tile shape");
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "wave-loads must divide evenly among the wavefronts");
+  static_assert(AR % (8 * NW) == 0 && BN % (8 * NW) == 0, "wave-loads must divide evenly among the wavefronts");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS of a CU");
   static_assert(LPS * (STAGES - 1) <= 63, "vmcnt range");
   // loads of the next slab issued inside MFMA group g (0..3), and those of group 3 issued after the hand-over
   static constexpr int loads_in_group(int g) { return LPS / 4 + (g < LPS % 4 ? 1 : 0); }
@@ -79,10 +87,12 @@ template <class Cfg, class Epi, int CALL>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const int* __restrict__ M_dev, int M_max,
                                                                          int N, int K,
                                                                          const uint16_t* __restrict__ A, int64_t lda,
+                                                                         int64_t a_plane,
                                                                          const uint16_t* __restrict__ W, int64_t ldw,
                                                                          Epi epi, float* __restrict__ part, int m_lo,
                                                                          int m_hi) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, STAGES = Cfg::STAGES, MI = Cfg::MI, NJ = Cfg::NJ, NW = Cfg::NW;
+  constexpr int AR = Cfg::AR, PL = Cfg::PLANES, AI = PL * MI;   // AI: A fragments per k group (all planes)
   constexpr int WM = Cfg::WM, WN = Cfg::WN;
   constexpr int A_LOADS = Cfg::A_LOADS, W_LOADS = Cfg::W_LOADS, LPS = Cfg::LPS, STAGE_BYTES = Cfg::STAGE_BYTES;
   extern __shared__ __attribute__((aligned(16))) uint8_t ldsb[];
@@ -110,9 +120,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   const uint16_t* wp[W_LOADS];
 #pragma unroll
   for (int p = 0; p < A_LOADS; ++p) {
-    const int row = (wave + NW * p) * 8 + lr;                // row inside the tile
-    const int chunk = (lane & 7) ^ ((row >> 1) & 7);         // global chunk that belongs in slot (lane & 7)
-    ap[p] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8 + k0;
+    const int srow = (wave + NW * p) * 8 + lr;               // row inside the stage: plane * BM + row inside the tile
+    const int plane = srow / BM, row = srow - plane * BM;    // (a wave-load's eight rows lie in one plane: BM % 8 == 0)
+    const int chunk = (lane & 7) ^ ((srow >> 1) & 7);        // global chunk that belongs in slot (lane & 7)
+    ap[p] = A + plane * a_plane + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8 + k0;
   }
 #pragma unroll
   for (int p = 0; p < W_LOADS; ++p) {
@@ -131,7 +142,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
                                          (lds_ptr_t)(sb + (wave + NW * q) * 1024), 16, 0, 0);
       else
         __builtin_amdgcn_global_load_lds((glb_ptr_t)(wp[q >= A_LOADS ? q - A_LOADS : 0] + (int64_t)kt * 64),
-                                         (lds_ptr_t)(sb + BM * 128 + (wave + NW * (q - A_LOADS)) * 1024), 16, 0, 0);
+                                         (lds_ptr_t)(sb + AR * 128 + (wave + NW * (q - A_LOADS)) * 1024), 16, 0, 0);
     }
   };
 
@@ -153,9 +164,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   //              others at the barrier (after which nobody reads slab kt's stage again: group 3's
   //              fragments are already in registers) and reads the first fragments of slab kt+1 --
   //              while the rest of group 3 executes.
-  constexpr int G = MI * NJ;                         // MFMAs per group
+  constexpr int G = AI * NJ;                         // MFMAs per group
   constexpr int H1 = (G + 1) / 2, H2 = G - H1;       // MFMAs of group 3 before / after the hand-over
-  constexpr int RD = MI + NJ, SLOTS = (RD + 1) / 2, RLAST = RD - 2 * (SLOTS - 1);
+  constexpr int RD = AI + NJ, SLOTS = (RD + 1) / 2, RLAST = RD - 2 * (SLOTS - 1);
   constexpr int REM = G > SLOTS ? G - SLOTS : 0;     // MFMAs of a group left after the read slots
   constexpr int LA = Cfg::LA, LB = Cfg::loads_in_group(3) - LA;
 #pragma unroll
@@ -164,15 +175,16 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
 
   const int sw = (l32 >> 1) & 7;  // swizzle key of this lane's rows (tile offsets are multiples of 16)
   const int a_row = (wm * WM + l32) * 128;
-  const int w_row = BM * 128 + (wn * WN + l32) * 128;
+  const int w_row = AR * 128 + (wn * WN + l32) * 128;
   int cp[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) cp[ks] = ((ks * 2 + half) ^ sw) * 16;
 
-  v8bf af[2][MI], wf[2][NJ];
+  v8bf af[2][AI], wf[2][NJ];
   auto read_frags = [&](const uint8_t* sb, int ks, int buf) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[buf][i] = *reinterpret_cast<const v8bf*>(sb + a_row + i * 32 * 128 + cp[ks]);
+    for (int i = 0; i < AI; ++i)   // fragment i: plane i / MI, 32-row block i % MI
+      af[buf][i] = *reinterpret_cast<const v8bf*>(sb + (i / MI) * (BM * 128) + a_row + (i % MI) * 32 * 128 + cp[ks]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) wf[buf][j] = *reinterpret_cast<const v8bf*>(sb + w_row + j * 32 * 128 + cp[ks]);
   };
@@ -180,8 +192,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
 #pragma unroll
     for (int q = 0; q < G; ++q)
       if (q >= first && q < first + count)
-        acc[q / NJ][q % NJ] =
-            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][q / NJ], wf[buf][q % NJ], acc[q / NJ][q % NJ], 0, 0, 0);
+        acc[(q / NJ) % MI][q % NJ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][q / NJ], wf[buf][q % NJ],
+                                                                             acc[(q / NJ) % MI][q % NJ], 0, 0, 0);
   };
 
   wait_vmcnt_slabs<LPS, 0>(min(STAGES - 2, nk - 1));   // slab 0 landed; the other prologue slabs may be in flight
@@ -297,8 +309,9 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const int* __restric
 // splits > 1 needs (K / 64) % splits == 0 and `part` of splits * M * N floats.
 template <class Cfg, int CALL, class Epi>
 inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K, const uint16_t* A, int64_t lda,
-                                           const uint16_t* W, int64_t ldw, Epi epi, hipStream_t st, int splits = 1,
-                                           float* part = nullptr, int m_lo = -1, int m_hi = 0x7fffffff) {
+                                           int64_t a_plane, const uint16_t* W, int64_t ldw, Epi epi, hipStream_t st,
+                                           int splits = 1, float* part = nullptr, int m_lo = -1,
+                                           int m_hi = 0x7fffffff) {
   if (splits < 1 || (K / 64) % splits != 0 || (splits > 1 && !part)) return hipErrorInvalidValue;
   dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)splits);
   auto kern = gemm_bf16_nt_pipe_kernel<Cfg, Epi, CALL>;
@@ -309,8 +322,8 @@ inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, W, ldw, epi, part,
-                     m_lo, m_hi);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, a_plane, W, ldw, epi,
+                     part, m_lo, m_hi);
   if (splits > 1)
     hipLaunchKernelGGL(splitk_finish_kernel<Epi>, dim3((unsigned)((N / 4 + 255) / 256), (unsigned)M), dim3(256), 0, st,
                        M_dev, M, N, splits, part, epi, m_lo, m_hi);

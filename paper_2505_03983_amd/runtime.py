@@ -21,7 +21,8 @@ def device_params(cfg, params, device="cuda:0"):
         return dict(kind="gmm", d=cfg["d"], C=cfg["C"], var=params["var"], means=up(params["means"]),
                     log_w=up(params["log_w"]))
     out = dict(kind="mlp", d=cfg["d"], width=cfg["width"], n_blocks=cfg["n_blocks"], temb_dim=cfg["E"],
-               out_clip=float(params.get("out_clip", 0.0)), predict_eps=bool(params.get("predict_eps", False)))
+               out_clip=float(params.get("out_clip", 0.0)), predict_eps=bool(params.get("predict_eps", False)),
+               act_terms=int(params.get("act_terms", 1)))
     for k in ("w_in", "w_blk", "w_out", "b_in", "b_blk", "b_out", "temb"):
         out[k] = up(params[k])
     return out

@@ -134,7 +134,11 @@ def test_mlp_shape_rules():
     with pytest.raises(binding.AsdError) as ei:
         binding.Ctx(s, den, 4, 2)
     assert ei.value.status == binding.ASD_EUNSUPPORTED
-    den.update(linears_per_block=1, w_out=None)
+    den.update(linears_per_block=1, act_terms=3)
+    with pytest.raises(binding.AsdError) as ei:
+        binding.Ctx(s, den, 4, 2)
+    assert ei.value.status == binding.ASD_EINVAL                 # activations: one bf16 term or two
+    den.update(act_terms=2, w_out=None)
     with pytest.raises(binding.AsdError) as ei:
         binding.Ctx(s, den, 4, 2)
     assert ei.value.status == binding.ASD_EINVAL

@@ -50,8 +50,50 @@ def test_hand_computed_two_wide_example():
     assert abs(got - (2 * h[0] - h[1] + 3.0)) < 1e-15
 
 
+def test_two_term_activation_rounding():
+    """An activation as the sum of two bf16 numbers: both terms are bf16 values, the sum is within 2^-16 of the
+    value (8 bits from each term), values of at most 16 significant bits survive exactly, and it agrees with
+    the same construction done with the library's own conversions."""
+    rng = np.random.default_rng(5)
+    a = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-5, 5, 4000), [0.0, 1.0 + 2.0 ** -10, 40503.0]])
+    a32 = a.astype(np.float32).astype(np.float64)
+    two = denoisers.round_to_bf16_terms(a, 2)
+    hi = denoisers.round_to_bf16(a)
+    lo = two - hi
+    np.testing.assert_array_equal(denoisers.round_to_bf16(lo), lo)            # the second term is a bf16 number
+    assert np.all(np.abs(two - a32) <= 2.0 ** -16 * np.abs(a32))
+    assert np.all(np.abs(hi - a32) <= 2.0 ** -8 * np.abs(a32)) and np.any(np.abs(hi - a32) > 2.0 ** -11 * np.abs(a32))
+    assert two[-2] == 1.0 + 2.0 ** -10 and hi[-2] == 1.0 and two[-1] == 40503.0 and hi[-1] != 40503.0
+    t = torch.from_numpy(a.astype(np.float32))
+    t_hi = t.to(torch.bfloat16).to(torch.float32)
+    t_lo = (t - t_hi).to(torch.bfloat16).to(torch.float32)
+    np.testing.assert_array_equal(two, t_hi.to(torch.float64).numpy() + t_lo.to(torch.float64).numpy())
+    np.testing.assert_array_equal(denoisers.round_to_bf16_terms(a, 1), hi)
+    with pytest.raises(ValueError):
+        denoisers.round_to_bf16_terms(a, 3)
+
+
+def test_two_term_network_is_the_unrounded_network_to_sixteen_bits():
+    """With exact activations (no rounding at all) as the yardstick: one-term activations sit at the 2^-9
+    level of the output scale, two-term ones a hundred times closer."""
+    p1 = W.mlp_params(d=24, E=8, width=256, n_blocks=4, K=10, model_seed=4, out_clip=0.0, act_terms=1)
+    p2 = dict(p1, act_terms=2)
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((16, 24)).astype(np.float32).astype(np.float64)
+    tau = rng.integers(1, 11, 16)
+    f = denoisers.bf16_bits_to_f64
+    h = np.concatenate([x, f(p1["temb"])[tau]], axis=1) @ f(p1["w_in"]).T
+    for l in range(4):
+        h = h + denoisers.silu(h @ f(p1["w_blk"])[l].T)
+    exact = h @ f(p1["w_out"]).T
+    scale = np.abs(exact).max()
+    e1 = np.abs(denoisers.MLPOracle(p1)(x, tau) - exact).max() / scale
+    e2 = np.abs(denoisers.MLPOracle(p2)(x, tau) - exact).max() / scale
+    assert 2e-4 < e1 < 2e-2 and e2 < 5e-5 and e2 < e1 / 50, (e1, e2)
+
+
 def test_rows_are_independent_and_rounding_points_matter():
-    p = W.mlp_params(d=12, E=8, width=32, n_blocks=2, K=10, model_seed=3)
+    p = W.mlp_params(d=12, E=8, width=32, n_blocks=2, K=10, model_seed=3, act_terms=1)
     mlp = denoisers.MLPOracle(p)
     rng = np.random.default_rng(1)
     x = rng.standard_normal((6, 12))
@@ -62,6 +104,11 @@ def test_rows_are_independent_and_rounding_points_matter():
     # inputs that differ by less than half a bf16 ulp are the same to the network
     np.testing.assert_array_equal(mlp(np.full((1, 12), 1.0), [2]), mlp(np.full((1, 12), 1.0 + 2.0 ** -10), [2]))
     assert np.max(np.abs(full)) < 50 and np.std(full) > 0.05
+    # ... but not to the network with two-term activations, which carries 16 bits of them
+    mlp2 = denoisers.MLPOracle(dict(p, act_terms=2))
+    assert not np.array_equal(mlp2(np.full((1, 12), 1.0), [2]), mlp2(np.full((1, 12), 1.0 + 2.0 ** -10), [2]))
+    np.testing.assert_array_equal(mlp2(np.full((1, 12), 1.0 + 2.0 ** -10), [2]),
+                                  mlp2(np.full((1, 12), 1.0 + 2.0 ** -10 + 2.0 ** -20), [2]))
 
 
 def test_noise_prediction_is_the_affine_map_of_the_output():
