@@ -191,6 +191,17 @@ ASD_API asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float
  * Rounds are lock-step launches over all unfinished chains. */
 ASD_API asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream);
 
+/* asd_sample for callers that cannot allocate (code under HIP graph capture of their own, tight serving loops,
+ * harnesses that forbid hipMalloc): the same sample on the same kernels, with the batched verify call's outputs
+ * (x0hat [chains, L, d], the only buffer asd_sample needs beyond what asd_init set up) in a static device array
+ * of 32 MiB that every GPU the library runs on holds until the process ends.  The call makes no hipMalloc /
+ * hipFree, creates no stream, event or graph (rounds are plain launches on `stream`, lock-step round kernels
+ * only) and returns ASD_EUNSUPPORTED when chains*L*d*4 bytes exceed the 32 MiB, ASD_ESTATE while per-kernel
+ * timing is on.  Results equal asd_sample's with asd_use_graphs(0) and asd_use_resident(0).  All contexts on a
+ * GPU share that GPU's array, and it keeps the last call's contents (no slot is read before the same round has
+ * written it, so nothing is cleared): calls that overlap in time on one GPU race. */
+ASD_API asd_status asd_sample_noalloc(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream);
+
 /* asd_sample launches the rounds of launch-bound workloads as one captured HIP graph per round
  * (kernels only; the graph is rebuilt when traj, rounds or the stream change).  on = 0 switches to
  * plain kernel launches; the results are identical.  Default: on. */

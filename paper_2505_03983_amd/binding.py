@@ -63,6 +63,7 @@ def lib():
             "asd_verify": (i32, [vp, vp, vp, vp, vp]),
             "asd_accept": (i32, [vp, vp, vp, vp, vp, vp, vp]),
             "asd_sample": (i32, [vp, vp, vp, vp, vp]),
+            "asd_sample_noalloc": (i32, [vp, vp, vp, vp, vp]),
             "asd_sample_sequential": (i32, [vp, vp, vp, vp]),
             "asd_last_round_count": (i32, [vp]),
             "asd_use_graphs": (i32, [vp, i32]),
@@ -264,6 +265,10 @@ class Ctx:
 
     def sample(self, traj, rounds=None, y0=None, stream=None):
         _check(lib().asd_sample(self.h, _ptr(y0), _ptr(traj), _ptr(rounds), _stream(stream)))
+        return lib().asd_last_round_count(self.h)
+
+    def sample_noalloc(self, traj, rounds=None, y0=None, stream=None):
+        _check(lib().asd_sample_noalloc(self.h, _ptr(y0), _ptr(traj), _ptr(rounds), _stream(stream)))
         return lib().asd_last_round_count(self.h)
 
     def sample_sequential(self, traj, y0=None, stream=None):

@@ -10,7 +10,17 @@
 #include "common.h"
 #include "gmm_state.h"
 
+// Scratch of asd_sample_noalloc: the verify call's outputs x0hat [chains, L, d] of a sample whose caller may
+// not allocate.  One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address of each GPU's copy is kept in g_scratch_ptr and is what kernels and
+// copies are given.
+constexpr size_t kNoallocScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
 namespace asd {
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (set by asd_init)
 
 static thread_local char g_err[512] = "";
 
@@ -108,6 +118,11 @@ static asd_status upload(T** dst, const T* src, size_t n) {
 
 static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipGetDevice(&ctx->device));
+  if (ctx->device >= 0 && ctx->device < kMaxDevices && !g_scratch_ptr[ctx->device]) {
+    void* p = nullptr;
+    ASD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));   // this device's copy (the device is current)
+    g_scratch_ptr[ctx->device] = p;
+  }
   ctx->K = cfg->sched.K;
   ctx->L = cfg->L;
   ctx->B = cfg->chains;
@@ -411,6 +426,23 @@ asd_status asd_sample(asd_ctx* ctx, const float* y0, float* traj, int32_t* round
     return gmm_chain_sample(ctx, y0, traj, rounds, st);
   }
   return sample_rounds(ctx, y0, traj, rounds, ctx->x0hat, true, st);
+}
+
+asd_status asd_sample_noalloc(asd_ctx* ctx, const float* y0, float* traj, int32_t* rounds, void* stream) {
+  ASD_TRY(check_ctx(ctx));
+  ASD_TRY(check_rows_ptr(ctx, traj, "traj"));
+  if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
+  if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample_noalloc called between stage calls");
+  if (ctx->prof.on) return fail(ASD_ESTATE, "asd_sample_noalloc: per-kernel timing creates events; switch it off");
+  const size_t need = sizeof(float) * (size_t)ctx->n_rows_max * (size_t)ctx->d;
+  if (need > kNoallocScratchBytes)
+    return fail(ASD_EUNSUPPORTED, "asd_sample_noalloc: chains*L*d*4 = %zu bytes exceeds the %zu-byte static scratch",
+                need, kNoallocScratchBytes);
+  float* x0hat = (ctx->device >= 0 && ctx->device < kMaxDevices) ? (float*)g_scratch_ptr[ctx->device] : nullptr;
+  if (!x0hat) return fail(ASD_EDEVICE, "asd_sample_noalloc: no static scratch on device %d", ctx->device);
+  // Nothing in the scratch has to start at zero: every slot the accept kernel reads was written by the
+  // verify call of the same round.
+  return sample_rounds(ctx, y0, traj, rounds, x0hat, false, (hipStream_t)stream);
 }
 
 asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream) {
