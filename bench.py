@@ -28,15 +28,27 @@ import numpy as np  # noqa: E402
 PEAK = {"f32": 157.3, "bf16": 2500.0}          # dense MFMA TFLOP/s, MI355X
 HBM_PEAK_GBS = 8000.0
 
-# HBM-side bytes per launch (mean over the launches of one sample of workload 5) of the two verify GEMMs:
-# rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a 1 GiB copy in the same run);
-# see profiles/cfg5_gmm_verify_gemm_hbm_traffic.txt for the commands and the raw readings.
-TRAFFIC_BYTES_PER_LAUNCH = {
-    (5, "GMM_LOGITS/verify", "bf16"): 1024.0 * (2.0 * 1229850.2 + 747404.7),     # split-operand kernels (default)
-    (5, "GMM_COMBINE/verify", "bf16"): 1024.0 * (2.0 * 1695031.3 + 175748.3),
-    (5, "GMM_LOGITS/verify", "f32"): 1024.0 * (2.0 * 1137560.1 + 758386.0),      # fp32 MFMA kernels (--fp32-mfma)
-    (5, "GMM_COMBINE/verify", "f32"): 1024.0 * (2.0 * 3308168.4 + 175748.3),
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_gmm_verify_gemm_hbm_traffic.txt")
+
+
+def traffic_bytes_per_launch(w, kernel, arithmetic):
+    """HBM-side bytes per launch of a verify GEMM as rocprofv3 measured them (FETCH_SIZE and WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size): parsed from the committed summary
+    of those runs, whose `TRAFFIC` lines carry the readings and the scale factors.  None if it has no line
+    for this kernel."""
+    import re
+    try:
+        text = open(TRAFFIC_FILE).read()
+    except OSError:
+        return None
+    for line in text.splitlines():
+        if not line.startswith("TRAFFIC "):
+            continue
+        kv = dict(re.findall(r"(\w+)=(\S+)", line))
+        if kv.get("workload") == str(w) and kv.get("kernel") == kernel and kv.get("arithmetic") == arithmetic:
+            return 1024.0 * (float(kv["fetch_scale"]) * float(kv["fetch_kib"]) +
+                             float(kv["write_scale"]) * float(kv["write_kib"]))
+    return None
 
 
 def workload_name(w, cfg):
@@ -85,12 +97,14 @@ class ClockSampler:
                     mean=sum(self.samples) / len(self.samples), last=self.samples[-1])
 
 
-def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, clocks=False):
+def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, clocks=False, act_terms=None):
     import torch
     import asd_workloads as W
     from paper_2505_03983_amd import binding, runtime
 
     cfg = W.CONFIGS[w]
+    if act_terms is not None and cfg["kind"] == "mlp":
+        cfg = dict(cfg, act_terms=act_terms)
     params = W.make_params(cfg, model_seed=1)
     ctx = runtime.open_ctx(cfg, params, seed=seed)
     ctx.use_adaptive_window(adaptive)
@@ -128,7 +142,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
                rounds_launched=launched, finite=finite, path=path, split=split_active,
-               sclk_mhz=sampler.summary() if sampler else None)
+               act_terms=params.get("act_terms"), sclk_mhz=sampler.summary() if sampler else None)
     if profile:
         P = binding.PROF
         table = {}
@@ -140,6 +154,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
                                                                                  avg_us=1e3 * ms / n)
         out["kernels"] = table
         out["rows"] = ctx.profile_rows()
+        out["accept_rows"] = ctx.profile_accept_rows()
         ctx.profile_enable(False)
     ctx.close()
     del traj
@@ -148,9 +163,15 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
 
 
 def roofline(res, w=None):
-    """Roofline entry of the dominant kernel of a profiled run."""
+    """Roofline entry of the dominant kernel of a profiled run.
+
+    Mixture denoiser: one GEMM of the model call does 2*C*d flop per row (the method's arithmetic, fp32).  The
+    default kernels evaluate every fp32 product as six bf16 MFMA products, so they *execute* six times that on
+    the bf16 pipe.  `achieved` / `peak` / `frac` are the executed bf16 work against the bf16 MFMA peak (how
+    busy the pipe in use is); `method` carries the 2*C*d figure and its ratio to the fp32 MFMA peak."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
+    executed_per_method = 1.0
     if cfg["kind"] == "gmm":
         cand = [n for n in ("GMM_LOGITS/verify", "GMM_COMBINE/verify", "GMM_ROWWISE/verify") if n in k]
         name = max(cand, key=lambda n: k[n]["total_ms"])
@@ -161,10 +182,8 @@ def roofline(res, w=None):
         # the row-wise kernel runs on the vector ALUs; its bound is the fp32 vector peak (same figure)
         bound = "mfma" if not name.startswith("GMM_ROWWISE") else "alu"
         if bound == "mfma" and res.get("split"):
-            # bf16 MFMA on three-way split operands: six bf16 products stand for one fp32 product, and
-            # those are the flops the kernel performs and its roofline is drawn against
             dtype = "bf16"
-            per_row *= 6.0
+            executed_per_method = 6.0
     else:
         name = "MLP_GEMM_BLK/verify"
         launches = k[name]["launches"]
@@ -172,48 +191,76 @@ def roofline(res, w=None):
         verify_rows = verify_rows * cfg["n_blocks"]      # one launch per block, each over all rows
         dtype = "bf16"
         bound = "mfma"
-    flops_per_launch = per_row * verify_rows / launches
+        executed_per_method = float(res.get("act_terms", 1))   # each activation term is multiplied with the weights
+    method_flops = per_row * verify_rows / launches
     avg_s = 1e-3 * k[name]["total_ms"] / launches
-    achieved = flops_per_launch / avg_s / 1e12
+    method_tflops = method_flops / avg_s / 1e12
+    achieved = executed_per_method * method_tflops
     peak = PEAK[dtype]
     out = dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
-               traffic=TRAFFIC_BYTES_PER_LAUNCH.get((w, name, dtype)), avg_launch_us=1e6 * avg_s, launches=launches,
-               algorithmic_flops_per_launch=flops_per_launch, mfma_dtype=dtype,
+               frac_is="executed %s MFMA flop/s over the %s MFMA peak" % (dtype, dtype) if bound == "mfma"
+               else "executed fp32 flop/s over the fp32 vector peak",
+               traffic=traffic_bytes_per_launch(w, name, dtype), avg_launch_us=1e6 * avg_s, launches=launches,
+               executed_flops_per_launch=executed_per_method * method_flops, mfma_dtype=dtype,
                share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
-    if cfg["kind"] == "gmm" and dtype == "bf16":
-        out["bf16_products_per_fp32_product"] = 6
-        out["fp32_equivalent_tflops"] = achieved / 6.0
+    if cfg["kind"] == "gmm":
+        out["method"] = dict(flops_per_launch=method_flops, what="2*C*d per row (fp32 contraction of the model call)",
+                             tflops=method_tflops, fp32_mfma_peak=PEAK["f32"],
+                             ratio_to_fp32_mfma_peak=method_tflops / PEAK["f32"])
+        out["executed_bf16_products_per_fp32_product"] = int(executed_per_method)
+    else:
+        out["method"] = dict(flops_per_launch=method_flops, what="2*width^2 per row and block",
+                             tflops=method_tflops, bf16_terms_per_activation=int(executed_per_method))
     return out
 
 
 def hbm_kernels(res):
-    """Achieved algorithmic HBM bandwidth of the draft and accept kernels (event-timed: a few
-    microseconds of launch overhead are inside each figure; profiles/ has the rocprofv3 durations).
-    The accept kernel's bytes are those of the whole window, (w + 3) rows per chain; it stops reading
-    at the group of eight slots that holds the first rejection, so it touches fewer."""
+    """Algorithmic HBM bytes per second of the draft and accept kernels (event-timed: a few microseconds of
+    launch overhead are inside each figure; profiles/ has the rocprofv3 durations).  Both kernels regenerate
+    their noise (Philox4x32-10 + Box-Muller per four coordinates) and are bound by that arithmetic, not by HBM;
+    the figures say how far from the HBM roof that leaves them.
+    draft: reads y_a and x0a (2 rows per live chain), writes the w drafted rows.
+    accept: reads x0a and the x0hat rows of the slots it examines -- it walks the window eight slots at a time
+    and stops at the group holding the first rejection, so it reads far fewer than the w - 1 rows of the window
+    (the count comes from the device) -- and, on a rejection, reads and rewrites one trajectory row.
+    `whole_window` is the same figure had it read every slot: an upper bound, kept for comparison."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
+    examined, resampled = res.get("accept_rows", (None, None))
     d = cfg["d"]
-    # draft: reads y_a and x0a (2 rows), writes w rows; accept: reads w rows of x0hat (w-1 new + x0a) and one
-    # trajectory row, writes one row.  w summed over chains and rounds = verify_rows + draft_rows.
-    w_total = verify_rows + draft_rows
+    w_total = verify_rows + draft_rows      # w summed over chains and rounds
     out = {}
     if "DRAFT/draft" in k:
         b = 4.0 * d * (2 * draft_rows + w_total)
         out["draft"] = dict(GBps=b / (1e-3 * k["DRAFT/draft"]["total_ms"]) / 1e9,
-                            avg_us=k["DRAFT/draft"]["avg_us"])
+                            avg_us=k["DRAFT/draft"]["avg_us"], bytes_per_launch=b / k["DRAFT/draft"]["launches"])
     if "ACCEPT/draft" in k:
-        b = 4.0 * d * (w_total + 3 * draft_rows)
-        out["accept"] = dict(GBps=b / (1e-3 * k["ACCEPT/draft"]["total_ms"]) / 1e9,
-                             avg_us=k["ACCEPT/draft"]["avg_us"])
+        t = 1e-3 * k["ACCEPT/draft"]["total_ms"]
+        whole = 4.0 * d * (w_total + 3 * draft_rows)
+        out["accept"] = dict(avg_us=k["ACCEPT/draft"]["avg_us"],
+                             whole_window=dict(GBps=whole / t / 1e9, frac_of_hbm_peak=whole / t / 1e9 / HBM_PEAK_GBS))
+        if examined is not None:
+            b = 4.0 * d * (examined + draft_rows + 2 * resampled)
+            out["accept"].update(GBps=b / t / 1e9, bytes_per_launch=b / k["ACCEPT/draft"]["launches"],
+                                 share_of_window_rows_read=examined / max(1.0, float(verify_rows)))
+        else:
+            out["accept"]["GBps"] = whole / t / 1e9
     for v in out.values():
         v["frac_of_hbm_peak"] = v["GBps"] / HBM_PEAK_GBS
+        v["bound_by"] = "ALU (counter-based noise regenerated in registers)"
     return out
 
 
-def cpu_baseline(w, seed, budget_s=15.0):
-    """The oracle as it stands, timed on the host: ASD rounds of single chains
-    of the same workload until `budget_s` seconds have been spent."""
+def cpu_baseline(w, seed, budget_s=24.0, n_phases=8):
+    """The oracle as it stands, timed on the host on one thread.
+
+    A round of Alg. 1 advances many steps while the noise is large and few near the end, so a rate taken
+    from the first rounds of a chain overstates the oracle.  Whole chains are timed when one fits in the
+    budget (workloads 1-3).  Otherwise the chain is sampled at n_phases phases (a = 0, K/n, 2K/n, ...): from
+    a synthetic state of that noise level -- a draw from the forward marginal of the data law, which is the law
+    of y_a since the chain is exact -- the oracle runs rounds for its share of the budget, and the chain's rate
+    is the steps-weighted harmonic mean of the phase rates (each phase stands for K/n steps; most of a chain's
+    time goes to its last phases, where a round advances few steps)."""
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import asd_workloads as W
     from oracle import asd as oasd
@@ -224,29 +271,71 @@ def cpu_baseline(w, seed, budget_s=15.0):
         threadpool_limits = None
     cfg = W.CONFIGS[w]
     T, p, model = oracle_setup(cfg)
-    K, L = cfg["K"], cfg["L"]
+    K, L, d = cfg["K"], cfg["L"], cfg["d"]
     ctxmgr = threadpool_limits(limits=1) if threadpool_limits else None
-    steps_done = rounds_done = 0
-    t0 = time.perf_counter()
-    chain = 0
+    host_cores = os.cpu_count()
+
+    def run_rounds(y, a, xi, u, t_end, stop_at=K):
+        steps = rounds = 0
+        while a < stop_at and time.perf_counter() < t_end:
+            rec = oasd.asd_round(y, a, L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+            y = rec["y_new"][-1]
+            steps += rec["a_next"] - a
+            a = rec["a_next"]
+            rounds += 1
+        return steps, rounds, a
+
     try:
-        while time.perf_counter() - t0 < budget_s:
-            xi, u = chain_randoms(seed, chain, K, cfg["d"])
-            a, y = 0, xi[0]
-            while a < K and time.perf_counter() - t0 < budget_s:
-                rec = oasd.asd_round(y, a, L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
-                y = rec["y_new"][-1]
-                steps_done += rec["a_next"] - a
-                a = rec["a_next"]
-                rounds_done += 1
-            chain += 1
+        t0 = time.perf_counter()
+        xi, u = chain_randoms(seed, 0, K, d)
+        s1, r1, a1 = run_rounds(xi[0], 0, xi, u, t0 + 1e-9)          # one round, to size the job
+        t_round = time.perf_counter() - t0
+        whole = t_round * (K / max(1, s1)) * 3.0 < 0.5 * budget_s        # late rounds advance ~3x less
+        if whole:
+            steps = rounds = chains = 0
+            t0 = time.perf_counter()
+            while time.perf_counter() - t0 < budget_s:
+                xi, u = chain_randoms(seed, chains, K, d)
+                s_, r_, a_ = run_rounds(xi[0], 0, xi, u, float("inf"))
+                steps, rounds, chains = steps + s_, rounds + r_, chains + 1
+            el = time.perf_counter() - t0
+            value = steps / el
+            sample = ("%d whole chains (chain ids 0..%d: %d ASD rounds, %d DDPM steps) of the same workload, %.1f s"
+                      % (chains, chains - 1, rounds, steps, el))
+        else:
+            rng = np.random.default_rng(seed)
+            phases, inv = [], 0.0
+            t_all = time.perf_counter()
+            for ph in range(n_phases):
+                a0 = ph * K // n_phases
+                xi, u = chain_randoms(seed, ph, K, d)
+                if a0 == 0:
+                    y = xi[0]
+                else:
+                    ab = T["abar"][T["tau"][a0]]
+                    if cfg["kind"] == "gmm":
+                        x0 = p["means"][rng.integers(0, cfg["C"])] + np.sqrt(p["var"]) * rng.standard_normal(d)
+                    else:
+                        x0 = rng.uniform(-1.0, 1.0, d)
+                    y = np.sqrt(ab) * x0 + np.sqrt(1.0 - ab) * rng.standard_normal(d)
+                t0 = time.perf_counter()
+                s_, r_, a_ = run_rounds(y, a0, xi, u, t0 + budget_s / n_phases)
+                el = time.perf_counter() - t0
+                phases.append(dict(a=a0, rounds=r_, steps=s_, seconds=round(el, 2), steps_per_s=s_ / el))
+                inv += (1.0 / n_phases) / (s_ / el)
+            value = 1.0 / inv
+            sample = ("rounds of single chains from %d phases of the chain (a = 0, K/%d, ...; synthetic states of that "
+                      "noise level), an equal share of the budget each, combined as the steps-weighted harmonic mean: "
+                      % (n_phases, n_phases)
+                      + "; ".join("a=%d: %d rounds, %d steps, %.1f steps/s" % (q["a"], q["rounds"], q["steps"],
+                                                                               q["steps_per_s"]) for q in phases)
+                      + "; %.1f s in all" % (time.perf_counter() - t_all))
     finally:
         if ctxmgr is not None:
             ctxmgr.__exit__(None, None, None)
-    el = time.perf_counter() - t0
-    return dict(value=steps_done / el, unit="DDPM steps/s", cores=1, kind="oracle",
-                sample="%d ASD rounds (%d DDPM steps) of single chains (chain ids 0..%d) of the same workload, "
-                       "fp64 numpy, BLAS limited to 1 thread, %.1f s" % (rounds_done, steps_done, chain - 1, el))
+    return dict(value=value, unit="DDPM steps/s", cores=1, kind="oracle", host_cores_available=host_cores,
+                sample=sample + "; fp64 numpy, one thread (BLAS limited to 1: the oracle's time is in element-wise "
+                                "fp64 work, which numpy does not thread)")
 
 
 def main():
@@ -268,6 +357,8 @@ def main():
     ap.add_argument("--window-control", action="store_true",
                     help="time the sample with the per-chain window controller on (an extension of Alg. 1; the "
                          "default run keeps the configured fixed L and reports this mode in `window_control`)")
+    ap.add_argument("--act-terms", type=int, default=None, choices=(1, 2),
+                    help="MLP workloads: bf16 terms per activation (default: the workload's own setting, 2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -289,8 +380,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    # (the clock is polled through rocm-smi child processes; under a profiler, whose preloaded library has
+    # initialised the GPU in this process, such children may not be started, and --plain is the profiler mode)
     res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma,
-                  clocks=True, adaptive=args.window_control)
+                  clocks=not args.plain, adaptive=args.window_control, act_terms=args.act_terms)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -318,6 +411,8 @@ def main():
     if cfg["kind"] == "gmm":
         line["verify_gemm_arithmetic"] = ("every fp32 product as six bf16 MFMA products of three-way split operands, "
                                           "fp32 accumulation" if res["split"] else "fp32 MFMA")
+    else:
+        line["mlp_activation_terms"] = res["act_terms"]
     if not args.plain:
         line["roofline"] = roofline(res, args.workload)
         if res["sclk_mhz"] and line["roofline"]["bound"] == "mfma":
@@ -366,6 +461,7 @@ def main():
             r = run_gpu(w, 1, 0, args.seed, profile=True)        # per-kernel figures
             ra = run_gpu(w, 2, 1, args.seed, profile=False, adaptive=True)
             rf = roofline(r)
+            one = run_gpu(w, 2, 1, args.seed, profile=False, act_terms=1) if r["cfg"]["kind"] == "mlp" else None
             others["cfg%d" % w] = dict(workload=workload_name(w, r["cfg"]), steps_per_s=r0["steps_per_s"],
                                        ms_per_sample=r0["ms_per_sample"], path=r0["path"],
                                        kernel_figures_from=r["path"] + " (profiled pass)",
@@ -378,6 +474,12 @@ def main():
                                                            ms_per_sample=ra["ms_per_sample"],
                                                            rounds_mean=ra["rounds_mean"],
                                                            rounds_max=ra["rounds_max"]))
+            if one is not None:
+                # the same network with activations rounded to one bf16 term (half the matrix-core work; its
+                # outputs agree with any other implementation to ~2e-3 of the unclipped output scale only)
+                others["cfg%d" % w]["mlp_activation_terms"] = r["act_terms"]
+                others["cfg%d" % w]["one_term_activations"] = dict(steps_per_s=one["steps_per_s"],
+                                                                   ms_per_sample=one["ms_per_sample"])
         line["other_workloads"] = others
     print(json.dumps(line))
 

@@ -54,6 +54,10 @@ typedef enum {
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
 ASD_API asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms);
 ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows);
+/* What the accept kernel touched since then: x0hat rows it read for the accept test (it examines a window eight
+ * slots at a time and stops at the group that holds the first rejection) and rows it resampled (one per
+ * chain-round that ended in a rejection). */
+ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t* resampled_rows);
 
 #ifdef __cplusplus
 }

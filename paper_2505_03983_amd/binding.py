@@ -76,6 +76,7 @@ def lib():
             "asd_profile_enable": (i32, [vp, i32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
             "asd_profile_rows": (i32, [vp, vp, vp]),
+            "asd_profile_accept_rows": (i32, [vp, vp, vp]),
             "asd_debug_philox": (i32, [u64, u32, u32, u32, i32, vp, vp]),
             "asd_debug_randoms": (i32, [u64, u32, u32, i32, vp, vp, vp]),
             "asd_schedule_ddpm_linear": (i32, [i32, C.c_double, C.c_double, vp, vp, vp, vp, vp]),
@@ -285,6 +286,11 @@ class Ctx:
     def profile_rows(self):
         a, b = C.c_int64(0), C.c_int64(0)
         _check(lib().asd_profile_rows(self.h, C.addressof(a), C.addressof(b)))
+        return a.value, b.value
+
+    def profile_accept_rows(self):
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(lib().asd_profile_accept_rows(self.h, C.addressof(a), C.addressof(b)))
         return a.value, b.value
 
     def denoise(self, x, tau, out, stream=None):

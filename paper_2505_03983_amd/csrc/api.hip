@@ -144,8 +144,8 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
   ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * rows * (size_t)ctx->d));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
-  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 2));
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
+  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 4));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMalloc(&ctx->win, sizeof(int32_t) * 2 * (size_t)ctx->B));
@@ -520,7 +520,7 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ASD_HIP(hipDeviceSynchronize());
   ctx->prof.reset();
   ctx->prof.on = on != 0;
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 2));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
   return ASD_OK;
 }
 
@@ -548,6 +548,15 @@ asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_r
   ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
   if (draft_rows) *draft_rows = h[0];
   if (verify_rows) *verify_rows = h[1];
+  return ASD_OK;
+}
+
+asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t* resampled_rows) {
+  ASD_TRY(check_ctx(ctx));
+  int64_t h[4] = {0, 0, 0, 0};
+  ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
+  if (examined_rows) *examined_rows = h[2];
+  if (resampled_rows) *resampled_rows = h[3];
   return ASD_OK;
 }
 

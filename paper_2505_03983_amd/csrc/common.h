@@ -142,7 +142,8 @@ struct asd_ctx {
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
-  int64_t* row_counts = nullptr;  // DEV [2]: live rows summed over launches (draft call, verify call)
+  int64_t* row_counts = nullptr;  // DEV [4], summed over launches while profiling: live rows of the draft call, of the verify
+                                  // call, x0hat rows the accept kernel read for its tests, rows it resampled
   double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
   asd::GmmState* gmm = nullptr;
   asd::MlpState* mlp = nullptr;

@@ -338,7 +338,8 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
                                                       const float* __restrict__ x0hat, float* __restrict__ traj,
                                                       int32_t* __restrict__ accepted, float* __restrict__ stats,
                                                       int32_t* __restrict__ rounds, int32_t* __restrict__ live,
-                                                      int32_t* __restrict__ win, PlanOut plan) {
+                                                      int32_t* __restrict__ win, PlanOut plan,
+                                                      int64_t* __restrict__ prof_counts) {
   __shared__ float s_part[kAcceptChunk][16][2];  // per slot of the chunk, per wavefront: partial <D,xi>, |D|^2
   __shared__ float s_rej[2];                     // <D,xi>, |D|^2 of the first rejected slot
   __shared__ int s_first;                        // index inside the chunk of the first rejection, 64 if none
@@ -381,7 +382,9 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   const float4 ga1 = (single && tid < nblk) ? load4(g_a, tid, d, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
 
   int n_acc = w;
+  int examined = 0;   // slots whose x0hat row was read for the test
   for (int base = 0; base < w; base += kAcceptChunk) {
+    examined = min(w, base + kAcceptChunk) - 1;
     // every thread walks the chunk's slots over its own coordinate blocks; the loads of the slots are
     // independent, so a whole chunk of rows is in flight per wavefront
     float dot[kAcceptChunk], vv[kAcceptChunk];
@@ -493,6 +496,10 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   }
   if (tid == 0) {
     a[c] = a_next;
+    if (prof_counts) {
+      atomicAdd((unsigned long long*)&prof_counts[2], (unsigned long long)examined);
+      if (n_acc < w) atomicAdd((unsigned long long*)&prof_counts[3], 1ull);
+    }
     if (accepted) accepted[c] = n_acc;
     if (rounds) rounds[c] += 1;
     if (win) {
@@ -519,12 +526,15 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
   const PlanOut plan = plan_out(ctx, nullptr);
+  int64_t* prof_counts = ctx->prof.on ? ctx->row_counts : nullptr;
   if (plan.in_off)
     hipLaunchKernelGGL(accept_kernel<true>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan);
+                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan,
+                       prof_counts);
   else
     hipLaunchKernelGGL(accept_kernel<false>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan);
+                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan,
+                       prof_counts);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
