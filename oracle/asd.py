@@ -47,8 +47,16 @@ def near_tie(log_u, log_ratio, eps):
     return abs(log_u - log_ratio) <= eps * (1.0 + abs(log_ratio) + abs(log_u))
 
 
-def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
+def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4, g_a=None, evaluate_end=False):
     """One iteration of the while-loop of Alg. 1 from state (a, y_a).
+
+    Model-call reuse across iterations (the paper's accounting of "sequential network calls" implies that
+    evaluations are carried over; Alg. 1 as printed makes both calls every time):
+    evaluate_end: the batched call also evaluates the model at the last proposal sample yhat_b (time index
+    b), returned as g_end (None when b = K: there is no step b).  If the whole window is accepted the next
+    iteration starts at y_b = yhat_b, and g_end is exactly its first model call; g_a: that value, handed in
+    by the caller -- the iteration then makes no model call of its own before drafting.  Nothing else
+    changes: the proposal still depends on the past only, through the same function of it.
 
     Returns a dict with every intermediate a device implementation can be
     compared against: yhat (proposal samples for steps a+1..b), g (model
@@ -65,8 +73,10 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
     b = min(K, a + L)
     w = b - a
     d = len(y_a)
-    # --- model call 1 and proposal means / samples
-    g_a = model([a], y_a[None, :])[0]
+    # --- model call 1 (unless its value was carried over) and proposal means / samples
+    carried = g_a is not None
+    if not carried:
+        g_a = model([a], y_a[None, :])[0]
     yhat = np.empty((w + 1, d))          # yhat[k] = \hat y_{a+k}
     m_hat = np.empty((w + 1, d))         # m_hat[k] = \hat m_{a+k}, k>=1
     yhat[0] = y_a
@@ -77,7 +87,12 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
     # --- model call 2: target means at the proposal samples, all slots at once
     g = np.empty((w, d))
     g[0] = g_a
-    if w > 1:
+    g_end = None
+    if evaluate_end and b < K:
+        vals = model(list(range(a + 1, b + 1)), yhat[1:w + 1])
+        g[1:] = vals[:w - 1]
+        g_end = vals[w - 1]
+    elif w > 1:
         g[1:] = model(list(range(a + 1, b)), yhat[1:w])
     m = np.empty((w + 1, d))
     for k in range(w):
@@ -124,7 +139,7 @@ def asd_round(y_a, a, L, A, Bc, sigma, model, xi, u, eps=1e-4):
         r = -1
     return dict(a=a, b=b, j=j, r=r, a_next=a_next, yhat=yhat[1:], g=g, acc=acc,
                 log_ratio=log_ratio, log_u=log_u, dot=dot, vv=vv, flagged=flagged,
-                y_new=y_new, z_rej=z_rej)
+                y_new=y_new, z_rej=z_rej, g_end=g_end, made_first_call=not carried)
 
 
 def window_init(L):
@@ -150,10 +165,12 @@ def window_next(state, w_used, n_acc):
     return state - (state >> 2) + obs
 
 
-def asd_sample(y0, L, A, Bc, sigma, model, xi, u, eps=1e-4, keep_rounds=True, adaptive=False):
+def asd_sample(y0, L, A, Bc, sigma, model, xi, u, eps=1e-4, keep_rounds=True, adaptive=False, reuse=False):
     """Alg. 1.  Returns (y [K+1, d], R, rounds) with rounds the list of
     per-iteration records of `asd_round` (empty if keep_rounds is False).
-    adaptive: the window of each round comes from the controller above (never longer than L)."""
+    adaptive: the window of each round comes from the controller above (never longer than L).
+    reuse: an iteration whose whole window is accepted hands the model value at its last sample to the next
+    one (see asd_round); the samples are the same, the number of model calls is not."""
     K = len(A)
     y = np.empty((K + 1, len(y0)))
     y[0] = y0
@@ -161,9 +178,11 @@ def asd_sample(y0, L, A, Bc, sigma, model, xi, u, eps=1e-4, keep_rounds=True, ad
     R = 0
     rounds = []
     state = window_init(L)
+    g_carry = None
     while a < K:
         win = window_of(state, L) if adaptive else L
-        rec = asd_round(y[a], a, win, A, Bc, sigma, model, xi, u, eps)
+        rec = asd_round(y[a], a, win, A, Bc, sigma, model, xi, u, eps, g_a=g_carry, evaluate_end=reuse)
+        g_carry = rec["g_end"] if (reuse and rec["j"] == rec["b"]) else None
         y[a + 1: rec["a_next"] + 1] = rec["y_new"]
         state = window_next(state, rec["b"] - a, rec["j"] - a)
         a = rec["a_next"]

@@ -90,6 +90,43 @@ def test_round_structure_invariants():
         np.testing.assert_allclose(y[K], T["c_x"][K - 1] * y[K - 1] + T["c_0"][K - 1] * g, atol=1e-13)
 
 
+def test_model_call_reuse_changes_the_call_count_and_nothing_else():
+    """Carrying the model value at yhat_b into the next iteration when the whole window was accepted: the
+    samples are the oracle's own, value for value (the mixture denoiser evaluates row by row, so a value does
+    not depend on which call computed it); first calls are made only by iteration 0 and after rejections;
+    with L = 1 every window is accepted whole, so one model call per step remains -- the sequential chain's
+    count -- and the trajectory is the sequential chain's."""
+    cfg = W.CONFIGS[1]
+    T, _, model = oracle_setup(cfg)
+    K = cfg["K"]
+    calls = []
+
+    def counting(idx, rows):
+        calls.append(len(idx))
+        return model(idx, rows)
+
+    for chain in range(4):
+        for L in (cfg["L"], 3, K):
+            xi, u = chain_randoms(4, chain, K, cfg["d"])
+            y0, R0, r0 = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u)
+            del calls[:]
+            y1, R1, r1 = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], counting, xi, u, reuse=True)
+            np.testing.assert_array_equal(y0, y1)
+            assert R0 == R1 and [r["j"] for r in r0] == [r["j"] for r in r1]
+            first = [r["made_first_call"] for r in r1]
+            assert first[0]
+            for prev, f in zip(r1[:-1], first[1:]):
+                assert f == (prev["j"] < prev["b"])            # a first call only after a rejection
+            # rows evaluated: one per first call; per iteration w - 1 tested slots plus yhat_b when b < K
+            want = sum(first) + sum((r["b"] - r["a"] - 1) + (r["b"] < K) for r in r1)
+            assert sum(calls) == want
+    xi, u = chain_randoms(4, 0, K, cfg["d"])
+    del calls[:]
+    y, R, _ = asd.asd_sample(xi[0], 1, T["c_x"], T["c_0"], T["sigma"], counting, xi, u, reuse=True)
+    assert R == K and sum(calls) == K and len(calls) == K         # y_0's call, then yhat_b of iterations 0..K-2
+    np.testing.assert_array_equal(y, asd.sequential_chain(xi[0], T["c_x"], T["c_0"], T["sigma"], model, xi))
+
+
 def test_worst_case_round_lemma():
     """R <= 1 + K/theta + #(rounds that advanced by at most theta - 1 steps and
     did not end at K)  -- a weaker, checkable form of the round-complexity lemma."""
@@ -120,11 +157,11 @@ def test_window_controller_is_bounded_and_follows_the_run_length():
     assert asd.window_next(40, 10, 7) == 40 - 10 + 7
 
 
-@pytest.mark.parametrize("adaptive", [False, True])
-def test_exact_in_law_gaussian_data_closed_form(adaptive):
+@pytest.mark.parametrize("adaptive,reuse", [(False, False), (True, False), (False, True), (True, True)])
+def test_exact_in_law_gaussian_data_closed_form(adaptive, reuse):
     """Single Gaussian data law: the chain is linear-Gaussian, so Law(y_i) is
-    N(mean_i, var_i) by a scalar recursion.  ASD samples must follow it -- with fixed windows and
-    with windows chosen from the chain's past by the controller."""
+    N(mean_i, var_i) by a scalar recursion.  ASD samples must follow it -- with fixed windows, with
+    windows chosen from the chain's past by the controller, and with model values carried across iterations."""
     K, d, L, n = 24, 1, 6, 3000
     T = schedule.ddpm_tables(K)
     mu, s2 = 1.5, 0.25
@@ -141,7 +178,8 @@ def test_exact_in_law_gaussian_data_closed_form(adaptive):
     rej = 0
     for c in range(n):
         xi, u = chain_randoms(9, c, K, d)
-        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u, adaptive=adaptive)
+        y, R, rounds = asd.asd_sample(xi[0], L, T["c_x"], T["c_0"], T["sigma"], model, xi, u, adaptive=adaptive,
+                                      reuse=reuse)
         Y[c] = y[:, 0]
         rej += sum(1 for r in rounds if r["r"] >= 0 and r["r"] < K)
     assert rej > n / 4                                      # the rejection branch is exercised
