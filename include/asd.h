@@ -217,6 +217,16 @@ ASD_API asd_status asd_use_graphs(asd_ctx* ctx, int32_t on);
  * calls always use L. */
 ASD_API asd_status asd_use_adaptive_window(asd_ctx* ctx, int32_t on);
 
+/* Model-call reuse across rounds in asd_sample (the paper counts "sequential network calls" as if evaluations
+ * were carried from one iteration of Alg. 1 to the next; Alg. 1 as printed makes two calls per iteration).
+ * on = 1: the batched verify call also evaluates the model at the last proposal sample yhat_b of every window
+ * that ends before K (one more row per chain); a chain whose whole window is accepted starts its next round at
+ * y_b = yhat_b with that value as x0a and is left out of the next draft call.  The samples are the same function
+ * of the random inputs (to the rounding difference between the two calls' GEMM tilings); what changes is the
+ * number of rows each call evaluates.  With a noalloc sample the scratch bound counts L + 1 slots per chain.
+ * Default: off.  The stage calls and the chain-resident path do not reuse. */
+ASD_API asd_status asd_use_call_reuse(asd_ctx* ctx, int32_t on);
+
 /* For a Gaussian-mixture denoiser small enough to sit in one CU's LDS (with the window of a chain),
  * asd_sample runs Alg. 1 for each chain inside one workgroup: one launch per sample instead of
  * several per round (chains do not interact, so no step of the method changes; rounds[c] keeps its

@@ -142,7 +142,10 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->n_rows_dev, sizeof(int32_t) * 2));
   ASD_HIP(hipMemset(ctx->n_rows_dev, 0, sizeof(int32_t) * 2));
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
-  ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * rows * (size_t)ctx->d));
+  // one more slot per chain than the window: with model-call reuse slot w holds the model value at yhat_b
+  ASD_HIP(hipMalloc(&ctx->x0hat, sizeof(float) * (size_t)ctx->B * ((size_t)ctx->L + 1) * (size_t)ctx->d));
+  ASD_HIP(hipMalloc(&ctx->carry, sizeof(int32_t) * (size_t)ctx->B));
+  ASD_HIP(hipMemset(ctx->carry, 0, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 4));
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
@@ -175,6 +178,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->n_rows_dev);
   (void)hipFree(ctx->x0a);
   (void)hipFree(ctx->x0hat);
+  (void)hipFree(ctx->carry);
   (void)hipFree(ctx->a);
   (void)hipFree(ctx->live);
   (void)hipFree(ctx->chain_max);
@@ -198,7 +202,8 @@ static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
 }
 
 static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
-  return RowPlan{ctx->B * (ctx->L - 1), ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
+  const int per_chain = ctx->L - 1 + (ctx->reuse_now ? 1 : 0);   // tested slots, plus yhat_b with model-call reuse
+  return RowPlan{ctx->B * per_chain, ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
 }
 
 __global__ void set_key_kernel(Key* dst, Key key) { *dst = key; }
@@ -298,7 +303,7 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
   if (!a) return fail(ASD_EINVAL, "a is NULL");
   if (ctx->stage != 2) return fail(ASD_ESTATE, "asd_accept called out of order (expected stage %d)", ctx->stage);
   ASD_TRY(flush_key(ctx, (hipStream_t)stream));
-  ASD_TRY(launch_accept(ctx, traj, a, x0hat, accepted, stats, nullptr, nullptr, (hipStream_t)stream));
+  ASD_TRY(launch_accept(ctx, traj, a, x0hat, ctx->L, accepted, stats, nullptr, nullptr, (hipStream_t)stream));
   ctx->stage = 0;
   return ASD_OK;
 }
@@ -311,11 +316,12 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, floa
   if (!ctx->fold_plans) ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
   ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
   ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live));
-  if (ctx->L > 1) {
+  if (ctx->L > 1 || ctx->reuse_now) {
     if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
     ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
   }
-  ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, nullptr, nullptr, rounds, ctx->live, st));
+  ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, ctx->L + (ctx->reuse_now ? 1 : 0), nullptr, nullptr, rounds, ctx->live,
+                        st));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
   ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * kLiveRing, hipMemcpyDeviceToHost, st));
@@ -327,7 +333,7 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, floa
 // advanced on the device, the seed is read from device memory.
 static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
   if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st &&
-      ctx->g_win == ctx->cur_win)
+      ctx->g_win == ctx->cur_win && ctx->g_reuse == ctx->reuse_now)
     return ASD_OK;
   hipGraph_t graph = nullptr;
   ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
@@ -349,6 +355,7 @@ static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds,
   ctx->g_rounds = rounds;
   ctx->g_stream = st;
   ctx->g_win = ctx->cur_win;
+  ctx->g_reuse = ctx->reuse_now;
   return ASD_OK;
 }
 
@@ -365,10 +372,12 @@ static asd_status sample_rounds(asd_ctx* ctx, const float* y0, float* traj, int3
       // -5% per sample), a wash for large batches, whose draft / accept kernels run near their own
       // limits (cfg 5: +13 and +18 us on them against 27 us of planning kernels).
       c->fold_plans = c->n_rows_max <= 16384;
+      c->reuse_now = c->reuse;
     }
     ~WinScope() {
       c->cur_win = nullptr;
       c->fold_plans = false;
+      c->reuse_now = false;
     }
   } win_scope(ctx);
   // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
@@ -434,7 +443,7 @@ asd_status asd_sample_noalloc(asd_ctx* ctx, const float* y0, float* traj, int32_
   if (y0) ASD_TRY(check_rows_ptr(ctx, y0, "y0"));
   if (ctx->stage != 0) return fail(ASD_ESTATE, "asd_sample_noalloc called between stage calls");
   if (ctx->prof.on) return fail(ASD_ESTATE, "asd_sample_noalloc: per-kernel timing creates events; switch it off");
-  const size_t need = sizeof(float) * (size_t)ctx->n_rows_max * (size_t)ctx->d;
+  const size_t need = sizeof(float) * (size_t)ctx->B * ((size_t)ctx->L + (ctx->reuse ? 1 : 0)) * (size_t)ctx->d;
   if (need > kNoallocScratchBytes)
     return fail(ASD_EUNSUPPORTED, "asd_sample_noalloc: chains*L*d*4 = %zu bytes exceeds the %zu-byte static scratch",
                 need, kNoallocScratchBytes);
@@ -471,6 +480,12 @@ asd_status asd_use_graphs(asd_ctx* ctx, int32_t on) {
 asd_status asd_use_adaptive_window(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   ctx->adaptive = on != 0;
+  return ASD_OK;
+}
+
+asd_status asd_use_call_reuse(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  ctx->reuse = on != 0;
   return ASD_OK;
 }
 

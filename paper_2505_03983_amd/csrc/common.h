@@ -138,7 +138,14 @@ struct asd_ctx {
   int32_t* cur_win = nullptr;  // what the round kernels are given: win while an adaptive sample runs, else NULL (= L)
   bool adaptive = false;
   const void* g_win = nullptr; // cur_win the round graph was captured with
+  bool g_reuse = false;        // reuse_now the round graph was captured with
   bool fold_plans = false;     // set while asd_sample's rounds run: see PlanOut
+  // Model-call reuse across rounds (asd_use_call_reuse): the verify call also evaluates the last proposal sample
+  // yhat_b of every window (slot w of x0hat, hence L + 1 slots per chain there); a chain whose whole window was
+  // accepted takes that value as its next x0a and is left out of the next draft call (carry[c] = 1).
+  bool reuse = false;          // the switch
+  bool reuse_now = false;      // set while asd_sample's rounds run with the switch on (the stage calls never reuse)
+  int32_t* carry = nullptr;    // DEV [B]
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
@@ -198,7 +205,8 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st);
 asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring = nullptr);
 asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st);
-asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
+// x0_slots: slots per chain of x0hat (L for the caller's array of the stage calls, L + 1 with model-call reuse)
+asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int x0_slots, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st);
 asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st);
 asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st);

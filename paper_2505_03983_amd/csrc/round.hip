@@ -13,7 +13,7 @@ namespace asd {
 __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ key_p, const float* __restrict__ y0,
                                   float* __restrict__ traj, int32_t* __restrict__ a,
                                   int32_t* __restrict__ rounds, int32_t* __restrict__ round_idx, int L,
-                                  int32_t* __restrict__ win, PlanOut plan) {
+                                  int32_t* __restrict__ win, int32_t* __restrict__ carry, PlanOut plan) {
   const int c = blockIdx.x;
   const Key key = *key_p;
   if (c == 0 && threadIdx.x == 0 && round_idx) *round_idx = 0;
@@ -36,6 +36,7 @@ __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ k
   }
   if (threadIdx.x == 0) {
     a[c] = 0;
+    if (carry) carry[c] = 0;
     if (rounds) rounds[c] = 0;
     if (win) {
       win[B + c] = 4 * L;
@@ -60,7 +61,7 @@ static PlanOut plan_out(asd_ctx* ctx, int32_t* ring) {
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds,
                              hipStream_t st) {
   hipLaunchKernelGGL(init_state_kernel, dim3(ctx->B), dim3(256), 0, st, ctx->B, ctx->K, ctx->d, ctx->key_dev, y0,
-                     traj, a, rounds, ctx->live, ctx->L, ctx->cur_win, plan_out(ctx, nullptr));
+                     traj, a, rounds, ctx->live, ctx->L, ctx->cur_win, ctx->carry, plan_out(ctx, nullptr));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -107,7 +108,10 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows,
                                                          int32_t* __restrict__ ring,
                                                          int64_t* __restrict__ row_counts,
-                                                         const int32_t* __restrict__ win) {
+                                                         const int32_t* __restrict__ win,
+                                                         const int32_t* __restrict__ carry, int extra, int slots) {
+  // carry (draft call): chains whose x0a was handed over by the last round are not listed.  extra (verify call):
+  // 1 = also list the last proposal sample yhat_b of a window that ends before K.  slots: slots per chain of x0hat.
   __shared__ int s_wave[16];
   __shared__ int s_total;
   __shared__ int s_off[1024], s_cnt[1024], s_ac[1024];
@@ -125,7 +129,10 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     int ac = K, cnt = 0;
     if (c < B) {
       ac = min(max(a[c], 0), K);
-      if (ac < K) cnt = (MODE == 0) ? 1 : min(win ? win[c] : L, K - ac) - 1;
+      if (ac < K) {
+        const int w = min(win ? win[c] : L, K - ac);
+        cnt = (MODE == 0) ? ((carry && carry[c]) ? 0 : 1) : w - 1 + ((extra && ac + w < K) ? 1 : 0);
+      }
     }
     const int off = base + block_exclusive_scan(cnt, s_wave, &s_total);
     if (MODE == 0) {
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
         for (int s = 1 + lane; s <= n_t; s += 64) {
           const int i = a_t + s;
           in_off[o_t + s - 1] = ((int64_t)c_t * (K + 1) + i) * d;
-          out_off[o_t + s - 1] = ((int64_t)c_t * L + s) * d;
+          out_off[o_t + s - 1] = ((int64_t)c_t * slots + s) * d;
           row_tau[o_t + s - 1] = tau[i];
         }
       }
@@ -165,19 +172,21 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, ring,
-                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win);
+                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win,
+                     ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
 
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
-  if (ctx->L <= 1) return ASD_OK;
+  if (ctx->L <= 1 && !ctx->reuse_now) return ASD_OK;
   ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
   // up to 64 workgroups share the filling of a large plan (a chain per wavefront at a time, see the kernel)
   const unsigned wgs = (unsigned)std::min<int64_t>(64, std::max<int64_t>(1, ctx->n_rows_max / 1024));
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
-                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win);
+                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
+                     ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -197,7 +206,9 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
                                                     const float* __restrict__ c_0,
                                                     const float* __restrict__ sigma,
                                                     const float* __restrict__ x0a, float* __restrict__ traj,
-                                                    const int32_t* __restrict__ win, PlanOut plan) {
+                                                    const int32_t* __restrict__ win, PlanOut plan, int extra) {
+  // extra (FOLD only): 1 = the verify call also evaluates yhat_b of a window that ends before K (slot w of
+  // x0hat, which then has Lwin + 1 slots per chain)
   const int c = blockIdx.y;
   const int blk = blockIdx.x * blockDim.x + threadIdx.x;
   const int nblk = (d + 3) >> 2;
@@ -217,17 +228,18 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
     }
     // This chain's rows of the verify call: the drafted samples of slots 1..w-1, read in place from the
     // trajectory, results to x0hat[c][slot].  One atomic add reserves the range; the first wavefront fills it.
-    if (threadIdx.x < 64 && w > 1) {
+    const int cnt = w - 1 + ((extra && live && ac + w < K) ? 1 : 0);
+    if (threadIdx.x < 64 && cnt > 0) {
       int base = 0;
       if (threadIdx.x == 0) {
-        base = atomicAdd(&plan.n_rows[1], w - 1);
-        if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[1], (unsigned long long)(w - 1));
+        base = atomicAdd(&plan.n_rows[1], cnt);
+        if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[1], (unsigned long long)cnt);
       }
       base = __shfl(base, 0, 64);
-      for (int s = 1 + (int)threadIdx.x; s < w; s += 64) {
+      for (int s = 1 + (int)threadIdx.x; s <= cnt; s += 64) {
         const int i = ac + s;
         plan.in_off[base + s - 1] = ((int64_t)c * (K + 1) + i) * d;
-        plan.out_off[base + s - 1] = ((int64_t)c * Lwin + s) * d;
+        plan.out_off[base + s - 1] = ((int64_t)c * (Lwin + extra) + s) * d;
         plan.row_tau[base + s - 1] = plan.tau[i];
       }
     }
@@ -259,10 +271,10 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   const PlanOut plan = plan_out(ctx, ring);
   if (plan.in_off)
     hipLaunchKernelGGL(draft_kernel<true>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan);
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, ctx->reuse_now ? 1 : 0);
   else
     hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan);
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, 0);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -286,7 +298,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut());
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut(), 0);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -334,8 +346,9 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
                                                       int32_t* __restrict__ a,
                                                       const float* __restrict__ c_0,
                                                       const float* __restrict__ sigma,
-                                                      const float* __restrict__ x0a,
-                                                      const float* __restrict__ x0hat, float* __restrict__ traj,
+                                                      float* x0a, int32_t* __restrict__ carry,
+                                                      const float* __restrict__ x0hat, int x0_slots,
+                                                      float* __restrict__ traj,
                                                       int32_t* __restrict__ accepted, float* __restrict__ stats,
                                                       int32_t* __restrict__ rounds, int32_t* __restrict__ live,
                                                       int32_t* __restrict__ win, PlanOut plan,
@@ -364,7 +377,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   const int nblk = (d + 3) >> 2;
   const bool vec = (d & 3) == 0;
   const float* g_a = x0a + (int64_t)c * d;
-  const float* g_w = x0hat + (int64_t)c * L * d;
+  const float* g_w = x0hat + (int64_t)c * x0_slots * d;
 
   auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {
     // coordinates past d load as zero in both rows, so they add nothing
@@ -494,8 +507,17 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   } else {
     a_next = ac + w;
   }
+  // Model-call reuse: the whole window was accepted, so the next round starts at yhat_b, where the verify call
+  // has already evaluated the model (slot w): that value becomes x0a and the chain skips the next draft call.
+  // (Every read of x0a by this workgroup lies before the barrier that ended the last group of slots.)
+  const bool carried = carry && n_acc == w && a_next < K;
+  if (carried) {
+    const float* g_e = g_w + (int64_t)w * d;
+    for (int blk = tid; blk < nblk; blk += nthreads) store4(x0a + (int64_t)c * d, blk, d, vec, load4(g_e, blk, d, vec));
+  }
   if (tid == 0) {
     a[c] = a_next;
+    if (carry) carry[c] = carried ? 1 : 0;
     if (prof_counts) {
       atomicAdd((unsigned long long*)&prof_counts[2], (unsigned long long)examined);
       if (n_acc < w) atomicAdd((unsigned long long*)&prof_counts[3], 1ull);
@@ -510,7 +532,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
     }
     // the round index was advanced at the start of this round
     if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
-    if constexpr (FOLD) if (a_next < K) {  // this chain's row of the next round's draft call
+    if constexpr (FOLD) if (a_next < K && !carried) {  // this chain's row of the next round's draft call
       const int idx = atomicAdd(&plan.n_rows[0], 1);
       plan.in_off[idx] = ((int64_t)c * (K + 1) + a_next) * d;
       plan.out_off[idx] = (int64_t)c * d;
@@ -520,21 +542,22 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   }
 }
 
-asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int32_t* accepted,
+asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int x0_slots, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
   ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
   const PlanOut plan = plan_out(ctx, nullptr);
   int64_t* prof_counts = ctx->prof.on ? ctx->row_counts : nullptr;
+  int32_t* carry = ctx->reuse_now ? ctx->carry : nullptr;
   if (plan.in_off)
     hipLaunchKernelGGL(accept_kernel<true>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan,
-                       prof_counts);
+                       ctx->c_0, ctx->sigma, ctx->x0a, carry, x0hat, x0_slots, traj, accepted, stats, rounds, live,
+                       ctx->cur_win, plan, prof_counts);
   else
     hipLaunchKernelGGL(accept_kernel<false>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                       ctx->c_0, ctx->sigma, ctx->x0a, x0hat, traj, accepted, stats, rounds, live, ctx->cur_win, plan,
-                       prof_counts);
+                       ctx->c_0, ctx->sigma, ctx->x0a, carry, x0hat, x0_slots, traj, accepted, stats, rounds, live,
+                       ctx->cur_win, plan, prof_counts);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }

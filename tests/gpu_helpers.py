@@ -175,26 +175,33 @@ def compare_round(out, c, rec, tol, K, c_0=None, x0_scale=1.0, worst=None, xi=No
     return n_dev == n_acc
 
 
-def follow_chain(cfg, T, model, seed, c, tj, tol, L=None, adaptive=False, max_rounds=None, y0=None, resync=False):
+def follow_chain(cfg, T, model, seed, c, tj, tol, L=None, adaptive=False, max_rounds=None, y0=None, resync=False,
+                 reuse=False):
     """The oracle's Alg. 1 for chain c next to a device trajectory tj [K+1, d] of a whole sample.
 
     Each round is the oracle's own (from its own state y[a]; from the device's state tj[a] if resync);
     on unflagged slots the oracle's decision stands, on a flagged slot of the walked prefix the branch is
     read off the device's row of that step (it equals one of the two branch values) and followed.
-    Returns dict(y, a, R, flips, flagged_slots, round_err): y the oracle's trajectory up to a, R rounds,
-    round_err the largest relative error of the rows written by a single round."""
+    reuse: model values carried across rounds on the oracle's side as well (a whole window accepted -- on the
+    branch the device took -- hands the value at yhat_b to the next round).
+    Returns dict(y, a, R, flips, flagged_slots, round_err, first_calls): y the oracle's trajectory up to a, R
+    rounds, round_err the largest relative error of the rows written by a single round, first_calls the
+    rounds that made a draft call of their own."""
     K, d = cfg["K"], cfg["d"]
     L = L or cfg["L"]
     xi, u = chain_randoms(seed, c, K, d)
     y = np.zeros((K + 1, d))
     y[0] = xi[0] if y0 is None else y0
-    a = R = flips = nflag = 0
+    a = R = flips = nflag = first_calls = 0
     round_err = 0.0
     state = oasd.window_init(L)
+    g_carry = None
     while a < K and (max_rounds is None or R < max_rounds):
         win = oasd.window_of(state, L) if adaptive else L
         start = np.asarray(tj[a], dtype=np.float64) if resync else y[a]
-        rec = oasd.asd_round(start, a, win, T["c_x"], T["c_0"], T["sigma"], model, xi, u, eps=tol)
+        rec = oasd.asd_round(start, a, win, T["c_x"], T["c_0"], T["sigma"], model, xi, u, eps=tol, g_a=g_carry,
+                             evaluate_end=reuse)
+        first_calls += rec["made_first_call"]
         w = rec["b"] - a
         n = 0
         while n < w:
@@ -209,9 +216,10 @@ def follow_chain(cfg, T, model, seed, c, tj, tol, L=None, adaptive=False, max_ro
                 break
             n += 1
         y_new, a_next = outcome(rec, n)
+        g_carry = rec["g_end"] if (reuse and n == w) else None
         round_err = max(round_err, rel_err(tj[a + 1: a_next + 1], y_new))
         y[a + 1: a_next + 1] = y_new
         state = oasd.window_next(state, w, n)
         a = a_next
         R += 1
-    return dict(y=y, a=a, R=R, flips=flips, flagged_slots=nflag, round_err=round_err)
+    return dict(y=y, a=a, R=R, flips=flips, flagged_slots=nflag, round_err=round_err, first_calls=first_calls)

@@ -296,7 +296,7 @@ def test_round_midsize_matrix_core_shapes():
 # ---------------------------------------------------------------------------
 # whole samples, free-running
 # ---------------------------------------------------------------------------
-def _free_running(cfg, seed, chains_checked, y0=None, resident=True, adaptive=False, graphs=True):
+def _free_running(cfg, seed, chains_checked, y0=None, resident=True, adaptive=False, graphs=True, reuse=False):
     """Whole samples from asd_sample against the oracle's Alg. 1 run next to them (H.follow_chain): every
     chain is compared over all K steps; on a flagged near-tie the oracle follows the branch the device took.
     resident: let asd_sample use the chain-resident kernel where the shape allows (the default);
@@ -308,6 +308,7 @@ def _free_running(cfg, seed, chains_checked, y0=None, resident=True, adaptive=Fa
     ctx.use_resident(resident)
     ctx.use_adaptive_window(adaptive)
     ctx.use_graphs(graphs)
+    ctx.use_call_reuse(reuse)
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
     n_launch = ctx.sample(traj, rounds)
@@ -316,7 +317,7 @@ def _free_running(cfg, seed, chains_checked, y0=None, resident=True, adaptive=Fa
     full = flips = flagged = 0
     worst = 0.0
     for c in chains_checked:
-        f = H.follow_chain(cfg, T, model, seed, c, tj[c], tol, adaptive=adaptive)
+        f = H.follow_chain(cfg, T, model, seed, c, tj[c], tol, adaptive=adaptive, reuse=reuse)
         e = H.rel_err(tj[c], f["y"])
         worst = max(worst, e)
         assert e <= tol, ("trajectory", c, e)
@@ -418,6 +419,51 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.profile_enable(False)
     _log("verify rows per sample: fixed", fixed_rows, "adaptive", adaptive_rows, "rounds max", int(r2.max()), int(r1.max()))
     assert adaptive_rows < fixed_rows
+    ctx.close()
+
+
+def test_model_call_reuse_matches_the_oracle():
+    """asd_use_call_reuse: the verify call also evaluates yhat_b, a fully accepted window hands that value to the
+    next round and the chain skips the next draft call.  Whole samples against the oracle run with the same rule,
+    on the lock-step round kernels: row-wise and matrix-core mixture paths, L = 1 (every round hands over),
+    L >= K, windows from the controller, the MLP; rounds as graphs and as plain launches."""
+    full = 0
+    for seed in range(2):
+        full += _free_running(W.CONFIGS[1], 60 + seed, range(8), resident=False, reuse=True)
+    assert full >= 12
+    _free_running(W.CONFIGS[2], 62, [0, 9, 63], resident=False, reuse=True, adaptive=True)
+    for cfg in (dict(kind="gmm", d=7, C=5, K=37, chains=5, L=6, var=0.25),
+                dict(kind="gmm", d=5, C=3, K=9, chains=3, L=1, var=0.25),
+                dict(W.CONFIGS[1], L=W.CONFIGS[1]["K"]),
+                dict(kind="gmm", d=8, C=6, K=150, chains=4, L=100, var=0.25),
+                dict(kind="gmm", d=64, C=1024, K=20, chains=70, L=16, var=0.25)):      # matrix-core path, both calls
+        _free_running(cfg, 63, range(min(cfg["chains"], 4)), resident=False, reuse=True, graphs=bool(cfg["d"] & 1))
+    small_mlp = dict(kind="mlp", d=16, E=8, width=64, n_blocks=2, K=30, chains=6, L=12)
+    _free_running(small_mlp, 64, range(6), resident=False, reuse=True)
+    _free_running(small_mlp, 64, range(6), resident=False, reuse=True, adaptive=True)
+    # the switch changes which call evaluates a row, not the sample: same seed with and without
+    cfg = W.CONFIGS[2]
+    _, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=5)
+    ctx.use_resident(False)
+    t0, t1 = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+    r0 = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+    r1 = torch.zeros_like(r0)
+    ctx.profile_enable(True)
+    ctx.sample(t0, r0)
+    rows0 = ctx.profile_rows()
+    ctx.profile_enable(False)
+    ctx.use_call_reuse(True)
+    ctx.profile_enable(True)
+    ctx.sample(t1, r1)
+    rows1 = ctx.profile_rows()
+    ctx.profile_enable(False)
+    _log("model rows per sample (draft call, verify call): without reuse", rows0, "with", rows1)
+    assert torch.equal(r0, r1) and H.rel_err(t1.cpu().numpy(), t0.cpu().numpy()) <= 1e-4
+    assert rows1[0] < rows0[0] and rows1[1] > rows0[1]
+    ctx.use_call_reuse(False)
+    ctx.sample(t1, r1)
+    assert torch.equal(t0, t1)
     ctx.close()
 
 
@@ -727,7 +773,7 @@ def _full_size_round(w, sampled, seed=0, split=None, states=None):
          "mean accepted", float(acc[acc >= 0].mean()), "worst errors", {k: float("%.2e" % v) for k, v in worst.items()})
 
 
-def _full_size_prefix(w, seed, chains_checked, n_rounds, adaptive):
+def _full_size_prefix(w, seed, chains_checked, n_rounds, adaptive, reuse=False):
     """The whole-sample driver at full size, in the launch configuration the benchmark times: sampled chains of
     a complete asd_sample against the oracle run freely from y_0 for n_rounds rounds (a whole chain would take the
     CPU minutes at these sizes), following the device through flagged near-ties."""
@@ -736,6 +782,7 @@ def _full_size_prefix(w, seed, chains_checked, n_rounds, adaptive):
     tol = H.TOL[cfg["kind"]]
     ctx = runtime.open_ctx(cfg, p, seed=seed)
     ctx.use_adaptive_window(adaptive)
+    ctx.use_call_reuse(reuse)
     assert not ctx.resident_active()
     if cfg["kind"] == "gmm":
         assert ctx.split_gemm_active()
@@ -746,7 +793,7 @@ def _full_size_prefix(w, seed, chains_checked, n_rounds, adaptive):
     steps = 0
     for c in chains_checked:
         tj = traj[c].cpu().numpy()
-        f = H.follow_chain(cfg, T, model, seed, c, tj, tol, adaptive=adaptive, max_rounds=n_rounds)
+        f = H.follow_chain(cfg, T, model, seed, c, tj, tol, adaptive=adaptive, max_rounds=n_rounds, reuse=reuse)
         e = H.rel_err(tj[: f["a"] + 1], f["y"][: f["a"] + 1])
         _log("cfg", w, "free-running prefix: chain", c, "adaptive", adaptive, "rounds", f["R"], "steps compared", f["a"],
              "rel err %.2e" % e, "flagged slots", f["flagged_slots"], "followed to the other branch", f["flips"])
@@ -761,6 +808,13 @@ def test_sample_config5_full_size_prefix(adaptive):
     """Headline size (lock-step round kernels, bf16 split-operand verify GEMMs): two chains of a full
     1024-chain sample, five rounds each from y_0."""
     assert _full_size_prefix(5, 3, (0, 777), 5, adaptive) >= 10
+
+
+def test_model_call_reuse_at_full_size():
+    """The two large workloads with model-call reuse and window control on (where handing over pays most)."""
+    assert _full_size_prefix(5, 4, (1, 1000), 5, True, reuse=True) >= 10
+    assert _full_size_prefix(4, 5, (2, 50), 6, True, reuse=True) >= 12
+    assert _full_size_prefix(4, 5, (3,), 6, False, reuse=True) >= 6
 
 
 def test_round_config4_full_size_sampled():

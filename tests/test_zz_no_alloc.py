@@ -17,8 +17,9 @@ import gpu_helpers as H                              # noqa: E402
 DEV = "cuda:0"
 
 
-def _pair(cfg, p, seed, chains=None, L=None, adaptive=False):
+def _pair(cfg, p, seed, chains=None, L=None, adaptive=False, reuse=False):
     ctx = runtime.open_ctx(cfg, p, seed=seed, chains=chains, L=L)
+    ctx.use_call_reuse(reuse)
     ctx.use_resident(False)          # asd_sample on the same lock-step round kernels, plainly launched
     ctx.use_graphs(False)
     ctx.use_adaptive_window(adaptive)
@@ -44,6 +45,7 @@ def test_noalloc_sample_equals_sample_twice_in_a_row_second_smaller():
     _pair(cfg, p, seed=7)                          # 64 chains, L = 16: 256 KB of scratch
     _pair(cfg, p, seed=8, chains=5, L=7)           # smaller: the scratch still holds the first call's values
     _pair(cfg, p, seed=9, chains=9, adaptive=True)
+    _pair(cfg, p, seed=11, chains=7, reuse=True)   # L + 1 slots per chain in the scratch
     small_mlp = dict(kind="mlp", d=16, E=8, width=64, n_blocks=2, K=30, chains=6, L=12)
     _, pm, _ = oracle_setup(small_mlp)
     _pair(small_mlp, pm, seed=10)
