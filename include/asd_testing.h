@@ -19,6 +19,12 @@ ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 /* 1 if the verify call of this context runs the split-operand bf16 kernels. */
 ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 
+/* The second GEMM of the split-operand mixture denoiser (softmax weights times means) skips the stretches of
+ * components whose weights are exactly 0.0f for every row of a tile (2^(logit - row maximum) underflows once a
+ * posterior has collapsed).  The skipped products are zeros, so results are identical bit for bit; on = 0 makes
+ * the kernel visit every component anyway (for tests and timing comparisons).  Default: on. */
+ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);
+
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
 ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,

@@ -69,6 +69,7 @@ def lib():
             "asd_use_graphs": (i32, [vp, i32]),
             "asd_use_resident": (i32, [vp, i32]),
             "asd_use_call_reuse": (i32, [vp, i32]),
+            "asd_use_sparse_combine": (i32, [vp, i32]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_use_split_gemm": (i32, [vp, i32]),
@@ -242,6 +243,9 @@ class Ctx:
 
     def use_call_reuse(self, on=True):
         _check(lib().asd_use_call_reuse(self.h, int(bool(on))))
+
+    def use_sparse_combine(self, on=True):
+        _check(lib().asd_use_sparse_combine(self.h, int(bool(on))))
 
     def use_resident(self, on=True):
         _check(lib().asd_use_resident(self.h, int(bool(on))))

@@ -507,6 +507,18 @@ asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on) {
   return ASD_OK;
 }
 
+asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  if (ctx->gmm && ctx->gmm->sparse_combine != (on != 0)) {
+    ctx->gmm->sparse_combine = on != 0;
+    if (ctx->gexec) {   // the captured round holds the other launch arguments
+      (void)hipGraphExecDestroy(ctx->gexec);
+      ctx->gexec = nullptr;
+    }
+  }
+  return ASD_OK;
+}
+
 int32_t asd_split_gemm_active(const asd_ctx* ctx) { return (ctx && ctx->gmm && ctx->gmm->use_split) ? 1 : 0; }
 
 int32_t asd_resident_active(const asd_ctx* ctx) {

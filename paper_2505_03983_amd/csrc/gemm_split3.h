@@ -39,6 +39,14 @@
 //
 // Requirements (checked by the host): K % 16 == 0, rows of A 16-byte aligned.  Rows of the image past
 // N are zero.  M is read from device memory; workgroups past it exit at once.
+//
+// Sparse K (Ops with kSparseK, no K split).  When load_a maps whole stretches of A to exactly 0.0f -- the
+// second GEMM of the mixture denoiser, whose A operand is 2^(logit - row maximum): once a posterior has
+// collapsed onto one component every other weight underflows to zero in fp32 -- the slabs of K in which
+// every row of the tile is zero contribute nothing, bit for bit, and are not visited.  The Op marks the
+// groups of columns that are live for some row of the tile (mark_live, from data the producer of A
+// left behind); one wavefront compacts them into a list of slabs in LDS and the K loop walks that list.
+// The result equals the dense loop's exactly: the skipped products and row-sum terms are zeros.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -143,7 +151,7 @@ template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
 __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
                                                                          int N, int K, RowSrc A,
                                                                          const uint8_t* __restrict__ Bimg, Op op,
-                                                                         float* __restrict__ part) {
+                                                                         float* __restrict__ part, int sparse) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ, BK = Cfg::BK, NG = Cfg::NG, RB = Cfg::RB;
   constexpr int RA = Cfg::RA, RPP = Cfg::RPP, A_PLANE = Cfg::A_PLANE, B_PLANE = Cfg::B_PLANE;
   constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS;
@@ -151,6 +159,7 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   uint8_t* lds_a = lds_all;                                   // [2 stages][3 planes][BM rows][RB bytes]
   uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][3 planes][BN rows][RB bytes]
   float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
+  uint16_t* s_list = reinterpret_cast<uint16_t*>(s_row + 8 * BM);                // sparse K: [K / BK] live slabs, in order
 
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
   int tile_n = blockIdx.x, tile_m = blockIdx.y;
@@ -169,7 +178,8 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   const int wave = tid >> 6;
   const Frag<Cfg> fr{wave / Cfg::WGN, wave % Cfg::WGN, lane & 31, lane >> 5, tile_n};
   const int splits = gridDim.z;                  // K split: this workgroup contracts slabs kb .. kb + nk - 1
-  const int nk_all = K / BK, nk = nk_all / splits, kb = blockIdx.z * nk;
+  const int nk_all = K / BK, kb = blockIdx.z * (nk_all / splits);
+  int nk = nk_all / splits;
 
   // ---- loaders.  A: thread = (row lrow + RPP p, chunk lkq of 8 k).  B: thread t copies bytes 16 t + 16 THREADS q
   // of a slab's image.  Slab j waits in register slot j & 1 and goes to LDS stage j & 1.
@@ -179,22 +189,53 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
 #pragma unroll
   for (int p = 0; p < RA; ++p) {
     const int r = lrow + RPP * p;
-    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8 + (int64_t)kb * BK;
+    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8;
     a_dst[p] = r * RB + Cfg::slot(r, lkq) * 16;
   }
   op.template init<Cfg>(m0, M, lrow, lkq, s_row);
-  const uint8_t* bsrc = Bimg + ((int64_t)tile_n * nk_all + kb) * B_STAGE + tid * 16;
+  bool listed = false;   // the K loop walks s_list instead of slabs kb, kb + 1, ...
+  if constexpr (Op::kSparseK) {
+    if (sparse && splits == 1) {
+      // flags of the Op's column groups (bytes, in the LDS of the list's tail), then the list itself
+      const int ng = op.groups(), spg = op.group_cols() / BK;   // slabs per group (host: group_cols % BK == 0, K % group_cols == 0)
+      uint8_t* flags = reinterpret_cast<uint8_t*>(s_list) + ((2 * nk_all + 15) & ~15);
+      int* s_cnt = reinterpret_cast<int*>(flags + ((ng + 15) & ~15));
+      for (int g = tid; g < ng; g += Cfg::THREADS) flags[g] = 0;
+      __syncthreads();
+      op.template mark_live<Cfg>(m0, M, lrow, lkq, flags);
+      __syncthreads();
+      if (wave == 0) {
+        int count = 0;
+        for (int g0 = 0; g0 < ng; g0 += 64) {
+          const int g = g0 + lane;
+          const bool live = g < ng && flags[g] != 0;
+          const unsigned long long mask = __ballot(live);
+          const int pos = count + __popcll(mask & ((1ull << lane) - 1ull));
+          if (live)
+            for (int t = 0; t < spg; ++t) s_list[pos * spg + t] = (uint16_t)(g * spg + t);
+          count += __popcll(mask);
+        }
+        if (lane == 0) *s_cnt = count * spg;
+      }
+      __syncthreads();
+      nk = *s_cnt;
+      listed = true;
+    }
+  }
+  const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk_all * B_STAGE + tid * 16;
+  auto slab_of = [&](int kt) -> int64_t { return listed ? (int64_t)s_list[kt] : (int64_t)(kb + kt); };
   float4 ra[2][RA][2];
   u32x4 rb[2][B_LOADS];
   auto gload = [&](int kt, auto slot) {
+    const int64_t sl = slab_of(kt);
 #pragma unroll
     for (int p = 0; p < RA; ++p) {
-      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * BK);
-      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + (int64_t)kt * BK + 4);
+      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + sl * BK);
+      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + sl * BK + 4);
     }
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q)
-      rb[slot][q] = *reinterpret_cast<const u32x4*>(bsrc + (int64_t)kt * B_STAGE + q * 16 * Cfg::THREADS);
+      rb[slot][q] = *reinterpret_cast<const u32x4*>(bsrc + sl * B_STAGE + q * 16 * Cfg::THREADS);
   };
   auto sstore = [&](auto slot) {   // register slot `slot` -> LDS stage `slot`
     uint8_t* sa = lds_a + slot * A_STAGE;
@@ -317,10 +358,25 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
 }
 
 // splits > 1 (Ops with kSplitK, not with ROWS_PER_XCD): `part` = gemm_f32_splitk_floats(splits, M_max, N) floats.
+// sparse: let an Op with kSparseK skip the slabs of K it marks dead (needs K / BK <= 65535, the Op's column groups a
+// multiple of BK wide and K a multiple of them; otherwise the loop stays dense).
 template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
-                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr) {
+                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false) {
   if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
+  size_t lds = Cfg::LDS_BYTES;
+  if constexpr (Op::kSparseK) {
+    const int gc = op.group_cols();
+    sparse = sparse && splits == 1 && gc > 0 && gc % Cfg::BK == 0 && K % gc == 0 && K / Cfg::BK <= 65535;
+    // list of slabs (2 bytes each), a flag byte per column group, the count
+    if (sparse) lds += (size_t)((2 * (K / Cfg::BK) + 15) & ~15) + (size_t)((op.groups() + 15) & ~15) + 16;
+    if (lds > 80 * 1024) {   // two workgroups per CU must still fit
+      sparse = false;
+      lds = Cfg::LDS_BYTES;
+    }
+  } else {
+    sparse = false;
+  }
   if (splits > 1 && (!Op::kSplitK || ROWS_PER_XCD || !part || (K / Cfg::BK) % splits != 0)) return hipErrorInvalidValue;
   unsigned mt = (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM);
   if (ROWS_PER_XCD) mt = (mt + 7) / 8 * 8;
@@ -328,12 +384,11 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
   auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL, ROWS_PER_XCD>;
   static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)Cfg::LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M_max, N, K, A, Bimg, op, part);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), lds, st, M_dev, M_max, N, K, A, Bimg, op, part, sparse ? 1 : 0);
   return hipGetLastError();
 }
 

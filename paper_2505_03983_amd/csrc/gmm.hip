@@ -231,6 +231,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
 // inside GEMM 2, so the logits are written once and read once.
 struct LogitOp {
   static constexpr bool kSplitK = false;
+  static constexpr bool kSparseK = false;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -305,8 +306,26 @@ struct LogitOp {
 // the side and divided out in the epilogue.
 struct CombineOp {
   static constexpr bool kSplitK = true;
+  static constexpr bool kSparseK = true;
   const float* pmax;
   int np;
+  int gcols;  // logits columns behind one partial maximum (sub-tile width of the first GEMM), 0: unknown
+  // Sparse K: column group q (the columns behind pmax[.][q]) is dead for a row when its largest logit lies more
+  // than kZeroGap below the row maximum: load_a then gives 2^(l - max) = 0.0f for every element of the group
+  // (2^-150 is below the smallest fp32 subnormal), so those products are exact zeros.
+  static constexpr float kZeroGap = 150.0f;
+  __host__ __device__ __forceinline__ int groups() const { return np; }
+  __host__ __device__ __forceinline__ int group_cols() const { return gcols; }
+  template <class Cfg>
+  __device__ __forceinline__ void mark_live(int m0, int M, int lrow, int lkq, uint8_t* flags) const {
+#pragma unroll
+    for (int p = 0; p < Cfg::RA; ++p) {
+      const int m = min(m0 + lrow + Cfg::RPP * p, M - 1);
+      const float lo = rmax[p] - kZeroGap;
+      for (int q = lkq; q < np; q += Cfg::KQ)
+        if (pmax[(int64_t)m * np + q] >= lo) flags[q] = 1;
+    }
+  }
   const float* in_base;
   const int64_t* in_off;
   float* out_base;
@@ -602,11 +621,14 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
   RowSrc P{g->logits, nullptr, C};
-  CombineOp op2{g->pmax, np, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
+  // columns behind one partial row maximum: the first GEMM's wavefront sub-tile width (the last group may be short)
+  const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
+  CombineOp op2{g->pmax, np, gcols, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
     if (split)
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st)
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1,
+                                                                       nullptr, g->sparse_combine)
                         : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img_s,
                                                                                op2, st, splits, g->part));
     else

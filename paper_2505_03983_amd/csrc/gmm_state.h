@@ -28,6 +28,7 @@ struct GmmState {
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
+  bool sparse_combine = true;      // the second split GEMM of the verify call skips slabs of exact zeros (gemm_split3.h)
   size_t rowwise_lds = 0;
   size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
 };

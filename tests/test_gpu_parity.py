@@ -268,6 +268,36 @@ def test_matrix_core_denoiser_is_deterministic():
     ctx.close()
 
 
+def test_sparse_combine_is_bit_identical_to_the_dense_loop():
+    """The second split GEMM skips the slabs of components whose softmax weights are exactly 0.0f for a whole
+    row tile.  Rows at all noise levels (broad posteriors early, collapsed ones late), ragged row tile: the
+    result must equal the dense loop's bit for bit, and both the oracle's."""
+    for cfg, n_rows in ((dict(kind="gmm", d=64, C=1024, K=200, chains=70, L=16, var=0.25), 700),
+                        (dict(kind="gmm", d=128, C=4096, K=1000, chains=40, L=16, var=0.25), 517)):
+        T, p, model = oracle_setup(cfg)
+        ctx = runtime.open_ctx(cfg, p, seed=0)
+        assert ctx.split_gemm_active()
+        rng = np.random.default_rng(7)
+        tau = np.sort(rng.integers(1, cfg["K"] + 1, n_rows)).astype(np.int32)      # tiles of similar noise level
+        ab = T["abar"][tau]
+        x0 = p["means"][rng.integers(0, cfg["C"], n_rows)] + np.sqrt(p["var"]) * rng.standard_normal((n_rows, cfg["d"]))
+        x = (np.sqrt(ab)[:, None] * x0 + np.sqrt(1 - ab)[:, None] * rng.standard_normal((n_rows, cfg["d"]))).astype(np.float32)
+        xd, td = torch.from_numpy(x).to(DEV), torch.from_numpy(tau).to(DEV)
+        outs = []
+        for sparse in (True, False, True):
+            ctx.use_sparse_combine(sparse)
+            out = torch.zeros_like(xd)
+            ctx.denoise(xd, td, out)
+            torch.cuda.synchronize()
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+        want = model(K_minus(tau, cfg["K"]), x.astype(np.float64))
+        e = H.rel_err(outs[0].cpu().numpy(), want)
+        _log("sparse combine", cfg["C"], "components: bit-identical to dense, rel err vs oracle", e)
+        assert e <= 1e-4
+        ctx.close()
+
+
 def test_mfma_ceiling_probe():
     """The probe of what the matrix pipes sustain: plausible, finite figures (no fixed expectation: the rate is set
     by the chip's power management), constant operands no slower than random ones."""
