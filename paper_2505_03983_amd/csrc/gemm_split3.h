@@ -219,7 +219,7 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
       }
       __syncthreads();
       nk = *s_cnt;
-      listed = true;
+      listed = nk < nk_all;   // everything live: walk the slabs in order, without the list
     }
   }
   const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk_all * B_STAGE + tid * 16;
