@@ -189,7 +189,7 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
 #pragma unroll
   for (int p = 0; p < RA; ++p) {
     const int r = lrow + RPP * p;
-    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8;
+    ap[p] = A.row(min(m0 + r, M - 1)) + lkq * 8 + (int64_t)kb * BK;
     a_dst[p] = r * RB + Cfg::slot(r, lkq) * 16;
   }
   op.template init<Cfg>(m0, M, lrow, lkq, s_row);
@@ -222,8 +222,12 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
       listed = nk < nk_all;   // everything live: walk the slabs in order, without the list
     }
   }
-  const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk_all * B_STAGE + tid * 16;
-  auto slab_of = [&](int kt) -> int64_t { return listed ? (int64_t)s_list[kt] : (int64_t)(kb + kt); };
+  const uint8_t* bsrc = Bimg + ((int64_t)tile_n * nk_all + kb) * B_STAGE + tid * 16;
+  // slab visited in step kt of the K loop, relative to kb (a list is only built when kb = 0)
+  auto slab_of = [&](int kt) -> int64_t {
+    if constexpr (Op::kSparseK) return listed ? (int64_t)s_list[kt] : (int64_t)kt;
+    return (int64_t)kt;
+  };
   float4 ra[2][RA][2];
   u32x4 rb[2][B_LOADS];
   auto gload = [&](int kt, auto slot) {
