@@ -218,14 +218,14 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
         if (lane == 0) *s_cnt = count * spg;
       }
       __syncthreads();
-      nk = *s_cnt;
+      nk = __builtin_amdgcn_readfirstlane(*s_cnt);   // the same for every lane: keep the K loop's control flow scalar
       listed = nk < nk_all;   // everything live: walk the slabs in order, without the list
     }
   }
   const uint8_t* bsrc = Bimg + ((int64_t)tile_n * nk_all + kb) * B_STAGE + tid * 16;
   // slab visited in step kt of the K loop, relative to kb (a list is only built when kb = 0)
   auto slab_of = [&](int kt) -> int64_t {
-    if constexpr (Op::kSparseK) return listed ? (int64_t)s_list[kt] : (int64_t)kt;
+    if constexpr (Op::kSparseK) return listed ? (int64_t)__builtin_amdgcn_readfirstlane((int)s_list[kt]) : (int64_t)kt;
     return (int64_t)kt;
   };
   float4 ra[2][RA][2];
