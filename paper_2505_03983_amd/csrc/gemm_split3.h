@@ -9,9 +9,9 @@
 // leaves out a2*b3 + a3*b2 + a3*b3: with |x2| < 2^-7 |x1| and |x3| < 2^-15 |x1| that is below 2^-21 |a||b|
 // always and 2^-23 |a||b| on average -- a few units of the rounding of one fp32 multiply-add (2^-24), and
 // small against the rounding that accumulating K = 10^3 terms in fp32 brings with it either way.  Six bf16 MFMAs replace one fp32 MFMA of the same shape, and the bf16 matrix
-// pipe of this chip is 16x as fast as its fp32 one on paper.  In practice dense bf16 MFMA work on random
-// data is power-limited at about half the data-sheet rate (asd_mfma_ceiling measures it: ~1.3 PFLOP/s),
-// so the gain over the fp32 pipe is ~1.5x, at fp32 accuracy.  (Splitting into bf16 terms for
+// pipe of this chip is 16x as fast as its fp32 one on paper.  In practice this kernel keeps the bf16 pipes busy
+// in ~61% of the cycles at a power-managed clock of ~1.8 GHz (a register-only MFMA loop on random operands
+// sustains ~1.75 PFLOP/s, not the data-sheet 2.5), so the gain over the fp32 pipe is ~1.6x, at fp32 accuracy.  (Splitting into bf16 terms for
 // higher-precision products is an old, published device -- e.g. Henry, Tang, Heinecke 2019; the
 // arrangement here is this file's.)
 //

@@ -148,16 +148,12 @@ __global__ void mlp_pack_kernel(const int* __restrict__ n_dev, int n_rows, int d
   if (in_plane) *reinterpret_cast<uint4*>(in_bf + in_plane + (int64_t)n * ld_in + q * 8) = l;
 }
 
-// SiLU with the hardware exp2 and reciprocal: relative error ~1e-6, far inside what the bf16
-// re-rounding of the activations leaves of the value.
+// SiLU with the hardware exp2 and reciprocal: relative error ~1e-6, inside what the re-rounding of the
+// activations leaves of the value (2^-9 with one bf16 term, 2^-17 with two).
 __device__ __forceinline__ float silu(float z) {
   return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
 }
 
-__device__ __forceinline__ uint2 pack4_bf16(float4 v) {
-  return make_uint2((uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16),
-                    (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16));
-}
 // hi and (lo_plane > 0) lo terms of four activations, to p and p + lo_plane
 __device__ __forceinline__ void store_act4(uint16_t* p, int64_t lo_plane, float4 v) {
   const uint16_t h0 = f32_to_bf16_rne(v.x), h1 = f32_to_bf16_rne(v.y), h2 = f32_to_bf16_rne(v.z), h3 = f32_to_bf16_rne(v.w);
