@@ -25,6 +25,17 @@ ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
  * the kernel visit every component anyway (for tests and timing comparisons).  Default: on. */
 ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);
 
+/* Screening of the verify call's first GEMM in the split-operand mixture denoiser: an int8 GEMM with a
+ * rigorous error bound finds the 128 x 128 tiles of logits that lie so far below their rows' maxima that every
+ * softmax weight in them is exactly 0.0f, and the exact GEMM leaves those tiles out.  Results are identical bit for
+ * bit.  mode 0: off; 1 (default): a verify call is screened when the draft call before it found its rows'
+ * posteriors collapsed; 2: every verify call is screened.  Needs the second GEMM's skipping
+ * (asd_use_sparse_combine) switched on, d a multiple of 128 (at most 2048) and C a multiple of 128; otherwise it
+ * stays off.
+ * asd_logit_screen_active: the mode in force (0 when the shape or the other switches rule it out). */
+ASD_API asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode);
+ASD_API int32_t asd_logit_screen_active(const asd_ctx* ctx);
+
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
 ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,
@@ -55,6 +66,7 @@ typedef enum {
   ASD_PROF_MLP_GEMM_OUT = 9, /* MLP output layer                              */
   ASD_PROF_DRAFT = 10,       /* fused draft kernel                            */
   ASD_PROF_ACCEPT = 11,      /* fused accept / scan / resample kernel         */
+  ASD_PROF_GMM_SCREEN = 12,  /* GMM screening pass of the verify call's logits */
   ASD_PROF_KINDS = 16
 } asd_prof_kernel;
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
@@ -64,6 +76,13 @@ ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* 
  * slots at a time and stops at the group that holds the first rejection) and rows it resampled (one per
  * chain-round that ended in a rejection). */
 ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t* resampled_rows);
+/* Matrix work the mixture denoiser's verify calls left out since then (split-operand kernels only; all zero
+ * otherwise).  logit_tiles_done / logit_tiles: 128 x 128 tiles of logits the first GEMM computed and how many there
+ * were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
+ * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
+ * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine). */
+ASD_API asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
+                                          int64_t* combine_slabs_done, int64_t* combine_slabs);
 
 #ifdef __cplusplus
 }

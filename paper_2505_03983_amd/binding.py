@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 ASD_OK, ASD_EINVAL, ASD_ENOMEM, ASD_EDEVICE, ASD_ESTATE, ASD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ASD_DEN_GMM, ASD_DEN_MLP = 1, 2
 PROF = dict(MODEL=0, PLAN=1, GMM_ROWWISE=2, GMM_LOGITS=3, GMM_SOFTMAX=4, GMM_COMBINE=5, MLP_PACK=6, MLP_GEMM_IN=7,
-            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11)
+            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11, GMM_SCREEN=12)
 
 
 class AsdError(RuntimeError):
@@ -70,6 +70,9 @@ def lib():
             "asd_use_resident": (i32, [vp, i32]),
             "asd_use_call_reuse": (i32, [vp, i32]),
             "asd_use_sparse_combine": (i32, [vp, i32]),
+            "asd_use_logit_screen": (i32, [vp, i32]),
+            "asd_logit_screen_active": (i32, [vp]),
+            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_use_split_gemm": (i32, [vp, i32]),
@@ -247,6 +250,12 @@ class Ctx:
     def use_sparse_combine(self, on=True):
         _check(lib().asd_use_sparse_combine(self.h, int(bool(on))))
 
+    def use_logit_screen(self, mode=1):
+        _check(lib().asd_use_logit_screen(self.h, int(mode)))
+
+    def logit_screen_active(self):
+        return int(lib().asd_logit_screen_active(self.h))
+
     def use_resident(self, on=True):
         _check(lib().asd_use_resident(self.h, int(bool(on))))
 
@@ -295,6 +304,12 @@ class Ctx:
         a, b = C.c_int64(0), C.c_int64(0)
         _check(lib().asd_profile_rows(self.h, C.addressof(a), C.addressof(b)))
         return a.value, b.value
+
+    def profile_model_work(self):
+        """(logit tiles computed, logit tiles, combine slabs visited, combine slabs) of the verify calls."""
+        v = [C.c_int64(0) for _ in range(4)]
+        _check(lib().asd_profile_model_work(self.h, *[C.addressof(x) for x in v]))
+        return tuple(x.value for x in v)
 
     def profile_accept_rows(self):
         a, b = C.c_int64(0), C.c_int64(0)

@@ -519,6 +519,24 @@ asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on) {
   return ASD_OK;
 }
 
+asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  if (mode < 0 || mode > 2) return fail(ASD_EINVAL, "asd_use_logit_screen: mode is 0 (off), 1 (when it pays) or 2 (always)");
+  if (ctx->gmm && ctx->gmm->screen_mode != mode) {
+    ctx->gmm->screen_mode = mode;
+    if (ctx->gexec) {   // the captured round holds the other launches
+      (void)hipGraphExecDestroy(ctx->gexec);
+      ctx->gexec = nullptr;
+    }
+  }
+  return ASD_OK;
+}
+
+int32_t asd_logit_screen_active(const asd_ctx* ctx) {
+  const asd::GmmState* g = ctx ? ctx->gmm : nullptr;
+  return (g && g->use_split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine) ? g->screen_mode : 0;
+}
+
 int32_t asd_split_gemm_active(const asd_ctx* ctx) { return (ctx && ctx->gmm && ctx->gmm->use_split) ? 1 : 0; }
 
 int32_t asd_resident_active(const asd_ctx* ctx) {
@@ -548,6 +566,7 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ctx->prof.reset();
   ctx->prof.on = on != 0;
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
+  if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 4 * sizeof(unsigned long long)));
   return ASD_OK;
 }
 
@@ -584,6 +603,17 @@ asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t
   ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
   if (examined_rows) *examined_rows = h[2];
   if (resampled_rows) *resampled_rows = h[3];
+  return ASD_OK;
+}
+
+asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
+                                  int64_t* combine_slabs_done, int64_t* combine_slabs) {
+  ASD_TRY(check_ctx(ctx));
+  unsigned long long h[4] = {0, 0, 0, 0};
+  if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemcpy(h, ctx->gmm->work_counts, sizeof(h), hipMemcpyDeviceToHost));
+  int64_t* out[4] = {logit_tiles_done, logit_tiles, combine_slabs_done, combine_slabs};
+  for (int i = 0; i < 4; ++i)
+    if (out[i]) *out[i] = (int64_t)h[i];
   return ASD_OK;
 }
 

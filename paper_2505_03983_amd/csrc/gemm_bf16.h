@@ -9,6 +9,8 @@ namespace asd {
 
 typedef float v16f_b __attribute__((ext_vector_type(16)));   // accumulator of v_mfma_f32_32x32x16_bf16
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));      // its A / B operand: 8 consecutive k of a row
+typedef int v16i_b __attribute__((ext_vector_type(16)));      // accumulator of v_mfma_i32_32x32x32_i8
+typedef int v4i_b __attribute__((ext_vector_type(4)));        // its A / B operand: 16 consecutive k of a row, one byte each
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;

@@ -140,7 +140,8 @@ inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K
 }
 
 // The Op interface is that of gemm_f32.h (init / load_a / finish / epilogue); load_a is applied when
-// the values are split, not when they are loaded.
+// the values are split, not when they are loaded.  An Op with kTileSkip may declare a whole output tile
+// unwanted (tile_dead, from data in device memory): the workgroup then only runs the Op's mark_dead.
 //
 // Tile order.  Workgroups go to the 8 XCDs round-robin by linear id (x fastest).  ROWS_PER_XCD = false: blockIdx.x
 // = column tile, so an XCD keeps a fixed set of column tiles (its share of B stays in its L2) and every XCD
@@ -172,6 +173,12 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   if (m0 >= M) return;
+  if constexpr (Op::kTileSkip) {
+    if (op.tile_dead(tile_m, tile_n, (int)gridDim.x)) {   // the same for the whole workgroup
+      op.template mark_dead<Cfg>(m0, M, tile_n, (int)threadIdx.x);
+      return;
+    }
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -222,6 +229,7 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
       listed = nk < nk_all;   // everything live: walk the slabs in order, without the list
     }
   }
+  if constexpr (Op::kSparseK) op.note_slabs(nk, nk_all / splits, tid);
   const uint8_t* bsrc = Bimg + ((int64_t)tile_n * nk_all + kb) * B_STAGE + tid * 16;
   // slab visited in step kt of the K loop, relative to kb (a list is only built when kb = 0)
   auto slab_of = [&](int kt) -> int64_t {
@@ -361,6 +369,14 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
+// Whether a launch with `sparse` set walks a slab list (else it stays dense): the list must fit beside the stages.
+template <class Cfg>
+inline bool split3_sparse_fits(int K, int groups, int group_cols) {
+  if (group_cols <= 0 || group_cols % Cfg::BK != 0 || K % group_cols != 0 || K / Cfg::BK > 65535) return false;
+  const size_t lds = Cfg::LDS_BYTES + (size_t)((2 * (K / Cfg::BK) + 15) & ~15) + (size_t)((groups + 15) & ~15) + 16;
+  return lds <= 80 * 1024;   // two workgroups per CU
+}
+
 // splits > 1 (Ops with kSplitK, not with ROWS_PER_XCD): `part` = gemm_f32_splitk_floats(splits, M_max, N) floats.
 // sparse: let an Op with kSparseK skip the slabs of K it marks dead (needs K / BK <= 65535, the Op's column groups a
 // multiple of BK wide and K a multiple of them; otherwise the loop stays dense).
@@ -370,14 +386,9 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
   if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
   size_t lds = Cfg::LDS_BYTES;
   if constexpr (Op::kSparseK) {
-    const int gc = op.group_cols();
-    sparse = sparse && splits == 1 && gc > 0 && gc % Cfg::BK == 0 && K % gc == 0 && K / Cfg::BK <= 65535;
+    sparse = sparse && splits == 1 && split3_sparse_fits<Cfg>(K, op.groups(), op.group_cols());
     // list of slabs (2 bytes each), a flag byte per column group, the count
     if (sparse) lds += (size_t)((2 * (K / Cfg::BK) + 15) & ~15) + (size_t)((op.groups() + 15) & ~15) + 16;
-    if (lds > 80 * 1024) {   // two workgroups per CU must still fit
-      sparse = false;
-      lds = Cfg::LDS_BYTES;
-    }
   } else {
     sparse = false;
   }

@@ -20,6 +20,8 @@
 //    then P M (second MFMA GEMM against the pre-transposed means) with the
 //    final affine combination fused in the epilogue.
 #include "common.h"
+#include "device_util.h"
+#include "gemm_bf16_pipe.h"
 #include "gemm_f32.h"
 #include "gemm_split3.h"
 #include "gmm_state.h"
@@ -232,6 +234,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
 struct LogitOp {
   static constexpr bool kSplitK = false;
   static constexpr bool kSparseK = false;
+  static constexpr bool kTileSkip = true;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -240,6 +243,20 @@ struct LogitOp {
   const int32_t* tau;
   const float* musq;
   const float* log_w;
+  // NULL, or [row tiles][column tiles] from the screening pass below: 0 = every logit of the tile lies more than
+  // CombineOp::kZeroGap below the maximum of its row.  Such a tile is not computed: its partial maxima are set to
+  // -inf, which the second GEMM reads as "all weights zero, skip" -- the logits themselves are never read again.
+  const uint8_t* live = nullptr;
+  __device__ __forceinline__ bool tile_dead(int tile_m, int tile_n, int ntn) const {
+    return live && live[(int64_t)tile_m * ntn + tile_n] == 0;
+  }
+  template <class Cfg>
+  __device__ __forceinline__ void mark_dead(int m0, int M, int tile_n, int tid) const {
+    for (int t = tid; t < Cfg::BM * Cfg::WGN; t += Cfg::THREADS) {
+      const int m = m0 + t / Cfg::WGN;
+      if (m < M) pmax[(int64_t)m * np + Cfg::WGN * tile_n + t % Cfg::WGN] = -INFINITY;
+    }
+  }
   static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
   // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
@@ -307,6 +324,7 @@ struct LogitOp {
 struct CombineOp {
   static constexpr bool kSplitK = true;
   static constexpr bool kSparseK = true;
+  static constexpr bool kTileSkip = false;
   const float* pmax;
   int np;
   int gcols;  // logits columns behind one partial maximum (sub-tile width of the first GEMM), 0: unknown
@@ -332,6 +350,13 @@ struct CombineOp {
   const int64_t* out_off;
   const float4* coef_tau;
   const int32_t* tau;
+  unsigned long long* work = nullptr;   // NULL, or DEV [2]: += K slabs this workgroup visits, += K slabs there are
+  __device__ __forceinline__ void note_slabs(int visited, int all, int tid) const {
+    if (work && tid == 0) {
+      atomicAdd(&work[0], (unsigned long long)visited);
+      atomicAdd(&work[1], (unsigned long long)all);
+    }
+  }
   static constexpr int kMaxPasses = 8;
   float rmax[kMaxPasses];
   float rsum[kMaxPasses];
@@ -433,6 +458,271 @@ struct CombineOp {
     }
   }
 };
+
+// ---------------------------------------------------------------------------
+// Screening of the verify call's logits.
+//
+// Once the noise is low a posterior sits on one or two components: every other softmax weight is exactly 0.0f
+// in fp32 (2^-150 underflows), and the 6-product logits GEMM spends its time on numbers that only have to be
+// "far below the row maximum".  An int8 GEMM (a twelfth of the matrix time, exact int32 sums) says which tiles
+// those are, rigorously.  Rows and means are quantised with one scale each,  x ~ sx qx,  mu ~ sm qm  (q = the
+// nearest integer in [-127, 127], s = max |.| / 127), so
+//   |sx sm <qx, qm> - <x, mu>|  <=  (sm / 2) |x|_1 + (sx / 2) |mu^|_1,      mu^ = sm qm,
+// from  x_k mu_k - x^_k mu^_k = x_k (mu_k - mu^_k) + mu^_k (x_k - x^_k).  With the same affine map as the exact
+// GEMM,  s = kappa' sx sm <qx, qm> - gamma' |mu|^2 + log2 w,  every exact logit of a column group lies within
+// e = kappa' (that bound, with the group's largest sm and |mu^|_1) + a rounding allowance of its screened value,
+// so the group's logits are all below s_max + e and the one at s_max is above s_max - e.  A 128 x 128 tile is dead
+// when, for each of its rows, the upper bound of its columns is more than kZeroGap below the largest lower bound
+// of the row.  Dead tiles are skipped by the exact GEMM (LogitOp::live) and, through their -inf partial maxima,
+// by the second GEMM; the result is bit-identical to computing everything, because the skipped weights are exact
+// zeros there too.  (kScreenFp32 covers what the exact GEMM's own fp32 sums may be off by: below 2^-13 sum |x_k
+// mu_k| <= 2^-13 127 sm |x|_1 for d <= 2048, i.e. 3% of the first term.)
+//
+// The pass costs a fraction of the exact GEMM but is pure overhead while the posteriors are broad, so it only
+// runs when it is likely to pay: the draft call of the same round (one row per chain, the noisiest row of each
+// window) counts the column groups its rows keep alive, and the verify call is screened when that is less than
+// a quarter of them.
+// ---------------------------------------------------------------------------
+#ifndef ASD_SCREEN_TILE
+#define ASD_SCREEN_TILE 256, 128, 3, 4, 2
+#endif
+typedef PipeCfg16<ASD_SCREEN_TILE, 1, true> ScreenTile;
+static_assert(GmmTileSplit::BN % ScreenTile::WN == 0, "whole sub-tiles of screened maxima per tile of the exact GEMM");
+constexpr float kScreenFp32 = 1.05f;    // see above
+constexpr float kScreenRound = 1.001f;  // the quantiser divides in fp32: a value may land 127 * 2^-23 steps off the nearest
+constexpr float kScreenDense = 0.25f;   // screen when the draft rows keep less than this share of their groups alive
+
+__device__ __forceinline__ int quant8(float v, float inv_s) { return max(-127, min(127, (int)rintf(v * inv_s))); }
+
+// means -> int8, one wavefront per component: qm [C, d], sm [C], l1 [C] = |mu^|_1
+__global__ __launch_bounds__(256) void gmm_screen_quant_means_kernel(int C, int d, const float* __restrict__ means,
+                                                                     int8_t* __restrict__ qm, float* __restrict__ sm,
+                                                                     float* __restrict__ l1) {
+  const int lane = threadIdx.x & 63, k = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (k >= C) return;
+  const float* mu = means + (int64_t)k * d;
+  float mx = 0.f;
+  for (int j = lane; j < d; j += 64) mx = fmaxf(mx, fabsf(mu[j]));
+  mx = wave_max(mx);
+  const float s = mx > 0.f ? mx / 127.f : 1.f, inv = 1.f / s;
+  float a = 0.f;
+  for (int j = lane; j < d; j += 64) {
+    const int q = quant8(mu[j], inv);
+    qm[(int64_t)k * d + j] = (int8_t)q;
+    a += fabsf((float)q);
+  }
+  a = wave_sum(a);   // an integer below 2^24: exact
+  if (lane == 0) {
+    sm[k] = s;
+    l1[k] = s * a * (1.f + 1e-6f);
+  }
+}
+// largest sm and |mu^|_1 of each group of `gc` components
+__global__ void gmm_screen_group_kernel(int C, int gc, const float* __restrict__ sm, const float* __restrict__ l1,
+                                        float2* __restrict__ grp) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g * gc >= C) return;
+  float a = 0.f, b = 0.f;
+  for (int k = g * gc; k < min(C, (g + 1) * gc); ++k) {
+    a = fmaxf(a, sm[k]);
+    b = fmaxf(b, l1[k]);
+  }
+  grp[g] = make_float2(a, b);
+}
+
+// rows of the plan -> int8 [n, d], their scales and 1-norms; one wavefront per row (d <= 2048: a row in registers)
+__global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restrict__ n_dev, int n_max, int d,
+                                                              const float* __restrict__ in_base,
+                                                              const int64_t* __restrict__ in_off,
+                                                              const int32_t* __restrict__ on,
+                                                              int8_t* __restrict__ xq, float2* __restrict__ xs) {
+  if (*on == 0) return;
+  const int n = min(*n_dev, n_max);
+  const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= n) return;
+  const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
+  constexpr int kMaxV = 2048 / 4 / 64;
+  float4 v[kMaxV];
+  float mx = 0.f, a = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMaxV; ++i) {
+    const int j = lane + 64 * i;
+    v[i] = j < d / 4 ? x[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+    mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v[i].x), fabsf(v[i].y))), fmaxf(fabsf(v[i].z), fabsf(v[i].w)));
+    a += (fabsf(v[i].x) + fabsf(v[i].y)) + (fabsf(v[i].z) + fabsf(v[i].w));
+  }
+  mx = wave_max(mx);
+  a = wave_sum(a);
+  const float s = mx > 0.f ? mx / 127.f : 1.f, inv = 1.f / s;
+  uint32_t* o = reinterpret_cast<uint32_t*>(xq + (int64_t)m * d);
+#pragma unroll
+  for (int i = 0; i < kMaxV; ++i) {
+    const int j = lane + 64 * i;
+    if (j < d / 4)
+      o[j] = (uint32_t)(quant8(v[i].x, inv) & 0xff) | ((uint32_t)(quant8(v[i].y, inv) & 0xff) << 8) |
+             ((uint32_t)(quant8(v[i].z, inv) & 0xff) << 16) | ((uint32_t)(quant8(v[i].w, inv) & 0xff) << 24);
+  }
+  if (lane == 0) xs[m] = make_float2(s, a * (1.f + 1e-5f));   // (the 1-norm's own fp32 rounding)
+}
+
+// Epilogue of the screening GEMM: the integer sums back to the scale of <x, mu>, the affine map of LogitOp, then
+// the maximum of each row over the columns of the wavefront's sub-tile -> smax[row][sub-tile].  Nothing else is stored.
+struct ScreenEpi {
+  static constexpr bool kLoads = false, kRowMax = true;
+  float* smax;
+  int nps;  // sub-tiles (ScreenTile::WN columns) per row
+  const float4* coef_tau;
+  const int32_t* tau;
+  const float* musq;
+  const float* log_w;
+  const float2* xs;    // per row: scale, 1-norm
+  const float* sm;     // per component: scale
+  const int32_t* on;   // DEV: 0 = this call is not screened
+  __device__ __forceinline__ bool off() const { return *on == 0; }
+  template <class Cfg>
+  __device__ __forceinline__ void row_max(const v16i_b (&acc)[Cfg::MI][Cfg::NJ], int m0, int n0, int M, int N, int wm,
+                                          int wn, int l32, int half) const {
+    constexpr int MI = Cfg::MI, NJ = Cfg::NJ;
+    float bias[NJ], q[NJ], sc[NJ];
+    bool nok[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int nn = n0 + wn * Cfg::WN + j * 32 + l32;
+      nok[j] = nn < N;
+      const int n = nok[j] ? nn : N - 1;
+      bias[j] = LogitOp::kLog2e * log_w[n];
+      q[j] = musq[n];
+      sc[j] = sm[n];
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * Cfg::WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const int mc = min(m, M - 1);
+        const float4 cf = coef_tau[tau[mc]];
+        const float c1 = LogitOp::kLog2e * cf.x * xs[mc].x, c2 = LogitOp::kLog2e * cf.y;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const float v = fmaf(c1, sc[j] * (float)acc[i][j][r], fmaf(-c2, q[j], bias[j]));
+          if (nok[j]) mx = fmaxf(mx, v);
+        }
+        // over the 32 lanes of the half-wave (see LogitOp::epilogue)
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xf, 0xf, true)));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        if (m < M && l32 == 0) smax[(int64_t)m * nps + (n0 + wn * Cfg::WN) / Cfg::WN] = mx;
+      }
+    }
+  }
+};
+
+// One workgroup per row tile of the exact GEMM: bounds from smax and the quantisers' figures -> live[row tile][column tile].
+// spt: sub-tiles of smax per column tile.  counts (or NULL): += tiles the exact GEMM will compute, += tiles.
+__global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __restrict__ n_dev, int n_max, int nps, int ntn,
+                                                                int spt, const float* __restrict__ smax,
+                                                                const float2* __restrict__ xs,
+                                                                const float2* __restrict__ grp,
+                                                                const float4* __restrict__ coef_tau,
+                                                                const int32_t* __restrict__ tau,
+                                                                const int32_t* __restrict__ on,
+                                                                uint8_t* __restrict__ live,
+                                                                unsigned long long* __restrict__ counts) {
+  extern __shared__ int s_flag[];   // [ntn]
+  constexpr int BM = GmmTileSplit::BM, RW = 4;   // rows a wavefront works on at a time (their loads overlap)
+  const int n = min(*n_dev, n_max);
+  const int m0 = blockIdx.x * BM;
+  if (m0 >= n) return;
+  uint8_t* out = live + (int64_t)blockIdx.x * ntn;
+  if (*on == 0) {   // not screened: everything is computed
+    for (int t = threadIdx.x; t < ntn; t += 256) out[t] = 1;
+    if (counts && threadIdx.x == 0) {
+      atomicAdd(&counts[0], (unsigned long long)ntn);
+      atomicAdd(&counts[1], (unsigned long long)ntn);
+    }
+    return;
+  }
+  for (int t = threadIdx.x; t < ntn; t += 256) s_flag[t] = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // how far an exact logit may lie from its screened value s: the quantisation (ea sm + eb |mu^|_1 of the group)
+  // and an allowance for the roundings of the affine map, which the two GEMMs apply to different sums
+  auto slack = [](float s, float ea, float eb, float2 g) { return fmaf(ea, g.x, fmaf(eb, g.y, 0.5f)) + 1e-6f * fabsf(s); };
+  for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
+    float ea[RW], eb[RW], lo[RW];
+    const float* s[RW];
+#pragma unroll
+    for (int k = 0; k < RW; ++k) {   // rows past the end repeat the last one: the same flags again
+      const int m = min(m0 + r0 + k, n - 1);
+      s[k] = smax + (int64_t)m * nps;
+      const float c1 = 0.5f * kScreenRound * LogitOp::kLog2e * coef_tau[tau[m]].x;
+      ea[k] = c1 * kScreenFp32 * xs[m].y;
+      eb[k] = c1 * xs[m].x;
+      lo[k] = -INFINITY;
+    }
+    for (int p = lane; p < nps; p += 64) {
+      const float2 g = grp[p];
+#pragma unroll
+      for (int k = 0; k < RW; ++k) lo[k] = fmaxf(lo[k], s[k][p] - slack(s[k][p], ea[k], eb[k], g));
+    }
+#pragma unroll
+    for (int k = 0; k < RW; ++k) lo[k] = wave_max(lo[k]) - CombineOp::kZeroGap;
+    for (int p = lane; p < nps; p += 64) {
+      const float2 g = grp[p];
+      bool any = false;
+#pragma unroll
+      for (int k = 0; k < RW; ++k) any = any || (s[k][p] + slack(s[k][p], ea[k], eb[k], g) >= lo[k]);
+      if (any) s_flag[p / spt] = 1;
+    }
+  }
+  __syncthreads();
+  int mine = 0;
+  for (int t = threadIdx.x; t < ntn; t += 256) {
+    out[t] = (uint8_t)s_flag[t];
+    mine += s_flag[t];
+  }
+  if (counts) {
+    const int total = (int)wave_sum((float)mine);   // this wavefront's share; at most a few thousand: exact in fp32
+    if (lane == 0 && total) atomicAdd(&counts[0], (unsigned long long)total);
+    if (threadIdx.x == 0) atomicAdd(&counts[1], (unsigned long long)ntn);
+  }
+}
+
+// After the draft call's logits: the share of column groups its rows keep alive -> on[0].  One wavefront per row;
+// acc[0] collects the count, acc[1] the workgroups that are done: the last one decides and clears both.
+constexpr int kRegimeBlocks = 64;
+__global__ __launch_bounds__(256) void gmm_regime_kernel(const int* __restrict__ n_dev, int n_max, int np,
+                                                         const float* __restrict__ pmax, int32_t* __restrict__ on,
+                                                         int32_t* __restrict__ acc) {
+  const int n = min(*n_dev, n_max);
+  if (n <= 0) return;   // every workgroup alike: nothing is counted, the verdict stands
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float alive = 0.f;
+  for (int m = blockIdx.x * 4 + wave; m < n; m += 4 * gridDim.x) {
+    const float* p = pmax + (int64_t)m * np;
+    float mx = -INFINITY;
+    for (int q = lane; q < np; q += 64) mx = fmaxf(mx, p[q]);
+    mx = wave_max(mx) - CombineOp::kZeroGap;
+    float c = 0.f;
+    for (int q = lane; q < np; q += 64) c += p[q] >= mx ? 1.f : 0.f;
+    alive += wave_sum(c);
+  }
+  if (lane == 0 && alive > 0.f) atomicAdd(&acc[0], (int32_t)alive);
+  __syncthreads();   // the four additions above come before this workgroup's ticket
+  if (threadIdx.x == 0) {
+    __threadfence();
+    if (atomicAdd(&acc[1], 1) == (int32_t)gridDim.x - 1) {
+      __threadfence();
+      const int32_t tot = atomicAdd(&acc[0], 0);
+      on[0] = (float)tot < kScreenDense * (float)n * (float)np ? 1 : 0;
+      acc[0] = 0;
+      acc[1] = 0;
+    }
+  }
+}
 
 // Finish of a split-K second GEMM: one workgroup per row adds the partial tiles and row sums in split order and
 // applies  out = c_x' x + c_m' acc / sum.
@@ -539,6 +829,32 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     }
     ASD_HIP(hipDeviceSynchronize());
     g->split_ok = g->use_split = true;
+    ASD_HIP(hipMalloc(&g->work_counts, 4 * sizeof(unsigned long long)));
+    ASD_HIP(hipMemset(g->work_counts, 0, 4 * sizeof(unsigned long long)));
+    // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
+    const int np_v = GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN);
+    if (d % 128 == 0 && C % ScreenTile::BN == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
+        split3_sparse_fits<GmmTileSplit>(C, np_v, GmmTileSplit::WN)) {
+      g->nps = C / ScreenTile::WN;
+      const int64_t row_tiles = ceil_div(ctx->n_rows_max, GmmTileSplit::BM);
+      ASD_HIP(hipMalloc(&g->means_q, (size_t)C * d));
+      ASD_HIP(hipMalloc(&g->means_s, sizeof(float) * 2 * (size_t)C));
+      ASD_HIP(hipMalloc(&g->means_grp, sizeof(float2) * (size_t)g->nps));
+      ASD_HIP(hipMalloc(&g->xq, (size_t)ctx->n_rows_max * d));
+      ASD_HIP(hipMalloc(&g->xs, sizeof(float2) * (size_t)ctx->n_rows_max));
+      ASD_HIP(hipMalloc(&g->smax, sizeof(float) * (size_t)ctx->n_rows_max * g->nps));
+      ASD_HIP(hipMalloc(&g->tile_live, (size_t)row_tiles * (C / GmmTileSplit::BN)));
+      ASD_HIP(hipMalloc(&g->screen_on, 4 * sizeof(int32_t)));
+      const int32_t on[4] = {1, 1, 0, 0};   // verdict, the constant 1, the regime kernel's two accumulators
+      ASD_HIP(hipMemcpy(g->screen_on, on, sizeof(on), hipMemcpyHostToDevice));
+      hipLaunchKernelGGL(gmm_screen_quant_means_kernel, dim3((unsigned)ceil_div(C, 4)), dim3(256), 0, 0, C, d, g->means,
+                         g->means_q, g->means_s, g->means_s + C);
+      hipLaunchKernelGGL(gmm_screen_group_kernel, dim3((unsigned)ceil_div(g->nps, 256)), dim3(256), 0, 0, C,
+                         ScreenTile::WN, g->means_s, g->means_s + C, g->means_grp);
+      ASD_HIP(hipGetLastError());
+      ASD_HIP(hipDeviceSynchronize());
+      g->screen_ok = true;
+    }
   }
   if (g->use_mfma) {
     g->np = 2 * (int)ceil_div(C, GmmTileSkinny::BN);  // room for the finest of the tilings
@@ -573,6 +889,15 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->part);
   (void)hipFree(g->logits);
   (void)hipFree(g->pmax);
+  (void)hipFree(g->means_q);
+  (void)hipFree(g->means_s);
+  (void)hipFree(g->means_grp);
+  (void)hipFree(g->xq);
+  (void)hipFree(g->xs);
+  (void)hipFree(g->smax);
+  (void)hipFree(g->tile_live);
+  (void)hipFree(g->screen_on);
+  (void)hipFree(g->work_counts);
   delete g;
   ctx->gmm = nullptr;
 }
@@ -610,6 +935,27 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const int splits = (!rows.call && g->draft_splits > 1 && n <= ctx->B) ? g->draft_splits : 1;
   RowSrc X{rows.in_base, rows.in_off, 0};
   LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
+  // the verify call of the split path may be screened; only when the second GEMM skips what the first leaves out
+  const bool screen = split && rows.call == 1 && g->screen_ok && g->screen_mode != 0 && g->sparse_combine;
+  if (screen) {
+    ProfScope ps(ctx, ASD_PROF_GMM_SCREEN, rows.call, st);
+    const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
+    const int ntn = C / GmmTileSplit::BN;
+    hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
+                       rows.in_base, rows.in_off, on, g->xq, g->xs);
+    ASD_HIP(hipGetLastError());
+    ScreenEpi epi{g->smax, g->nps, g->coef_tau, rows.tau, g->musq, g->log_w, g->xs, g->means_s, on};
+    // int8 operands, handed over as 16-bit units (two k each)
+    ASD_HIP(launch_gemm_bf16_nt_pipe<ScreenTile, 1>(rows.n_dev, n, C, d / 2, reinterpret_cast<const uint16_t*>(g->xq),
+                                                    d / 2, 0, reinterpret_cast<const uint16_t*>(g->means_q), d / 2, epi,
+                                                    st));
+    hipLaunchKernelGGL(gmm_screen_decide_kernel, dim3((unsigned)ceil_div(n, GmmTileSplit::BM)), dim3(256),
+                       sizeof(int) * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / ScreenTile::WN, g->smax,
+                       g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_live,
+                       ctx->prof.on ? g->work_counts : nullptr);
+    ASD_HIP(hipGetLastError());
+    op1.live = g->tile_live;
+  }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
     if (split)
@@ -620,10 +966,16 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
       ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
   }
+  if (rows.call == 0 && g->screen_ok && g->screen_mode == 1) {   // this round's verify call: screen or not
+    hipLaunchKernelGGL(gmm_regime_kernel, dim3(kRegimeBlocks), dim3(256), 0, st, rows.n_dev, n, np, g->pmax,
+                       g->screen_on, g->screen_on + 2);
+    ASD_HIP(hipGetLastError());
+  }
   RowSrc P{g->logits, nullptr, C};
   // columns behind one partial row maximum: the first GEMM's wavefront sub-tile width (the last group may be short)
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
-  CombineOp op2{g->pmax, np, gcols, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau, {}, {}};
+  CombineOp op2{g->pmax, np, gcols, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau,
+                (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
     if (split)

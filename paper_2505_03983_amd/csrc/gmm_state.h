@@ -28,7 +28,23 @@ struct GmmState {
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
+  // DEV [4], summed over the verify calls while profiling: tiles of logits computed / there were (screened path
+  // only), K slabs the second GEMM's workgroups visited / there were
+  unsigned long long* work_counts = nullptr;
   bool sparse_combine = true;      // the second split GEMM of the verify call skips slabs of exact zeros (gemm_split3.h)
+  // Screening of the verify call's logits GEMM (gmm.hip): an int8 GEMM finds the tiles whose softmax weights are
+  // all exactly zero; the exact GEMM skips them.
+  bool screen_ok = false;          // the shape allows it (and the buffers below exist)
+  int screen_mode = 1;             // 0: off, 1: when the draft call of the round found its posteriors collapsed, 2: always
+  int8_t* means_q = nullptr;       // [C, d] quantised means
+  float* means_s = nullptr;        // [2 C]: their scales, then the 1-norms of the quantised means
+  float2* means_grp = nullptr;     // [nps] largest of either over each sub-tile of columns
+  int8_t* xq = nullptr;            // [rows_max, d] the call's rows, quantised
+  float2* xs = nullptr;            // [rows_max]: scale, 1-norm
+  float* smax = nullptr;           // [rows_max, nps] screened row maxima per sub-tile
+  int nps = 0;
+  uint8_t* tile_live = nullptr;    // [row tiles][column tiles]
+  int32_t* screen_on = nullptr;    // DEV [4]: the draft call's verdict for this round; the constant 1; two accumulators
   size_t rowwise_lds = 0;
   size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
 };

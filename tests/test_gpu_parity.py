@@ -298,6 +298,70 @@ def test_sparse_combine_is_bit_identical_to_the_dense_loop():
         ctx.close()
 
 
+def test_logit_screen_is_bit_identical_and_skips_work():
+    """The screening pass in front of the verify call's first GEMM (a one-product bf16 GEMM with a rigorous error
+    bound) lets the exact GEMM leave out the tiles whose softmax weights are all exactly 0.0f.  (a) Rows at all noise
+    levels through the model call alone, ragged row tile, every row of a tile near the same component so that
+    tiles do die: always screened == never screened, bit for bit, tiles are left out, and the oracle agrees.
+    (b) Whole samples (draft verdict -> screened or not, graphs on): the three modes give the same trajectories and
+    round counts bit for bit."""
+    cfg = dict(kind="gmm", d=128, C=1024, K=200, chains=72, L=16, var=0.25)
+    T, p, model = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=0)
+    assert ctx.split_gemm_active() and ctx.logit_screen_active() == 1
+    rng = np.random.default_rng(11)
+    n_rows = 1000                                                     # 7 full row tiles and one of 104 rows
+    tau = np.sort(rng.integers(1, cfg["K"] + 1, n_rows)).astype(np.int32)
+    comp = np.repeat(rng.integers(0, cfg["C"], (n_rows + 127) // 128), 128)[:n_rows]   # one component per row tile
+    ab = T["abar"][tau]
+    x0 = p["means"][comp] + np.sqrt(p["var"]) * rng.standard_normal((n_rows, cfg["d"]))
+    x = (np.sqrt(ab)[:, None] * x0 + np.sqrt(1 - ab)[:, None] * rng.standard_normal((n_rows, cfg["d"]))).astype(np.float32)
+    xd, td = torch.from_numpy(x).to(DEV), torch.from_numpy(tau).to(DEV)
+    outs, work = [], []
+    ctx.profile_enable(True)
+    for mode in (2, 0, 2):
+        ctx.use_logit_screen(mode)
+        assert ctx.logit_screen_active() == mode
+        out = torch.zeros_like(xd)
+        ctx.denoise(xd, td, out)
+        torch.cuda.synchronize()
+        outs.append(out)
+        work.append(ctx.profile_model_work())
+        ctx.profile_enable(True)                                      # clears the counters
+    ctx.profile_enable(False)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    done, tiles = work[0][0], work[0][1]
+    assert tiles == 8 * (cfg["C"] // 128) and 8 <= done < tiles and work[1][:2] == (0, 0)
+    want = model(K_minus(tau, cfg["K"]), x.astype(np.float64))
+    e = H.rel_err(outs[0].cpu().numpy(), want)
+    _log("logit screen: %d of %d tiles computed, bit-identical to unscreened, rel err vs oracle" % (done, tiles), e)
+    assert e <= 1e-4
+    with pytest.raises(binding.AsdError):
+        ctx.use_logit_screen(3)
+    ctx.use_logit_screen(1)
+    ctx.use_sparse_combine(False)                                     # nothing would skip what the screen leaves out
+    assert ctx.logit_screen_active() == 0
+    out = torch.zeros_like(xd)
+    ctx.denoise(xd, td, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, outs[0])
+    ctx.use_sparse_combine(True)
+    # (b) whole samples
+    res = []
+    for mode in (0, 1, 2):
+        ctx.use_logit_screen(mode)
+        ctx.set_seed(5)
+        traj = runtime.alloc_traj(ctx)
+        rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+        ctx.sample(traj, rounds)
+        torch.cuda.synchronize()
+        res.append((traj, rounds))
+    for traj, rounds in res[1:]:
+        assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
+    assert bool(torch.isfinite(res[0][0]).all())
+    ctx.close()
+
+
 def test_mfma_ceiling_probe():
     """The probe of what the matrix pipes sustain: plausible, finite figures (no fixed expectation: the rate is set
     by the chip's power management), constant operands no slower than random ones."""
