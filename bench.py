@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
-PEAK = {"f32": 157.3, "bf16": 2500.0}          # dense MFMA TFLOP/s, MI355X
+PEAK = {"f32": 157.3, "bf16": 2500.0, "i8": 5000.0}          # dense MFMA TFLOP/s (int8: TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_gmm_verify_gemm_hbm_traffic.txt")
@@ -97,7 +97,8 @@ class ClockSampler:
                     mean=sum(self.samples) / len(self.samples), last=self.samples[-1])
 
 
-def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, clocks=False, act_terms=None):
+def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, clocks=False, act_terms=None,
+            screen=None):
     import torch
     import asd_workloads as W
     from paper_2505_03983_amd import binding, runtime
@@ -110,6 +111,9 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
     ctx.use_adaptive_window(adaptive)
     ctx.use_split_gemm(split)
     split_active = ctx.split_gemm_active()
+    if screen is not None:
+        ctx.use_logit_screen(screen)
+    screen_mode = ctx.logit_screen_active()
     traj = runtime.alloc_traj(ctx)
     rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device="cuda:0")
     for i in range(warmup):
@@ -142,7 +146,8 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
                rounds_launched=launched, finite=finite, path=path, split=split_active,
-               act_terms=params.get("act_terms"), sclk_mhz=sampler.summary() if sampler else None)
+               act_terms=params.get("act_terms"), sclk_mhz=sampler.summary() if sampler else None,
+               screen_mode=screen_mode)
     if profile:
         P = binding.PROF
         table = {}
@@ -155,6 +160,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
         out["kernels"] = table
         out["rows"] = ctx.profile_rows()
         out["accept_rows"] = ctx.profile_accept_rows()
+        out["model_work"] = ctx.profile_model_work()
         ctx.profile_enable(False)
     ctx.close()
     del traj
@@ -168,10 +174,14 @@ def roofline(res, w=None):
     Mixture denoiser: one GEMM of the model call does 2*C*d flop per row (the method's arithmetic, fp32).  The
     default kernels evaluate every fp32 product as six bf16 MFMA products, so they *execute* six times that on
     the bf16 pipe.  `achieved` / `peak` / `frac` are the executed bf16 work against the bf16 MFMA peak (how
-    busy the pipe in use is); `method` carries the 2*C*d figure and its ratio to the fp32 MFMA peak."""
+    busy the pipe in use is); `method` carries the 2*C*d figure and its ratio to the fp32 MFMA peak.
+    Both split-operand GEMMs leave out work whose result is known to be exact zeros (tiles of logits far below
+    their rows' maxima, found by the screening pass; slabs of components with zero weights): what they executed
+    is then counted by the device (128 x 128 tiles, slabs of 16 components per tile) and not inferred from rows."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
     executed_per_method = 1.0
+    executed_flops = None
     if cfg["kind"] == "gmm":
         cand = [n for n in ("GMM_LOGITS/verify", "GMM_COMBINE/verify", "GMM_ROWWISE/verify") if n in k]
         name = max(cand, key=lambda n: k[n]["total_ms"])
@@ -184,6 +194,11 @@ def roofline(res, w=None):
         if bound == "mfma" and res.get("split"):
             dtype = "bf16"
             executed_per_method = 6.0
+            done, tiles, slabs_done, slabs, _ = res.get("model_work", (0, 0, 0, 0, 0))
+            if name == "GMM_LOGITS/verify" and tiles:
+                executed_flops = 6.0 * 2.0 * 128 * 128 * cfg["d"] * done / launches
+            if name == "GMM_COMBINE/verify" and slabs:
+                executed_flops = 6.0 * 2.0 * 128 * 128 * 16 * slabs_done / launches
     else:
         name = "MLP_GEMM_BLK/verify"
         launches = k[name]["launches"]
@@ -195,23 +210,45 @@ def roofline(res, w=None):
     method_flops = per_row * verify_rows / launches
     avg_s = 1e-3 * k[name]["total_ms"] / launches
     method_tflops = method_flops / avg_s / 1e12
-    achieved = executed_per_method * method_tflops
+    if executed_flops is None:
+        executed_flops = executed_per_method * method_flops
+    achieved = executed_flops / avg_s / 1e12
     peak = PEAK[dtype]
     out = dict(bound=bound, kernel=name, achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
                frac_is="executed %s MFMA flop/s over the %s MFMA peak" % (dtype, dtype) if bound == "mfma"
                else "executed fp32 flop/s over the fp32 vector peak",
                traffic=traffic_bytes_per_launch(w, name, dtype), avg_launch_us=1e6 * avg_s, launches=launches,
-               executed_flops_per_launch=executed_per_method * method_flops, mfma_dtype=dtype,
+               executed_flops_per_launch=executed_flops, mfma_dtype=dtype,
                share_of_wall=1e-3 * k[name]["total_ms"] / res["wall_s"])
     if cfg["kind"] == "gmm":
         out["method"] = dict(flops_per_launch=method_flops, what="2*C*d per row (fp32 contraction of the model call)",
                              tflops=method_tflops, fp32_mfma_peak=PEAK["f32"],
                              ratio_to_fp32_mfma_peak=method_tflops / PEAK["f32"])
         out["executed_bf16_products_per_fp32_product"] = int(executed_per_method)
+        if executed_flops != executed_per_method * method_flops:
+            out["executed_share_of_dense"] = executed_flops / (executed_per_method * method_flops)
     else:
         out["method"] = dict(flops_per_launch=method_flops, what="2*width^2 per row and block",
                              tflops=method_tflops, bf16_terms_per_activation=int(executed_per_method))
     return out
+
+
+def logit_screen(res):
+    """The int8 screening pass of the mixture denoiser's verify calls: its cost, what it saved, and how busy it keeps
+    the int8 matrix pipe (2 * 128 * 128 * d operations per screened tile against the 5 POP/s data-sheet peak)."""
+    k = res["kernels"]
+    if not res.get("screen_mode") or "GMM_SCREEN/verify" not in k:
+        return dict(mode=res.get("screen_mode", 0))
+    done, tiles, _, _, screened = res["model_work"]
+    s = k["GMM_SCREEN/verify"]
+    ops = 2.0 * 128 * 128 * res["cfg"]["d"] * screened
+    return dict(mode=res["screen_mode"], launches=s["launches"], total_ms=s["total_ms"],
+                share_of_wall=1e-3 * s["total_ms"] / res["wall_s"],
+                logit_tiles=tiles, logit_tiles_of_screened_calls=screened, logit_tiles_computed=done,
+                computed_share=done / tiles if tiles else None,
+                int8_tops=ops / (1e-3 * s["total_ms"]) / 1e12 if screened else 0.0, int8_peak_tops=PEAK["i8"],
+                note="total_ms covers the quantiser, the int8 GEMM and the decision kernel; calls the draft call's "
+                     "verdict switched the screen off for still launch all three (they exit at once)")
 
 
 def hbm_kernels(res):
@@ -354,6 +391,8 @@ def main():
     ap.add_argument("--fp32-mfma", action="store_true",
                     help="Gaussian-mixture verify GEMMs on the fp32 matrix pipe instead of the bf16 pipe with "
                          "three-way split operands")
+    ap.add_argument("--no-screen", action="store_true",
+                    help="Gaussian-mixture verify calls without the int8 screening pass (every tile of logits computed)")
     ap.add_argument("--window-control", action="store_true",
                     help="time the sample with the per-chain window controller on (an extension of Alg. 1; the "
                          "default run keeps the configured fixed L and reports this mode in `window_control`)")
@@ -383,7 +422,8 @@ def main():
     # (the clock is polled through rocm-smi child processes; under a profiler, whose preloaded library has
     # initialised the GPU in this process, such children may not be started, and --plain is the profiler mode)
     res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma,
-                  clocks=not args.plain, adaptive=args.window_control, act_terms=args.act_terms)
+                  clocks=not args.plain, adaptive=args.window_control, act_terms=args.act_terms,
+                  screen=0 if args.no_screen else None)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -421,6 +461,8 @@ def main():
             rf0["peak_at_measured_clock"] = rf0["peak"] * res["sclk_mhz"]["mean"] / 2400.0
             rf0["frac_at_measured_clock"] = rf0["achieved"] / rf0["peak_at_measured_clock"]
         line["hbm_kernels"] = hbm_kernels(res)
+        if cfg["kind"] == "gmm" and res["split"]:
+            line["logit_screen"] = logit_screen(res)
         line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
                                "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
     if not args.plain and args.others:
@@ -440,6 +482,13 @@ def main():
     # The same workload with the window controller on (windows <= L chosen per chain from its past:
     # an extension of Alg. 1, exact in law; the headline `value` above keeps the configured fixed L).
     # (Skipped with --others 0, so that a profiler run of this script sees the fixed-L launches only.)
+    if args.others and res["split"] and res["screen_mode"]:
+        # the same sample with every tile of logits computed (asd_use_logit_screen off)
+        rn = run_gpu(args.workload, 1, 1, args.seed, profile=True, screen=0)
+        rfn = roofline(rn, args.workload)
+        line["unscreened"] = dict(steps_per_s=rn["steps_per_s"], ms_per_sample=rn["ms_per_sample"],
+                                  roofline_kernel=rfn["kernel"], achieved=rfn["achieved"], frac=rfn["frac"],
+                                  avg_launch_us=rfn["avg_launch_us"], share_of_wall=rfn["share_of_wall"])
     if args.others and res["split"]:
         # the same sample with the verify GEMMs on the fp32 matrix pipe (asd_use_split_gemm off)
         rp = run_gpu(args.workload, 1, 1, args.seed, profile=True, split=False, clocks=True)

@@ -80,9 +80,10 @@ ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows,
  * otherwise).  logit_tiles_done / logit_tiles: 128 x 128 tiles of logits the first GEMM computed and how many there
  * were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
  * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
- * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine). */
+ * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine).
+ * screened_tiles: the part of logit_tiles that belongs to calls the screening GEMM ran for. */
 ASD_API asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
-                                          int64_t* combine_slabs_done, int64_t* combine_slabs);
+                                          int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles);
 
 #ifdef __cplusplus
 }

@@ -72,7 +72,7 @@ def lib():
             "asd_use_sparse_combine": (i32, [vp, i32]),
             "asd_use_logit_screen": (i32, [vp, i32]),
             "asd_logit_screen_active": (i32, [vp]),
-            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp]),
+            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_use_split_gemm": (i32, [vp, i32]),
@@ -306,8 +306,9 @@ class Ctx:
         return a.value, b.value
 
     def profile_model_work(self):
-        """(logit tiles computed, logit tiles, combine slabs visited, combine slabs) of the verify calls."""
-        v = [C.c_int64(0) for _ in range(4)]
+        """(logit tiles computed, logit tiles, combine slabs visited, combine slabs, logit tiles of screened calls)
+        of the verify calls."""
+        v = [C.c_int64(0) for _ in range(5)]
         _check(lib().asd_profile_model_work(self.h, *[C.addressof(x) for x in v]))
         return tuple(x.value for x in v)
 

@@ -332,10 +332,21 @@ struct CombineOp {
   // than kZeroGap below the row maximum: load_a then gives 2^(l - max) = 0.0f for every element of the group
   // (2^-150 is below the smallest fp32 subnormal), so those products are exact zeros.
   static constexpr float kZeroGap = 150.0f;
+  // NULL, or what gmm_rowmax_kernel made of pmax once for all the column tiles of a row tile: the row maxima [rows]
+  // and the live flag of every column group [row tiles of kRowmaxTile rows][np]
+  const float* rmax_pre = nullptr;
+  const uint8_t* live_pre = nullptr;
+  static constexpr int kRowmaxTile = 128;
   __host__ __device__ __forceinline__ int groups() const { return np; }
   __host__ __device__ __forceinline__ int group_cols() const { return gcols; }
   template <class Cfg>
   __device__ __forceinline__ void mark_live(int m0, int M, int lrow, int lkq, uint8_t* flags) const {
+    if (live_pre) {
+      static_assert(Cfg::BM == kRowmaxTile || Cfg::BM * 2 == kRowmaxTile, "row tiles of the precomputed flags");
+      const uint8_t* src = live_pre + (int64_t)(m0 / kRowmaxTile) * np;   // (a half-height tile takes its parent's flags)
+      for (int q = lrow * Cfg::KQ + lkq; q < np; q += Cfg::THREADS) flags[q] = src[q];
+      return;
+    }
 #pragma unroll
     for (int p = 0; p < Cfg::RA; ++p) {
       const int m = min(m0 + lrow + Cfg::RPP * p, M - 1);
@@ -369,9 +380,13 @@ struct CombineOp {
       const int r = lrow + Cfg::RPP * p;
       const int m = min(m0 + r, M - 1);
       float mx = -INFINITY;
-      for (int q = lkq; q < np; q += Cfg::KQ) mx = fmaxf(mx, pmax[(int64_t)m * np + q]);
+      if (rmax_pre) {
+        mx = rmax_pre[m];
+      } else {
+        for (int q = lkq; q < np; q += Cfg::KQ) mx = fmaxf(mx, pmax[(int64_t)m * np + q]);
 #pragma unroll
-      for (int o = 1; o < Cfg::KQ; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // the KQ lanes of a row are adjacent
+        for (int o = 1; o < Cfg::KQ; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));  // the KQ lanes of a row are adjacent
+      }
       rmax[p] = mx;
       rsum[p] = 0.f;
       if (lkq == 0) {
@@ -459,6 +474,47 @@ struct CombineOp {
   }
 };
 
+// Between the two GEMMs of a verify call: the maximum of every row over its partial maxima, and for every row
+// tile the column groups that are live for one of its rows (CombineOp::mark_live's rule) -- once, instead of by
+// each of the second GEMM's workgroups that share the row tile (d / 128 of them, each scanning 32 KB).
+__global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__ n_dev, int n_max, int np,
+                                                         const float* __restrict__ pmax, float* __restrict__ rmax,
+                                                         uint8_t* __restrict__ glive) {
+  extern __shared__ int s_any[];   // [np]
+  constexpr int BM = CombineOp::kRowmaxTile, RW = 4;
+  const int n = min(*n_dev, n_max);
+  const int m0 = blockIdx.x * BM;
+  if (m0 >= n) return;
+  for (int q = threadIdx.x; q < np; q += 256) s_any[q] = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
+    const float* p[RW];
+    float mx[RW];
+#pragma unroll
+    for (int k = 0; k < RW; ++k) {   // rows past the end repeat the last one
+      p[k] = pmax + (int64_t)min(m0 + r0 + k, n - 1) * np;
+      mx[k] = -INFINITY;
+    }
+    for (int q = lane; q < np; q += 64)
+#pragma unroll
+      for (int k = 0; k < RW; ++k) mx[k] = fmaxf(mx[k], p[k][q]);
+#pragma unroll
+    for (int k = 0; k < RW; ++k) {
+      mx[k] = wave_max(mx[k]);
+      if (lane == 0 && m0 + r0 + k < n) rmax[m0 + r0 + k] = mx[k];
+    }
+    for (int q = lane; q < np; q += 64) {
+      bool any = false;
+#pragma unroll
+      for (int k = 0; k < RW; ++k) any = any || (p[k][q] >= mx[k] - CombineOp::kZeroGap);
+      if (any) s_any[q] = 1;
+    }
+  }
+  __syncthreads();
+  for (int q = threadIdx.x; q < np; q += 256) glive[(int64_t)blockIdx.x * np + q] = (uint8_t)s_any[q];
+}
+
 // ---------------------------------------------------------------------------
 // Screening of the verify call's logits.
 //
@@ -530,12 +586,15 @@ __global__ void gmm_screen_group_kernel(int C, int gc, const float* __restrict__
   grp[g] = make_float2(a, b);
 }
 
-// rows of the plan -> int8 [n, d], their scales and 1-norms; one wavefront per row (d <= 2048: a row in registers)
+// rows of the plan -> int8 [n, d]; per row (scale, 1-norm, kappa' scale, gamma'); one wavefront per row (d <= 2048: a
+// row in registers)
 __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restrict__ n_dev, int n_max, int d,
                                                               const float* __restrict__ in_base,
                                                               const int64_t* __restrict__ in_off,
+                                                              const int32_t* __restrict__ tau,
+                                                              const float4* __restrict__ coef_tau,
                                                               const int32_t* __restrict__ on,
-                                                              int8_t* __restrict__ xq, float2* __restrict__ xs) {
+                                                              int8_t* __restrict__ xq, float4* __restrict__ xs) {
   if (*on == 0) return;
   const int n = min(*n_dev, n_max);
   const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -562,7 +621,10 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
       o[j] = (uint32_t)(quant8(v[i].x, inv) & 0xff) | ((uint32_t)(quant8(v[i].y, inv) & 0xff) << 8) |
              ((uint32_t)(quant8(v[i].z, inv) & 0xff) << 16) | ((uint32_t)(quant8(v[i].w, inv) & 0xff) << 24);
   }
-  if (lane == 0) xs[m] = make_float2(s, a * (1.f + 1e-5f));   // (the 1-norm's own fp32 rounding)
+  if (lane == 0) {   // scale, 1-norm (with its own fp32 rounding), and the row's two factors of the affine map
+    const float4 cf = coef_tau[tau[m]];
+    xs[m] = make_float4(s, a * (1.f + 1e-5f), LogitOp::kLog2e * cf.x * s, LogitOp::kLog2e * cf.y);
+  }
 }
 
 // Epilogue of the screening GEMM: the integer sums back to the scale of <x, mu>, the affine map of LogitOp, then
@@ -571,11 +633,9 @@ struct ScreenEpi {
   static constexpr bool kLoads = false, kRowMax = true;
   float* smax;
   int nps;  // sub-tiles (ScreenTile::WN columns) per row
-  const float4* coef_tau;
-  const int32_t* tau;
   const float* musq;
   const float* log_w;
-  const float2* xs;    // per row: scale, 1-norm
+  const float4* xs;    // per row: scale, 1-norm, kappa' scale, gamma'
   const float* sm;     // per component: scale
   const int32_t* on;   // DEV: 0 = this call is not screened
   __device__ __forceinline__ bool off() const { return *on == 0; }
@@ -599,9 +659,8 @@ struct ScreenEpi {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wm * Cfg::WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const int mc = min(m, M - 1);
-        const float4 cf = coef_tau[tau[mc]];
-        const float c1 = LogitOp::kLog2e * cf.x * xs[mc].x, c2 = LogitOp::kLog2e * cf.y;
+        const float4 rc = xs[min(m, M - 1)];
+        const float c1 = rc.z, c2 = rc.w;
         float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
@@ -620,11 +679,12 @@ struct ScreenEpi {
   }
 };
 
-// One workgroup per row tile of the exact GEMM: bounds from smax and the quantisers' figures -> live[row tile][column tile].
-// spt: sub-tiles of smax per column tile.  counts (or NULL): += tiles the exact GEMM will compute, += tiles.
+// One workgroup per row tile of the exact GEMM: bounds from smax and the quantisers' figures -> live[row tile][column
+// tile].  Not screened (*on == 0): every tile is live.  spt: sub-tiles of smax per column tile.
+// counts (or NULL): [0] += tiles to compute, [1] += tiles, [4] += tiles of screened launches.
 __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __restrict__ n_dev, int n_max, int nps, int ntn,
                                                                 int spt, const float* __restrict__ smax,
-                                                                const float2* __restrict__ xs,
+                                                                const float4* __restrict__ xs,
                                                                 const float2* __restrict__ grp,
                                                                 const float4* __restrict__ coef_tau,
                                                                 const int32_t* __restrict__ tau,
@@ -636,58 +696,56 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
   const int n = min(*n_dev, n_max);
   const int m0 = blockIdx.x * BM;
   if (m0 >= n) return;
-  uint8_t* out = live + (int64_t)blockIdx.x * ntn;
-  if (*on == 0) {   // not screened: everything is computed
-    for (int t = threadIdx.x; t < ntn; t += 256) out[t] = 1;
-    if (counts && threadIdx.x == 0) {
-      atomicAdd(&counts[0], (unsigned long long)ntn);
-      atomicAdd(&counts[1], (unsigned long long)ntn);
-    }
-    return;
-  }
-  for (int t = threadIdx.x; t < ntn; t += 256) s_flag[t] = 0;
+  const bool screened = *on != 0;
+  for (int t = threadIdx.x; t < ntn; t += 256) s_flag[t] = screened ? 0 : 1;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // how far an exact logit may lie from its screened value s: the quantisation (ea sm + eb |mu^|_1 of the group)
   // and an allowance for the roundings of the affine map, which the two GEMMs apply to different sums
   auto slack = [](float s, float ea, float eb, float2 g) { return fmaf(ea, g.x, fmaf(eb, g.y, 0.5f)) + 1e-6f * fabsf(s); };
-  for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
-    float ea[RW], eb[RW], lo[RW];
-    const float* s[RW];
+  if (screened) {
+    for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
+      float ea[RW], eb[RW], lo[RW];
+      const float* s[RW];
 #pragma unroll
-    for (int k = 0; k < RW; ++k) {   // rows past the end repeat the last one: the same flags again
-      const int m = min(m0 + r0 + k, n - 1);
-      s[k] = smax + (int64_t)m * nps;
-      const float c1 = 0.5f * kScreenRound * LogitOp::kLog2e * coef_tau[tau[m]].x;
-      ea[k] = c1 * kScreenFp32 * xs[m].y;
-      eb[k] = c1 * xs[m].x;
-      lo[k] = -INFINITY;
+      for (int k = 0; k < RW; ++k) {   // rows past the end repeat the last one: the same flags again
+        const int m = min(m0 + r0 + k, n - 1);
+        s[k] = smax + (int64_t)m * nps;
+        const float4 rc = xs[m];
+        const float c1 = 0.5f * kScreenRound * LogitOp::kLog2e * coef_tau[tau[m]].x;
+        ea[k] = c1 * kScreenFp32 * rc.y;
+        eb[k] = c1 * rc.x;
+        lo[k] = -INFINITY;
+      }
+      for (int p = lane; p < nps; p += 64) {
+        const float2 g = grp[p];
+#pragma unroll
+        for (int k = 0; k < RW; ++k) lo[k] = fmaxf(lo[k], s[k][p] - slack(s[k][p], ea[k], eb[k], g));
+      }
+#pragma unroll
+      for (int k = 0; k < RW; ++k) lo[k] = wave_max(lo[k]) - CombineOp::kZeroGap;
+      for (int p = lane; p < nps; p += 64) {
+        const float2 g = grp[p];
+        bool any = false;
+#pragma unroll
+        for (int k = 0; k < RW; ++k) any = any || (s[k][p] + slack(s[k][p], ea[k], eb[k], g) >= lo[k]);
+        if (any) s_flag[p / spt] = 1;
+      }
     }
-    for (int p = lane; p < nps; p += 64) {
-      const float2 g = grp[p];
-#pragma unroll
-      for (int k = 0; k < RW; ++k) lo[k] = fmaxf(lo[k], s[k][p] - slack(s[k][p], ea[k], eb[k], g));
-    }
-#pragma unroll
-    for (int k = 0; k < RW; ++k) lo[k] = wave_max(lo[k]) - CombineOp::kZeroGap;
-    for (int p = lane; p < nps; p += 64) {
-      const float2 g = grp[p];
-      bool any = false;
-#pragma unroll
-      for (int k = 0; k < RW; ++k) any = any || (s[k][p] + slack(s[k][p], ea[k], eb[k], g) >= lo[k]);
-      if (any) s_flag[p / spt] = 1;
-    }
+    __syncthreads();
   }
-  __syncthreads();
   int mine = 0;
   for (int t = threadIdx.x; t < ntn; t += 256) {
-    out[t] = (uint8_t)s_flag[t];
+    live[(int64_t)blockIdx.x * ntn + t] = (uint8_t)s_flag[t];
     mine += s_flag[t];
   }
   if (counts) {
     const int total = (int)wave_sum((float)mine);   // this wavefront's share; at most a few thousand: exact in fp32
     if (lane == 0 && total) atomicAdd(&counts[0], (unsigned long long)total);
-    if (threadIdx.x == 0) atomicAdd(&counts[1], (unsigned long long)ntn);
+    if (threadIdx.x == 0) {
+      atomicAdd(&counts[1], (unsigned long long)ntn);
+      if (screened) atomicAdd(&counts[4], (unsigned long long)ntn);
+    }
   }
 }
 
@@ -829,10 +887,12 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     }
     ASD_HIP(hipDeviceSynchronize());
     g->split_ok = g->use_split = true;
-    ASD_HIP(hipMalloc(&g->work_counts, 4 * sizeof(unsigned long long)));
-    ASD_HIP(hipMemset(g->work_counts, 0, 4 * sizeof(unsigned long long)));
+    const int np_v = GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN);   // partial maxima per row, verify call
+    ASD_HIP(hipMalloc(&g->rmax, sizeof(float) * (size_t)ctx->n_rows_max));
+    ASD_HIP(hipMalloc(&g->glive, (size_t)ceil_div(ctx->n_rows_max, CombineOp::kRowmaxTile) * np_v));
+    ASD_HIP(hipMalloc(&g->work_counts, 6 * sizeof(unsigned long long)));
+    ASD_HIP(hipMemset(g->work_counts, 0, 6 * sizeof(unsigned long long)));
     // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
-    const int np_v = GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN);
     if (d % 128 == 0 && C % ScreenTile::BN == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
         split3_sparse_fits<GmmTileSplit>(C, np_v, GmmTileSplit::WN)) {
       g->nps = C / ScreenTile::WN;
@@ -841,7 +901,7 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
       ASD_HIP(hipMalloc(&g->means_s, sizeof(float) * 2 * (size_t)C));
       ASD_HIP(hipMalloc(&g->means_grp, sizeof(float2) * (size_t)g->nps));
       ASD_HIP(hipMalloc(&g->xq, (size_t)ctx->n_rows_max * d));
-      ASD_HIP(hipMalloc(&g->xs, sizeof(float2) * (size_t)ctx->n_rows_max));
+      ASD_HIP(hipMalloc(&g->xs, sizeof(float4) * (size_t)ctx->n_rows_max));
       ASD_HIP(hipMalloc(&g->smax, sizeof(float) * (size_t)ctx->n_rows_max * g->nps));
       ASD_HIP(hipMalloc(&g->tile_live, (size_t)row_tiles * (C / GmmTileSplit::BN)));
       ASD_HIP(hipMalloc(&g->screen_on, 4 * sizeof(int32_t)));
@@ -898,6 +958,8 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->tile_live);
   (void)hipFree(g->screen_on);
   (void)hipFree(g->work_counts);
+  (void)hipFree(g->rmax);
+  (void)hipFree(g->glive);
   delete g;
   ctx->gmm = nullptr;
 }
@@ -942,9 +1004,9 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
     const int ntn = C / GmmTileSplit::BN;
     hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
-                       rows.in_base, rows.in_off, on, g->xq, g->xs);
+                       rows.in_base, rows.in_off, rows.tau, g->coef_tau, on, g->xq, g->xs);
     ASD_HIP(hipGetLastError());
-    ScreenEpi epi{g->smax, g->nps, g->coef_tau, rows.tau, g->musq, g->log_w, g->xs, g->means_s, on};
+    ScreenEpi epi{g->smax, g->nps, g->musq, g->log_w, g->xs, g->means_s, on};
     // int8 operands, handed over as 16-bit units (two k each)
     ASD_HIP(launch_gemm_bf16_nt_pipe<ScreenTile, 1>(rows.n_dev, n, C, d / 2, reinterpret_cast<const uint16_t*>(g->xq),
                                                     d / 2, 0, reinterpret_cast<const uint16_t*>(g->means_q), d / 2, epi,
@@ -974,10 +1036,17 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   RowSrc P{g->logits, nullptr, C};
   // columns behind one partial row maximum: the first GEMM's wavefront sub-tile width (the last group may be short)
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
-  CombineOp op2{g->pmax, np, gcols, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau,
-                (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
+  CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
+                rows.tau, (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
+    if (split && rows.call == 1) {   // row maxima and live groups once per row tile
+      hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
+                         sizeof(int) * np, st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive);
+      ASD_HIP(hipGetLastError());
+      op2.rmax_pre = g->rmax;
+      op2.live_pre = g->glive;
+    }
     if (split)
       ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1,
                                                                        nullptr, g->sparse_combine)

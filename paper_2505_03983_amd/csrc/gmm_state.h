@@ -17,6 +17,8 @@ struct GmmState {
   float* logits = nullptr;       // [rows_max, C] (matrix-core path only)
   float* pmax = nullptr;         // [rows_max, np] partial row maxima of the logits
   int np = 0;
+  float* rmax = nullptr;         // [rows_max] row maxima of the verify call's logits (split-operand path)
+  uint8_t* glive = nullptr;      // [row tiles][np] column groups that are live for a row of the tile
   float* part = nullptr;         // split-K scratch of the draft call's second GEMM: [splits][chains][d] tiles, [splits][chains] sums
   int draft_splits = 1;
   bool use_mfma = false;
@@ -28,8 +30,9 @@ struct GmmState {
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
-  // DEV [4], summed over the verify calls while profiling: tiles of logits computed / there were (screened path
-  // only), K slabs the second GEMM's workgroups visited / there were
+  // DEV [6], summed over the verify calls while profiling: tiles of logits computed / there were (calls that went
+  // through the screening launches), K slabs the second GEMM's workgroups visited / there were, tiles of the calls
+  // that were screened, unused
   unsigned long long* work_counts = nullptr;
   bool sparse_combine = true;      // the second split GEMM of the verify call skips slabs of exact zeros (gemm_split3.h)
   // Screening of the verify call's logits GEMM (gmm.hip): an int8 GEMM finds the tiles whose softmax weights are
@@ -40,7 +43,7 @@ struct GmmState {
   float* means_s = nullptr;        // [2 C]: their scales, then the 1-norms of the quantised means
   float2* means_grp = nullptr;     // [nps] largest of either over each sub-tile of columns
   int8_t* xq = nullptr;            // [rows_max, d] the call's rows, quantised
-  float2* xs = nullptr;            // [rows_max]: scale, 1-norm
+  float4* xs = nullptr;            // [rows_max]: scale, 1-norm, the row's two factors of the affine map
   float* smax = nullptr;           // [rows_max, nps] screened row maxima per sub-tile
   int nps = 0;
   uint8_t* tile_live = nullptr;    // [row tiles][column tiles]
