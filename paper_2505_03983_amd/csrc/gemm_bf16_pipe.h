@@ -21,10 +21,6 @@
 // segments.  A lane feeds k = 16*ks + 8*half .. +7 of its row to MFMA ks, for
 // both operands, so the pairing of elements is exact.
 //
-// Epilogues: Epi::kRowMax = false -- store4(m, n, values, previous) on four columns of a row at a time (and
-// load4 first when Epi::kLoads); true -- row_max<Cfg>(accumulators, ...) instead, for a caller that wants a
-// reduction over each row's columns and not the product itself, and off() to skip the launch from the device.
-//
 // Requirements (checked by the host): K % 64 == 0, lda and ldw multiples of 8,
 // 16-byte aligned bases.  M comes from device memory (compacted row plan).
 //
@@ -32,12 +28,6 @@
 // elements apart (activations kept to 16 significant bits as hi + lo, see mlp.hip).  A stage then holds
 // the slab of both planes above the W slab and every (A fragment, W fragment) pair is multiplied twice,
 // once per plane, into the same accumulator: the weights are loaded once for both.
-//
-// int8 operands (INT8): the data movement is that of bf16 with two int8 in the place of one bf16 -- a row's slab is
-// still 128 bytes, a lane's 16-byte chunk now holds 16 consecutive k and feeds one v_mfma_i32_32x32x32_i8 (twice
-// the multiply-adds of the bf16 instruction in the same time), and the accumulators are int32, so the sums are
-// exact.  The caller passes A and W as arrays of 16-bit units: K, lda and ldw count pairs of int8.  Only for
-// epilogues that reduce (kRowMax), which get the int32 accumulators.
 //
 // Split K (gridDim.z > 1): for a handful of rows the kernel is a stream of the weight matrix, and HBM
 // only delivers its bandwidth with ~16 MB in flight -- more workgroups than the output has tiles.  The
@@ -49,8 +39,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <type_traits>
-
 #include "gemm_bf16.h"
 
 namespace asd {
@@ -59,10 +47,9 @@ namespace asd {
 // Eight wavefronts (two per SIMD) let one wavefront's MFMAs run while its SIMD neighbour waits on the
 // address unit: a direct-to-LDS load of 1 KB occupies the CU's single address path for ~16 cycles and
 // the issuing wavefront stalls until it is accepted.
-template <int BM_, int BN_, int STAGES_, int WGM_ = 2, int WGN_ = 4, int PLANES_ = 1, bool INT8_ = false>
+template <int BM_, int BN_, int STAGES_, int WGM_ = 2, int WGN_ = 4, int PLANES_ = 1>
 struct PipeCfg16 {
   static constexpr int BM = BM_, BN = BN_, STAGES = STAGES_, BK = 64, WGM = WGM_, WGN = WGN_, PLANES = PLANES_;
-  static constexpr bool INT8 = INT8_;   // operands are int8, two to a 16-bit unit: see the header
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;          // wavefront sub-tile
   static constexpr int MI = WM / 32, NJ = WN / 32;
@@ -116,9 +103,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
   // (m_lo, m_hi]: the row counts this launch serves -- the caller may queue several tile shapes for one
   // product and let the row count, known on the device only, pick the one that runs
   if (m0 >= M || M_all <= m_lo || M_all > m_hi) return;
-  if constexpr (Epi::kRowMax) {
-    if (epi.off()) return;   // the caller's switch, in device memory
-  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -162,16 +146,13 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
     }
   };
 
-  static_assert(!Cfg::INT8 || (Epi::kRowMax && PL == 1), "int8 operands: reducing epilogues, one plane");
-  typedef typename std::conditional<Cfg::INT8, v16i_b, v16f_b>::type acc_t;
-  typedef typename std::conditional<Cfg::INT8, v4i_b, v8bf>::type frag_t;
-  acc_t acc[MI][NJ];
+  v16f_b acc[MI][NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // ---- software pipeline, rotated so that everything that is not an MFMA runs in the shadow of MFMAs:
   //   prologue : loads of slabs 0..STAGES-2 in flight, slab 0 landed, its first fragments read
@@ -199,22 +180,20 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) cp[ks] = ((ks * 2 + half) ^ sw) * 16;
 
-  frag_t af[2][AI], wf[2][NJ];
+  v8bf af[2][AI], wf[2][NJ];
   auto read_frags = [&](const uint8_t* sb, int ks, int buf) {
 #pragma unroll
     for (int i = 0; i < AI; ++i)   // fragment i: plane i / MI, 32-row block i % MI
-      af[buf][i] = *reinterpret_cast<const frag_t*>(sb + (i / MI) * (BM * 128) + a_row + (i % MI) * 32 * 128 + cp[ks]);
+      af[buf][i] = *reinterpret_cast<const v8bf*>(sb + (i / MI) * (BM * 128) + a_row + (i % MI) * 32 * 128 + cp[ks]);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) wf[buf][j] = *reinterpret_cast<const frag_t*>(sb + w_row + j * 32 * 128 + cp[ks]);
+    for (int j = 0; j < NJ; ++j) wf[buf][j] = *reinterpret_cast<const v8bf*>(sb + w_row + j * 32 * 128 + cp[ks]);
   };
   auto mma = [&](int buf, int first, int count) {  // MFMAs first .. first+count-1 of a group, row-major over (i, j)
 #pragma unroll
     for (int q = 0; q < G; ++q)
-      if (q >= first && q < first + count) {
-        acc_t& c = acc[(q / NJ) % MI][q % NJ];
-        if constexpr (Cfg::INT8) c = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[buf][q / NJ], wf[buf][q % NJ], c, 0, 0, 0);
-        else c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][q / NJ], wf[buf][q % NJ], c, 0, 0, 0);
-      }
+      if (q >= first && q < first + count)
+        acc[(q / NJ) % MI][q % NJ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][q / NJ], wf[buf][q % NJ],
+                                                                             acc[(q / NJ) % MI][q % NJ], 0, 0, 0);
   };
 
   wait_vmcnt_slabs<LPS, 0>(min(STAGES - 2, nk - 1));   // slab 0 landed; the other prologue slabs may be in flight
@@ -259,56 +238,51 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_bf16_nt_pipe_kernel(const i
     sched_pairs<0x100, (SLOTS - 1 < H2 ? SLOTS - 1 : H2), 2>();
   }
 
-  // An epilogue that only reduces over the columns of a row works on the accumulators where they are.
-  if constexpr (Epi::kRowMax) {
-    epi.template row_max<Cfg>(acc, m0, n0, M, N, wm, wn, l32, half);
-  } else {
-    // Epilogue through LDS (the pipeline stages are free now): each wavefront parks its WM x WN fp32
-    // sub-tile in its own LDS region, then walks it row by row with 16-byte accesses, so global traffic
-    // is row-contiguous and the code is a short loop rather than 16*MI*NJ unrolled scalar stores.
-    static_assert((size_t)BM * BN * 4 <= Cfg::LDS_BYTES, "epilogue staging must fit in the pipeline's LDS");
-    __builtin_amdgcn_s_barrier();  // every wavefront is done reading the last stage
-    float* stage = reinterpret_cast<float*>(ldsb) + wave * (WM * WN);
+  // Epilogue through LDS (the pipeline stages are free now): each wavefront parks its WM x WN fp32
+  // sub-tile in its own LDS region, then walks it row by row with 16-byte accesses, so global traffic
+  // is row-contiguous and the code is a short loop rather than 16*MI*NJ unrolled scalar stores.
+  static_assert((size_t)BM * BN * 4 <= Cfg::LDS_BYTES, "epilogue staging must fit in the pipeline's LDS");
+  __builtin_amdgcn_s_barrier();  // every wavefront is done reading the last stage
+  float* stage = reinterpret_cast<float*>(ldsb) + wave * (WM * WN);
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          stage[(i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * WN + j * 32 + l32] = acc[i][j][r];
-    // the region is private to this wavefront: LDS operations of one wavefront complete in order
-    constexpr int LPR = WN / 4;        // lanes per row (one float4 each)
-    constexpr int RPI = 64 / LPR;      // rows per iteration
-    const int lrow = lane / LPR, lcol = (lane % LPR) * 4;
-    // The residual stream is read and rewritten in place: all reads of a batch of rows are issued
-    // before its first write, so a batch costs one memory round trip.
-    constexpr int ITERS = WM / RPI, BATCH = ITERS < 8 ? ITERS : 8;
-    static_assert(ITERS % BATCH == 0, "epilogue batching");
-    const int n = n0 + wn * WN + lcol;
-    if (splits > 1) {
-      for (int it = 0; it < ITERS; ++it) {
-        const int row = it * RPI + lrow;
-        const int m = m0 + wm * WM + row;
-        if (m < M && n < N)
-          *reinterpret_cast<float4*>(part + ((int64_t)blockIdx.z * M_max + m) * N + n) =
-              *reinterpret_cast<const float4*>(&stage[row * WN + lcol]);
-      }
-      return;
+      for (int r = 0; r < 16; ++r)
+        stage[(i * 32 + 8 * (r >> 2) + 4 * half + (r & 3)) * WN + j * 32 + l32] = acc[i][j][r];
+  // the region is private to this wavefront: LDS operations of one wavefront complete in order
+  constexpr int LPR = WN / 4;        // lanes per row (one float4 each)
+  constexpr int RPI = 64 / LPR;      // rows per iteration
+  const int lrow = lane / LPR, lcol = (lane % LPR) * 4;
+  // The residual stream is read and rewritten in place: all reads of a batch of rows are issued
+  // before its first write, so a batch costs one memory round trip.
+  constexpr int ITERS = WM / RPI, BATCH = ITERS < 8 ? ITERS : 8;
+  static_assert(ITERS % BATCH == 0, "epilogue batching");
+  const int n = n0 + wn * WN + lcol;
+  if (splits > 1) {
+    for (int it = 0; it < ITERS; ++it) {
+      const int row = it * RPI + lrow;
+      const int m = m0 + wm * WM + row;
+      if (m < M && n < N)
+        *reinterpret_cast<float4*>(part + ((int64_t)blockIdx.z * M_max + m) * N + n) =
+            *reinterpret_cast<const float4*>(&stage[row * WN + lcol]);
     }
-    for (int it0 = 0; it0 < ITERS; it0 += BATCH) {
-      float4 v[BATCH], prev[BATCH];
+    return;
+  }
+  for (int it0 = 0; it0 < ITERS; it0 += BATCH) {
+    float4 v[BATCH], prev[BATCH];
 #pragma unroll
-      for (int b = 0; b < BATCH; ++b) {
-        const int row = (it0 + b) * RPI + lrow;
-        const int m = m0 + wm * WM + row;
-        v[b] = *reinterpret_cast<const float4*>(&stage[row * WN + lcol]);
-        prev[b] = (Epi::kLoads && m < M && n < N) ? epi.load4(m, n) : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
+    for (int b = 0; b < BATCH; ++b) {
+      const int row = (it0 + b) * RPI + lrow;
+      const int m = m0 + wm * WM + row;
+      v[b] = *reinterpret_cast<const float4*>(&stage[row * WN + lcol]);
+      prev[b] = (Epi::kLoads && m < M && n < N) ? epi.load4(m, n) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 #pragma unroll
-      for (int b = 0; b < BATCH; ++b) {
-        const int m = m0 + wm * WM + (it0 + b) * RPI + lrow;
-        if (m < M && n < N) epi.store4(m, n, v[b], prev[b]);
-      }
+    for (int b = 0; b < BATCH; ++b) {
+      const int m = m0 + wm * WM + (it0 + b) * RPI + lrow;
+      if (m < M && n < N) epi.store4(m, n, v[b], prev[b]);
     }
   }
 }
@@ -339,7 +313,6 @@ inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K
                                            int splits = 1, float* part = nullptr, int m_lo = -1,
                                            int m_hi = 0x7fffffff) {
   if (splits < 1 || (K / 64) % splits != 0 || (splits > 1 && !part)) return hipErrorInvalidValue;
-  if (Epi::kRowMax && splits > 1) return hipErrorInvalidValue;   // a row reduction needs the whole of K
   dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), (unsigned)((M + Cfg::BM - 1) / Cfg::BM), (unsigned)splits);
   auto kern = gemm_bf16_nt_pipe_kernel<Cfg, Epi, CALL>;
   static bool attr_set = false;  // dynamic LDS above the default limit needs the attribute once per kernel
@@ -351,10 +324,9 @@ inline hipError_t launch_gemm_bf16_nt_pipe(const int* M_dev, int M, int N, int K
   }
   hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, M_dev, M, N, K, A, lda, a_plane, W, ldw, epi,
                      part, m_lo, m_hi);
-  if constexpr (!Epi::kRowMax)
-    if (splits > 1)
-      hipLaunchKernelGGL(splitk_finish_kernel<Epi>, dim3((unsigned)((N / 4 + 255) / 256), (unsigned)M), dim3(256), 0, st,
-                         M_dev, M, N, splits, part, epi, m_lo, m_hi);
+  if (splits > 1)
+    hipLaunchKernelGGL(splitk_finish_kernel<Epi>, dim3((unsigned)((N / 4 + 255) / 256), (unsigned)M), dim3(256), 0, st,
+                       M_dev, M, N, splits, part, epi, m_lo, m_hi);
   return hipGetLastError();
 }
 

@@ -140,19 +140,19 @@ inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K
 }
 
 // The Op interface is that of gemm_f32.h (init / load_a / finish / epilogue); load_a is applied when
-// the values are split, not when they are loaded.  An Op with kTileSkip may declare a whole output tile
-// unwanted (tile_dead, from data in device memory): the workgroup then only runs the Op's mark_dead.
+// the values are split, not when they are loaded.  An Op with kTileList may carry lists of the output tiles
+// that are wanted (tile_list, tile_count, list_cap: in device memory); see the list form of the kernel.
 //
 // Tile order.  Workgroups go to the 8 XCDs round-robin by linear id (x fastest).  ROWS_PER_XCD = false: blockIdx.x
 // = column tile, so an XCD keeps a fixed set of column tiles (its share of B stays in its L2) and every XCD
 // streams all of A.  ROWS_PER_XCD = true, for an A that is large and a B that is re-read anyway (the second
 // GEMM of the mixture denoiser: A = 1 GB of logits, 8 column tiles): all column tiles of a row tile run on one
 // XCD, back to back, so a tile of A crosses the fabric once instead of once per XCD.
-template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
-__global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
-                                                                         int N, int K, RowSrc A,
-                                                                         const uint8_t* __restrict__ Bimg, Op op,
-                                                                         float* __restrict__ part, int sparse) {
+// One output tile (tile_m, tile_n) by the calling workgroup.
+template <class Cfg, class Op>
+__device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, const RowSrc& A,
+                                            const uint8_t* __restrict__ Bimg, Op& op, float* __restrict__ part,
+                                            int sparse, int tile_m, int tile_n) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ, BK = Cfg::BK, NG = Cfg::NG, RB = Cfg::RB;
   constexpr int RA = Cfg::RA, RPP = Cfg::RPP, A_PLANE = Cfg::A_PLANE, B_PLANE = Cfg::B_PLANE;
   constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS;
@@ -162,25 +162,14 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
   uint16_t* s_list = reinterpret_cast<uint16_t*>(s_row + 8 * BM);                // sparse K: [K / BK] live slabs, in order
 
-  const int M = M_dev ? min(*M_dev, M_max) : M_max;
-  int tile_n = blockIdx.x, tile_m = blockIdx.y;
-  if (ROWS_PER_XCD) {
-    // linear id = 8 ntn G + r: XCD r % 8 takes row tile 8 G + r % 8, column tile r / 8 (grid.y is a multiple of 8)
-    const unsigned ntn = gridDim.x, lin = blockIdx.x + ntn * blockIdx.y;
-    const unsigned G = lin / (8 * ntn), r = lin % (8 * ntn);
-    tile_m = (int)(8 * G + r % 8);
-    tile_n = (int)(r / 8);
-  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   if (m0 >= M) return;
-  if constexpr (Op::kTileSkip) {
-    if (op.tile_dead(tile_m, tile_n, (int)gridDim.x)) {   // the same for the whole workgroup
-      op.template mark_dead<Cfg>(m0, M, tile_n, (int)threadIdx.x);
-      return;
-    }
-  }
 
-  const int tid = threadIdx.x;
+  // (opaque to the optimiser: when this is called in a loop over tiles, everything derived from the thread index
+  // below would otherwise be hoisted out of that loop and held in registers across it, which the K loop has none
+  // to spare for)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const Frag<Cfg> fr{wave / Cfg::WGN, wave % Cfg::WGN, lane & 31, lane >> 5, tile_n};
@@ -369,6 +358,72 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
   op.template epilogue<Cfg>(acc, fr, m0, n0, M, N, s_row);
 }
 
+// Grid: (column tiles, row tiles, K splits), one tile per workgroup.
+template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
+__global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
+                                                                         int N, int K, RowSrc A,
+                                                                         const uint8_t* __restrict__ Bimg, Op op,
+                                                                         float* __restrict__ part, int sparse) {
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  int tile_n = blockIdx.x, tile_m = blockIdx.y;
+  if (ROWS_PER_XCD) {
+    // linear id = 8 ntn G + r: XCD r % 8 takes row tile 8 G + r % 8, column tile r / 8 (grid.y is a multiple of 8)
+    const unsigned ntn = gridDim.x, lin = blockIdx.x + ntn * blockIdx.y;
+    const unsigned G = lin / (8 * ntn), r = lin % (8 * ntn);
+    tile_m = (int)(8 * G + r % 8);
+    tile_n = (int)(r / 8);
+  }
+  split3_tile<Cfg, Op>(M, M_max, N, K, A, Bimg, op, part, sparse, tile_m, tile_n);
+}
+
+// The list form, for an Op with kTileList that carries lists of the wanted tiles: tile_list = 8 lists of list_cap
+// entries (entry = row tile * column tiles + column tile), tile_count[q] = length of list q, and a ticket counter per
+// list at tile_count[kTicketBase + kTicketStride * q], zero at launch (each on a cache line of its own: read-modify-
+// write operations on one line are served one after the other, some 60 ns each).  Any number of workgroups (a
+// multiple of 8) stay resident and draw tiles by ticket.  The lists are by column tile modulo 8 and workgroup w
+// starts on list w % 8 -- its XCD's, so an XCD keeps to its share of B, as in the grid order -- and moves on to the
+// next list when one has run dry, so the launch ends evenly.  Nothing is launched for the tiles that are not wanted,
+// which matters when those are nearly all.
+constexpr int kTicketBase = 32, kTicketStride = 32, kTicketInts = kTicketBase + 8 * kTicketStride;
+template <class Cfg, class Op, int CALL>
+__global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_list_kernel(const int* __restrict__ M_dev, int M_max,
+                                                                              int N, int K, RowSrc A,
+                                                                              const uint8_t* __restrict__ Bimg, Op op) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
+  int* s_ticket = reinterpret_cast<int*>(lds_all + Cfg::LDS_BYTES);   // the launcher adds 16 bytes for it
+  const int M = M_dev ? min(*M_dev, M_max) : M_max;
+  const int ntn = (N + Cfg::BN - 1) / Cfg::BN;
+  int lists_done = 0;   // thread 0: lists this workgroup has found dry
+  auto draw = [&]() -> int {   // thread 0: the next tile (index into tile_list), or -1
+    while (lists_done < 8) {
+      const int q = (blockIdx.x + lists_done) % 8;
+      const int count = min(op.tile_count[q], op.list_cap);
+      int32_t* ticket = const_cast<int32_t*>(op.tile_count) + kTicketBase + kTicketStride * q;
+      // a look before the draw: a dry list then costs a load, not a place in the line's queue
+      if (__hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < count) {
+        const int i = atomicAdd(ticket, 1);
+        if (i < count) return q * op.list_cap + i;
+      }
+      ++lists_done;
+    }
+    return -1;
+  };
+  if (threadIdx.x == 0) *s_ticket = draw();
+  __syncthreads();
+  for (;;) {
+    const int cur = __builtin_amdgcn_readfirstlane(*s_ticket);
+    if (cur < 0) break;
+    __syncthreads();   // everyone has read the ticket
+    // the next ticket is drawn now and published at the end of this tile: its latency hides under the tile
+    int nxt = -1;
+    if (threadIdx.x == 0) nxt = draw();
+    const uint32_t e = (uint32_t)__builtin_amdgcn_readfirstlane((int)op.tile_list[cur]);
+    split3_tile<Cfg, Op>(M, M_max, N, K, A, Bimg, op, nullptr, 0, (int)(e / (uint32_t)ntn), (int)(e % (uint32_t)ntn));
+    if (threadIdx.x == 0) *s_ticket = nxt;
+    __syncthreads();   // the ticket is visible; the next tile reuses the stages and the Op's rows
+  }
+}
+
 // Whether a launch with `sparse` set walks a slab list (else it stays dense): the list must fit beside the stages.
 template <class Cfg>
 inline bool split3_sparse_fits(int K, int groups, int group_cols) {
@@ -377,13 +432,16 @@ inline bool split3_sparse_fits(int K, int groups, int group_cols) {
   return lds <= 80 * 1024;   // two workgroups per CU
 }
 
+// resident_wgs > 0: the list form of the kernel, with that many workgroups.
 // splits > 1 (Ops with kSplitK, not with ROWS_PER_XCD): `part` = gemm_f32_splitk_floats(splits, M_max, N) floats.
 // sparse: let an Op with kSparseK skip the slabs of K it marks dead (needs K / BK <= 65535, the Op's column groups a
 // multiple of BK wide and K a multiple of them; otherwise the loop stays dense).
 template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
-                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false) {
+                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false,
+                                        int resident_wgs = 0) {
   if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
+  if (resident_wgs && (!Op::kTileList || resident_wgs % 8 != 0 || splits != 1 || ROWS_PER_XCD)) return hipErrorInvalidValue;
   size_t lds = Cfg::LDS_BYTES;
   if constexpr (Op::kSparseK) {
     sparse = sparse && splits == 1 && split3_sparse_fits<Cfg>(K, op.groups(), op.group_cols());
@@ -396,6 +454,20 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
   unsigned mt = (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM);
   if (ROWS_PER_XCD) mt = (mt + 7) / 8 * 8;
   dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), mt, (unsigned)splits);
+  if constexpr (Op::kTileList) {
+    if (resident_wgs) {   // the Op carries the lists of tiles
+      auto lkern = gemm_split3_nt_list_kernel<Cfg, Op, CALL>;
+      static bool lattr_set = false;
+      if (!lattr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)lkern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+        if (e != hipSuccess) return e;
+        lattr_set = true;
+      }
+      hipLaunchKernelGGL(lkern, dim3((unsigned)resident_wgs), dim3(Cfg::THREADS), lds + 16, st, M_dev, M_max, N, K, A, Bimg,
+                         op);
+      return hipGetLastError();
+    }
+  }
   auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL, ROWS_PER_XCD>;
   static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {

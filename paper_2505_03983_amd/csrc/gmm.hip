@@ -22,6 +22,7 @@
 #include "common.h"
 #include "device_util.h"
 #include "gemm_bf16_pipe.h"
+#include "gemm_i8_stream.h"
 #include "gemm_f32.h"
 #include "gemm_split3.h"
 #include "gmm_state.h"
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
 struct LogitOp {
   static constexpr bool kSplitK = false;
   static constexpr bool kSparseK = false;
-  static constexpr bool kTileSkip = true;
+  static constexpr bool kTileList = true;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -243,20 +244,13 @@ struct LogitOp {
   const int32_t* tau;
   const float* musq;
   const float* log_w;
-  // NULL, or [row tiles][column tiles] from the screening pass below: 0 = every logit of the tile lies more than
-  // CombineOp::kZeroGap below the maximum of its row.  Such a tile is not computed: its partial maxima are set to
-  // -inf, which the second GEMM reads as "all weights zero, skip" -- the logits themselves are never read again.
-  const uint8_t* live = nullptr;
-  __device__ __forceinline__ bool tile_dead(int tile_m, int tile_n, int ntn) const {
-    return live && live[(int64_t)tile_m * ntn + tile_n] == 0;
-  }
-  template <class Cfg>
-  __device__ __forceinline__ void mark_dead(int m0, int M, int tile_n, int tid) const {
-    for (int t = tid; t < Cfg::BM * Cfg::WGN; t += Cfg::THREADS) {
-      const int m = m0 + t / Cfg::WGN;
-      if (m < M) pmax[(int64_t)m * np + Cfg::WGN * tile_n + t % Cfg::WGN] = -INFINITY;
-    }
-  }
+  // NULL, or the lists of tiles the screening pass below wants computed (see the list form of the kernel for the
+  // layout).  The tiles left out hold only logits more than CombineOp::kZeroGap below the maxima of their rows; the
+  // screening pass has set their partial maxima to -inf, which the second GEMM reads as "all weights zero, skip",
+  // and the logits themselves are never read.
+  const uint32_t* tile_list = nullptr;
+  const int32_t* tile_count = nullptr;
+  int list_cap = 0;
   static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
   // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
@@ -324,7 +318,7 @@ struct LogitOp {
 struct CombineOp {
   static constexpr bool kSplitK = true;
   static constexpr bool kSparseK = true;
-  static constexpr bool kTileSkip = false;
+  static constexpr bool kTileList = false;
   const float* pmax;
   int np;
   int gcols;  // logits columns behind one partial maximum (sub-tile width of the first GEMM), 0: unknown
@@ -521,80 +515,93 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
 // Once the noise is low a posterior sits on one or two components: every other softmax weight is exactly 0.0f
 // in fp32 (2^-150 underflows), and the 6-product logits GEMM spends its time on numbers that only have to be
 // "far below the row maximum".  An int8 GEMM (a twelfth of the matrix time, exact int32 sums) says which tiles
-// those are, rigorously.  Rows and means are quantised with one scale each,  x ~ sx qx,  mu ~ sm qm  (q = the
-// nearest integer in [-127, 127], s = max |.| / 127), so
-//   |sx sm <qx, qm> - <x, mu>|  <=  (sm / 2) |x|_1 + (sx / 2) |mu^|_1,      mu^ = sm qm,
-// from  x_k mu_k - x^_k mu^_k = x_k (mu_k - mu^_k) + mu^_k (x_k - x^_k).  With the same affine map as the exact
-// GEMM,  s = kappa' sx sm <qx, qm> - gamma' |mu|^2 + log2 w,  every exact logit of a column group lies within
-// e = kappa' (that bound, with the group's largest sm and |mu^|_1) + a rounding allowance of its screened value,
-// so the group's logits are all below s_max + e and the one at s_max is above s_max - e.  A 128 x 128 tile is dead
-// when, for each of its rows, the upper bound of its columns is more than kZeroGap below the largest lower bound
-// of the row.  Dead tiles are skipped by the exact GEMM (LogitOp::live) and, through their -inf partial maxima,
-// by the second GEMM; the result is bit-identical to computing everything, because the skipped weights are exact
-// zeros there too.  (kScreenFp32 covers what the exact GEMM's own fp32 sums may be off by: below 2^-13 sum |x_k
-// mu_k| <= 2^-13 127 sm |x|_1 for d <= 2048, i.e. 3% of the first term.)
+// those are, rigorously.  A row x is quantised with its own scale, the means with one scale per group of kGroup
+// components:  x ~ sx qx,  mu ~ sg qm  (q = the nearest integer in [-127, 127], s = max |.| / 127), so
+//   |sx sg <qx, qm> - <x, mu>|  <=  (sg / 2) |x|_1 + (sx / 2) |mu^|_1,      mu^ = sg qm,
+// from  x_k mu_k - x^_k mu^_k = x_k (mu_k - mu^_k) + mu^_k (x_k - x^_k).  The GEMM keeps, for every row and group,
+// only the largest integer sum I (gemm_i8_stream.h).  The exact logit of component n is
+// kappa' <x, mu_n> - gamma' |mu_n|^2 + log2 w_n  with kappa', gamma' >= 0, so with e = kappa' (the bound above, with
+// the group's largest |mu^|_1) + a rounding allowance every logit of the group lies below
+//   U = kappa' sx sg I - gamma' min |mu|^2 + max log2 w + e
+// and the one at the largest sum lies above
+//   L = kappa' sx sg I - gamma' max |mu|^2 + min log2 w - e      (min, max over the group).
+// A 128 x 128 tile is dead when, for each of its rows, the U of its groups are all more than kZeroGap below the
+// largest L of the row.  Dead tiles are left out by the exact GEMM and, through their -inf partial maxima, by the
+// second GEMM; the result is bit-identical to computing everything, because the skipped weights are exact zeros
+// there too.  (kScreenFp32 covers what the exact GEMM's own fp32 sums may be off by: below 2^-13 sum |x_k mu_k| <=
+// 2^-13 127 sg |x|_1 for d <= 2048, i.e. 3% of the first term.  The spread of |mu|^2 inside a group loosens the
+// test by gamma' (max - min), a few percent of the gap between two components' logits at any noise level.)
 //
 // The pass costs a fraction of the exact GEMM but is pure overhead while the posteriors are broad, so it only
 // runs when it is likely to pay: the draft call of the same round (one row per chain, the noisiest row of each
 // window) counts the column groups its rows keep alive, and the verify call is screened when that is less than
 // a quarter of them.
 // ---------------------------------------------------------------------------
-#ifndef ASD_SCREEN_TILE
-#define ASD_SCREEN_TILE 256, 128, 3, 4, 2
-#endif
-typedef PipeCfg16<ASD_SCREEN_TILE, 1, true> ScreenTile;
-static_assert(GmmTileSplit::BN % ScreenTile::WN == 0, "whole sub-tiles of screened maxima per tile of the exact GEMM");
+typedef PipeCfg16<256, 128, 3, 4, 2> ScreenTile;   // 256 components x 128 rows; a wavefront owns 64 x 64
+constexpr int kGroup = ScreenTile::WM;             // components per group = rows of a wavefront's sub-tile
+static_assert(GmmTileSplit::BN % kGroup == 0, "whole groups per tile of the exact GEMM");
 constexpr float kScreenFp32 = 1.05f;    // see above
 constexpr float kScreenRound = 1.001f;  // the quantiser divides in fp32: a value may land 127 * 2^-23 steps off the nearest
+constexpr int kScreenWgs = 256;         // resident workgroups of the screening GEMM: one per CU
+constexpr int kResidentWgs = 512;       // workgroups of the list form of the exact GEMM: two per CU
 constexpr float kScreenDense = 0.25f;   // screen when the draft rows keep less than this share of their groups alive
 
 __device__ __forceinline__ int quant8(float v, float inv_s) { return max(-127, min(127, (int)rintf(v * inv_s))); }
 
-// means -> int8, one wavefront per component: qm [C, d], sm [C], l1 [C] = |mu^|_1
+// means -> int8, one workgroup per group of kGroup components: qm [C, d], and per group
+//   grp[2 g] = (sg, largest |mu^|_1, min |mu|^2, max |mu|^2),  grp[2 g + 1] = (min log2 w, max log2 w, -, -)
 __global__ __launch_bounds__(256) void gmm_screen_quant_means_kernel(int C, int d, const float* __restrict__ means,
-                                                                     int8_t* __restrict__ qm, float* __restrict__ sm,
-                                                                     float* __restrict__ l1) {
-  const int lane = threadIdx.x & 63, k = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (k >= C) return;
-  const float* mu = means + (int64_t)k * d;
+                                                                     const float* __restrict__ musq,
+                                                                     const float* __restrict__ log_w,
+                                                                     int8_t* __restrict__ qm, float4* __restrict__ grp) {
+  __shared__ float s_red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int k0 = blockIdx.x * kGroup, k1 = min(C, k0 + kGroup);
   float mx = 0.f;
-  for (int j = lane; j < d; j += 64) mx = fmaxf(mx, fabsf(mu[j]));
+  for (int64_t i = (int64_t)k0 * d + threadIdx.x; i < (int64_t)k1 * d; i += 256) mx = fmaxf(mx, fabsf(means[i]));
   mx = wave_max(mx);
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  __syncthreads();
   const float s = mx > 0.f ? mx / 127.f : 1.f, inv = 1.f / s;
-  float a = 0.f;
-  for (int j = lane; j < d; j += 64) {
-    const int q = quant8(mu[j], inv);
-    qm[(int64_t)k * d + j] = (int8_t)q;
-    a += fabsf((float)q);
+  float l1max = 0.f;   // per wavefront: components wave, wave + 4, ...
+  for (int k = k0 + wave; k < k1; k += 4) {
+    float a = 0.f;
+    for (int j = lane; j < d; j += 64) {
+      const int q = quant8(means[(int64_t)k * d + j], inv);
+      qm[(int64_t)k * d + j] = (int8_t)q;
+      a += fabsf((float)q);
+    }
+    l1max = fmaxf(l1max, wave_sum(a));   // an integer below 2^24: exact
   }
-  a = wave_sum(a);   // an integer below 2^24: exact
-  if (lane == 0) {
-    sm[k] = s;
-    l1[k] = s * a * (1.f + 1e-6f);
+  if (lane == 0) s_red[wave] = l1max;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    l1max = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    float qlo = INFINITY, qhi = -INFINITY, blo = INFINITY, bhi = -INFINITY;
+    for (int k = k0; k < k1; ++k) {
+      qlo = fminf(qlo, musq[k]);
+      qhi = fmaxf(qhi, musq[k]);
+      const float b = LogitOp::kLog2e * log_w[k];
+      blo = fminf(blo, b);
+      bhi = fmaxf(bhi, b);
+    }
+    grp[2 * blockIdx.x] = make_float4(s, s * l1max * (1.f + 1e-6f), qlo, qhi);
+    grp[2 * blockIdx.x + 1] = make_float4(blo, bhi, 0.f, 0.f);
   }
-}
-// largest sm and |mu^|_1 of each group of `gc` components
-__global__ void gmm_screen_group_kernel(int C, int gc, const float* __restrict__ sm, const float* __restrict__ l1,
-                                        float2* __restrict__ grp) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
-  if (g * gc >= C) return;
-  float a = 0.f, b = 0.f;
-  for (int k = g * gc; k < min(C, (g + 1) * gc); ++k) {
-    a = fmaxf(a, sm[k]);
-    b = fmaxf(b, l1[k]);
-  }
-  grp[g] = make_float2(a, b);
 }
 
-// rows of the plan -> int8 [n, d]; per row (scale, 1-norm, kappa' scale, gamma'); one wavefront per row (d <= 2048: a
-// row in registers)
+// rows of the plan -> int8 [n, d]; per row (scale, 1-norm); one wavefront per row (d <= 2048: a row in registers)
 __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restrict__ n_dev, int n_max, int d,
                                                               const float* __restrict__ in_base,
                                                               const int64_t* __restrict__ in_off,
-                                                              const int32_t* __restrict__ tau,
-                                                              const float4* __restrict__ coef_tau,
                                                               const int32_t* __restrict__ on,
-                                                              int8_t* __restrict__ xq, float4* __restrict__ xs) {
+                                                              int8_t* __restrict__ xq, float2* __restrict__ xs,
+                                                              int32_t* __restrict__ tile_count) {
+  // list lengths (the decision kernel appends) and tickets of the exact GEMM
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i < kTicketInts; i += 256) tile_count[i] = 0;
   if (*on == 0) return;
   const int n = min(*n_dev, n_max);
   const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -621,75 +628,24 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
       o[j] = (uint32_t)(quant8(v[i].x, inv) & 0xff) | ((uint32_t)(quant8(v[i].y, inv) & 0xff) << 8) |
              ((uint32_t)(quant8(v[i].z, inv) & 0xff) << 16) | ((uint32_t)(quant8(v[i].w, inv) & 0xff) << 24);
   }
-  if (lane == 0) {   // scale, 1-norm (with its own fp32 rounding), and the row's two factors of the affine map
-    const float4 cf = coef_tau[tau[m]];
-    xs[m] = make_float4(s, a * (1.f + 1e-5f), LogitOp::kLog2e * cf.x * s, LogitOp::kLog2e * cf.y);
-  }
+  if (lane == 0) xs[m] = make_float2(s, a * (1.f + 1e-5f));   // (the 1-norm's own fp32 rounding)
 }
 
-// Epilogue of the screening GEMM: the integer sums back to the scale of <x, mu>, the affine map of LogitOp, then
-// the maximum of each row over the columns of the wavefront's sub-tile -> smax[row][sub-tile].  Nothing else is stored.
-struct ScreenEpi {
-  static constexpr bool kLoads = false, kRowMax = true;
-  float* smax;
-  int nps;  // sub-tiles (ScreenTile::WN columns) per row
-  const float* musq;
-  const float* log_w;
-  const float4* xs;    // per row: scale, 1-norm, kappa' scale, gamma'
-  const float* sm;     // per component: scale
-  const int32_t* on;   // DEV: 0 = this call is not screened
-  __device__ __forceinline__ bool off() const { return *on == 0; }
-  template <class Cfg>
-  __device__ __forceinline__ void row_max(const v16i_b (&acc)[Cfg::MI][Cfg::NJ], int m0, int n0, int M, int N, int wm,
-                                          int wn, int l32, int half) const {
-    constexpr int MI = Cfg::MI, NJ = Cfg::NJ;
-    float bias[NJ], q[NJ], sc[NJ];
-    bool nok[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int nn = n0 + wn * Cfg::WN + j * 32 + l32;
-      nok[j] = nn < N;
-      const int n = nok[j] ? nn : N - 1;
-      bias[j] = LogitOp::kLog2e * log_w[n];
-      q[j] = musq[n];
-      sc[j] = sm[n];
-    }
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * Cfg::WM + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float4 rc = xs[min(m, M - 1)];
-        const float c1 = rc.z, c2 = rc.w;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-          const float v = fmaf(c1, sc[j] * (float)acc[i][j][r], fmaf(-c2, q[j], bias[j]));
-          if (nok[j]) mx = fmaxf(mx, v);
-        }
-        // over the 32 lanes of the half-wave (see LogitOp::epilogue)
-        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xf, 0xf, true)));
-        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xf, 0xf, true)));
-        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xf, 0xf, true)));
-        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xf, 0xf, true)));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        if (m < M && l32 == 0) smax[(int64_t)m * nps + (n0 + wn * Cfg::WN) / Cfg::WN] = mx;
-      }
-    }
-  }
-};
-
-// One workgroup per row tile of the exact GEMM: bounds from smax and the quantisers' figures -> live[row tile][column
-// tile].  Not screened (*on == 0): every tile is live.  spt: sub-tiles of smax per column tile.
-// counts (or NULL): [0] += tiles to compute, [1] += tiles, [4] += tiles of screened launches.
+// One workgroup per row tile of the exact GEMM: the bounds U, L above from the largest integer sums imax[row][group]
+// -> the tiles of this row tile that the exact GEMM has to compute, appended to the lists (list t % 8 for column tile
+// t), and -inf into the partial maxima of the others (pmax[row][np], gpt of them per column tile).  Not screened
+// (*on == 0): every tile.  spt: groups per column tile.  counts (or NULL): [0] += tiles to compute, [1] += tiles,
+// [4] += tiles of screened launches.
 __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __restrict__ n_dev, int n_max, int nps, int ntn,
-                                                                int spt, const float* __restrict__ smax,
-                                                                const float4* __restrict__ xs,
-                                                                const float2* __restrict__ grp,
+                                                                int spt, const int32_t* __restrict__ imax,
+                                                                const float2* __restrict__ xs,
+                                                                const float4* __restrict__ grp,
                                                                 const float4* __restrict__ coef_tau,
                                                                 const int32_t* __restrict__ tau,
                                                                 const int32_t* __restrict__ on,
-                                                                uint8_t* __restrict__ live,
+                                                                uint32_t* __restrict__ tile_list,
+                                                                int32_t* __restrict__ tile_count, int list_cap,
+                                                                float* __restrict__ pmax, int np, int gpt,
                                                                 unsigned long long* __restrict__ counts) {
   extern __shared__ int s_flag[];   // [ntn]
   constexpr int BM = GmmTileSplit::BM, RW = 4;   // rows a wavefront works on at a time (their loads overlap)
@@ -700,44 +656,65 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
   for (int t = threadIdx.x; t < ntn; t += 256) s_flag[t] = screened ? 0 : 1;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  // how far an exact logit may lie from its screened value s: the quantisation (ea sm + eb |mu^|_1 of the group)
-  // and an allowance for the roundings of the affine map, which the two GEMMs apply to different sums
-  auto slack = [](float s, float ea, float eb, float2 g) { return fmaf(ea, g.x, fmaf(eb, g.y, 0.5f)) + 1e-6f * fabsf(s); };
   if (screened) {
     for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
-      float ea[RW], eb[RW], lo[RW];
-      const float* s[RW];
+      float c1s[RW], c2[RW], ea[RW], eb[RW], lo[RW];
+      const int32_t* im[RW];
 #pragma unroll
       for (int k = 0; k < RW; ++k) {   // rows past the end repeat the last one: the same flags again
         const int m = min(m0 + r0 + k, n - 1);
-        s[k] = smax + (int64_t)m * nps;
-        const float4 rc = xs[m];
-        const float c1 = 0.5f * kScreenRound * LogitOp::kLog2e * coef_tau[tau[m]].x;
-        ea[k] = c1 * kScreenFp32 * rc.y;
-        eb[k] = c1 * rc.x;
+        im[k] = imax + (int64_t)m * nps;
+        const float2 rc = xs[m];
+        const float4 cf = coef_tau[tau[m]];
+        const float c1 = LogitOp::kLog2e * cf.x;
+        c1s[k] = c1 * rc.x;
+        c2[k] = LogitOp::kLog2e * cf.y;
+        ea[k] = 0.5f * kScreenRound * kScreenFp32 * c1 * rc.y;   // times sg
+        eb[k] = 0.5f * kScreenRound * c1 * rc.x;                 // times the group's largest |mu^|_1
         lo[k] = -INFINITY;
       }
+      // (base, e): kappa' sx sg I, and how far an exact logit may lie from what the bounds say -- the quantisation and
+      // an allowance for the roundings of these few operations and of the exact GEMM's affine map
+      auto bounds = [&](int k, int p, float4 g1, float& base, float& e) {
+        base = c1s[k] * g1.x * (float)im[k][p];
+        e = fmaf(ea[k], g1.x, fmaf(eb[k], g1.y, 0.5f)) + 1e-6f * (fabsf(base) + c2[k] * g1.w);
+      };
       for (int p = lane; p < nps; p += 64) {
-        const float2 g = grp[p];
+        const float4 g1 = grp[2 * p], g2 = grp[2 * p + 1];
 #pragma unroll
-        for (int k = 0; k < RW; ++k) lo[k] = fmaxf(lo[k], s[k][p] - slack(s[k][p], ea[k], eb[k], g));
+        for (int k = 0; k < RW; ++k) {
+          float base, e;
+          bounds(k, p, g1, base, e);
+          lo[k] = fmaxf(lo[k], base - c2[k] * g1.w + g2.x - e);
+        }
       }
 #pragma unroll
       for (int k = 0; k < RW; ++k) lo[k] = wave_max(lo[k]) - CombineOp::kZeroGap;
       for (int p = lane; p < nps; p += 64) {
-        const float2 g = grp[p];
+        const float4 g1 = grp[2 * p], g2 = grp[2 * p + 1];
         bool any = false;
 #pragma unroll
-        for (int k = 0; k < RW; ++k) any = any || (s[k][p] + slack(s[k][p], ea[k], eb[k], g) >= lo[k]);
+        for (int k = 0; k < RW; ++k) {
+          float base, e;
+          bounds(k, p, g1, base, e);
+          any = any || (base - c2[k] * g1.z + g2.y + e >= lo[k]);
+        }
         if (any) s_flag[p / spt] = 1;
       }
     }
     __syncthreads();
   }
   int mine = 0;
-  for (int t = threadIdx.x; t < ntn; t += 256) {
-    live[(int64_t)blockIdx.x * ntn + t] = (uint8_t)s_flag[t];
-    mine += s_flag[t];
+  for (int t = threadIdx.x; t < ntn; t += 256)
+    if (s_flag[t]) {
+      ++mine;
+      const int pos = atomicAdd(&tile_count[t % 8], 1);
+      if (pos < list_cap) tile_list[(int64_t)(t % 8) * list_cap + pos] = (uint32_t)(blockIdx.x * ntn + t);
+    }
+  if (screened) {   // the tiles left out: nothing will write their partial maxima
+    const int rows = min(BM, n - m0);
+    for (int i = threadIdx.x; i < rows * np; i += 256)
+      if (!s_flag[(i % np) / gpt]) pmax[(int64_t)m0 * np + i] = -INFINITY;
   }
   if (counts) {
     const int total = (int)wave_sum((float)mine);   // this wavefront's share; at most a few thousand: exact in fp32
@@ -893,24 +870,24 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     ASD_HIP(hipMalloc(&g->work_counts, 6 * sizeof(unsigned long long)));
     ASD_HIP(hipMemset(g->work_counts, 0, 6 * sizeof(unsigned long long)));
     // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
-    if (d % 128 == 0 && C % ScreenTile::BN == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
+    if (d % 128 == 0 && C % ScreenTile::BM == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
         split3_sparse_fits<GmmTileSplit>(C, np_v, GmmTileSplit::WN)) {
-      g->nps = C / ScreenTile::WN;
+      g->nps = C / kGroup;
       const int64_t row_tiles = ceil_div(ctx->n_rows_max, GmmTileSplit::BM);
       ASD_HIP(hipMalloc(&g->means_q, (size_t)C * d));
-      ASD_HIP(hipMalloc(&g->means_s, sizeof(float) * 2 * (size_t)C));
-      ASD_HIP(hipMalloc(&g->means_grp, sizeof(float2) * (size_t)g->nps));
+      ASD_HIP(hipMalloc(&g->means_grp, sizeof(float4) * 2 * (size_t)g->nps));
       ASD_HIP(hipMalloc(&g->xq, (size_t)ctx->n_rows_max * d));
-      ASD_HIP(hipMalloc(&g->xs, sizeof(float4) * (size_t)ctx->n_rows_max));
-      ASD_HIP(hipMalloc(&g->smax, sizeof(float) * (size_t)ctx->n_rows_max * g->nps));
-      ASD_HIP(hipMalloc(&g->tile_live, (size_t)row_tiles * (C / GmmTileSplit::BN)));
+      ASD_HIP(hipMalloc(&g->xs, sizeof(float2) * (size_t)ctx->n_rows_max));
+      ASD_HIP(hipMalloc(&g->imax, sizeof(int32_t) * (size_t)ctx->n_rows_max * g->nps));
+      g->list_cap = (int)(row_tiles * ceil_div(C / GmmTileSplit::BN, 8));
+      ASD_HIP(hipMalloc(&g->tile_list, sizeof(uint32_t) * 8 * (size_t)g->list_cap));
+      ASD_HIP(hipMalloc(&g->tile_count, kTicketInts * sizeof(int32_t)));
+      ASD_HIP(hipMemset(g->tile_count, 0, kTicketInts * sizeof(int32_t)));
       ASD_HIP(hipMalloc(&g->screen_on, 4 * sizeof(int32_t)));
       const int32_t on[4] = {1, 1, 0, 0};   // verdict, the constant 1, the regime kernel's two accumulators
       ASD_HIP(hipMemcpy(g->screen_on, on, sizeof(on), hipMemcpyHostToDevice));
-      hipLaunchKernelGGL(gmm_screen_quant_means_kernel, dim3((unsigned)ceil_div(C, 4)), dim3(256), 0, 0, C, d, g->means,
-                         g->means_q, g->means_s, g->means_s + C);
-      hipLaunchKernelGGL(gmm_screen_group_kernel, dim3((unsigned)ceil_div(g->nps, 256)), dim3(256), 0, 0, C,
-                         ScreenTile::WN, g->means_s, g->means_s + C, g->means_grp);
+      hipLaunchKernelGGL(gmm_screen_quant_means_kernel, dim3((unsigned)g->nps), dim3(256), 0, 0, C, d, g->means, g->musq,
+                         g->log_w, g->means_q, g->means_grp);
       ASD_HIP(hipGetLastError());
       ASD_HIP(hipDeviceSynchronize());
       g->screen_ok = true;
@@ -950,12 +927,12 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->logits);
   (void)hipFree(g->pmax);
   (void)hipFree(g->means_q);
-  (void)hipFree(g->means_s);
   (void)hipFree(g->means_grp);
   (void)hipFree(g->xq);
   (void)hipFree(g->xs);
-  (void)hipFree(g->smax);
-  (void)hipFree(g->tile_live);
+  (void)hipFree(g->imax);
+  (void)hipFree(g->tile_list);
+  (void)hipFree(g->tile_count);
   (void)hipFree(g->screen_on);
   (void)hipFree(g->work_counts);
   (void)hipFree(g->rmax);
@@ -1004,24 +981,26 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
     const int ntn = C / GmmTileSplit::BN;
     hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
-                       rows.in_base, rows.in_off, rows.tau, g->coef_tau, on, g->xq, g->xs);
+                       rows.in_base, rows.in_off, on, g->xq, g->xs, g->tile_count);
     ASD_HIP(hipGetLastError());
-    ScreenEpi epi{g->smax, g->nps, g->musq, g->log_w, g->xs, g->means_s, on};
-    // int8 operands, handed over as 16-bit units (two k each)
-    ASD_HIP(launch_gemm_bf16_nt_pipe<ScreenTile, 1>(rows.n_dev, n, C, d / 2, reinterpret_cast<const uint16_t*>(g->xq),
-                                                    d / 2, 0, reinterpret_cast<const uint16_t*>(g->means_q), d / 2, epi,
-                                                    st));
+    // int8 operands, handed over as 16-bit units (two k each): the means as the kernel's rows, the call's rows as its columns
+    ASD_HIP(launch_gemm_i8_colmax_stream<ScreenTile>(C, rows.n_dev, n, d / 2, reinterpret_cast<const uint16_t*>(g->means_q),
+                                                     d / 2, reinterpret_cast<const uint16_t*>(g->xq), d / 2, on, g->imax,
+                                                     g->nps, kScreenWgs, st));
     hipLaunchKernelGGL(gmm_screen_decide_kernel, dim3((unsigned)ceil_div(n, GmmTileSplit::BM)), dim3(256),
-                       sizeof(int) * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / ScreenTile::WN, g->smax,
-                       g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_live,
-                       ctx->prof.on ? g->work_counts : nullptr);
+                       sizeof(int) * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
+                       g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_list, g->tile_count, g->list_cap,
+                       g->pmax, np, GmmTileSplit::WGN, ctx->prof.on ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
-    op1.live = g->tile_live;
+    op1.tile_list = g->tile_list;
+    op1.tile_count = g->tile_count;
+    op1.list_cap = g->list_cap;
   }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
     if (split)
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st, 1,
+                                                                        nullptr, false, screen ? kResidentWgs : 0)
                         : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img_s,
                                                                                op1, st));
     else

@@ -39,14 +39,15 @@ struct GmmState {
   // all exactly zero; the exact GEMM skips them.
   bool screen_ok = false;          // the shape allows it (and the buffers below exist)
   int screen_mode = 1;             // 0: off, 1: when the draft call of the round found its posteriors collapsed, 2: always
-  int8_t* means_q = nullptr;       // [C, d] quantised means
-  float* means_s = nullptr;        // [2 C]: their scales, then the 1-norms of the quantised means
-  float2* means_grp = nullptr;     // [nps] largest of either over each sub-tile of columns
+  int8_t* means_q = nullptr;       // [C, d] quantised means, one scale per group of components
+  float4* means_grp = nullptr;     // [2 nps] per group: scale, largest 1-norm, range of |mu|^2; range of log2 w
   int8_t* xq = nullptr;            // [rows_max, d] the call's rows, quantised
-  float4* xs = nullptr;            // [rows_max]: scale, 1-norm, the row's two factors of the affine map
-  float* smax = nullptr;           // [rows_max, nps] screened row maxima per sub-tile
-  int nps = 0;
-  uint8_t* tile_live = nullptr;    // [row tiles][column tiles]
+  float2* xs = nullptr;            // [rows_max]: scale, 1-norm
+  int32_t* imax = nullptr;         // [rows_max, nps] largest integer sum per row and group
+  int nps = 0;                     // groups of components
+  uint32_t* tile_list = nullptr;   // [8][list_cap] tiles of logits to compute, by column tile modulo 8
+  int32_t* tile_count = nullptr;   // the lists' lengths and the tickets drawn from each (layout: gemm_split3.h)
+  int list_cap = 0;
   int32_t* screen_on = nullptr;    // DEV [4]: the draft call's verdict for this round; the constant 1; two accumulators
   size_t rowwise_lds = 0;
   size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)

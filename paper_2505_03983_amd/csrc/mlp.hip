@@ -173,7 +173,7 @@ struct InEpi {  // h = acc + b; hb = bf16 terms of h
   const float* bias;
   int64_t ld, ldb;  // pitch of h (fp32) and of hb (bf16)
   int64_t lo_plane; // > 0: offset of hb's second plane (two-term activations)
-  static constexpr bool kLoads = false, kRowMax = false;
+  static constexpr bool kLoads = false;
   // four consecutive columns n..n+3 (n % 4 == 0) of row m
   __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
@@ -190,7 +190,7 @@ struct BlockEpi {  // h += SiLU(acc + b); hb_next = bf16 terms of h
   const float* bias;
   int64_t ld, ldb;
   int64_t lo_plane;
-  static constexpr bool kLoads = true, kRowMax = false;
+  static constexpr bool kLoads = true;
   __device__ __forceinline__ float4 load4(int m, int n) const {
     return *reinterpret_cast<const float4*>(h + (int64_t)m * ld + n);
   }
@@ -214,7 +214,7 @@ struct OutEpi {  // out[out_off[m] + n] = acc + b, as x_0 (or converted from a n
   const int32_t* tau;
   const float* in_base;
   const int64_t* in_off;
-  static constexpr bool kLoads = false, kRowMax = false;
+  static constexpr bool kLoads = false;
   __device__ __forceinline__ float4 load4(int, int) const { return make_float4(0.f, 0.f, 0.f, 0.f); }
   __device__ __forceinline__ void store4(int m, int n, float4 a, float4) const {
     const float4 b = load_bias4(bias, n);
