@@ -202,7 +202,9 @@ static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
 }
 
 static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
-  const int per_chain = ctx->L - 1 + (ctx->reuse_now ? 1 : 0);   // tested slots, plus yhat_b with model-call reuse
+  int per_chain = ctx->L - 1 + (ctx->reuse_now ? 1 : 0);   // tested slots, plus yhat_b with model-call reuse
+  const int block = ctx->cur_win ? 0 : model_row_block(ctx);    // the planner's filling of each chain's block (launch_plan_verify)
+  if (block > 0) per_chain = (per_chain + block - 1) / block * block;
   return RowPlan{ctx->B * per_chain, ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
 }
 

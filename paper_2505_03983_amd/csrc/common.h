@@ -193,6 +193,10 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den);
 void mlp_destroy(asd_ctx* ctx);
 asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
 
+// Rows per chain block the denoiser would like the verify call's plan laid out in (0: as they come): see gmm.hip.
+int gmm_row_block(const asd_ctx* ctx);
+inline int model_row_block(const asd_ctx* ctx) { return ctx->kind == ASD_DEN_GMM ? gmm_row_block(ctx) : 0; }
+
 inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   if (rows.n <= 0) return ASD_OK;
   ProfScope ps(ctx, ASD_PROF_MODEL, rows.call, st);

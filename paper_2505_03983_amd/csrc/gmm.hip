@@ -913,6 +913,16 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
   return ASD_OK;
 }
 
+// The screened verify call works on 128 x 128 tiles of (rows, components) and can leave out a tile only if all its
+// rows agree that its components are irrelevant.  Rows of one chain do (its window sits on one component once the
+// posterior has collapsed); with each chain's rows starting at a multiple of 64 a tile holds two chains, not three.
+// Only when the filling cannot overflow the plan: windows of at most L - 1 rows (+ 1 with reuse) fit L = 64 m.
+int gmm_row_block(const asd_ctx* ctx) {
+  const GmmState* g = ctx->gmm;
+  const bool screening = g && g->use_split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine;
+  return (screening && ctx->L % 64 == 0) ? 64 : 0;
+}
+
 void gmm_destroy(asd_ctx* ctx) {
   GmmState* g = ctx->gmm;
   if (!g) return;

@@ -109,9 +109,13 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          int32_t* __restrict__ ring,
                                                          int64_t* __restrict__ row_counts,
                                                          const int32_t* __restrict__ win,
-                                                         const int32_t* __restrict__ carry, int extra, int slots) {
+                                                         const int32_t* __restrict__ carry, int extra, int slots,
+                                                         int pad) {
   // carry (draft call): chains whose x0a was handed over by the last round are not listed.  extra (verify call):
   // 1 = also list the last proposal sample yhat_b of a window that ends before K.  slots: slots per chain of x0hat.
+  // pad (verify call; 0 = none): every chain's rows start at a multiple of `pad` rows -- its block is filled up with
+  // repeats of its last row (same input, same output address, same value) -- so that a row tile of the model call
+  // holds rows of few chains: what a tile of the mixture denoiser can leave out depends on how alike its rows are.
   __shared__ int s_wave[16];
   __shared__ int s_total;
   __shared__ int s_off[1024], s_cnt[1024], s_ac[1024];
@@ -122,8 +126,9 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     ring[0] = r + 1;
     ring[1 + (r % kLiveRing)] = 0;
   }
+  __shared__ int s_pc[1024];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int base = 0;
+  int base = 0, real = 0;
   for (int c0 = 0; c0 < B; c0 += 1024) {
     const int c = c0 + threadIdx.x;
     int ac = K, cnt = 0;
@@ -134,7 +139,15 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
         cnt = (MODE == 0) ? ((carry && carry[c]) ? 0 : 1) : w - 1 + ((extra && ac + w < K) ? 1 : 0);
       }
     }
-    const int off = base + block_exclusive_scan(cnt, s_wave, &s_total);
+    // rows of the chain's block (a window cut short by the end of the chain is not worth filling up: the blocks
+    // behind it merely lose their alignment)
+    const int pc = (MODE == 1 && pad > 0 && 2 * cnt > pad) ? (cnt + pad - 1) / pad * pad : cnt;
+    if (MODE == 1 && pad > 0) {   // the rows asked for, without the filling
+      (void)block_exclusive_scan(cnt, s_wave, &s_total);
+      real += s_total;
+      __syncthreads();
+    }
+    const int off = base + block_exclusive_scan(pc, s_wave, &s_total);
     if (MODE == 0) {
       if (cnt) {
         in_off[off] = ((int64_t)c * (K + 1) + ac) * d;
@@ -145,16 +158,18 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
       // the rows of a chain are written by a whole wavefront (consecutive entries, coalesced)
       s_off[threadIdx.x] = off;
       s_cnt[threadIdx.x] = cnt;
+      s_pc[threadIdx.x] = pc;
       s_ac[threadIdx.x] = ac;
       __syncthreads();
       // (every workgroup of the launch computes the whole scan -- it is a thousand integers -- and fills the rows of
       // its share of the chains, so nothing has to pass between workgroups)
       for (int t = wave + 16 * (int)blockIdx.x; t < 1024 && c0 + t < B; t += 16 * (int)gridDim.x) {
-        const int n_t = s_cnt[t], o_t = s_off[t], a_t = s_ac[t], c_t = c0 + t;
-        for (int s = 1 + lane; s <= n_t; s += 64) {
-          const int i = a_t + s;
+        const int n_t = s_cnt[t], p_t = s_pc[t], o_t = s_off[t], a_t = s_ac[t], c_t = c0 + t;
+        for (int s = 1 + lane; s <= p_t; s += 64) {
+          const int sr = min(s, n_t);   // past the chain's rows: its last row again
+          const int i = a_t + sr;
           in_off[o_t + s - 1] = ((int64_t)c_t * (K + 1) + i) * d;
-          out_off[o_t + s - 1] = ((int64_t)c_t * slots + s) * d;
+          out_off[o_t + s - 1] = ((int64_t)c_t * slots + sr) * d;
           row_tau[o_t + s - 1] = tau[i];
         }
       }
@@ -164,7 +179,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
   }
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     *n_rows = base;
-    if (row_counts) atomicAdd((unsigned long long*)&row_counts[MODE], (unsigned long long)base);
+    if (row_counts) atomicAdd((unsigned long long*)&row_counts[MODE], (unsigned long long)((MODE == 1 && pad > 0) ? real : base));
   }
 }
 
@@ -173,7 +188,7 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, ring,
                      ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win,
-                     ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L);
+                     ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L, 0);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -186,7 +201,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
                      ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
-                     ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0));
+                     ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0), ctx->cur_win ? 0 : model_row_block(ctx));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
