@@ -347,20 +347,27 @@ def test_logit_screen_is_bit_identical_and_skips_work():
     torch.cuda.synchronize()
     assert torch.equal(out, outs[0])
     ctx.use_sparse_combine(True)
-    # (b) whole samples
-    res = []
-    for mode in (0, 1, 2):
-        ctx.use_logit_screen(mode)
-        ctx.set_seed(5)
-        traj = runtime.alloc_traj(ctx)
-        rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
-        ctx.sample(traj, rounds)
-        torch.cuda.synchronize()
-        res.append((traj, rounds))
-    for traj, rounds in res[1:]:
-        assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
-    assert bool(torch.isfinite(res[0][0]).all())
-    ctx.close()
+    # (b) whole samples: this shape, and the shape of the largest workload with fewer chains (windows of 64: the
+    # verify plan then lays the chains' rows out in blocks of 64, repeats of a chain's last row filling its block)
+    for cfg_b, ctx_b in ((cfg, ctx), (dict(W.CONFIGS[5], chains=48), None)):
+        if ctx_b is None:
+            ctx_b = runtime.open_ctx(cfg_b, W.make_params(cfg_b, 1), seed=0)
+            assert ctx_b.logit_screen_active() == 1
+        res = []
+        for mode in (0, 1, 2):
+            ctx_b.use_logit_screen(mode)
+            ctx_b.set_seed(5)
+            traj = runtime.alloc_traj(ctx_b)
+            rounds = torch.zeros(cfg_b["chains"], dtype=torch.int32, device=DEV)
+            ctx_b.sample(traj, rounds)
+            torch.cuda.synchronize()
+            res.append((traj, rounds))
+        for traj, rounds in res[1:]:
+            assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
+        assert bool(torch.isfinite(res[0][0]).all())
+        _log("logit screen: whole samples of d", cfg_b["d"], "C", cfg_b["C"], "bit-identical in the three modes, rounds max",
+             int(res[0][1].max()))
+        ctx_b.close()
 
 
 def test_mfma_ceiling_probe():
