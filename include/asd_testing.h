@@ -22,7 +22,8 @@ ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 /* The second GEMM of the split-operand mixture denoiser (softmax weights times means) skips the stretches of
  * components whose weights are exactly 0.0f for every row of a tile (2^(logit - row maximum) underflows once a
  * posterior has collapsed).  The skipped products are zeros, so results are identical bit for bit; on = 0 makes
- * the kernel visit every component anyway (for tests and timing comparisons).  Default: on. */
+ * the kernel visit every component anyway (for tests and timing comparisons).  Default: on.  The same switch covers
+ * the closed form for rows with a single non-zero weight (asd_profile_model_work). */
 ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);
 
 /* Screening of the verify call's first GEMM in the split-operand mixture denoiser: an int8 GEMM with a
@@ -50,7 +51,10 @@ ASD_API asd_status asd_debug_randoms(uint64_t seed, uint32_t chain, uint32_t ste
  * returns, for one kernel kind within one of the two model calls (call = 0:
  * the draft call on one row per chain, call = 1: the batched verify call;
  * kinds that belong to no model call use call = 0), the number of launches
- * and their summed duration since the last asd_profile_enable(ctx, 1).
+ * and their summed duration since the last asd_profile_enable(ctx, on).
+ * on = 1 times the kernels of the denoisers and the draft and accept kernels; on = 2 also the scopes around
+ * them (ASD_PROF_MODEL: a whole model call) and the row planning (ASD_PROF_PLAN) -- every scope costs two
+ * events on the stream, a few microseconds each, which shows in a round of a millisecond.
  * asd_profile_rows returns the number of live rows (rows inside a window of an
  * unfinished chain) the two model calls were asked to evaluate since then. */
 typedef enum {
@@ -81,9 +85,13 @@ ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows,
  * were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
  * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
  * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine).
- * screened_tiles: the part of logit_tiles that belongs to calls the screening GEMM ran for. */
+ * (Workgroups of row tiles written in closed form count in neither.)
+ * screened_tiles: the part of logit_tiles that belongs to calls the screening GEMM ran for.
+ * onehot_row_tiles: tiles of 128 rows whose rows all have one softmax weight of 1.0 and zeros, which the second GEMM
+ * leaves to a kernel that writes  c_x' x + c_m' mu_b  directly (same switch as the sparse second GEMM). */
 ASD_API asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
-                                          int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles);
+                                          int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles,
+                                          int64_t* onehot_row_tiles);
 
 #ifdef __cplusplus
 }

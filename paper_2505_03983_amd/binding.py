@@ -72,7 +72,7 @@ def lib():
             "asd_use_sparse_combine": (i32, [vp, i32]),
             "asd_use_logit_screen": (i32, [vp, i32]),
             "asd_logit_screen_active": (i32, [vp]),
-            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp]),
+            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp, vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_use_split_gemm": (i32, [vp, i32]),
@@ -293,7 +293,8 @@ class Ctx:
         _check(lib().asd_sample_sequential(self.h, _ptr(y0), _ptr(traj), _stream(stream)))
 
     def profile_enable(self, on=True):
-        _check(lib().asd_profile_enable(self.h, int(bool(on))))
+        """on: False / True (the denoisers' kernels, draft, accept) / 2 (also whole model calls and row planning)."""
+        _check(lib().asd_profile_enable(self.h, int(on)))
 
     def profile_read(self, kernel, call=0):
         n, ms = C.c_int64(0), C.c_double(0.0)
@@ -306,9 +307,9 @@ class Ctx:
         return a.value, b.value
 
     def profile_model_work(self):
-        """(logit tiles computed, logit tiles, combine slabs visited, combine slabs, logit tiles of screened calls)
-        of the verify calls."""
-        v = [C.c_int64(0) for _ in range(5)]
+        """(logit tiles computed, logit tiles, combine slabs visited, combine slabs, logit tiles of screened calls,
+        row tiles written in closed form) of the verify calls."""
+        v = [C.c_int64(0) for _ in range(6)]
         _check(lib().asd_profile_model_work(self.h, *[C.addressof(x) for x in v]))
         return tuple(x.value for x in v)
 

@@ -567,6 +567,7 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ASD_HIP(hipDeviceSynchronize());
   ctx->prof.reset();
   ctx->prof.on = on != 0;
+  ctx->prof.outer = on >= 2;
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
   if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 6 * sizeof(unsigned long long)));
   return ASD_OK;
@@ -609,12 +610,13 @@ asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t
 }
 
 asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
-                                  int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles) {
+                                  int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles,
+                                  int64_t* onehot_row_tiles) {
   ASD_TRY(check_ctx(ctx));
   unsigned long long h[6] = {0, 0, 0, 0, 0, 0};
   if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemcpy(h, ctx->gmm->work_counts, sizeof(h), hipMemcpyDeviceToHost));
-  int64_t* out[5] = {logit_tiles_done, logit_tiles, combine_slabs_done, combine_slabs, screened_tiles};
-  for (int i = 0; i < 5; ++i)
+  int64_t* out[6] = {logit_tiles_done, logit_tiles, combine_slabs_done, combine_slabs, screened_tiles, onehot_row_tiles};
+  for (int i = 0; i < 6; ++i)
     if (out[i]) *out[i] = (int64_t)h[i];
   return ASD_OK;
 }

@@ -73,6 +73,7 @@ struct Profiler {
     hipEvent_t e0, e1;
   };
   bool on = false;
+  bool outer = false;   // also time the scopes that enclose other scopes (a whole model call) and the row planning
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   size_t used = 0;
@@ -168,6 +169,7 @@ struct ProfScope {
   int slot;
   ProfScope(asd_ctx* c, int kernel, int call, hipStream_t s) : ctx(c), st(s), slot(kernel + 16 * call) {
     if (!ctx->prof.on) return;
+    if ((kernel == ASD_PROF_MODEL || kernel == ASD_PROF_PLAN) && !ctx->prof.outer) return;
     e0 = ctx->prof.take();
     e1 = ctx->prof.take();
     if (e0 && e1) (void)hipEventRecord(e0, st);

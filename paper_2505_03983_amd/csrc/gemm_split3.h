@@ -141,7 +141,8 @@ inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K
 
 // The Op interface is that of gemm_f32.h (init / load_a / finish / epilogue); load_a is applied when
 // the values are split, not when they are loaded.  An Op with kTileList may carry lists of the output tiles
-// that are wanted (tile_list, tile_count, list_cap: in device memory); see the list form of the kernel.
+// that are wanted (tile_list, tile_count, list_cap: in device memory); see the list form of the kernel.  An Op with
+// kRowTileSkip may declare the rows of a tile somebody else's business (skip_row_tile).
 //
 // Tile order.  Workgroups go to the 8 XCDs round-robin by linear id (x fastest).  ROWS_PER_XCD = false: blockIdx.x
 // = column tile, so an XCD keeps a fixed set of column tiles (its share of B stays in its L2) and every XCD
@@ -164,6 +165,9 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
 
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   if (m0 >= M) return;
+  if constexpr (Op::kRowTileSkip) {
+    if (op.skip_row_tile(m0)) return;   // the same for the whole workgroup: someone else writes these rows
+  }
 
   // (opaque to the optimiser: when this is called in a loop over tiles, everything derived from the thread index
   // below would otherwise be hoisted out of that loop and held in registers across it, which the K loop has none

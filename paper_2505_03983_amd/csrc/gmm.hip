@@ -236,6 +236,7 @@ struct LogitOp {
   static constexpr bool kSplitK = false;
   static constexpr bool kSparseK = false;
   static constexpr bool kTileList = true;
+  static constexpr bool kRowTileSkip = false;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -331,6 +332,11 @@ struct CombineOp {
   const float* rmax_pre = nullptr;
   const uint8_t* live_pre = nullptr;
   static constexpr int kRowmaxTile = 128;
+  // NULL, or [row tiles of kRowmaxTile rows]: 1 = every row of the tile has one weight of 1.0 and zeros, and
+  // gmm_onehot_kernel writes its results in closed form (below): the tile's workgroups have nothing to do
+  const uint8_t* onehot_tile = nullptr;
+  static constexpr bool kRowTileSkip = true;
+  __device__ __forceinline__ bool skip_row_tile(int m0) const { return onehot_tile && onehot_tile[m0 / kRowmaxTile] != 0; }
   __host__ __device__ __forceinline__ int groups() const { return np; }
   __host__ __device__ __forceinline__ int group_cols() const { return gcols; }
   template <class Cfg>
@@ -471,15 +477,29 @@ struct CombineOp {
 // Between the two GEMMs of a verify call: the maximum of every row over its partial maxima, and for every row
 // tile the column groups that are live for one of its rows (CombineOp::mark_live's rule) -- once, instead of by
 // each of the second GEMM's workgroups that share the row tile (d / 128 of them, each scanning 32 KB).
+//
+// One-hot rows (onehot != NULL; needs np <= 64 and column groups of 64).  Once a posterior has collapsed a row has
+// exactly one logit within kZeroGap of its maximum -- the maximum itself.  Its weights are then 2^0 = 1.0 for that
+// component b and exact zeros elsewhere, the row sum is 1.0, and the second GEMM's result for it is mu_b bit for bit
+// (the three bf16 terms of mu_b times 1.0, added in an order in which every partial sum is exact; all other
+// products are zeros), so  out = fma(c_x', x, c_m' mu_b)  needs no GEMM.  A row's few live groups are scanned for
+// that (rows with more than two live groups are not candidates): onehot[row] = b or -1, and onehot_tile[row tile] =
+// 1 when all its rows qualify -- the second GEMM then skips the tile and gmm_onehot_kernel writes it.
 __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__ n_dev, int n_max, int np,
                                                          const float* __restrict__ pmax, float* __restrict__ rmax,
-                                                         uint8_t* __restrict__ glive) {
-  extern __shared__ int s_any[];   // [np]
+                                                         uint8_t* __restrict__ glive,
+                                                         const float* __restrict__ logits, int64_t ldl, int gcols,
+                                                         int32_t* __restrict__ onehot, uint8_t* __restrict__ onehot_tile,
+                                                         unsigned long long* __restrict__ counts) {
+  // counts (or NULL): [5] += row tiles found one-hot
+  extern __shared__ int s_any[];   // [np], then one flag: every row so far is one-hot
   constexpr int BM = CombineOp::kRowmaxTile, RW = 4;
   const int n = min(*n_dev, n_max);
   const int m0 = blockIdx.x * BM;
   if (m0 >= n) return;
+  const bool want_onehot = onehot && np <= 64 && gcols == 64;
   for (int q = threadIdx.x; q < np; q += 256) s_any[q] = 0;
+  if (threadIdx.x == 0) s_any[np] = want_onehot ? 1 : 0;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
@@ -504,9 +524,64 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
       for (int k = 0; k < RW; ++k) any = any || (p[k][q] >= mx[k] - CombineOp::kZeroGap);
       if (any) s_any[q] = 1;
     }
+    if (want_onehot) {
+#pragma unroll
+      for (int k = 0; k < RW; ++k) {
+        const int row = m0 + r0 + k;
+        if (row >= n) continue;   // the same for the whole wavefront
+        const float thr = mx[k] - CombineOp::kZeroGap;
+        unsigned long long groups = __ballot(lane < np && p[k][lane] >= thr);
+        int count = 0, b = -1;
+        if (__popcll(groups) <= 2) {
+          while (groups) {
+            const int g = __ffsll((long long)groups) - 1;
+            groups &= groups - 1;
+            const float v = logits[(int64_t)row * ldl + g * 64 + lane];
+            count += __popcll(__ballot(v >= thr));
+            const unsigned long long at_max = __ballot(v == mx[k]);
+            if (at_max) b = g * 64 + __ffsll((long long)at_max) - 1;
+          }
+        }
+        const bool one = count == 1 && b >= 0;
+        if (lane == 0) {
+          onehot[row] = one ? b : -1;
+          if (!one) s_any[np] = 0;
+        }
+      }
+    }
   }
   __syncthreads();
   for (int q = threadIdx.x; q < np; q += 256) glive[(int64_t)blockIdx.x * np + q] = (uint8_t)s_any[q];
+  if (onehot_tile && threadIdx.x == 0) {
+    onehot_tile[blockIdx.x] = (uint8_t)s_any[np];
+    if (counts && s_any[np]) atomicAdd(&counts[5], 1ull);
+  }
+}
+
+// The rows of the one-hot tiles, in closed form (see gmm_rowmax_kernel): one workgroup per row.
+__global__ __launch_bounds__(256) void gmm_onehot_kernel(const int* __restrict__ n_dev, int n_max, int d,
+                                                         const int32_t* __restrict__ onehot,
+                                                         const uint8_t* __restrict__ onehot_tile,
+                                                         const float* __restrict__ means,
+                                                         const float* __restrict__ in_base,
+                                                         const int64_t* __restrict__ in_off,
+                                                         float* __restrict__ out_base,
+                                                         const int64_t* __restrict__ out_off,
+                                                         const float4* __restrict__ coef_tau,
+                                                         const int32_t* __restrict__ tau) {
+  const int m = blockIdx.x;
+  if (m >= min(*n_dev, n_max) || !onehot_tile[m / CombineOp::kRowmaxTile]) return;
+  const float4 cf = coef_tau[tau[m]];
+  const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
+  const float4* mu = reinterpret_cast<const float4*>(means + (int64_t)onehot[m] * d);
+  float4* o = reinterpret_cast<float4*>(out_base + out_off[m]);
+  // what the second GEMM's epilogue computes with acc = mu_b (+0.0: the accumulator never holds a negative zero)
+  // and scale = c_m' / 1.0
+  for (int j = threadIdx.x; j < d / 4; j += 256) {
+    const float4 xv = x[j], mv = mu[j];
+    o[j] = make_float4(fmaf(cf.z, xv.x, __fmul_rn(cf.w, mv.x + 0.f)), fmaf(cf.z, xv.y, __fmul_rn(cf.w, mv.y + 0.f)),
+                       fmaf(cf.z, xv.z, __fmul_rn(cf.w, mv.z + 0.f)), fmaf(cf.z, xv.w, __fmul_rn(cf.w, mv.w + 0.f)));
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -867,6 +942,8 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     const int np_v = GmmTileSplit::WGN * (int)ceil_div(C, GmmTileSplit::BN);   // partial maxima per row, verify call
     ASD_HIP(hipMalloc(&g->rmax, sizeof(float) * (size_t)ctx->n_rows_max));
     ASD_HIP(hipMalloc(&g->glive, (size_t)ceil_div(ctx->n_rows_max, CombineOp::kRowmaxTile) * np_v));
+    ASD_HIP(hipMalloc(&g->onehot, sizeof(int32_t) * (size_t)ctx->n_rows_max));
+    ASD_HIP(hipMalloc(&g->onehot_tile, (size_t)ceil_div(ctx->n_rows_max, CombineOp::kRowmaxTile)));
     ASD_HIP(hipMalloc(&g->work_counts, 6 * sizeof(unsigned long long)));
     ASD_HIP(hipMemset(g->work_counts, 0, 6 * sizeof(unsigned long long)));
     // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
@@ -947,6 +1024,8 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->work_counts);
   (void)hipFree(g->rmax);
   (void)hipFree(g->glive);
+  (void)hipFree(g->onehot);
+  (void)hipFree(g->onehot_tile);
   delete g;
   ctx->gmm = nullptr;
 }
@@ -1025,14 +1104,25 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   RowSrc P{g->logits, nullptr, C};
   // columns behind one partial row maximum: the first GEMM's wavefront sub-tile width (the last group may be short)
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
-  CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
+  CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
                 rows.tau, (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
+    // one-hot rows in closed form: with the sparse second GEMM only (the same switch), whole float4 rows
+    const bool onehot = split && rows.call == 1 && g->sparse_combine && d % 4 == 0 && np <= 64 && gcols == 64;
     if (split && rows.call == 1) {   // row maxima and live groups once per row tile
       hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
-                         sizeof(int) * np, st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive);
+                         sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
+                         gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
+                         ctx->prof.on ? g->work_counts : nullptr);
       ASD_HIP(hipGetLastError());
+      if (onehot) {
+        hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
+                           g->onehot_tile, g->means, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
+                           rows.tau);
+        ASD_HIP(hipGetLastError());
+        op2.onehot_tile = g->onehot_tile;
+      }
       op2.rmax_pre = g->rmax;
       op2.live_pre = g->glive;
     }

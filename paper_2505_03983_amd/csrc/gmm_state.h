@@ -19,6 +19,8 @@ struct GmmState {
   int np = 0;
   float* rmax = nullptr;         // [rows_max] row maxima of the verify call's logits (split-operand path)
   uint8_t* glive = nullptr;      // [row tiles][np] column groups that are live for a row of the tile
+  int32_t* onehot = nullptr;     // [rows_max] the one component with a non-zero weight, or -1
+  uint8_t* onehot_tile = nullptr;  // [row tiles] every row of the tile is one-hot: written in closed form, no GEMM
   float* part = nullptr;         // split-K scratch of the draft call's second GEMM: [splits][chains][d] tiles, [splits][chains] sums
   int draft_splits = 1;
   bool use_mfma = false;
@@ -32,7 +34,7 @@ struct GmmState {
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
   // DEV [6], summed over the verify calls while profiling: tiles of logits computed / there were (calls that went
   // through the screening launches), K slabs the second GEMM's workgroups visited / there were, tiles of the calls
-  // that were screened, unused
+  // that were screened, row tiles of the second GEMM written in closed form (one-hot rows)
   unsigned long long* work_counts = nullptr;
   bool sparse_combine = true;      // the second split GEMM of the verify call skips slabs of exact zeros (gemm_split3.h)
   // Screening of the verify call's logits GEMM (gmm.hip): an int8 GEMM finds the tiles whose softmax weights are
