@@ -177,7 +177,8 @@ def roofline(res, w=None, kernel=None):
     busy the pipe in use is); `method` carries the 2*C*d figure and its ratio to the fp32 MFMA peak.
     Both split-operand GEMMs leave out work whose result is known to be exact zeros (tiles of logits far below
     their rows' maxima, found by the screening pass; slabs of components with zero weights): what they executed
-    is then counted by the device (128 x 128 tiles, slabs of 16 components per tile) and not inferred from rows."""
+    is then counted by the device (half tiles of 64 rows x 128 components, slabs of 16 components per tile) and not
+    inferred from rows."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
     executed_per_method = 1.0
@@ -196,7 +197,7 @@ def roofline(res, w=None, kernel=None):
             executed_per_method = 6.0
             done, tiles, slabs_done, slabs = res.get("model_work", (0, 0, 0, 0, 0, 0))[:4]
             if name == "GMM_LOGITS/verify" and tiles:
-                executed_flops = 6.0 * 2.0 * 128 * 128 * cfg["d"] * done / launches
+                executed_flops = 6.0 * 2.0 * 64 * 128 * cfg["d"] * done / launches      # counted in half tiles of 64 rows
             if name == "GMM_COMBINE/verify" and slabs:
                 executed_flops = 6.0 * 2.0 * 128 * 128 * 16 * slabs_done / launches
     else:
@@ -235,16 +236,16 @@ def roofline(res, w=None, kernel=None):
 
 def logit_screen(res):
     """The int8 screening pass of the mixture denoiser's verify calls: its cost, what it saved, and how busy it keeps
-    the int8 matrix pipe (2 * 128 * 128 * d operations per screened tile against the 5 POP/s data-sheet peak)."""
+    the int8 matrix pipe (2 * 64 * 128 * d operations per screened half tile against the 5 POP/s data-sheet peak)."""
     k = res["kernels"]
     if not res.get("screen_mode") or "GMM_SCREEN/verify" not in k:
         return dict(mode=res.get("screen_mode", 0))
     done, tiles, _, _, screened, onehot = res["model_work"]
     s = k["GMM_SCREEN/verify"]
-    ops = 2.0 * 128 * 128 * res["cfg"]["d"] * screened
+    ops = 2.0 * 64 * 128 * res["cfg"]["d"] * screened
     return dict(mode=res["screen_mode"], launches=s["launches"], total_ms=s["total_ms"],
                 share_of_wall=1e-3 * s["total_ms"] / res["wall_s"],
-                logit_tiles=tiles, logit_tiles_of_screened_calls=screened, logit_tiles_computed=done,
+                logit_half_tiles=tiles, logit_half_tiles_of_screened_calls=screened, logit_half_tiles_computed=done,
                 computed_share=done / tiles if tiles else None,
                 row_tiles_of_second_gemm_in_closed_form=onehot,
                 int8_tops=ops / (1e-3 * s["total_ms"]) / 1e12 if screened else 0.0, int8_peak_tops=PEAK["i8"],

@@ -81,8 +81,8 @@ ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* 
  * chain-round that ended in a rejection). */
 ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t* resampled_rows);
 /* Matrix work the mixture denoiser's verify calls left out since then (split-operand kernels only; all zero
- * otherwise).  logit_tiles_done / logit_tiles: 128 x 128 tiles of logits the first GEMM computed and how many there
- * were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
+ * otherwise).  logit_tiles_done / logit_tiles: half tiles (64 rows x 128 components) of logits the first GEMM computed
+ * and how many there were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
  * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
  * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine).
  * (Workgroups of row tiles written in closed form count in neither.)

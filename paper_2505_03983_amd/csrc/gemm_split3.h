@@ -381,20 +381,27 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const i
 }
 
 // The list form, for an Op with kTileList that carries lists of the wanted tiles: tile_list = 8 lists of list_cap
-// entries (entry = row tile * column tiles + column tile), tile_count[q] = length of list q, and a ticket counter per
-// list at tile_count[kTicketBase + kTicketStride * q], zero at launch (each on a cache line of its own: read-modify-
-// write operations on one line are served one after the other, some 60 ns each).  Any number of workgroups (a
-// multiple of 8) stay resident and draw tiles by ticket.  The lists are by column tile modulo 8 and workgroup w
-// starts on list w % 8 -- its XCD's, so an XCD keeps to its share of B, as in the grid order -- and moves on to the
-// next list when one has run dry, so the launch ends evenly.  Nothing is launched for the tiles that are not wanted,
-// which matters when those are nearly all.
+// entries, tile_count[q] = length of list q, and a ticket counter per list at tile_count[kTicketBase + kTicketStride *
+// q], zero at launch (each on a cache line of its own: read-modify-write operations on one line are served one after
+// the other, some 60 ns each).  Any number of workgroups (a multiple of 8) stay resident and draw tiles by ticket.
+// The lists are by column tile modulo 8 and workgroup w starts on list w % 8 -- its XCD's, so an XCD keeps to its
+// share of B, as in the grid order -- and moves on to the next list when one has run dry, so the launch ends evenly.
+// Nothing is launched for the tiles that are not wanted, which matters when those are nearly all.
+// An entry is  row tile * column tiles + column tile  of Cfg's tile grid; with kListHalf set it names only the upper
+// (kListLower clear) or lower half of that tile's rows, which is then computed as a tile of CfgH (half the rows, the
+// same columns, its own image of B): when the rows of a half have nothing in common with the other half's, one of
+// them usually needs the tile and the other does not.
 constexpr int kTicketBase = 32, kTicketStride = 32, kTicketInts = kTicketBase + 8 * kTicketStride;
-template <class Cfg, class Op, int CALL>
+constexpr uint32_t kListHalf = 1u << 31, kListLower = 1u << 30, kListIndex = kListLower - 1;
+template <class Cfg, class CfgH, class Op, int CALL>
 __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_list_kernel(const int* __restrict__ M_dev, int M_max,
                                                                               int N, int K, RowSrc A,
-                                                                              const uint8_t* __restrict__ Bimg, Op op) {
+                                                                              const uint8_t* __restrict__ Bimg,
+                                                                              const uint8_t* __restrict__ BimgH, Op op) {
+  static_assert(CfgH::BM * 2 == Cfg::BM && CfgH::BN == Cfg::BN && CfgH::THREADS == Cfg::THREADS, "half tiles");
+  constexpr size_t kLds = Cfg::LDS_BYTES > CfgH::LDS_BYTES ? Cfg::LDS_BYTES : CfgH::LDS_BYTES;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
-  int* s_ticket = reinterpret_cast<int*>(lds_all + Cfg::LDS_BYTES);   // the launcher adds 16 bytes for it
+  int* s_ticket = reinterpret_cast<int*>(lds_all + kLds);   // the launcher adds 16 bytes for it
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
   const int ntn = (N + Cfg::BN - 1) / Cfg::BN;
   int lists_done = 0;   // thread 0: lists this workgroup has found dry
@@ -422,7 +429,11 @@ __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_list_kernel(co
     int nxt = -1;
     if (threadIdx.x == 0) nxt = draw();
     const uint32_t e = (uint32_t)__builtin_amdgcn_readfirstlane((int)op.tile_list[cur]);
-    split3_tile<Cfg, Op>(M, M_max, N, K, A, Bimg, op, nullptr, 0, (int)(e / (uint32_t)ntn), (int)(e % (uint32_t)ntn));
+    const int tile_m = (int)((e & kListIndex) / (uint32_t)ntn), tile_n = (int)((e & kListIndex) % (uint32_t)ntn);
+    if (e & kListHalf)
+      split3_tile<CfgH, Op>(M, M_max, N, K, A, BimgH, op, nullptr, 0, 2 * tile_m + ((e & kListLower) ? 1 : 0), tile_n);
+    else
+      split3_tile<Cfg, Op>(M, M_max, N, K, A, Bimg, op, nullptr, 0, tile_m, tile_n);
     if (threadIdx.x == 0) *s_ticket = nxt;
     __syncthreads();   // the ticket is visible; the next tile reuses the stages and the Op's rows
   }
@@ -436,16 +447,13 @@ inline bool split3_sparse_fits(int K, int groups, int group_cols) {
   return lds <= 80 * 1024;   // two workgroups per CU
 }
 
-// resident_wgs > 0: the list form of the kernel, with that many workgroups.
 // splits > 1 (Ops with kSplitK, not with ROWS_PER_XCD): `part` = gemm_f32_splitk_floats(splits, M_max, N) floats.
 // sparse: let an Op with kSparseK skip the slabs of K it marks dead (needs K / BK <= 65535, the Op's column groups a
 // multiple of BK wide and K a multiple of them; otherwise the loop stays dense).
 template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
-                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false,
-                                        int resident_wgs = 0) {
+                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false) {
   if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
-  if (resident_wgs && (!Op::kTileList || resident_wgs % 8 != 0 || splits != 1 || ROWS_PER_XCD)) return hipErrorInvalidValue;
   size_t lds = Cfg::LDS_BYTES;
   if constexpr (Op::kSparseK) {
     sparse = sparse && splits == 1 && split3_sparse_fits<Cfg>(K, op.groups(), op.group_cols());
@@ -458,20 +466,6 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
   unsigned mt = (unsigned)((M_max + Cfg::BM - 1) / Cfg::BM);
   if (ROWS_PER_XCD) mt = (mt + 7) / 8 * 8;
   dim3 grid((unsigned)((N + Cfg::BN - 1) / Cfg::BN), mt, (unsigned)splits);
-  if constexpr (Op::kTileList) {
-    if (resident_wgs) {   // the Op carries the lists of tiles
-      auto lkern = gemm_split3_nt_list_kernel<Cfg, Op, CALL>;
-      static bool lattr_set = false;
-      if (!lattr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)lkern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-        if (e != hipSuccess) return e;
-        lattr_set = true;
-      }
-      hipLaunchKernelGGL(lkern, dim3((unsigned)resident_wgs), dim3(Cfg::THREADS), lds + 16, st, M_dev, M_max, N, K, A, Bimg,
-                         op);
-      return hipGetLastError();
-    }
-  }
   auto kern = gemm_split3_nt_kernel<Cfg, Op, CALL, ROWS_PER_XCD>;
   static bool attr_set = false;   // dynamic LDS above the default limit needs the attribute once per kernel
   if (!attr_set) {
@@ -480,6 +474,26 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), lds, st, M_dev, M_max, N, K, A, Bimg, op, part, sparse ? 1 : 0);
+  return hipGetLastError();
+}
+
+// The list form: `wgs` resident workgroups (a multiple of 8), the Op carries the lists.  BimgH: B's image for CfgH, or
+// NULL if no entry of the lists names a half tile.
+template <class Cfg, class CfgH, int CALL, class Op>
+inline hipError_t launch_gemm_split3_nt_list(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
+                                             const uint8_t* BimgH, Op op, int wgs, hipStream_t st) {
+  static_assert(Op::kTileList && !Op::kSparseK, "an Op with tile lists and a dense K loop");
+  if (K <= 0 || K % Cfg::BK != 0 || K % CfgH::BK != 0 || wgs <= 0 || wgs % 8 != 0) return hipErrorInvalidValue;
+  auto kern = gemm_split3_nt_list_kernel<Cfg, CfgH, Op, CALL>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const size_t lds = (Cfg::LDS_BYTES > CfgH::LDS_BYTES ? Cfg::LDS_BYTES : CfgH::LDS_BYTES) + 16;
+  static_assert((Cfg::LDS_BYTES > CfgH::LDS_BYTES ? Cfg::LDS_BYTES : CfgH::LDS_BYTES) + 16 <= 80 * 1024, "two workgroups per CU");
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::THREADS), lds, st, M_dev, M_max, N, K, A, Bimg, BimgH, op);
   return hipGetLastError();
 }
 

@@ -708,9 +708,12 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
 
 // One workgroup per row tile of the exact GEMM: the bounds U, L above from the largest integer sums imax[row][group]
 // -> the tiles of this row tile that the exact GEMM has to compute, appended to the lists (list t % 8 for column tile
-// t), and -inf into the partial maxima of the others (pmax[row][np], gpt of them per column tile).  Not screened
-// (*on == 0): every tile.  spt: groups per column tile.  counts (or NULL): [0] += tiles to compute, [1] += tiles,
-// [4] += tiles of screened launches.
+// t), and -inf into the partial maxima of the others (pmax[row][np], gpt of them per column tile).  The two halves of
+// the tile's rows are judged separately: a column tile that only one half needs is listed as a half tile (halves != 0;
+// see gemm_split3.h) -- with every chain's rows in a block of 64 a half holds one chain -- and the other half's logits
+// of that tile are set to -inf here: the second GEMM visits a column group for all rows of its row tile, and those rows'
+// weights there must come out as the zeros they are.  Not screened (*on == 0): every tile, whole.  spt: groups per column tile.  counts (or NULL), in half tiles: [0] += to compute, [1] += all, [4] +=
+// all of screened launches.
 __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __restrict__ n_dev, int n_max, int nps, int ntn,
                                                                 int spt, const int32_t* __restrict__ imax,
                                                                 const float2* __restrict__ xs,
@@ -720,19 +723,22 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
                                                                 const int32_t* __restrict__ on,
                                                                 uint32_t* __restrict__ tile_list,
                                                                 int32_t* __restrict__ tile_count, int list_cap,
-                                                                float* __restrict__ pmax, int np, int gpt,
+                                                                float* __restrict__ pmax, int np, int gpt, int halves,
+                                                                float* __restrict__ logits, int64_t ldl,
                                                                 unsigned long long* __restrict__ counts) {
-  extern __shared__ int s_flag[];   // [ntn]
+  extern __shared__ int s_flag[];   // [2][ntn]: upper, lower half of the rows
   constexpr int BM = GmmTileSplit::BM, RW = 4;   // rows a wavefront works on at a time (their loads overlap)
   const int n = min(*n_dev, n_max);
   const int m0 = blockIdx.x * BM;
   if (m0 >= n) return;
   const bool screened = *on != 0;
-  for (int t = threadIdx.x; t < ntn; t += 256) s_flag[t] = screened ? 0 : 1;
+  const bool lower_exists = m0 + BM / 2 < n;
+  for (int t = threadIdx.x; t < 2 * ntn; t += 256) s_flag[t] = screened ? 0 : ((t < ntn || lower_exists) ? 1 : 0);
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (screened) {
-    for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {
+    for (int r0 = RW * wave; r0 < BM && m0 + r0 < n; r0 += 4 * RW) {   // (r0 .. r0 + RW - 1 lie in one half)
+      int* flag = s_flag + (r0 < BM / 2 ? 0 : ntn);
       float c1s[RW], c2[RW], ea[RW], eb[RW], lo[RW];
       const int32_t* im[RW];
 #pragma unroll
@@ -774,29 +780,46 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
           bounds(k, p, g1, base, e);
           any = any || (base - c2[k] * g1.z + g2.y + e >= lo[k]);
         }
-        if (any) s_flag[p / spt] = 1;
+        if (any) flag[p / spt] = 1;
       }
     }
     __syncthreads();
   }
   int mine = 0;
-  for (int t = threadIdx.x; t < ntn; t += 256)
-    if (s_flag[t]) {
-      ++mine;
-      const int pos = atomicAdd(&tile_count[t % 8], 1);
-      if (pos < list_cap) tile_list[(int64_t)(t % 8) * list_cap + pos] = (uint32_t)(blockIdx.x * ntn + t);
+  for (int t = threadIdx.x; t < ntn; t += 256) {
+    const int up = s_flag[t], low = s_flag[ntn + t];
+    if (!up && !low) continue;
+    mine += up + low;
+    uint32_t e = (uint32_t)(blockIdx.x * ntn + t);
+    if (halves && up != low) e |= kListHalf | (low ? kListLower : 0u);
+    const int pos = atomicAdd(&tile_count[t % 8], 1);
+    if (pos < list_cap) tile_list[(int64_t)(t % 8) * list_cap + pos] = e;
+  }
+  if (screened && halves) {   // the half of a half tile that is not computed: logits of -inf (16-byte pieces)
+    for (int t = 0; t < ntn; ++t) {
+      const int up = s_flag[t], low = s_flag[ntn + t];
+      if (up == low) continue;   // the same for the whole workgroup
+      const int r_first = up ? BM / 2 : 0, r_end = min(r_first + BM / 2, n - m0);
+      constexpr int kPieces = GmmTileSplit::BN / 4;
+      for (int i = threadIdx.x; i < (r_end - r_first) * kPieces; i += 256)
+        *reinterpret_cast<float4*>(logits + (int64_t)(m0 + r_first + i / kPieces) * ldl + (int64_t)t * GmmTileSplit::BN +
+                                   4 * (i % kPieces)) = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
     }
-  if (screened) {   // the tiles left out: nothing will write their partial maxima
+  }
+  if (screened) {   // what is left out: nothing will write those partial maxima
     const int rows = min(BM, n - m0);
-    for (int i = threadIdx.x; i < rows * np; i += 256)
-      if (!s_flag[(i % np) / gpt]) pmax[(int64_t)m0 * np + i] = -INFINITY;
+    for (int i = threadIdx.x; i < rows * np; i += 256) {
+      const int r = i / np, t = (i % np) / gpt;
+      const bool computed = halves ? s_flag[(r < BM / 2 ? 0 : ntn) + t] != 0 : (s_flag[t] | s_flag[ntn + t]) != 0;
+      if (!computed) pmax[(int64_t)m0 * np + i] = -INFINITY;
+    }
   }
   if (counts) {
     const int total = (int)wave_sum((float)mine);   // this wavefront's share; at most a few thousand: exact in fp32
     if (lane == 0 && total) atomicAdd(&counts[0], (unsigned long long)total);
     if (threadIdx.x == 0) {
-      atomicAdd(&counts[1], (unsigned long long)ntn);
-      if (screened) atomicAdd(&counts[4], (unsigned long long)ntn);
+      atomicAdd(&counts[1], (unsigned long long)(2 * ntn));
+      if (screened) atomicAdd(&counts[4], (unsigned long long)(2 * ntn));
     }
   }
 }
@@ -1077,9 +1100,10 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                                                      d / 2, reinterpret_cast<const uint16_t*>(g->xq), d / 2, on, g->imax,
                                                      g->nps, kScreenWgs, st));
     hipLaunchKernelGGL(gmm_screen_decide_kernel, dim3((unsigned)ceil_div(n, GmmTileSplit::BM)), dim3(256),
-                       sizeof(int) * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
+                       sizeof(int) * 2 * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
                        g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_list, g->tile_count, g->list_cap,
-                       g->pmax, np, GmmTileSplit::WGN, ctx->prof.on ? g->work_counts : nullptr);
+                       g->pmax, np, GmmTileSplit::WGN, g->split_draft_ok ? 1 : 0, g->logits, (int64_t)C,
+                       ctx->prof.on ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.tile_list = g->tile_list;
     op1.tile_count = g->tile_count;
@@ -1087,14 +1111,18 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    if (split)
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st, 1,
-                                                                        nullptr, false, screen ? kResidentWgs : 0)
+    if (split && screen) {
+      // resident workgroups draw the tiles (and half tiles, on the draft call's tiling) the screening pass listed
+      ASD_HIP(launch_gemm_split3_nt_list<GmmTileSplit, GmmTileSplitSkinny, 1>(rows.n_dev, n, C, d, X, g->means_img,
+                                                                               g->means_img_s, op1, kResidentWgs, st));
+    } else if (split) {
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
                         : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img_s,
                                                                                op1, st));
-    else
+    } else {
       ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
+    }
   }
   if (rows.call == 0 && g->screen_ok && g->screen_mode == 1) {   // this round's verify call: screen or not
     hipLaunchKernelGGL(gmm_regime_kernel, dim3(kRegimeBlocks), dim3(256), 0, st, rows.n_dev, n, np, g->pmax,

@@ -331,12 +331,12 @@ def test_logit_screen_is_bit_identical_and_skips_work():
     ctx.profile_enable(False)
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     done, tiles = work[0][0], work[0][1]
-    assert tiles == 8 * (cfg["C"] // 128) and 8 <= done < tiles and work[0][4] == tiles and work[1][:2] == (0, 0)
+    assert tiles == 16 * (cfg["C"] // 128) and 16 <= done < tiles and work[0][4] == tiles and work[1][:2] == (0, 0)   # half tiles
     # the second GEMM leaves the same work out either way: whole row tiles to the closed form, slabs of the others
     assert 0 < work[0][2] <= work[0][3] and work[1][2:4] == work[0][2:4] and 0 < work[0][5] < 8 and work[1][5] == work[0][5]
     want = model(K_minus(tau, cfg["K"]), x.astype(np.float64))
     e = H.rel_err(outs[0].cpu().numpy(), want)
-    _log("logit screen: %d of %d tiles computed, bit-identical to unscreened, rel err vs oracle" % (done, tiles), e)
+    _log("logit screen: %d of %d half tiles computed, bit-identical to unscreened, rel err vs oracle" % (done, tiles), e)
     assert e <= 1e-4
     with pytest.raises(binding.AsdError):
         ctx.use_logit_screen(3)
