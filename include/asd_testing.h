@@ -27,11 +27,13 @@ ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);
 
 /* Screening of the verify call's first GEMM in the split-operand mixture denoiser: an int8 GEMM with a
- * rigorous error bound finds the 128 x 128 tiles of logits that lie so far below their rows' maxima that every
- * softmax weight in them is exactly 0.0f, and the exact GEMM leaves those tiles out.  Results are identical bit for
- * bit.  mode 0: off; 1 (default): a verify call is screened when the draft call before it found its rows'
+ * rigorous error bound finds the tiles of logits (128 components x 128 rows, or 64 rows: the halves of a row tile
+ * are judged separately) that lie so far below their rows' maxima that every softmax weight in them is exactly 0.0f,
+ * and the exact GEMM leaves those tiles out.  Results are identical bit for bit.  While it is on and L is a multiple
+ * of 64, the verify call's row plan starts every chain's rows at a multiple of 64 rows (filling up with repeats of
+ * the chain's last row), so that a row tile holds rows of two chains.  mode 0: off; 1 (default): a verify call is screened when the draft call before it found its rows'
  * posteriors collapsed; 2: every verify call is screened.  Needs the second GEMM's skipping
- * (asd_use_sparse_combine) switched on, d a multiple of 128 (at most 2048) and C a multiple of 128; otherwise it
+ * (asd_use_sparse_combine) switched on, d a multiple of 128 (at most 2048) and C a multiple of 256; otherwise it
  * stays off.
  * asd_logit_screen_active: the mode in force (0 when the shape or the other switches rule it out). */
 ASD_API asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode);
@@ -62,7 +64,7 @@ typedef enum {
   ASD_PROF_PLAN = 1,         /* row planning                                  */
   ASD_PROF_GMM_ROWWISE = 2,  /* GMM denoiser, one wavefront per row           */
   ASD_PROF_GMM_LOGITS = 3,   /* GMM logits GEMM  X M^T  (fp32 MFMA)           */
-  ASD_PROF_GMM_SOFTMAX = 4,  /* GMM row softmax                               */
+  ASD_PROF_GMM_SOFTMAX = 4,  /* GMM, between the two GEMMs: row maxima, one-hot rows */
   ASD_PROF_GMM_COMBINE = 5,  /* GMM  P M  GEMM + affine combination           */
   ASD_PROF_MLP_PACK = 6,     /* MLP input packing (bf16 x ; time embedding)   */
   ASD_PROF_MLP_GEMM_IN = 7,  /* MLP first layer                               */

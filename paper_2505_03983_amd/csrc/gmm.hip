@@ -1134,26 +1134,27 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
   CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
                 rows.tau, (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
+  if (split && rows.call == 1) {   // between the GEMMs: row maxima and live groups once per row tile; one-hot rows
+    ProfScope ps(ctx, ASD_PROF_GMM_SOFTMAX, rows.call, st);
+    // one-hot rows in closed form: with the sparse second GEMM only (the same switch), whole float4 rows
+    const bool onehot = g->sparse_combine && d % 4 == 0 && np <= 64 && gcols == 64;
+    hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
+                       sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
+                       gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
+                       ctx->prof.on ? g->work_counts : nullptr);
+    ASD_HIP(hipGetLastError());
+    if (onehot) {
+      hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
+                         g->onehot_tile, g->means, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
+                         rows.tau);
+      ASD_HIP(hipGetLastError());
+      op2.onehot_tile = g->onehot_tile;
+    }
+    op2.rmax_pre = g->rmax;
+    op2.live_pre = g->glive;
+  }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    // one-hot rows in closed form: with the sparse second GEMM only (the same switch), whole float4 rows
-    const bool onehot = split && rows.call == 1 && g->sparse_combine && d % 4 == 0 && np <= 64 && gcols == 64;
-    if (split && rows.call == 1) {   // row maxima and live groups once per row tile
-      hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
-                         sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
-                         gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
-                         ctx->prof.on ? g->work_counts : nullptr);
-      ASD_HIP(hipGetLastError());
-      if (onehot) {
-        hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
-                           g->onehot_tile, g->means, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
-                           rows.tau);
-        ASD_HIP(hipGetLastError());
-        op2.onehot_tile = g->onehot_tile;
-      }
-      op2.rmax_pre = g->rmax;
-      op2.live_pre = g->glive;
-    }
     if (split)
       ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1,
                                                                        nullptr, g->sparse_combine)
