@@ -47,6 +47,10 @@
 // groups of columns that are live for some row of the tile (mark_live, from data the producer of A
 // left behind); one wavefront compacts them into a list of slabs in LDS and the K loop walks that list.
 // The result equals the dense loop's exactly: the skipped products and row-sum terms are zeros.
+//
+// Two forms of the kernel share the tile code (split3_tile): one workgroup per tile of the grid, and -- for an Op that
+// carries lists of the tiles that are wanted at all -- resident workgroups that draw tiles (or half tiles, on a
+// second tiling of half the rows) from those lists by ticket; see gemm_split3_nt_list_kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -12,13 +12,24 @@
 // Two paths:
 //  * row-wise kernel (one wavefront per row) for small or oddly shaped
 //    problems, where a launch is latency-bound anyway;
-//  * matrix-core path for large aligned problems: logits = X M^T (fp32 MFMA
-//    GEMM with the affine map fused in the epilogue) materialised in HBM
+//  * matrix-core path for large aligned problems: logits = X M^T (MFMA GEMM
+//    with the affine map fused in the epilogue) materialised in HBM
 //    [rows, C] -- at 288 GB of HBM the 1 GB of logits of the largest workload
 //    costs ~4% of the GEMM time to write and re-read, and keeps both GEMMs at
-//    full tile efficiency with head dimension d = 1024 -- then a row softmax,
-//    then P M (second MFMA GEMM against the pre-transposed means) with the
-//    final affine combination fused in the epilogue.
+//    full tile efficiency with head dimension d = 1024 -- then P M (second
+//    MFMA GEMM against the pre-transposed means) with the softmax fused into
+//    its operand load and the final affine combination into its epilogue.
+//    By default on the bf16 matrix pipe with three-way split operands
+//    (gemm_split3.h; fp32 accuracy), else on the fp32 pipe (gemm_f32.h).
+//
+// The verify call of the split path leaves out the matrix work whose result is
+// an exact zero, bit-identically (sections below, in this order of the call):
+//  1. screening: an int8 product with a rigorous error bound finds the tiles
+//     of logits that cannot hold a softmax weight other than 0.0f;
+//  2. the first GEMM computes the other tiles only (list form of the kernel);
+//  3. row maxima and live column groups once per row tile; rows with a single
+//     non-zero weight are written in closed form;
+//  4. the second GEMM visits the live K slabs of the remaining row tiles.
 #include "common.h"
 #include "device_util.h"
 #include "gemm_bf16_pipe.h"
