@@ -496,6 +496,25 @@ struct CombineOp {
 // products are zeros), so  out = fma(c_x', x, c_m' mu_b)  needs no GEMM.  A row's few live groups are scanned for
 // that (rows with more than two live groups are not candidates): onehot[row] = b or -1, and onehot_tile[row tile] =
 // 1 when all its rows qualify -- the second GEMM then skips the tile and gmm_onehot_kernel writes it.
+// The component b of a one-hot row, or -1: called by a whole wavefront with the row's partial maxima p[np] (np <= 64,
+// groups of 64 columns), its maximum mx and its logits.
+__device__ __forceinline__ int onehot_component(const float* __restrict__ p, int np, float mx,
+                                                const float* __restrict__ row_logits, int lane) {
+  const float thr = mx - CombineOp::kZeroGap;
+  unsigned long long groups = __ballot(lane < np && p[min(lane, np - 1)] >= thr);
+  if (__popcll(groups) > 2) return -1;
+  int count = 0, b = -1;
+  while (groups) {
+    const int g = __ffsll((long long)groups) - 1;
+    groups &= groups - 1;
+    const float v = row_logits[g * 64 + lane];
+    count += __popcll(__ballot(v >= thr));
+    const unsigned long long at_max = __ballot(v == mx);
+    if (at_max) b = g * 64 + __ffsll((long long)at_max) - 1;
+  }
+  return count == 1 ? b : -1;
+}
+
 __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__ n_dev, int n_max, int np,
                                                          const float* __restrict__ pmax, float* __restrict__ rmax,
                                                          uint8_t* __restrict__ glive,
@@ -540,23 +559,10 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
       for (int k = 0; k < RW; ++k) {
         const int row = m0 + r0 + k;
         if (row >= n) continue;   // the same for the whole wavefront
-        const float thr = mx[k] - CombineOp::kZeroGap;
-        unsigned long long groups = __ballot(lane < np && p[k][lane] >= thr);
-        int count = 0, b = -1;
-        if (__popcll(groups) <= 2) {
-          while (groups) {
-            const int g = __ffsll((long long)groups) - 1;
-            groups &= groups - 1;
-            const float v = logits[(int64_t)row * ldl + g * 64 + lane];
-            count += __popcll(__ballot(v >= thr));
-            const unsigned long long at_max = __ballot(v == mx[k]);
-            if (at_max) b = g * 64 + __ffsll((long long)at_max) - 1;
-          }
-        }
-        const bool one = count == 1 && b >= 0;
+        const int b = onehot_component(p[k], np, mx[k], logits + (int64_t)row * ldl, lane);
         if (lane == 0) {
-          onehot[row] = one ? b : -1;
-          if (!one) s_any[np] = 0;
+          onehot[row] = b;
+          if (b < 0) s_any[np] = 0;
         }
       }
     }
@@ -567,6 +573,34 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
     onehot_tile[blockIdx.x] = (uint8_t)s_any[np];
     if (counts && s_any[np]) atomicAdd(&counts[5], 1ull);
   }
+}
+
+// The same for a call of few rows (the draft call: one row per chain), where a workgroup per 128 rows would be eight
+// workgroups: one wavefront per row for the maxima and the one-hot components (no live groups: that call's second
+// GEMM does not skip slabs), then one small workgroup per row tile for the tile flags.
+__global__ __launch_bounds__(256) void gmm_rowmax_rows_kernel(const int* __restrict__ n_dev, int n_max, int np,
+                                                              const float* __restrict__ pmax, float* __restrict__ rmax,
+                                                              const float* __restrict__ logits, int64_t ldl,
+                                                              int32_t* __restrict__ onehot) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= min(*n_dev, n_max)) return;
+  const float* p = pmax + (int64_t)row * np;
+  float mx = -INFINITY;
+  for (int q = lane; q < np; q += 64) mx = fmaxf(mx, p[q]);
+  mx = wave_max(mx);
+  if (lane == 0) rmax[row] = mx;
+  if (onehot) {
+    const int b = onehot_component(p, np, mx, logits + (int64_t)row * ldl, lane);
+    if (lane == 0) onehot[row] = b;
+  }
+}
+__global__ __launch_bounds__(CombineOp::kRowmaxTile) void gmm_onehot_tiles_kernel(const int* __restrict__ n_dev, int n_max,
+                                                                                 const int32_t* __restrict__ onehot,
+                                                                                 uint8_t* __restrict__ onehot_tile) {
+  const int n = min(*n_dev, n_max), m = blockIdx.x * CombineOp::kRowmaxTile + threadIdx.x;
+  if (blockIdx.x * CombineOp::kRowmaxTile >= n) return;
+  const int bad = __syncthreads_or(m < n && onehot[m] < 0);
+  if (threadIdx.x == 0) onehot_tile[blockIdx.x] = bad ? 0 : 1;
 }
 
 // The rows of the one-hot tiles, in closed form (see gmm_rowmax_kernel): one workgroup per row.
@@ -877,10 +911,12 @@ __global__ __launch_bounds__(256) void combine_finish_kernel(const int* __restri
                                                              float* __restrict__ out_base,
                                                              const int64_t* __restrict__ out_off,
                                                              const float4* __restrict__ coef_tau,
-                                                             const int32_t* __restrict__ tau) {
+                                                             const int32_t* __restrict__ tau,
+                                                             const uint8_t* __restrict__ onehot_tile) {
   const int M = min(*M_dev, M_max);
   const int m = blockIdx.x;
   if (m >= M) return;
+  if (onehot_tile && onehot_tile[m / CombineOp::kRowmaxTile]) return;   // written in closed form; no partials exist
   const float* psum = part + (size_t)splits * M_max * N;
   float sum = 0.f;
   for (int z = 0; z < splits; ++z) sum += psum[(size_t)z * M_max + m];
@@ -1145,14 +1181,24 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
   CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
                 rows.tau, (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
-  if (split && rows.call == 1) {   // between the GEMMs: row maxima and live groups once per row tile; one-hot rows
+  // between the GEMMs: row maxima and live groups once per row tile; one-hot rows (the draft call's rows -- one per
+  // chain -- are one-hot too once the posteriors have collapsed)
+  if (split) {
     ProfScope ps(ctx, ASD_PROF_GMM_SOFTMAX, rows.call, st);
     // one-hot rows in closed form: with the sparse second GEMM only (the same switch), whole float4 rows
     const bool onehot = g->sparse_combine && d % 4 == 0 && np <= 64 && gcols == 64;
-    hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
-                       sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
-                       gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
-                       ctx->prof.on ? g->work_counts : nullptr);
+    if (rows.call == 1) {
+      hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
+                         sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
+                         gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
+                         ctx->prof.on ? g->work_counts : nullptr);
+    } else {
+      hipLaunchKernelGGL(gmm_rowmax_rows_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, np,
+                         g->pmax, g->rmax, g->logits, (int64_t)C, onehot ? g->onehot : (int32_t*)nullptr);
+      if (onehot)
+        hipLaunchKernelGGL(gmm_onehot_tiles_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)),
+                           dim3(CombineOp::kRowmaxTile), 0, st, rows.n_dev, n, g->onehot, g->onehot_tile);
+    }
     ASD_HIP(hipGetLastError());
     if (onehot) {
       hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
@@ -1162,7 +1208,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
       op2.onehot_tile = g->onehot_tile;
     }
     op2.rmax_pre = g->rmax;
-    op2.live_pre = g->glive;
+    if (rows.call == 1) op2.live_pre = g->glive;
   }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
@@ -1177,7 +1223,8 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                                                                 g->part));
     if (splits > 1) {
       hipLaunchKernelGGL(combine_finish_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, ctx->B, d, splits,
-                         g->part, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau);
+                         g->part, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau,
+                         op2.onehot_tile);
       ASD_HIP(hipGetLastError());
     }
   }

@@ -363,10 +363,20 @@ def test_logit_screen_is_bit_identical_and_skips_work():
             ctx_b.sample(traj, rounds)
             torch.cuda.synchronize()
             res.append((traj, rounds))
+        # and with the second GEMM visiting everything (no slab skipped, no row in closed form, hence no screen either)
+        ctx_b.use_logit_screen(1)
+        ctx_b.use_sparse_combine(False)
+        ctx_b.set_seed(5)
+        traj = runtime.alloc_traj(ctx_b)
+        rounds = torch.zeros(cfg_b["chains"], dtype=torch.int32, device=DEV)
+        ctx_b.sample(traj, rounds)
+        torch.cuda.synchronize()
+        res.append((traj, rounds))
+        ctx_b.use_sparse_combine(True)
         for traj, rounds in res[1:]:
             assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
         assert bool(torch.isfinite(res[0][0]).all())
-        _log("logit screen: whole samples of d", cfg_b["d"], "C", cfg_b["C"], "bit-identical in the three modes, rounds max",
+        _log("logit screen: whole samples of d", cfg_b["d"], "C", cfg_b["C"], "bit-identical in the three modes and with the dense second GEMM, rounds max",
              int(res[0][1].max()))
         ctx_b.close()
 
