@@ -195,7 +195,7 @@ def roofline(res, w=None, kernel=None):
         if bound == "mfma" and res.get("split"):
             dtype = "bf16"
             executed_per_method = 6.0
-            done, tiles, slabs_done, slabs = res.get("model_work", (0, 0, 0, 0, 0, 0))[:4]
+            done, tiles, slabs_done, slabs = res.get("model_work", (0, 0, 0, 0, 0, 0, 0))[:4]
             if name == "GMM_LOGITS/verify" and tiles:
                 executed_flops = 6.0 * 2.0 * 64 * 128 * cfg["d"] * done / launches      # counted in half tiles of 64 rows
             if name == "GMM_COMBINE/verify" and slabs:
@@ -240,14 +240,14 @@ def logit_screen(res):
     k = res["kernels"]
     if not res.get("screen_mode") or "GMM_SCREEN/verify" not in k:
         return dict(mode=res.get("screen_mode", 0))
-    done, tiles, _, _, screened, onehot = res["model_work"]
+    done, tiles, _, _, screened, onehot, certified = res["model_work"]
     s = k["GMM_SCREEN/verify"]
     ops = 2.0 * 64 * 128 * res["cfg"]["d"] * screened
     return dict(mode=res["screen_mode"], launches=s["launches"], total_ms=s["total_ms"],
                 share_of_wall=1e-3 * s["total_ms"] / res["wall_s"],
                 logit_half_tiles=tiles, logit_half_tiles_of_screened_calls=screened, logit_half_tiles_computed=done,
                 computed_share=done / tiles if tiles else None,
-                row_tiles_of_second_gemm_in_closed_form=onehot,
+                row_tiles_of_second_gemm_in_closed_form=onehot, row_tiles_certified_before_any_matrix_work=certified,
                 int8_tops=ops / (1e-3 * s["total_ms"]) / 1e12 if screened else 0.0, int8_peak_tops=PEAK["i8"],
                 note="total_ms covers the quantiser, the int8 GEMM and the decision kernel; calls the draft call's "
                      "verdict switched the screen off for still launch all three (they exit at once)")

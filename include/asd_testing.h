@@ -39,6 +39,18 @@ ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);
 ASD_API asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode);
 ASD_API int32_t asd_logit_screen_active(const asd_ctx* ctx);
 
+/* One-hot certificate of the screened verify call (split-operand mixture denoiser).  Before any matrix work, a row
+ * tile (128 rows) whose rows all lie so close to the mean their chain's last draft-call row was found one-hot on
+ * that the distances between the means alone prove every other softmax weight exactly 0.0f (Cauchy-Schwarz on
+ * x - s mu_b, two C x C tables of the means' geometry built at asd_init) is written in closed form,
+ * c_x' x + c_m' mu_b, and skips the screening pass and both GEMMs.  Results are identical bit for bit: it certifies
+ * what the exact path would have found.  Works inside asd_sample and the stage calls (the row plan names every row's
+ * chain), not in asd_denoise.  Default: on; needs the screening pass (asd_logit_screen_active != 0), at most 64
+ * groups of 64 components (C <= 4096) and 8 C^2 bytes <= 1 GiB; otherwise it stays off.
+ * asd_onehot_certificate_active: 1 if the verify calls of this context run it. */
+ASD_API asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on);
+ASD_API int32_t asd_onehot_certificate_active(const asd_ctx* ctx);
+
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
 ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,
@@ -88,12 +100,14 @@ ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows,
  * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
  * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine).
  * (Workgroups of row tiles written in closed form count in neither.)
- * screened_tiles: the part of logit_tiles that belongs to calls the screening GEMM ran for.
+ * screened_tiles: the part of logit_tiles the screening GEMM looked at (calls it ran for, row tiles not certified).
  * onehot_row_tiles: tiles of 128 rows whose rows all have one softmax weight of 1.0 and zeros, which the second GEMM
- * leaves to a kernel that writes  c_x' x + c_m' mu_b  directly (same switch as the sparse second GEMM). */
+ * leaves to a kernel that writes  c_x' x + c_m' mu_b  directly (same switch as the sparse second GEMM).
+ * certified_row_tiles: the part of onehot_row_tiles that was proven one-hot before any matrix work
+ * (asd_use_onehot_certificate); their half tiles of logits count in logit_tiles, none in logit_tiles_done. */
 ASD_API asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
                                           int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles,
-                                          int64_t* onehot_row_tiles);
+                                          int64_t* onehot_row_tiles, int64_t* certified_row_tiles);
 
 #ifdef __cplusplus
 }

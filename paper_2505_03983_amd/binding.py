@@ -72,7 +72,9 @@ def lib():
             "asd_use_sparse_combine": (i32, [vp, i32]),
             "asd_use_logit_screen": (i32, [vp, i32]),
             "asd_logit_screen_active": (i32, [vp]),
-            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp, vp]),
+            "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp, vp, vp]),
+            "asd_use_onehot_certificate": (i32, [vp, i32]),
+            "asd_onehot_certificate_active": (i32, [vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
             "asd_resident_active": (i32, [vp]),
             "asd_use_split_gemm": (i32, [vp, i32]),
@@ -256,6 +258,12 @@ class Ctx:
     def logit_screen_active(self):
         return int(lib().asd_logit_screen_active(self.h))
 
+    def use_onehot_certificate(self, on=True):
+        _check(lib().asd_use_onehot_certificate(self.h, int(bool(on))))
+
+    def onehot_certificate_active(self):
+        return bool(lib().asd_onehot_certificate_active(self.h))
+
     def use_resident(self, on=True):
         _check(lib().asd_use_resident(self.h, int(bool(on))))
 
@@ -308,8 +316,8 @@ class Ctx:
 
     def profile_model_work(self):
         """(logit tiles computed, logit tiles, combine slabs visited, combine slabs, logit tiles of screened calls,
-        row tiles written in closed form) of the verify calls."""
-        v = [C.c_int64(0) for _ in range(6)]
+        row tiles written in closed form, row tiles certified one-hot before any matrix work) of the verify calls."""
+        v = [C.c_int64(0) for _ in range(7)]
         _check(lib().asd_profile_model_work(self.h, *[C.addressof(x) for x in v]))
         return tuple(x.value for x in v)
 

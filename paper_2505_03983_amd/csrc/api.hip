@@ -139,6 +139,7 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->in_off, sizeof(int64_t) * rows));
   ASD_HIP(hipMalloc(&ctx->out_off, sizeof(int64_t) * rows));
   ASD_HIP(hipMalloc(&ctx->row_tau, sizeof(int32_t) * rows));
+  ASD_HIP(hipMalloc(&ctx->row_chain, sizeof(int32_t) * rows));
   ASD_HIP(hipMalloc(&ctx->n_rows_dev, sizeof(int32_t) * 2));
   ASD_HIP(hipMemset(ctx->n_rows_dev, 0, sizeof(int32_t) * 2));
   ASD_HIP(hipMalloc(&ctx->x0a, sizeof(float) * (size_t)ctx->B * ctx->d));
@@ -175,6 +176,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->in_off);
   (void)hipFree(ctx->out_off);
   (void)hipFree(ctx->row_tau);
+  (void)hipFree(ctx->row_chain);
   (void)hipFree(ctx->n_rows_dev);
   (void)hipFree(ctx->x0a);
   (void)hipFree(ctx->x0hat);
@@ -198,14 +200,15 @@ static void teardown(asd_ctx* ctx) {
 }
 
 static RowPlan draft_rows(asd_ctx* ctx, const float* traj) {
-  return RowPlan{ctx->B, ctx->n_rows_dev + 0, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau, 0};
+  return RowPlan{ctx->B, ctx->n_rows_dev + 0, traj, ctx->x0a, ctx->in_off, ctx->out_off, ctx->row_tau, 0, ctx->row_chain};
 }
 
 static RowPlan verify_rows(asd_ctx* ctx, const float* traj, float* x0hat) {
   int per_chain = ctx->L - 1 + (ctx->reuse_now ? 1 : 0);   // tested slots, plus yhat_b with model-call reuse
   const int block = ctx->cur_win ? 0 : model_row_block(ctx);    // the planner's filling of each chain's block (launch_plan_verify)
   if (block > 0) per_chain = (per_chain + block - 1) / block * block;
-  return RowPlan{ctx->B * per_chain, ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1};
+  return RowPlan{ctx->B * per_chain, ctx->n_rows_dev + 1, traj, x0hat, ctx->in_off, ctx->out_off, ctx->row_tau, 1,
+                 ctx->row_chain};
 }
 
 __global__ void set_key_kernel(Key* dst, Key key) { *dst = key; }
@@ -534,6 +537,23 @@ asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode) {
   return ASD_OK;
 }
 
+asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  if (ctx->gmm && ctx->gmm->cert_on != (on != 0)) {
+    ctx->gmm->cert_on = on != 0;
+    if (ctx->gexec) {   // the captured round holds the other launches
+      (void)hipGraphExecDestroy(ctx->gexec);
+      ctx->gexec = nullptr;
+    }
+  }
+  return ASD_OK;
+}
+
+int32_t asd_onehot_certificate_active(const asd_ctx* ctx) {
+  const asd::GmmState* g = ctx ? ctx->gmm : nullptr;
+  return (asd_logit_screen_active(ctx) != 0 && g->cert_ok && g->cert_on) ? 1 : 0;
+}
+
 int32_t asd_logit_screen_active(const asd_ctx* ctx) {
   const asd::GmmState* g = ctx ? ctx->gmm : nullptr;
   return (g && g->use_split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine) ? g->screen_mode : 0;
@@ -569,7 +589,7 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ctx->prof.on = on != 0;
   ctx->prof.outer = on >= 2;
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
-  if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 6 * sizeof(unsigned long long)));
+  if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 8 * sizeof(unsigned long long)));
   return ASD_OK;
 }
 
@@ -611,12 +631,13 @@ asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows, int64_t
 
 asd_status asd_profile_model_work(asd_ctx* ctx, int64_t* logit_tiles_done, int64_t* logit_tiles,
                                   int64_t* combine_slabs_done, int64_t* combine_slabs, int64_t* screened_tiles,
-                                  int64_t* onehot_row_tiles) {
+                                  int64_t* onehot_row_tiles, int64_t* certified_row_tiles) {
   ASD_TRY(check_ctx(ctx));
-  unsigned long long h[6] = {0, 0, 0, 0, 0, 0};
+  unsigned long long h[7] = {0, 0, 0, 0, 0, 0, 0};
   if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemcpy(h, ctx->gmm->work_counts, sizeof(h), hipMemcpyDeviceToHost));
-  int64_t* out[6] = {logit_tiles_done, logit_tiles, combine_slabs_done, combine_slabs, screened_tiles, onehot_row_tiles};
-  for (int i = 0; i < 6; ++i)
+  int64_t* out[7] = {logit_tiles_done, logit_tiles, combine_slabs_done, combine_slabs, screened_tiles, onehot_row_tiles,
+                     certified_row_tiles};
+  for (int i = 0; i < 7; ++i)
     if (out[i]) *out[i] = (int64_t)h[i];
   return ASD_OK;
 }

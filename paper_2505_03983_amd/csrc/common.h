@@ -39,6 +39,7 @@ struct PlanOut {
   int64_t* in_off = nullptr;    // NULL: the kernel writes no plan
   int64_t* out_off = nullptr;
   int32_t* row_tau = nullptr;
+  int32_t* row_chain = nullptr; // chain of every row (a hint for the denoiser: rows of one chain are alike)
   int32_t* n_rows = nullptr;    // [2]: rows of the draft call, rows of the verify call
   const int32_t* tau = nullptr; // step -> time index
   int64_t* row_counts = nullptr;  // [2] running totals for the profiler, or NULL
@@ -60,6 +61,9 @@ struct RowPlan {
   const int64_t* out_off; // DEV [n]
   const int32_t* tau;     // DEV [n]
   int call;               // 0: draft model call (one row per chain), 1: verify (batched)
+  // DEV [n] or NULL: the chain (0 .. chains-1) every row belongs to.  Only a hint: a denoiser may use what it learnt
+  // about a chain's earlier rows to guess -- never to decide -- something about this one.
+  const int32_t* chain = nullptr;
 };
 
 struct GmmState;
@@ -116,6 +120,7 @@ struct asd_ctx {
   int64_t* in_off = nullptr;
   int64_t* out_off = nullptr;
   int32_t* row_tau = nullptr;
+  int32_t* row_chain = nullptr;   // chain of every row of the current plan
   int32_t* n_rows_dev = nullptr;  // DEV [2]: rows of the current draft-call / verify-call plan
   // x0a: model value at y_a of every chain [B, d]
   float* x0a = nullptr;

@@ -39,6 +39,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i8_colmax_stream_kernel(int
                                                                              const uint16_t* __restrict__ A, int64_t lda,
                                                                              const uint16_t* __restrict__ W, int64_t ldw,
                                                                              const int32_t* __restrict__ on,
+                                                                             const int32_t* __restrict__ live_cols,
                                                                              int32_t* __restrict__ out, int nsub) {
   static_assert(Cfg::PLANES == 1, "one plane");
   constexpr int BM = Cfg::BM, BN = Cfg::BN, STAGES = Cfg::STAGES, MI = Cfg::MI, NJ = Cfg::NJ, NW = Cfg::NW;
@@ -48,7 +49,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i8_colmax_stream_kernel(int
 
   if (on && *on == 0) return;   // the caller's switch, in device memory
   const int N = min(N_dev ? *N_dev : N_max, N_max);
-  const int ntm = Ma / BM, ntn = (N + BN - 1) / BN;
+  // live_cols (or NULL): [0] = how many column tiles of W are wanted, then their indices (each below ceil(N / BN))
+  const int ntn_all = (N + BN - 1) / BN;
+  const int ntm = Ma / BM, ntn = live_cols ? max(0, min(live_cols[0], ntn_all)) : ntn_all;
   const int total = ntm * ntn;
   if ((int)blockIdx.x >= total) return;
   const int n_my = (total - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // tiles of this workgroup
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i8_colmax_stream_kernel(int
   const uint16_t* ap[A_LOADS];
   const uint16_t* wp[W_LOADS];
   auto point_at = [&](int tile) {   // loader addresses of slab 0 of a tile
-    const int m0 = (tile % ntm) * BM, n0 = (tile / ntm) * BN;
+    const int m0 = (tile % ntm) * BM, n0 = (live_cols ? max(0, min(live_cols[1 + tile / ntm], ntn_all - 1)) : tile / ntm) * BN;
 #pragma unroll
     for (int p = 0; p < A_LOADS; ++p) {
       const int row = (wave + NW * p) * 8 + lr;
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i8_colmax_stream_kernel(int
     }
     if (++kt_c == nk) {   // the tile is complete: reduce it, clear the accumulators
       const int tile = (int)blockIdx.x + ti_c * (int)gridDim.x;
-      const int m0 = (tile % ntm) * BM, n0 = (tile / ntm) * BN;
+      const int m0 = (tile % ntm) * BM, n0 = (live_cols ? max(0, min(live_cols[1 + tile / ntm], ntn_all - 1)) : tile / ntm) * BN;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         // entry r of block i is row 32 i + 8 (r / 4) + 4 half + r % 4 of the wavefront's rows, column 32 j + l32
@@ -220,7 +223,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_i8_colmax_stream_kernel(int
 template <class Cfg>
 inline hipError_t launch_gemm_i8_colmax_stream(int Ma, const int* N_dev, int N_max, int K16, const uint16_t* A,
                                                int64_t lda, const uint16_t* W, int64_t ldw, const int32_t* on,
-                                               int32_t* out, int nsub, int wgs, hipStream_t st) {
+                                               const int32_t* live_cols, int32_t* out, int nsub, int wgs,
+                                               hipStream_t st) {
   if (K16 <= 0 || K16 % 64 != 0 || Ma <= 0 || Ma % Cfg::BM != 0 || lda % 8 != 0 || ldw % 8 != 0 || wgs <= 0 ||
       nsub < Ma / Cfg::WM)
     return hipErrorInvalidValue;
@@ -232,7 +236,7 @@ inline hipError_t launch_gemm_i8_colmax_stream(int Ma, const int* N_dev, int N_m
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(Cfg::THREADS), Cfg::LDS_BYTES, st, Ma, N_dev, N_max, K16, A, lda, W, ldw,
-                     on, out, nsub);
+                     on, live_cols, out, nsub);
   return hipGetLastError();
 }
 

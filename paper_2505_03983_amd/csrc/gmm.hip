@@ -24,6 +24,8 @@
 //
 // The verify call of the split path leaves out the matrix work whose result is
 // an exact zero, bit-identically (sections below, in this order of the call):
+//  0. certificate: row tiles whose rows are provably one-hot on the component their chain's draft-call row sat on
+//     are written in closed form and skip everything else;
 //  1. screening: an int8 product with a rigorous error bound finds the tiles
 //     of logits that cannot hold a softmax weight other than 0.0f;
 //  2. the first GEMM computes the other tiles only (list form of the kernel);
@@ -247,7 +249,7 @@ struct LogitOp {
   static constexpr bool kSplitK = false;
   static constexpr bool kSparseK = false;
   static constexpr bool kTileList = true;
-  static constexpr bool kRowTileSkip = false;
+  static constexpr bool kRowTileSkip = true;
   float* logits;
   int64_t ld;
   float* pmax;
@@ -263,6 +265,11 @@ struct LogitOp {
   const uint32_t* tile_list = nullptr;
   const int32_t* tile_count = nullptr;
   int list_cap = 0;
+  // NULL, or [row tiles of kSkipTile rows]: 1 = nobody will read this tile's logits (the one-hot certificate below
+  // has written its rows)
+  const uint8_t* skip_tile = nullptr;
+  static constexpr int kSkipTile = 128;
+  __device__ __forceinline__ bool skip_row_tile(int m0) const { return skip_tile && skip_tile[m0 / kSkipTile] != 0; }
   static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
   // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
@@ -520,13 +527,16 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
                                                          uint8_t* __restrict__ glive,
                                                          const float* __restrict__ logits, int64_t ldl, int gcols,
                                                          int32_t* __restrict__ onehot, uint8_t* __restrict__ onehot_tile,
+                                                         const uint8_t* __restrict__ cert_tile,
                                                          unsigned long long* __restrict__ counts) {
-  // counts (or NULL): [5] += row tiles found one-hot
+  // counts (or NULL): [5] += row tiles found one-hot.  cert_tile (or NULL): row tiles already known to be one-hot
+  // (gmm_certify_kernel); their logits do not exist.
   extern __shared__ int s_any[];   // [np], then one flag: every row so far is one-hot
   constexpr int BM = CombineOp::kRowmaxTile, RW = 4;
   const int n = min(*n_dev, n_max);
   const int m0 = blockIdx.x * BM;
   if (m0 >= n) return;
+  if (cert_tile && cert_tile[blockIdx.x]) return;
   const bool want_onehot = onehot && np <= 64 && gcols == 64;
   for (int q = threadIdx.x; q < np; q += 256) s_any[q] = 0;
   if (threadIdx.x == 0) s_any[np] = want_onehot ? 1 : 0;
@@ -581,9 +591,16 @@ __global__ __launch_bounds__(256) void gmm_rowmax_kernel(const int* __restrict__
 __global__ __launch_bounds__(256) void gmm_rowmax_rows_kernel(const int* __restrict__ n_dev, int n_max, int np,
                                                               const float* __restrict__ pmax, float* __restrict__ rmax,
                                                               const float* __restrict__ logits, int64_t ldl,
-                                                              int32_t* __restrict__ onehot) {
+                                                              int32_t* __restrict__ onehot,
+                                                              const int32_t* __restrict__ chain,
+                                                              int32_t* __restrict__ chain_comp,
+                                                              const uint8_t* __restrict__ cert_tile) {
+  // chain, chain_comp (or NULL): the component of a one-hot row (or -1) is also kept per chain, as the candidate of
+  // the one-hot certificate (gmm_certify_kernel).  cert_tile (or NULL): row tiles it has certified in this call --
+  // their rows have no logits, and their chains' candidates stand.
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= min(*n_dev, n_max)) return;
+  if (cert_tile && cert_tile[row / CombineOp::kRowmaxTile]) return;
   const float* p = pmax + (int64_t)row * np;
   float mx = -INFINITY;
   for (int q = lane; q < np; q += 64) mx = fmaxf(mx, p[q]);
@@ -591,7 +608,10 @@ __global__ __launch_bounds__(256) void gmm_rowmax_rows_kernel(const int* __restr
   if (lane == 0) rmax[row] = mx;
   if (onehot) {
     const int b = onehot_component(p, np, mx, logits + (int64_t)row * ldl, lane);
-    if (lane == 0) onehot[row] = b;
+    if (lane == 0) {
+      onehot[row] = b;
+      if (chain && chain_comp) chain_comp[chain[row]] = b;
+    }
   }
 }
 __global__ __launch_bounds__(CombineOp::kRowmaxTile) void gmm_onehot_tiles_kernel(const int* __restrict__ n_dev, int n_max,
@@ -613,9 +633,12 @@ __global__ __launch_bounds__(256) void gmm_onehot_kernel(const int* __restrict__
                                                          float* __restrict__ out_base,
                                                          const int64_t* __restrict__ out_off,
                                                          const float4* __restrict__ coef_tau,
-                                                         const int32_t* __restrict__ tau) {
+                                                         const int32_t* __restrict__ tau,
+                                                         const uint8_t* __restrict__ cert_tile) {
+  // cert_tile (or NULL): one-hot row tiles whose rows gmm_certify_kernel has written already
   const int m = blockIdx.x;
   if (m >= min(*n_dev, n_max) || !onehot_tile[m / CombineOp::kRowmaxTile]) return;
+  if (cert_tile && cert_tile[m / CombineOp::kRowmaxTile]) return;
   const float4 cf = coef_tau[tau[m]];
   const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
   const float4* mu = reinterpret_cast<const float4*>(means + (int64_t)onehot[m] * d);
@@ -626,6 +649,188 @@ __global__ __launch_bounds__(256) void gmm_onehot_kernel(const int* __restrict__
     const float4 xv = x[j], mv = mu[j];
     o[j] = make_float4(fmaf(cf.z, xv.x, __fmul_rn(cf.w, mv.x + 0.f)), fmaf(cf.z, xv.y, __fmul_rn(cf.w, mv.y + 0.f)),
                        fmaf(cf.z, xv.z, __fmul_rn(cf.w, mv.z + 0.f)), fmaf(cf.z, xv.w, __fmul_rn(cf.w, mv.w + 0.f)));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// One-hot certificate of a model call.
+//
+// Late in a chain a row lies so close to s mu_b -- b the component the chain's last draft-call row was found one-hot
+// on -- that the distance from mu_b to its nearest other mean alone proves every other softmax weight an exact zero,
+// with no product against the other means.  For a row x, a candidate b (any guess is safe: a wrong one fails the
+// test) and any s >= 0, with e = x - s mu_b, D_n = mu_n - mu_b, a_n = |D_n|:
+//   logit_n - logit_b  =  kappa' <x, D_n> - gamma' (|mu_n|^2 - |mu_b|^2) + log2 w_n - log2 w_b,
+//   <x, D_n>  =  s <mu_b, D_n> + <e, D_n>  <=  s (|mu_n|^2 - |mu_b|^2 - a_n^2) / 2 + |e| a_n        (Cauchy-Schwarz).
+// With A = kappa' s, B = kappa' |e| the part that depends on a_n is the parabola  f(a) = -(A/2) a^2 + B a, which
+// falls beyond its vertex B / A: if the nearest neighbour of mu_b is at least that far, a_min(b) >= B / A, then
+// f(a_n) <= f(a_min(b)) for every n.  What is left, (A/2 - gamma') (|mu_n|^2 - |mu_b|^2) + log2 w_n - log2 w_b, is
+// small (A/2 = gamma' at s = sqrt(abar)) and is bounded with the extremes of |mu|^2 and log2 w over the mixture.  So
+//   logit_n - logit_b  <=  f(a_min(b)) + (A/2 - gamma') (q* - |mu_b|^2) + max log2 w - log2 w_b      for all n != b,
+// q* = max or min |mu|^2 by the sign of the factor: four numbers per row -- s = <x, mu_b> / |mu_b|^2, which makes |e|
+// least, |e|, |x| -- and one table, a_min, of C floats.  A row passes when the bound stays below
+// -(kZeroGap + margin).  The exact path would then find logit b the row's maximum and nothing else within kZeroGap of
+// it, so onehot[row] = b is what gmm_rowmax_kernel would have written and out = fma(c_x', x, c_m' mu_b) what
+// gmm_onehot_kernel would have: the kernel writes both at once, from the registers the row was tested in.  A row tile
+// (kCertTile rows) whose rows all passed is certified: it skips the screening pass, both GEMMs and the row maxima.
+// In any other tile the normal path runs over all rows and overwrites what the passing rows wrote, with the same bits.
+//
+// Margin.  A computed logit is fl(c1 acc + fl(-c2 musq[n] + bias[n])), acc the split-operand sum: three of the nine
+// products of pieces are dropped (3 * 2^-24 sum |x_k mu_k| at most) and 6 d products are added in fp32 in some order
+// (6 d 2^-24 sum |x_k mu_k| at most), so for d <= 2048 |acc - <x, mu_n>| <= 2^-10 |x| |mu_n|.  Two logits are
+// compared: c1 2^-9 |x| max |mu| covers the sums.  musq[] is an fp32 sum of squares (within 2^-13 of |mu|^2, which
+// the geometry above is about): (c2 + |A/2 - c2|) 2^-12 max |mu|^2.  1e-5 of the terms' magnitudes covers the
+// roundings of the affine map and of the bound's own evaluation here (a few 2^-24 each).
+// ---------------------------------------------------------------------------
+constexpr int kCertTile = CombineOp::kRowmaxTile;   // rows per certified tile = rows per one-hot flag
+
+// a_min[b] = a lower bound of the distance from mu_b to the nearest other mean: one thread per pair (b, n), double
+// sums from LDS tiles of 16 + 16 means, then a minimum per b (positive floats order like their bit patterns).
+// a_min must hold +inf (0x7f800000) on entry.
+__global__ __launch_bounds__(256) void gmm_cert_amin_kernel(int C, int d, const float* __restrict__ means,
+                                                            int32_t* __restrict__ a_min) {
+  __shared__ float s_b[16][65], s_n[16][65];
+  const int tb = threadIdx.x >> 4, tn = threadIdx.x & 15;
+  const int b0 = blockIdx.y * 16, n0 = blockIdx.x * 16;
+  double dist = 0.0;
+  for (int k0 = 0; k0 < d; k0 += 64) {
+    for (int i = threadIdx.x; i < 16 * 64; i += 256) {
+      const int r = i >> 6, k = i & 63;
+      const bool kin = k0 + k < d;
+      s_b[r][k] = (kin && b0 + r < C) ? means[(int64_t)(b0 + r) * d + k0 + k] : 0.f;
+      s_n[r][k] = (kin && n0 + r < C) ? means[(int64_t)(n0 + r) * d + k0 + k] : 0.f;
+    }
+    __syncthreads();
+    for (int k = 0; k < 64; ++k) {
+      const double df = (double)s_n[tn][k] - (double)s_b[tb][k];   // the difference of two floats: exact
+      dist = fma(df, df, dist);
+    }
+    __syncthreads();
+  }
+  const int b = b0 + tb, n = n0 + tn;
+  if (b >= C || n >= C || b == n) return;
+  // (the double sum is off by d 2^-53 of itself at most; rounded down, then one part in a million off)
+  const float a = __double2float_rd(sqrt(dist)) * (1.f - 1e-6f);
+  atomicMin(&a_min[b], __float_as_int(fmaxf(a, 0.f)));
+}
+
+// One wavefront per row, four rows per workgroup; V float4 per lane hold the row (d <= 256 V) and as many mu_b.
+// chain_comp[chain[row]]: the candidate component of the row (< 0: none).  glob = (largest |mu_n|, largest and
+// smallest musq, -), globw = (largest log2 w_n, largest |log2 w_n|, -, -).  Rows of a tile count themselves through
+// tile_cnt[tile] (finished in the low half, passed in the high half); the workgroup that brings the tile to its
+// full count writes cert_tile (always) and onehot_tile = 1 (if certified) and clears the counter for the next call.
+// counts (or NULL): [5] += one-hot row tiles, [6] += certified row tiles (verify call only: count_tiles).
+template <int V>
+__global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict__ n_dev, int n_max, int d, int C,
+                                                          const float* __restrict__ in_base,
+                                                          const int64_t* __restrict__ in_off,
+                                                          float* __restrict__ out_base,
+                                                          const int64_t* __restrict__ out_off,
+                                                          const int32_t* __restrict__ tau,
+                                                          const float4* __restrict__ coef_tau,
+                                                          const int32_t* __restrict__ chain,
+                                                          const int32_t* __restrict__ chain_comp,
+                                                          const float* __restrict__ means,
+                                                          const float* __restrict__ musq,
+                                                          const float* __restrict__ log_w,
+                                                          const float* __restrict__ a_min, float4 glob, float4 globw,
+                                                          int32_t* __restrict__ onehot,
+                                                          uint8_t* __restrict__ onehot_tile,
+                                                          uint8_t* __restrict__ cert_tile,
+                                                          int32_t* __restrict__ tile_cnt,
+                                                          unsigned long long* __restrict__ counts) {
+  static_assert(kCertTile % 4 == 0, "whole workgroups per row tile");
+  __shared__ int s_pass[4];
+  const int n = min(*n_dev, n_max), m0 = blockIdx.x * 4;
+  if (m0 >= n) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = m0 + wave;
+  bool pass = false;
+  if (m < n) {   // the same for the whole wavefront
+    int b = chain_comp[chain[m]];
+    if (b >= C) b = -1;
+    if (b >= 0) {
+      const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
+      const float4* mu = reinterpret_cast<const float4*>(means + (int64_t)b * d);
+      float4 xv[V], mv[V];
+      float p = 0.f, xx = 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const int j = lane + 64 * i;
+        const bool in = j < d / 4;
+        xv[i] = in ? x[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+        mv[i] = in ? mu[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+      const float4 cf = coef_tau[tau[m]];
+      const float qb = musq[b], am = a_min[b], bias_b = LogitOp::kLog2e * log_w[b];
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        p += (xv[i].x * mv[i].x + xv[i].y * mv[i].y) + (xv[i].z * mv[i].z + xv[i].w * mv[i].w);
+        xx += (xv[i].x * xv[i].x + xv[i].y * xv[i].y) + (xv[i].z * xv[i].z + xv[i].w * xv[i].w);
+      }
+      p = wave_sum(p);
+      xx = wave_sum(xx);
+      const float s = p / qb;   // any s is valid: its rounding does not matter
+      float r2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const float ex = fmaf(-s, mv[i].x, xv[i].x), ey = fmaf(-s, mv[i].y, xv[i].y);
+        const float ez = fmaf(-s, mv[i].z, xv[i].z), ew = fmaf(-s, mv[i].w, xv[i].w);
+        r2 += (ex * ex + ey * ey) + (ez * ez + ew * ew);
+      }
+      r2 = wave_sum(r2);
+      // upper bounds of the two norms (their fp32 sums are off by a few 2^-24 d of themselves at most)
+      const float e_up = sqrtf(r2) * (1.f + 0x1p-10f), x_up = sqrtf(xx) * (1.f + 0x1p-10f);
+      const float c1 = LogitOp::kLog2e * cf.x, c2 = LogitOp::kLog2e * cf.y;
+      const float A = c1 * s, B = c1 * e_up, half = 0.5f * A;
+      const float f = am * (B - half * am);                 // the parabola at the nearest neighbour ...
+      const bool beyond = am * A >= B;                      // ... which must lie beyond its vertex
+      const float dq = half - c2;
+      const float qterm = dq * ((dq >= 0.f ? glob.y : glob.z) - qb);
+      const float bterm = globw.x - bias_b;
+      const float mag = (am * B + half * am * am) + fabsf(qterm) + (globw.y + fabsf(bias_b)) + c2 * glob.y;
+      const float margin = fmaf(c1 * x_up * glob.x, 0x1p-9f + 1e-5f,
+                                fmaf((c2 + fabsf(dq)) * glob.y, 0x1p-12f, fmaf(1e-5f, mag, 1.f)));
+      // (a NaN or an infinity anywhere above fails these comparisons)
+      pass = s >= 0.f && c1 >= 0.f && c2 >= 0.f && beyond && mag < 1e30f && margin < 1e30f &&
+             (f + qterm + bterm) + (CombineOp::kZeroGap + margin) < 0.f;
+      if (pass) {
+        // what the second GEMM's epilogue computes with acc = mu_b (+0.0: the accumulator never holds a negative
+        // zero) and scale = c_m' / 1.0
+        float4* o = reinterpret_cast<float4*>(out_base + out_off[m]);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const int j = lane + 64 * i;
+          if (j < d / 4)
+            o[j] = make_float4(fmaf(cf.z, xv[i].x, __fmul_rn(cf.w, mv[i].x + 0.f)),
+                               fmaf(cf.z, xv[i].y, __fmul_rn(cf.w, mv[i].y + 0.f)),
+                               fmaf(cf.z, xv[i].z, __fmul_rn(cf.w, mv[i].z + 0.f)),
+                               fmaf(cf.z, xv[i].w, __fmul_rn(cf.w, mv[i].w + 0.f)));
+        }
+        if (lane == 0) onehot[m] = b;
+      }
+    }
+  }
+  if (lane == 0) s_pass[wave] = pass ? 1 : 0;
+  __syncthreads();   // the rows of all four wavefronts before the workgroup's count
+  if (threadIdx.x == 0) {
+    const int tile = m0 / kCertTile;
+    const int rows = min(4, n - m0), rows_tile = min(kCertTile, n - tile * kCertTile);
+    const int add = rows + ((s_pass[0] + s_pass[1] + s_pass[2] + s_pass[3]) << 16);
+    // (no fence: within this kernel only the counter passes between workgroups; the flags and the rows are read by
+    // later kernels.  A device-wide release per workgroup would write the L2 back sixteen thousand times.)
+    const int seen = atomicAdd(&tile_cnt[tile], add) + add;
+    if ((seen & 0xffff) == rows_tile) {   // the tile is complete
+      const bool all = (seen >> 16) == rows_tile;
+      tile_cnt[tile] = 0;
+      cert_tile[tile] = all ? 1 : 0;
+      if (all) {
+        onehot_tile[tile] = 1;
+        if (counts) {
+          atomicAdd(&counts[5], 1ull);
+          atomicAdd(&counts[6], 1ull);
+        }
+      }
+    }
   }
 }
 
@@ -718,14 +923,33 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
                                                               const int64_t* __restrict__ in_off,
                                                               const int32_t* __restrict__ on,
                                                               int8_t* __restrict__ xq, float2* __restrict__ xs,
-                                                              int32_t* __restrict__ tile_count) {
-  // list lengths (the decision kernel appends) and tickets of the exact GEMM
-  if (blockIdx.x == 0)
-    for (int i = threadIdx.x; i < kTicketInts; i += 256) tile_count[i] = 0;
-  if (*on == 0) return;
+                                                              int32_t* __restrict__ tile_count,
+                                                              const uint8_t* __restrict__ cert_tile,
+                                                              int32_t* __restrict__ live_tiles) {
+  // cert_tile, live_tiles (or NULL): row tiles of kCertTile rows that need no screening (gmm_certify_kernel) are not
+  // packed, and the others are listed for the screening GEMM: live_tiles[0] = how many, then their indices in order
   const int n = min(*n_dev, n_max);
-  const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (blockIdx.x == 0) {
+    // list lengths (the decision kernel appends) and tickets of the exact GEMM
+    for (int i = threadIdx.x; i < kTicketInts; i += 256) tile_count[i] = 0;
+    if (live_tiles && threadIdx.x < 64) {
+      const int nt = (n + kCertTile - 1) / kCertTile;
+      int base = 0;
+      for (int t0 = 0; t0 < nt; t0 += 64) {
+        const int tt = t0 + lane;
+        const bool live = tt < nt && !cert_tile[tt];
+        const unsigned long long mask = __ballot(live);
+        if (live) live_tiles[1 + base + __popcll(mask & ((1ull << lane) - 1ull))] = tt;
+        base += __popcll(mask);
+      }
+      if (lane == 0) live_tiles[0] = base;
+    }
+  }
+  if (*on == 0) return;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (m >= n) return;
+  if (cert_tile && cert_tile[m / kCertTile]) return;
   const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
   constexpr int kMaxV = 2048 / 4 / 64;
   float4 v[kMaxV];
@@ -770,6 +994,7 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
                                                                 int32_t* __restrict__ tile_count, int list_cap,
                                                                 float* __restrict__ pmax, int np, int gpt, int halves,
                                                                 float* __restrict__ logits, int64_t ldl,
+                                                                const uint8_t* __restrict__ cert_tile,
                                                                 unsigned long long* __restrict__ counts) {
   extern __shared__ int s_flag[];   // [2][ntn]: upper, lower half of the rows
   constexpr int BM = GmmTileSplit::BM, RW = 4;   // rows a wavefront works on at a time (their loads overlap)
@@ -777,6 +1002,10 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
   const int m0 = blockIdx.x * BM;
   if (m0 >= n) return;
   const bool screened = *on != 0;
+  if (cert_tile && cert_tile[blockIdx.x]) {   // certified one-hot (gmm_certify_kernel): no tile of logits is wanted
+    if (counts && threadIdx.x == 0) atomicAdd(&counts[1], (unsigned long long)(2 * ntn));   // (not among the screened)
+    return;
+  }
   const bool lower_exists = m0 + BM / 2 < n;
   for (int t = threadIdx.x; t < 2 * ntn; t += 256) s_flag[t] = screened ? 0 : ((t < ntn || lower_exists) ? 1 : 0);
   __syncthreads();
@@ -874,12 +1103,18 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
 constexpr int kRegimeBlocks = 64;
 __global__ __launch_bounds__(256) void gmm_regime_kernel(const int* __restrict__ n_dev, int n_max, int np,
                                                          const float* __restrict__ pmax, int32_t* __restrict__ on,
-                                                         int32_t* __restrict__ acc) {
+                                                         int32_t* __restrict__ acc,
+                                                         const uint8_t* __restrict__ cert_tile) {
+  // cert_tile (or NULL): row tiles certified one-hot; their rows have no logits and keep one group alive each
   const int n = min(*n_dev, n_max);
   if (n <= 0) return;   // every workgroup alike: nothing is counted, the verdict stands
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float alive = 0.f;
   for (int m = blockIdx.x * 4 + wave; m < n; m += 4 * gridDim.x) {
+    if (cert_tile && cert_tile[m / kCertTile]) {
+      alive += 1.f;
+      continue;
+    }
     const float* p = pmax + (int64_t)m * np;
     float mx = -INFINITY;
     for (int q = lane; q < np; q += 64) mx = fmaxf(mx, p[q]);
@@ -1014,8 +1249,8 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     ASD_HIP(hipMalloc(&g->glive, (size_t)ceil_div(ctx->n_rows_max, CombineOp::kRowmaxTile) * np_v));
     ASD_HIP(hipMalloc(&g->onehot, sizeof(int32_t) * (size_t)ctx->n_rows_max));
     ASD_HIP(hipMalloc(&g->onehot_tile, (size_t)ceil_div(ctx->n_rows_max, CombineOp::kRowmaxTile)));
-    ASD_HIP(hipMalloc(&g->work_counts, 6 * sizeof(unsigned long long)));
-    ASD_HIP(hipMemset(g->work_counts, 0, 6 * sizeof(unsigned long long)));
+    ASD_HIP(hipMalloc(&g->work_counts, 8 * sizeof(unsigned long long)));
+    ASD_HIP(hipMemset(g->work_counts, 0, 8 * sizeof(unsigned long long)));
     // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
     if (d % 128 == 0 && C % ScreenTile::BM == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
         split3_sparse_fits<GmmTileSplit>(C, np_v, GmmTileSplit::WN)) {
@@ -1038,6 +1273,52 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
       ASD_HIP(hipGetLastError());
       ASD_HIP(hipDeviceSynchronize());
       g->screen_ok = true;
+      // one-hot certificate: needs the one-hot closed form (64 groups of 64 columns at most)
+      static_assert(ScreenTile::BN == kCertTile && GmmTileSplit::BM == kCertTile, "one row tile for every stage");
+      if (np_v <= 64 && GmmTileSplit::WN == 64 && d % 4 == 0) {
+        float* h_q = new (std::nothrow) float[2 * (size_t)C];
+        if (!h_q) return ASD_ENOMEM;
+        hipError_t e1 = hipMemcpy(h_q, g->musq, sizeof(float) * (size_t)C, hipMemcpyDeviceToHost);
+        hipError_t e2 = hipMemcpy(h_q + C, g->log_w, sizeof(float) * (size_t)C, hipMemcpyDeviceToHost);
+        float qmax = 0.f, qmin = INFINITY, bmax = -INFINITY, babs = 0.f;
+        for (int k = 0; k < C; ++k) {
+          qmax = fmaxf(qmax, h_q[k]);
+          qmin = fminf(qmin, h_q[k]);
+          const float bias = LogitOp::kLog2e * h_q[C + k];   // as the kernels form it
+          bmax = fmaxf(bmax, bias);
+          babs = fmaxf(babs, fabsf(bias));
+        }
+        delete[] h_q;
+        ASD_HIP(e1);
+        ASD_HIP(e2);
+        // (musq is an fp32 sum of d squares: 1e-3 covers its rounding many times over)
+        const float mumax = sqrtf(qmax) * 1.001f;
+        g->cert_glob = make_float4(mumax, qmax, qmin, 0.f);
+        g->cert_globw = make_float4(bmax, babs, 0.f, 0.f);
+        ASD_HIP(hipMalloc(&g->cert_amin, sizeof(float) * (size_t)C));
+        ASD_HIP(hipMemset(g->cert_amin, 0, sizeof(float) * (size_t)C));
+        {
+          int32_t* h_inf = new (std::nothrow) int32_t[C];
+          if (!h_inf) return ASD_ENOMEM;
+          for (int k = 0; k < C; ++k) h_inf[k] = 0x7f800000;
+          hipError_t e3 = hipMemcpy(g->cert_amin, h_inf, sizeof(int32_t) * (size_t)C, hipMemcpyHostToDevice);
+          delete[] h_inf;
+          ASD_HIP(e3);
+        }
+        ASD_HIP(hipMalloc(&g->chain_comp, sizeof(int32_t) * (size_t)ctx->B));
+        ASD_HIP(hipMemset(g->chain_comp, 0xff, sizeof(int32_t) * (size_t)ctx->B));   // -1: no candidate yet
+        ASD_HIP(hipMalloc(&g->cert_tile, (size_t)row_tiles));
+        ASD_HIP(hipMemset(g->cert_tile, 0, (size_t)row_tiles));
+        ASD_HIP(hipMalloc(&g->cert_cnt, sizeof(int32_t) * (size_t)row_tiles));
+        ASD_HIP(hipMemset(g->cert_cnt, 0, sizeof(int32_t) * (size_t)row_tiles));
+        ASD_HIP(hipMalloc(&g->live_tiles, sizeof(int32_t) * (1 + (size_t)row_tiles)));
+        ASD_HIP(hipMemset(g->live_tiles, 0, sizeof(int32_t) * (1 + (size_t)row_tiles)));
+        hipLaunchKernelGGL(gmm_cert_amin_kernel, dim3((unsigned)ceil_div(C, 16), (unsigned)ceil_div(C, 16)), dim3(256), 0,
+                           0, C, d, g->means, reinterpret_cast<int32_t*>(g->cert_amin));
+        ASD_HIP(hipGetLastError());
+        ASD_HIP(hipDeviceSynchronize());
+        g->cert_ok = std::isfinite(mumax) && std::isfinite(babs);
+      }
     }
   }
   if (g->use_mfma) {
@@ -1096,6 +1377,11 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->glive);
   (void)hipFree(g->onehot);
   (void)hipFree(g->onehot_tile);
+  (void)hipFree(g->cert_amin);
+  (void)hipFree(g->chain_comp);
+  (void)hipFree(g->cert_tile);
+  (void)hipFree(g->cert_cnt);
+  (void)hipFree(g->live_tiles);
   delete g;
   ctx->gmm = nullptr;
 }
@@ -1135,21 +1421,38 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   LogitOp op1{g->logits, C, g->pmax, np, g->coef_tau, rows.tau, g->musq, g->log_w};
   // the verify call of the split path may be screened; only when the second GEMM skips what the first leaves out
   const bool screen = split && rows.call == 1 && g->screen_ok && g->screen_mode != 0 && g->sparse_combine;
+  // ... and rows may be certified one-hot before anything else (the plan says which chain a row belongs to): in the
+  // verify call, and in the draft call of a context whose verify calls are
+  const bool cert = split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine && g->cert_ok && g->cert_on &&
+                    rows.chain != nullptr && (rows.call == 1 || g->split_draft_ok);
+  const uint8_t* cert_tile = cert ? g->cert_tile : nullptr;
+  if (cert) {
+    ProfScope ps(ctx, ASD_PROF_GMM_SCREEN, rows.call, st);
+    auto kern = d <= 1024 ? gmm_certify_kernel<4> : gmm_certify_kernel<8>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d, C, rows.in_base,
+                       rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, rows.chain, g->chain_comp,
+                       g->means, g->musq, g->log_w, g->cert_amin, g->cert_glob, g->cert_globw, g->onehot, g->onehot_tile,
+                       g->cert_tile, g->cert_cnt, (ctx->prof.on && rows.call == 1) ? g->work_counts : nullptr);
+    ASD_HIP(hipGetLastError());
+    op1.skip_tile = cert_tile;
+  }
   if (screen) {
     ProfScope ps(ctx, ASD_PROF_GMM_SCREEN, rows.call, st);
     const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
     const int ntn = C / GmmTileSplit::BN;
     hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
-                       rows.in_base, rows.in_off, on, g->xq, g->xs, g->tile_count);
+                       rows.in_base, rows.in_off, on, g->xq, g->xs, g->tile_count, cert_tile,
+                       cert ? g->live_tiles : (int32_t*)nullptr);
     ASD_HIP(hipGetLastError());
     // int8 operands, handed over as 16-bit units (two k each): the means as the kernel's rows, the call's rows as its columns
     ASD_HIP(launch_gemm_i8_colmax_stream<ScreenTile>(C, rows.n_dev, n, d / 2, reinterpret_cast<const uint16_t*>(g->means_q),
-                                                     d / 2, reinterpret_cast<const uint16_t*>(g->xq), d / 2, on, g->imax,
-                                                     g->nps, kScreenWgs, st));
+                                                     d / 2, reinterpret_cast<const uint16_t*>(g->xq), d / 2, on,
+                                                     cert ? g->live_tiles : (const int32_t*)nullptr, g->imax, g->nps,
+                                                     kScreenWgs, st));
     hipLaunchKernelGGL(gmm_screen_decide_kernel, dim3((unsigned)ceil_div(n, GmmTileSplit::BM)), dim3(256),
                        sizeof(int) * 2 * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
                        g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_list, g->tile_count, g->list_cap,
-                       g->pmax, np, GmmTileSplit::WGN, g->split_draft_ok ? 1 : 0, g->logits, (int64_t)C,
+                       g->pmax, np, GmmTileSplit::WGN, g->split_draft_ok ? 1 : 0, g->logits, (int64_t)C, cert_tile,
                        ctx->prof.on ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.tile_list = g->tile_list;
@@ -1173,7 +1476,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   if (rows.call == 0 && g->screen_ok && g->screen_mode == 1) {   // this round's verify call: screen or not
     hipLaunchKernelGGL(gmm_regime_kernel, dim3(kRegimeBlocks), dim3(256), 0, st, rows.n_dev, n, np, g->pmax,
-                       g->screen_on, g->screen_on + 2);
+                       g->screen_on, g->screen_on + 2, cert_tile);
     ASD_HIP(hipGetLastError());
   }
   RowSrc P{g->logits, nullptr, C};
@@ -1191,10 +1494,11 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
       hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
                          sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
                          gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
-                         ctx->prof.on ? g->work_counts : nullptr);
+                         cert_tile, ctx->prof.on ? g->work_counts : nullptr);
     } else {
       hipLaunchKernelGGL(gmm_rowmax_rows_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, np,
-                         g->pmax, g->rmax, g->logits, (int64_t)C, onehot ? g->onehot : (int32_t*)nullptr);
+                         g->pmax, g->rmax, g->logits, (int64_t)C, onehot ? g->onehot : (int32_t*)nullptr, rows.chain,
+                         (onehot && g->cert_ok) ? g->chain_comp : (int32_t*)nullptr, cert_tile);
       if (onehot)
         hipLaunchKernelGGL(gmm_onehot_tiles_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)),
                            dim3(CombineOp::kRowmaxTile), 0, st, rows.n_dev, n, g->onehot, g->onehot_tile);
@@ -1203,7 +1507,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     if (onehot) {
       hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
                          g->onehot_tile, g->means, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
-                         rows.tau);
+                         rows.tau, cert_tile);
       ASD_HIP(hipGetLastError());
       op2.onehot_tile = g->onehot_tile;
     }

@@ -32,9 +32,10 @@ struct GmmState {
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
-  // DEV [6], summed over the verify calls while profiling: tiles of logits computed / there were (calls that went
+  // DEV [8], summed over the verify calls while profiling: tiles of logits computed / there were (calls that went
   // through the screening launches), K slabs the second GEMM's workgroups visited / there were, tiles of the calls
-  // that were screened, row tiles of the second GEMM written in closed form (one-hot rows)
+  // that were screened, row tiles of the second GEMM written in closed form (one-hot rows), row tiles that the
+  // certificate below proved one-hot before any matrix work
   unsigned long long* work_counts = nullptr;
   bool sparse_combine = true;      // the second split GEMM of the verify call skips slabs of exact zeros (gemm_split3.h)
   // Screening of the verify call's logits GEMM (gmm.hip): an int8 GEMM finds the tiles whose softmax weights are
@@ -51,6 +52,18 @@ struct GmmState {
   int32_t* tile_count = nullptr;   // the lists' lengths and the tickets drawn from each (layout: gemm_split3.h)
   int list_cap = 0;
   int32_t* screen_on = nullptr;    // DEV [4]: the draft call's verdict for this round; the constant 1; two accumulators
+  // One-hot certificate (gmm.hip): rows proven one-hot from the distance of a mean to its nearest neighbour and the
+  // component the chain's last draft-call row sat on, written in closed form at once; row tiles of such rows skip the
+  // rest of the call.
+  bool cert_ok = false;            // the shape allows it (and the buffers below exist)
+  bool cert_on = true;             // the switch (asd_use_onehot_certificate)
+  float* cert_amin = nullptr;      // [C]: lower bounds of the distance from mu_b to the nearest other mean
+  float4 cert_glob = {0.f, 0.f, 0.f, 0.f};   // largest |mu_n|, largest and smallest musq
+  float4 cert_globw = {0.f, 0.f, 0.f, 0.f};  // largest log2 w_n, largest |log2 w_n|
+  int32_t* chain_comp = nullptr;   // [chains]: component of the chain's last one-hot draft-call row, or -1
+  uint8_t* cert_tile = nullptr;    // [row tiles]: 1 = certified in this call
+  int32_t* cert_cnt = nullptr;     // [row tiles]: rows of the tile that have finished / passed (zero between calls)
+  int32_t* live_tiles = nullptr;   // [1 + row tiles]: number of row tiles that are not certified, then their indices
   size_t rowwise_lds = 0;
   size_t lds_rowwise_bytes = 0;  // > 0: the mixture fits in LDS and d % 4 == 0 (gmm_rowwise_lds_kernel)
 };

@@ -21,6 +21,7 @@ __global__ void init_state_kernel(int B, int K, int d, const Key* __restrict__ k
     plan.in_off[c] = (int64_t)c * (K + 1) * d;
     plan.out_off[c] = (int64_t)c * d;
     plan.row_tau[c] = plan.tau[0];
+    plan.row_chain[c] = c;
     if (c == 0) {
       plan.n_rows[0] = B;
       plan.n_rows[1] = 0;
@@ -51,6 +52,7 @@ static PlanOut plan_out(asd_ctx* ctx, int32_t* ring) {
   p.in_off = ctx->in_off;
   p.out_off = ctx->out_off;
   p.row_tau = ctx->row_tau;
+  p.row_chain = ctx->row_chain;
   p.n_rows = ctx->n_rows_dev;
   p.tau = ctx->tau;
   p.row_counts = ctx->prof.on ? ctx->row_counts : nullptr;
@@ -105,7 +107,8 @@ template <int MODE>
 __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, int d, const int32_t* __restrict__ a,
                                                          const int32_t* __restrict__ tau,
                                                          int64_t* __restrict__ in_off, int64_t* __restrict__ out_off,
-                                                         int32_t* __restrict__ row_tau, int32_t* __restrict__ n_rows,
+                                                         int32_t* __restrict__ row_tau,
+                                                         int32_t* __restrict__ row_chain, int32_t* __restrict__ n_rows,
                                                          int32_t* __restrict__ ring,
                                                          int64_t* __restrict__ row_counts,
                                                          const int32_t* __restrict__ win,
@@ -153,6 +156,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
         in_off[off] = ((int64_t)c * (K + 1) + ac) * d;
         out_off[off] = (int64_t)c * d;
         row_tau[off] = tau[ac];
+        row_chain[off] = c;
       }
     } else {
       // the rows of a chain are written by a whole wavefront (consecutive entries, coalesced)
@@ -171,6 +175,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
           in_off[o_t + s - 1] = ((int64_t)c_t * (K + 1) + i) * d;
           out_off[o_t + s - 1] = ((int64_t)c_t * slots + sr) * d;
           row_tau[o_t + s - 1] = tau[i];
+          row_chain[o_t + s - 1] = c_t;
         }
       }
     }
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* ring) {
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
-                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 0, ring,
+                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 0, ring,
                      ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win,
                      ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L, 0);
   ASD_HIP(hipGetLastError());
@@ -199,7 +204,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   // up to 64 workgroups share the filling of a large plan (a chain per wavefront at a time, see the kernel)
   const unsigned wgs = (unsigned)std::min<int64_t>(64, std::max<int64_t>(1, ctx->n_rows_max / 1024));
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
-                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->n_rows_dev + 1, (int32_t*)nullptr,
+                     ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 1, (int32_t*)nullptr,
                      ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
                      ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0), ctx->cur_win ? 0 : model_row_block(ctx));
   ASD_HIP(hipGetLastError());
@@ -256,6 +261,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
         plan.in_off[base + s - 1] = ((int64_t)c * (K + 1) + i) * d;
         plan.out_off[base + s - 1] = ((int64_t)c * (Lwin + extra) + s) * d;
         plan.row_tau[base + s - 1] = plan.tau[i];
+        plan.row_chain[base + s - 1] = c;
       }
     }
   }
@@ -552,6 +558,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
       plan.in_off[idx] = ((int64_t)c * (K + 1) + a_next) * d;
       plan.out_off[idx] = (int64_t)c * d;
       plan.row_tau[idx] = plan.tau[a_next];
+      plan.row_chain[idx] = c;
       if (plan.row_counts) atomicAdd((unsigned long long*)&plan.row_counts[0], 1ull);
     }
   }

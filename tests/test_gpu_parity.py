@@ -304,7 +304,7 @@ def test_logit_screen_is_bit_identical_and_skips_work():
     levels through the model call alone, ragged row tile, every row of a tile near the same component so that
     tiles do die: always screened == never screened, bit for bit, tiles are left out, and the oracle agrees.
     (b) Whole samples (draft verdict -> screened or not, graphs on): the three modes give the same trajectories and
-    round counts bit for bit."""
+    round counts bit for bit, and so do samples without the one-hot certificate, which does certify row tiles."""
     cfg = dict(kind="gmm", d=128, C=1024, K=200, chains=72, L=16, var=0.25)
     T, p, model = oracle_setup(cfg)
     ctx = runtime.open_ctx(cfg, p, seed=0)
@@ -373,11 +373,33 @@ def test_logit_screen_is_bit_identical_and_skips_work():
         torch.cuda.synchronize()
         res.append((traj, rounds))
         ctx_b.use_sparse_combine(True)
+        # without the one-hot certificate (row tiles proven one-hot before any matrix work), and with it under the
+        # profiler (plain launches instead of graphs), which also says how many row tiles it took
+        assert ctx_b.onehot_certificate_active()
+        ctx_b.use_onehot_certificate(False)
+        assert not ctx_b.onehot_certificate_active()
+        ctx_b.set_seed(5)
+        traj = runtime.alloc_traj(ctx_b)
+        rounds = torch.zeros(cfg_b["chains"], dtype=torch.int32, device=DEV)
+        ctx_b.sample(traj, rounds)
+        torch.cuda.synchronize()
+        res.append((traj, rounds))
+        ctx_b.use_onehot_certificate(True)
+        ctx_b.profile_enable(True)
+        ctx_b.set_seed(5)
+        traj = runtime.alloc_traj(ctx_b)
+        rounds = torch.zeros(cfg_b["chains"], dtype=torch.int32, device=DEV)
+        ctx_b.sample(traj, rounds)
+        torch.cuda.synchronize()
+        res.append((traj, rounds))
+        work_b = ctx_b.profile_model_work()
+        ctx_b.profile_enable(False)
+        assert 0 < work_b[6] <= work_b[5]
         for traj, rounds in res[1:]:
             assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
         assert bool(torch.isfinite(res[0][0]).all())
-        _log("logit screen: whole samples of d", cfg_b["d"], "C", cfg_b["C"], "bit-identical in the three modes and with the dense second GEMM, rounds max",
-             int(res[0][1].max()))
+        _log("logit screen: whole samples of d", cfg_b["d"], "C", cfg_b["C"], "bit-identical in the three modes, with the dense second GEMM and without the certificate; rounds max",
+             int(res[0][1].max()), "row tiles in closed form", work_b[5], "of them certified", work_b[6])
         ctx_b.close()
 
 

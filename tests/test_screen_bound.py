@@ -1,13 +1,17 @@
 """The arithmetic behind the work the mixture denoiser's verify call leaves out, checked on the CPU (numpy only; no
 product or oracle code).
 
-Three facts the bit-identity of the screened path rests on:
+Four facts the bit-identity of the screened path rests on:
  * the int8 screening product's error bound: with x ~ sx qx and mu ~ sg qm (nearest integers in [-127, 127]),
    |sx sg <qx, qm> - <x, mu>| <= (sg / 2) |x|_1 + (sx / 2) |sg qm|_1;
  * the bounds U, L the decision is taken with really bracket the logits of a group, so that a tile declared dead
    holds only logits more than the zero gap below their rows' maxima -- and such logits give weights of exactly 0.0f;
  * a row with one weight of 1.0 and zeros gets mu_b bit for bit from the split-operand accumulation: the three bf16
-   pieces of an fp32 number add up exactly in the order the matrix cores add them.
+   pieces of an fp32 number add up exactly in the order the matrix cores add them;
+ * the one-hot certificate: with e = x - s mu_b and a_n = |mu_n - mu_b|, logit_n - logit_b <= -(A/2) a_n^2 + B a_n
+   + (A/2 - gamma') (|mu_n|^2 - |mu_b|^2) + log2 w_n - log2 w_b  (A = kappa' s, B = kappa' |e|), largest at the
+   nearest neighbour of mu_b once that lies beyond the parabola's vertex, so a row that passes has all other logits
+   more than the zero gap (plus what fp32 sums may be off by) below logit b.
 """
 import numpy as np
 
@@ -121,3 +125,65 @@ def test_one_hot_row_gives_the_mean_bit_for_bit():
     assert np.array_equal(acc.view(np.uint32), (mu + F(0)).view(np.uint32))
     # and the epilogue: scale = c_m' / 1.0 is c_m', out = fma(c_x', x, scale * acc) -- the same expression either way
     assert F(0.37) / F(1.0) == F(0.37)
+
+
+def test_onehot_certificate_bounds_every_other_logit():
+    """The one-hot certificate, re-derived in fp32 as its kernel evaluates it (nearest-neighbour distance rounded
+    down, s = <x, mu_b> / |mu_b|^2, the parabola beyond its vertex, the margin for what computed logits may be off
+    by), against the logit differences in double: the bound really is one, a certified row is one-hot with room to
+    spare for the fp32 sums of the exact path, rows late in the chain do get certified, and a wrong candidate never is."""
+    rng = np.random.default_rng(3)
+    d, C = 256, 384
+    means = (2.0 * rng.standard_normal((C, d))).astype(F)
+    means[7] = means[3] + F(0.05) * rng.standard_normal(d).astype(F)     # two components close together
+    logw2 = (LOG2E * np.log(rng.dirichlet(np.ones(C))).astype(F)).astype(F)
+    m64 = means.astype(np.float64)
+    musq = (means ** 2).sum(1, dtype=F)
+    dist = np.sqrt(((m64[None, :, :] - m64[:, None, :]) ** 2).sum(2))
+    np.fill_diagonal(dist, np.inf)
+    a_min = (np.nextafter(dist.min(1).astype(F), F(0)) * F(1 - 1e-6)).astype(F)    # rounded down
+    mumax = F(np.sqrt(musq.max()) * F(1.001))
+    qmax, qmin = musq.max(), musq.min()
+    bmax, babs = logw2.max(), np.abs(logw2).max()
+    certified = wrong_certified = 0
+    for trial in range(400):
+        ab = float(rng.uniform(0.2, 0.9995))
+        V = ab * 0.25 + 1 - ab
+        c1, c2 = F(LOG2E * F(np.sqrt(ab) / V)), F(LOG2E * F(ab / (2 * V)))
+        b = 3 if trial % 50 == 0 else int(rng.integers(0, C))
+        x = (np.sqrt(ab) * (means[b] + 0.5 * rng.standard_normal(d)) + np.sqrt(1 - ab) * rng.standard_normal(d)).astype(F)
+        # the logits as exact arithmetic on what the kernels are given (musq and log2 w as fp32 numbers)
+        exact = float(c1) * (m64 @ x.astype(np.float64)) - float(c2) * musq.astype(np.float64) + logw2.astype(np.float64)
+        for cand in (b, (b + 1) % C):
+            s = F(np.dot(x, means[cand]) / musq[cand])
+            e = (x - s * means[cand]).astype(F)
+            e_up = F(np.sqrt(np.dot(e, e)) * F(1 + 2.0 ** -10))
+            x_up = F(np.sqrt(np.dot(x, x)) * F(1 + 2.0 ** -10))
+            A, B = F(c1 * s), F(c1 * e_up)
+            half, am, qb = F(0.5) * A, a_min[cand], musq[cand]
+            f = F(am * (B - half * am))
+            beyond = bool(am * A >= B)
+            dq = F(half - c2)
+            qterm = F(dq * ((qmax if dq >= 0 else qmin) - qb))
+            bterm = F(bmax - logw2[cand])
+            mag = (am * B + half * am * am) + abs(qterm) + (babs + abs(logw2[cand])) + c2 * qmax
+            margin = F(c1 * x_up * mumax * F(2.0 ** -9 + 1e-5) + ((c2 + abs(dq)) * qmax * F(2.0 ** -12) + (F(1e-5) * mag + F(1))))
+            bound = F(f + qterm + bterm)
+            others = np.arange(C) != cand
+            gap = exact - exact[cand]
+            if s >= 0 and beyond:
+                # Cauchy-Schwarz and the parabola, whatever the candidate: every exact difference lies below the
+                # bound (musq against |mu|^2 and this fp32 evaluation against double: inside the margin less the
+                # part that is for the exact path's sums)
+                assert np.all(gap[others] <= float(bound) + float((c2 + abs(dq)) * qmax * F(2.0 ** -12)) + 1e-5 * float(mag))
+            ok = bool(s >= 0 and beyond and bound + (ZERO_GAP + margin) < 0)
+            if ok:
+                # one-hot, with room for two fp32 split-operand sums (2^-10 |x| |mu| each) on top of the zero gap
+                room = float(c1) * 2.0 ** -9 * float(x_up) * float(mumax)
+                assert np.all(gap[others] < -float(ZERO_GAP) - room)
+                wts = np.exp2((exact[others] - exact[cand]).astype(F), dtype=F)
+                assert np.all(wts == 0)
+            certified += ok and cand == b
+            wrong_certified += ok and cand != b
+            assert not (ok and cand in (3, 7))          # their nearest neighbour is too close at any noise level here
+    assert certified > 60 and wrong_certified == 0
