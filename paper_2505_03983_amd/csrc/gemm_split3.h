@@ -65,9 +65,11 @@ namespace asd {
 // BK: K slab, 16 (one MFMA group) or 32 (two).  The large tile with BK = 16 lets two workgroups share a CU; small
 // tiles for few rows take BK = 32, so that a slab carries enough MFMAs to cover the load -> LDS -> fragment
 // chain of the next one even with few wavefronts per SIMD.
-template <int BM_, int BN_, int WGM_ = 2, int WGN_ = 2, int BK_ = 16>
+// PLANES: 3 = three bf16 terms per operand and six products, 2 = two fp16 terms and three products (see above).
+template <int BM_, int BN_, int WGM_ = 2, int WGN_ = 2, int BK_ = 16, int PLANES_ = 3>
 struct Split3Cfg {
-  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, BK = BK_, STAGES = 2;
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, BK = BK_, STAGES = 2, PLANES = PLANES_;
+  static constexpr int NPROD = PLANES == 3 ? 6 : 3;   // MFMAs per block of the tile and MFMA group
   static constexpr int NG = BK / 16;             // MFMA groups (k = 16) per slab
   static constexpr int RB = 2 * BK;              // bytes of a row of a plane in LDS
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
@@ -76,10 +78,11 @@ struct Split3Cfg {
   static constexpr int RPP = THREADS / KQ;       // rows covered by one loader pass
   static constexpr int RA = BM / RPP;            // loader passes over the A tile
   static constexpr int A_PLANE = BM * RB, B_PLANE = BN * RB;      // bytes of one plane of a slab
-  static constexpr int A_STAGE = 3 * A_PLANE, B_STAGE = 3 * B_PLANE;
+  static constexpr int A_STAGE = PLANES * A_PLANE, B_STAGE = PLANES * B_PLANE;
   static constexpr int B_LOADS = B_STAGE / (16 * THREADS);        // 16-byte pieces of a slab's B image per thread
   static constexpr size_t LDS_BYTES = (size_t)STAGES * (A_STAGE + B_STAGE) + sizeof(float) * 8 * BM;
   static_assert(BK == 16 || BK == 32, "K slab");
+  static_assert(PLANES == 2 || PLANES == 3, "terms per operand");
   static_assert(WM % 32 == 0 && WN % 32 == 0 && RA >= 1 && BM % RPP == 0 && B_STAGE % (16 * THREADS) == 0, "tile shape");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   // 16-byte slot of chunk c of row r inside the row: 16 consecutive rows reading one chunk cover all 64 banks once
@@ -93,6 +96,7 @@ inline size_t split3_image_bytes(int N, int K) {
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));   // A / B operand of v_mfma_f32_32x32x16_f16
 
 // x[0..7] -> three planes of 8 bf16 each (element 0 in the low half of word 0)
 __device__ __forceinline__ void split3_pack(const float (&x)[8], u32x4& p1, u32x4& p2, u32x4& p3) {
@@ -114,10 +118,33 @@ __device__ __forceinline__ void split3_pack(const float (&x)[8], u32x4& p1, u32x
   p3 = u32x4{w3[0], w3[1], w3[2], w3[3]};
 }
 
-// B [N, K] fp32 (row stride ldb) -> image.  One thread per (row of the padded tile grid, chunk of 8 k).
+// x[0..7] -> two planes of 8 fp16 each: x1 = the nearest fp16, x2 = the nearest fp16 of x - x1 (that difference is
+// exact in fp32).  The caller has scaled x into fp16's range (see the header).
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split2_pack(const float (&x)[8], u32x4& p1, u32x4& p2) {
+  uint32_t w1[4], w2[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float xa = x[2 * j], xb = x[2 * j + 1];
+    const f16x2 h = {(_Float16)xa, (_Float16)xb};
+    const f16x2 l = {(_Float16)(xa - (float)h.x), (_Float16)(xb - (float)h.y)};
+    w1[j] = __builtin_bit_cast(uint32_t, h);
+    w2[j] = __builtin_bit_cast(uint32_t, l);
+  }
+  p1 = u32x4{w1[0], w1[1], w1[2], w1[3]};
+  p2 = u32x4{w2[0], w2[1], w2[2], w2[3]};
+}
+template <int PLANES>
+__device__ __forceinline__ void split_pack(const float (&x)[8], u32x4 (&p)[3]) {
+  if constexpr (PLANES == 3) split3_pack(x, p[0], p[1], p[2]);
+  else split2_pack(x, p[0], p[1]);
+}
+
+// B [N, K] fp32 (row stride ldb), times `scale` (a power of two; 1 for three bf16 terms) -> image.  One thread per
+// (row of the padded tile grid, chunk of 8 k).
 template <class Cfg>
 __global__ __launch_bounds__(256) void split3_pack_b_kernel(const float* __restrict__ B, int64_t ldb, int N, int K,
-                                                            uint8_t* __restrict__ img) {
+                                                            uint8_t* __restrict__ img, float scale) {
   const int kc = K / 8;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t n_pad = (int64_t)((N + Cfg::BN - 1) / Cfg::BN) * Cfg::BN;
@@ -125,21 +152,22 @@ __global__ __launch_bounds__(256) void split3_pack_b_kernel(const float* __restr
   const int n = (int)(idx / kc), c8 = (int)(idx % kc);
   float x[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x[e] = n < N ? B[(int64_t)n * ldb + c8 * 8 + e] : 0.f;
+  for (int e = 0; e < 8; ++e) x[e] = n < N ? scale * B[(int64_t)n * ldb + c8 * 8 + e] : 0.f;
   u32x4 p[3];
-  split3_pack(x, p[0], p[1], p[2]);
+  split_pack<Cfg::PLANES>(x, p);
   const int tn = n / Cfg::BN, r = n % Cfg::BN, ks = c8 / Cfg::KQ, c = c8 % Cfg::KQ;
   uint8_t* dst = img + ((int64_t)tn * (K / Cfg::BK) + ks) * Cfg::B_STAGE + r * Cfg::RB + Cfg::slot(r, c) * 16;
 #pragma unroll
-  for (int pl = 0; pl < 3; ++pl) *reinterpret_cast<u32x4*>(dst + pl * Cfg::B_PLANE) = p[pl];
+  for (int pl = 0; pl < Cfg::PLANES; ++pl) *reinterpret_cast<u32x4*>(dst + pl * Cfg::B_PLANE) = p[pl];
 }
 
 template <class Cfg>
-inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K, uint8_t* img, hipStream_t st) {
+inline hipError_t launch_split3_pack_b(const float* B, int64_t ldb, int N, int K, uint8_t* img, hipStream_t st,
+                                       float scale = 1.f) {
   const int64_t n_pad = (int64_t)((N + Cfg::BN - 1) / Cfg::BN) * Cfg::BN;
   const int64_t threads = n_pad * (K / 8);
   hipLaunchKernelGGL(split3_pack_b_kernel<Cfg>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, B, ldb, N, K,
-                     img);
+                     img, scale);
   return hipGetLastError();
 }
 
@@ -160,10 +188,10 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
                                             int sparse, int tile_m, int tile_n) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, MI = Cfg::MI, NJ = Cfg::NJ, BK = Cfg::BK, NG = Cfg::NG, RB = Cfg::RB;
   constexpr int RA = Cfg::RA, RPP = Cfg::RPP, A_PLANE = Cfg::A_PLANE, B_PLANE = Cfg::B_PLANE;
-  constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS;
+  constexpr int A_STAGE = Cfg::A_STAGE, B_STAGE = Cfg::B_STAGE, B_LOADS = Cfg::B_LOADS, PLANES = Cfg::PLANES;
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
-  uint8_t* lds_a = lds_all;                                   // [2 stages][3 planes][BM rows][RB bytes]
-  uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][3 planes][BN rows][RB bytes]
+  uint8_t* lds_a = lds_all;                                   // [2 stages][PLANES][BM rows][RB bytes]
+  uint8_t* lds_b = lds_all + 2 * A_STAGE;                     // [2 stages][PLANES][BN rows][RB bytes]
   float* s_row = reinterpret_cast<float*>(lds_all + 2 * (A_STAGE + B_STAGE));   // [8 * BM], the Op's
   uint16_t* s_list = reinterpret_cast<uint16_t*>(s_row + 8 * BM);                // sparse K: [K / BK] live slabs, in order
 
@@ -255,11 +283,10 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
     for (int p = 0; p < RA; ++p) {
       const float4 v0 = op.load_a(ra[slot][p][0], p), v1 = op.load_a(ra[slot][p][1], p);
       const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      u32x4 p1, p2, p3;
-      split3_pack(x, p1, p2, p3);
-      *reinterpret_cast<u32x4*>(sa + a_dst[p]) = p1;
-      *reinterpret_cast<u32x4*>(sa + A_PLANE + a_dst[p]) = p2;
-      *reinterpret_cast<u32x4*>(sa + 2 * A_PLANE + a_dst[p]) = p3;
+      u32x4 pp[3];
+      split_pack<PLANES>(x, pp);
+#pragma unroll
+      for (int pl = 0; pl < PLANES; ++pl) *reinterpret_cast<u32x4*>(sa + pl * A_PLANE + a_dst[p]) = pp[pl];
     }
   };
 
@@ -277,10 +304,10 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
   for (int g = 0; g < NG; ++g) f_off[g] = fr.l32 * RB + Cfg::slot(fr.l32, 2 * g + fr.half) * 16;
   const uint8_t* fa = lds_a + fr.wm * Cfg::WM * RB;
   const uint8_t* fb = lds_b + fr.wn * Cfg::WN * RB;
-  v8bf af[2][3][MI], bf[2][3][NJ];
+  v8bf af[2][PLANES][MI], bf[2][PLANES][NJ];   // (fp16 terms travel in the same 16-byte type)
   auto read_frags = [&](auto stage, auto g, auto buf) {   // group g of LDS stage `stage` -> fragment buffer `buf`
 #pragma unroll
-    for (int pl = 0; pl < 3; ++pl) {
+    for (int pl = 0; pl < PLANES; ++pl) {
 #pragma unroll
       for (int i = 0; i < MI; ++i)
         af[buf][pl][i] = *reinterpret_cast<const v8bf*>(fa + stage * A_STAGE + pl * A_PLANE + i * 32 * RB + f_off[g]);
@@ -289,15 +316,20 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
         bf[buf][pl][j] = *reinterpret_cast<const v8bf*>(fb + stage * B_STAGE + pl * B_PLANE + j * 32 * RB + f_off[g]);
     }
   };
-  constexpr int G = MI * NJ, NM = 6 * G;     // MFMAs per plane pair and per group
+  constexpr int G = MI * NJ, NM = Cfg::NPROD * G;     // MFMAs per plane pair and per group
   auto mma = [&](auto buf, int first, int count) {   // MFMAs first .. first+count-1 of a group
+    // pairs of terms, largest products first; with two terms the first three are all
     constexpr int pa[6] = {0, 0, 1, 1, 0, 2};
     constexpr int pb[6] = {0, 1, 0, 1, 2, 0};
 #pragma unroll
     for (int q = 0; q < NM; ++q)
       if (q >= first && q < first + count) {
         const int pr = q / G, i = (q % G) / NJ, j = q % NJ;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][pa[pr]][i], bf[buf][pb[pr]][j], acc[i][j], 0, 0, 0);
+        if constexpr (PLANES == 3)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][pa[pr]][i], bf[buf][pb[pr]][j], acc[i][j], 0, 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, af[buf][pa[pr]][i]),
+                                                             __builtin_bit_cast(v8h, bf[buf][pb[pr]][j]), acc[i][j], 0, 0, 0);
       }
   };
   // this wavefront's LDS stores have completed; then meet the others (no fence: global loads stay in flight)
@@ -339,7 +371,7 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
       read_frags(npar, I0(), NextBuf());
     }
     mma(LastBuf(), NM / 2, NM - NM / 2);
-    if (steady && NG == 1) sched_pairs<0x100, NM - NM / 2, (3 * (MI + NJ) + NM - NM / 2 - 1) / (NM - NM / 2)>();
+    if (steady && NG == 1) sched_pairs<0x100, NM - NM / 2, (PLANES * (MI + NJ) + NM - NM / 2 - 1) / (NM - NM / 2)>();
     __builtin_amdgcn_s_setprio(0);
   };
   typedef std::integral_constant<bool, true> Steady;

@@ -50,6 +50,14 @@ typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one
 typedef Split3Cfg<128, 128, 2, 2> GmmTileSplit;
 // draft call on the same pipe: half-height tiles, four wavefronts of 32 x 64, K slabs of 32
 typedef Split3Cfg<64, 128, 2, 2, 32> GmmTileSplitSkinny;
+// d and C multiples of 32: both GEMMs of both calls with two fp16 terms per operand and three products, K slabs of 32;
+// one image of an operand serves the full and the half-height tiling.  (Otherwise: the verify call on the two bf16
+// tilings above, the draft call on the fp32 pipe.)
+typedef Split3Cfg<128, 128, 2, 2, 32, 2> GmmTile2;
+typedef Split3Cfg<64, 128, 2, 2, 32, 2> GmmTile2Skinny;
+static_assert(GmmTile2::BN == GmmTileSplit::BN && GmmTile2::WGN == GmmTileSplit::WGN && GmmTile2::BM == GmmTileSplit::BM &&
+              GmmTile2::B_STAGE == GmmTile2Skinny::B_STAGE && GmmTile2::BK == GmmTile2Skinny::BK,
+              "the tilings lay rows, row maxima and images out alike");
 
 // (kappa, gamma, cx, cm) of a row
 __device__ __forceinline__ float4 row_coef(const float4* coef_tau, const int32_t* tau, int n) {
@@ -76,6 +84,61 @@ __global__ void gmm_prep_kernel(int C, int d, const float* __restrict__ means, f
     __syncthreads();
   }
   if (threadIdx.x == 0) musq[k] = red[0];
+}
+
+// Largest |v[i]| as the bits of a float (non-negative floats order like their bit patterns); *out = 0 on entry.
+__global__ __launch_bounds__(256) void gmm_absmax_kernel(const float* __restrict__ v, int64_t n, uint32_t* __restrict__ out) {
+  float mx = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) mx = fmaxf(mx, fabsf(v[i]));
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(mx));
+}
+
+// The power of two that brings a largest magnitude mx into [2^14, 2^15): fp16's largest finite number is 65504, and
+// the larger the scaled values, the less of their second terms falls below fp16's normal range.  1 for 0, inf, NaN.
+__host__ __device__ __forceinline__ float fp16_scale(float mx) {
+  if (!(mx > 0.f) || !(mx < 3.0e38f)) return 1.f;
+  int e;
+  (void)frexpf(mx, &e);   // mx = f 2^e, f in [0.5, 1)
+  return ldexpf(1.f, max(-100, min(100, 15 - e)));
+}
+
+// The means as the two fp16 terms of the split carry them: out = (m1 + m2) / scale with m1 = the nearest fp16 of
+// scale * v, m2 = the nearest fp16 of scale * v - m1 (both differences and the sum are exact in fp32).  A row of
+// softmax weights (1, 0, 0, ...) gets exactly this from the second GEMM on fp16 terms.
+__global__ __launch_bounds__(256) void gmm_means22_kernel(const float* __restrict__ v, int64_t n, float scale,
+                                                          float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float x = scale * v[i];
+  const float m1 = (float)(_Float16)x;
+  const float m2 = (float)(_Float16)(x - m1);
+  out[i] = (m1 + m2) / scale;
+}
+
+// a_scale[m] = fp16_scale(largest |x| of row m), for the rows a split-operand GEMM with fp16 terms will read: one
+// wavefront per row.  skip_tile (or NULL): row tiles of 128 rows nobody reads.
+__global__ __launch_bounds__(256) void gmm_row_scale_kernel(const int* __restrict__ n_dev, int n_max, int d,
+                                                            const float* __restrict__ in_base,
+                                                            const int64_t* __restrict__ in_off,
+                                                            float* __restrict__ a_scale,
+                                                            const uint8_t* __restrict__ skip_tile) {
+  const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= min(*n_dev, n_max)) return;
+  if (skip_tile && skip_tile[m / 128]) return;
+  const float* x = in_base + in_off[m];
+  float mx = 0.f;
+  if ((d & 3) == 0) {
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    for (int j = lane; j < d / 4; j += 64) {
+      const float4 v = x4[j];
+      mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    }
+  } else {
+    for (int j = lane; j < d; j += 64) mx = fmaxf(mx, fabsf(x[j]));
+  }
+  mx = wave_max(mx);
+  if (lane == 0) a_scale[m] = fp16_scale(mx);
 }
 
 // ---------------------------------------------------------------------------
@@ -268,22 +331,34 @@ struct LogitOp {
   // NULL, or [row tiles of kSkipTile rows]: 1 = nobody will read this tile's logits (the one-hot certificate below
   // has written its rows)
   const uint8_t* skip_tile = nullptr;
+  // Operand scales of the fp16-term kernels (powers of two; 1 elsewhere): row m of A is multiplied by a_scale[m]
+  // (NULL: 1) on its way into the split, B's image holds b_scale B, and the epilogue takes both out again (exactly)
+  const float* a_scale = nullptr;
+  float b_scale = 1.f;
+  static constexpr int kMaxPasses = 8;
+  float asc[kMaxPasses];
   static constexpr int kSkipTile = 128;
   __device__ __forceinline__ bool skip_row_tile(int m0) const { return skip_tile && skip_tile[m0 / kSkipTile] != 0; }
   static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
   // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
   __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq, float* s_row) {
-    if (lkq != 0) return;
+    static_assert(Cfg::RA <= kMaxPasses, "loader passes");
 #pragma unroll
     for (int p = 0; p < Cfg::RA; ++p) {
       const int r = lrow + Cfg::RPP * p;
-      const float4 cf = coef_tau[tau[min(m0 + r, M - 1)]];
-      s_row[8 * r + 1] = kLog2e * cf.x;
+      const int m = min(m0 + r, M - 1);
+      asc[p] = a_scale ? a_scale[m] : 1.f;
+      if (lkq != 0) continue;
+      const float4 cf = coef_tau[tau[m]];
+      s_row[8 * r + 1] = (kLog2e * cf.x) / (asc[p] * b_scale);   // (a division by a power of two: exact)
       s_row[8 * r + 2] = kLog2e * cf.y;
     }
   }
-  __device__ __forceinline__ float4 load_a(float4 v, int) const { return v; }
+  __device__ __forceinline__ float4 load_a(float4 v, int p) const {
+    const float s = asc[p];
+    return make_float4(s * v.x, s * v.y, s * v.z, s * v.w);
+  }
   template <class Cfg>
   __device__ __forceinline__ void finish(int, int, float*) {}
   template <class Cfg>
@@ -389,7 +464,11 @@ struct CombineOp {
   static constexpr int kMaxPasses = 8;
   float rmax[kMaxPasses];
   float rsum[kMaxPasses];
-  // s_row[8 r ..]: row sum, c_x', c_m', -, in_off (8 bytes), out_off (8 bytes) of tile row r
+  // Operand scales of the fp16-term kernels (powers of two; 1 elsewhere): the weights -- at most 1 -- go into the
+  // split times a_scale, B's image holds b_scale B, and the epilogue takes both out again (exactly).  The row sums
+  // are those of the unscaled weights.
+  float a_scale = 1.f, b_scale = 1.f;
+  // s_row[8 r ..]: row sum, c_x', c_m' / (a_scale b_scale), -, in_off (8 bytes), out_off (8 bytes) of tile row r
   template <class Cfg>
   __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq, float* s_row) {
     static_assert(Cfg::RA <= kMaxPasses, "loader passes");
@@ -410,7 +489,7 @@ struct CombineOp {
       if (lkq == 0) {
         const float4 cf = coef_tau[tau[m]];
         s_row[8 * r + 1] = cf.z;
-        s_row[8 * r + 2] = cf.w;
+        s_row[8 * r + 2] = cf.w / (a_scale * b_scale);   // (a division by a power of two: exact)
         *reinterpret_cast<int64_t*>(&s_row[8 * r + 4]) = in_off[m];
         *reinterpret_cast<int64_t*>(&s_row[8 * r + 6]) = out_off[m];
       }
@@ -422,7 +501,7 @@ struct CombineOp {
     float4 e = make_float4(__builtin_amdgcn_exp2f(v.x - mx), __builtin_amdgcn_exp2f(v.y - mx),
                            __builtin_amdgcn_exp2f(v.z - mx), __builtin_amdgcn_exp2f(v.w - mx));
     rsum[p] += (e.x + e.y) + (e.z + e.w);
-    return e;
+    return make_float4(a_scale * e.x, a_scale * e.y, a_scale * e.z, a_scale * e.w);
   }
   template <class Cfg>
   __device__ __forceinline__ void finish(int lrow, int lkq, float* s_row) {
@@ -714,8 +793,9 @@ __global__ __launch_bounds__(256) void gmm_cert_amin_kernel(int C, int d, const 
 }
 
 // One wavefront per row, four rows per workgroup; V float4 per lane hold the row (d <= 256 V) and as many mu_b.
-// chain_comp[chain[row]]: the candidate component of the row (< 0: none).  glob = (largest |mu_n|, largest and
-// smallest musq, -), globw = (largest log2 w_n, largest |log2 w_n|, -, -).  Rows of a tile count themselves through
+// chain_comp[chain[row]]: the candidate component of the row (< 0: none).  means: as the second GEMM carries them
+// (gmm_means22_kernel; the caller's own where that GEMM takes them whole): what a one-hot row's result is made of.
+// glob = (largest |mu_n|, largest and smallest musq, -), globw = (largest log2 w_n, largest |log2 w_n|, -, -).  Rows of a tile count themselves through
 // tile_cnt[tile] (finished in the low half, passed in the high half); the workgroup that brings the tile to its
 // full count writes cert_tile (always) and onehot_tile = 1 (if certified) and clears the counter for the next call.
 // counts (or NULL): [5] += one-hot row tiles, [6] += certified row tiles (verify call only: count_tiles).
@@ -778,8 +858,10 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
         r2 += (ex * ex + ey * ey) + (ez * ez + ew * ew);
       }
       r2 = wave_sum(r2);
-      // upper bounds of the two norms (their fp32 sums are off by a few 2^-24 d of themselves at most)
-      const float e_up = sqrtf(r2) * (1.f + 0x1p-10f), x_up = sqrtf(xx) * (1.f + 0x1p-10f);
+      // upper bounds of the two norms (their fp32 sums are off by a few 2^-24 d of themselves at most); `means` holds
+      // the means as the second GEMM carries them, within 2^-21 max |mu| of the true ones in norm, and |e| is about
+      // the true mu_b
+      const float e_up = fmaf(fabsf(s) * glob.x, 0x1p-21f, sqrtf(r2) * (1.f + 0x1p-10f)), x_up = sqrtf(xx) * (1.f + 0x1p-10f);
       const float c1 = LogitOp::kLog2e * cf.x, c2 = LogitOp::kLog2e * cf.y;
       const float A = c1 * s, B = c1 * e_up, half = 0.5f * A;
       const float f = am * (B - half * am);                 // the parabola at the nearest neighbour ...
@@ -1147,7 +1229,8 @@ __global__ __launch_bounds__(256) void combine_finish_kernel(const int* __restri
                                                              const int64_t* __restrict__ out_off,
                                                              const float4* __restrict__ coef_tau,
                                                              const int32_t* __restrict__ tau,
-                                                             const uint8_t* __restrict__ onehot_tile) {
+                                                             const uint8_t* __restrict__ onehot_tile, float acc_scale) {
+  // acc_scale: what the partial tiles are scaled by (the operand scales of the fp16-term kernels; 1 otherwise)
   const int M = min(*M_dev, M_max);
   const int m = blockIdx.x;
   if (m >= M) return;
@@ -1156,7 +1239,7 @@ __global__ __launch_bounds__(256) void combine_finish_kernel(const int* __restri
   float sum = 0.f;
   for (int z = 0; z < splits; ++z) sum += psum[(size_t)z * M_max + m];
   const float4 cf = coef_tau[tau[m]];
-  const float scale = cf.w / sum;
+  const float scale = (cf.w / acc_scale) / sum;
   const float* x = in_base + in_off[m];
   float* o = out_base + out_off[m];
   for (int n = threadIdx.x; n < N; n += 256) {
@@ -1231,16 +1314,35 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     }
   }
   if (g->use_mfma && d % 16 == 0 && C % 16 == 0) {
-    ASD_HIP(hipMalloc(&g->means_img, split3_image_bytes<GmmTileSplit>(C, d)));
-    ASD_HIP(hipMalloc(&g->means_t_img, split3_image_bytes<GmmTileSplit>(d, C)));
-    ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means, d, C, d, g->means_img, 0));
-    ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means_t, C, d, C, g->means_t_img, 0));
-    if (d % 32 == 0 && C % 32 == 0) {   // the draft call's tiling has its own images (K slabs of 32)
-      ASD_HIP(hipMalloc(&g->means_img_s, split3_image_bytes<GmmTileSplitSkinny>(C, d)));
-      ASD_HIP(hipMalloc(&g->means_t_img_s, split3_image_bytes<GmmTileSplitSkinny>(d, C)));
-      ASD_HIP(launch_split3_pack_b<GmmTileSplitSkinny>(g->means, d, C, d, g->means_img_s, 0));
-      ASD_HIP(launch_split3_pack_b<GmmTileSplitSkinny>(g->means_t, C, d, C, g->means_t_img_s, 0));
-      g->split_draft_ok = true;
+    if (d % GmmTile2::BK == 0 && C % GmmTile2::BK == 0) {
+      // fp16 terms for both calls: the means times b_scale (a power of two that brings the largest |mu| into fp16's
+      // upper range), one image per GEMM for both tilings, and the means as their two fp16 terms carry them
+      uint32_t* mx_dev = nullptr;
+      uint32_t mx_bits = 0;
+      ASD_HIP(hipMalloc(&mx_dev, sizeof(uint32_t)));
+      ASD_HIP(hipMemset(mx_dev, 0, sizeof(uint32_t)));
+      hipLaunchKernelGGL(gmm_absmax_kernel, dim3(256), dim3(256), 0, 0, g->means, (int64_t)C * d, mx_dev);
+      hipError_t e1 = hipGetLastError();
+      hipError_t e2 = hipMemcpy(&mx_bits, mx_dev, sizeof(uint32_t), hipMemcpyDeviceToHost);
+      (void)hipFree(mx_dev);
+      ASD_HIP(e1);
+      ASD_HIP(e2);
+      g->b_scale = fp16_scale(__builtin_bit_cast(float, mx_bits));
+      ASD_HIP(hipMalloc(&g->means_img2, split3_image_bytes<GmmTile2>(C, d)));
+      ASD_HIP(hipMalloc(&g->means_t_img2, split3_image_bytes<GmmTile2>(d, C)));
+      ASD_HIP(launch_split3_pack_b<GmmTile2>(g->means, d, C, d, g->means_img2, 0, g->b_scale));
+      ASD_HIP(launch_split3_pack_b<GmmTile2>(g->means_t, C, d, C, g->means_t_img2, 0, g->b_scale));
+      ASD_HIP(hipMalloc(&g->a_scale, sizeof(float) * (size_t)ctx->n_rows_max));
+      ASD_HIP(hipMalloc(&g->means22, sizeof(float) * (size_t)C * d));
+      hipLaunchKernelGGL(gmm_means22_kernel, dim3((unsigned)ceil_div((int64_t)C * d, 256)), dim3(256), 0, 0, g->means,
+                         (int64_t)C * d, g->b_scale, g->means22);
+      ASD_HIP(hipGetLastError());
+      g->two_ok = g->split_draft_ok = true;
+    } else {   // the verify call only, on three bf16 terms
+      ASD_HIP(hipMalloc(&g->means_img, split3_image_bytes<GmmTileSplit>(C, d)));
+      ASD_HIP(hipMalloc(&g->means_t_img, split3_image_bytes<GmmTileSplit>(d, C)));
+      ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means, d, C, d, g->means_img, 0));
+      ASD_HIP(launch_split3_pack_b<GmmTileSplit>(g->means_t, C, d, C, g->means_t_img, 0));
     }
     ASD_HIP(hipDeviceSynchronize());
     g->split_ok = g->use_split = true;
@@ -1252,8 +1354,8 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
     ASD_HIP(hipMalloc(&g->work_counts, 8 * sizeof(unsigned long long)));
     ASD_HIP(hipMemset(g->work_counts, 0, 8 * sizeof(unsigned long long)));
     // screening pass of the verify call: full tiles only, and the second GEMM must be able to skip what it leaves out
-    if (d % 128 == 0 && C % ScreenTile::BM == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 &&
-        split3_sparse_fits<GmmTileSplit>(C, np_v, GmmTileSplit::WN)) {
+    if (d % 128 == 0 && C % ScreenTile::BM == 0 && C % GmmTileSplit::BN == 0 && d <= 2048 && g->two_ok &&
+        split3_sparse_fits<GmmTile2>(C, np_v, GmmTile2::WN)) {
       g->nps = C / kGroup;
       const int64_t row_tiles = ceil_div(ctx->n_rows_max, GmmTileSplit::BM);
       ASD_HIP(hipMalloc(&g->means_q, (size_t)C * d));
@@ -1359,6 +1461,10 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->means_t_img);
   (void)hipFree(g->means_img_s);
   (void)hipFree(g->means_t_img_s);
+  (void)hipFree(g->means_img2);
+  (void)hipFree(g->means_t_img2);
+  (void)hipFree(g->means22);
+  (void)hipFree(g->a_scale);
   (void)hipFree(g->musq);
   (void)hipFree(g->coef_tau);
   (void)hipFree(g->part);
@@ -1431,7 +1537,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     auto kern = d <= 1024 ? gmm_certify_kernel<4> : gmm_certify_kernel<8>;
     hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d, C, rows.in_base,
                        rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, rows.chain, g->chain_comp,
-                       g->means, g->musq, g->log_w, g->cert_amin, g->cert_glob, g->cert_globw, g->onehot, g->onehot_tile,
+                       g->means22, g->musq, g->log_w, g->cert_amin, g->cert_glob, g->cert_globw, g->onehot, g->onehot_tile,
                        g->cert_tile, g->cert_cnt, (ctx->prof.on && rows.call == 1) ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.skip_tile = cert_tile;
@@ -1459,16 +1565,25 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     op1.tile_count = g->tile_count;
     op1.list_cap = g->list_cap;
   }
+  const bool two = split && g->two_ok;   // fp16 terms (both calls), else three bf16 terms (verify call only)
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    if (split && screen) {
+    if (two) {   // every row gets its scale first
+      hipLaunchKernelGGL(gmm_row_scale_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
+                         rows.in_base, rows.in_off, g->a_scale, cert_tile);
+      ASD_HIP(hipGetLastError());
+      op1.a_scale = g->a_scale;
+      op1.b_scale = g->b_scale;
+    }
+    if (screen) {
       // resident workgroups draw the tiles (and half tiles, on the draft call's tiling) the screening pass listed
-      ASD_HIP(launch_gemm_split3_nt_list<GmmTileSplit, GmmTileSplitSkinny, 1>(rows.n_dev, n, C, d, X, g->means_img,
-                                                                               g->means_img_s, op1, kResidentWgs, st));
+      ASD_HIP(launch_gemm_split3_nt_list<GmmTile2, GmmTile2Skinny, 1>(rows.n_dev, n, C, d, X, g->means_img2, g->means_img2,
+                                                                       op1, kResidentWgs, st));
+    } else if (two) {
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTile2, 1, false>(rows.n_dev, n, C, d, X, g->means_img2, op1, st)
+                        : launch_gemm_split3_nt<GmmTile2Skinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img2, op1, st));
     } else if (split) {
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st)
-                        : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img_s,
-                                                                               op1, st));
+      ASD_HIP(launch_gemm_split3_nt<GmmTileSplit, 1, false>(rows.n_dev, n, C, d, X, g->means_img, op1, st));
     } else {
       ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, C, d, X, g->means, d, op1, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, C, d, X, g->means, d, op1, st));
@@ -1506,8 +1621,8 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     ASD_HIP(hipGetLastError());
     if (onehot) {
       hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
-                         g->onehot_tile, g->means, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
-                         rows.tau, cert_tile);
+                         g->onehot_tile, two ? g->means22 : g->means, rows.in_base, rows.in_off, rows.out_base,
+                         rows.out_off, g->coef_tau, rows.tau, cert_tile);
       ASD_HIP(hipGetLastError());
       op2.onehot_tile = g->onehot_tile;
     }
@@ -1516,11 +1631,16 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   {
     ProfScope ps(ctx, ASD_PROF_GMM_COMBINE, rows.call, st);
-    if (split)
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1,
-                                                                       nullptr, g->sparse_combine)
-                        : launch_gemm_split3_nt<GmmTileSplitSkinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img_s,
-                                                                               op2, st, splits, g->part));
+    if (two) {
+      op2.a_scale = 32768.f;   // the weights are at most 1: 2^15 is the largest power of two fp16 can take them at
+      op2.b_scale = g->b_scale;
+      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTile2, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st, 1, nullptr,
+                                                                   g->sparse_combine)
+                        : launch_gemm_split3_nt<GmmTile2Skinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st,
+                                                                           splits, g->part));
+    } else if (split)
+      ASD_HIP(launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1, nullptr,
+                                                           g->sparse_combine));
     else
       ASD_HIP(rows.call ? launch_gemm_f32_nt<GmmTile, 1>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st)
                         : launch_gemm_f32_nt<GmmTileSkinny, 0>(rows.n_dev, n, d, C, P, g->means_t, C, op2, st, splits,
@@ -1528,7 +1648,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     if (splits > 1) {
       hipLaunchKernelGGL(combine_finish_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, ctx->B, d, splits,
                          g->part, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau, rows.tau,
-                         op2.onehot_tile);
+                         op2.onehot_tile, op2.a_scale * op2.b_scale);
       ASD_HIP(hipGetLastError());
     }
   }

@@ -29,6 +29,15 @@ struct GmmState {
   uint8_t* means_t_img = nullptr;  // B of the combine GEMM ([d, C])
   uint8_t* means_img_s = nullptr;  // the same two for the draft call's tiling (K slabs of 32)
   uint8_t* means_t_img_s = nullptr;
+  // Both GEMMs on two fp16 terms per operand (d and C multiples of 32; then the images above do not exist): the means
+  // times b_scale as one image per GEMM for both tilings, the scale of every row of a call's first GEMM, and the
+  // means as two fp16 terms carry them (what the closed form of a one-hot row must use)
+  uint8_t* means_img2 = nullptr;
+  uint8_t* means_t_img2 = nullptr;
+  float b_scale = 1.f;
+  float* a_scale = nullptr;        // [rows_max]
+  float* means22 = nullptr;        // [C, d]
+  bool two_ok = false;
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)
