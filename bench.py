@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
 
-PEAK = {"f32": 157.3, "bf16": 2500.0, "i8": 5000.0}          # dense MFMA TFLOP/s (int8: TOP/s), MI355X
+PEAK = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0, "i8": 5000.0}          # dense MFMA TFLOP/s (int8: TOP/s), MI355X
 HBM_PEAK_GBS = 8000.0
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg5_gmm_verify_gemm_hbm_traffic.txt")
@@ -111,6 +111,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
     ctx.use_adaptive_window(adaptive)
     ctx.use_split_gemm(split)
     split_active = ctx.split_gemm_active()
+    split_products = ctx.split_gemm_products()
     if screen is not None:
         ctx.use_logit_screen(screen)
     screen_mode = ctx.logit_screen_active()
@@ -145,7 +146,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
     wall = t1 - t0
     out = dict(cfg=cfg, wall_s=wall, steps_per_s=cfg["chains"] * cfg["K"] * steps / wall,
                ms_per_sample=1e3 * wall / steps, rounds_mean=rmean[-1], rounds_max=rmax[-1],
-               rounds_launched=launched, finite=finite, path=path, split=split_active,
+               rounds_launched=launched, finite=finite, path=path, split=split_active, split_products=split_products,
                act_terms=params.get("act_terms"), sclk_mhz=sampler.summary() if sampler else None,
                screen_mode=screen_mode)
     if profile:
@@ -172,13 +173,14 @@ def roofline(res, w=None, kernel=None):
     """Roofline entry of the dominant kernel of a profiled run.
 
     Mixture denoiser: one GEMM of the model call does 2*C*d flop per row (the method's arithmetic, fp32).  The
-    default kernels evaluate every fp32 product as six bf16 MFMA products, so they *execute* six times that on
-    the bf16 pipe.  `achieved` / `peak` / `frac` are the executed bf16 work against the bf16 MFMA peak (how
+    default kernels evaluate every fp32 product as three fp16 MFMA products (two fp16 terms per operand; six bf16
+    products of three terms where d or C is not a multiple of 32), so they *execute* three (six) times that on
+    the 16-bit pipe.  `achieved` / `peak` / `frac` are the executed 16-bit work against that pipe's MFMA peak (how
     busy the pipe in use is); `method` carries the 2*C*d figure and its ratio to the fp32 MFMA peak.
     Both split-operand GEMMs leave out work whose result is known to be exact zeros (tiles of logits far below
     their rows' maxima, found by the screening pass; slabs of components with zero weights): what they executed
-    is then counted by the device (half tiles of 64 rows x 128 components, slabs of 16 components per tile) and not
-    inferred from rows."""
+    is then counted by the device (half tiles of 64 rows x 128 components, slabs of 32 or 16 components per tile) and
+    not inferred from rows."""
     cfg, k = res["cfg"], res["kernels"]
     draft_rows, verify_rows = res["rows"]
     executed_per_method = 1.0
@@ -193,13 +195,14 @@ def roofline(res, w=None, kernel=None):
         # the row-wise kernel runs on the vector ALUs; its bound is the fp32 vector peak (same figure)
         bound = "mfma" if not name.startswith("GMM_ROWWISE") else "alu"
         if bound == "mfma" and res.get("split"):
-            dtype = "bf16"
-            executed_per_method = 6.0
+            executed_per_method = float(res.get("split_products") or 6)
+            dtype = "f16" if executed_per_method == 3.0 else "bf16"
+            slab = 32 if executed_per_method == 3.0 else 16                      # components per K slab of the second GEMM
             done, tiles, slabs_done, slabs = res.get("model_work", (0, 0, 0, 0, 0, 0, 0))[:4]
             if name == "GMM_LOGITS/verify" and tiles:
-                executed_flops = 6.0 * 2.0 * 64 * 128 * cfg["d"] * done / launches      # counted in half tiles of 64 rows
+                executed_flops = executed_per_method * 2.0 * 64 * 128 * cfg["d"] * done / launches   # half tiles of 64 rows
             if name == "GMM_COMBINE/verify" and slabs:
-                executed_flops = 6.0 * 2.0 * 128 * 128 * 16 * slabs_done / launches
+                executed_flops = executed_per_method * 2.0 * 128 * 128 * slab * slabs_done / launches
     else:
         name = "MLP_GEMM_BLK/verify"
         launches = k[name]["launches"]
@@ -225,7 +228,7 @@ def roofline(res, w=None, kernel=None):
         out["method"] = dict(flops_per_launch=method_flops, what="2*C*d per row (fp32 contraction of the model call)",
                              tflops=method_tflops, fp32_mfma_peak=PEAK["f32"],
                              ratio_to_fp32_mfma_peak=method_tflops / PEAK["f32"])
-        out["executed_bf16_products_per_fp32_product"] = int(executed_per_method)
+        out["executed_16bit_products_per_fp32_product"] = int(executed_per_method)
         if executed_flops != executed_per_method * method_flops:
             out["executed_share_of_dense"] = executed_flops / (executed_per_method * method_flops)
     else:
@@ -248,6 +251,10 @@ def logit_screen(res):
                 logit_half_tiles=tiles, logit_half_tiles_of_screened_calls=screened, logit_half_tiles_computed=done,
                 computed_share=done / tiles if tiles else None,
                 row_tiles_of_second_gemm_in_closed_form=onehot, row_tiles_certified_before_any_matrix_work=certified,
+                certificate=({"launches": k["GMM_CERT/verify"]["launches"], "total_ms": k["GMM_CERT/verify"]["total_ms"],
+                              "share_of_wall": 1e-3 * k["GMM_CERT/verify"]["total_ms"] / res["wall_s"],
+                              "note": "one kernel: reads a row, tests it, writes its result if it passes"}
+                             if "GMM_CERT/verify" in k else None),
                 int8_tops=ops / (1e-3 * s["total_ms"]) / 1e12 if screened else 0.0, int8_peak_tops=PEAK["i8"],
                 note="total_ms covers the quantiser, the int8 GEMM and the decision kernel; calls the draft call's "
                      "verdict switched the screen off for still launch all three (they exit at once)")
@@ -391,8 +398,8 @@ def main():
                          "graphs or the chain-resident kernel); the line then has no roofline object -- meant for "
                          "runs under rocprofv3, which times the kernels itself")
     ap.add_argument("--fp32-mfma", action="store_true",
-                    help="Gaussian-mixture verify GEMMs on the fp32 matrix pipe instead of the bf16 pipe with "
-                         "three-way split operands")
+                    help="Gaussian-mixture verify GEMMs on the fp32 matrix pipe instead of the 16-bit pipe with "
+                         "split operands")
     ap.add_argument("--no-screen", action="store_true",
                     help="Gaussian-mixture verify calls without the int8 screening pass (every tile of logits computed)")
     ap.add_argument("--window-control", action="store_true",
@@ -451,8 +458,11 @@ def main():
         "sclk_mhz_during_timed_region": res["sclk_mhz"],     # rocm-smi, polled from the host (nominal 2400)
     }
     if cfg["kind"] == "gmm":
-        line["verify_gemm_arithmetic"] = ("every fp32 product as six bf16 MFMA products of three-way split operands, "
-                                          "fp32 accumulation" if res["split"] else "fp32 MFMA")
+        line["verify_gemm_arithmetic"] = (
+            "fp32 MFMA" if not res["split"] else
+            "every fp32 product as three fp16 MFMA products of two-term split operands, fp32 accumulation"
+            if res["split_products"] == 3 else
+            "every fp32 product as six bf16 MFMA products of three-way split operands, fp32 accumulation")
     else:
         line["mlp_activation_terms"] = res["act_terms"]
     if not args.plain:
@@ -479,8 +489,8 @@ def main():
         # what the matrix pipes of this chip sustain on random operands with no memory traffic at all (the chip is
         # power-limited on dense MFMA work: the data-sheet peaks above hold for constant operands only)
         from paper_2505_03983_amd import probe
-        sus = {"bf16": probe.asd_probe_mfma_ceiling(True, True, 300),
-               "f32": probe.asd_probe_mfma_ceiling(False, True, 300)}
+        sus = {"bf16": probe.asd_probe_mfma_ceiling(1, True, 300), "f16": probe.asd_probe_mfma_ceiling(2, True, 300),
+               "f32": probe.asd_probe_mfma_ceiling(0, True, 300)}
         rf = line["roofline"]
         if rf["bound"] == "mfma":
             rf["sustained_random_operands"] = sus[rf["mfma_dtype"]]

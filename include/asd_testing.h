@@ -16,7 +16,9 @@ extern "C" {
 /* 1 if the next asd_sample on this context runs whole chains inside one workgroup (shape fits, switch on,
  * profiling off). */
 ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
-/* 1 if the verify call of this context runs the split-operand bf16 kernels. */
+/* Non-zero if the verify call of this context runs the split-operand kernels of the Gaussian-mixture denoiser: the
+ * number of 16-bit matrix-core products they spend on one fp32 product -- 3 (two fp16 terms per operand: d and C
+ * multiples of 32, both model calls) or 6 (three bf16 terms: multiples of 16, the verify call only). */
 ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 
 /* The second GEMM of the split-operand mixture denoiser (softmax weights times means) skips the stretches of
@@ -75,7 +77,7 @@ typedef enum {
   ASD_PROF_MODEL = 0,        /* a whole model call (all its kernels)          */
   ASD_PROF_PLAN = 1,         /* row planning                                  */
   ASD_PROF_GMM_ROWWISE = 2,  /* GMM denoiser, one wavefront per row           */
-  ASD_PROF_GMM_LOGITS = 3,   /* GMM logits GEMM  X M^T  (fp32 MFMA)           */
+  ASD_PROF_GMM_LOGITS = 3,   /* GMM logits GEMM  X M^T (+ the rows' fp16 scales) */
   ASD_PROF_GMM_SOFTMAX = 4,  /* GMM, between the two GEMMs: row maxima, one-hot rows */
   ASD_PROF_GMM_COMBINE = 5,  /* GMM  P M  GEMM + affine combination           */
   ASD_PROF_MLP_PACK = 6,     /* MLP input packing (bf16 x ; time embedding)   */
@@ -85,6 +87,7 @@ typedef enum {
   ASD_PROF_DRAFT = 10,       /* fused draft kernel                            */
   ASD_PROF_ACCEPT = 11,      /* fused accept / scan / resample kernel         */
   ASD_PROF_GMM_SCREEN = 12,  /* GMM screening pass of the verify call's logits */
+  ASD_PROF_GMM_CERT = 13,    /* GMM one-hot certificate (rows it passes are written by it) */
   ASD_PROF_KINDS = 16
 } asd_prof_kernel;
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
@@ -97,8 +100,9 @@ ASD_API asd_status asd_profile_accept_rows(asd_ctx* ctx, int64_t* examined_rows,
 /* Matrix work the mixture denoiser's verify calls left out since then (split-operand kernels only; all zero
  * otherwise).  logit_tiles_done / logit_tiles: half tiles (64 rows x 128 components) of logits the first GEMM computed
  * and how many there were, over the calls that went through the screening pass (asd_use_logit_screen; a call it was switched off for by
- * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs of 16
- * components the second GEMM's workgroups visited and how many there were (asd_use_sparse_combine).
+ * the draft call's verdict counts all its tiles as done).  combine_slabs_done / combine_slabs: K slabs (32 components
+ * with fp16 terms, 16 with bf16 terms: asd_split_gemm_active) the second GEMM's workgroups visited and how many there
+ * were (asd_use_sparse_combine).
  * (Workgroups of row tiles written in closed form count in neither.)
  * screened_tiles: the part of logit_tiles the screening GEMM looked at (calls it ran for, row tiles not certified).
  * onehot_row_tiles: tiles of 128 rows whose rows all have one softmax weight of 1.0 and zeros, which the second GEMM

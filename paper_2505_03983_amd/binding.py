@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 ASD_OK, ASD_EINVAL, ASD_ENOMEM, ASD_EDEVICE, ASD_ESTATE, ASD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ASD_DEN_GMM, ASD_DEN_MLP = 1, 2
 PROF = dict(MODEL=0, PLAN=1, GMM_ROWWISE=2, GMM_LOGITS=3, GMM_SOFTMAX=4, GMM_COMBINE=5, MLP_PACK=6, MLP_GEMM_IN=7,
-            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11, GMM_SCREEN=12)
+            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11, GMM_SCREEN=12, GMM_CERT=13)
 
 
 class AsdError(RuntimeError):
@@ -275,6 +275,10 @@ class Ctx:
 
     def split_gemm_active(self):
         return bool(lib().asd_split_gemm_active(self.h))
+
+    def split_gemm_products(self):
+        """16-bit matrix-core products per fp32 product of the split-operand kernels: 3 (fp16 terms), 6 (bf16), 0 (off)."""
+        return int(lib().asd_split_gemm_active(self.h))
 
     def set_seed(self, seed):
         _check(lib().asd_set_seed(self.h, int(seed)))

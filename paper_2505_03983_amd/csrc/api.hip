@@ -559,7 +559,10 @@ int32_t asd_logit_screen_active(const asd_ctx* ctx) {
   return (g && g->use_split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine) ? g->screen_mode : 0;
 }
 
-int32_t asd_split_gemm_active(const asd_ctx* ctx) { return (ctx && ctx->gmm && ctx->gmm->use_split) ? 1 : 0; }
+int32_t asd_split_gemm_active(const asd_ctx* ctx) {
+  if (!ctx || !ctx->gmm || !ctx->gmm->use_split) return 0;
+  return ctx->gmm->two_ok ? 3 : 6;
+}
 
 int32_t asd_resident_active(const asd_ctx* ctx) {
   return (ctx && ctx->resident_enabled && !ctx->prof.on && gmm_chain_supported(ctx)) ? 1 : 0;

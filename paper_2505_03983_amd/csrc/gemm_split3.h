@@ -251,7 +251,10 @@ __device__ __forceinline__ void split3_tile(int M, int M_max, int N, int K, cons
       }
       __syncthreads();
       nk = __builtin_amdgcn_readfirstlane(*s_cnt);   // the same for every lane: keep the K loop's control flow scalar
-      listed = nk < nk_all;   // everything live: walk the slabs in order, without the list
+      // everything live: walk the slabs in order, without the list.  Nothing live -- rows of NaN, whose comparisons
+      // all fail: the same, so that the loop's first loads never index with a list that was not written
+      if (nk == 0) nk = nk_all;
+      listed = nk < nk_all;
     }
   }
   if constexpr (Op::kSparseK) op.note_slabs(nk, nk_all / splits, tid);

@@ -828,6 +828,21 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
   if (m < n) {   // the same for the whole wavefront
     int b = chain_comp[chain[m]];
     if (b >= C) b = -1;
+    float4 cf = make_float4(0.f, 0.f, 0.f, 0.f);
+    float am = 0.f;
+    if (b >= 0) {
+      // A look before the row is read.  Under the mixture a row at this time index has s = 2 gamma / kappa and
+      // |e|^2 = d / (kappa / s) to within a few percent (the noise of d coordinates); if the test would fail even with
+      // four fifths of that |e| and nothing of its smaller terms, the row is not worth its 4 d bytes.  (Only a
+      // guess that saves work: a row it turns away takes the exact path.)
+      cf = coef_tau[tau[m]];
+      am = a_min[b];
+      if (cf.x > 0.f && cf.y > 0.f) {
+        const float s0 = 2.f * cf.y / cf.x, e0 = 0.8f * sqrtf((float)d * s0 / cf.x);
+        const float A0 = LogitOp::kLog2e * cf.x * s0, B0 = LogitOp::kLog2e * cf.x * e0;
+        if (!(am * A0 >= B0 && am * (B0 - 0.5f * A0 * am) + CombineOp::kZeroGap < 0.f)) b = -1;
+      }
+    }
     if (b >= 0) {
       const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
       const float4* mu = reinterpret_cast<const float4*>(means + (int64_t)b * d);
@@ -840,8 +855,7 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
         xv[i] = in ? x[j] : make_float4(0.f, 0.f, 0.f, 0.f);
         mv[i] = in ? mu[j] : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-      const float4 cf = coef_tau[tau[m]];
-      const float qb = musq[b], am = a_min[b], bias_b = LogitOp::kLog2e * log_w[b];
+      const float qb = musq[b], bias_b = LogitOp::kLog2e * log_w[b];
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         p += (xv[i].x * mv[i].x + xv[i].y * mv[i].y) + (xv[i].z * mv[i].z + xv[i].w * mv[i].w);
@@ -999,12 +1013,15 @@ __global__ __launch_bounds__(256) void gmm_screen_quant_means_kernel(int C, int 
   }
 }
 
-// rows of the plan -> int8 [n, d]; per row (scale, 1-norm); one wavefront per row (d <= 2048: a row in registers)
+// rows of the plan -> int8 [n, d]; per row (scale, 1-norm); one wavefront per row (d <= 2048: a row in registers).
+// The row's largest magnitude is at hand: a_scale[m] = its fp16 scale for the exact GEMM's split (gmm_row_scale_kernel),
+// also when the screening pass is switched off (*on == 0: nothing is packed).
 __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restrict__ n_dev, int n_max, int d,
                                                               const float* __restrict__ in_base,
                                                               const int64_t* __restrict__ in_off,
                                                               const int32_t* __restrict__ on,
                                                               int8_t* __restrict__ xq, float2* __restrict__ xs,
+                                                              float* __restrict__ a_scale,
                                                               int32_t* __restrict__ tile_count,
                                                               const uint8_t* __restrict__ cert_tile,
                                                               int32_t* __restrict__ live_tiles) {
@@ -1028,10 +1045,10 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
       if (lane == 0) live_tiles[0] = base;
     }
   }
-  if (*on == 0) return;
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (m >= n) return;
   if (cert_tile && cert_tile[m / kCertTile]) return;
+  const bool pack = *on != 0;
   const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
   constexpr int kMaxV = 2048 / 4 / 64;
   float4 v[kMaxV];
@@ -1044,6 +1061,8 @@ __global__ __launch_bounds__(256) void gmm_screen_pack_kernel(const int* __restr
     a += (fabsf(v[i].x) + fabsf(v[i].y)) + (fabsf(v[i].z) + fabsf(v[i].w));
   }
   mx = wave_max(mx);
+  if (lane == 0 && a_scale) a_scale[m] = fp16_scale(mx);
+  if (!pack) return;
   a = wave_sum(a);
   const float s = mx > 0.f ? mx / 127.f : 1.f, inv = 1.f / s;
   uint32_t* o = reinterpret_cast<uint32_t*>(xq + (int64_t)m * d);
@@ -1533,7 +1552,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                     rows.chain != nullptr && (rows.call == 1 || g->split_draft_ok);
   const uint8_t* cert_tile = cert ? g->cert_tile : nullptr;
   if (cert) {
-    ProfScope ps(ctx, ASD_PROF_GMM_SCREEN, rows.call, st);
+    ProfScope ps(ctx, ASD_PROF_GMM_CERT, rows.call, st);
     auto kern = d <= 1024 ? gmm_certify_kernel<4> : gmm_certify_kernel<8>;
     hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d, C, rows.in_base,
                        rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, rows.chain, g->chain_comp,
@@ -1547,7 +1566,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
     const int ntn = C / GmmTileSplit::BN;
     hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
-                       rows.in_base, rows.in_off, on, g->xq, g->xs, g->tile_count, cert_tile,
+                       rows.in_base, rows.in_off, on, g->xq, g->xs, g->a_scale, g->tile_count, cert_tile,
                        cert ? g->live_tiles : (int32_t*)nullptr);
     ASD_HIP(hipGetLastError());
     // int8 operands, handed over as 16-bit units (two k each): the means as the kernel's rows, the call's rows as its columns
@@ -1568,10 +1587,12 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const bool two = split && g->two_ok;   // fp16 terms (both calls), else three bf16 terms (verify call only)
   {
     ProfScope ps(ctx, ASD_PROF_GMM_LOGITS, rows.call, st);
-    if (two) {   // every row gets its scale first
-      hipLaunchKernelGGL(gmm_row_scale_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
-                         rows.in_base, rows.in_off, g->a_scale, cert_tile);
-      ASD_HIP(hipGetLastError());
+    if (two) {   // every row has its scale first: from the screening pass's quantiser, else from a kernel of its own
+      if (!screen) {
+        hipLaunchKernelGGL(gmm_row_scale_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
+                           rows.in_base, rows.in_off, g->a_scale, cert_tile);
+        ASD_HIP(hipGetLastError());
+      }
       op1.a_scale = g->a_scale;
       op1.b_scale = g->b_scale;
     }

@@ -16,6 +16,7 @@
 namespace asd_probe {
 
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));      // A / B operand of v_mfma_f32_32x32x16_bf16
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));     // A / B operand of v_mfma_f32_32x32x16_f16
 
 static thread_local char g_err[256] = "";
 static void set_error(const char* fmt, ...) {
@@ -28,24 +29,30 @@ static void set_error(const char* fmt, ...) {
 typedef uint32_t cu32x4 __attribute__((ext_vector_type(4)));
 typedef float cv16f __attribute__((ext_vector_type(16)));
 
-// 24 MFMAs per iteration on four accumulators, six A and six B fragments in rotation
-__global__ __launch_bounds__(256, 2) void ceiling_bf16_kernel(float* __restrict__ out, const cu32x4* __restrict__ in,
-                                                              int iters) {
+// 24 MFMAs per iteration on four accumulators, six A and six B fragments in rotation.  HALF: fp16 operands, else bf16.
+template <bool HALF>
+__device__ __forceinline__ cv16f mfma16(cu32x4 a, cu32x4 b, cv16f c) {
+  if constexpr (HALF) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+template <bool HALF>
+__global__ __launch_bounds__(256, 2) void ceiling_16bit_kernel(float* __restrict__ out, const cu32x4* __restrict__ in,
+                                                               int iters) {
   cv16f acc[4];
   for (int i = 0; i < 4; ++i)
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  v8bf a[6], b[6];
+  cu32x4 a[6], b[6];
   for (int i = 0; i < 6; ++i) {
-    a[i] = __builtin_bit_cast(v8bf, in[(threadIdx.x + 256 * i) & 4095]);
-    b[i] = __builtin_bit_cast(v8bf, in[(threadIdx.x + 256 * i + 2048) & 4095]);
+    a[i] = in[(threadIdx.x + 256 * i) & 4095];
+    b[i] = in[(threadIdx.x + 256 * i + 2048) & 4095];
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int u = 0; u < 6; ++u) {
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 1) % 6], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 2) % 6], acc[1], 0, 0, 0);
-      acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 3) % 6], b[u], acc[2], 0, 0, 0);
-      acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 4) % 6], b[u], acc[3], 0, 0, 0);
+      acc[0] = mfma16<HALF>(a[u], b[(u + 1) % 6], acc[0]);
+      acc[1] = mfma16<HALF>(a[u], b[(u + 2) % 6], acc[1]);
+      acc[2] = mfma16<HALF>(a[(u + 3) % 6], b[u], acc[2]);
+      acc[3] = mfma16<HALF>(a[(u + 4) % 6], b[u], acc[3]);
     }
   }
   float s = 0.f;
@@ -86,11 +93,12 @@ using namespace asd_probe;
 
 extern "C" const char* asd_probe_last_error(void) { return g_err; }
 
-extern "C" int32_t asd_probe_mfma_ceiling(int32_t bf16, int32_t random_data, int32_t ms_target, double* tflops) {
-  if (!tflops || ms_target < 1 || ms_target > 5000) {
-    set_error("asd_probe_mfma_ceiling: tflops is NULL or ms_target outside [1, 5000]");
+extern "C" int32_t asd_probe_mfma_ceiling(int32_t dtype, int32_t random_data, int32_t ms_target, double* tflops) {
+  if (!tflops || ms_target < 1 || ms_target > 5000 || dtype < 0 || dtype > 2) {
+    set_error("asd_probe_mfma_ceiling: tflops is NULL, ms_target outside [1, 5000] or dtype not 0 (fp32), 1 (bf16), 2 (fp16)");
     return -1;
   }
+  const bool bf16 = dtype != 0, half = dtype == 2;   // (bf16: a 16-bit operand type)
   constexpr int kWgs = 512, kWords = 4096 * 4, kBatch = 8;
   float* out = nullptr;
   cu32x4* in = nullptr;
@@ -107,8 +115,10 @@ extern "C" int32_t asd_probe_mfma_ceiling(int32_t bf16, int32_t random_data, int
     uint32_t w = 0;
     for (int hlf = 0; hlf < 2; ++hlf) {
       const uint32_t r = next();
-      const uint32_t sign = r & 1u, e = 125u + ((r >> 1) & 3u), m = (r >> 3) & 127u;   // |value| in [0.25, 4)
-      w |= (random_data ? ((sign << 15) | (e << 7) | m) : 0x3f80u) << (16 * hlf);
+      // |value| in [0.25, 4): bf16 = 1 + 8 + 7 bits, fp16 = 1 + 5 + 10
+      const uint32_t sign = r & 1u, e = (half ? 13u : 125u) + ((r >> 1) & 3u), m = (r >> 3) & (half ? 1023u : 127u);
+      const uint32_t one = half ? 0x3c00u : 0x3f80u;
+      w |= (random_data ? ((sign << 15) | (e << (half ? 10 : 7)) | m) : one) << (16 * hlf);
     }
     h[i] = w;
   }
@@ -145,7 +155,8 @@ extern "C" int32_t asd_probe_mfma_ceiling(int32_t bf16, int32_t random_data, int
     while (phase_ms < 0.5 * ms_target) {
       CEIL_HIP(hipEventRecord(e0, 0));
       for (int l = 0; l < kBatch; ++l) {   // back to back: host round trips between launches let the chip recover
-        if (bf16) hipLaunchKernelGGL(ceiling_bf16_kernel, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
+        if (half) hipLaunchKernelGGL(ceiling_16bit_kernel<true>, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
+        else if (bf16) hipLaunchKernelGGL(ceiling_16bit_kernel<false>, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
         else hipLaunchKernelGGL(ceiling_f32_kernel, dim3(kWgs), dim3(256), 0, 0, out, in, iters);
       }
       CEIL_HIP(hipGetLastError());

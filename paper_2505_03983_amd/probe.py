@@ -22,10 +22,10 @@ def lib():
     return _lib
 
 
-def asd_probe_mfma_ceiling(bf16, random_data=True, ms_target=200):
-    """TFLOP/s a register-only MFMA loop sustains on the current device."""
+def asd_probe_mfma_ceiling(dtype, random_data=True, ms_target=200):
+    """TFLOP/s a register-only MFMA loop sustains on the current device.  dtype: 0 / False fp32, 1 / True bf16, 2 fp16."""
     t = C.c_double(0.0)
-    rc = lib().asd_probe_mfma_ceiling(int(bool(bf16)), int(bool(random_data)), int(ms_target), C.addressof(t))
+    rc = lib().asd_probe_mfma_ceiling(int(dtype), int(bool(random_data)), int(ms_target), C.addressof(t))
     if rc != 0:
         raise RuntimeError("asd_probe_mfma_ceiling failed (%d): %s" % (rc, lib().asd_probe_last_error().decode()))
     return t.value

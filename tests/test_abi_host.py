@@ -169,4 +169,5 @@ def test_null_handles():
     t = ctypes.c_double(0.0)
     assert P.asd_probe_mfma_ceiling(1, 1, 0, ctypes.addressof(t)) == -1
     assert P.asd_probe_mfma_ceiling(0, 0, 5001, ctypes.addressof(t)) == -1
+    assert P.asd_probe_mfma_ceiling(3, 1, 100, ctypes.addressof(t)) == -1          # dtype is 0, 1 or 2
     assert b"ms_target" in P.asd_probe_last_error()

@@ -406,11 +406,13 @@ def test_logit_screen_is_bit_identical_and_skips_work():
 def test_mfma_ceiling_probe():
     """The probe of what the matrix pipes sustain: plausible, finite figures (no fixed expectation: the rate is set
     by the chip's power management), constant operands no slower than random ones."""
-    r_bf16 = probe.asd_probe_mfma_ceiling(True, True, 60)
-    c_bf16 = probe.asd_probe_mfma_ceiling(True, False, 60)
-    r_f32 = probe.asd_probe_mfma_ceiling(False, True, 60)
-    _log("mfma ceiling: bf16 random", r_bf16, "constant", c_bf16, "f32 random", r_f32)
+    r_bf16 = probe.asd_probe_mfma_ceiling(1, True, 60)
+    c_bf16 = probe.asd_probe_mfma_ceiling(1, False, 60)
+    r_f16 = probe.asd_probe_mfma_ceiling(2, True, 60)
+    r_f32 = probe.asd_probe_mfma_ceiling(0, True, 60)
+    _log("mfma ceiling: bf16 random", r_bf16, "constant", c_bf16, "fp16 random", r_f16, "f32 random", r_f32)
     assert 200.0 < r_bf16 <= 2600.0 and 200.0 < c_bf16 <= 2600.0 and c_bf16 >= 0.95 * r_bf16
+    assert 200.0 < r_f16 <= 2600.0
     assert 40.0 < r_f32 <= 165.0
 
 
