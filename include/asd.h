@@ -234,13 +234,14 @@ ASD_API asd_status asd_use_call_reuse(asd_ctx* ctx, int32_t on);
  * round kernels; the two paths agree to rounding.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_resident(asd_ctx* ctx, int32_t on);
 
-/* Model-call GEMMs of the large Gaussian-mixture denoiser on the bf16 matrix pipe with every fp32
- * operand split into three bf16 terms (six bf16 products per fp32 product, fp32 accumulation; what
- * is left out is 2^-23 of |a||b| per product on average and never above 2^-21, a few units of fp32
- * rounding).  Nothing in the method changes: it is another way to evaluate the same fp32 contraction,
- * about 1.5x faster on this chip than its fp32 matrix pipe.  The verify call takes it when d % 16 == 0
- * and C % 16 == 0 on the matrix-core path, the draft call when both are multiples of 32; on = 0
- * selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
+/* Model-call GEMMs of the large Gaussian-mixture denoiser on the 16-bit matrix pipes with every fp32
+ * operand split into 16-bit terms, fp32 accumulation.  d and C multiples of 32: two fp16 terms per operand
+ * (the nearest fp16 and the nearest fp16 of the remainder, operands scaled by powers of two into fp16's range) and
+ * three products per fp32 product, in both model calls; what is left out is 2^-23 of |a||b| per product on
+ * average and never above 3 * 2^-22, a few units of fp32 rounding.  Multiples of 16 only: three bf16 terms and
+ * six products (2^-23 on average, never above 2^-21), in the verify call.  Nothing in the method changes: it is
+ * another way to evaluate the same fp32 contraction, about 2.3x (1.5x) faster on this chip than its fp32 matrix
+ * pipe.  on = 0 selects the fp32 MFMA kernels.  Default: on.  Other shapes ignore the switch. */
 ASD_API asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on);
 
 /* Sequential chain with the same random inputs (one model call per step, K

@@ -1,21 +1,32 @@
-// fp32 "NT" GEMM on the gfx950 *bf16* matrix cores:  acc[m][n] = sum_k f(A[m][k]) * B[n][k]
-// with every fp32 operand split into three bf16 terms.
+// fp32 "NT" GEMM on the gfx950 16-bit matrix cores:  acc[m][n] = sum_k f(A[m][k]) * B[n][k]
+// with every fp32 operand split into 16-bit terms, in two forms (Split3Cfg::PLANES).
 //
-// An fp32 number has a 24-bit significand; cut into three runs of 8 bits it is the exact sum
-// x = x1 + x2 + x3 of three bf16 numbers (bf16 has fp32's exponent range, so nothing overflows; the
+// Three bf16 terms, six products.  An fp32 number has a 24-bit significand; cut into three runs of 8 bits it is the
+// exact sum x = x1 + x2 + x3 of three bf16 numbers (bf16 has fp32's exponent range, so nothing overflows; the
 // cut is by truncation: x1 = the top 16 bits of x, x2 = the top 16 bits of x - x1, x3 = the rest).
 // A product of two bf16 numbers is exact in fp32, and the matrix cores accumulate in fp32, so
 //   a*b ~= a1*b1 + (a1*b2 + a2*b1) + (a2*b2 + a1*b3 + a3*b1)
 // leaves out a2*b3 + a3*b2 + a3*b3: with |x2| < 2^-7 |x1| and |x3| < 2^-15 |x1| that is below 2^-21 |a||b|
 // always and 2^-23 |a||b| on average -- a few units of the rounding of one fp32 multiply-add (2^-24), and
-// small against the rounding that accumulating K = 10^3 terms in fp32 brings with it either way.  Six bf16 MFMAs replace one fp32 MFMA of the same shape, and the bf16 matrix
-// pipe of this chip is 16x as fast as its fp32 one on paper.  In practice this kernel keeps the bf16 pipes busy
-// in ~61% of the cycles at a power-managed clock of ~1.8 GHz (a register-only MFMA loop on random operands
-// sustains ~1.75 PFLOP/s, not the data-sheet 2.5), so the gain over the fp32 pipe is ~1.6x, at fp32 accuracy.  (Splitting into bf16 terms for
-// higher-precision products is an old, published device -- e.g. Henry, Tang, Heinecke 2019; the
-// arrangement here is this file's.)
+// small against the rounding that accumulating K = 10^3 terms in fp32 brings with it either way.  Six bf16 MFMAs
+// replace one fp32 MFMA of the same shape, on a pipe that is 16x as fast on paper.  (Splitting into bf16 terms for
+// higher-precision products is an old, published device -- e.g. Henry, Tang, Heinecke 2019; the arrangement here is
+// this file's.)
 //
-// Dataflow per K slab of 16 (one MFMA group):
+// Two fp16 terms, three products.  fp16 has an 11-bit significand: x1 = the nearest fp16 of x and x2 = the nearest
+// fp16 of x - x1 (exact in fp32) carry 22 bits, |x - x1 - x2| <= 2^-22 |x|, and
+//   a*b ~= a1*b1 + a1*b2 + a2*b1
+// leaves out a2*b2 and what the terms miss of a and of b: at most 3 * 2^-22 |a||b|, 2^-23 on average -- the same
+// accuracy from half the matrix instructions.  fp16 lacks the range, so the caller scales each operand by a power of
+// two (exact) that brings its largest magnitude into [2^14, 2^15) -- per row of A through the Op's load_a, once for B
+// (split3_pack_b_kernel's scale) -- and the Op's epilogue takes the scales out again.  A second term then leaves
+// fp16's normal range only where the element is below 2^-10 of the largest one: an absolute error of 2^-39 of that.
+//
+// Either way the loop moves as much as it multiplies.  Per 128 x 128 x 32 slab with fp16 terms a workgroup has 768
+// cycles of MFMA per SIMD, 96 KB through LDS and 32 KB from L2, and on this chip the three overlap little: a full
+// launch keeps the matrix pipes busy in ~40% of the cycles (three bf16 terms: ~62%, at a power-managed ~1.8 GHz).
+//
+// Dataflow per K slab (BK = 16: one MFMA group; 32: two), written for three planes -- two are the same with a plane less:
 //  * B is constant across calls: it is split once (split3_pack_b_kernel) into an *image* of what a
 //    workgroup's LDS stage holds -- per column tile and slab: three planes of BN rows x 32 bytes,
 //    chunk-swizzled -- so a thread copies three 16-byte pieces (one per plane) at fixed offsets:

@@ -19,8 +19,9 @@
 //    full tile efficiency with head dimension d = 1024 -- then P M (second
 //    MFMA GEMM against the pre-transposed means) with the softmax fused into
 //    its operand load and the final affine combination into its epilogue.
-//    By default on the bf16 matrix pipe with three-way split operands
-//    (gemm_split3.h; fp32 accuracy), else on the fp32 pipe (gemm_f32.h).
+//    By default on the 16-bit matrix pipes with split operands (gemm_split3.h;
+//    two fp16 or three bf16 terms, fp32 accuracy), else on the fp32 pipe
+//    (gemm_f32.h).
 //
 // The verify call of the split path leaves out the matrix work whose result is
 // an exact zero, bit-identically (sections below, in this order of the call):
@@ -46,7 +47,7 @@ namespace asd {
 // combine GEMM): 128x128x16 74 / 76%, 128x128x32 71 / 71%, 256x128x16 60 / 56%, 256x128x32 61 / 42%.
 typedef GemmCfg<128, 128, 16> GmmTile;
 typedef GemmCfg<64, 64, 32> GmmTileSkinny;                    // draft call: one row per chain, fill the chip
-// verify call on the bf16 matrix pipe with three-way split operands (fp32 accuracy)
+// verify call on the bf16 matrix pipe with three-way split operands (fp32 accuracy; shapes that are multiples of 16 only)
 typedef Split3Cfg<128, 128, 2, 2> GmmTileSplit;
 // draft call on the same pipe: half-height tiles, four wavefronts of 32 x 64, K slabs of 32
 typedef Split3Cfg<64, 128, 2, 2, 32> GmmTileSplitSkinny;
@@ -577,9 +578,10 @@ struct CombineOp {
 //
 // One-hot rows (onehot != NULL; needs np <= 64 and column groups of 64).  Once a posterior has collapsed a row has
 // exactly one logit within kZeroGap of its maximum -- the maximum itself.  Its weights are then 2^0 = 1.0 for that
-// component b and exact zeros elsewhere, the row sum is 1.0, and the second GEMM's result for it is mu_b bit for bit
-// (the three bf16 terms of mu_b times 1.0, added in an order in which every partial sum is exact; all other
-// products are zeros), so  out = fma(c_x', x, c_m' mu_b)  needs no GEMM.  A row's few live groups are scanned for
+// component b and exact zeros elsewhere, the row sum is 1.0, and the second GEMM's result for it is known bit for bit:
+// the terms of mu_b times the terms of 1.0, added in an order in which every partial sum is exact, all other products
+// zeros -- mu_b itself from three bf16 terms, (m1 + m2) / scale from two fp16 terms (gmm_means22_kernel) -- so
+// out = fma(c_x', x, c_m' mu_b)  with that mu_b needs no GEMM.  A row's few live groups are scanned for
 // that (rows with more than two live groups are not candidates): onehot[row] = b or -1, and onehot_tile[row tile] =
 // 1 when all its rows qualify -- the second GEMM then skips the tile and gmm_onehot_kernel writes it.
 // The component b of a one-hot row, or -1: called by a whole wavefront with the row's partial maxima p[np] (np <= 64,
