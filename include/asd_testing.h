@@ -53,6 +53,15 @@ ASD_API int32_t asd_logit_screen_active(const asd_ctx* ctx);
 ASD_API asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on);
 ASD_API int32_t asd_onehot_certificate_active(const asd_ctx* ctx);
 
+/* Verify calls of the split-operand mixture denoiser on fp16 terms whose every tile is wanted -- calls that are not
+ * screened, by the draft call's verdict or at all -- run their two GEMMs on 256 x 256 tiles (eight wavefronts of
+ * 128 x 64, fragments streamed one plane pair at a time) when the context has at least 16384 model rows per call
+ * (chains * L); otherwise, and for every other launch, on 128 x 128 tiles.  The same terms are added in the same order
+ * per output element: results are identical bit for bit.  on = 0 keeps every launch on the small tiles (for tests and
+ * timing comparisons).  Default: on.  asd_tall_tiles_active: 1 if this context's dense verify calls take them. */
+ASD_API asd_status asd_use_tall_tiles(asd_ctx* ctx, int32_t on);
+ASD_API int32_t asd_tall_tiles_active(const asd_ctx* ctx);
+
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
 ASD_API asd_status asd_debug_philox(uint64_t seed, uint32_t chain, uint32_t step, uint32_t stream_id,

@@ -73,6 +73,8 @@ def lib():
             "asd_use_logit_screen": (i32, [vp, i32]),
             "asd_logit_screen_active": (i32, [vp]),
             "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp, vp, vp]),
+            "asd_use_tall_tiles": (i32, [vp, i32]),
+            "asd_tall_tiles_active": (i32, [vp]),
             "asd_use_onehot_certificate": (i32, [vp, i32]),
             "asd_onehot_certificate_active": (i32, [vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
@@ -257,6 +259,12 @@ class Ctx:
 
     def logit_screen_active(self):
         return int(lib().asd_logit_screen_active(self.h))
+
+    def use_tall_tiles(self, on=True):
+        _check(lib().asd_use_tall_tiles(self.h, int(bool(on))))
+
+    def tall_tiles_active(self):
+        return bool(lib().asd_tall_tiles_active(self.h))
 
     def use_onehot_certificate(self, on=True):
         _check(lib().asd_use_onehot_certificate(self.h, int(bool(on))))

@@ -549,6 +549,23 @@ asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on) {
   return ASD_OK;
 }
 
+asd_status asd_use_tall_tiles(asd_ctx* ctx, int32_t on) {
+  if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
+  if (ctx->gmm && ctx->gmm->big_on != (on != 0)) {
+    ctx->gmm->big_on = on != 0;
+    if (ctx->gexec) {   // the captured round holds the other launches
+      (void)hipGraphExecDestroy(ctx->gexec);
+      ctx->gexec = nullptr;
+    }
+  }
+  return ASD_OK;
+}
+
+int32_t asd_tall_tiles_active(const asd_ctx* ctx) {
+  const asd::GmmState* g = ctx ? ctx->gmm : nullptr;
+  return (g && g->use_split && g->two_ok && g->big_ok && g->big_on) ? 1 : 0;
+}
+
 int32_t asd_onehot_certificate_active(const asd_ctx* ctx) {
   const asd::GmmState* g = ctx ? ctx->gmm : nullptr;
   return (asd_logit_screen_active(ctx) != 0 && g->cert_ok && g->cert_on) ? 1 : 0;

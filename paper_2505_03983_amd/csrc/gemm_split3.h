@@ -417,7 +417,11 @@ template <class Cfg, class Op, int CALL, bool ROWS_PER_XCD>
 __global__ __launch_bounds__(Cfg::THREADS, 2) void gemm_split3_nt_kernel(const int* __restrict__ M_dev, int M_max,
                                                                          int N, int K, RowSrc A,
                                                                          const uint8_t* __restrict__ Bimg, Op op,
-                                                                         float* __restrict__ part, int sparse) {
+                                                                         float* __restrict__ part, int sparse,
+                                                                         const int32_t* __restrict__ run_if, int run_val) {
+  // run_if (or NULL): the kernel runs only if *run_if == run_val -- a switch in device memory, so that one captured
+  // graph can hold two forms of a GEMM and the device picks one
+  if (run_if && *run_if != run_val) return;
   const int M = M_dev ? min(*M_dev, M_max) : M_max;
   int tile_n = blockIdx.x, tile_m = blockIdx.y;
   if (ROWS_PER_XCD) {
@@ -502,7 +506,8 @@ inline bool split3_sparse_fits(int K, int groups, int group_cols) {
 // multiple of BK wide and K a multiple of them; otherwise the loop stays dense).
 template <class Cfg, int CALL, bool ROWS_PER_XCD, class Op>
 inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int K, RowSrc A, const uint8_t* Bimg,
-                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false) {
+                                        Op op, hipStream_t st, int splits = 1, float* part = nullptr, bool sparse = false,
+                                        const int32_t* run_if = nullptr, int run_val = 0) {
   if (K % Cfg::BK != 0 || K <= 0 || splits < 1) return hipErrorInvalidValue;
   size_t lds = Cfg::LDS_BYTES;
   if constexpr (Op::kSparseK) {
@@ -523,7 +528,8 @@ inline hipError_t launch_gemm_split3_nt(const int* M_dev, int M_max, int N, int 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), lds, st, M_dev, M_max, N, K, A, Bimg, op, part, sparse ? 1 : 0);
+  hipLaunchKernelGGL(kern, grid, dim3(Cfg::THREADS), lds, st, M_dev, M_max, N, K, A, Bimg, op, part, sparse ? 1 : 0, run_if,
+                     run_val);
   return hipGetLastError();
 }
 

@@ -39,6 +39,7 @@
 #include "gemm_i8_stream.h"
 #include "gemm_f32.h"
 #include "gemm_split3.h"
+#include "gemm_split2_big.h"
 #include "gmm_state.h"
 
 namespace asd {
@@ -56,6 +57,10 @@ typedef Split3Cfg<64, 128, 2, 2, 32> GmmTileSplitSkinny;
 // tilings above, the draft call on the fp32 pipe.)
 typedef Split3Cfg<128, 128, 2, 2, 32, 2> GmmTile2;
 typedef Split3Cfg<64, 128, 2, 2, 32, 2> GmmTile2Skinny;
+// ... and verify calls of at least kBigRows rows, where every tile is wanted, on 256 x 256 tiles (gemm_split2_big.h):
+// the same terms in the same order per element, so the same bits; 64-column groups of partial maxima as the others
+constexpr int kBigRows = 16384;
+static_assert(Split2BigCfg::WN == GmmTile2::WN && Split2BigCfg::BM % 128 == 0, "partial maxima and row flags");
 static_assert(GmmTile2::BN == GmmTileSplit::BN && GmmTile2::WGN == GmmTileSplit::WGN && GmmTile2::BM == GmmTileSplit::BM &&
               GmmTile2::B_STAGE == GmmTile2Skinny::B_STAGE && GmmTile2::BK == GmmTile2Skinny::BK,
               "the tilings lay rows, row maxima and images out alike");
@@ -340,6 +345,13 @@ struct LogitOp {
   float asc[kMaxPasses];
   static constexpr int kSkipTile = 128;
   __device__ __forceinline__ bool skip_row_tile(int m0) const { return skip_tile && skip_tile[m0 / kSkipTile] != 0; }
+  template <int BM>   // a taller tile (gemm_split2_big.h): every flag of its rows m0 .. min(m0 + BM, M) - 1
+  __device__ __forceinline__ bool skip_rows(int m0, int M) const {
+    if (!skip_tile) return false;
+    for (int m = m0; m < min(m0 + BM, M); m += kSkipTile)
+      if (!skip_tile[m / kSkipTile]) return false;
+    return true;
+  }
   static constexpr float kLog2e = 1.4426950408889634f;  // logits are stored in base-2 units for the exp2 of GEMM 2
   // s_row[8 r + 1], [8 r + 2]: log2(e) kappa, log2(e) gamma of tile row r
   template <class Cfg>
@@ -431,14 +443,32 @@ struct CombineOp {
   const uint8_t* onehot_tile = nullptr;
   static constexpr bool kRowTileSkip = true;
   __device__ __forceinline__ bool skip_row_tile(int m0) const { return onehot_tile && onehot_tile[m0 / kRowmaxTile] != 0; }
+  // A taller tile (gemm_split2_big.h) is skipped when every flag of its rows is set; when only some are, the rows
+  // behind them are computed along (on whatever their logits hold) and not stored (the epilogue's per-row flag).
+  template <int BM>
+  __device__ __forceinline__ bool skip_rows(int m0, int M) const {
+    if (!onehot_tile) return false;
+    for (int m = m0; m < min(m0 + BM, M); m += kRowmaxTile)
+      if (!onehot_tile[m / kRowmaxTile]) return false;
+    return true;
+  }
   __host__ __device__ __forceinline__ int groups() const { return np; }
   __host__ __device__ __forceinline__ int group_cols() const { return gcols; }
   template <class Cfg>
   __device__ __forceinline__ void mark_live(int m0, int M, int lrow, int lkq, uint8_t* flags) const {
     if (live_pre) {
-      static_assert(Cfg::BM == kRowmaxTile || Cfg::BM * 2 == kRowmaxTile, "row tiles of the precomputed flags");
+      static_assert(Cfg::BM * 2 == kRowmaxTile || Cfg::BM % kRowmaxTile == 0, "row tiles of the precomputed flags");
       const uint8_t* src = live_pre + (int64_t)(m0 / kRowmaxTile) * np;   // (a half-height tile takes its parent's flags)
-      for (int q = lrow * Cfg::KQ + lkq; q < np; q += Cfg::THREADS) flags[q] = src[q];
+      if constexpr (Cfg::BM <= kRowmaxTile) {
+        for (int q = lrow * Cfg::KQ + lkq; q < np; q += Cfg::THREADS) flags[q] = src[q];
+      } else {   // a taller tile: what any of its row tiles wants, those written in closed form aside
+        for (int q = lrow * Cfg::KQ + lkq; q < np; q += Cfg::THREADS) {
+          uint8_t f = 0;
+          for (int s = 0; s < Cfg::BM / kRowmaxTile && m0 + s * kRowmaxTile < M; ++s)
+            if (!(onehot_tile && onehot_tile[m0 / kRowmaxTile + s])) f |= src[(int64_t)s * np + q];
+          flags[q] = f;
+        }
+      }
       return;
     }
 #pragma unroll
@@ -469,7 +499,7 @@ struct CombineOp {
   // split times a_scale, B's image holds b_scale B, and the epilogue takes both out again (exactly).  The row sums
   // are those of the unscaled weights.
   float a_scale = 1.f, b_scale = 1.f;
-  // s_row[8 r ..]: row sum, c_x', c_m' / (a_scale b_scale), -, in_off (8 bytes), out_off (8 bytes) of tile row r
+  // s_row[8 r ..]: row sum, c_x', c_m' / (a_scale b_scale), 1 = do not store, in_off (8 bytes), out_off (8 bytes) of tile row r
   template <class Cfg>
   __device__ __forceinline__ void init(int m0, int M, int lrow, int lkq, float* s_row) {
     static_assert(Cfg::RA <= kMaxPasses, "loader passes");
@@ -491,6 +521,7 @@ struct CombineOp {
         const float4 cf = coef_tau[tau[m]];
         s_row[8 * r + 1] = cf.z;
         s_row[8 * r + 2] = cf.w / (a_scale * b_scale);   // (a division by a power of two: exact)
+        s_row[8 * r + 3] = (onehot_tile && onehot_tile[m / kRowmaxTile]) ? 1.f : 0.f;   // written in closed form: not ours
         *reinterpret_cast<int64_t*>(&s_row[8 * r + 4]) = in_off[m];
         *reinterpret_cast<int64_t*>(&s_row[8 * r + 6]) = out_off[m];
       }
@@ -557,7 +588,7 @@ struct CombineOp {
 #pragma unroll
         for (int rr = 0; rr < RB; ++rr) {
           const int ml = fr.row(i, r0 + rr);
-          if (m0 + ml >= M) continue;
+          if (m0 + ml >= M || s_row[8 * ml + 3] != 0.f) continue;
           const float cz = s_row[8 * ml + 1];
           const float scale = s_row[8 * ml + 2] / s_row[8 * ml];
           float* o = out_base + *reinterpret_cast<const int64_t*>(&s_row[8 * ml + 6]);
@@ -1098,7 +1129,10 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
                                                                 float* __restrict__ pmax, int np, int gpt, int halves,
                                                                 float* __restrict__ logits, int64_t ldl,
                                                                 const uint8_t* __restrict__ cert_tile,
+                                                                int dense_elsewhere,
                                                                 unsigned long long* __restrict__ counts) {
+  // dense_elsewhere: a call that is not screened (*on == 0) has its tiles computed by another kernel (the tall-tile
+  // form, which runs on the same switch): nothing is listed for it, the tiles are only counted.
   extern __shared__ int s_flag[];   // [2][ntn]: upper, lower half of the rows
   constexpr int BM = GmmTileSplit::BM, RW = 4;   // rows a wavefront works on at a time (their loads overlap)
   const int n = min(*n_dev, n_max);
@@ -1167,6 +1201,7 @@ __global__ __launch_bounds__(256) void gmm_screen_decide_kernel(const int* __res
     const int up = s_flag[t], low = s_flag[ntn + t];
     if (!up && !low) continue;
     mine += up + low;
+    if (dense_elsewhere && !screened) continue;
     uint32_t e = (uint32_t)(blockIdx.x * ntn + t);
     if (halves && up != low) e |= kListHalf | (low ? kListLower : 0u);
     const int pos = atomicAdd(&tile_count[t % 8], 1);
@@ -1359,6 +1394,13 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
                          (int64_t)C * d, g->b_scale, g->means22);
       ASD_HIP(hipGetLastError());
       g->two_ok = g->split_draft_ok = true;
+      if (ctx->n_rows_max >= kBigRows) {   // enough rows for 256 x 256 tiles to fill the chip
+        ASD_HIP(hipMalloc(&g->means_img_big, split3_image_bytes<Split2BigCfg>(C, d)));
+        ASD_HIP(hipMalloc(&g->means_t_img_big, split3_image_bytes<Split2BigCfg>(d, C)));
+        ASD_HIP(launch_split3_pack_b<Split2BigCfg>(g->means, d, C, d, g->means_img_big, 0, g->b_scale));
+        ASD_HIP(launch_split3_pack_b<Split2BigCfg>(g->means_t, C, d, C, g->means_t_img_big, 0, g->b_scale));
+        g->big_ok = true;
+      }
     } else {   // the verify call only, on three bf16 terms
       ASD_HIP(hipMalloc(&g->means_img, split3_image_bytes<GmmTileSplit>(C, d)));
       ASD_HIP(hipMalloc(&g->means_t_img, split3_image_bytes<GmmTileSplit>(d, C)));
@@ -1484,6 +1526,8 @@ void gmm_destroy(asd_ctx* ctx) {
   (void)hipFree(g->means_t_img_s);
   (void)hipFree(g->means_img2);
   (void)hipFree(g->means_t_img2);
+  (void)hipFree(g->means_img_big);
+  (void)hipFree(g->means_t_img_big);
   (void)hipFree(g->means22);
   (void)hipFree(g->a_scale);
   (void)hipFree(g->musq);
@@ -1553,6 +1597,11 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const bool cert = split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine && g->cert_ok && g->cert_on &&
                     rows.chain != nullptr && (rows.call == 1 || g->split_draft_ok);
   const uint8_t* cert_tile = cert ? g->cert_tile : nullptr;
+  // the screening pass's switch in device memory: this round's verdict of the draft call, or the constant 1
+  const int32_t* on = screen ? g->screen_on + (g->screen_mode == 2 ? 1 : 0) : nullptr;
+  // launches in which every tile is wanted -- a verify call of many rows that is not screened, by this round's verdict
+  // or at all -- take the 256 x 256 tiles; both forms of a GEMM are queued then and the switch picks one
+  const bool big = split && g->two_ok && g->big_ok && g->big_on && rows.call == 1 && n >= kBigRows;
   if (cert) {
     ProfScope ps(ctx, ASD_PROF_GMM_CERT, rows.call, st);
     auto kern = d <= 1024 ? gmm_certify_kernel<4> : gmm_certify_kernel<8>;
@@ -1565,7 +1614,6 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   }
   if (screen) {
     ProfScope ps(ctx, ASD_PROF_GMM_SCREEN, rows.call, st);
-    const int32_t* on = g->screen_on + (g->screen_mode == 2 ? 1 : 0);
     const int ntn = C / GmmTileSplit::BN;
     hipLaunchKernelGGL(gmm_screen_pack_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d,
                        rows.in_base, rows.in_off, on, g->xq, g->xs, g->a_scale, g->tile_count, cert_tile,
@@ -1580,7 +1628,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                        sizeof(int) * 2 * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
                        g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_list, g->tile_count, g->list_cap,
                        g->pmax, np, GmmTileSplit::WGN, g->split_draft_ok ? 1 : 0, g->logits, (int64_t)C, cert_tile,
-                       ctx->prof.on ? g->work_counts : nullptr);
+                       big ? 1 : 0, ctx->prof.on ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.tile_list = g->tile_list;
     op1.tile_count = g->tile_count;
@@ -1599,9 +1647,13 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
       op1.b_scale = g->b_scale;
     }
     if (screen) {
-      // resident workgroups draw the tiles (and half tiles, on the draft call's tiling) the screening pass listed
+      // resident workgroups draw the tiles (and half tiles, on the draft call's tiling) the screening pass listed;
+      // a call it was switched off for lists nothing when the tall tiles take it
       ASD_HIP(launch_gemm_split3_nt_list<GmmTile2, GmmTile2Skinny, 1>(rows.n_dev, n, C, d, X, g->means_img2, g->means_img2,
                                                                        op1, kResidentWgs, st));
+      if (big) ASD_HIP(launch_gemm_split2_big<false>(rows.n_dev, n, C, d, X, g->means_img_big, op1, st, false, on, 0));
+    } else if (big) {
+      ASD_HIP(launch_gemm_split2_big<false>(rows.n_dev, n, C, d, X, g->means_img_big, op1, st, false, nullptr, 0));
     } else if (two) {
       ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTile2, 1, false>(rows.n_dev, n, C, d, X, g->means_img2, op1, st)
                         : launch_gemm_split3_nt<GmmTile2Skinny, 0, false>(rows.n_dev, n, C, d, X, g->means_img2, op1, st));
@@ -1657,10 +1709,18 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     if (two) {
       op2.a_scale = 32768.f;   // the weights are at most 1: 2^15 is the largest power of two fp16 can take them at
       op2.b_scale = g->b_scale;
-      ASD_HIP(rows.call ? launch_gemm_split3_nt<GmmTile2, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st, 1, nullptr,
-                                                                   g->sparse_combine)
-                        : launch_gemm_split3_nt<GmmTile2Skinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st,
-                                                                           splits, g->part));
+      if (rows.call == 0) {
+        ASD_HIP(launch_gemm_split3_nt<GmmTile2Skinny, 0, false>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st, splits,
+                                                                 g->part));
+      } else {
+        // (with the tall tiles queued as well: the small ones when this call was screened, the tall ones when not)
+        if (!big || screen)
+          ASD_HIP(launch_gemm_split3_nt<GmmTile2, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img2, op2, st, 1, nullptr,
+                                                           g->sparse_combine, big ? on : nullptr, 1));
+        if (big)
+          ASD_HIP(launch_gemm_split2_big<true>(rows.n_dev, n, d, C, P, g->means_t_img_big, op2, st, g->sparse_combine,
+                                               screen ? on : nullptr, 0));
+      }
     } else if (split)
       ASD_HIP(launch_gemm_split3_nt<GmmTileSplit, 1, true>(rows.n_dev, n, d, C, P, g->means_t_img, op2, st, 1, nullptr,
                                                            g->sparse_combine));

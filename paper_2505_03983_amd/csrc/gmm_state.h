@@ -38,6 +38,12 @@ struct GmmState {
   float* a_scale = nullptr;        // [rows_max]
   float* means22 = nullptr;        // [C, d]
   bool two_ok = false;
+  // ... and for verify calls of many rows the same two images for 256 x 256 tiles (gemm_split2_big.h): launches in
+  // which every tile is wanted take those
+  uint8_t* means_img_big = nullptr;
+  uint8_t* means_t_img_big = nullptr;
+  bool big_ok = false;
+  bool big_on = true;              // the switch (asd_use_tall_tiles)
   bool split_draft_ok = false;     // d and C are multiples of 32: the draft call can take the split kernels too
   bool split_ok = false;           // the shape allows them
   bool use_split = false;          // ... and they are switched on (asd_use_split_gemm)

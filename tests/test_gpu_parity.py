@@ -403,6 +403,32 @@ def test_logit_screen_is_bit_identical_and_skips_work():
         ctx_b.close()
 
 
+def test_tall_tiles_are_bit_identical_to_the_small_ones():
+    """Verify calls of many rows whose every tile is wanted run their GEMMs on 256 x 256 tiles (the same terms in the
+    same order per element).  The largest workload's shape with a quarter of its chains -- 16384 model rows per
+    call, the least that takes them: whole samples with the tall tiles, without, and without the screening pass
+    either way (then every verify call is a dense one, the late ones with rows of one weight among them)."""
+    cfg = dict(W.CONFIGS[5], chains=256)
+    ctx = runtime.open_ctx(cfg, W.make_params(cfg, 1), seed=0)
+    assert ctx.tall_tiles_active() and ctx.logit_screen_active() == 1
+    res = []
+    for tall, screen in ((True, 1), (False, 1), (True, 0), (False, 0)):
+        ctx.use_tall_tiles(tall)
+        ctx.use_logit_screen(screen)
+        assert ctx.tall_tiles_active() == tall
+        ctx.set_seed(9)
+        traj = runtime.alloc_traj(ctx)
+        rounds = torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV)
+        ctx.sample(traj, rounds)
+        torch.cuda.synchronize()
+        res.append((traj, rounds))
+    for traj, rounds in res[1:]:
+        assert torch.equal(traj, res[0][0]) and torch.equal(rounds, res[0][1])
+    assert bool(torch.isfinite(res[0][0]).all())
+    _log("tall tiles: whole samples of 256 chains bit-identical with and without them, screened and not; rounds max", int(res[0][1].max()))
+    ctx.close()
+
+
 def test_mfma_ceiling_probe():
     """The probe of what the matrix pipes sustain: plausible, finite figures (no fixed expectation: the rate is set
     by the chip's power management), constant operands no slower than random ones."""
