@@ -8,9 +8,10 @@
 // wavefront holds one plane of A and one of B at a time and takes the three plane pairs in the order
 //   a1 b1,  a1 b2,  a2 b1
 // reading b2 under the first eight MFMAs, a2 under the second and the next group's a1, b1 under the third (a1's
-// registers are free by then; b1 has a second buffer).  Global loads run one slab ahead in a single register slot:
-// a slab is 48 MFMAs = 1536 cycles per wavefront, enough to cover an L2 round trip.  Same terms, same order of
-// accumulation per output element as gemm_split3.h's tile: the results are bit-identical to it.
+// registers are free by then; b1 has a second buffer).  Global loads: B -- an image that stays in the caches -- one
+// slab ahead in a single register slot (a slab is 48 MFMAs = 1536 cycles per wavefront), A -- which streams from
+// memory -- two slabs ahead in two.  Same terms, same order of accumulation per output element as gemm_split3.h's
+// tile: the results are bit-identical to it.
 //
 // Requirements (checked by the launcher): K % 32 == 0, B's image packed for this tiling (BN = 256), rows of A 16-byte
 // aligned.  One workgroup per CU (136 KB of LDS).  No K split, no tile lists.
@@ -106,26 +107,29 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
     if constexpr (Op::kSparseK) return listed ? (int64_t)__builtin_amdgcn_readfirstlane((int)s_list[kt]) : (int64_t)kt;
     return (int64_t)kt;
   };
-  float4 ra[RA][2];
+  float4 ra[2][RA][2];
   u32x4 rb[B_LOADS];
-  auto gload = [&](int kt) {
+  auto gload_a = [&](int kt, int slot) {
     const int64_t sl = slab_of(kt);
 #pragma unroll
     for (int p = 0; p < RA; ++p) {
-      ra[p][0] = *reinterpret_cast<const float4*>(ap[p] + sl * BK);
-      ra[p][1] = *reinterpret_cast<const float4*>(ap[p] + sl * BK + 4);
+      ra[slot][p][0] = *reinterpret_cast<const float4*>(ap[p] + sl * BK);
+      ra[slot][p][1] = *reinterpret_cast<const float4*>(ap[p] + sl * BK + 4);
     }
+  };
+  auto gload_b = [&](int kt) {
+    const int64_t sl = slab_of(kt);
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) rb[q] = *reinterpret_cast<const u32x4*>(bsrc + sl * B_STAGE + q * 16 * Cfg::THREADS);
   };
-  auto sstore = [&](int stage) {   // the register slot -> LDS stage `stage`
+  auto sstore = [&](int stage, int slot) {   // register slot -> LDS stage `stage`
     uint8_t* sa = lds_a + stage * A_STAGE;
     uint8_t* sb = lds_b + stage * B_STAGE + tid * 16;
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) *reinterpret_cast<u32x4*>(sb + q * 16 * Cfg::THREADS) = rb[q];
 #pragma unroll
     for (int p = 0; p < RA; ++p) {
-      const float4 v0 = op.load_a(ra[p][0], p), v1 = op.load_a(ra[p][1], p);
+      const float4 v0 = op.load_a(ra[slot][p][0], p), v1 = op.load_a(ra[slot][p][1], p);
       const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
       u32x4 p1, p2;
       split2_pack(x, p1, p2);
@@ -166,17 +170,20 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
   };
   auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-  // ---- prologue: slab 0 in stage 0, slab 1 on its way into the register slot, the first fragments read
-  gload(0);
-  sstore(0);
-  if (nk > 1) gload(1);
+  // ---- prologue: slab 0 in stage 0; A of slabs 1 and 2 and B of slab 1 on their way.  Slab k's A waits in register
+  // slot k & 1.
+  gload_a(0, 0);
+  gload_b(0);
+  if (nk > 1) gload_a(1, 1);
+  sstore(0, 0);
+  if (nk > 1) gload_b(1);
+  if (nk > 2) gload_a(2, 0);
   lds_barrier();
   read_a(0, 0, 0, a1);
   read_b(0, 0, 0, b1[0]);
-
-  // One slab (LDS stage par): two groups of three plane pairs.  The slab after it goes from the register slot into the
-  // other stage under the first group, and its loads' successor is issued right behind; the barrier sits in front of
-  // the last eight MFMAs, under which the next slab's first fragments arrive.
+  // One slab (LDS stage par): two groups of three plane pairs.  The slab after it goes from the registers into the
+  // other stage under the first group, and the loads that refill them are issued right behind; the barrier sits in
+  // front of the last eight MFMAs, under which the next slab's first fragments arrive.
   auto slab = [&](int kt, auto par_c) {
     constexpr int par = decltype(par_c)::value, npar = par ^ 1;
     const bool more = kt + 1 < nk;
@@ -186,11 +193,13 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
     mma(a1, b1[0]);
     read_a(par, 1, 0, a2);
     mma(a1, b2);
-    if (more) sstore(npar);          // stage npar: its last readers passed the barrier of the slab before
+    // (stage npar: its last readers passed the barrier of the slab before; slab kt + 1 sits in A slot (kt + 1) & 1)
+    if (more) sstore(npar, npar);
+    if (kt + 2 < nk) gload_b(kt + 2);
     read_a(par, 0, 1, a1);
     read_b(par, 0, 1, b1[1]);
     mma(a2, b1[0]);
-    if (kt + 2 < nk) gload(kt + 2);
+    if (kt + 3 < nk) gload_a(kt + 3, npar);   // the slot sstore has just emptied
     // group 1
     read_b(par, 1, 1, b2);
     mma(a1, b1[1]);
