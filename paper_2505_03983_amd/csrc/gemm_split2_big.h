@@ -104,7 +104,10 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
   }
   const uint8_t* bsrc = Bimg + (int64_t)tile_n * nk_all * B_STAGE + tid * 16;
   auto slab_of = [&](int kt) -> int64_t {
-    if constexpr (Op::kSparseK) return listed ? (int64_t)__builtin_amdgcn_readfirstlane((int)s_list[kt]) : (int64_t)kt;
+    if constexpr (Op::kSparseK) {   // read in either case (the list's room is always there): a branch here would cut
+      const int sl = __builtin_amdgcn_readfirstlane((int)s_list[kt]);   // the slab's code into scheduling regions
+      return (int64_t)(listed ? sl : kt);
+    }
     return (int64_t)kt;
   };
   float4 ra[2][RA][2];
@@ -184,9 +187,16 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
   // One slab (LDS stage par): two groups of three plane pairs.  The slab after it goes from the registers into the
   // other stage under the first group, and the loads that refill them are issued right behind; the barrier sits in
   // front of the last eight MFMAs, under which the next slab's first fragments arrive.
-  auto slab = [&](int kt, auto par_c) {
+  // steady: slabs kt + 1 .. kt + 3 exist -- no branches, so that the slab is one scheduling region and the interleaving
+  // asked for below holds: three VALU instructions of the split behind each of the first sixteen MFMAs, in the first
+  // GEMM also the stores into the other stage and B's loads behind the next eight and A's loads behind the eight after.
+  // (An MFMA holds its pipe for 32 cycles in which the wavefront can issue half a dozen other instructions for
+  // nothing; clumped behind the MFMAs they cost their full time.  Measured on 65536 x 4096 x 1024: first GEMM 1.84 ->
+  // 1.80 ms, second 1.64 -> 1.53 ms, most of the latter from the single region.)
+  auto slab = [&](int kt, auto par_c, auto steady_c) {
     constexpr int par = decltype(par_c)::value, npar = par ^ 1;
-    const bool more = kt + 1 < nk;
+    constexpr bool steady = decltype(steady_c)::value;
+    const bool more = steady || kt + 1 < nk;
     __builtin_amdgcn_s_setprio(1);
     // group 0
     read_b(par, 1, 0, b2);
@@ -195,14 +205,21 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
     mma(a1, b2);
     // (stage npar: its last readers passed the barrier of the slab before; slab kt + 1 sits in A slot (kt + 1) & 1)
     if (more) sstore(npar, npar);
-    if (kt + 2 < nk) gload_b(kt + 2);
+    if (steady || kt + 2 < nk) gload_b(kt + 2);
     read_a(par, 0, 1, a1);
     read_b(par, 0, 1, b1[1]);
     mma(a2, b1[0]);
-    if (kt + 3 < nk) gload_a(kt + 3, npar);   // the slot sstore has just emptied
+    if (steady || kt + 3 < nk) gload_a(kt + 3, npar);   // the slot sstore has just emptied
     // group 1
     read_b(par, 1, 1, b2);
     mma(a1, b1[1]);
+    if constexpr (steady) {
+      sched_pairs<0x002, 16, 3>();
+      if constexpr (!Op::kSparseK) {   // (the second GEMM, with four times the VALU work in load_a, ran slower with these)
+        sched_pairs<0x200, 8, 1>();
+        sched_pairs<0x020, 8, 1>();
+      }
+    }
     read_a(par, 1, 1, a2);
     mma(a1, b2);
     if (more) {
@@ -215,9 +232,16 @@ __global__ __launch_bounds__(512, 1) void gemm_split2_big_kernel(const int* __re
   };
   typedef std::integral_constant<int, 0> I0;
   typedef std::integral_constant<int, 1> I1;
-  for (int kt = 0; kt < nk; kt += 2) {
-    slab(kt, I0());
-    if (kt + 1 < nk) slab(kt + 1, I1());
+  typedef std::integral_constant<bool, true> Steady;
+  typedef std::integral_constant<bool, false> Tail;
+  int kt = 0;
+  for (; kt + 4 < nk; kt += 2) {
+    slab(kt, I0(), Steady());
+    slab(kt + 1, I1(), Steady());
+  }
+  for (; kt < nk; kt += 2) {
+    slab(kt, I0(), Tail());
+    if (kt + 1 < nk) slab(kt + 1, I1(), Tail());
   }
   __syncthreads();   // every wavefront is done with the operand stages
 
@@ -231,7 +255,8 @@ template <class Op>
 inline size_t split2_big_lds(int K, const Op& op, bool sparse) {
   size_t lds = Split2BigCfg::LDS_BYTES;
   if constexpr (Op::kSparseK) {
-    if (sparse) lds += (size_t)((2 * (K / Split2BigCfg::BK) + 15) & ~15) + (size_t)((op.groups() + 15) & ~15) + 16;
+    (void)sparse;   // the list's room also when nothing is listed: the kernel reads it without asking
+    lds += (size_t)((2 * (K / Split2BigCfg::BK) + 15) & ~15) + (size_t)((op.groups() + 15) & ~15) + 16;
   }
   return lds;
 }
