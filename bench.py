@@ -122,9 +122,15 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
         ctx.sample(traj, rounds)
     torch.cuda.synchronize()
     if profile:
+        # profile = True: every kernel of the path is bracketed by events; a list: those slots only (an event ends
+        # the overlap of the kernels around it and costs a few microseconds: two thousand of them per sample of
+        # workload 5 are a tenth of its time, the four per round around the two verify GEMMs are not)
+        ctx.profile_select(None if profile is True else profile)
         ctx.profile_enable(True)
     path = "chain-resident kernel, one launch per sample" if ctx.resident_active() else \
-        "lock-step round kernels" + ("" if profile else ", one captured graph per round")
+        "lock-step round kernels" + ((", plain launches, events around every kernel" if profile is True else
+                                      ", plain launches, events around " + " and ".join(profile)) if profile
+                                     else ", one captured graph per round")
     launched = []
     rmean, rmax = [], []
     sampler = ClockSampler() if clocks else None
@@ -163,6 +169,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
         out["accept_rows"] = ctx.profile_accept_rows()
         out["model_work"] = ctx.profile_model_work()
         ctx.profile_enable(False)
+        ctx.profile_select(None)
     ctx.close()
     del traj
     torch.cuda.empty_cache()
@@ -430,9 +437,15 @@ def main():
         torch.cuda.empty_cache()
     # (the clock is polled through rocm-smi child processes; under a profiler, whose preloaded library has
     # initialised the GPU in this process, such children may not be started, and --plain is the profiler mode)
-    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=not args.plain, split=not args.fp32_mfma,
-                  clocks=not args.plain, adaptive=args.window_control, act_terms=args.act_terms,
+    # The timed region carries events around the kernels the roofline object may be about (the exact GEMMs of the
+    # verify call; the block GEMM of the network); a second, shorter pass with events around every kernel gives the
+    # per-kernel table and the figures of the other kernels (all_kernel_events).
+    kind = W.CONFIGS[args.workload]["kind"]
+    cand = ["GMM_LOGITS/verify", "GMM_COMBINE/verify", "GMM_ROWWISE/verify"] if kind == "gmm" else ["MLP_GEMM_BLK/verify"]
+    common = dict(split=not args.fp32_mfma, adaptive=args.window_control, act_terms=args.act_terms,
                   screen=0 if args.no_screen else None)
+    res = run_gpu(args.workload, args.steps, args.warmup, args.seed, profile=False if args.plain else cand,
+                  clocks=not args.plain, **common)
     if not res["finite"]:
         print("bench.py: non-finite samples", file=sys.stderr)
         sys.exit(4)
@@ -472,9 +485,15 @@ def main():
             rf0 = line["roofline"]
             rf0["peak_at_measured_clock"] = rf0["peak"] * res["sclk_mhz"]["mean"] / 2400.0
             rf0["frac_at_measured_clock"] = rf0["achieved"] / rf0["peak_at_measured_clock"]
-        line["hbm_kernels"] = hbm_kernels(res)
+        rall = res      # (--others 0, the mode of the profiler runs: no second pass, the table has the GEMMs only)
+        if args.others:
+            rall = run_gpu(args.workload, max(1, min(args.steps, 5)), 1, args.seed, profile=True, **common)
+            line["all_kernel_events"] = dict(steps_per_s=rall["steps_per_s"], ms_per_sample=rall["ms_per_sample"],
+                                             samples=max(1, min(args.steps, 5)), path=rall["path"],
+                                             note="the pass behind `kernels`, `hbm_kernels` and `logit_screen`")
+        line["hbm_kernels"] = hbm_kernels(rall)
         if cfg["kind"] == "gmm" and res["split"]:
-            line["logit_screen"] = logit_screen(res)
+            line["logit_screen"] = logit_screen(rall)
             # the other exact GEMM of the verify call, by the same accounting
             other = [n for n in ("GMM_LOGITS/verify", "GMM_COMBINE/verify")
                      if n in res["kernels"] and n != line["roofline"]["kernel"]]
@@ -483,7 +502,7 @@ def main():
                     if kk in ("achieved", "peak", "frac", "avg_launch_us", "launches", "share_of_wall", "traffic",
                               "executed_flops_per_launch", "executed_share_of_dense")} for n in other}
         line["kernels"] = {k: {"launches": v["launches"], "avg_us": round(v["avg_us"], 2),
-                               "total_ms": round(v["total_ms"], 3)} for k, v in res["kernels"].items()}
+                               "total_ms": round(v["total_ms"], 3)} for k, v in rall["kernels"].items()}
     if not args.plain and args.others:
         # (skipped with --others 0, so that a profiler run of this script sees the sampling kernels only)
         # what the matrix pipes of this chip sustain on random operands with no memory traffic at all (the chip is
@@ -502,21 +521,20 @@ def main():
     # an extension of Alg. 1, exact in law; the headline `value` above keeps the configured fixed L).
     # (Skipped with --others 0, so that a profiler run of this script sees the fixed-L launches only.)
     if args.others and not args.plain:
-        # the same sample as the library runs it in production: no per-kernel events, one captured graph per round
+        # the same sample as the library runs it in production: no events, one captured graph per round
         # (or the chain-resident kernel); `value` above is the event-timed pass that the roofline figures come from
-        rq = run_gpu(args.workload, max(1, min(args.steps, 5)), 1, args.seed, profile=False, adaptive=args.window_control,
-                     split=not args.fp32_mfma, act_terms=args.act_terms, screen=0 if args.no_screen else None)
+        rq = run_gpu(args.workload, max(1, min(args.steps, 5)), 1, args.seed, profile=False, **common)
         line["without_kernel_events"] = dict(steps_per_s=rq["steps_per_s"], ms_per_sample=rq["ms_per_sample"], path=rq["path"])
     if args.others and res["split"] and res["screen_mode"]:
         # the same sample with every tile of logits computed (asd_use_logit_screen off)
-        rn = run_gpu(args.workload, 1, 1, args.seed, profile=True, screen=0)
+        rn = run_gpu(args.workload, 1, 1, args.seed, profile=cand, screen=0)
         rfn = roofline(rn, args.workload)
         line["unscreened"] = dict(steps_per_s=rn["steps_per_s"], ms_per_sample=rn["ms_per_sample"],
                                   roofline_kernel=rfn["kernel"], achieved=rfn["achieved"], frac=rfn["frac"],
                                   avg_launch_us=rfn["avg_launch_us"], share_of_wall=rfn["share_of_wall"])
     if args.others and res["split"]:
         # the same sample with the verify GEMMs on the fp32 matrix pipe (asd_use_split_gemm off)
-        rp = run_gpu(args.workload, 1, 1, args.seed, profile=True, split=False, clocks=True)
+        rp = run_gpu(args.workload, 1, 1, args.seed, profile=cand, split=False, clocks=True)
         rfp = roofline(rp, args.workload)
         line["fp32_mfma_path"] = dict(steps_per_s=rp["steps_per_s"], ms_per_sample=rp["ms_per_sample"],
                                       roofline_kernel=rfp["kernel"], achieved=rfp["achieved"], peak=rfp["peak"],

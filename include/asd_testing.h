@@ -100,6 +100,12 @@ typedef enum {
   ASD_PROF_KINDS = 16
 } asd_prof_kernel;
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);
+/* Which scopes are timed while timing is enabled: bit (kernel + 16 * call) of `slots` (all by default).  An event
+ * on the stream ends the overlap of the kernels on either side of it and costs a few microseconds itself -- at two
+ * thousand scopes per sample of the largest workload, a tenth of the sample -- so a caller that wants the durations
+ * of one kernel selects it alone.  The counters of rows and of executed work run either way.  Takes effect with the
+ * next launch and lasts until changed. */
+ASD_API asd_status asd_profile_select(asd_ctx* ctx, uint32_t slots);
 ASD_API asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms);
 ASD_API asd_status asd_profile_rows(asd_ctx* ctx, int64_t* draft_rows, int64_t* verify_rows);
 /* What the accept kernel touched since then: x0hat rows it read for the accept test (it examines a window eight

@@ -83,6 +83,7 @@ def lib():
             "asd_split_gemm_active": (i32, [vp]),
             "asd_denoise": (i32, [vp, vp, vp, i32, vp, vp]),
             "asd_profile_enable": (i32, [vp, i32]),
+            "asd_profile_select": (i32, [vp, C.c_uint32]),
             "asd_profile_read": (i32, [vp, i32, i32, vp, vp]),
             "asd_profile_rows": (i32, [vp, vp, vp]),
             "asd_profile_accept_rows": (i32, [vp, vp, vp]),
@@ -315,6 +316,17 @@ class Ctx:
     def profile_enable(self, on=True):
         """on: False / True (the denoisers' kernels, draft, accept) / 2 (also whole model calls and row planning)."""
         _check(lib().asd_profile_enable(self.h, int(on)))
+
+    def profile_select(self, slots=None):
+        """slots: the scopes timed while profiling is on, as "KIND/draft" or "KIND/verify" with KIND from PROF
+        (None: all)."""
+        mask = 0xFFFFFFFF
+        if slots is not None:
+            mask = 0
+            for s in slots:
+                kind, call = s.split("/")
+                mask |= 1 << (PROF[kind] + 16 * {"draft": 0, "verify": 1}[call])
+        _check(lib().asd_profile_select(self.h, mask))
 
     def profile_read(self, kernel, call=0):
         n, ms = C.c_int64(0), C.c_double(0.0)

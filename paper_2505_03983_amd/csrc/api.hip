@@ -613,6 +613,12 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   return ASD_OK;
 }
 
+asd_status asd_profile_select(asd_ctx* ctx, uint32_t slots) {
+  ASD_TRY(check_ctx(ctx));
+  ctx->prof.slots = slots;
+  return ASD_OK;
+}
+
 asd_status asd_profile_read(asd_ctx* ctx, int32_t kernel, int32_t call, int64_t* launches, double* total_ms) {
   ASD_TRY(check_ctx(ctx));
   if (kernel < 0 || kernel >= ASD_PROF_KINDS || call < 0 || call > 1) return fail(ASD_EINVAL, "bad profile slot");

@@ -78,6 +78,7 @@ struct Profiler {
   };
   bool on = false;
   bool outer = false;   // also time the scopes that enclose other scopes (a whole model call) and the row planning
+  uint32_t slots = ~0u; // bit (kind + 16 call): that slot's scopes are timed (asd_profile_select)
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
   size_t used = 0;
@@ -166,6 +167,9 @@ namespace asd {
 
 constexpr int kLiveRing = 8;
 
+// Whether kernels get the device-side counters of rows and executed work (asd_profile_rows, asd_profile_model_work).
+inline bool prof_counting(const asd_ctx* ctx) { return ctx->prof.on; }
+
 // Times everything launched on `st` during its lifetime under `slot`.
 struct ProfScope {
   asd_ctx* ctx;
@@ -175,6 +179,7 @@ struct ProfScope {
   ProfScope(asd_ctx* c, int kernel, int call, hipStream_t s) : ctx(c), st(s), slot(kernel + 16 * call) {
     if (!ctx->prof.on) return;
     if ((kernel == ASD_PROF_MODEL || kernel == ASD_PROF_PLAN) && !ctx->prof.outer) return;
+    if (!((ctx->prof.slots >> slot) & 1u)) return;
     e0 = ctx->prof.take();
     e1 = ctx->prof.take();
     if (e0 && e1) (void)hipEventRecord(e0, st);

@@ -1608,7 +1608,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, d, C, rows.in_base,
                        rows.in_off, rows.out_base, rows.out_off, rows.tau, g->coef_tau, rows.chain, g->chain_comp,
                        g->means22, g->musq, g->log_w, g->cert_amin, g->cert_glob, g->cert_globw, g->onehot, g->onehot_tile,
-                       g->cert_tile, g->cert_cnt, (ctx->prof.on && rows.call == 1) ? g->work_counts : nullptr);
+                       g->cert_tile, g->cert_cnt, (prof_counting(ctx) && rows.call == 1) ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.skip_tile = cert_tile;
   }
@@ -1628,7 +1628,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
                        sizeof(int) * 2 * ntn, st, rows.n_dev, n, g->nps, ntn, GmmTileSplit::BN / kGroup, g->imax,
                        g->xs, g->means_grp, g->coef_tau, rows.tau, on, g->tile_list, g->tile_count, g->list_cap,
                        g->pmax, np, GmmTileSplit::WGN, g->split_draft_ok ? 1 : 0, g->logits, (int64_t)C, cert_tile,
-                       big ? 1 : 0, ctx->prof.on ? g->work_counts : nullptr);
+                       big ? 1 : 0, prof_counting(ctx) ? g->work_counts : nullptr);
     ASD_HIP(hipGetLastError());
     op1.tile_list = g->tile_list;
     op1.tile_count = g->tile_count;
@@ -1673,7 +1673,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   // columns behind one partial row maximum: the first GEMM's wavefront sub-tile width (the last group may be short)
   const int gcols = split ? GmmTileSplit::WN : (rows.call ? GmmTile::WN : GmmTileSkinny::WN);
   CombineOp op2{g->pmax, np, gcols, nullptr, nullptr, nullptr, rows.in_base, rows.in_off, rows.out_base, rows.out_off, g->coef_tau,
-                rows.tau, (ctx->prof.on && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
+                rows.tau, (prof_counting(ctx) && rows.call == 1 && split) ? g->work_counts + 2 : nullptr, {}, {}};
   // between the GEMMs: row maxima and live groups once per row tile; one-hot rows (the draft call's rows -- one per
   // chain -- are one-hot too once the posteriors have collapsed)
   if (split) {
@@ -1684,7 +1684,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
       hipLaunchKernelGGL(gmm_rowmax_kernel, dim3((unsigned)ceil_div(n, CombineOp::kRowmaxTile)), dim3(256),
                          sizeof(int) * (np + 1), st, rows.n_dev, n, np, g->pmax, g->rmax, g->glive, g->logits, (int64_t)C,
                          gcols, onehot ? g->onehot : (int32_t*)nullptr, onehot ? g->onehot_tile : (uint8_t*)nullptr,
-                         cert_tile, ctx->prof.on ? g->work_counts : nullptr);
+                         cert_tile, prof_counting(ctx) ? g->work_counts : nullptr);
     } else {
       hipLaunchKernelGGL(gmm_rowmax_rows_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, rows.n_dev, n, np,
                          g->pmax, g->rmax, g->logits, (int64_t)C, onehot ? g->onehot : (int32_t*)nullptr, rows.chain,

@@ -55,7 +55,7 @@ static PlanOut plan_out(asd_ctx* ctx, int32_t* ring) {
   p.row_chain = ctx->row_chain;
   p.n_rows = ctx->n_rows_dev;
   p.tau = ctx->tau;
-  p.row_counts = ctx->prof.on ? ctx->row_counts : nullptr;
+  p.row_counts = prof_counting(ctx) ? ctx->row_counts : nullptr;
   p.ring = ring;
   return p;
 }
@@ -192,7 +192,7 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
   ProfScope ps(ctx, ASD_PROF_PLAN, 0, st);
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 0, ring,
-                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win,
+                     prof_counting(ctx) ? ctx->row_counts : nullptr, ctx->cur_win,
                      ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L, 0);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -205,7 +205,7 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   const unsigned wgs = (unsigned)std::min<int64_t>(64, std::max<int64_t>(1, ctx->n_rows_max / 1024));
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 1, (int32_t*)nullptr,
-                     ctx->prof.on ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
+                     prof_counting(ctx) ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
                      ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0), ctx->cur_win ? 0 : model_row_block(ctx));
   ASD_HIP(hipGetLastError());
   return ASD_OK;
@@ -570,7 +570,7 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
   const PlanOut plan = plan_out(ctx, nullptr);
-  int64_t* prof_counts = ctx->prof.on ? ctx->row_counts : nullptr;
+  int64_t* prof_counts = prof_counting(ctx) ? ctx->row_counts : nullptr;
   int32_t* carry = ctx->reuse_now ? ctx->carry : nullptr;
   if (plan.in_off)
     hipLaunchKernelGGL(accept_kernel<true>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,

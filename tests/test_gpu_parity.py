@@ -585,6 +585,34 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.close()
 
 
+def test_profile_select_times_the_chosen_slots_only():
+    """asd_profile_select: only the selected scopes take events, the work counters run regardless, and the sample
+    is the same with any selection."""
+    cfg = W.CONFIGS[2]
+    _, p, _ = oracle_setup(cfg)
+    ctx = runtime.open_ctx(cfg, p, seed=5)
+    ctx.use_resident(False)
+    t0, t1 = runtime.alloc_traj(ctx), runtime.alloc_traj(ctx)
+    P = binding.PROF
+    ctx.profile_enable(True)
+    ctx.sample(t0)
+    every = {(k, c): ctx.profile_read(P[k], c)[0] for k in ("DRAFT", "ACCEPT", "GMM_ROWWISE") for c in (0, 1)}
+    rows_all = ctx.profile_rows()
+    ctx.profile_select(["GMM_ROWWISE/verify"])
+    ctx.profile_enable(True)
+    ctx.sample(t1)
+    some = {(k, c): ctx.profile_read(P[k], c)[0] for k in ("DRAFT", "ACCEPT", "GMM_ROWWISE") for c in (0, 1)}
+    rows_some = ctx.profile_rows()
+    ctx.profile_enable(False)
+    ctx.profile_select(None)
+    assert every[("DRAFT", 0)] > 0 and every[("ACCEPT", 0)] > 0 and every[("GMM_ROWWISE", 0)] > 0
+    assert some[("GMM_ROWWISE", 1)] == every[("GMM_ROWWISE", 1)] > 0
+    assert all(n == 0 for key, n in some.items() if key != ("GMM_ROWWISE", 1))
+    assert rows_some == rows_all and rows_all[1] > 0
+    assert torch.equal(t0, t1)
+    ctx.close()
+
+
 def test_model_call_reuse_matches_the_oracle():
     """asd_use_call_reuse: the verify call also evaluates yhat_b, a fully accepted window hands that value to the
     next round and the chain skips the next draft call.  Whole samples against the oracle run with the same rule,
