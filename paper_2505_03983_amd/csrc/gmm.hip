@@ -735,7 +735,11 @@ __global__ __launch_bounds__(CombineOp::kRowmaxTile) void gmm_onehot_tiles_kerne
   if (threadIdx.x == 0) onehot_tile[blockIdx.x] = bad ? 0 : 1;
 }
 
-// The rows of the one-hot tiles, in closed form (see gmm_rowmax_kernel): one workgroup per row.
+// The rows of the one-hot tiles, in closed form (see gmm_rowmax_kernel): kOnehotRows rows per workgroup, four of them
+// in flight at a time.  (A workgroup per row was 65 k workgroups at cfg 5's verify call: 14 us of dispatch even when
+// every one of them leaves at once, which is the common case.)
+constexpr int kOnehotRows = 8;
+static_assert(CombineOp::kRowmaxTile % kOnehotRows == 0, "a workgroup's rows lie in one row tile");
 __global__ __launch_bounds__(256) void gmm_onehot_kernel(const int* __restrict__ n_dev, int n_max, int d,
                                                          const int32_t* __restrict__ onehot,
                                                          const uint8_t* __restrict__ onehot_tile,
@@ -748,19 +752,44 @@ __global__ __launch_bounds__(256) void gmm_onehot_kernel(const int* __restrict__
                                                          const int32_t* __restrict__ tau,
                                                          const uint8_t* __restrict__ cert_tile) {
   // cert_tile (or NULL): one-hot row tiles whose rows gmm_certify_kernel has written already
-  const int m = blockIdx.x;
-  if (m >= min(*n_dev, n_max) || !onehot_tile[m / CombineOp::kRowmaxTile]) return;
-  if (cert_tile && cert_tile[m / CombineOp::kRowmaxTile]) return;
-  const float4 cf = coef_tau[tau[m]];
-  const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
-  const float4* mu = reinterpret_cast<const float4*>(means + (int64_t)onehot[m] * d);
-  float4* o = reinterpret_cast<float4*>(out_base + out_off[m]);
-  // what the second GEMM's epilogue computes with acc = mu_b (+0.0: the accumulator never holds a negative zero)
-  // and scale = c_m' / 1.0
-  for (int j = threadIdx.x; j < d / 4; j += 256) {
-    const float4 xv = x[j], mv = mu[j];
-    o[j] = make_float4(fmaf(cf.z, xv.x, __fmul_rn(cf.w, mv.x + 0.f)), fmaf(cf.z, xv.y, __fmul_rn(cf.w, mv.y + 0.f)),
-                       fmaf(cf.z, xv.z, __fmul_rn(cf.w, mv.z + 0.f)), fmaf(cf.z, xv.w, __fmul_rn(cf.w, mv.w + 0.f)));
+  const int n = min(*n_dev, n_max), m0 = blockIdx.x * kOnehotRows;
+  if (m0 >= n) return;
+  const int tile = m0 / CombineOp::kRowmaxTile;
+  if (!onehot_tile[tile]) return;
+  if (cert_tile && cert_tile[tile]) return;
+  constexpr int U = 4;
+  for (int r0 = 0; r0 < kOnehotRows && m0 + r0 < n; r0 += U) {
+    float4 cf[U];
+    const float4* x[U];
+    const float4* mu[U];
+    float4* o[U];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int m = min(m0 + r0 + u, n - 1);
+      live[u] = m0 + r0 + u < n;
+      cf[u] = coef_tau[tau[m]];
+      x[u] = reinterpret_cast<const float4*>(in_base + in_off[m]);
+      mu[u] = reinterpret_cast<const float4*>(means + (int64_t)onehot[m] * d);
+      o[u] = reinterpret_cast<float4*>(out_base + out_off[m]);
+    }
+    for (int j = threadIdx.x; j < d / 4; j += 256) {
+      float4 xv[U], mv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        xv[u] = x[u][j];
+        mv[u] = mu[u][j];
+      }
+      // what the second GEMM's epilogue computes with acc = mu_b (+0.0: the accumulator never holds a negative zero)
+      // and scale = c_m' / 1.0
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (live[u])
+          o[u][j] = make_float4(fmaf(cf[u].z, xv[u].x, __fmul_rn(cf[u].w, mv[u].x + 0.f)),
+                                fmaf(cf[u].z, xv[u].y, __fmul_rn(cf[u].w, mv[u].y + 0.f)),
+                                fmaf(cf[u].z, xv[u].z, __fmul_rn(cf[u].w, mv[u].z + 0.f)),
+                                fmaf(cf[u].z, xv[u].w, __fmul_rn(cf[u].w, mv[u].w + 0.f)));
+    }
   }
 }
 
@@ -1695,7 +1724,7 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
     }
     ASD_HIP(hipGetLastError());
     if (onehot) {
-      hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)n), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
+      hipLaunchKernelGGL(gmm_onehot_kernel, dim3((unsigned)ceil_div(n, kOnehotRows)), dim3(256), 0, st, rows.n_dev, n, d, g->onehot,
                          g->onehot_tile, two ? g->means22 : g->means, rows.in_base, rows.in_off, rows.out_base,
                          rows.out_off, g->coef_tau, rows.tau, cert_tile);
       ASD_HIP(hipGetLastError());
