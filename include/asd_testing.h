@@ -43,12 +43,12 @@ ASD_API int32_t asd_logit_screen_active(const asd_ctx* ctx);
 
 /* One-hot certificate of the screened verify call (split-operand mixture denoiser).  Before any matrix work, a row
  * tile (128 rows) whose rows all lie so close to the mean their chain's last draft-call row was found one-hot on
- * that the distances between the means alone prove every other softmax weight exactly 0.0f (Cauchy-Schwarz on
- * x - s mu_b, two C x C tables of the means' geometry built at asd_init) is written in closed form,
+ * that the distance from that mean to its nearest neighbour alone proves every other softmax weight exactly 0.0f
+ * (Cauchy-Schwarz on x - s mu_b; one float per component, made at asd_init) is written in closed form,
  * c_x' x + c_m' mu_b, and skips the screening pass and both GEMMs.  Results are identical bit for bit: it certifies
  * what the exact path would have found.  Works inside asd_sample and the stage calls (the row plan names every row's
- * chain), not in asd_denoise.  Default: on; needs the screening pass (asd_logit_screen_active != 0), at most 64
- * groups of 64 components (C <= 4096) and 8 C^2 bytes <= 1 GiB; otherwise it stays off.
+ * chain), not in asd_denoise.  Default: on; needs the screening pass (asd_logit_screen_active != 0) and at most 64
+ * groups of 64 components (C <= 4096); otherwise it stays off.
  * asd_onehot_certificate_active: 1 if the verify calls of this context run it. */
 ASD_API asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on);
 ASD_API int32_t asd_onehot_certificate_active(const asd_ctx* ctx);
@@ -61,6 +61,22 @@ ASD_API int32_t asd_onehot_certificate_active(const asd_ctx* ctx);
  * timing comparisons).  Default: on.  asd_tall_tiles_active: 1 if this context's dense verify calls take them. */
 ASD_API asd_status asd_use_tall_tiles(asd_ctx* ctx, int32_t on);
 ASD_API int32_t asd_tall_tiles_active(const asd_ctx* ctx);
+
+/* Early accept (inside asd_sample and asd_sample_noalloc; mixture denoiser with the one-hot certificate on fp16
+ * terms, d a multiple of 4 and at most 1024, more than 16384 model rows per call, no model-call reuse).  A certified
+ * row's model value is c_x' x + c_m' mu_b, which the accept stage can form itself; so after the draft stage a kernel
+ * takes every chain it can through its accept stage on values formed that way -- slot by slot, certifying each row
+ * it examines, stopping at the first rejection like the accept stage proper -- and only the chains with a slot it
+ * cannot certify go through the verify call and the accept kernel.  A chain's round is the same either way, bit for
+ * bit: the same sums in the same order on the same values.  Late in a sample, when every row is certifiable, a round
+ * then reads a third of the window's rows once instead of reading all of them, writing their model values and
+ * reading a third of those back.  Default: on.  asd_early_accept_active: 1 if asd_sample of this context does it.
+ * asd_profile_early_accept (while asd_profile_enable is on): model rows the kernel formed itself and chain-rounds it
+ * committed since then (asd_profile_rows counts the windows of those chain-rounds among the verify rows all the
+ * same, so that figure stays the number of drafted rows). */
+ASD_API asd_status asd_use_early_accept(asd_ctx* ctx, int32_t on);
+ASD_API int32_t asd_early_accept_active(const asd_ctx* ctx);
+ASD_API asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds);
 
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */
@@ -97,6 +113,7 @@ typedef enum {
   ASD_PROF_ACCEPT = 11,      /* fused accept / scan / resample kernel         */
   ASD_PROF_GMM_SCREEN = 12,  /* GMM screening pass of the verify call's logits */
   ASD_PROF_GMM_CERT = 13,    /* GMM one-hot certificate (rows it passes are written by it) */
+  ASD_PROF_ACCEPT_EARLY = 14, /* accept stage of certified chains, ahead of the verify call (asd_use_early_accept) */
   ASD_PROF_KINDS = 16
 } asd_prof_kernel;
 ASD_API asd_status asd_profile_enable(asd_ctx* ctx, int32_t on);

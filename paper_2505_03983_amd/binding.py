@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 ASD_OK, ASD_EINVAL, ASD_ENOMEM, ASD_EDEVICE, ASD_ESTATE, ASD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 ASD_DEN_GMM, ASD_DEN_MLP = 1, 2
 PROF = dict(MODEL=0, PLAN=1, GMM_ROWWISE=2, GMM_LOGITS=3, GMM_SOFTMAX=4, GMM_COMBINE=5, MLP_PACK=6, MLP_GEMM_IN=7,
-            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11, GMM_SCREEN=12, GMM_CERT=13)
+            MLP_GEMM_BLK=8, MLP_GEMM_OUT=9, DRAFT=10, ACCEPT=11, GMM_SCREEN=12, GMM_CERT=13, ACCEPT_EARLY=14)
 
 
 class AsdError(RuntimeError):
@@ -75,6 +75,9 @@ def lib():
             "asd_profile_model_work": (i32, [vp, vp, vp, vp, vp, vp, vp, vp]),
             "asd_use_tall_tiles": (i32, [vp, i32]),
             "asd_tall_tiles_active": (i32, [vp]),
+            "asd_use_early_accept": (i32, [vp, i32]),
+            "asd_early_accept_active": (i32, [vp]),
+            "asd_profile_early_accept": (i32, [vp, vp, vp]),
             "asd_use_onehot_certificate": (i32, [vp, i32]),
             "asd_onehot_certificate_active": (i32, [vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
@@ -266,6 +269,18 @@ class Ctx:
 
     def tall_tiles_active(self):
         return bool(lib().asd_tall_tiles_active(self.h))
+
+    def use_early_accept(self, on=True):
+        _check(lib().asd_use_early_accept(self.h, int(bool(on))))
+
+    def early_accept_active(self):
+        return bool(lib().asd_early_accept_active(self.h))
+
+    def profile_early_accept(self):
+        """(model rows the early accept kernel formed itself, chain-rounds it committed) since profile_enable."""
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(lib().asd_profile_early_accept(self.h, C.addressof(a), C.addressof(b)))
+        return a.value, b.value
 
     def use_onehot_certificate(self, on=True):
         _check(lib().asd_use_onehot_certificate(self.h, int(bool(on))))

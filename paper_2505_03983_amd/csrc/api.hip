@@ -148,8 +148,10 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->carry, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMemset(ctx->carry, 0, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
-  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 4));
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
+  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 6));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 6));
+  ASD_HIP(hipMalloc(&ctx->pending, sizeof(int32_t) * (size_t)ctx->B));
+  ASD_HIP(hipMemset(ctx->pending, 0, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
   ASD_HIP(hipMalloc(&ctx->win, sizeof(int32_t) * 2 * (size_t)ctx->B));
@@ -189,6 +191,7 @@ static void teardown(asd_ctx* ctx) {
   if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->own_stream);
   (void)hipFree(ctx->row_counts);
+  (void)hipFree(ctx->pending);
   ctx->prof.destroy();
   if (ctx->live_host) (void)hipHostFree(ctx->live_host);
   if (ctx->live_ev) {
@@ -321,12 +324,15 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, floa
   if (!ctx->fold_plans) ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
   ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
   ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live));
+  // chains the denoiser can certify have their accept stage now; the verify call is planned for the others only
+  const int32_t* pending = ctx->early_now ? ctx->pending : nullptr;
+  if (pending) ASD_TRY(launch_accept_early(ctx, traj, ctx->a, rounds, ctx->live, st));
   if (ctx->L > 1 || ctx->reuse_now) {
-    if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st));
+    if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st, pending));
     ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
   }
   ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, ctx->L + (ctx->reuse_now ? 1 : 0), nullptr, nullptr, rounds, ctx->live,
-                        st));
+                        st, pending));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
   ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * kLiveRing, hipMemcpyDeviceToHost, st));
@@ -338,7 +344,7 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, floa
 // advanced on the device, the seed is read from device memory.
 static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
   if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st &&
-      ctx->g_win == ctx->cur_win && ctx->g_reuse == ctx->reuse_now)
+      ctx->g_win == ctx->cur_win && ctx->g_reuse == ctx->reuse_now && ctx->g_early == ctx->early_now)
     return ASD_OK;
   hipGraph_t graph = nullptr;
   ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
@@ -361,7 +367,14 @@ static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds,
   ctx->g_stream = st;
   ctx->g_win = ctx->cur_win;
   ctx->g_reuse = ctx->reuse_now;
+  ctx->g_early = ctx->early_now;
   return ASD_OK;
+}
+
+// Whether asd_sample's rounds may take certified chains through their accept stage ahead of the verify call.
+static bool early_accept_possible(const asd_ctx* ctx) {
+  asd::OneHotCert oc;
+  return ctx->early && ctx->pending && ctx->L > 1 && ctx->d % 4 == 0 && ctx->d / 4 <= 256 && model_onehot_cert(ctx, &oc);
 }
 
 // The while-loop of Alg. 1 in lock step over the chains, on the round kernels.  x0hat: where the verify call
@@ -378,11 +391,13 @@ static asd_status sample_rounds(asd_ctx* ctx, const float* y0, float* traj, int3
       // limits (cfg 5: +13 and +18 us on them against 27 us of planning kernels).
       c->fold_plans = c->n_rows_max <= 16384;
       c->reuse_now = c->reuse;
+      c->early_now = early_accept_possible(c) && !c->fold_plans && !c->reuse_now;
     }
     ~WinScope() {
       c->cur_win = nullptr;
       c->fold_plans = false;
       c->reuse_now = false;
+      c->early_now = false;
     }
   } win_scope(ctx);
   // The live-chain count of a round is read back `lag` rounds later, so the host never waits for the
@@ -608,8 +623,29 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ctx->prof.reset();
   ctx->prof.on = on != 0;
   ctx->prof.outer = on >= 2;
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 4));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 6));
   if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 8 * sizeof(unsigned long long)));
+  return ASD_OK;
+}
+
+asd_status asd_use_early_accept(asd_ctx* ctx, int32_t on) {
+  ASD_TRY(check_ctx(ctx));
+  ctx->early = on != 0;
+  return ASD_OK;
+}
+
+int32_t asd_early_accept_active(const asd_ctx* ctx) {
+  if (!ctx) return 0;
+  // (as asd_sample decides it: plans folded into the round kernels and model-call reuse exclude it)
+  return (early_accept_possible(ctx) && ctx->n_rows_max > 16384 && !ctx->reuse) ? 1 : 0;
+}
+
+asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds) {
+  ASD_TRY(check_ctx(ctx));
+  int64_t h[6] = {0, 0, 0, 0, 0, 0};
+  ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
+  if (model_rows) *model_rows = h[4];
+  if (chain_rounds) *chain_rounds = h[5];
   return ASD_OK;
 }
 

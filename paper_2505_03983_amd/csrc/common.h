@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "../../include/asd_testing.h"
+#include "gmm_cert.h"
 #include "rng.h"
 
 namespace asd {
@@ -153,11 +154,18 @@ struct asd_ctx {
   bool reuse = false;          // the switch
   bool reuse_now = false;      // set while asd_sample's rounds run with the switch on (the stage calls never reuse)
   int32_t* carry = nullptr;    // DEV [B]
+  // Early accept (asd_use_early_accept): chains whose rows the denoiser can certify one-hot have their accept stage
+  // before the verify call, on model values formed in the accept kernel; the verify call sees the other chains only.
+  bool early = true;           // the switch
+  bool early_now = false;      // set while asd_sample's rounds run with it
+  bool g_early = false;        // early_now the round graph was captured with
+  int32_t* pending = nullptr;  // DEV [B]: 1 = the chain still needs this round's verify call and accept kernel
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
-  int64_t* row_counts = nullptr;  // DEV [4], summed over launches while profiling: live rows of the draft call, of the verify
-                                  // call, x0hat rows the accept kernel read for its tests, rows it resampled
+  int64_t* row_counts = nullptr;  // DEV [6], summed over launches while profiling: live rows of the draft call, of the verify
+                                  // call, x0hat rows the accept kernel read for its tests, rows it resampled; model rows
+                                  // the early accept kernel formed itself, chain-rounds it committed
   double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
   asd::GmmState* gmm = nullptr;
   asd::MlpState* mlp = nullptr;
@@ -205,6 +213,12 @@ asd_status mlp_create(asd_ctx* ctx, const asd_denoiser& den);
 void mlp_destroy(asd_ctx* ctx);
 asd_status mlp_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st);
 
+// What a kernel outside the mixture denoiser needs to certify rows one-hot and form their model values (gmm_cert.h);
+// false when the denoiser's own verify call would not do the same, bit for bit.
+bool gmm_onehot_cert(const asd_ctx* ctx, asd::OneHotCert* out);
+inline bool model_onehot_cert(const asd_ctx* ctx, asd::OneHotCert* out) {
+  return ctx->kind == ASD_DEN_GMM && gmm_onehot_cert(ctx, out);
+}
 // Rows per chain block the denoiser would like the verify call's plan laid out in (0: as they come): see gmm.hip.
 int gmm_row_block(const asd_ctx* ctx);
 inline int model_row_block(const asd_ctx* ctx) { return ctx->kind == ASD_DEN_GMM ? gmm_row_block(ctx) : 0; }
@@ -218,12 +232,15 @@ inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) 
 // round kernels (round.hip)
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds, hipStream_t st);
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me = nullptr);
-asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st);
+asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st, const int32_t* pending = nullptr);
 asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring = nullptr);
 asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st);
 // x0_slots: slots per chain of x0hat (L for the caller's array of the stage calls, L + 1 with model-call reuse)
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int x0_slots, int32_t* accepted,
-                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st);
+                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st, const int32_t* pending = nullptr);
+// The accept stage of the chains the denoiser's one-hot certificate covers, ahead of the verify call; leaves
+// ctx->pending[c] = 1 for every chain that still needs the verify call and launch_accept (see accept_early_kernel).
+asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st);
 asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st);
 asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st);
 asd_status launch_debug_philox(Key key, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,

@@ -41,6 +41,7 @@
 #include "gemm_split3.h"
 #include "gemm_split2_big.h"
 #include "gmm_state.h"
+#include "gmm_cert.h"
 
 namespace asd {
 
@@ -433,6 +434,7 @@ struct CombineOp {
   // than kZeroGap below the row maximum: load_a then gives 2^(l - max) = 0.0f for every element of the group
   // (2^-150 is below the smallest fp32 subnormal), so those products are exact zeros.
   static constexpr float kZeroGap = 150.0f;
+  static_assert(kZeroGap == kCertZeroGap, "the certificate proves weights zero by this gap");
   // NULL, or what gmm_rowmax_kernel made of pmax once for all the column tiles of a row tile: the row maxima [rows]
   // and the live flag of every column group [row tiles of kRowmaxTile rows][np]
   const float* rmax_pre = nullptr;
@@ -893,17 +895,9 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
     float4 cf = make_float4(0.f, 0.f, 0.f, 0.f);
     float am = 0.f;
     if (b >= 0) {
-      // A look before the row is read.  Under the mixture a row at this time index has s = 2 gamma / kappa and
-      // |e|^2 = d / (kappa / s) to within a few percent (the noise of d coordinates); if the test would fail even with
-      // four fifths of that |e| and nothing of its smaller terms, the row is not worth its 4 d bytes.  (Only a
-      // guess that saves work: a row it turns away takes the exact path.)
       cf = coef_tau[tau[m]];
       am = a_min[b];
-      if (cf.x > 0.f && cf.y > 0.f) {
-        const float s0 = 2.f * cf.y / cf.x, e0 = 0.8f * sqrtf((float)d * s0 / cf.x);
-        const float A0 = LogitOp::kLog2e * cf.x * s0, B0 = LogitOp::kLog2e * cf.x * e0;
-        if (!(am * A0 >= B0 && am * (B0 - 0.5f * A0 * am) + CombineOp::kZeroGap < 0.f)) b = -1;
-      }
+      if (!cert_worth_reading(cf, am, d)) b = -1;
     }
     if (b >= 0) {
       const float4* x = reinterpret_cast<const float4*>(in_base + in_off[m]);
@@ -934,35 +928,13 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
         r2 += (ex * ex + ey * ey) + (ez * ez + ew * ew);
       }
       r2 = wave_sum(r2);
-      // upper bounds of the two norms (their fp32 sums are off by a few 2^-24 d of themselves at most); `means` holds
-      // the means as the second GEMM carries them, within 2^-21 max |mu| of the true ones in norm, and |e| is about
-      // the true mu_b
-      const float e_up = fmaf(fabsf(s) * glob.x, 0x1p-21f, sqrtf(r2) * (1.f + 0x1p-10f)), x_up = sqrtf(xx) * (1.f + 0x1p-10f);
-      const float c1 = LogitOp::kLog2e * cf.x, c2 = LogitOp::kLog2e * cf.y;
-      const float A = c1 * s, B = c1 * e_up, half = 0.5f * A;
-      const float f = am * (B - half * am);                 // the parabola at the nearest neighbour ...
-      const bool beyond = am * A >= B;                      // ... which must lie beyond its vertex
-      const float dq = half - c2;
-      const float qterm = dq * ((dq >= 0.f ? glob.y : glob.z) - qb);
-      const float bterm = globw.x - bias_b;
-      const float mag = (am * B + half * am * am) + fabsf(qterm) + (globw.y + fabsf(bias_b)) + c2 * glob.y;
-      const float margin = fmaf(c1 * x_up * glob.x, 0x1p-9f + 1e-5f,
-                                fmaf((c2 + fabsf(dq)) * glob.y, 0x1p-12f, fmaf(1e-5f, mag, 1.f)));
-      // (a NaN or an infinity anywhere above fails these comparisons)
-      pass = s >= 0.f && c1 >= 0.f && c2 >= 0.f && beyond && mag < 1e30f && margin < 1e30f &&
-             (f + qterm + bterm) + (CombineOp::kZeroGap + margin) < 0.f;
+      pass = cert_passes(cf, s, r2, xx, am, qb, bias_b, glob, globw);
       if (pass) {
-        // what the second GEMM's epilogue computes with acc = mu_b (+0.0: the accumulator never holds a negative
-        // zero) and scale = c_m' / 1.0
         float4* o = reinterpret_cast<float4*>(out_base + out_off[m]);
 #pragma unroll
         for (int i = 0; i < V; ++i) {
           const int j = lane + 64 * i;
-          if (j < d / 4)
-            o[j] = make_float4(fmaf(cf.z, xv[i].x, __fmul_rn(cf.w, mv[i].x + 0.f)),
-                               fmaf(cf.z, xv[i].y, __fmul_rn(cf.w, mv[i].y + 0.f)),
-                               fmaf(cf.z, xv[i].z, __fmul_rn(cf.w, mv[i].z + 0.f)),
-                               fmaf(cf.z, xv[i].w, __fmul_rn(cf.w, mv[i].w + 0.f)));
+          if (j < d / 4) o[j] = cert_value(cf, xv[i], mv[i]);
         }
         if (lane == 0) onehot[m] = b;
       }
@@ -1539,6 +1511,25 @@ asd_status gmm_create(asd_ctx* ctx, const asd_denoiser& den) {
 // rows agree that its components are irrelevant.  Rows of one chain do (its window sits on one component once the
 // posterior has collapsed); with each chain's rows starting at a multiple of 64 a tile holds two chains, not three.
 // Only when the filling cannot overflow the plan: windows of at most L - 1 rows (+ 1 with reuse) fit L = 64 m.
+bool gmm_onehot_cert(const asd_ctx* ctx, OneHotCert* out) {
+  const GmmState* g = ctx->gmm;
+  // the conditions under which the verify call certifies rows itself (gmm_eval) and carries the means as two fp16
+  // terms: only then is a certified row's value what that call would have stored
+  if (!g || !g->use_mfma || !g->use_split || !g->two_ok || !g->screen_ok || g->screen_mode == 0 || !g->sparse_combine ||
+      !g->cert_ok || !g->cert_on || !g->means22 || !g->chain_comp || !g->cert_amin)
+    return false;
+  out->chain_comp = g->chain_comp;
+  out->means = g->means22;
+  out->musq = g->musq;
+  out->log_w = g->log_w;
+  out->a_min = g->cert_amin;
+  out->coef_tau = g->coef_tau;
+  out->glob = g->cert_glob;
+  out->globw = g->cert_globw;
+  out->C = g->C;
+  return true;
+}
+
 int gmm_row_block(const asd_ctx* ctx) {
   const GmmState* g = ctx->gmm;
   const bool screening = g && g->use_split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine;

@@ -113,7 +113,9 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
                                                          int64_t* __restrict__ row_counts,
                                                          const int32_t* __restrict__ win,
                                                          const int32_t* __restrict__ carry, int extra, int slots,
-                                                         int pad) {
+                                                         int pad, const int32_t* __restrict__ pending) {
+  // pending (verify call, or NULL): only chains with pending[c] != 0 are listed -- the others have had their round
+  // already (accept_early_kernel) and their a[c] is the next round's.
   // carry (draft call): chains whose x0a was handed over by the last round are not listed.  extra (verify call):
   // 1 = also list the last proposal sample yhat_b of a window that ends before K.  slots: slots per chain of x0hat.
   // pad (verify call; 0 = none): every chain's rows start at a multiple of `pad` rows -- its block is filled up with
@@ -140,6 +142,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
       if (ac < K) {
         const int w = min(win ? win[c] : L, K - ac);
         cnt = (MODE == 0) ? ((carry && carry[c]) ? 0 : 1) : w - 1 + ((extra && ac + w < K) ? 1 : 0);
+        if (MODE == 1 && pending && !pending[c]) cnt = 0;
       }
     }
     // rows of the chain's block (a window cut short by the end of the chain is not worth filling up: the blocks
@@ -193,12 +196,12 @@ asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int
   hipLaunchKernelGGL(plan_rows_kernel<0>, dim3(1), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 0, ring,
                      prof_counting(ctx) ? ctx->row_counts : nullptr, ctx->cur_win,
-                     ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L, 0);
+                     ctx->reuse_now ? ctx->carry : (const int32_t*)nullptr, 0, ctx->L, 0, (const int32_t*)nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
 
-asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
+asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st, const int32_t* pending) {
   if (ctx->L <= 1 && !ctx->reuse_now) return ASD_OK;
   ProfScope ps(ctx, ASD_PROF_PLAN, 1, st);
   // up to 64 workgroups share the filling of a large plan (a chain per wavefront at a time, see the kernel)
@@ -206,7 +209,8 @@ asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st) {
   hipLaunchKernelGGL(plan_rows_kernel<1>, dim3(wgs), dim3(1024), 0, st, ctx->B, ctx->K, ctx->L, ctx->d, a, ctx->tau,
                      ctx->in_off, ctx->out_off, ctx->row_tau, ctx->row_chain, ctx->n_rows_dev + 1, (int32_t*)nullptr,
                      prof_counting(ctx) ? ctx->row_counts : nullptr, ctx->cur_win, (const int32_t*)nullptr,
-                     ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0), ctx->cur_win ? 0 : model_row_block(ctx));
+                     ctx->reuse_now ? 1 : 0, ctx->L + (ctx->reuse_now ? 1 : 0), ctx->cur_win ? 0 : model_row_block(ctx),
+                     pending);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -373,7 +377,9 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
                                                       int32_t* __restrict__ accepted, float* __restrict__ stats,
                                                       int32_t* __restrict__ rounds, int32_t* __restrict__ live,
                                                       int32_t* __restrict__ win, PlanOut plan,
-                                                      int64_t* __restrict__ prof_counts) {
+                                                      int64_t* __restrict__ prof_counts,
+                                                      const int32_t* __restrict__ pending) {
+  // pending (or NULL): chains with pending[c] == 0 have had their round already (accept_early_kernel)
   __shared__ float s_part[kAcceptChunk][16][2];  // per slot of the chunk, per wavefront: partial <D,xi>, |D|^2
   __shared__ float s_rej[2];                     // <D,xi>, |D|^2 of the first rejected slot
   __shared__ int s_first;                        // index inside the chunk of the first rejection, 64 if none
@@ -393,6 +399,7 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
     if (tid == 0 && accepted) accepted[c] = -1;
     return;
   }
+  if (pending && !pending[c]) return;
   const Key key = *key_p;
   const int w = min(win ? win[c] : L, K - ac);
   const int nblk = (d + 3) >> 2;
@@ -564,8 +571,245 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
   }
 }
 
+// ----------------------------------------------------------------------------
+// The accept stage ahead of the verify call, for chains whose rows the mixture denoiser's one-hot certificate
+// covers (gmm_cert.h).  A certified row's model value is c_x' x + c_m' mu_b -- the same bits the verify call would
+// store for it -- so this kernel forms the values of the slots it examines itself, from the drafted rows, and takes
+// the chain through its round: the same sums, in the same order, as accept_kernel on stored values, hence the same
+// decisions and the same resampled row.  It stops at the first rejection like accept_kernel; rows behind it are
+// never read, and nothing is written to x0hat.  A chain commits only if every slot up to and including its first
+// rejection (all of them, if none is rejected) passes the certificate; any other chain is left untouched with
+// pending[c] = 1 and goes through the verify call and accept_kernel as before (the plan lists pending chains only).
+// One coordinate block per thread (d a multiple of 4, d / 4 <= 256).
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, const Key* __restrict__ key_p,
+                                                           int32_t* __restrict__ a,
+                                                           const float* __restrict__ c_0,
+                                                           const float* __restrict__ sigma,
+                                                           const int32_t* __restrict__ tau_tab,
+                                                           const float* __restrict__ x0a, float* __restrict__ traj,
+                                                           int32_t* __restrict__ rounds, int32_t* __restrict__ live,
+                                                           int32_t* __restrict__ win, OneHotCert oc,
+                                                           int32_t* __restrict__ pending,
+                                                           int64_t* __restrict__ prof_counts) {
+  __shared__ float s_part[kAcceptChunk][4][4];   // per slot of the chunk, per wavefront: <D,xi>, |D|^2, <x,mu_b>, |x|^2
+  __shared__ float s_r2[kAcceptChunk][4];        // ... |x - s mu_b|^2
+  __shared__ float s_s[kAcceptChunk];            // s = <x,mu_b> / |mu_b|^2 of every slot
+  __shared__ float s_rej[2];
+  __shared__ int s_first, s_fail;
+
+  const int c = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int ac = a[c];
+  if (ac >= K || ac < 0) {
+    if (tid == 0) pending[c] = 0;
+    return;
+  }
+  const int w = min(win ? win[c] : L, K - ac);
+  // is the chain worth a try: a candidate, and a first slot (the noisiest) whose time index does not rule it out
+  const int b = oc.chain_comp[c];
+  bool go = w > 1 && b >= 0 && b < oc.C;
+  float am = 0.f;
+  if (go) {
+    am = oc.a_min[b];
+    go = cert_worth_reading(oc.coef_tau[tau_tab[ac + 1]], am, d);
+  }
+  if (!go) {
+    if (tid == 0) pending[c] = 1;
+    return;
+  }
+  const Key key = *key_p;
+  const int nblk = d >> 2;
+  const bool mine = tid < nblk;
+  const float qb = oc.musq[b], bias_b = kCertLog2e * oc.log_w[b];
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float4 ga1 = mine ? load4(x0a + (int64_t)c * d, tid, d, true) : zero4;
+  const float4 mv = mine ? load4(oc.means + (int64_t)b * d, tid, d, true) : zero4;
+  const float* rows = traj + ((int64_t)c * (K + 1) + ac) * d;   // slot k's model input: row k from here
+
+  auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {   // as in accept_kernel
+    const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
+    dot = fmaf(dx, xi.x, dot);
+    dot = fmaf(dy, xi.y, dot);
+    dot = fmaf(dz, xi.z, dot);
+    dot = fmaf(dw, xi.w, dot);
+    vv = fmaf(dx, dx, vv);
+    vv = fmaf(dy, dy, vv);
+    vv = fmaf(dz, dz, vv);
+    vv = fmaf(dw, dw, vv);
+  };
+
+  int n_acc = w, examined = 0, base = 0;
+  float4 xk[kAcceptChunk];
+#pragma unroll
+  for (int kk = 0; kk < kAcceptChunk; ++kk) xk[kk] = zero4;
+  for (; base < w; base += kAcceptChunk) {
+    examined = min(w, base + kAcceptChunk) - 1;
+    float dot[kAcceptChunk], vv[kAcceptChunk], pp[kAcceptChunk], xx[kAcceptChunk];
+#pragma unroll
+    for (int kk = 0; kk < kAcceptChunk; ++kk) dot[kk] = vv[kk] = pp[kk] = xx[kk] = 0.f;
+    if (mine) {
+#pragma unroll
+      for (int kk = 0; kk < kAcceptChunk; ++kk) {
+        const int k = base + kk;
+        if (k >= 1 && k < w) {
+          const float4 cf = oc.coef_tau[tau_tab[ac + k]];
+          const float4 x = load4(rows + (int64_t)k * d, tid, d, true);
+          xk[kk] = x;
+          const float4 gk = cert_value(cf, x, mv);
+          const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)tid);
+          slot_terms(ga1, gk, xi, dot[kk], vv[kk]);
+          pp[kk] = (x.x * mv.x + x.y * mv.y) + (x.z * mv.z + x.w * mv.w);
+          xx[kk] = (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
+        }
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < kAcceptChunk; ++kk) {
+      const float ds = wave_sum(dot[kk]), vs = wave_sum(vv[kk]), ps = wave_sum(pp[kk]), xs = wave_sum(xx[kk]);
+      if (lane == 0) {
+        s_part[kk][wave][0] = ds;
+        s_part[kk][wave][1] = vs;
+        s_part[kk][wave][2] = ps;
+        s_part[kk][wave][3] = xs;
+      }
+    }
+    __syncthreads();
+    if (tid < kAcceptChunk) {
+      float p = 0.f;
+      for (int q = 0; q < nwaves; ++q) p += s_part[tid][q][2];
+      s_s[tid] = p / qb;   // any s is valid: its rounding does not matter
+    }
+    __syncthreads();
+    {
+      float r2[kAcceptChunk];
+#pragma unroll
+      for (int kk = 0; kk < kAcceptChunk; ++kk) {
+        const float s = s_s[kk];
+        const float ex = fmaf(-s, mv.x, xk[kk].x), ey = fmaf(-s, mv.y, xk[kk].y);
+        const float ez = fmaf(-s, mv.z, xk[kk].z), ew = fmaf(-s, mv.w, xk[kk].w);
+        r2[kk] = wave_sum((ex * ex + ey * ey) + (ez * ez + ew * ew));
+      }
+      if (lane == 0) {
+#pragma unroll
+        for (int kk = 0; kk < kAcceptChunk; ++kk) s_r2[kk][wave] = r2[kk];
+      }
+    }
+    __syncthreads();
+
+    // Alg. 3 accept test (as in accept_kernel) and the certificate, one thread per slot of the chunk
+    if (tid < 64) {
+      const int k = base + lane;
+      const bool valid = lane < kAcceptChunk && k < w;
+      float sd = 0.f, sv = 0.f;
+      int bit = 1, uncert = 0;
+      if (valid && k >= 1) {
+        float xs = 0.f, rs = 0.f;
+        for (int q = 0; q < nwaves; ++q) {
+          sd += s_part[lane][q][0];
+          sv += s_part[lane][q][1];
+          xs += s_part[lane][q][3];
+          rs += s_r2[lane][q];
+        }
+        const int i = ac + k;
+        const float sg = sigma[i], c0 = c_0[i];
+        bit = 0;
+        if (sg > 0.f) {
+          const float vxi = c0 * sd;
+          const float v2 = c0 * c0 * sv;
+          const float rho = -(vxi / sg + v2 / (2.0f * sg * sg));
+          const float logu = logf(uniform1(key, (uint32_t)c, (uint32_t)(i + 1)));
+          bit = (logu <= rho) ? 1 : 0;
+        }
+        uncert = cert_passes(oc.coef_tau[tau_tab[i]], s_s[lane], rs, xs, am, qb, bias_b, oc.glob, oc.globw) ? 0 : 1;
+      }
+      const unsigned long long inv = ~__ballot(bit);
+      const int first = inv ? (__ffsll((long long)inv) - 1) : 64;
+      const unsigned long long bad = __ballot(uncert);
+      const unsigned long long need = first < 63 ? ((2ull << first) - 1ull) : ~0ull;   // slots up to the first rejection
+      if (lane == first) {
+        s_rej[0] = sd;
+        s_rej[1] = sv;
+      }
+      if (lane == 0) {
+        s_first = first;
+        s_fail = (bad & need) ? 1 : 0;
+      }
+    }
+    __syncthreads();
+    if (s_fail) {   // a slot that matters is not certified: the chain takes the verify call
+      if (tid == 0) pending[c] = 1;
+      return;
+    }
+    if (s_first < 64) {
+      n_acc = base + s_first;
+      break;
+    }
+  }
+
+  int a_next;
+  if (n_acc < w) {
+    const int k = n_acc;  // slot index of the first rejection (>= 1), in the chunk at `base`
+    const int i = ac + k;
+    const float sg = sigma[i], c0 = c_0[i];
+    const float dotr = s_rej[0], vvr = s_rej[1];
+    const float coef = (vvr > 0.f) ? (c0 + 2.0f * sg * dotr / vvr) : 0.f;
+    if (mine) {
+      float4 x = xk[0];
+#pragma unroll
+      for (int kk = 1; kk < kAcceptChunk; ++kk)
+        if (kk == k - base) x = xk[kk];
+      const float4 gk = cert_value(oc.coef_tau[tau_tab[i]], x, mv);
+      float* row = traj + ((int64_t)c * (K + 1) + i + 1) * d;
+      float4 y = load4(row, tid, d, true);
+      y.x = fmaf(-(ga1.x - gk.x), coef, y.x);
+      y.y = fmaf(-(ga1.y - gk.y), coef, y.y);
+      y.z = fmaf(-(ga1.z - gk.z), coef, y.z);
+      y.w = fmaf(-(ga1.w - gk.w), coef, y.w);
+      store4(row, tid, d, true, y);
+    }
+    a_next = i + 1;
+  } else {
+    a_next = ac + w;
+  }
+  if (tid == 0) {
+    a[c] = a_next;
+    pending[c] = 0;
+    if (prof_counts) {
+      atomicAdd((unsigned long long*)&prof_counts[1], (unsigned long long)(w - 1));   // rows the verify call is spared
+      atomicAdd((unsigned long long*)&prof_counts[2], (unsigned long long)examined);
+      if (n_acc < w) atomicAdd((unsigned long long*)&prof_counts[3], 1ull);
+      atomicAdd((unsigned long long*)&prof_counts[4], (unsigned long long)examined);
+      atomicAdd((unsigned long long*)&prof_counts[5], 1ull);
+    }
+    if (rounds) rounds[c] += 1;
+    if (win) {
+      const int B = gridDim.x;
+      const int st = window_next(win[B + c], w, n_acc);
+      win[B + c] = st;
+      win[c] = window_of(st, L);
+    }
+    // the round index was advanced at the start of this round
+    if (live && a_next < K) atomicAdd(&live[1 + ((live[0] - 1) % kLiveRing)], 1);
+  }
+}
+
+asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st) {
+  OneHotCert oc;
+  if (!model_onehot_cert(ctx, &oc) || ctx->d % 4 != 0 || ctx->d / 4 > 256 || !ctx->pending)
+    return ASD_ESTATE;
+  ProfScope ps(ctx, ASD_PROF_ACCEPT_EARLY, 0, st);
+  const int threads = (int)(ceil_div(ctx->d / 4, 64) * 64);
+  hipLaunchKernelGGL(accept_early_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
+                     ctx->c_0, ctx->sigma, ctx->tau, ctx->x0a, traj, rounds, live, ctx->cur_win, oc, ctx->pending,
+                     prof_counting(ctx) ? ctx->row_counts : nullptr);
+  ASD_HIP(hipGetLastError());
+  return ASD_OK;
+}
+
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int x0_slots, int32_t* accepted,
-                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st) {
+                         float* stats, int32_t* rounds, int32_t* live, hipStream_t st, const int32_t* pending) {
   ProfScope ps(ctx, ASD_PROF_ACCEPT, 0, st);
   const int nblk = (ctx->d + 3) / 4;
   const int threads = (int)std::min<int64_t>(1024, ceil_div(nblk, 64) * 64);
@@ -575,11 +819,11 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
   if (plan.in_off)
     hipLaunchKernelGGL(accept_kernel<true>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
                        ctx->c_0, ctx->sigma, ctx->x0a, carry, x0hat, x0_slots, traj, accepted, stats, rounds, live,
-                       ctx->cur_win, plan, prof_counts);
+                       ctx->cur_win, plan, prof_counts, pending);
   else
     hipLaunchKernelGGL(accept_kernel<false>, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
                        ctx->c_0, ctx->sigma, ctx->x0a, carry, x0hat, x0_slots, traj, accepted, stats, rounds, live,
-                       ctx->cur_win, plan, prof_counts);
+                       ctx->cur_win, plan, prof_counts, pending);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }

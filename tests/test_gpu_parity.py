@@ -585,6 +585,54 @@ def test_adaptive_windows_save_model_rows_and_toggle_cleanly():
     ctx.close()
 
 
+def test_early_accept_is_bit_identical_and_takes_chains():
+    """asd_use_early_accept: chains whose rows the one-hot certificate covers have their accept stage ahead of the
+    verify call, on model values the accept kernel forms itself.  Whole samples of the largest workload's shape (fewer
+    chains, but enough rows that the row plans are made by the planning kernels) with it on and off: the same
+    trajectories and round counts bit for bit, fixed windows and controlled ones, rounds as graphs and as plain
+    launches; it does take chain-rounds; the drafted rows counted are the same either way."""
+    cfg = dict(W.CONFIGS[5], chains=320)
+    ctx = runtime.open_ctx(cfg, W.make_params(cfg, 1), seed=0)
+    assert ctx.early_accept_active() and ctx.onehot_certificate_active()
+    traj = [runtime.alloc_traj(ctx) for _ in range(2)]
+    rounds = [torch.zeros(cfg["chains"], dtype=torch.int32, device=DEV) for _ in range(2)]
+    for adaptive in (False, True):
+        ctx.use_adaptive_window(adaptive)
+        for plain in (False, True):
+            rows = []
+            for i, early in enumerate((True, False)):
+                ctx.use_early_accept(early)
+                assert ctx.early_accept_active() == early
+                ctx.set_seed(7)
+                if plain:
+                    ctx.profile_enable(True)
+                ctx.sample(traj[i], rounds[i])
+                torch.cuda.synchronize()
+                if plain:
+                    rows.append((ctx.profile_rows(), ctx.profile_accept_rows(), ctx.profile_early_accept()))
+                    ctx.profile_enable(False)
+            assert torch.equal(traj[0], traj[1]) and torch.equal(rounds[0], rounds[1]), (adaptive, plain)
+            assert torch.isfinite(traj[0][:, -1]).all()
+            if plain:
+                (rows_on, acc_on, early_on), (rows_off, acc_off, early_off) = rows
+                _log("early accept, adaptive", adaptive, ": model rows formed in the accept kernel", early_on[0],
+                     "chain-rounds", early_on[1], "of", int(rounds[0].sum()), "; verify rows", rows_on[1])
+                assert early_off == (0, 0) and early_on[1] > int(rounds[0].sum()) // 4 and early_on[0] > 0
+                assert rows_on == rows_off and acc_on == acc_off
+    ctx.use_early_accept(True)
+    ctx.use_adaptive_window(False)
+    # ... and it stays out of the way where it does not apply
+    ctx.use_call_reuse(True)
+    assert not ctx.early_accept_active()
+    ctx.use_call_reuse(False)
+    ctx.use_onehot_certificate(False)
+    assert not ctx.early_accept_active()
+    ctx.close()
+    small = runtime.open_ctx(dict(W.CONFIGS[5], chains=48), W.make_params(dict(W.CONFIGS[5], chains=48), 1), seed=0)
+    assert not small.early_accept_active()      # plans folded into the round kernels
+    small.close()
+
+
 def test_profile_select_times_the_chosen_slots_only():
     """asd_profile_select: only the selected scopes take events, the work counters run regardless, and the sample
     is the same with any selection."""
