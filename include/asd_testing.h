@@ -22,8 +22,9 @@ ASD_API int32_t asd_resident_active(const asd_ctx* ctx);
 ASD_API int32_t asd_split_gemm_active(const asd_ctx* ctx);
 
 /* The second GEMM of the split-operand mixture denoiser (softmax weights times means) skips the stretches of
- * components whose weights are exactly 0.0f for every row of a tile (2^(logit - row maximum) underflows once a
- * posterior has collapsed).  The skipped products are zeros, so results are identical bit for bit; on = 0 makes
+ * components whose weights are exactly 0.0f for every row of a tile (the denoiser takes a weight below 2^-40 of its
+ * row's largest as zero -- that moves a result by less than 2 C 2^-40 of the largest |mean| -- and once a posterior
+ * has narrowed most are).  The skipped products are zeros, so results are identical bit for bit; on = 0 makes
  * the kernel visit every component anyway (for tests and timing comparisons).  Default: on.  The same switch covers
  * the closed form for rows with a single non-zero weight (asd_profile_model_work). */
 ASD_API asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on);

@@ -53,7 +53,7 @@
 //
 // Sparse K (Ops with kSparseK, no K split).  When load_a maps whole stretches of A to exactly 0.0f -- the
 // second GEMM of the mixture denoiser, whose A operand is 2^(logit - row maximum): once a posterior has
-// collapsed onto one component every other weight underflows to zero in fp32 -- the slabs of K in which
+// narrowed to a few components every other weight is 0.0f (the Op's load_a cuts them off) -- the slabs of K in which
 // every row of the tile is zero contribute nothing, bit for bit, and are not visited.  The Op marks the
 // groups of columns that are live for some row of the tile (mark_live, from data the producer of A
 // left behind); one wavefront compacts them into a list of slabs in LDS and the K loop walks that list.

@@ -152,6 +152,7 @@ __global__ __launch_bounds__(256) void gmm_row_scale_kernel(const int* __restric
 // row-wise path: 4 wavefronts per workgroup, one row per wavefront per pass
 // LDS per wavefront: x[d] then p[C]
 // ---------------------------------------------------------------------------
+constexpr float kZeroGapNat = kCertZeroGap * 0.6931471805599453f;   // the zero gap in the natural-log units of these kernels
 __global__ __launch_bounds__(256) void gmm_rowwise_kernel(const int* __restrict__ n_dev, int nrows_max, int d, int C, const float* __restrict__ in_base,
                                                           const int64_t* __restrict__ in_off,
                                                           float* __restrict__ out_base,
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_kernel(const int* __restrict_
     float sum = 0.f;
     if (active) {
       for (int k = lane; k < C; k += 64) {
-        const float p = expf(ps[k] - mx);
+        const float p = (ps[k] - mx < -kZeroGapNat) ? 0.f : expf(ps[k] - mx);
         ps[k] = p;
         sum += p;
       }
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(256) void gmm_rowwise_lds_kernel(const int* __restr
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
     float sum = 0.f;
     for (int k = lane; k < C4; k += 64) {
-      const float p = (k < C) ? expf(ps[k] - mx) : 0.f;
+      const float p = (k < C && !(ps[k] - mx < -kZeroGapNat)) ? expf(ps[k] - mx) : 0.f;
       ps[k] = p;
       sum += p;
     }
@@ -430,10 +431,11 @@ struct CombineOp {
   const float* pmax;
   int np;
   int gcols;  // logits columns behind one partial maximum (sub-tile width of the first GEMM), 0: unknown
-  // Sparse K: column group q (the columns behind pmax[.][q]) is dead for a row when its largest logit lies more
-  // than kZeroGap below the row maximum: load_a then gives 2^(l - max) = 0.0f for every element of the group
-  // (2^-150 is below the smallest fp32 subnormal), so those products are exact zeros.
-  static constexpr float kZeroGap = 150.0f;
+  // Weights below 2^-kZeroGap of the row's largest are zero by definition (gmm_cert.h): load_a gives 0.0f for a logit
+  // below lo = row maximum - kZeroGap.  Sparse K: column group q (the columns behind pmax[.][q]) is dead for a row when
+  // its largest logit lies below the same lo (the same fp32 expression, so "left out" and "computed" agree bit for
+  // bit): every product of the group is then an exact zero.
+  static constexpr float kZeroGap = 40.0f;
   static_assert(kZeroGap == kCertZeroGap, "the certificate proves weights zero by this gap");
   // NULL, or what gmm_rowmax_kernel made of pmax once for all the column tiles of a row tile: the row maxima [rows]
   // and the live flag of every column group [row tiles of kRowmaxTile rows][np]
@@ -531,9 +533,9 @@ struct CombineOp {
   }
   // logits are in base-2 units: p = 2^(l - rowmax) <= 1
   __device__ __forceinline__ float4 load_a(float4 v, int p) {
-    const float mx = rmax[p];
-    float4 e = make_float4(__builtin_amdgcn_exp2f(v.x - mx), __builtin_amdgcn_exp2f(v.y - mx),
-                           __builtin_amdgcn_exp2f(v.z - mx), __builtin_amdgcn_exp2f(v.w - mx));
+    const float mx = rmax[p], lo = mx - kZeroGap;
+    float4 e = make_float4(v.x < lo ? 0.f : __builtin_amdgcn_exp2f(v.x - mx), v.y < lo ? 0.f : __builtin_amdgcn_exp2f(v.y - mx),
+                           v.z < lo ? 0.f : __builtin_amdgcn_exp2f(v.z - mx), v.w < lo ? 0.f : __builtin_amdgcn_exp2f(v.w - mx));
     rsum[p] += (e.x + e.y) + (e.z + e.w);
     return make_float4(a_scale * e.x, a_scale * e.y, a_scale * e.z, a_scale * e.w);
   }
@@ -967,8 +969,8 @@ __global__ __launch_bounds__(256) void gmm_certify_kernel(const int* __restrict_
 // ---------------------------------------------------------------------------
 // Screening of the verify call's logits.
 //
-// Once the noise is low a posterior sits on one or two components: every other softmax weight is exactly 0.0f
-// in fp32 (2^-150 underflows), and the 6-product logits GEMM spends its time on numbers that only have to be
+// Once the noise is low a posterior sits on one or two components: every other softmax weight is 0.0f (below
+// 2^-kZeroGap of the largest: CombineOp), and the exact logits GEMM spends its time on numbers that only have to be
 // "far below the row maximum".  An int8 GEMM (a twelfth of the matrix time, exact int32 sums) says which tiles
 // those are, rigorously.  A row x is quantised with its own scale, the means with one scale per group of kGroup
 // components:  x ~ sx qx,  mu ~ sg qm  (q = the nearest integer in [-127, 127], s = max |.| / 127), so

@@ -7,7 +7,11 @@
 namespace asd {
 
 constexpr float kCertLog2e = 1.4426950408889634f;   // the logits' unit (LogitOp::kLog2e)
-constexpr float kCertZeroGap = 150.0f;              // CombineOp::kZeroGap: weights that far below the maximum are 0.0f
+// Softmax weights more than this many base-2 units below their row's largest are taken as exactly zero, in every
+// kernel of the mixture denoiser: a row's result moves by less than 2 C 2^-40 max |mu| for it (C <= 4096: 2^-27, a
+// tenth of what fp32 rounding does to it), and everything that can be shown to lie that far down -- most of both
+// GEMMs once a posterior has begun to narrow -- need not be computed at all.
+constexpr float kCertZeroGap = 40.0f;               // = CombineOp::kZeroGap
 
 // What a kernel outside the denoiser needs to certify rows and to write their model values in closed form.
 struct OneHotCert {

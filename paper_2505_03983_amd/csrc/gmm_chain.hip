@@ -129,7 +129,8 @@ __device__ __forceinline__ void gmm_eval_tiles(int first, int n, int a, const Ch
     mx = wave_max(mx);
     float sum = 0.f;
     for (int k = lane; k < l.C16; k += 64) {
-      const float p = (k < C) ? __builtin_amdgcn_exp2f(pr[k] - mx) : 0.f;  // components past C weigh nothing
+      // components past C weigh nothing, nor do weights below 2^-kCertZeroGap of the largest (gmm_cert.h)
+      const float p = (k < C && !(pr[k] - mx < -kCertZeroGap)) ? __builtin_amdgcn_exp2f(pr[k] - mx) : 0.f;
       pr[k] = p;
       sum += p;
     }
@@ -220,7 +221,7 @@ __device__ __forceinline__ void gmm_eval_row(int slot, int a, const ChainLayout&
     mx = wave_max(mx);
     float sum = 0.f;
     for (int k = lane; k < l.C16; k += 64) {
-      const float p = (k < C) ? __builtin_amdgcn_exp2f(ps[k] - mx) : 0.f;
+      const float p = (k < C && !(ps[k] - mx < -kCertZeroGap)) ? __builtin_amdgcn_exp2f(ps[k] - mx) : 0.f;
       ps[k] = p;
       sum += p;
     }

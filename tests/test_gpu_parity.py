@@ -315,6 +315,10 @@ def test_logit_screen_is_bit_identical_and_skips_work():
     comp = np.repeat(rng.integers(0, cfg["C"], (n_rows + 127) // 128), 128)[:n_rows]   # one component per row tile
     ab = T["abar"][tau]
     x0 = p["means"][comp] + np.sqrt(p["var"]) * rng.standard_normal((n_rows, cfg["d"]))
+    # every other row tile sits half way between two components: two weights survive there, so the tile is not one-hot
+    comp2 = np.repeat(rng.integers(0, cfg["C"], (n_rows + 127) // 128), 128)[:n_rows]
+    odd = (np.arange(n_rows) // 128) % 2 == 1
+    x0[odd] = 0.5 * (p["means"][comp[odd]] + p["means"][comp2[odd]]) + np.sqrt(p["var"]) * rng.standard_normal((int(odd.sum()), cfg["d"]))
     x = (np.sqrt(ab)[:, None] * x0 + np.sqrt(1 - ab)[:, None] * rng.standard_normal((n_rows, cfg["d"]))).astype(np.float32)
     xd, td = torch.from_numpy(x).to(DEV), torch.from_numpy(tau).to(DEV)
     outs, work = [], []

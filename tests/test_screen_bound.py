@@ -5,7 +5,8 @@ Four facts the bit-identity of the screened path rests on:
  * the int8 screening product's error bound: with x ~ sx qx and mu ~ sg qm (nearest integers in [-127, 127]),
    |sx sg <qx, qm> - <x, mu>| <= (sg / 2) |x|_1 + (sx / 2) |sg qm|_1;
  * the bounds U, L the decision is taken with really bracket the logits of a group, so that a tile declared dead
-   holds only logits more than the zero gap below their rows' maxima -- and such logits give weights of exactly 0.0f;
+   holds only logits more than the zero gap below their rows' maxima -- and such logits get weights of exactly 0.0f:
+   the kernels cut a weight off below 2^-gap of its row's largest, which moves a result by less than fp32 rounding does;
  * a row with one weight of 1.0 and zeros gets mu_b bit for bit from the split-operand accumulation: the three bf16
    pieces of an fp32 number add up exactly in the order the matrix cores add them;
  * the one-hot certificate: with e = x - s mu_b and a_n = |mu_n - mu_b|, logit_n - logit_b <= -(A/2) a_n^2 + B a_n
@@ -19,7 +20,7 @@ from test_split_scheme import cut3
 
 F = np.float32
 LOG2E = F(1.4426950408889634)
-ZERO_GAP = F(150.0)
+ZERO_GAP = F(40.0)      # the kernels' zero gap: weights below 2^-40 of the row's largest are zero by definition
 
 
 def quant(v):
@@ -97,16 +98,37 @@ def test_group_bounds_bracket_the_logits_and_dead_means_zero_weight():
         dead = U < L.max() - ZERO_GAP
         for g in np.nonzero(dead)[0]:
             sl = slice(g * per, (g + 1) * per)
-            # as the second GEMM forms the weights: exp2 of an fp32 difference
-            wts = np.exp2((exact[sl].astype(F) - F(row_max)).astype(F), dtype=F)
+            # as the second GEMM forms the weights: zero below lo = fl(row maximum - gap), else exp2 of an fp32 difference
+            lo = F(F(row_max) - ZERO_GAP)
+            lg = exact[sl].astype(F)
+            wts = np.where(lg < lo, F(0), np.exp2((lg - F(row_max)).astype(F), dtype=F))
             assert np.all(exact[sl] < row_max - float(ZERO_GAP)) and np.all(wts == 0)
             left_out += 1
     assert left_out > 100                    # the test does leave groups out
 
 
-def test_smallest_weight_the_gap_allows_is_zero():
-    # 2^-150 is half the smallest fp32 subnormal and rounds to zero (the hardware exp2 also flushes subnormals)
-    assert np.exp2(F(-150.0), dtype=F) == 0 and np.exp2(np.nextafter(F(-150.0), F(-200.0)), dtype=F) == 0
+def test_weights_below_the_gap_move_a_result_by_less_than_fp32_rounding():
+    """The kernels take a softmax weight below 2^-gap of its row's largest as zero.  With w_max = 1 the sum of the
+    weights is at least 1, the weights cut off add up to less than C 2^-gap, and the posterior mean moves by less than
+    2 C 2^-gap max |mu|: for C = 4096 that is 2^-27, an eighth of fp32's unit roundoff.  Brute force in double on logits
+    with gaps of every size around the cut."""
+    rng = np.random.default_rng(5)
+    gap = float(ZERO_GAP)
+    worst = 0.0
+    for trial in range(200):
+        C, d = int(rng.integers(2, 600)), int(rng.integers(1, 9))
+        mu = rng.standard_normal((C, d)) * rng.choice([0.1, 2.0, 50.0])
+        logits = -rng.exponential(rng.choice([1.0, 15.0, 40.0, 100.0]), C)     # base-2 units, largest near 0
+        logits[rng.integers(0, C)] = 0.0
+        logits[rng.integers(0, C, 3)] = -gap + rng.uniform(-1e-3, 1e-3, 3)      # some right at the cut
+        w = np.exp2(logits - logits.max())
+        exact = (w[:, None] * mu).sum(0) / w.sum()
+        wc = np.where(logits < logits.max() - gap, 0.0, w)
+        cut = (wc[:, None] * mu).sum(0) / wc.sum()
+        bound = 2.0 * C * 2.0 ** -gap * np.abs(mu).max()
+        assert np.abs(cut - exact).max() <= bound
+        worst = max(worst, np.abs(cut - exact).max() / np.abs(mu).max())
+    assert 2.0 * 4096 * 2.0 ** -gap <= 2.0 ** -27 and worst <= 2.0 ** -27
     assert np.exp2(F(0.0), dtype=F) == 1
 
 
