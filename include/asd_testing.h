@@ -65,19 +65,21 @@ ASD_API int32_t asd_tall_tiles_active(const asd_ctx* ctx);
 
 /* Early accept (inside asd_sample and asd_sample_noalloc; mixture denoiser with the one-hot certificate on fp16
  * terms, d a multiple of 4 and at most 1024, more than 16384 model rows per call, no model-call reuse).  A certified
- * row's model value is c_x' x + c_m' mu_b, which the accept stage can form itself; so after the draft stage a kernel
- * takes every chain it can through its accept stage on values formed that way -- slot by slot, certifying each row
- * it examines, stopping at the first rejection like the accept stage proper -- and only the chains with a slot it
- * cannot certify go through the verify call and the accept kernel.  A chain's round is the same either way, bit for
- * bit: the same sums in the same order on the same values.  Late in a sample, when every row is certifiable, a round
- * then reads a third of the window's rows once instead of reading all of them, writing their model values and
+ * row's model value is c_x' x + c_m' mu_b, which the accept stage can form itself, and a drafted row is a recurrence
+ * on the row before it.  So after the draft call one kernel takes every chain it can through its whole round: it
+ * drafts a slot from the slot before it in registers, certifies it, forms its model value and takes the accept test,
+ * stopping at the first rejection like the accept stage proper; only the rows the chain keeps go to the trajectory.
+ * Chains with a slot it cannot certify are left as they were and go through the draft kernel, the verify call and the
+ * accept kernel, which then take those chains only.  A chain's round is the same either way, bit for bit: the same
+ * sums in the same order on the same values.  Late in a sample, when every row is certifiable, a round then writes
+ * the dozen rows per chain it keeps, instead of writing the whole window, reading it, writing its model values and
  * reading a third of those back.  Default: on.  asd_early_accept_active: 1 if asd_sample of this context does it.
- * asd_profile_early_accept (while asd_profile_enable is on): model rows the kernel formed itself and chain-rounds it
- * committed since then (asd_profile_rows counts the windows of those chain-rounds among the verify rows all the
- * same, so that figure stays the number of drafted rows). */
+ * asd_profile_early_accept (while asd_profile_enable is on): model rows the kernel formed itself, chain-rounds it
+ * committed and the rows of their windows (slots 1 .. w - 1) since then.  asd_profile_rows counts those window rows
+ * among the verify rows all the same, so that figure stays the number of rows Alg. 1 verifies. */
 ASD_API asd_status asd_use_early_accept(asd_ctx* ctx, int32_t on);
 ASD_API int32_t asd_early_accept_active(const asd_ctx* ctx);
-ASD_API asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds);
+ASD_API asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds, int64_t* window_rows);
 
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */

@@ -163,9 +163,9 @@ struct asd_ctx {
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
-  int64_t* row_counts = nullptr;  // DEV [6], summed over launches while profiling: live rows of the draft call, of the verify
+  int64_t* row_counts = nullptr;  // DEV [7], summed over launches while profiling: live rows of the draft call, of the verify
                                   // call, x0hat rows the accept kernel read for its tests, rows it resampled; model rows
-                                  // the early accept kernel formed itself, chain-rounds it committed
+                                  // the early accept kernel formed itself, chain-rounds it committed, window rows of those
   double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
   asd::GmmState* gmm = nullptr;
   asd::MlpState* mlp = nullptr;
@@ -233,13 +233,14 @@ inline asd_status model_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) 
 asd_status launch_init_state(asd_ctx* ctx, const float* y0, float* traj, int32_t* a, int32_t* rounds, hipStream_t st);
 asd_status launch_plan_draft(asd_ctx* ctx, const int32_t* a, hipStream_t st, int32_t* zero_me = nullptr);
 asd_status launch_plan_verify(asd_ctx* ctx, const int32_t* a, hipStream_t st, const int32_t* pending = nullptr);
-asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring = nullptr);
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring = nullptr,
+                        const int32_t* pending = nullptr);
 asd_status launch_copy_slot0(asd_ctx* ctx, float* x0hat, hipStream_t st);
 // x0_slots: slots per chain of x0hat (L for the caller's array of the stage calls, L + 1 with model-call reuse)
 asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat, int x0_slots, int32_t* accepted,
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st, const int32_t* pending = nullptr);
-// The accept stage of the chains the denoiser's one-hot certificate covers, ahead of the verify call; leaves
-// ctx->pending[c] = 1 for every chain that still needs the verify call and launch_accept (see accept_early_kernel).
+// Draft and accept stage of the chains the denoiser's one-hot certificate covers, ahead of the draft kernel and the
+// verify call; leaves ctx->pending[c] = 1 for every chain that still needs those and launch_accept (accept_early_kernel).
 asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st);
 asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st);
 asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st);

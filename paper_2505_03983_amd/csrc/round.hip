@@ -230,14 +230,16 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
                                                     const float* __restrict__ c_0,
                                                     const float* __restrict__ sigma,
                                                     const float* __restrict__ x0a, float* __restrict__ traj,
-                                                    const int32_t* __restrict__ win, PlanOut plan, int extra) {
+                                                    const int32_t* __restrict__ win, PlanOut plan, int extra,
+                                                    const int32_t* __restrict__ pending) {
   // extra (FOLD only): 1 = the verify call also evaluates yhat_b of a window that ends before K (slot w of
-  // x0hat, which then has Lwin + 1 slots per chain)
+  // x0hat, which then has Lwin + 1 slots per chain).  pending (or NULL; not with FOLD): chains with pending[c] == 0
+  // have had their round already (accept_early_kernel).
   const int c = blockIdx.y;
   const int blk = blockIdx.x * blockDim.x + threadIdx.x;
   const int nblk = (d + 3) >> 2;
   const int ac = a[c];
-  const bool live = ac < K && ac >= 0;
+  const bool live = ac < K && ac >= 0 && !(pending && !pending[c]);
   const int w = live ? min(win ? win[c] : Lwin, K - ac) : 0;
   if (FOLD && blockIdx.x == 0) {
     // Bookkeeping of the round, once: the draft call has consumed its row count; the round index
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
   }
 }
 
-asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring) {
+asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t st, int32_t* ring, const int32_t* pending) {
   const int nblk = (ctx->d + 3) / 4;
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
@@ -296,10 +298,10 @@ asd_status launch_draft(asd_ctx* ctx, float* traj, const int32_t* a, hipStream_t
   const PlanOut plan = plan_out(ctx, ring);
   if (plan.in_off)
     hipLaunchKernelGGL(draft_kernel<true>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, ctx->reuse_now ? 1 : 0);
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, ctx->reuse_now ? 1 : 0, (const int32_t*)nullptr);
   else
     hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a, ctx->c_x,
-                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, 0);
+                       ctx->c_0, ctx->sigma, ctx->x0a, traj, ctx->cur_win, plan, 0, pending);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -323,7 +325,7 @@ asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t 
   const int threads = nblk >= 256 ? 256 : (int)(ceil_div(nblk, 64) * 64);
   dim3 grid((unsigned)ceil_div(nblk, threads), (unsigned)ctx->B);
   hipLaunchKernelGGL(draft_kernel<false>, grid, dim3(threads), 0, st, ctx->K, 1, ctx->d, ctx->key_dev, ctx->a, ctx->c_x,
-                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut(), 0);
+                     ctx->c_0, ctx->sigma, ctx->x0a, traj, (const int32_t*)nullptr, PlanOut(), 0, (const int32_t*)nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
 }
@@ -572,18 +574,22 @@ __global__ __launch_bounds__(1024) void accept_kernel(int K, int L, int d, const
 }
 
 // ----------------------------------------------------------------------------
-// The accept stage ahead of the verify call, for chains whose rows the mixture denoiser's one-hot certificate
-// covers (gmm_cert.h).  A certified row's model value is c_x' x + c_m' mu_b -- the same bits the verify call would
-// store for it -- so this kernel forms the values of the slots it examines itself, from the drafted rows, and takes
-// the chain through its round: the same sums, in the same order, as accept_kernel on stored values, hence the same
-// decisions and the same resampled row.  It stops at the first rejection like accept_kernel; rows behind it are
-// never read, and nothing is written to x0hat.  A chain commits only if every slot up to and including its first
-// rejection (all of them, if none is rejected) passes the certificate; any other chain is left untouched with
-// pending[c] = 1 and goes through the verify call and accept_kernel as before (the plan lists pending chains only).
-// One coordinate block per thread (d a multiple of 4, d / 4 <= 256).
+// Draft and accept stage in one, ahead of the draft kernel and the verify call, for chains whose rows the mixture
+// denoiser's one-hot certificate covers (gmm_cert.h).  A certified row's model value is c_x' x + c_m' mu_b -- the
+// same bits the verify call would store for it -- and a drafted row is a recurrence on the row before it, so a
+// workgroup walks its chain's window in registers: it drafts slot k from slot k - 1 (draft_kernel's expression, with
+// the noise the accept test of slot k - 1 has just used), certifies it, forms its model value and takes the accept
+// test -- the same sums, in the same order, as accept_kernel on stored values, hence the same decisions and the
+// same resampled row.  It stops at the first rejection like accept_kernel; what lies behind is neither drafted nor
+// read, nothing goes to x0hat, and only the rows the chain keeps go to the trajectory.  A chain commits only if
+// every slot up to and including its first rejection (all of them, if none is rejected) passes the certificate; any
+// other chain is left with pending[c] = 1 and unchanged state (rows already stored are the drafts draft_kernel stores
+// again) and goes through draft_kernel, the verify call and accept_kernel as before: all three take the pending
+// chains only.  One coordinate block per thread (d a multiple of 4, d / 4 <= 256).
 // ----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, const Key* __restrict__ key_p,
                                                            int32_t* __restrict__ a,
+                                                           const float* __restrict__ c_x,
                                                            const float* __restrict__ c_0,
                                                            const float* __restrict__ sigma,
                                                            const int32_t* __restrict__ tau_tab,
@@ -626,7 +632,9 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   const float4 ga1 = mine ? load4(x0a + (int64_t)c * d, tid, d, true) : zero4;
   const float4 mv = mine ? load4(oc.means + (int64_t)b * d, tid, d, true) : zero4;
-  const float* rows = traj + ((int64_t)c * (K + 1) + ac) * d;   // slot k's model input: row k from here
+  float* rows = traj + ((int64_t)c * (K + 1) + ac) * d;   // slot k's row: yhat_{a+k}, row k from here
+  float4 y = mine ? load4(rows, tid, d, true) : zero4;    // yhat_a = y_a; then the last row drafted
+  float4 xi_d = normal4(key, (uint32_t)c, (uint32_t)(ac + 1), (uint32_t)tid);   // the noise of the next draft step
 
   auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {   // as in accept_kernel
     const float dx = ga.x - gk.x, dy = ga.y - gk.y, dz = ga.z - gk.z, dw = ga.w - gk.w;
@@ -638,6 +646,11 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
     vv = fmaf(dy, dy, vv);
     vv = fmaf(dz, dz, vv);
     vv = fmaf(dw, dw, vv);
+  };
+  auto draft_step = [&](int i, float4 from, float4 xi) -> float4 {   // yhat_{i+1} from yhat_i: as in draft_kernel
+    const float cx = c_x[i], c0 = c_0[i], sg = sigma[i];
+    return make_float4(fmaf(sg, xi.x, fmaf(cx, from.x, c0 * ga1.x)), fmaf(sg, xi.y, fmaf(cx, from.y, c0 * ga1.y)),
+                       fmaf(sg, xi.z, fmaf(cx, from.z, c0 * ga1.z)), fmaf(sg, xi.w, fmaf(cx, from.w, c0 * ga1.w)));
   };
 
   int n_acc = w, examined = 0, base = 0;
@@ -654,11 +667,13 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
       for (int kk = 0; kk < kAcceptChunk; ++kk) {
         const int k = base + kk;
         if (k >= 1 && k < w) {
-          const float4 cf = oc.coef_tau[tau_tab[ac + k]];
-          const float4 x = load4(rows + (int64_t)k * d, tid, d, true);
+          const float4 x = draft_step(ac + k - 1, y, xi_d);   // yhat_{a+k}
+          y = x;
           xk[kk] = x;
+          const float4 cf = oc.coef_tau[tau_tab[ac + k]];
           const float4 gk = cert_value(cf, x, mv);
           const float4 xi = normal4(key, (uint32_t)c, (uint32_t)(ac + k + 1), (uint32_t)tid);
+          xi_d = xi;
           slot_terms(ga1, gk, xi, dot[kk], vv[kk]);
           pp[kk] = (x.x * mv.x + x.y * mv.y) + (x.z * mv.z + x.w * mv.w);
           xx[kk] = (x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w);
@@ -742,6 +757,14 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
       if (tid == 0) pending[c] = 1;
       return;
     }
+    // the rows the chain keeps of this chunk: up to the slot of the first rejection, all of them if there is none
+    if (mine) {
+#pragma unroll
+      for (int kk = 0; kk < kAcceptChunk; ++kk) {
+        const int k = base + kk;
+        if (k >= 1 && k < w && kk <= s_first) store4(rows + (int64_t)k * d, tid, d, true, xk[kk]);
+      }
+    }
     if (s_first < 64) {
       n_acc = base + s_first;
       break;
@@ -761,27 +784,30 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
       for (int kk = 1; kk < kAcceptChunk; ++kk)
         if (kk == k - base) x = xk[kk];
       const float4 gk = cert_value(oc.coef_tau[tau_tab[i]], x, mv);
-      float* row = traj + ((int64_t)c * (K + 1) + i + 1) * d;
-      float4 y = load4(row, tid, d, true);
-      y.x = fmaf(-(ga1.x - gk.x), coef, y.x);
-      y.y = fmaf(-(ga1.y - gk.y), coef, y.y);
-      y.z = fmaf(-(ga1.z - gk.z), coef, y.z);
-      y.w = fmaf(-(ga1.w - gk.w), coef, y.w);
-      store4(row, tid, d, true, y);
+      // the drafted yhat_{i+1}, reflected
+      float4 yr = draft_step(i, x, normal4(key, (uint32_t)c, (uint32_t)(i + 1), (uint32_t)tid));
+      yr.x = fmaf(-(ga1.x - gk.x), coef, yr.x);
+      yr.y = fmaf(-(ga1.y - gk.y), coef, yr.y);
+      yr.z = fmaf(-(ga1.z - gk.z), coef, yr.z);
+      yr.w = fmaf(-(ga1.w - gk.w), coef, yr.w);
+      store4(rows + (int64_t)(k + 1) * d, tid, d, true, yr);
     }
     a_next = i + 1;
   } else {
+    // the whole window: its last proposal sample yhat_{a+w} is the next round's start
+    if (mine) store4(rows + (int64_t)w * d, tid, d, true, draft_step(ac + w - 1, y, xi_d));
     a_next = ac + w;
   }
   if (tid == 0) {
     a[c] = a_next;
     pending[c] = 0;
     if (prof_counts) {
-      atomicAdd((unsigned long long*)&prof_counts[1], (unsigned long long)(w - 1));   // rows the verify call is spared
+      atomicAdd((unsigned long long*)&prof_counts[1], (unsigned long long)(w - 1));   // the window's rows, as the plan counts them
       atomicAdd((unsigned long long*)&prof_counts[2], (unsigned long long)examined);
       if (n_acc < w) atomicAdd((unsigned long long*)&prof_counts[3], 1ull);
       atomicAdd((unsigned long long*)&prof_counts[4], (unsigned long long)examined);
       atomicAdd((unsigned long long*)&prof_counts[5], 1ull);
+      atomicAdd((unsigned long long*)&prof_counts[6], (unsigned long long)(w - 1));
     }
     if (rounds) rounds[c] += 1;
     if (win) {
@@ -802,7 +828,7 @@ asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* r
   ProfScope ps(ctx, ASD_PROF_ACCEPT_EARLY, 0, st);
   const int threads = (int)(ceil_div(ctx->d / 4, 64) * 64);
   hipLaunchKernelGGL(accept_early_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                     ctx->c_0, ctx->sigma, ctx->tau, ctx->x0a, traj, rounds, live, ctx->cur_win, oc, ctx->pending,
+                     ctx->c_x, ctx->c_0, ctx->sigma, ctx->tau, ctx->x0a, traj, rounds, live, ctx->cur_win, oc, ctx->pending,
                      prof_counting(ctx) ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;
