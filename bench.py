@@ -167,6 +167,7 @@ def run_gpu(w, steps, warmup, seed, profile=True, adaptive=False, split=True, cl
         out["kernels"] = table
         out["rows"] = ctx.profile_rows()
         out["accept_rows"] = ctx.profile_accept_rows()
+        out["early_accept"] = ctx.profile_early_accept() if ctx.early_accept_active() else None
         out["model_work"] = ctx.profile_model_work()
         ctx.profile_enable(False)
         ctx.profile_select(None)
@@ -282,22 +283,40 @@ def hbm_kernels(res):
     examined, resampled = res.get("accept_rows", (None, None))
     d = cfg["d"]
     w_total = verify_rows + draft_rows      # w summed over chains and rounds
+    chain_rounds = draft_rows               # one draft-call row per live chain and round
+    ea = res.get("early_accept")
+    if ea:
+        # chain-rounds the early accept kernel took whole: neither the draft kernel nor the accept kernel saw them
+        e_rows, e_rounds, e_window, e_resampled = ea
+        w_total -= e_window + e_rounds
+        chain_rounds -= e_rounds
+        if examined is not None:
+            examined, resampled = examined - e_rows, resampled - e_resampled
+        verify_rows -= e_window
     out = {}
     if "DRAFT/draft" in k:
-        b = 4.0 * d * (2 * draft_rows + w_total)
+        b = 4.0 * d * (2 * chain_rounds + w_total)
         out["draft"] = dict(GBps=b / (1e-3 * k["DRAFT/draft"]["total_ms"]) / 1e9,
                             avg_us=k["DRAFT/draft"]["avg_us"], bytes_per_launch=b / k["DRAFT/draft"]["launches"])
     if "ACCEPT/draft" in k:
         t = 1e-3 * k["ACCEPT/draft"]["total_ms"]
-        whole = 4.0 * d * (w_total + 3 * draft_rows)
+        whole = 4.0 * d * (w_total + 3 * chain_rounds)
         out["accept"] = dict(avg_us=k["ACCEPT/draft"]["avg_us"],
                              whole_window=dict(GBps=whole / t / 1e9, frac_of_hbm_peak=whole / t / 1e9 / HBM_PEAK_GBS))
         if examined is not None:
-            b = 4.0 * d * (examined + draft_rows + 2 * resampled)
+            b = 4.0 * d * (examined + chain_rounds + 2 * resampled)
             out["accept"].update(GBps=b / t / 1e9, bytes_per_launch=b / k["ACCEPT/draft"]["launches"],
                                  share_of_window_rows_read=examined / max(1.0, float(verify_rows)))
         else:
             out["accept"]["GBps"] = whole / t / 1e9
+    if ea and "ACCEPT_EARLY/draft" in k:
+        # reads y_a, x0a and mu_b per chain-round; writes the rows the chain keeps (about the examined ones)
+        t = 1e-3 * k["ACCEPT_EARLY/draft"]["total_ms"]
+        b = 4.0 * d * (3 * ea[1] + ea[0])
+        out["accept_early"] = dict(GBps=b / t / 1e9, avg_us=k["ACCEPT_EARLY/draft"]["avg_us"],
+                                   bytes_per_launch=b / k["ACCEPT_EARLY/draft"]["launches"],
+                                   chain_rounds_taken=ea[1], share_of_chain_rounds=ea[1] / max(1.0, float(draft_rows)),
+                                   model_rows_formed=ea[0], window_rows_spared_the_verify_call=ea[2])
     for v in out.values():
         v["frac_of_hbm_peak"] = v["GBps"] / HBM_PEAK_GBS
         v["bound_by"] = "ALU (counter-based noise regenerated in registers)"

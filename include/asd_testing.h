@@ -75,11 +75,13 @@ ASD_API int32_t asd_tall_tiles_active(const asd_ctx* ctx);
  * the dozen rows per chain it keeps, instead of writing the whole window, reading it, writing its model values and
  * reading a third of those back.  Default: on.  asd_early_accept_active: 1 if asd_sample of this context does it.
  * asd_profile_early_accept (while asd_profile_enable is on): model rows the kernel formed itself, chain-rounds it
- * committed and the rows of their windows (slots 1 .. w - 1) since then.  asd_profile_rows counts those window rows
- * among the verify rows all the same, so that figure stays the number of rows Alg. 1 verifies. */
+ * committed, the rows of their windows (slots 1 .. w - 1) and the rows it resampled since then.  asd_profile_rows
+ * counts those window rows among the verify rows all the same, so that figure stays the number of rows Alg. 1
+ * verifies; asd_profile_accept_rows likewise covers both accept kernels. */
 ASD_API asd_status asd_use_early_accept(asd_ctx* ctx, int32_t on);
 ASD_API int32_t asd_early_accept_active(const asd_ctx* ctx);
-ASD_API asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds, int64_t* window_rows);
+ASD_API asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds, int64_t* window_rows,
+                                            int64_t* resampled_rows);
 
 /* Raw generator output: out DEV uint32 [nblk, 4] = Philox4x32-10 words for
  * counters (blk, step, chain, stream_id), blk = 0..nblk-1, key = seed. */

@@ -77,7 +77,7 @@ def lib():
             "asd_tall_tiles_active": (i32, [vp]),
             "asd_use_early_accept": (i32, [vp, i32]),
             "asd_early_accept_active": (i32, [vp]),
-            "asd_profile_early_accept": (i32, [vp, vp, vp, vp]),
+            "asd_profile_early_accept": (i32, [vp, vp, vp, vp, vp]),
             "asd_use_onehot_certificate": (i32, [vp, i32]),
             "asd_onehot_certificate_active": (i32, [vp]),
             "asd_use_adaptive_window": (i32, [vp, i32]),
@@ -277,11 +277,11 @@ class Ctx:
         return bool(lib().asd_early_accept_active(self.h))
 
     def profile_early_accept(self):
-        """(model rows the early accept kernel formed itself, chain-rounds it committed, rows of their windows) since
-        profile_enable."""
-        a, b, c = C.c_int64(0), C.c_int64(0), C.c_int64(0)
-        _check(lib().asd_profile_early_accept(self.h, C.addressof(a), C.addressof(b), C.addressof(c)))
-        return a.value, b.value, c.value
+        """(model rows the early accept kernel formed itself, chain-rounds it committed, rows of their windows, rows
+        it resampled) since profile_enable."""
+        v = [C.c_int64(0) for _ in range(4)]
+        _check(lib().asd_profile_early_accept(self.h, *[C.addressof(x) for x in v]))
+        return tuple(x.value for x in v)
 
     def use_onehot_certificate(self, on=True):
         _check(lib().asd_use_onehot_certificate(self.h, int(bool(on))))

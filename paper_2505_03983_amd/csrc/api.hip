@@ -148,8 +148,8 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMalloc(&ctx->carry, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMemset(ctx->carry, 0, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->a, sizeof(int32_t) * (size_t)ctx->B));
-  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 7));
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 7));
+  ASD_HIP(hipMalloc(&ctx->row_counts, sizeof(int64_t) * 8));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 8));
   ASD_HIP(hipMalloc(&ctx->pending, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMemset(ctx->pending, 0, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
@@ -624,7 +624,7 @@ asd_status asd_profile_enable(asd_ctx* ctx, int32_t on) {
   ctx->prof.reset();
   ctx->prof.on = on != 0;
   ctx->prof.outer = on >= 2;
-  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 7));
+  ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 8));
   if (ctx->gmm && ctx->gmm->work_counts) ASD_HIP(hipMemset(ctx->gmm->work_counts, 0, 8 * sizeof(unsigned long long)));
   return ASD_OK;
 }
@@ -641,13 +641,15 @@ int32_t asd_early_accept_active(const asd_ctx* ctx) {
   return (early_accept_possible(ctx) && ctx->n_rows_max > 16384 && !ctx->reuse) ? 1 : 0;
 }
 
-asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds, int64_t* window_rows) {
+asd_status asd_profile_early_accept(asd_ctx* ctx, int64_t* model_rows, int64_t* chain_rounds, int64_t* window_rows,
+                                    int64_t* resampled_rows) {
   ASD_TRY(check_ctx(ctx));
-  int64_t h[7] = {0, 0, 0, 0, 0, 0, 0};
+  int64_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   ASD_HIP(hipMemcpy(h, ctx->row_counts, sizeof(h), hipMemcpyDeviceToHost));
   if (model_rows) *model_rows = h[4];
   if (chain_rounds) *chain_rounds = h[5];
   if (window_rows) *window_rows = h[6];
+  if (resampled_rows) *resampled_rows = h[7];
   return ASD_OK;
 }
 

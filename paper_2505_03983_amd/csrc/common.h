@@ -163,9 +163,9 @@ struct asd_ctx {
   bool resident_enabled = true;  // asd_sample may run whole chains in one launch (gmm_chain.hip) when the shape allows
   int stage = 0;  // 0: expect draft, 1: expect verify, 2: expect accept
   asd::Profiler prof;
-  int64_t* row_counts = nullptr;  // DEV [7], summed over launches while profiling: live rows of the draft call, of the verify
+  int64_t* row_counts = nullptr;  // DEV [8], summed over launches while profiling: live rows of the draft call, of the verify
                                   // call, x0hat rows the accept kernel read for its tests, rows it resampled; model rows
-                                  // the early accept kernel formed itself, chain-rounds it committed, window rows of those
+                                  // the early accept kernel formed itself, chain-rounds it committed, window rows of those, rows it resampled
   double model_macs_per_row = 0.0;  // multiply-adds of one denoiser row (set by the denoiser)
   asd::GmmState* gmm = nullptr;
   asd::MlpState* mlp = nullptr;

@@ -808,6 +808,7 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
       atomicAdd((unsigned long long*)&prof_counts[4], (unsigned long long)examined);
       atomicAdd((unsigned long long*)&prof_counts[5], 1ull);
       atomicAdd((unsigned long long*)&prof_counts[6], (unsigned long long)(w - 1));
+      if (n_acc < w) atomicAdd((unsigned long long*)&prof_counts[7], 1ull);
     }
     if (rounds) rounds[c] += 1;
     if (win) {

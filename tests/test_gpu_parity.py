@@ -621,7 +621,8 @@ def test_early_accept_is_bit_identical_and_takes_chains():
                 (rows_on, acc_on, early_on), (rows_off, acc_off, early_off) = rows
                 _log("early accept, adaptive", adaptive, ": model rows formed in the accept kernel", early_on[0],
                      "chain-rounds", early_on[1], "of", int(rounds[0].sum()), "; verify rows", rows_on[1])
-                assert early_off == (0, 0, 0) and early_on[1] > int(rounds[0].sum()) // 4 and 0 < early_on[0] <= early_on[2]
+                assert early_off == (0, 0, 0, 0) and early_on[1] > int(rounds[0].sum()) // 4 and 0 < early_on[0] <= early_on[2]
+                assert 0 < early_on[3] <= early_on[1] and early_on[3] <= acc_on[1]
                 assert rows_on == rows_off and acc_on == acc_off
     ctx.use_early_accept(True)
     ctx.use_adaptive_window(False)
