@@ -1616,8 +1616,10 @@ asd_status gmm_eval(asd_ctx* ctx, const RowPlan& rows, hipStream_t st) {
   const bool screen = split && rows.call == 1 && g->screen_ok && g->screen_mode != 0 && g->sparse_combine;
   // ... and rows may be certified one-hot before anything else (the plan says which chain a row belongs to): in the
   // verify call, and in the draft call of a context whose verify calls are
+  // (not in a verify call behind the early accept kernel: a chain is in that call because one of its rows failed this
+  // very test, so no row tile of it -- two chains' blocks -- can pass whole)
   const bool cert = split && g->screen_ok && g->screen_mode != 0 && g->sparse_combine && g->cert_ok && g->cert_on &&
-                    rows.chain != nullptr && (rows.call == 1 || g->split_draft_ok);
+                    rows.chain != nullptr && (rows.call == 1 || g->split_draft_ok) && !(rows.call == 1 && ctx->early_now);
   const uint8_t* cert_tile = cert ? g->cert_tile : nullptr;
   // the screening pass's switch in device memory: this round's verdict of the draft call, or the constant 1
   const int32_t* on = screen ? g->screen_on + (g->screen_mode == 2 ? 1 : 0) : nullptr;
