@@ -152,19 +152,27 @@ static asd_status build(asd_ctx* ctx, const asd_config* cfg) {
   ASD_HIP(hipMemset(ctx->row_counts, 0, sizeof(int64_t) * 8));
   ASD_HIP(hipMalloc(&ctx->pending, sizeof(int32_t) * (size_t)ctx->B));
   ASD_HIP(hipMemset(ctx->pending, 0, sizeof(int32_t) * (size_t)ctx->B));
-  ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + kLiveRing)));
-  ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + kLiveRing)));
+  ASD_HIP(hipMalloc(&ctx->live, sizeof(int32_t) * (1 + 2 * kLiveRing)));
+  ASD_HIP(hipMemset(ctx->live, 0, sizeof(int32_t) * (1 + 2 * kLiveRing)));
   ASD_HIP(hipMalloc(&ctx->win, sizeof(int32_t) * 2 * (size_t)ctx->B));
   ASD_HIP(hipMalloc(&ctx->chain_max, sizeof(unsigned long long)));
   ASD_HIP(hipMemset(ctx->chain_max, 0, sizeof(unsigned long long)));
   ASD_HIP(hipMalloc(&ctx->key_dev, sizeof(Key)));
   ASD_HIP(hipMemcpy(ctx->key_dev, &ctx->key, sizeof(Key), hipMemcpyHostToDevice));
-  ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * kLiveRing, hipHostMallocDefault));
+  ASD_HIP(hipHostMalloc((void**)&ctx->live_host, sizeof(int32_t) * 2 * kLiveRing, hipHostMallocDefault));
   ctx->live_ev = new (std::nothrow) hipEvent_t[kLiveRing]();
   if (!ctx->live_ev) return ASD_ENOMEM;
   for (int i = 0; i < kLiveRing; ++i) ASD_HIP(hipEventCreateWithFlags(&ctx->live_ev[i], hipEventDisableTiming));
   if (ctx->kind == ASD_DEN_GMM) return gmm_create(ctx, cfg->den);
   return mlp_create(ctx, cfg->den);
+}
+
+// The captured rounds hold the launch arguments and kernels of the settings they were captured under.
+static void drop_round_graphs(asd_ctx* ctx) {
+  if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
+  if (ctx->gexec_light) (void)hipGraphExecDestroy(ctx->gexec_light);
+  ctx->gexec = nullptr;
+  ctx->gexec_light = nullptr;
 }
 
 static void teardown(asd_ctx* ctx) {
@@ -188,7 +196,7 @@ static void teardown(asd_ctx* ctx) {
   (void)hipFree(ctx->chain_max);
   (void)hipFree(ctx->win);
   (void)hipFree(ctx->key_dev);
-  if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
+  drop_round_graphs(ctx);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->own_stream);
   (void)hipFree(ctx->row_counts);
   (void)hipFree(ctx->pending);
@@ -317,7 +325,9 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
 }
 
 // All launches of one round of Alg. 1 on `st`, plus the copy of the live-chain ring to the host.
-static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, float* x0hat, hipStream_t st) {
+// light (early accept only): the draft call and the early accept kernel alone -- for rounds in which, as far as the
+// host knows, that kernel takes every chain.  A chain it does not take stays where it is until the next full round.
+static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, float* x0hat, hipStream_t st, bool light) {
   // No planning kernels here: the rows of the draft call were listed by the previous round's accept
   // kernel (by init_state before round 0), those of the verify call are listed by the draft kernel.
   // (or, for large batches, by the planning kernels: see fold_plans)
@@ -326,41 +336,41 @@ static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, floa
   // chains the denoiser can certify have their draft and accept stage in one kernel now; the draft kernel, the verify
   // call and the accept kernel take the others only
   const int32_t* pending = ctx->early_now ? ctx->pending : nullptr;
-  if (pending) ASD_TRY(launch_accept_early(ctx, traj, ctx->a, rounds, ctx->live, st));
-  ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live, pending));
-  if (ctx->L > 1 || ctx->reuse_now) {
-    if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st, pending));
-    ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
+  if (pending) ASD_TRY(launch_accept_early(ctx, traj, ctx->a, rounds, ctx->live, st, light));
+  if (!(pending && light)) {
+    ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live, pending));
+    if (ctx->L > 1 || ctx->reuse_now) {
+      if (!ctx->fold_plans) ASD_TRY(launch_plan_verify(ctx, ctx->a, st, pending));
+      ASD_TRY(model_eval(ctx, verify_rows(ctx, traj, x0hat), st));
+    }
+    ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, ctx->L + (ctx->reuse_now ? 1 : 0), nullptr, nullptr, rounds,
+                          ctx->live, st, pending));
   }
-  ASD_TRY(launch_accept(ctx, traj, ctx->a, x0hat, ctx->L + (ctx->reuse_now ? 1 : 0), nullptr, nullptr, rounds, ctx->live,
-                        st, pending));
   // The whole ring is copied: slot r % kLiveRing keeps its value until round r + kLiveRing overwrites it,
   // long after the host has read it.
-  ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * kLiveRing, hipMemcpyDeviceToHost, st));
+  ASD_HIP(hipMemcpyAsync(ctx->live_host, ctx->live + 1, sizeof(int32_t) * 2 * kLiveRing, hipMemcpyDeviceToHost, st));
   return ASD_OK;
 }
 
 // Capture one round into a graph (launch-bound workloads: one graph launch instead of ~8 kernel launches).
 // Every launch argument of a round is the same in every round: the round index and the live ring are
 // advanced on the device, the seed is read from device memory.
-static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st) {
-  if (ctx->gexec && ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st &&
-      ctx->g_win == ctx->cur_win && ctx->g_reuse == ctx->reuse_now && ctx->g_early == ctx->early_now)
-    return ASD_OK;
+static asd_status ensure_round_graph(asd_ctx* ctx, float* traj, int32_t* rounds, hipStream_t st, bool light) {
+  const bool valid = ctx->g_traj == traj && ctx->g_rounds == rounds && ctx->g_stream == st &&
+                     ctx->g_win == ctx->cur_win && ctx->g_reuse == ctx->reuse_now && ctx->g_early == ctx->early_now;
+  if (!valid) drop_round_graphs(ctx);   // both forms were captured for other arguments
+  hipGraphExec_t& exec = light ? ctx->gexec_light : ctx->gexec;
+  if (exec) return ASD_OK;
   hipGraph_t graph = nullptr;
   ASD_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-  asd_status s = enqueue_round(ctx, traj, rounds, ctx->x0hat, st);
+  asd_status s = enqueue_round(ctx, traj, rounds, ctx->x0hat, st, light);
   hipError_t e = hipStreamEndCapture(st, &graph);
   if (s != ASD_OK) {
     if (graph) (void)hipGraphDestroy(graph);
     return s;
   }
   ASD_HIP(e);
-  if (ctx->gexec) {
-    (void)hipGraphExecDestroy(ctx->gexec);
-    ctx->gexec = nullptr;
-  }
-  e = hipGraphInstantiate(&ctx->gexec, graph, nullptr, nullptr, 0);
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   ASD_HIP(e);
   ctx->g_traj = traj;
@@ -418,14 +428,17 @@ static asd_status sample_rounds(asd_ctx* ctx, const float* y0, float* traj, int3
   ASD_TRY(launch_init_state(ctx, y0, traj, ctx->a, rounds, st));
   int r = 0;
   int done_at = -1;
-  const int r_cap = ctx->K + lag + 1;  // Alg. 1 ends within K iterations (correctness theorem)
+  bool light = false;
+  // Alg. 1 ends within K iterations (correctness theorem); a light round may leave a chain waiting, at most `lag`
+  // rounds in a row before a full one comes
+  const int r_cap = (ctx->early_now ? (lag + 2) : 1) * ctx->K + lag + 1;
   for (; r < r_cap; ++r) {
     const int slot = r % kLiveRing;
     if (use_graph && r > 0) {
-      if (r == 1) ASD_TRY(ensure_round_graph(ctx, traj, rounds, st));  // round 0 ran eagerly (first-use set-up)
-      ASD_HIP(hipGraphLaunch(ctx->gexec, st));
+      ASD_TRY(ensure_round_graph(ctx, traj, rounds, st, light));  // round 0 ran eagerly (first-use set-up)
+      ASD_HIP(hipGraphLaunch(light ? ctx->gexec_light : ctx->gexec, st));
     } else {
-      ASD_TRY(enqueue_round(ctx, traj, rounds, x0hat, st));
+      ASD_TRY(enqueue_round(ctx, traj, rounds, x0hat, st, light));
     }
     ASD_HIP(hipEventRecord(ctx->live_ev[slot], st));
     if (r >= lag) {
@@ -435,6 +448,9 @@ static asd_status sample_rounds(asd_ctx* ctx, const float* y0, float* traj, int3
         done_at = r - lag;
         break;
       }
+      // the early accept kernel took every chain of round r - lag: the rounds to come are launched without the
+      // kernels behind it, until one of them reports a chain it could not take (which has waited since)
+      light = ctx->early_now && ctx->live_host[kLiveRing + q] == 0;
     }
   }
   ASD_HIP(hipStreamSynchronize(st));
@@ -520,10 +536,7 @@ asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   if (ctx->gmm && ctx->gmm->split_ok && ctx->gmm->use_split != (on != 0)) {
     ctx->gmm->use_split = on != 0;
-    if (ctx->gexec) {   // the captured round holds the other kernels
-      (void)hipGraphExecDestroy(ctx->gexec);
-      ctx->gexec = nullptr;
-    }
+    drop_round_graphs(ctx);   // the captured round holds the other kernels
   }
   return ASD_OK;
 }
@@ -532,10 +545,7 @@ asd_status asd_use_sparse_combine(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   if (ctx->gmm && ctx->gmm->sparse_combine != (on != 0)) {
     ctx->gmm->sparse_combine = on != 0;
-    if (ctx->gexec) {   // the captured round holds the other launch arguments
-      (void)hipGraphExecDestroy(ctx->gexec);
-      ctx->gexec = nullptr;
-    }
+    drop_round_graphs(ctx);   // the captured round holds the other launch arguments
   }
   return ASD_OK;
 }
@@ -545,10 +555,7 @@ asd_status asd_use_logit_screen(asd_ctx* ctx, int32_t mode) {
   if (mode < 0 || mode > 2) return fail(ASD_EINVAL, "asd_use_logit_screen: mode is 0 (off), 1 (when it pays) or 2 (always)");
   if (ctx->gmm && ctx->gmm->screen_mode != mode) {
     ctx->gmm->screen_mode = mode;
-    if (ctx->gexec) {   // the captured round holds the other launches
-      (void)hipGraphExecDestroy(ctx->gexec);
-      ctx->gexec = nullptr;
-    }
+    drop_round_graphs(ctx);   // the captured round holds the other launches
   }
   return ASD_OK;
 }
@@ -557,10 +564,7 @@ asd_status asd_use_onehot_certificate(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   if (ctx->gmm && ctx->gmm->cert_on != (on != 0)) {
     ctx->gmm->cert_on = on != 0;
-    if (ctx->gexec) {   // the captured round holds the other launches
-      (void)hipGraphExecDestroy(ctx->gexec);
-      ctx->gexec = nullptr;
-    }
+    drop_round_graphs(ctx);   // the captured round holds the other launches
   }
   return ASD_OK;
 }
@@ -569,10 +573,7 @@ asd_status asd_use_tall_tiles(asd_ctx* ctx, int32_t on) {
   if (!ctx) return fail(ASD_EINVAL, "ctx is NULL");
   if (ctx->gmm && ctx->gmm->big_on != (on != 0)) {
     ctx->gmm->big_on = on != 0;
-    if (ctx->gexec) {   // the captured round holds the other launches
-      (void)hipGraphExecDestroy(ctx->gexec);
-      ctx->gexec = nullptr;
-    }
+    drop_round_graphs(ctx);   // the captured round holds the other launches
   }
   return ASD_OK;
 }

@@ -129,12 +129,14 @@ struct asd_ctx {
   // owned by asd_sample
   float* x0hat = nullptr;  // [B, L, d]
   int32_t* a = nullptr;    // [B]
-  int32_t* live = nullptr;       // DEV [1 + kLiveRing]: round index, then the ring of live-chain counters
+  int32_t* live = nullptr;       // DEV [1 + 2 kLiveRing]: round index, the ring of live-chain counters, the ring of
+                                 // chains a round's early accept kernel left pending
   int32_t* live_host = nullptr;  // pinned mirror
   hipEvent_t* live_ev = nullptr;
   int32_t last_rounds = 0;
   // one round of the cheap-round path as an instantiated HIP graph, valid for (g_traj, g_rounds, g_stream)
   hipGraphExec_t gexec = nullptr;
+  hipGraphExec_t gexec_light = nullptr;   // the light round (draft call + early accept kernel only), same validity
   const void* g_traj = nullptr;
   const void* g_rounds = nullptr;
   hipStream_t g_stream = nullptr;
@@ -241,7 +243,8 @@ asd_status launch_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0h
                          float* stats, int32_t* rounds, int32_t* live, hipStream_t st, const int32_t* pending = nullptr);
 // Draft and accept stage of the chains the denoiser's one-hot certificate covers, ahead of the draft kernel and the
 // verify call; leaves ctx->pending[c] = 1 for every chain that still needs those and launch_accept (accept_early_kernel).
-asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st);
+asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st,
+                               bool light = false);
 asd_status launch_seq_step(asd_ctx* ctx, float* traj, int32_t step, hipStream_t st);
 asd_status launch_plan_seq(asd_ctx* ctx, int32_t step, hipStream_t st);
 asd_status launch_debug_philox(Key key, uint32_t chain, uint32_t step, uint32_t stream_id, int32_t nblk,

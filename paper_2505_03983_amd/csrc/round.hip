@@ -130,6 +130,7 @@ __global__ __launch_bounds__(1024) void plan_rows_kernel(int B, int K, int L, in
     const int r = ring[0];
     ring[0] = r + 1;
     ring[1 + (r % kLiveRing)] = 0;
+    ring[1 + kLiveRing + (r % kLiveRing)] = 0;
   }
   __shared__ int s_pc[1024];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -250,6 +251,7 @@ __global__ __launch_bounds__(256) void draft_kernel(int K, int Lwin, int d, cons
         const int r = plan.ring[0];
         plan.ring[0] = r + 1;
         plan.ring[1 + (r % kLiveRing)] = 0;
+        plan.ring[1 + kLiveRing + (r % kLiveRing)] = 0;
       }
     }
     // This chain's rows of the verify call: the drafted samples of slots 1..w-1, read in place from the
@@ -596,8 +598,12 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
                                                            const float* __restrict__ x0a, float* __restrict__ traj,
                                                            int32_t* __restrict__ rounds, int32_t* __restrict__ live,
                                                            int32_t* __restrict__ win, OneHotCert oc,
-                                                           int32_t* __restrict__ pending,
+                                                           int32_t* __restrict__ pending, int light,
                                                            int64_t* __restrict__ prof_counts) {
+  // live: [0] round index (advanced at the start of this round), then the ring of chains unfinished after a round,
+  // then the ring of chains a round left pending.  light: nothing follows this kernel in the round (the host has seen
+  // rounds without pending chains and launches the draft call and this kernel only): a pending chain then simply
+  // waits for the next full round, and counts as unfinished here because no accept kernel will count it.
   __shared__ float s_part[kAcceptChunk][4][4];   // per slot of the chunk, per wavefront: <D,xi>, |D|^2, <x,mu_b>, |x|^2
   __shared__ float s_r2[kAcceptChunk][4];        // ... |x - s mu_b|^2
   __shared__ float s_s[kAcceptChunk];            // s = <x,mu_b> / |mu_b|^2 of every slot
@@ -621,8 +627,18 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
     am = oc.a_min[b];
     go = cert_worth_reading(oc.coef_tau[tau_tab[ac + 1]], am, d);
   }
+  auto leave_pending = [&]() {
+    if (tid == 0) {
+      pending[c] = 1;
+      if (live) {
+        const int slot = (live[0] - 1) % kLiveRing;
+        atomicAdd(&live[1 + kLiveRing + slot], 1);
+        if (light) atomicAdd(&live[1 + slot], 1);
+      }
+    }
+  };
   if (!go) {
-    if (tid == 0) pending[c] = 1;
+    leave_pending();
     return;
   }
   const Key key = *key_p;
@@ -754,7 +770,7 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
     }
     __syncthreads();
     if (s_fail) {   // a slot that matters is not certified: the chain takes the verify call
-      if (tid == 0) pending[c] = 1;
+      leave_pending();
       return;
     }
     // the rows the chain keeps of this chunk: up to the slot of the first rejection, all of them if there is none
@@ -822,14 +838,15 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
   }
 }
 
-asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st) {
+asd_status launch_accept_early(asd_ctx* ctx, float* traj, int32_t* a, int32_t* rounds, int32_t* live, hipStream_t st,
+                               bool light) {
   OneHotCert oc;
   if (!model_onehot_cert(ctx, &oc) || ctx->d % 4 != 0 || ctx->d / 4 > 256 || !ctx->pending)
     return ASD_ESTATE;
   ProfScope ps(ctx, ASD_PROF_ACCEPT_EARLY, 0, st);
   const int threads = (int)(ceil_div(ctx->d / 4, 64) * 64);
   hipLaunchKernelGGL(accept_early_kernel, dim3(ctx->B), dim3(threads), 0, st, ctx->K, ctx->L, ctx->d, ctx->key_dev, a,
-                     ctx->c_x, ctx->c_0, ctx->sigma, ctx->tau, ctx->x0a, traj, rounds, live, ctx->cur_win, oc, ctx->pending,
+                     ctx->c_x, ctx->c_0, ctx->sigma, ctx->tau, ctx->x0a, traj, rounds, live, ctx->cur_win, oc, ctx->pending, light ? 1 : 0,
                      prof_counting(ctx) ? ctx->row_counts : nullptr);
   ASD_HIP(hipGetLastError());
   return ASD_OK;

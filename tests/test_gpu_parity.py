@@ -623,7 +623,10 @@ def test_early_accept_is_bit_identical_and_takes_chains():
                      "chain-rounds", early_on[1], "of", int(rounds[0].sum()), "; verify rows", rows_on[1])
                 assert early_off == (0, 0, 0, 0) and early_on[1] > int(rounds[0].sum()) // 4 and 0 < early_on[0] <= early_on[2]
                 assert 0 < early_on[3] <= early_on[1] and early_on[3] <= acc_on[1]
-                assert rows_on == rows_off and acc_on == acc_off
+                # the windows verified are the same; the draft call may see a few chain-rounds more: a chain the
+                # early kernel could not take in a round launched without the kernels behind it waits for the next full one
+                assert rows_on[1] == rows_off[1] and acc_on == acc_off
+                assert rows_off[0] <= rows_on[0] <= rows_off[0] + rows_off[0] // 100
     ctx.use_early_accept(True)
     ctx.use_adaptive_window(False)
     # ... and it stays out of the way where it does not apply
