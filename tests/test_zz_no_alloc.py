@@ -49,6 +49,11 @@ def test_noalloc_sample_equals_sample_twice_in_a_row_second_smaller():
     small_mlp = dict(kind="mlp", d=16, E=8, width=64, n_blocks=2, K=30, chains=6, L=12)
     _, pm, _ = oracle_setup(small_mlp)
     _pair(small_mlp, pm, seed=10)
+    # a shape on which the early accept kernel and the rounds launched without the kernels behind it are at work
+    # (17 k model rows per call; 8.5 MiB of scratch, which the chains left to the verify call use)
+    early = dict(kind="gmm", d=128, C=256, K=200, chains=272, L=64, var=0.25)
+    _, pe, _ = oracle_setup(early)
+    _pair(early, pe, seed=12)
 
 
 def test_noalloc_sample_refuses_what_does_not_fit_and_states_the_limit():
