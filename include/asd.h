@@ -248,7 +248,9 @@ ASD_API asd_status asd_use_split_gemm(asd_ctx* ctx, int32_t on);
  * launches): the baseline ASD is compared against in the paper's speedups. */
 ASD_API asd_status asd_sample_sequential(asd_ctx* ctx, const float* y0, float* traj, void* stream);
 
-/* Number of lock-step rounds launched by the last asd_sample (host value). */
+/* Number of lock-step rounds launched by the last asd_sample (host value): the largest rounds[c], or a few more
+ * where early accept is at work (asd_testing.h) -- a round launched without the verify call may leave a chain
+ * waiting for the next full one, which rounds[c] does not count. */
 ASD_API int32_t asd_last_round_count(const asd_ctx* ctx);
 
 /* ---- the model call on its own ---------------------------------------------
