@@ -74,8 +74,8 @@ ASD_API int32_t asd_tall_tiles_active(const asd_ctx* ctx);
  * sums in the same order on the same values.  Late in a sample, when every row is certifiable, a round then writes
  * the dozen rows per chain it keeps, instead of writing the whole window, reading it, writing its model values and
  * reading a third of those back.  Once a round has left no chain to the kernels behind it, the rounds that follow are
- * launched without them (the draft call and this kernel only) until one reports a chain it could not take; that chain
- * has not moved and is taken up by the next full round.  Default: on.  asd_early_accept_active: 1 if asd_sample of
+ * this kernel alone -- it then certifies y_a as well and forms the draft call's model value itself -- until one reports
+ * a chain it could not take; that chain has not moved and is taken up by the next full round.  Default: on.  asd_early_accept_active: 1 if asd_sample of
  * this context does it.
  * asd_profile_early_accept (while asd_profile_enable is on): model rows the kernel formed itself, chain-rounds it
  * committed, the rows of their windows (slots 1 .. w - 1) and the rows it resampled since then.  asd_profile_rows

@@ -325,17 +325,19 @@ asd_status asd_accept(asd_ctx* ctx, float* traj, int32_t* a, const float* x0hat,
 }
 
 // All launches of one round of Alg. 1 on `st`, plus the copy of the live-chain ring to the host.
-// light (early accept only): the draft call and the early accept kernel alone -- for rounds in which, as far as the
-// host knows, that kernel takes every chain.  A chain it does not take stays where it is until the next full round.
+// light (early accept only): the early accept kernel alone (behind the planning kernel, which starts the round) --
+// for rounds in which, as far as the host knows, that kernel takes every chain.  A chain it does not take stays where
+// it is until the next full round.
 static asd_status enqueue_round(asd_ctx* ctx, float* traj, int32_t* rounds, float* x0hat, hipStream_t st, bool light) {
   // No planning kernels here: the rows of the draft call were listed by the previous round's accept
   // kernel (by init_state before round 0), those of the verify call are listed by the draft kernel.
   // (or, for large batches, by the planning kernels: see fold_plans)
+  const int32_t* pending = ctx->early_now ? ctx->pending : nullptr;
   if (!ctx->fold_plans) ASD_TRY(launch_plan_draft(ctx, ctx->a, st, ctx->live));
-  ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
+  // (a light round has no draft call either: the early accept kernel forms the model value at y_a itself)
+  if (!(pending && light)) ASD_TRY(model_eval(ctx, draft_rows(ctx, traj), st));
   // chains the denoiser can certify have their draft and accept stage in one kernel now; the draft kernel, the verify
   // call and the accept kernel take the others only
-  const int32_t* pending = ctx->early_now ? ctx->pending : nullptr;
   if (pending) ASD_TRY(launch_accept_early(ctx, traj, ctx->a, rounds, ctx->live, st, light));
   if (!(pending && light)) {
     ASD_TRY(launch_draft(ctx, traj, ctx->a, st, ctx->live, pending));

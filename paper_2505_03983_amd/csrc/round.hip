@@ -601,9 +601,10 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
                                                            int32_t* __restrict__ pending, int light,
                                                            int64_t* __restrict__ prof_counts) {
   // live: [0] round index (advanced at the start of this round), then the ring of chains unfinished after a round,
-  // then the ring of chains a round left pending.  light: nothing follows this kernel in the round (the host has seen
-  // rounds without pending chains and launches the draft call and this kernel only): a pending chain then simply
-  // waits for the next full round, and counts as unfinished here because no accept kernel will count it.
+  // then the ring of chains a round left pending.  light: this kernel is the round (the host has seen rounds without
+  // pending chains and launches neither the draft call nor anything behind this kernel): the model value at y_a is
+  // formed here like the others, if y_a passes the certificate; a pending chain simply waits for the next full round,
+  // and counts as unfinished here because no accept kernel will count it.
   __shared__ float s_part[kAcceptChunk][4][4];   // per slot of the chunk, per wavefront: <D,xi>, |D|^2, <x,mu_b>, |x|^2
   __shared__ float s_r2[kAcceptChunk][4];        // ... |x - s mu_b|^2
   __shared__ float s_s[kAcceptChunk];            // s = <x,mu_b> / |mu_b|^2 of every slot
@@ -646,10 +647,41 @@ __global__ __launch_bounds__(256) void accept_early_kernel(int K, int L, int d, 
   const bool mine = tid < nblk;
   const float qb = oc.musq[b], bias_b = kCertLog2e * oc.log_w[b];
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float4 ga1 = mine ? load4(x0a + (int64_t)c * d, tid, d, true) : zero4;
   const float4 mv = mine ? load4(oc.means + (int64_t)b * d, tid, d, true) : zero4;
   float* rows = traj + ((int64_t)c * (K + 1) + ac) * d;   // slot k's row: yhat_{a+k}, row k from here
   float4 y = mine ? load4(rows, tid, d, true) : zero4;    // yhat_a = y_a; then the last row drafted
+  float4 ga1;                                             // x0a: the model value at y_a
+  if (!light) {
+    ga1 = mine ? load4(x0a + (int64_t)c * d, tid, d, true) : zero4;
+  } else {
+    // no draft call in this round: y_a is certified here and its value formed as gmm_certify_kernel would have
+    const float4 cf0 = oc.coef_tau[tau_tab[ac]];
+    const float p0 = wave_sum((y.x * mv.x + y.y * mv.y) + (y.z * mv.z + y.w * mv.w));
+    const float x0 = wave_sum((y.x * y.x + y.y * y.y) + (y.z * y.z + y.w * y.w));
+    if (lane == 0) {
+      s_part[0][wave][2] = p0;
+      s_part[0][wave][3] = x0;
+    }
+    __syncthreads();
+    float ps = 0.f, xs = 0.f;
+    for (int q = 0; q < nwaves; ++q) {
+      ps += s_part[0][q][2];
+      xs += s_part[0][q][3];
+    }
+    const float s0 = ps / qb;
+    const float ex = fmaf(-s0, mv.x, y.x), ey = fmaf(-s0, mv.y, y.y), ez = fmaf(-s0, mv.z, y.z), ew = fmaf(-s0, mv.w, y.w);
+    const float r0 = wave_sum((ex * ex + ey * ey) + (ez * ez + ew * ew));
+    if (lane == 0) s_r2[0][wave] = r0;
+    __syncthreads();
+    float rs = 0.f;
+    for (int q = 0; q < nwaves; ++q) rs += s_r2[0][q];
+    __syncthreads();   // the sums are read; the slots' sums go to the same places
+    if (!cert_passes(cf0, s0, rs, xs, am, qb, bias_b, oc.glob, oc.globw)) {   // (the same for every thread)
+      leave_pending();
+      return;
+    }
+    ga1 = cert_value(cf0, y, mv);
+  }
   float4 xi_d = normal4(key, (uint32_t)c, (uint32_t)(ac + 1), (uint32_t)tid);   // the noise of the next draft step
 
   auto slot_terms = [&](float4 ga, float4 gk, float4 xi, float& dot, float& vv) {   // as in accept_kernel
