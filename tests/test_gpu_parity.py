@@ -663,6 +663,12 @@ def test_early_accept_sample_matches_the_oracle():
     full += _free_running(cfg, 32, [7, 200], resident=False, adaptive=True)
     full += _free_running(cfg, 33, [64], resident=False, graphs=False)
     assert full >= 4
+    # windows longer than a wavefront has lanes (the walk goes on chunk by chunk), one wavefront per chain; and
+    # windows that are no multiple of 64 (no chain blocks in the verify plan)
+    long_w = dict(kind="gmm", d=256, C=256, K=300, chains=70, L=256, var=0.25)
+    assert _free_running(long_w, 41, [0, 69], resident=False) >= 1
+    short_w = dict(kind="gmm", d=128, C=512, K=90, chains=600, L=32, var=0.25)
+    assert _free_running(short_w, 43, [0, 599], resident=False) >= 1
 
 
 def test_profile_select_times_the_chosen_slots_only():
